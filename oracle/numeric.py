@@ -1,0 +1,132 @@
+"""numpy front end of the numeric oracle (oracle/conv_ref.c).
+
+Arrays: activations NHWC, weights KRSC.  dtype 'f32' uses float32 arrays,
+'bf16' uses uint16 arrays holding bf16 bit patterns.  See conv_ref.c for the
+definition that is computed and the tests that pin it.
+"""
+import ctypes
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(_build.build())
+        L.oracle_conv_bn_act.restype = ctypes.c_int
+        L.oracle_conv_bn_act.argtypes = ([ctypes.c_int] + [ctypes.c_void_p] * 7 + [ctypes.c_double]
+                                         + [ctypes.c_int] * 10 + [ctypes.c_void_p] * 2)
+        L.oracle_maxpool.restype = ctypes.c_int
+        L.oracle_maxpool.argtypes = [ctypes.c_int, ctypes.c_void_p] + [ctypes.c_int] * 8 + [ctypes.c_void_p]
+        L.oracle_avgpool.restype = ctypes.c_int
+        L.oracle_avgpool.argtypes = [ctypes.c_int, ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+        L.oracle_double_to_bf16.restype = ctypes.c_uint16
+        L.oracle_double_to_bf16.argtypes = [ctypes.c_double]
+        L.oracle_bf16_to_double.restype = ctypes.c_double
+        L.oracle_bf16_to_double.argtypes = [ctypes.c_uint16]
+        L.oracle_num_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _code(dtype):
+    return {"f32": 0, "bf16": 1}[dtype]
+
+
+def _np(dtype):
+    return np.float32 if dtype == "f32" else np.uint16
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())
+
+
+def double_to_bf16(v):
+    return int(lib().oracle_double_to_bf16(float(v)))
+
+
+def bf16_to_double(b):
+    return float(lib().oracle_bf16_to_double(int(b)))
+
+
+def to_f64(a, dtype):
+    """Exact widening of a stored array to float64."""
+    if dtype == "f32":
+        return np.asarray(a, dtype=np.float32).astype(np.float64)
+    b = np.ascontiguousarray(a, dtype=np.uint16)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def conv_bn_act(x, w, bn, res=None, stride=1, pad=0, relu=True, dtype="f32", want_f64=False):
+    """One fused layer; bn = dict(gamma, beta, mean, var, eps) or None.  Returns y
+    (storage dtype) or (y, y64) where y64 holds the values before the final rounding."""
+    x = np.ascontiguousarray(x, dtype=_np(dtype))
+    w = np.ascontiguousarray(w, dtype=_np(dtype))
+    N, H, W, Cin = x.shape
+    Cout, R, S, Cin2 = w.shape
+    assert Cin == Cin2
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    y = np.empty((N, P, Q, Cout), dtype=_np(dtype))
+    y64 = np.empty((N, P, Q, Cout), dtype=np.float64) if want_f64 else None
+    if res is not None:
+        res = np.ascontiguousarray(res, dtype=_np(dtype))
+        assert res.shape == y.shape
+    if bn is not None:
+        g, b, m, v = (np.ascontiguousarray(bn[k], dtype=np.float32) for k in ("gamma", "beta", "mean", "var"))
+        assert g.shape == b.shape == m.shape == v.shape == (Cout,)
+        eps = float(bn["eps"])
+    else:
+        g = b = m = v = None
+        eps = 0.0
+    rc = lib().oracle_conv_bn_act(_code(dtype), _ptr(x), _ptr(w), _ptr(res), _ptr(g), _ptr(b),
+                                  _ptr(m), _ptr(v), eps, N, H, W, Cin, Cout, R, S, stride, pad,
+                                  1 if relu else 0, _ptr(y), _ptr(y64))
+    if rc != 0:
+        raise ValueError("oracle_conv_bn_act rejected its arguments")
+    return (y, y64) if want_f64 else y
+
+
+def maxpool(x, R, S, stride, pad, dtype="f32"):
+    x = np.ascontiguousarray(x, dtype=_np(dtype))
+    N, H, W, C = x.shape
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    y = np.empty((N, P, Q, C), dtype=_np(dtype))
+    if lib().oracle_maxpool(_code(dtype), _ptr(x), N, H, W, C, R, S, stride, pad, _ptr(y)) != 0:
+        raise ValueError("oracle_maxpool rejected its arguments")
+    return y
+
+
+def avgpool(x, dtype="f32"):
+    x = np.ascontiguousarray(x, dtype=_np(dtype))
+    N, H, W, C = x.shape
+    y = np.empty((N, 1, 1, C), dtype=_np(dtype))
+    if lib().oracle_avgpool(_code(dtype), _ptr(x), N, H, W, C, _ptr(y)) != 0:
+        raise ValueError("oracle_avgpool rejected its arguments")
+    return y
+
+
+def run_layers(layers, params, x0, dtype):
+    """Forward of a list of synth.LayerSpec conv layers; returns {tensor name: stored array}."""
+    acts = {"x0": x0}
+    for l in layers:
+        if l.kind == "conv":
+            acts[l.y] = conv_bn_act(acts[l.x], params[l.name]["w"], params[l.name],
+                                    res=acts[l.res] if l.res else None, stride=l.stride,
+                                    pad=l.pad, relu=l.relu, dtype=dtype)
+        elif l.kind == "maxpool":
+            acts[l.y] = maxpool(acts[l.x], l.R, l.S, l.stride, l.pad, dtype)
+        elif l.kind == "avgpool":
+            acts[l.y] = avgpool(acts[l.x], dtype)
+        else:
+            raise ValueError("no oracle for layer kind %r" % l.kind)
+    return acts

@@ -1,0 +1,321 @@
+"""CPU oracle, planner half: DELTA's main loop, Filter, Director and Prefetcher
+simulated over a static operator trace.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).  Pure Python integers, so
+the 128-bit products the C++ planner needs are exact here for free.
+
+The algorithm is a heuristic, so this follows the paper's steps in its order
+and notation:
+
+  * Main loop (DELTA Algorithm 1): on access, an evicted tensor is recomputed;
+    an offloaded tensor that is not on the GPU is recomputed when it can be and
+    reloaded otherwise; then, while three quarters of the budget is used or
+    memory is short, Filter picks a tensor, Director picks Evict or Offload.
+  * Filter (Algorithm 2, Eq. 1-3): the resident tensor with the minimum
+    H = 1/(m*s) (base), 1/s (LRU) or 1/m (GREEDY), i.e. the maximum of m*s, s
+    or m; ties go to the lowest id; s = 0 gives H = infinity (least preferred)
+    without ever dividing.
+  * Director (Algorithm 3, Eq. 4-6): evict_pinned -> Offload, offload_pinned ->
+    Evict, otherwise F = h_r/h_o = c_r/c_s and F <= 1 -> Evict else Offload.
+    c_s is the time to offload plus the time to reload (Sec. 3); c_r is the
+    tensor's own cost plus that of its non-resident ancestors (Sec. 3, Eq. 5).
+  * Prefetcher (Algorithm 4): reload the head of the offloaded queue while
+    memory allows and fewer than n reloads have been issued.
+  * Assumption 2: no Evict/Offload after the last forward step.
+
+Readings taken where the paper is silent (each listed in the design notes):
+logical clock = sum of executed operator costs; queue ordered by next use;
+prefetch guard is "and"; release stops at 3/4 of the budget or when no candidate
+is left, failing only above the full budget; parents rebuilt only as operands of a
+recomputation stay on the GPU as provisional tensors while a later step still
+reads them, and are the first to go (DROP_TEMP, farthest next use first) when
+an allocation does not fit or the 3/4 trigger fires.
+
+Pins (tests/test_oracle_planner.py): Table 5 cost pairs give Evict; pin flags
+override; b = 0 gives all Evict, huge b all Offload; tie gives Evict; equal m
+makes base = LRU, equal s makes base = GREEDY; closed-form victim order on a
+chain; budget >= 4/3 of the peak gives an empty plan; every plan passes the
+independent checker (oracle/checker.py); brute force on <= 12 tensors
+(oracle/brute.py) bounds the plan cost from below.  The greedy sequence beyond
+those cases has no printed example in the paper: parity unpinned.
+"""
+
+UNCOMPUTABLE, EVICT_PINNED, OFFLOAD_PINNED = 1, 2, 4
+FILTER_BASE, FILTER_LRU, FILTER_GREEDY = 0, 1, 2
+EV_EVICT, EV_OFFLOAD, EV_RECOMPUTE, EV_RELOAD_PREFETCH = 1, 2, 3, 4
+EV_RELOAD_DEMAND, EV_FREE, EV_DROP_TEMP = 5, 6, 7
+EVENT_NAMES = {1: "EVICT", 2: "OFFLOAD", 3: "RECOMPUTE", 4: "RELOAD_PREFETCH",
+               5: "RELOAD_DEMAND", 6: "FREE", 7: "DROP_TEMP"}
+U64_MAX = (1 << 64) - 1
+
+
+class Infeasible(Exception):
+    """The budget cannot hold what one step needs."""
+
+    def __init__(self, step, msg):
+        super().__init__("step %d: %s" % (step, msg))
+        self.step = step
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+def transfer_ns(nbytes, bw_Bps):
+    """Time to move nbytes at bw bytes/s, in ns, rounded up; bw = 0 means never (saturates)."""
+    if bw_Bps == 0:
+        return U64_MAX
+    return min(ceil_div(nbytes * 10**9, bw_Bps), U64_MAX)
+
+
+def swap_cost_ns(nbytes, bw_d2h, bw_h2d):
+    """c_s(t): offload time plus reload time (Sec. 3), saturating at 2^64 - 1."""
+    return min(transfer_ns(nbytes, bw_d2h) + transfer_ns(nbytes, bw_h2d), U64_MAX)
+
+
+def default_params(budget, n_fwd, **kw):
+    p = dict(budget_bytes=int(budget), trigger_num=3, trigger_den=4, filter=FILTER_BASE,
+             prefetch_distance=2, max_reloads=2, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9,
+             n_fwd_steps=int(n_fwd))
+    p.update(kw)
+    return p
+
+
+class _Held:
+    """Stack of parent lists of the recomputations in progress; `in` looks through all."""
+
+    def __init__(self):
+        self.frames = []
+
+    def append(self, frame):
+        self.frames.append(frame)
+
+    def pop(self):
+        self.frames.pop()
+
+    def __contains__(self, t):
+        return any(t in f for f in self.frames)
+
+
+class _Sim:
+    def __init__(self, tensors, steps, params):
+        self.T = tensors
+        self.S = steps
+        self.p = params
+        self.B = params["budget_bytes"]
+        n = len(tensors)
+        self.resident = [False] * n
+        self.evicted = [False] * n
+        self.swapout = [False] * n
+        self.last_access = [0] * n
+        self.reads_at = [[] for _ in range(n)]       # ascending step indices
+        for k, st in enumerate(steps):
+            for t in st["reads"]:
+                self.reads_at[t].append(k)
+        self.tau = 0
+        self.live = 0
+        self.peak = 0
+        self.events = []
+        self.k = 0
+        self.locked = set()
+        self.provisional = [False] * n
+        self.held = _Held()
+
+    # -- bookkeeping -------------------------------------------------------
+    def emit(self, action, t):
+        self.events.append((self.k, action, t))
+
+    def grow(self, nbytes):
+        """Allocate nbytes.  Tensors that sit on the GPU only as leftovers of an earlier
+        recomputation (provisional) give way first: the one needed farthest in the future
+        goes first, ties to the lowest id."""
+        while self.live + nbytes > self.B:
+            best, best_nr = None, None
+            for t in range(len(self.T)):
+                if self.provisional[t] and t not in self.locked and t not in self.held:
+                    nr = self.next_read(t, self.k)
+                    if best is None or nr > best_nr:
+                        best, best_nr = t, nr
+            if best is None:
+                raise Infeasible(self.k, "live %d + %d exceeds budget %d"
+                                 % (self.live, nbytes, self.B))
+            self.drop(best)
+        self.live += nbytes
+        self.peak = max(self.peak, self.live)
+
+    def drop(self, t):
+        self.emit(EV_DROP_TEMP, t)
+        self.live -= self.T[t]["bytes"]
+        self.resident[t] = False
+        self.provisional[t] = False
+
+    def next_read(self, t, from_step):
+        for s in self.reads_at[t]:
+            if s >= from_step:
+                return s
+        return None
+
+    def computable(self, t):
+        return not (self.T[t]["flags"] & UNCOMPUTABLE)
+
+    # -- Algorithm 1, access part -----------------------------------------
+    def materialise(self, t):
+        """Bring t onto the GPU (Recompute when it can be recomputed, Reload otherwise).
+        Missing parents are brought in first; they stay afterwards as provisional tensors
+        when a later step reads them and are dropped at once when none does."""
+        if self.computable(t):
+            parents = self.T[t]["parents"]
+            self.held.append(parents)
+            mine = []
+            for p in parents:                           # ascending id
+                if not self.resident[p]:
+                    self.materialise(p)
+                    mine.append(p)
+            self.grow(self.T[t]["bytes"])
+            self.emit(EV_RECOMPUTE, t)
+            self.tau += self.T[t]["cost_ns"]
+            self.held.pop()
+            for p in mine:
+                if p in self.locked:
+                    continue
+                if self.next_read(p, self.k + 1) is None:
+                    self.drop(p)
+                else:
+                    self.provisional[p] = True
+        elif self.swapout[t]:
+            self.grow(self.T[t]["bytes"])
+            self.emit(EV_RELOAD_DEMAND, t)
+        else:
+            raise Infeasible(self.k, "tensor %d cannot be recomputed and has no host copy" % t)
+        self.resident[t] = True
+
+    # -- Algorithm 2 -------------------------------------------------------
+    def filter(self, cands):
+        kind = self.p["filter"]
+        best, best_key = None, None
+        for t in cands:                                  # ascending id: first maximum wins
+            m = self.T[t]["bytes"]
+            s = self.tau - self.last_access[t]
+            key = m * s if kind == FILTER_BASE else (s if kind == FILTER_LRU else m)
+            if best is None or key > best_key:
+                best, best_key = t, key
+        return best
+
+    # -- Algorithm 3 -------------------------------------------------------
+    def recompute_cost(self, t):
+        """c_r(t): own cost plus every non-resident ancestor reached through non-resident
+        tensors (its compute cost, or its reload time when it cannot be recomputed)."""
+        total = self.T[t]["cost_ns"]
+        seen = set()
+        stack = list(self.T[t]["parents"])
+        while stack:
+            a = stack.pop()
+            if a in seen or self.resident[a]:
+                continue
+            seen.add(a)
+            if self.computable(a):
+                total += self.T[a]["cost_ns"]
+                stack.extend(self.T[a]["parents"])
+            else:
+                total += transfer_ns(self.T[a]["bytes"], self.p["bw_h2d_Bps"])
+        return min(total, U64_MAX)
+
+    def director(self, t):
+        f = self.T[t]["flags"]
+        if f & (EVICT_PINNED | UNCOMPUTABLE):
+            return EV_OFFLOAD
+        if f & OFFLOAD_PINNED:
+            return EV_EVICT
+        c_s = swap_cost_ns(self.T[t]["bytes"], self.p["bw_d2h_Bps"], self.p["bw_h2d_Bps"])
+        return EV_EVICT if self.recompute_cost(t) <= c_s else EV_OFFLOAD
+
+    # -- Algorithm 4 -------------------------------------------------------
+    def prefetch(self):
+        d, n = self.p["prefetch_distance"], self.p["max_reloads"]
+        issued = 0
+        while issued < n:
+            q = []
+            for t in range(len(self.T)):
+                if self.swapout[t] and not self.resident[t]:
+                    nr = self.next_read(t, self.k)
+                    if nr is not None:
+                        q.append((nr, t))
+            if not q:
+                break
+            nr, head = min(q)
+            if nr > self.k + d or self.live + self.T[head]["bytes"] > self.B:
+                break
+            self.emit(EV_RELOAD_PREFETCH, head)
+            self.live += self.T[head]["bytes"]
+            self.peak = max(self.peak, self.live)
+            self.resident[head] = True
+            issued += 1
+
+    # -- one step ----------------------------------------------------------
+    def doubly_pinned(self, t):
+        f = self.T[t]["flags"]
+        return bool(f & (EVICT_PINNED | UNCOMPUTABLE)) and bool(f & OFFLOAD_PINNED)
+
+    def step(self, k):
+        self.k = k
+        st = self.S[k]
+        fwd = k < self.p["n_fwd_steps"]
+        if not fwd:
+            self.prefetch()
+        self.locked = set(st["reads"])
+        if st["produces"] >= 0:
+            self.locked.add(st["produces"])
+        for t in st["reads"]:                           # ascending id
+            if not self.resident[t]:
+                self.materialise(t)
+            self.provisional[t] = False
+            self.evicted[t] = False
+        need = self.T[st["produces"]]["bytes"] if st["produces"] >= 0 else 0
+        if fwd:
+            num, den = self.p["trigger_num"], self.p["trigger_den"]
+            while den * (self.live + need) > num * self.B:
+                prov = [(self.next_read(t, k), -t) for t in range(len(self.T))
+                        if self.provisional[t] and t not in self.locked]
+                if prov:
+                    self.drop(-max(prov)[1])
+                    continue
+                cands = [t for t in range(len(self.T))
+                         if self.resident[t] and t not in self.locked
+                         and not self.doubly_pinned(t) and self.next_read(t, k + 1) is not None]
+                if not cands:
+                    if self.live + need <= self.B:
+                        break
+                    raise Infeasible(k, "nothing left to release")
+                v = self.filter(cands)
+                act = self.director(v)
+                self.emit(act, v)
+                self.live -= self.T[v]["bytes"]
+                self.resident[v] = False
+                if act == EV_EVICT:
+                    self.evicted[v], self.swapout[v] = True, False
+                else:
+                    self.swapout[v] = True
+        if st["produces"] >= 0:
+            self.grow(need)
+            self.resident[st["produces"]] = True
+        self.tau += st["cost_ns"]
+        touched = list(st["reads"]) + ([st["produces"]] if st["produces"] >= 0 else [])
+        for t in touched:
+            self.last_access[t] = self.tau
+        for t in sorted(set(touched)):
+            if self.next_read(t, k + 1) is None:
+                self.emit(EV_FREE, t)
+                self.live -= self.T[t]["bytes"]
+                self.resident[t] = False
+                self.provisional[t] = False
+                self.evicted[t] = True
+        self.locked = set()
+
+
+def plan(tensors, steps, params):
+    """Returns (events, peak_bytes); events are (step, action, tensor) in issue order.
+    Raises Infeasible when some step cannot fit into the budget."""
+    sim = _Sim(tensors, steps, params)
+    for k in range(len(steps)):
+        sim.step(k)
+    return sim.events, sim.peak
