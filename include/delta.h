@@ -1,0 +1,209 @@
+/*
+ * delta.h -- C ABI of the MI355X hot path behind DELTA (arXiv 2203.15980,
+ * "Dynamically Optimizing GPU Memory beyond Tensor Recomputation").
+ *
+ * The library covers what DELTA's Filter and Director trade against each other:
+ *   - planning: which resident activation to Release, and whether to Evict or
+ *     Offload it (Algorithms 1-4, Eq. 1-6);
+ *   - Evict / Recompute: dropping an activation and regenerating it by re-running
+ *     the fused conv + BN-affine (+ residual) + ReLU layers that produced it;
+ *   - Offload / Reload: copying an activation to pinned host memory and back on
+ *     side streams that overlap the compute stream (Sec. 4.2).
+ *
+ * Conventions for every entry point
+ *   - Plain C: no exceptions cross the boundary; every call returns a
+ *     delta_status (0 = DELTA_OK, negative = error) and leaves a message that
+ *     delta_last_error() returns.
+ *   - "device" pointers are HIP device addresses on the context's GPU, "host"
+ *     pointers are ordinary process memory.  The caller owns every array it
+ *     passes; the library copies what it keeps before the call returns.
+ *   - The caller owns the device arena and the compute stream handed to
+ *     delta_create().  The library owns the context, its two copy streams, its
+ *     events, its pinned host buffers, and sub-allocates the arena: the arena
+ *     size is the physical activation budget.
+ *   - delta_swap_out, delta_prefetch, delta_release and delta_recompute_segment
+ *     only enqueue work; delta_sync (and delta_destroy) block the host.
+ *   - One context is used from one host thread at a time.
+ *   - There is no CPU fallback: calls that need the GPU fail with
+ *     DELTA_ERR_HIP when no device is usable.
+ */
+#ifndef DELTA_H
+#define DELTA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct delta_ctx delta_ctx;
+typedef int32_t delta_status;
+
+enum {
+    DELTA_OK = 0,
+    DELTA_ERR_INVALID = -1,     /* bad argument, id, shape or unsupported layer */
+    DELTA_ERR_INFEASIBLE = -2,  /* delta_plan: some step cannot fit into the budget */
+    DELTA_ERR_OOM_ARENA = -3,   /* no arena block large enough */
+    DELTA_ERR_OOM_PINNED = -4,  /* pinned host allocation failed */
+    DELTA_ERR_STATE = -5,       /* tensor not in the state the call needs */
+    DELTA_ERR_BUFFER = -6,      /* delta_plan: out_events too small (count is still returned) */
+    DELTA_ERR_HIP = -7          /* a HIP call failed */
+};
+
+/* Tensor flags: the pin flags of struct DELTATensor (Sec. 4.3). */
+enum { DELTA_F_UNCOMPUTABLE = 1, DELTA_F_EVICT_PINNED = 2, DELTA_F_OFFLOAD_PINNED = 4 };
+/* Filter heuristics: Eq. (1) base 1/(m*s), Eq. (2) LRU 1/s, Eq. (3) GREEDY 1/m. */
+enum { DELTA_FILTER_BASE = 0, DELTA_FILTER_LRU = 1, DELTA_FILTER_GREEDY = 2 };
+/* Plan events: the actions of Table 1, plus FREE (last use passed) and DROP_TEMP (a
+ * tensor that was back on the GPU only as an operand of a recomputation leaves again). */
+enum {
+    DELTA_EV_EVICT = 1, DELTA_EV_OFFLOAD = 2, DELTA_EV_RECOMPUTE = 3,
+    DELTA_EV_RELOAD_PREFETCH = 4, DELTA_EV_RELOAD_DEMAND = 5, DELTA_EV_FREE = 6,
+    DELTA_EV_DROP_TEMP = 7
+};
+enum { DELTA_DTYPE_F32 = 0, DELTA_DTYPE_BF16 = 1 };
+enum { DELTA_SYNC_D2H = 1, DELTA_SYNC_H2D = 2, DELTA_SYNC_COMPUTE = 4, DELTA_SYNC_ALL = 7 };
+enum { DELTA_DIR_D2H = 0, DELTA_DIR_H2D = 1, DELTA_DIR_BOTH = 2 };
+#define DELTA_NO_TENSOR 0xFFFFFFFFu
+
+/* One tensor of the planner graph (the cost fields of struct DELTATensor, Sec. 4.3).
+ * Tensors are numbered in production order; parents[i] < own id. */
+typedef struct {
+    uint64_t bytes;        /* m(t) */
+    uint64_t cost_ns;      /* time to compute t from resident parents */
+    uint64_t flops;        /* informational */
+    uint32_t flags;        /* DELTA_F_* */
+    uint32_t n_parents;
+    const uint32_t *parents;   /* host, ascending ids */
+} delta_tensor_desc;
+
+/* One operator of the per-iteration sequence (Assumption 1).  Steps [0, n_fwd_steps) are
+ * the forward pass and produce one tensor each; later steps only read. */
+typedef struct {
+    int32_t produces;      /* tensor id, or -1 */
+    uint32_t n_reads;
+    const uint32_t *reads; /* host, ascending ids */
+    uint64_t cost_ns;
+} delta_step_desc;
+
+typedef struct {
+    uint64_t budget_bytes;                 /* B */
+    uint32_t trigger_num, trigger_den;     /* early start, 3/4 in the paper (Sec. 4.3) */
+    uint32_t filter;                       /* DELTA_FILTER_* */
+    uint32_t prefetch_distance;            /* d: look-ahead of Algorithm 4, in steps */
+    uint32_t max_reloads;                  /* n of Algorithm 4, per step */
+    uint32_t n_fwd_steps;
+    uint64_t bw_d2h_Bps, bw_h2d_Bps;       /* b of Eq. (6), per direction; 0 = no link */
+} delta_plan_params;
+
+typedef struct { uint32_t step, action, tensor, pad; } delta_event;
+
+/* One fused layer y = relu?(scale_k * conv(x, w) + shift_k (+ res)), activations NHWC,
+ * weights KRSC (w[k][r][s][c]), scale/shift fp32 per output channel (folded batch-norm
+ * with frozen statistics).  x, res, y are tensor ids of the bound table. */
+typedef struct {
+    uint32_t x, res, y;        /* res = DELTA_NO_TENSOR when there is no residual */
+    uint32_t dtype;            /* DELTA_DTYPE_*: storage type of x, res, y and w */
+    const void *w;             /* device, 16-byte aligned */
+    const float *scale;        /* device */
+    const float *shift;        /* device */
+    int32_t N, H, W, Cin, Cout, R, S, stride, pad;
+    uint32_t relu;
+} delta_layer_desc;
+
+typedef struct {
+    uint64_t arena_bytes, arena_in_use, arena_high_water;
+    uint64_t d2h_bytes, h2d_bytes;         /* copied since the last delta_stats_reset */
+    uint64_t d2h_copies, h2d_copies;
+    double d2h_ms, h2d_ms;                 /* sum of copy durations (device timestamps) */
+    uint64_t recompute_launches, recompute_flops;
+    uint64_t releases_evict, releases_offload, releases_free;
+    uint64_t pinned_bytes;
+} delta_stats_t;
+
+/* Creates a context on the current HIP device.  arena_dev: device, 256-byte aligned,
+ * arena_bytes long, or NULL for a planner-only context (then every call but delta_plan,
+ * delta_last_error and delta_destroy fails with DELTA_ERR_STATE).  compute_stream: a
+ * hipStream_t (NULL = the default stream). */
+delta_status delta_create(void *arena_dev, uint64_t arena_bytes, void *compute_stream,
+                          delta_ctx **out);
+/* Waits for all three streams, frees pinned buffers, events and streams.  NULL is a no-op. */
+void delta_destroy(delta_ctx *ctx);
+/* Message of the last failed call on ctx (ctx-owned, valid until the next call). */
+const char *delta_last_error(delta_ctx *ctx);
+
+/*
+ * Filter + Director + Prefetcher over a static trace (Algorithms 1-4, Eq. 1-6,
+ * Assumptions 1-2).  Pure CPU, integer arithmetic only, deterministic.
+ * Writes at most `capacity` events in issue order and always sets *out_count to the
+ * number the plan has (DELTA_ERR_BUFFER when capacity was too small) and *out_peak to the
+ * peak of live bytes.  DELTA_ERR_INFEASIBLE: last_error names the failing step.
+ */
+delta_status delta_plan(delta_ctx *ctx, const delta_tensor_desc *tensors, uint32_t n_tensors,
+                        const delta_step_desc *steps, uint32_t n_steps,
+                        const delta_plan_params *params, delta_event *out_events,
+                        uint32_t capacity, uint32_t *out_count, uint64_t *out_peak);
+
+/* Declares the run-time tensor table: n tensors with the given byte sizes, none resident.
+ * Drops every tensor and host copy of a previous table (after waiting for the streams). */
+delta_status delta_bind(delta_ctx *ctx, const uint64_t *bytes, uint32_t n_tensors);
+/* Makes `tensor` resident in a fresh arena block without computing it (network input).
+ * The block may be written on the compute stream right away. */
+delta_status delta_alloc(delta_ctx *ctx, uint32_t tensor, void **dev_out);
+/* Device address of a resident tensor, valid until it is released.  Makes the compute
+ * stream wait for a pending reload of that tensor.  DELTA_ERR_STATE when not resident. */
+delta_status delta_tensor_ptr(delta_ctx *ctx, uint32_t tensor, void **dev_out);
+
+/*
+ * Release (Table 1).  action DELTA_EV_EVICT: the block returns to the arena, a host copy
+ * is forgotten.  DELTA_EV_OFFLOAD: delta_swap_out if no valid host copy exists, then the
+ * block returns to the arena; whoever gets the block next waits for the copy on its own
+ * stream, the host never blocks.  DELTA_EV_FREE / DELTA_EV_DROP_TEMP: the block returns, a
+ * host copy stays valid.  DELTA_ERR_STATE when the tensor is not resident.
+ */
+delta_status delta_release(delta_ctx *ctx, uint32_t tensor, uint32_t action);
+/* Offload without release: async copy to the tensor's pinned host buffer on the D2H
+ * stream, ordered after everything enqueued so far on the compute stream (Sec. 4.2). */
+delta_status delta_swap_out(delta_ctx *ctx, uint32_t tensor);
+/* Reload (Algorithm 4): fresh arena block, async copy from the host buffer on the H2D
+ * stream; later uses of the tensor on the compute stream wait for the copy's event.
+ * DELTA_ERR_STATE when the tensor is resident or has no valid host copy. */
+delta_status delta_prefetch(delta_ctx *ctx, uint32_t tensor);
+/*
+ * Recompute (Table 1), also used for the first forward so that both produce the same
+ * bits: runs the layers in order on the compute stream.  Every x / res must be resident;
+ * y gets a fresh block when it is not resident and is overwritten when it is.
+ * Supported: Cin a multiple of 64 (bf16) or 32 (fp32), Cout a multiple of 64, any R, S,
+ * stride, pad; other shapes return DELTA_ERR_INVALID before anything is launched.
+ */
+delta_status delta_recompute_segment(delta_ctx *ctx, const delta_layer_desc *layers,
+                                     uint32_t n_layers);
+/* Blocks the host until the selected streams (DELTA_SYNC_* bit mask) are idle. */
+delta_status delta_sync(delta_ctx *ctx, uint32_t which);
+
+/* Folds frozen batch-norm statistics into scale = gamma / sqrt(var + eps) and
+ * shift = beta - mean * scale (fp32, on the compute stream).  All pointers: device. */
+delta_status delta_bn_fold(delta_ctx *ctx, const float *gamma, const float *beta,
+                           const float *mean, const float *var, float eps, uint32_t C,
+                           float *scale, float *shift);
+
+delta_status delta_stats(delta_ctx *ctx, delta_stats_t *out);   /* waits for the copy streams */
+delta_status delta_stats_reset(delta_ctx *ctx);
+/* When skip != 0, swap-out and prefetch keep all their bookkeeping and stream ordering
+ * but move no bytes: the replay then shows what the step costs without the link. */
+delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
+
+/* Measurement probes (rooflines the hot path is reported against). */
+/* Pinned host <-> device hipMemcpyAsync throughput for `bytes` per copy, `iters` copies,
+ * direction DELTA_DIR_*; BOTH runs the two directions concurrently and reports their sum. */
+delta_status delta_probe_hostlink(delta_ctx *ctx, uint64_t bytes, uint32_t iters, uint32_t dir,
+                                  double *out_GBps);
+/* Device copy kernel (read + write of `bytes` each) -> achieved HBM GB/s, counting both. */
+delta_status delta_probe_hbm(delta_ctx *ctx, uint64_t bytes, uint32_t iters, double *out_GBps);
+/* Register-resident bf16 MFMA loop -> achieved TFLOP/s. */
+delta_status delta_probe_mfma(delta_ctx *ctx, uint32_t iters, double *out_TFLOPs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DELTA_H */

@@ -1,0 +1,712 @@
+// C ABI of the library (include/delta.h): context, arena sub-allocator, swap engine,
+// recompute dispatch and measurement probes.  The planner lives in planner.cpp, the
+// kernels in conv_igemm.hip.
+//
+// Stream model (DELTA Sec. 4.2: copies run on a memory stream of their own so that they
+// overlap the computation stream).  Three streams: the caller's compute stream, a D2H
+// stream for Offload and an H2D stream for Reload -- two copy streams so that both
+// directions of the host link can be busy at once.  Nothing here blocks the host except
+// delta_sync / delta_stats / delta_bind / delta_destroy.  Ordering between streams is
+// carried by events:
+//   - every arena block remembers, per stream, the last event after which its old
+//     contents are no longer touched (a "fence"); whoever receives the block makes its
+//     own stream wait for the fences of the other streams before writing;
+//   - a reloaded tensor carries the event of its H2D copy; the compute stream waits for it
+//     at the first use;
+//   - an offloaded tensor carries the event of its D2H copy; a reload waits for it.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/delta.h"
+#include "kernels.hpp"
+#include "planner.hpp"
+
+namespace {
+
+enum { S_COMPUTE = 0, S_D2H = 1, S_H2D = 2, N_STREAMS = 3 };
+const uint64_t kAlign = 256;
+
+// An ordering event plus its position in the order of recording: of two events recorded on
+// the same stream, waiting for the one with the larger seq covers the other.
+struct Ev {
+    hipEvent_t e;
+    uint64_t seq;
+    Ev() : e(nullptr), seq(0) {}
+    explicit operator bool() const { return e != nullptr; }
+};
+
+struct Fence {
+    Ev ev[N_STREAMS];
+};
+
+struct Block {
+    uint64_t size;
+    Fence fence;
+};
+
+struct Tensor {
+    uint64_t bytes = 0;
+    bool resident = false;
+    uint64_t offset = 0;            // arena offset when resident
+    void *host = nullptr;           // pinned buffer (lazily allocated, kept for reuse)
+    bool host_valid = false;
+    Ev d2h_done;                    // last Offload copy of this tensor
+    Ev h2d_done;                    // pending Reload the compute stream has not waited for
+};
+
+struct Timed {
+    hipEvent_t start, stop;
+    int dir;
+};
+
+}  // namespace
+
+struct delta_ctx {
+    unsigned char *arena = nullptr;
+    uint64_t arena_bytes = 0;
+    int device = -1;
+    hipStream_t stream[N_STREAMS] = {nullptr, nullptr, nullptr};
+    std::map<uint64_t, Block> free_blocks;         // offset -> block, coalesced
+    std::map<uint64_t, uint64_t> used;             // offset -> size
+    std::vector<Tensor> tensors;
+    std::vector<hipEvent_t> ev_pool, ev_live;      // ordering events (no timing)
+    std::vector<hipEvent_t> tev_pool;              // timing events
+    std::vector<Timed> timed;
+    delta_stats_t st;
+    bool skip_copies = false;
+    uint64_t ev_seq = 0;
+    std::string err;
+
+    delta_ctx() { memset(&st, 0, sizeof st); }
+};
+
+namespace {
+
+delta_status fail(delta_ctx *c, delta_status code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                       \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail((c), DELTA_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_));    \
+    } while (0)
+
+delta_status need_gpu(delta_ctx *c) {
+    if (!c) return DELTA_ERR_INVALID;
+    if (!c->arena) return fail(c, DELTA_ERR_STATE, "planner-only context: no arena was given");
+    return DELTA_OK;
+}
+
+// ---- events
+
+delta_status new_event(delta_ctx *c, hipStream_t s, Ev *out) {
+    hipEvent_t e;
+    if (!c->ev_pool.empty()) {
+        e = c->ev_pool.back();
+        c->ev_pool.pop_back();
+    } else {
+        HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    c->ev_live.push_back(e);
+    HIP_TRY(c, hipEventRecord(e, s));
+    out->e = e;
+    out->seq = ++c->ev_seq;
+    return DELTA_OK;
+}
+
+delta_status new_timing_event(delta_ctx *c, hipStream_t s, hipEvent_t *out) {
+    hipEvent_t e;
+    if (!c->tev_pool.empty()) {
+        e = c->tev_pool.back();
+        c->tev_pool.pop_back();
+    } else {
+        HIP_TRY(c, hipEventCreate(&e));
+    }
+    HIP_TRY(c, hipEventRecord(e, s));
+    *out = e;
+    return DELTA_OK;
+}
+
+// Folds finished copy timings into the statistics.  Streams must be idle.
+delta_status harvest_timings(delta_ctx *c) {
+    for (size_t i = 0; i < c->timed.size(); ++i) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->timed[i].start, c->timed[i].stop));
+        (c->timed[i].dir == DELTA_DIR_D2H ? c->st.d2h_ms : c->st.h2d_ms) += ms;
+        c->tev_pool.push_back(c->timed[i].start);
+        c->tev_pool.push_back(c->timed[i].stop);
+    }
+    c->timed.clear();
+    return DELTA_OK;
+}
+
+// After all three streams are idle every fence is satisfied: recycle the events.
+void retire_events(delta_ctx *c) {
+    for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it)
+        it->second.fence = Fence();
+    for (size_t i = 0; i < c->tensors.size(); ++i) c->tensors[i].d2h_done = c->tensors[i].h2d_done = Ev();
+    c->ev_pool.insert(c->ev_pool.end(), c->ev_live.begin(), c->ev_live.end());
+    c->ev_live.clear();
+}
+
+delta_status sync_all(delta_ctx *c) {
+    for (int s = 0; s < N_STREAMS; ++s) HIP_TRY(c, hipStreamSynchronize(c->stream[s]));
+    delta_status r = harvest_timings(c);
+    if (r != DELTA_OK) return r;
+    retire_events(c);
+    return DELTA_OK;
+}
+
+// ---- arena: first fit over an offset-ordered free list, coalescing on free
+
+Ev later(const Ev &a, const Ev &b) { return a.seq > b.seq ? a : b; }
+
+delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t *off) {
+    const uint64_t need = (bytes + kAlign - 1) / kAlign * kAlign;
+    for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it) {
+        if (it->second.size < need) continue;
+        const uint64_t o = it->first;
+        Block b = it->second;
+        c->free_blocks.erase(it);
+        if (b.size > need) {
+            Block rest;
+            rest.size = b.size - need;
+            rest.fence = b.fence;
+            c->free_blocks[o + need] = rest;
+        }
+        for (int s = 0; s < N_STREAMS; ++s)
+            if (s != for_stream && b.fence.ev[s])
+                HIP_TRY(c, hipStreamWaitEvent(c->stream[for_stream], b.fence.ev[s].e, 0));
+        c->used[o] = need;
+        c->st.arena_in_use += need;
+        if (c->st.arena_in_use > c->st.arena_high_water) c->st.arena_high_water = c->st.arena_in_use;
+        *off = o;
+        return DELTA_OK;
+    }
+    return fail(c, DELTA_ERR_OOM_ARENA, "no arena block of %llu bytes (in use %llu of %llu)",
+                (unsigned long long)need, (unsigned long long)c->st.arena_in_use,
+                (unsigned long long)c->arena_bytes);
+}
+
+void arena_free(delta_ctx *c, uint64_t off, const Fence &f) {
+    std::map<uint64_t, uint64_t>::iterator u = c->used.find(off);
+    if (u == c->used.end()) return;
+    Block b;
+    b.size = u->second;
+    b.fence = f;
+    c->st.arena_in_use -= b.size;
+    c->used.erase(u);
+    uint64_t o = off;
+    std::map<uint64_t, Block>::iterator nx = c->free_blocks.lower_bound(off);   // first block above
+    if (nx != c->free_blocks.begin()) {
+        std::map<uint64_t, Block>::iterator pv = nx;
+        --pv;
+        if (pv->first + pv->second.size == off) {                               // merge downwards
+            o = pv->first;
+            b.size += pv->second.size;
+            for (int s = 0; s < N_STREAMS; ++s) b.fence.ev[s] = later(pv->second.fence.ev[s], b.fence.ev[s]);
+            c->free_blocks.erase(pv);
+        }
+    }
+    if (nx != c->free_blocks.end() && o + b.size == nx->first) {                // merge upwards
+        b.size += nx->second.size;
+        for (int s = 0; s < N_STREAMS; ++s) b.fence.ev[s] = later(nx->second.fence.ev[s], b.fence.ev[s]);
+        c->free_blocks.erase(nx);
+    }
+    c->free_blocks[o] = b;
+}
+
+delta_status check_id(delta_ctx *c, uint32_t t) {
+    if (t >= c->tensors.size()) return fail(c, DELTA_ERR_INVALID, "tensor id %u out of range (%zu bound)", t, c->tensors.size());
+    return DELTA_OK;
+}
+
+// The compute stream is about to touch tensor t: wait for a reload still in flight.
+delta_status compute_uses(delta_ctx *c, Tensor &t) {
+    if (t.h2d_done) {
+        HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], t.h2d_done.e, 0));
+        t.h2d_done = Ev();
+    }
+    return DELTA_OK;
+}
+
+// Returns the tensor's block to the arena.  Its next owner must wait for: everything the
+// compute stream was told to do with it so far, an Offload copy still reading it, and a
+// Reload nobody waited for yet that still writes it.
+delta_status drop_block(delta_ctx *c, Tensor &t) {
+    Fence f;
+    delta_status r = new_event(c, c->stream[S_COMPUTE], &f.ev[S_COMPUTE]);
+    if (r != DELTA_OK) return r;
+    f.ev[S_D2H] = t.d2h_done;
+    f.ev[S_H2D] = t.h2d_done;
+    t.h2d_done = Ev();
+    arena_free(c, t.offset, f);
+    t.resident = false;
+    return DELTA_OK;
+}
+
+delta_status swap_out_impl(delta_ctx *c, uint32_t id) {
+    Tensor &t = c->tensors[id];
+    if (!t.resident) return fail(c, DELTA_ERR_STATE, "swap_out: tensor %u is not resident", id);
+    if (!t.host) {
+        hipError_t e = hipHostMalloc(&t.host, t.bytes ? t.bytes : 1, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            t.host = nullptr;
+            (void)hipGetLastError();
+            return fail(c, DELTA_ERR_OOM_PINNED, "hipHostMalloc(%llu) failed: %s",
+                        (unsigned long long)t.bytes, hipGetErrorString(e));
+        }
+        c->st.pinned_bytes += t.bytes;
+    }
+    Ev produced;
+    delta_status r = new_event(c, c->stream[S_COMPUTE], &produced);
+    if (r != DELTA_OK) return r;
+    HIP_TRY(c, hipStreamWaitEvent(c->stream[S_D2H], produced.e, 0));
+    if (t.h2d_done) HIP_TRY(c, hipStreamWaitEvent(c->stream[S_D2H], t.h2d_done.e, 0));
+    if (!c->skip_copies && t.bytes) {
+        Timed tm;
+        tm.dir = DELTA_DIR_D2H;
+        if ((r = new_timing_event(c, c->stream[S_D2H], &tm.start)) != DELTA_OK) return r;
+        HIP_TRY(c, hipMemcpyAsync(t.host, c->arena + t.offset, t.bytes, hipMemcpyDeviceToHost, c->stream[S_D2H]));
+        if ((r = new_timing_event(c, c->stream[S_D2H], &tm.stop)) != DELTA_OK) return r;
+        c->timed.push_back(tm);
+    }
+    if ((r = new_event(c, c->stream[S_D2H], &t.d2h_done)) != DELTA_OK) return r;
+    t.host_valid = true;
+    c->st.d2h_bytes += t.bytes;
+    c->st.d2h_copies += 1;
+    return DELTA_OK;
+}
+
+void free_host_buffers(delta_ctx *c) {
+    for (size_t i = 0; i < c->tensors.size(); ++i)
+        if (c->tensors[i].host) (void)hipHostFree(c->tensors[i].host);
+    c->st.pinned_bytes = 0;
+}
+
+}  // namespace
+
+// =========================================================================== C ABI
+
+extern "C" {
+
+delta_status delta_create(void *arena_dev, uint64_t arena_bytes, void *compute_stream, delta_ctx **out) {
+    if (!out) return DELTA_ERR_INVALID;
+    *out = nullptr;
+    delta_ctx *c = new (std::nothrow) delta_ctx();
+    if (!c) return DELTA_ERR_INVALID;
+    if (arena_dev) {
+        if (((uintptr_t)arena_dev % kAlign) || arena_bytes < kAlign) {
+            delete c;
+            return DELTA_ERR_INVALID;
+        }
+        if (hipGetDevice(&c->device) != hipSuccess) {
+            delete c;
+            return DELTA_ERR_HIP;
+        }
+        c->arena = static_cast<unsigned char *>(arena_dev);
+        c->arena_bytes = arena_bytes / kAlign * kAlign;
+        c->st.arena_bytes = c->arena_bytes;
+        c->stream[S_COMPUTE] = static_cast<hipStream_t>(compute_stream);
+        if (hipStreamCreateWithFlags(&c->stream[S_D2H], hipStreamNonBlocking) != hipSuccess ||
+            hipStreamCreateWithFlags(&c->stream[S_H2D], hipStreamNonBlocking) != hipSuccess) {
+            delete c;
+            return DELTA_ERR_HIP;
+        }
+        Block b;
+        b.size = c->arena_bytes;
+        c->free_blocks[0] = b;
+    }
+    *out = c;
+    return DELTA_OK;
+}
+
+void delta_destroy(delta_ctx *c) {
+    if (!c) return;
+    if (c->arena) {
+        for (int s = 0; s < N_STREAMS; ++s) (void)hipStreamSynchronize(c->stream[s]);
+        free_host_buffers(c);
+        for (size_t i = 0; i < c->ev_live.size(); ++i) (void)hipEventDestroy(c->ev_live[i]);
+        for (size_t i = 0; i < c->ev_pool.size(); ++i) (void)hipEventDestroy(c->ev_pool[i]);
+        for (size_t i = 0; i < c->tev_pool.size(); ++i) (void)hipEventDestroy(c->tev_pool[i]);
+        for (size_t i = 0; i < c->timed.size(); ++i) {
+            (void)hipEventDestroy(c->timed[i].start);
+            (void)hipEventDestroy(c->timed[i].stop);
+        }
+        (void)hipStreamDestroy(c->stream[S_D2H]);
+        (void)hipStreamDestroy(c->stream[S_H2D]);
+    }
+    delete c;
+}
+
+const char *delta_last_error(delta_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+delta_status delta_plan(delta_ctx *c, const delta_tensor_desc *tensors, uint32_t n_tensors,
+                        const delta_step_desc *steps, uint32_t n_steps, const delta_plan_params *params,
+                        delta_event *out_events, uint32_t capacity, uint32_t *out_count, uint64_t *out_peak) {
+    if (!c) return DELTA_ERR_INVALID;
+    if (!out_count || (capacity && !out_events)) return fail(c, DELTA_ERR_INVALID, "null output argument");
+    std::vector<delta::PlanTensor> T;
+    std::vector<delta::PlanStep> S;
+    std::string err;
+    delta_status r = delta::load_graph(tensors, n_tensors, steps, n_steps, params, T, S, err);
+    if (r != DELTA_OK) return fail(c, r, "%s", err.c_str());
+    std::vector<delta_event> ev;
+    uint64_t peak = 0;
+    r = delta::run_plan(T, S, *params, ev, peak, err);
+    *out_count = (uint32_t)ev.size();
+    if (out_peak) *out_peak = peak;
+    if (r != DELTA_OK) return fail(c, r, "%s", err.c_str());
+    if (ev.size() > capacity)
+        return fail(c, DELTA_ERR_BUFFER, "plan has %zu events, buffer holds %u", ev.size(), capacity);
+    if (!ev.empty()) memcpy(out_events, ev.data(), ev.size() * sizeof(delta_event));
+    return DELTA_OK;
+}
+
+delta_status delta_bind(delta_ctx *c, const uint64_t *bytes, uint32_t n) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!bytes && n) return fail(c, DELTA_ERR_INVALID, "null sizes");
+    if ((r = sync_all(c)) != DELTA_OK) return r;
+    free_host_buffers(c);
+    c->tensors.assign(n, Tensor());
+    for (uint32_t i = 0; i < n; ++i) c->tensors[i].bytes = bytes[i];
+    c->free_blocks.clear();
+    c->used.clear();
+    Block b;
+    b.size = c->arena_bytes;
+    c->free_blocks[0] = b;
+    c->st.arena_in_use = 0;
+    return DELTA_OK;
+}
+
+delta_status delta_alloc(delta_ctx *c, uint32_t id, void **dev_out) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if ((r = check_id(c, id)) != DELTA_OK) return r;
+    Tensor &t = c->tensors[id];
+    if (t.resident) return fail(c, DELTA_ERR_STATE, "alloc: tensor %u is already resident", id);
+    if ((r = arena_alloc(c, t.bytes, S_COMPUTE, &t.offset)) != DELTA_OK) return r;
+    t.resident = true;
+    t.host_valid = false;
+    if (dev_out) *dev_out = c->arena + t.offset;
+    return DELTA_OK;
+}
+
+delta_status delta_tensor_ptr(delta_ctx *c, uint32_t id, void **dev_out) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if ((r = check_id(c, id)) != DELTA_OK) return r;
+    if (!dev_out) return fail(c, DELTA_ERR_INVALID, "null output argument");
+    Tensor &t = c->tensors[id];
+    if (!t.resident) {
+        *dev_out = nullptr;
+        return fail(c, DELTA_ERR_STATE, "tensor %u is not resident", id);
+    }
+    if ((r = compute_uses(c, t)) != DELTA_OK) return r;
+    *dev_out = c->arena + t.offset;
+    return DELTA_OK;
+}
+
+delta_status delta_swap_out(delta_ctx *c, uint32_t id) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if ((r = check_id(c, id)) != DELTA_OK) return r;
+    return swap_out_impl(c, id);
+}
+
+delta_status delta_release(delta_ctx *c, uint32_t id, uint32_t action) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if ((r = check_id(c, id)) != DELTA_OK) return r;
+    Tensor &t = c->tensors[id];
+    if (!t.resident) return fail(c, DELTA_ERR_STATE, "release: tensor %u is not resident", id);
+    switch (action) {
+    case DELTA_EV_EVICT:
+        t.host_valid = false;
+        c->st.releases_evict += 1;
+        return drop_block(c, t);
+    case DELTA_EV_OFFLOAD:
+        if (!t.host_valid && (r = swap_out_impl(c, id)) != DELTA_OK) return r;
+        c->st.releases_offload += 1;
+        return drop_block(c, t);
+    case DELTA_EV_FREE:
+    case DELTA_EV_DROP_TEMP:
+        c->st.releases_free += 1;
+        return drop_block(c, t);
+    default:
+        return fail(c, DELTA_ERR_INVALID, "release: action %u is not a release", action);
+    }
+}
+
+delta_status delta_prefetch(delta_ctx *c, uint32_t id) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if ((r = check_id(c, id)) != DELTA_OK) return r;
+    Tensor &t = c->tensors[id];
+    if (t.resident) return fail(c, DELTA_ERR_STATE, "prefetch: tensor %u is already resident", id);
+    if (!t.host_valid || !t.host) return fail(c, DELTA_ERR_STATE, "prefetch: tensor %u has no host copy", id);
+    if ((r = arena_alloc(c, t.bytes, S_H2D, &t.offset)) != DELTA_OK) return r;
+    t.resident = true;
+    if (t.d2h_done) HIP_TRY(c, hipStreamWaitEvent(c->stream[S_H2D], t.d2h_done.e, 0));
+    if (!c->skip_copies && t.bytes) {
+        Timed tm;
+        tm.dir = DELTA_DIR_H2D;
+        if ((r = new_timing_event(c, c->stream[S_H2D], &tm.start)) != DELTA_OK) return r;
+        HIP_TRY(c, hipMemcpyAsync(c->arena + t.offset, t.host, t.bytes, hipMemcpyHostToDevice, c->stream[S_H2D]));
+        if ((r = new_timing_event(c, c->stream[S_H2D], &tm.stop)) != DELTA_OK) return r;
+        c->timed.push_back(tm);
+    }
+    if ((r = new_event(c, c->stream[S_H2D], &t.h2d_done)) != DELTA_OK) return r;
+    c->st.h2d_bytes += t.bytes;
+    c->st.h2d_copies += 1;
+    return DELTA_OK;
+}
+
+delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layers, uint32_t n_layers) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!layers && n_layers) return fail(c, DELTA_ERR_INVALID, "null layers");
+    // Pass 1: validate everything before anything is launched or allocated.
+    std::vector<uint8_t> will_exist(c->tensors.size(), 0);
+    for (uint32_t i = 0; i < n_layers; ++i) {
+        const delta_layer_desc &L = layers[i];
+        if (L.x >= c->tensors.size() || L.y >= c->tensors.size() ||
+            (L.res != DELTA_NO_TENSOR && L.res >= c->tensors.size()))
+            return fail(c, DELTA_ERR_INVALID, "layer %u: tensor id out of range", i);
+        if (L.dtype != DELTA_DTYPE_F32 && L.dtype != DELTA_DTYPE_BF16)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: unknown dtype %u", i, L.dtype);
+        if (L.y == L.x || L.y == L.res) return fail(c, DELTA_ERR_INVALID, "layer %u: output aliases an input", i);
+        delta::ConvArgs a;
+        memset(&a, 0, sizeof a);
+        a.N = L.N; a.H = L.H; a.W = L.W; a.Cin = L.Cin; a.Cout = L.Cout; a.R = L.R; a.S = L.S;
+        a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0; a.bf16 = L.dtype == DELTA_DTYPE_BF16;
+        if (L.stride <= 0 || L.R <= 0 || L.S <= 0)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: non-positive dimension", i);
+        a.P = (L.H + 2 * L.pad - L.R) / L.stride + 1;
+        a.Q = (L.W + 2 * L.pad - L.S) / L.stride + 1;
+        const long long M = (long long)L.N * a.P * a.Q;
+        a.M = (M > 0 && M <= 0x7FFFFFFFLL) ? (int)M : -1;
+        a.x = a.y = c->arena;                      // placeholders for the alignment check
+        a.w = L.w; a.scale = L.scale; a.shift = L.shift;
+        const char *why = delta::conv_check(a);
+        if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
+        const uint64_t es = a.bf16 ? 2 : 4;
+        if (c->tensors[L.x].bytes != (uint64_t)L.N * L.H * L.W * L.Cin * es)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: input tensor %u has %llu bytes, layer needs %llu", i, L.x,
+                        (unsigned long long)c->tensors[L.x].bytes, (unsigned long long)((uint64_t)L.N * L.H * L.W * L.Cin * es));
+        const uint64_t ybytes = (uint64_t)M * L.Cout * es;
+        if (c->tensors[L.y].bytes != ybytes)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: output tensor %u has the wrong size", i, L.y);
+        if (L.res != DELTA_NO_TENSOR && c->tensors[L.res].bytes != ybytes)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: residual tensor %u has the wrong size", i, L.res);
+        if (!c->tensors[L.x].resident && !will_exist[L.x])
+            return fail(c, DELTA_ERR_STATE, "layer %u: input tensor %u is not resident", i, L.x);
+        if (L.res != DELTA_NO_TENSOR && !c->tensors[L.res].resident && !will_exist[L.res])
+            return fail(c, DELTA_ERR_STATE, "layer %u: residual tensor %u is not resident", i, L.res);
+        will_exist[L.y] = 1;
+    }
+    // Pass 2: allocate outputs and launch, in order, on the compute stream.
+    for (uint32_t i = 0; i < n_layers; ++i) {
+        const delta_layer_desc &L = layers[i];
+        Tensor &tx = c->tensors[L.x];
+        Tensor &ty = c->tensors[L.y];
+        if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
+        if (L.res != DELTA_NO_TENSOR && (r = compute_uses(c, c->tensors[L.res])) != DELTA_OK) return r;
+        if (!ty.resident) {
+            if ((r = arena_alloc(c, ty.bytes, S_COMPUTE, &ty.offset)) != DELTA_OK) return r;
+            ty.resident = true;
+        } else {
+            if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+            if (ty.d2h_done)                        // an Offload copy may still be reading it
+                HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.d2h_done.e, 0));
+        }
+        ty.host_valid = false;                      // the host copy, if any, is of older contents
+        delta::ConvArgs a;
+        memset(&a, 0, sizeof a);
+        a.x = c->arena + tx.offset;
+        a.y = c->arena + ty.offset;
+        a.res = L.res != DELTA_NO_TENSOR ? c->arena + c->tensors[L.res].offset : nullptr;
+        a.w = L.w; a.scale = L.scale; a.shift = L.shift;
+        a.N = L.N; a.H = L.H; a.W = L.W; a.Cin = L.Cin; a.Cout = L.Cout; a.R = L.R; a.S = L.S;
+        a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0; a.bf16 = L.dtype == DELTA_DTYPE_BF16;
+        a.P = (L.H + 2 * L.pad - L.R) / L.stride + 1;
+        a.Q = (L.W + 2 * L.pad - L.S) / L.stride + 1;
+        a.M = L.N * a.P * a.Q;
+        HIP_TRY(c, delta::launch_conv(a, c->stream[S_COMPUTE]));
+        c->st.recompute_launches += 1;
+        c->st.recompute_flops += 2ull * (uint64_t)a.M * L.R * L.S * L.Cin * L.Cout;
+    }
+    return DELTA_OK;
+}
+
+delta_status delta_sync(delta_ctx *c, uint32_t which) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (which == 0 || (which & ~(uint32_t)DELTA_SYNC_ALL)) return fail(c, DELTA_ERR_INVALID, "bad sync mask %u", which);
+    if (which == DELTA_SYNC_ALL) return sync_all(c);
+    if (which & DELTA_SYNC_COMPUTE) HIP_TRY(c, hipStreamSynchronize(c->stream[S_COMPUTE]));
+    if (which & DELTA_SYNC_D2H) HIP_TRY(c, hipStreamSynchronize(c->stream[S_D2H]));
+    if (which & DELTA_SYNC_H2D) HIP_TRY(c, hipStreamSynchronize(c->stream[S_H2D]));
+    return DELTA_OK;
+}
+
+delta_status delta_bn_fold(delta_ctx *c, const float *gamma, const float *beta, const float *mean,
+                           const float *var, float eps, uint32_t C, float *scale, float *shift) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!gamma || !beta || !mean || !var || !scale || !shift) return fail(c, DELTA_ERR_INVALID, "null pointer");
+    HIP_TRY(c, delta::launch_bn_fold(gamma, beta, mean, var, eps, C, scale, shift, c->stream[S_COMPUTE]));
+    return DELTA_OK;
+}
+
+delta_status delta_stats(delta_ctx *c, delta_stats_t *out) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!out) return fail(c, DELTA_ERR_INVALID, "null output argument");
+    HIP_TRY(c, hipStreamSynchronize(c->stream[S_D2H]));
+    HIP_TRY(c, hipStreamSynchronize(c->stream[S_H2D]));
+    if ((r = harvest_timings(c)) != DELTA_OK) return r;
+    *out = c->st;
+    return DELTA_OK;
+}
+
+delta_status delta_stats_reset(delta_ctx *c) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    HIP_TRY(c, hipStreamSynchronize(c->stream[S_D2H]));
+    HIP_TRY(c, hipStreamSynchronize(c->stream[S_H2D]));
+    if ((r = harvest_timings(c)) != DELTA_OK) return r;
+    const uint64_t ab = c->st.arena_bytes, iu = c->st.arena_in_use, pb = c->st.pinned_bytes;
+    memset(&c->st, 0, sizeof c->st);
+    c->st.arena_bytes = ab;
+    c->st.arena_in_use = c->st.arena_high_water = iu;
+    c->st.pinned_bytes = pb;
+    return DELTA_OK;
+}
+
+delta_status delta_set_skip_copies(delta_ctx *c, int32_t skip) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    c->skip_copies = skip != 0;
+    return DELTA_OK;
+}
+
+// ---- probes
+
+delta_status delta_probe_hostlink(delta_ctx *c, uint64_t bytes, uint32_t iters, uint32_t dir, double *out) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!out || !bytes || !iters || dir > DELTA_DIR_BOTH) return fail(c, DELTA_ERR_INVALID, "bad probe arguments");
+    void *h[2] = {nullptr, nullptr}, *d[2] = {nullptr, nullptr};
+    delta_status rc = DELTA_OK;
+    for (int i = 0; i < 2 && rc == DELTA_OK; ++i) {
+        if (hipHostMalloc(&h[i], bytes, hipHostMallocDefault) != hipSuccess) rc = fail(c, DELTA_ERR_OOM_PINNED, "probe: hipHostMalloc failed");
+        else if (hipMalloc(&d[i], bytes) != hipSuccess) rc = fail(c, DELTA_ERR_HIP, "probe: hipMalloc failed");
+        else memset(h[i], 1, bytes);
+    }
+    if (rc == DELTA_OK) {
+        const bool down = dir == DELTA_DIR_D2H || dir == DELTA_DIR_BOTH;
+        const bool up = dir == DELTA_DIR_H2D || dir == DELTA_DIR_BOTH;
+        hipError_t e = hipSuccess;
+        for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {      // rep 0 warms up
+            const uint32_t n = rep == 0 ? 2 : iters;
+            (void)hipStreamSynchronize(c->stream[S_D2H]);
+            (void)hipStreamSynchronize(c->stream[S_H2D]);
+            std::chrono::steady_clock::time_point t0 = std::chrono::steady_clock::now();
+            for (uint32_t i = 0; i < n && e == hipSuccess; ++i) {
+                if (down) e = hipMemcpyAsync(h[0], d[0], bytes, hipMemcpyDeviceToHost, c->stream[S_D2H]);
+                if (up && e == hipSuccess) e = hipMemcpyAsync(d[1], h[1], bytes, hipMemcpyHostToDevice, c->stream[S_H2D]);
+            }
+            if (e == hipSuccess) e = hipStreamSynchronize(c->stream[S_D2H]);
+            if (e == hipSuccess) e = hipStreamSynchronize(c->stream[S_H2D]);
+            const double sec = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+            if (rep == 1) *out = (double)bytes * n * ((down ? 1 : 0) + (up ? 1 : 0)) / sec / 1e9;
+        }
+        if (e != hipSuccess) rc = fail(c, DELTA_ERR_HIP, "probe copy failed: %s", hipGetErrorString(e));
+    }
+    for (int i = 0; i < 2; ++i) {
+        if (h[i]) (void)hipHostFree(h[i]);
+        if (d[i]) (void)hipFree(d[i]);
+    }
+    return rc;
+}
+
+delta_status delta_probe_hbm(delta_ctx *c, uint64_t bytes, uint32_t iters, double *out) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!out || bytes < 16 || !iters) return fail(c, DELTA_ERR_INVALID, "bad probe arguments");
+    void *a = nullptr, *b = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    delta_status rc = DELTA_OK;
+    hipStream_t s = c->stream[S_COMPUTE];
+    if (hipMalloc(&a, bytes) != hipSuccess || hipMalloc(&b, bytes) != hipSuccess) rc = fail(c, DELTA_ERR_HIP, "probe: hipMalloc failed");
+    if (rc == DELTA_OK && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) rc = fail(c, DELTA_ERR_HIP, "probe: event");
+    if (rc == DELTA_OK) {
+        hipError_t e = hipMemsetAsync(a, 1, bytes, s);
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) e = delta::launch_copy(a, b, bytes, s);
+        if (e == hipSuccess) e = hipEventRecord(e0, s);
+        for (uint32_t i = 0; i < iters && e == hipSuccess; ++i) e = delta::launch_copy(a, b, bytes, s);
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) rc = fail(c, DELTA_ERR_HIP, "probe failed: %s", hipGetErrorString(e));
+        else *out = 2.0 * (double)(bytes / 16 * 16) * iters / (ms * 1e-3) / 1e9;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (a) (void)hipFree(a);
+    if (b) (void)hipFree(b);
+    return rc;
+}
+
+delta_status delta_probe_mfma(delta_ctx *c, uint32_t iters, double *out) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!out || !iters || iters > (1u << 24)) return fail(c, DELTA_ERR_INVALID, "bad probe arguments");
+    float *buf = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    delta_status rc = DELTA_OK;
+    hipStream_t s = c->stream[S_COMPUTE];
+    const int blocks = 256 * 8;
+    if (hipMalloc((void **)&buf, 256) != hipSuccess) rc = fail(c, DELTA_ERR_HIP, "probe: hipMalloc failed");
+    if (rc == DELTA_OK && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) rc = fail(c, DELTA_ERR_HIP, "probe: event");
+    if (rc == DELTA_OK) {
+        hipError_t e = delta::launch_mfma_probe(buf, 16, blocks, s);
+        if (e == hipSuccess) e = hipEventRecord(e0, s);
+        if (e == hipSuccess) e = delta::launch_mfma_probe(buf, (int)iters, blocks, s);
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) rc = fail(c, DELTA_ERR_HIP, "probe failed: %s", hipGetErrorString(e));
+        else {
+            // per wavefront and iteration: 4 MFMAs of 32x32x16 = 4 * 2*32*32*16 flops
+            const double flops = (double)blocks * 4 /*waves*/ * iters * 4.0 * 2.0 * 32 * 32 * 16;
+            *out = flops / (ms * 1e-3) / 1e12;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (buf) (void)hipFree(buf);
+    return rc;
+}
+
+}  // extern "C"

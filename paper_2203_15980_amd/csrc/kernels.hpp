@@ -1,0 +1,29 @@
+// Internal launchers of the HIP kernels (conv_igemm.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace delta {
+
+struct ConvArgs {
+    const void *x;        // [N,H,W,Cin]
+    const void *w;        // [Cout,R,S,Cin]
+    const void *res;      // [N,P,Q,Cout] or nullptr
+    void *y;              // [N,P,Q,Cout]
+    const float *scale;   // [Cout]
+    const float *shift;   // [Cout]
+    int N, H, W, Cin, Cout, R, S, stride, pad, P, Q, M;
+    int relu;
+    int bf16;             // 1: bf16 storage, fp32 accumulate; 0: fp32
+};
+
+// nullptr when the kernel supports the shape, else the reason.
+const char *conv_check(const ConvArgs &a);
+const char *conv_kernel_name(const ConvArgs &a);
+hipError_t launch_conv(const ConvArgs &a, hipStream_t stream);
+hipError_t launch_bn_fold(const float *gamma, const float *beta, const float *mean, const float *var,
+                          float eps, unsigned C, float *scale, float *shift, hipStream_t stream);
+hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
+hipError_t launch_mfma_probe(float *out, int iters, int blocks, hipStream_t stream);
+
+}  // namespace delta

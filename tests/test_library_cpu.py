@@ -1,0 +1,130 @@
+"""CPU-side checks of the HIP library: it loads, exports what include/delta.h declares, and
+its planner (C++) produces byte-identical plans to the oracle planner (Python)."""
+import os
+import random
+import re
+import subprocess
+
+import pytest
+
+import paper_2203_15980_amd as dl
+import synth
+from oracle import checker, planner as pl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "delta.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(delta_[a-z_0-9]+)\s*\(", hdr))
+    assert len(declared) >= 19
+    lib = dl.load_library()
+    nm = subprocess.check_output(["nm", "-D", "--defined-only", dl.binding.LIB_PATH]).decode()
+    exported = set(re.findall(r" T (delta_[a-z_0-9]+)", nm))
+    assert declared <= exported, declared - exported
+    assert declared == set(dl.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_planner_only_context_rejects_gpu_calls():
+    d = dl.Delta()
+    with pytest.raises(dl.DeltaError) as e:
+        d.bind([16])
+    assert e.value.status == dl.ERR_STATE
+    d.close()
+
+
+@pytest.mark.parametrize("cfg,frac", [(1, 0.5), (3, 0.5), (4, 0.4), (5, 0.3)])
+def test_plans_match_oracle_on_configs(cfg, frac):
+    g = synth.config_graph(cfg)
+    B = int(frac * g.total_bytes())
+    for kind in (pl.FILTER_BASE, pl.FILTER_LRU, pl.FILTER_GREEDY):
+        for bw in (0, 20 * 10**9, 55 * 10**9, 10**13):
+            for d in (0, 1, 4):
+                p = pl.default_params(B, g.n_fwd, filter=kind, bw_d2h_Bps=bw, bw_h2d_Bps=bw * 9 // 10,
+                                      prefetch_distance=d, max_reloads=d)
+                try:
+                    want = pl.plan(g.tensors, g.steps, p)
+                except pl.Infeasible as e:
+                    with pytest.raises(dl.DeltaError) as got:
+                        dl.plan(g.tensors, g.steps, p)
+                    assert got.value.status == dl.ERR_INFEASIBLE
+                    assert ("step %d:" % e.step) in got.value.message
+                    continue
+                assert dl.plan(g.tensors, g.steps, p) == want
+
+
+def test_opgranular_resnet50_plan_matches_oracle():
+    g = synth.opgranular_graph(synth.resnet_layers(128), "bf16")
+    assert 150 <= len(g.tensors) <= 190
+    p = pl.default_params(g.total_bytes() // 2, g.n_fwd)
+    want = pl.plan(g.tensors, g.steps, p)
+    assert dl.plan(g.tensors, g.steps, p) == want
+    checker.check(g.tensors, g.steps, p, want[0])
+
+
+def _random_graph(rnd, n):
+    T = [dict(bytes=rnd.choice([256, 512, 1024]), cost_ns=0, flops=0, flags=pl.UNCOMPUTABLE, parents=[])]
+    for i in range(1, n):
+        par = {i - 1} | ({rnd.randrange(i)} if rnd.random() < 0.35 else set())
+        flags = 0
+        r = rnd.random()
+        if r < 0.08:
+            flags = pl.EVICT_PINNED
+        elif r < 0.16:
+            flags = pl.OFFLOAD_PINNED
+        T.append(dict(bytes=rnd.choice([256, 512, 1024, 4096]), cost_ns=rnd.randint(1, 3000), flops=0,
+                      flags=flags, parents=sorted(par)))
+    S = [dict(produces=0, reads=[], cost_ns=0)]
+    S += [dict(produces=i, reads=list(T[i]["parents"]), cost_ns=T[i]["cost_ns"]) for i in range(1, n)]
+    for i in range(n - 1, 0, -1):
+        if rnd.random() < 0.85:
+            S.append(dict(produces=-1, reads=sorted(set(T[i]["parents"]) | {i}), cost_ns=2 * T[i]["cost_ns"]))
+    return T, S, n
+
+
+def test_plans_match_oracle_on_random_graphs():
+    rnd = random.Random(2203)
+    ok = bad = 0
+    for trial in range(300):
+        T, S, n_fwd = _random_graph(rnd, rnd.randint(3, 40))
+        total = sum(t["bytes"] for t in T)
+        p = pl.default_params(int(total * rnd.uniform(0.15, 0.9)), n_fwd,
+                              filter=rnd.randrange(3), prefetch_distance=rnd.randrange(5),
+                              max_reloads=rnd.randrange(4),
+                              trigger_num=rnd.choice([1, 3, 3, 7]), trigger_den=rnd.choice([1, 4, 8]),
+                              bw_d2h_Bps=rnd.choice([0, 10**9, 10**12]), bw_h2d_Bps=rnd.choice([0, 10**9, 10**12]))
+        if p["trigger_num"] > p["trigger_den"]:
+            p["trigger_num"] = p["trigger_den"]
+        try:
+            want = pl.plan(T, S, p)
+        except pl.Infeasible as e:
+            with pytest.raises(dl.DeltaError) as got:
+                dl.plan(T, S, p)
+            assert got.value.status == dl.ERR_INFEASIBLE and ("step %d:" % e.step) in got.value.message
+            bad += 1
+            continue
+        assert dl.plan(T, S, p) == want
+        checker.check(T, S, p, want[0])
+        ok += 1
+    assert ok > 100 and bad > 10        # both outcomes are exercised
+
+
+def test_plan_rejects_malformed_graphs():
+    g = synth.config_graph(1)
+    p = pl.default_params(g.total_bytes(), g.n_fwd)
+    bad = [dict(t) for t in g.tensors]
+    bad[3] = dict(bad[3], parents=[5])                      # parent id above own id
+    with pytest.raises(dl.DeltaError) as e:
+        dl.plan(bad, g.steps, p)
+    assert e.value.status == dl.ERR_INVALID
+    steps = [dict(s) for s in g.steps]
+    steps[2] = dict(steps[2], reads=[9])                    # reads a tensor not produced yet
+    with pytest.raises(dl.DeltaError) as e:
+        dl.plan(g.tensors, steps, p)
+    assert e.value.status == dl.ERR_INVALID
+    with pytest.raises(dl.DeltaError) as e:
+        dl.plan(g.tensors, g.steps, dict(p, trigger_den=0))
+    assert e.value.status == dl.ERR_INVALID
