@@ -1,0 +1,234 @@
+// Streaming kernel for 1x1 convolutions with small weights (bf16, fp32 accumulate):
+// y = relu?(scale_k * (x . w_k) + shift_k (+ res)).
+//
+// These are the HBM-bound layers of a bottleneck (28-51 flop per byte against a ridge of
+// about 310 on MI355X): the job is to keep as many bytes in flight as possible, not to
+// feed the matrix cores.  So, unlike the tiled kernel in conv_igemm.hip:
+//   - the whole weight matrix (plus scale/shift) is staged once per workgroup in LDS;
+//   - after that single barrier every wavefront works alone on its own 32 pixels: it
+//     loads its activation operand straight from global memory into registers (each lane
+//     64 contiguous bytes per 128-byte slice of Cin), so there is no LDS traffic and no
+//     barrier on the streaming side, and many wavefronts per CU overlap freely;
+//   - output channels are processed 64 at a time (two 32x32 accumulators, 32 registers),
+//     which keeps the kernel under 128 VGPRs: 16 wavefronts per CU.
+// Orientation as in conv_igemm.hip: channels on the MFMA row axis, pixels on the column
+// axis, so a lane owns 4 consecutive channels of one pixel in each 8-row block.  One
+// v_permlane32_swap per register pair then gives every lane 8 consecutive channels
+// (16 bytes of bf16): the residual is read and y is written with 16 bytes per lane and 32
+// contiguous bytes per pixel and instruction, without a trip through LDS.
+// The summation order is fixed (slices of Cin in order, MFMA internal order), so forward
+// and recomputation give the same bits.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.hpp"
+
+namespace delta {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+namespace {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ float lo16(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float hi16(uint32_t p) { return __uint_as_float(p & 0xFFFF0000u); }
+__device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.f ? 0.f : v; }   // NaN stays NaN
+
+}  // namespace
+
+// NS = Cin / 64 (128-byte slices of the reduction axis), NG = Cout / 64.  Dynamic LDS:
+// weights [Cout][Cin*2 + 16 bytes], then scale[Cout], shift[Cout] (fp32).
+template <int NS, int NG, int WAVES, bool HAS_RES>
+__global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) {
+    constexpr int THREADS = WAVES * 64;
+    constexpr int Cout = NG * 64;
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int WPITCH = NS * 128 + 16;       // rows 4 banks apart: conflict-free b128 reads
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    float *lscale = reinterpret_cast<float *>(lds + (size_t)Cout * WPITCH);
+    float *lshift = lscale + Cout;
+
+    // ---- this wavefront's 32 output pixels.  Everything it reads from HBM (its activation
+    // operand and, if present, its residual rows) goes into flight first, so that the
+    // latency overlaps the staging of the weights and the wavefront never waits twice.
+    const long long tile = (long long)blockIdx.x * WAVES + wv;
+    const long long m = tile * 32 + l32;
+    const bool active = tile * 32 < a.M;         // wavefronts past the end only help staging
+    const bool valid = m < a.M;
+    const long long mm = valid ? m : (long long)a.M - 1;      // clamp: loads stay in bounds
+    size_t xpix;
+    if (a.stride == 1) {
+        xpix = (size_t)mm;
+    } else {
+        const int PQ = a.P * a.Q;
+        const int n = (int)(mm / PQ), pq = (int)(mm - (long long)n * PQ);
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        xpix = ((size_t)n * a.H + (size_t)p * a.stride) * a.W + (size_t)q * a.stride;
+    }
+    const unsigned char *xp = static_cast<const unsigned char *>(a.x) + xpix * (NS * 128) + half * 64;
+    u32x4_t xf[NS][4];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xf[s][j] = *reinterpret_cast<const u32x4_t *>(xp + s * 128 + j * 16);
+
+    const size_t orow = (size_t)mm * Cout * 2;
+    unsigned char *yg = static_cast<unsigned char *>(a.y);
+    const unsigned char *rg = static_cast<const unsigned char *>(a.res);
+    // residual in the post-swap layout: piece (u, i2) of group g covers channels
+    // g*64 + u*32 + 16*i2 + 8*half .. +8 of this lane's pixel.  Two groups are held: the one
+    // being finished and the next one, already in flight.
+    u32x4_t rv[2][2][2];
+    auto load_res = [&](int g, u32x4_t (&dst)[2][2]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2)
+                dst[u][i2] = *reinterpret_cast<const u32x4_t *>(
+                    rg + orow + (size_t)(g * 64 + u * 32 + 16 * i2 + 8 * half) * 2);
+    };
+    if constexpr (HAS_RES) load_res(0, rv[0]);
+
+    // ---- stage weights and batch-norm factors (once per workgroup)
+    {
+        const unsigned char *wg = static_cast<const unsigned char *>(a.w);
+        constexpr int SEGS = NS * 8;             // 16-byte pieces per weight row
+        constexpr int pieces = Cout * SEGS;
+        for (int c = tid; c < pieces; c += THREADS) {
+            const int row = c / SEGS, seg = c - row * SEGS;
+            *reinterpret_cast<u32x4_t *>(lds + row * WPITCH + seg * 16) =
+                *reinterpret_cast<const u32x4_t *>(wg + ((size_t)row * SEGS + seg) * 16);
+        }
+        for (int c = tid; c < Cout; c += THREADS) {
+            lscale[c] = a.scale[c];
+            lshift[c] = a.shift[c];
+        }
+    }
+    __syncthreads();                             // the only barrier
+    if (!active) return;
+    const int relu = a.relu;
+
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        if constexpr (HAS_RES) {
+            if (g + 1 < NG) load_res(g + 1, rv[(g + 1) & 1]);
+        }
+        f32x16_t acc[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+        const unsigned char *wrow = lds + (size_t)(g * 64 + l32) * WPITCH + half * 64;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4_t w0 = *reinterpret_cast<const u32x4_t *>(wrow + s * 128 + j * 16);
+                const u32x4_t w1 = *reinterpret_cast<const u32x4_t *>(wrow + 32 * WPITCH + s * 128 + j * 16);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w0),
+                                                                 __builtin_bit_cast(bf16x8_t, xf[s][j]), acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w1),
+                                                                 __builtin_bit_cast(bf16x8_t, xf[s][j]), acc[1], 0, 0, 0);
+            }
+        // ---- epilogue of the two 32-channel tiles
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int cb = g * 64 + u * 32;
+            float v[16];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const f32x4_t sc = *reinterpret_cast<const f32x4_t *>(lscale + cb + 8 * rb + 4 * half);
+                const f32x4_t sh = *reinterpret_cast<const f32x4_t *>(lshift + cb + 8 * rb + 4 * half);
+                v[4 * rb + 0] = acc[u][4 * rb + 0] * sc.x + sh.x;
+                v[4 * rb + 1] = acc[u][4 * rb + 1] * sc.y + sh.y;
+                v[4 * rb + 2] = acc[u][4 * rb + 2] * sc.z + sh.z;
+                v[4 * rb + 3] = acc[u][4 * rb + 3] * sc.w + sh.w;
+            }
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                // blocks 2*i2 and 2*i2+1: after the swap the lower half-wave holds channels
+                // cb + 16*i2 .. +8 and the upper half-wave the next eight, in order
+                float o[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]),
+                                                              __float_as_uint(v[8 * i2 + 4 + j]), false, false);
+                    o[j] = __uint_as_float(r[0]);
+                    o[4 + j] = __uint_as_float(r[1]);
+                }
+                if constexpr (HAS_RES) {
+                    const u32x4_t r4 = rv[g & 1][u][i2];
+                    o[0] += lo16(r4.x); o[1] += hi16(r4.x); o[2] += lo16(r4.y); o[3] += hi16(r4.y);
+                    o[4] += lo16(r4.z); o[5] += hi16(r4.z); o[6] += lo16(r4.w); o[7] += hi16(r4.w);
+                }
+                if (relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
+                }
+                u32x4_t out;
+                out.x = pack2(o[0], o[1]); out.y = pack2(o[2], o[3]);
+                out.z = pack2(o[4], o[5]); out.w = pack2(o[6], o[7]);
+                if (valid) *reinterpret_cast<u32x4_t *>(yg + orow + (size_t)(cb + 16 * i2 + 8 * half) * 2) = out;
+            }
+        }
+    }
+}
+
+size_t conv1x1_stream_lds_bytes(const ConvArgs &a) {
+    return (size_t)a.Cout * ((size_t)a.Cin * 2 + 16) + (size_t)a.Cout * 8;
+}
+
+// The streaming kernel applies to bf16 1x1 convolutions without padding whose weights fit LDS.
+bool conv1x1_stream_applies(const ConvArgs &a) {
+    return a.bf16 && a.R == 1 && a.S == 1 && a.pad == 0 && (a.Cin == 64 || a.Cin == 128 || a.Cin == 256) &&
+           (a.Cout == 64 || a.Cout == 128 || a.Cout == 256) && conv1x1_stream_lds_bytes(a) <= 56 * 1024;
+}
+
+template <int NS, int NG, int WAVES>
+static hipError_t launch_stream(const ConvArgs &a, hipStream_t stream) {
+    const long long tiles = ((long long)a.M + 31) / 32;
+    const long long blocks = (tiles + WAVES - 1) / WAVES;
+    if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(WAVES * 64);
+    const size_t lds = conv1x1_stream_lds_bytes(a);
+    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true><<<grid, block, lds, stream>>>(a);
+    else conv1x1_stream_kernel<NS, NG, WAVES, false><<<grid, block, lds, stream>>>(a);
+    return hipGetLastError();
+}
+
+template <int WAVES>
+hipError_t launch_conv1x1_stream_t(const ConvArgs &a, hipStream_t stream) {
+    if (conv_check(a) || !conv1x1_stream_applies(a)) return hipErrorInvalidValue;
+    const int key = (a.Cin / 64) * 10 + a.Cout / 64;
+    switch (key) {
+    case 11: return launch_stream<1, 1, WAVES>(a, stream);
+    case 12: return launch_stream<1, 2, WAVES>(a, stream);
+    case 14: return launch_stream<1, 4, WAVES>(a, stream);
+    case 21: return launch_stream<2, 1, WAVES>(a, stream);
+    case 22: return launch_stream<2, 2, WAVES>(a, stream);
+    case 41: return launch_stream<4, 1, WAVES>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream) {
+    // Workgroups share one staged copy of the weights, so larger ones stage less; small
+    // problems keep small workgroups so that every CU still gets one.
+    const long long tiles = ((long long)a.M + 31) / 32;
+    if (tiles >= 2048) return launch_conv1x1_stream_t<16>(a, stream);
+    if (tiles >= 1024) return launch_conv1x1_stream_t<8>(a, stream);
+    return launch_conv1x1_stream_t<4>(a, stream);
+}
+
+}  // namespace delta

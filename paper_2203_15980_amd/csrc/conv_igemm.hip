@@ -40,10 +40,12 @@ static constexpr int kThreads = 256;
 static constexpr int kRowBytes = 128;   // bytes of the reduction axis per LDS row and slice
 static constexpr int kRowPitch = 144;   // padded pitch: 16 consecutive rows hit 64 distinct banks
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
@@ -259,14 +261,14 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
                 }
                 if (a.relu) {
 #pragma unroll
-                    for (int e = 0; e < CPL; ++e) v[e] = v[e] > 0.f ? v[e] : (v[e] != v[e] ? v[e] : 0.f);
+                    for (int e = 0; e < CPL; ++e) v[e] = v[e] < 0.f ? 0.f : v[e];   // NaN stays NaN
                 }
                 u32x4 o;
                 if constexpr (BF16) {
-                    o.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
-                    o.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
-                    o.z = f32_to_bf16_rne(v[4]) | (f32_to_bf16_rne(v[5]) << 16);
-                    o.w = f32_to_bf16_rne(v[6]) | (f32_to_bf16_rne(v[7]) << 16);
+                    o.x = pack_bf16(v[0], v[1]);
+                    o.y = pack_bf16(v[2], v[3]);
+                    o.z = pack_bf16(v[4], v[5]);
+                    o.w = pack_bf16(v[6], v[7]);
                 } else {
                     o.x = __float_as_uint(v[0]); o.y = __float_as_uint(v[1]);
                     o.z = __float_as_uint(v[2]); o.w = __float_as_uint(v[3]);
@@ -287,6 +289,7 @@ static hipError_t launch(const ConvArgs &a, hipStream_t stream) {
 }
 
 const char *conv_kernel_name(const ConvArgs &a) {
+    if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
     const int bn = a.Cout % 256 == 0 ? 256 : (a.Cout % 128 == 0 ? 128 : 64);
     static const char *names[2][3] = {{"conv_igemm f32 128x64", "conv_igemm f32 128x128", "conv_igemm f32 128x256"},
                                       {"conv_igemm bf16 128x64", "conv_igemm bf16 128x128", "conv_igemm bf16 128x256"}};
@@ -314,6 +317,7 @@ const char *conv_check(const ConvArgs &a) {
 
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
     if (conv_check(a)) return hipErrorInvalidValue;
+    if (conv1x1_stream_applies(a)) return launch_conv1x1_stream(a, stream);
     const int bn = a.Cout % 256 == 0 ? 256 : (a.Cout % 128 == 0 ? 128 : 64);
     if (a.bf16) {
         if (bn == 256) return launch<true, 128, 256, 4, 1>(a, stream);

@@ -21,6 +21,9 @@ struct ConvArgs {
 const char *conv_check(const ConvArgs &a);
 const char *conv_kernel_name(const ConvArgs &a);
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream);
+// conv1x1.hip: streaming kernel for bf16 1x1 convolutions whose weights fit LDS
+bool conv1x1_stream_applies(const ConvArgs &a);
+hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_bn_fold(const float *gamma, const float *beta, const float *mean, const float *var,
                           float eps, unsigned C, float *scale, float *shift, hipStream_t stream);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
