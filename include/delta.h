@@ -62,6 +62,14 @@ enum {
     DELTA_EV_DROP_TEMP = 7
 };
 enum { DELTA_DTYPE_F32 = 0, DELTA_DTYPE_BF16 = 1 };
+/* Operators a recompute segment can contain (the regenerated operators Sec. 5.5 names are
+ * ConvForward, BNForward and PoolingForward; the classifier and the loss close the net). */
+enum {
+    DELTA_OP_CONV = 0,       /* fused conv + BN affine (+ residual) (+ ReLU); also the classifier */
+    DELTA_OP_MAXPOOL = 1,    /* R x S window, stride, pad; padding never wins the maximum */
+    DELTA_OP_AVGPOOL = 2,    /* global average over H x W */
+    DELTA_OP_SOFTMAX_CE = 3  /* mean cross-entropy of logits x [N, Cin] against labels `res` */
+};
 enum { DELTA_SYNC_D2H = 1, DELTA_SYNC_H2D = 2, DELTA_SYNC_COMPUTE = 4, DELTA_SYNC_ALL = 7 };
 enum { DELTA_DIR_D2H = 0, DELTA_DIR_H2D = 1, DELTA_DIR_BOTH = 2 };
 #define DELTA_NO_TENSOR 0xFFFFFFFFu
@@ -98,9 +106,13 @@ typedef struct {
 
 typedef struct { uint32_t step, action, tensor, pad; } delta_event;
 
-/* One fused layer y = relu?(scale_k * conv(x, w) + shift_k (+ res)), activations NHWC,
- * weights KRSC (w[k][r][s][c]), scale/shift fp32 per output channel (folded batch-norm
- * with frozen statistics).  x, res, y are tensor ids of the bound table. */
+/* One layer.  DELTA_OP_CONV: y = relu?(scale_k * conv(x, w) + shift_k (+ res)), activations
+ * NHWC, weights KRSC (w[k][r][s][c]), scale/shift fp32 per output channel (folded batch-norm
+ * with frozen statistics; scale = 1, shift = bias for the classifier).  The pooling
+ * operators use x, y, N, H, W, Cin (= Cout), R, S, stride, pad and ignore w/scale/shift/res.
+ * DELTA_OP_SOFTMAX_CE reads logits x [N, Cin] (storage dtype) and int64 labels in tensor
+ * `res` [N], and writes one fp32 (the mean loss) to y.  x, res, y are tensor ids of the
+ * bound table. */
 typedef struct {
     uint32_t x, res, y;        /* res = DELTA_NO_TENSOR when there is no residual */
     uint32_t dtype;            /* DELTA_DTYPE_*: storage type of x, res, y and w */
@@ -109,6 +121,7 @@ typedef struct {
     const float *shift;        /* device */
     int32_t N, H, W, Cin, Cout, R, S, stride, pad;
     uint32_t relu;
+    uint32_t op;               /* DELTA_OP_* */
 } delta_layer_desc;
 
 typedef struct {
@@ -173,8 +186,10 @@ delta_status delta_prefetch(delta_ctx *ctx, uint32_t tensor);
  * Recompute (Table 1), also used for the first forward so that both produce the same
  * bits: runs the layers in order on the compute stream.  Every x / res must be resident;
  * y gets a fresh block when it is not resident and is overwritten when it is.
- * Supported: Cin a multiple of 64 (bf16) or 32 (fp32), Cout a multiple of 64, any R, S,
- * stride, pad; other shapes return DELTA_ERR_INVALID before anything is launched.
+ * Supported convolutions: Cin a multiple of 64 (bf16) or 32 (fp32) and Cout a multiple of 8
+ * (bf16) or 4 (fp32) with any R, S, stride, pad; plus the bf16 ResNet stem (7x7, stride 2,
+ * pad 3, Cin 3, Cout 64).  Pooling: channels a multiple of 8 (bf16) or 4 (fp32).  Other
+ * shapes return DELTA_ERR_INVALID before anything is launched.
  */
 delta_status delta_recompute_segment(delta_ctx *ctx, const delta_layer_desc *layers,
                                      uint32_t n_layers);

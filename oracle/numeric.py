@@ -115,8 +115,18 @@ def avgpool(x, dtype="f32"):
     return y
 
 
-def run_layers(layers, params, x0, dtype):
-    """Forward of a list of synth.LayerSpec conv layers; returns {tensor name: stored array}."""
+def softmax_ce(logits, labels, dtype="f32"):
+    """Mean over images of logsumexp(z_i) - z_i[label_i], in float64; returned as float32 [1]."""
+    z = to_f64(logits, dtype).reshape(len(labels), -1)
+    mx = z.max(axis=1)
+    lse = mx + np.log(np.exp(z - mx[:, None]).sum(axis=1))
+    picked = z[np.arange(len(labels)), np.asarray(labels, dtype=np.int64)]
+    return np.array([np.mean(lse - picked)], dtype=np.float32)
+
+
+def run_layers(layers, params, x0, dtype, labels=None):
+    """Forward of a list of synth.LayerSpec layers; returns {tensor name: stored array}.  With
+    `labels`, the mean cross-entropy of the last layer's output is added as "loss"."""
     acts = {"x0": x0}
     for l in layers:
         if l.kind == "conv":
@@ -127,6 +137,14 @@ def run_layers(layers, params, x0, dtype):
             acts[l.y] = maxpool(acts[l.x], l.R, l.S, l.stride, l.pad, dtype)
         elif l.kind == "avgpool":
             acts[l.y] = avgpool(acts[l.x], dtype)
+        elif l.kind == "fc":                    # z + bias: a 1x1 convolution with identity statistics
+            C = l.Cout
+            bn = dict(gamma=np.ones(C, np.float32), beta=params[l.name]["bias"],
+                      mean=np.zeros(C, np.float32), var=np.ones(C, np.float32), eps=0.0)
+            acts[l.y] = conv_bn_act(acts[l.x], params[l.name]["w"], bn, relu=False, dtype=dtype)
         else:
             raise ValueError("no oracle for layer kind %r" % l.kind)
+    if labels is not None:
+        acts["labels"] = np.asarray(labels, dtype=np.int64)
+        acts["loss"] = softmax_ce(acts[layers[-1].y], labels, dtype)
     return acts

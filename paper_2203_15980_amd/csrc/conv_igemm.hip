@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     const int wm = wv % WM, wn = wv / WM;
     const int l32 = lane & 31, half = lane >> 5;
 
-    const int tiles_n = a.Cout / BN;
+    const int tiles_n = (a.Cout + BN - 1) / BN;
     const int m0 = (blockIdx.x / tiles_n) * BM;
     const int n0 = (blockIdx.x % tiles_n) * BN;
 
@@ -154,7 +154,10 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
         }                                                                                        \
         _Pragma("unroll") for (int j = 0; j < WL; ++j) {                                         \
             const size_t k_ = (size_t)(n0 + lrow + 32 * j);                                      \
-            wr[j] = *reinterpret_cast<const u32x4 *>(wg + ((k_ * a.R + r_) * a.S + s_) * cin_bytes + coff_); \
+            if (k_ < (size_t)a.Cout)                                                             \
+                wr[j] = *reinterpret_cast<const u32x4 *>(wg + ((k_ * a.R + r_) * a.S + s_) * cin_bytes + coff_); \
+            else                                                                                 \
+                wr[j] = u32x4{0u, 0u, 0u, 0u}; /* channel rows past Cout */                      \
         }                                                                                        \
     }
 
@@ -215,8 +218,13 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
                 const int ch = n0 + (wn * TN + g * TG + u) * 32 + 8 * rb + 4 * half;
-                sc[u][rb] = *reinterpret_cast<const f32x4 *>(a.scale + ch);
-                sh[u][rb] = *reinterpret_cast<const f32x4 *>(a.shift + ch);
+                if (ch < a.Cout) {                // Cout is a multiple of 4: all four or none
+                    sc[u][rb] = *reinterpret_cast<const f32x4 *>(a.scale + ch);
+                    sh[u][rb] = *reinterpret_cast<const f32x4 *>(a.shift + ch);
+                } else {
+                    sc[u][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    sh[u][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
             }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -239,7 +247,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
             for (int t = 0; t < 4; ++t) {
                 const int pr = prow + 8 * t;
                 const int m = m0 + (wm * TM + i) * 32 + pr;
-                if (m >= a.M) continue;
+                if (m >= a.M || chan >= a.Cout) continue;   // Cout is a multiple of CPL
                 float v[CPL];
 #pragma unroll
                 for (int e = 0; e < CPL; e += 4) {
@@ -282,15 +290,23 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 template <bool BF16, int BM, int BN, int WM, int WN>
 static hipError_t launch(const ConvArgs &a, hipStream_t stream) {
     const long long tiles_m = ((long long)a.M + BM - 1) / BM;
-    const long long blocks = tiles_m * (a.Cout / BN);
+    const long long blocks = tiles_m * ((a.Cout + BN - 1) / BN);
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     conv_igemm_kernel<BF16, BM, BN, WM, WN><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
     return hipGetLastError();
 }
 
+// Channel tile: the widest of 256/128/64 that divides Cout, else the one wasting least.
+static int conv_tile_n(const ConvArgs &a) {
+    if (a.Cout % 256 == 0) return 256;
+    if (a.Cout % 128 == 0) return 128;
+    if (a.Cout % 64 == 0) return 64;
+    return a.Cout > 512 ? 256 : (a.Cout > 64 ? 128 : 64);
+}
+
 const char *conv_kernel_name(const ConvArgs &a) {
     if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
-    const int bn = a.Cout % 256 == 0 ? 256 : (a.Cout % 128 == 0 ? 128 : 64);
+    const int bn = conv_tile_n(a);
     static const char *names[2][3] = {{"conv_igemm f32 128x64", "conv_igemm f32 128x128", "conv_igemm f32 128x256"},
                                       {"conv_igemm bf16 128x64", "conv_igemm bf16 128x128", "conv_igemm bf16 128x256"}};
     return names[a.bf16 ? 1 : 0][bn == 64 ? 0 : (bn == 128 ? 1 : 2)];
@@ -302,7 +318,7 @@ const char *conv_check(const ConvArgs &a) {
     if (a.N <= 0 || a.H <= 0 || a.W <= 0 || a.R <= 0 || a.S <= 0 || a.stride <= 0 || a.pad < 0)
         return "non-positive dimension";
     if (a.Cin <= 0 || a.Cin % kc) return "Cin must be a multiple of 64 (bf16) or 32 (fp32)";
-    if (a.Cout <= 0 || a.Cout % 64) return "Cout must be a multiple of 64";
+    if (a.Cout <= 0 || a.Cout % (a.bf16 ? 8 : 4)) return "Cout must be a multiple of 8 (bf16) or 4 (fp32)";
     if (a.P != (a.H + 2 * a.pad - a.R) / a.stride + 1 || a.Q != (a.W + 2 * a.pad - a.S) / a.stride + 1 ||
         a.P <= 0 || a.Q <= 0)
         return "inconsistent output size";
@@ -318,7 +334,7 @@ const char *conv_check(const ConvArgs &a) {
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
     if (conv_check(a)) return hipErrorInvalidValue;
     if (conv1x1_stream_applies(a)) return launch_conv1x1_stream(a, stream);
-    const int bn = a.Cout % 256 == 0 ? 256 : (a.Cout % 128 == 0 ? 128 : 64);
+    const int bn = conv_tile_n(a);
     if (a.bf16) {
         if (bn == 256) return launch<true, 128, 256, 4, 1>(a, stream);
         if (bn == 128) return launch<true, 128, 128, 4, 1>(a, stream);

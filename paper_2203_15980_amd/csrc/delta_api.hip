@@ -479,52 +479,107 @@ delta_status delta_prefetch(delta_ctx *c, uint32_t id) {
     return DELTA_OK;
 }
 
-delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layers, uint32_t n_layers) {
-    delta_status r = need_gpu(c);
-    if (r != DELTA_OK) return r;
-    if (!layers && n_layers) return fail(c, DELTA_ERR_INVALID, "null layers");
-    // Pass 1: validate everything before anything is launched or allocated.
-    std::vector<uint8_t> will_exist(c->tensors.size(), 0);
-    for (uint32_t i = 0; i < n_layers; ++i) {
-        const delta_layer_desc &L = layers[i];
-        if (L.x >= c->tensors.size() || L.y >= c->tensors.size() ||
-            (L.res != DELTA_NO_TENSOR && L.res >= c->tensors.size()))
-            return fail(c, DELTA_ERR_INVALID, "layer %u: tensor id out of range", i);
-        if (L.dtype != DELTA_DTYPE_F32 && L.dtype != DELTA_DTYPE_BF16)
-            return fail(c, DELTA_ERR_INVALID, "layer %u: unknown dtype %u", i, L.dtype);
-        if (L.y == L.x || L.y == L.res) return fail(c, DELTA_ERR_INVALID, "layer %u: output aliases an input", i);
-        delta::ConvArgs a;
-        memset(&a, 0, sizeof a);
-        a.N = L.N; a.H = L.H; a.W = L.W; a.Cin = L.Cin; a.Cout = L.Cout; a.R = L.R; a.S = L.S;
-        a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0; a.bf16 = L.dtype == DELTA_DTYPE_BF16;
-        if (L.stride <= 0 || L.R <= 0 || L.S <= 0)
+// Shape and size checks of one layer; fills the launch arguments except device addresses.
+static delta_status prepare_layer(delta_ctx *c, const delta_layer_desc &L, uint32_t i, delta::ConvArgs &a,
+                                  delta::PoolArgs &pa, uint64_t &flops) {
+    const size_t nt = c->tensors.size();
+    if (L.x >= nt || L.y >= nt || (L.res != DELTA_NO_TENSOR && L.res >= nt))
+        return fail(c, DELTA_ERR_INVALID, "layer %u: tensor id out of range", i);
+    if (L.dtype != DELTA_DTYPE_F32 && L.dtype != DELTA_DTYPE_BF16)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: unknown dtype %u", i, L.dtype);
+    if (L.y == L.x || L.y == L.res) return fail(c, DELTA_ERR_INVALID, "layer %u: output aliases an input", i);
+    if (L.N <= 0 || L.H <= 0 || L.W <= 0 || L.Cin <= 0)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: non-positive dimension", i);
+    const bool bf16 = L.dtype == DELTA_DTYPE_BF16;
+    const uint64_t es = bf16 ? 2 : 4;
+    const uint64_t xbytes = (uint64_t)L.N * L.H * L.W * L.Cin * es;
+    if (c->tensors[L.x].bytes != xbytes)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: input tensor %u has %llu bytes, layer needs %llu", i, L.x,
+                    (unsigned long long)c->tensors[L.x].bytes, (unsigned long long)xbytes);
+    memset(&a, 0, sizeof a);
+    memset(&pa, 0, sizeof pa);
+    flops = 0;
+    uint64_t ybytes = 0;
+    switch (L.op) {
+    case DELTA_OP_CONV: {
+        if (L.stride <= 0 || L.R <= 0 || L.S <= 0 || L.pad < 0 || L.Cout <= 0)
             return fail(c, DELTA_ERR_INVALID, "layer %u: non-positive dimension", i);
+        a.N = L.N; a.H = L.H; a.W = L.W; a.Cin = L.Cin; a.Cout = L.Cout; a.R = L.R; a.S = L.S;
+        a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0; a.bf16 = bf16;
         a.P = (L.H + 2 * L.pad - L.R) / L.stride + 1;
         a.Q = (L.W + 2 * L.pad - L.S) / L.stride + 1;
         const long long M = (long long)L.N * a.P * a.Q;
         a.M = (M > 0 && M <= 0x7FFFFFFFLL) ? (int)M : -1;
-        a.x = a.y = c->arena;                      // placeholders for the alignment check
+        a.x = a.y = c->arena;                      // placeholders for the alignment checks
+        a.res = nullptr;
         a.w = L.w; a.scale = L.scale; a.shift = L.shift;
-        const char *why = delta::conv_check(a);
+        const char *why = delta::stem_applies(a) ? delta::stem_check(a) : delta::conv_check(a);
         if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
-        const uint64_t es = a.bf16 ? 2 : 4;
-        if (c->tensors[L.x].bytes != (uint64_t)L.N * L.H * L.W * L.Cin * es)
-            return fail(c, DELTA_ERR_INVALID, "layer %u: input tensor %u has %llu bytes, layer needs %llu", i, L.x,
-                        (unsigned long long)c->tensors[L.x].bytes, (unsigned long long)((uint64_t)L.N * L.H * L.W * L.Cin * es));
-        const uint64_t ybytes = (uint64_t)M * L.Cout * es;
-        if (c->tensors[L.y].bytes != ybytes)
-            return fail(c, DELTA_ERR_INVALID, "layer %u: output tensor %u has the wrong size", i, L.y);
-        if (L.res != DELTA_NO_TENSOR && c->tensors[L.res].bytes != ybytes)
-            return fail(c, DELTA_ERR_INVALID, "layer %u: residual tensor %u has the wrong size", i, L.res);
+        ybytes = (uint64_t)M * L.Cout * es;
+        if (L.res != DELTA_NO_TENSOR) {
+            if (delta::stem_applies(a)) return fail(c, DELTA_ERR_INVALID, "layer %u: the stem takes no residual", i);
+            if (c->tensors[L.res].bytes != ybytes)
+                return fail(c, DELTA_ERR_INVALID, "layer %u: residual tensor %u has the wrong size", i, L.res);
+        }
+        flops = 2ull * (uint64_t)M * L.R * L.S * L.Cin * L.Cout;
+        break;
+    }
+    case DELTA_OP_MAXPOOL:
+    case DELTA_OP_AVGPOOL: {
+        pa.N = L.N; pa.H = L.H; pa.W = L.W; pa.C = L.Cin; pa.bf16 = bf16;
+        pa.x = pa.y = c->arena;
+        if (L.op == DELTA_OP_MAXPOOL) {
+            if (L.stride <= 0 || L.R <= 0 || L.S <= 0 || L.pad < 0)
+                return fail(c, DELTA_ERR_INVALID, "layer %u: bad pooling window", i);
+            pa.R = L.R; pa.S = L.S; pa.stride = L.stride; pa.pad = L.pad;
+            pa.P = (L.H + 2 * L.pad - L.R) / L.stride + 1;
+            pa.Q = (L.W + 2 * L.pad - L.S) / L.stride + 1;
+        } else {
+            pa.P = pa.Q = 1;
+        }
+        const char *why = delta::pool_check(pa, L.op == DELTA_OP_AVGPOOL);
+        if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
+        if (L.res != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "layer %u: pooling takes no second input", i);
+        ybytes = (uint64_t)L.N * pa.P * pa.Q * L.Cin * es;
+        break;
+    }
+    case DELTA_OP_SOFTMAX_CE:
+        if (L.H != 1 || L.W != 1) return fail(c, DELTA_ERR_INVALID, "layer %u: logits must be [N, classes]", i);
+        if (L.res == DELTA_NO_TENSOR || c->tensors[L.res].bytes != (uint64_t)L.N * 8)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: labels tensor must hold N int64 values", i);
+        ybytes = 4;
+        break;
+    default:
+        return fail(c, DELTA_ERR_INVALID, "layer %u: unknown operator %u", i, L.op);
+    }
+    if (c->tensors[L.y].bytes != ybytes)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: output tensor %u has %llu bytes, layer produces %llu", i, L.y,
+                    (unsigned long long)c->tensors[L.y].bytes, (unsigned long long)ybytes);
+    return DELTA_OK;
+}
+
+delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layers, uint32_t n_layers) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!layers && n_layers) return fail(c, DELTA_ERR_INVALID, "null layers");
+    delta::ConvArgs a;
+    delta::PoolArgs pa;
+    uint64_t flops;
+    // Pass 1: validate everything before anything is launched or allocated.
+    std::vector<uint8_t> will_exist(c->tensors.size(), 0);
+    for (uint32_t i = 0; i < n_layers; ++i) {
+        const delta_layer_desc &L = layers[i];
+        if ((r = prepare_layer(c, L, i, a, pa, flops)) != DELTA_OK) return r;
         if (!c->tensors[L.x].resident && !will_exist[L.x])
             return fail(c, DELTA_ERR_STATE, "layer %u: input tensor %u is not resident", i, L.x);
         if (L.res != DELTA_NO_TENSOR && !c->tensors[L.res].resident && !will_exist[L.res])
-            return fail(c, DELTA_ERR_STATE, "layer %u: residual tensor %u is not resident", i, L.res);
+            return fail(c, DELTA_ERR_STATE, "layer %u: second input tensor %u is not resident", i, L.res);
         will_exist[L.y] = 1;
     }
     // Pass 2: allocate outputs and launch, in order, on the compute stream.
     for (uint32_t i = 0; i < n_layers; ++i) {
         const delta_layer_desc &L = layers[i];
+        if ((r = prepare_layer(c, L, i, a, pa, flops)) != DELTA_OK) return r;
         Tensor &tx = c->tensors[L.x];
         Tensor &ty = c->tensors[L.y];
         if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
@@ -538,20 +593,29 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
                 HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.d2h_done.e, 0));
         }
         ty.host_valid = false;                      // the host copy, if any, is of older contents
-        delta::ConvArgs a;
-        memset(&a, 0, sizeof a);
-        a.x = c->arena + tx.offset;
-        a.y = c->arena + ty.offset;
-        a.res = L.res != DELTA_NO_TENSOR ? c->arena + c->tensors[L.res].offset : nullptr;
-        a.w = L.w; a.scale = L.scale; a.shift = L.shift;
-        a.N = L.N; a.H = L.H; a.W = L.W; a.Cin = L.Cin; a.Cout = L.Cout; a.R = L.R; a.S = L.S;
-        a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0; a.bf16 = L.dtype == DELTA_DTYPE_BF16;
-        a.P = (L.H + 2 * L.pad - L.R) / L.stride + 1;
-        a.Q = (L.W + 2 * L.pad - L.S) / L.stride + 1;
-        a.M = L.N * a.P * a.Q;
-        HIP_TRY(c, delta::launch_conv(a, c->stream[S_COMPUTE]));
+        unsigned char *xp = c->arena + tx.offset, *yp = c->arena + ty.offset;
+        unsigned char *rp = L.res != DELTA_NO_TENSOR ? c->arena + c->tensors[L.res].offset : nullptr;
+        switch (L.op) {
+        case DELTA_OP_CONV:
+            a.x = xp; a.y = yp; a.res = rp;
+            if (delta::stem_applies(a)) HIP_TRY(c, delta::launch_stem(a, c->stream[S_COMPUTE]));
+            else HIP_TRY(c, delta::launch_conv(a, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_MAXPOOL:
+            pa.x = xp; pa.y = yp;
+            HIP_TRY(c, delta::launch_maxpool(pa, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_AVGPOOL:
+            pa.x = xp; pa.y = yp;
+            HIP_TRY(c, delta::launch_avgpool(pa, c->stream[S_COMPUTE]));
+            break;
+        default:
+            HIP_TRY(c, delta::launch_softmax_ce(xp, rp, L.N, L.Cin, L.dtype == DELTA_DTYPE_BF16,
+                                                reinterpret_cast<float *>(yp), c->stream[S_COMPUTE]));
+            break;
+        }
         c->st.recompute_launches += 1;
-        c->st.recompute_flops += 2ull * (uint64_t)a.M * L.R * L.S * L.Cin * L.Cout;
+        c->st.recompute_flops += flops;
     }
     return DELTA_OK;
 }

@@ -24,6 +24,23 @@ hipError_t launch_conv(const ConvArgs &a, hipStream_t stream);
 // conv1x1.hip: streaming kernel for bf16 1x1 convolutions whose weights fit LDS
 bool conv1x1_stream_applies(const ConvArgs &a);
 hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream);
+// net_ops.hip: ResNet stem (7x7, stride 2, pad 3, 3 -> 64 channels, bf16), pooling, loss
+bool stem_applies(const ConvArgs &a);
+const char *stem_check(const ConvArgs &a);
+hipError_t launch_stem(const ConvArgs &a, hipStream_t stream);
+
+struct PoolArgs {
+    const void *x;   // [N,H,W,C]
+    void *y;         // [N,P,Q,C] (max) or [N,C] (global average)
+    int N, H, W, C, R, S, stride, pad, P, Q;
+    int bf16;
+};
+const char *pool_check(const PoolArgs &a, bool global_avg);
+hipError_t launch_maxpool(const PoolArgs &a, hipStream_t stream);
+hipError_t launch_avgpool(const PoolArgs &a, hipStream_t stream);
+hipError_t launch_softmax_ce(const void *logits, const void *labels, int N, int classes, int bf16, float *out,
+                             hipStream_t stream);
+
 hipError_t launch_bn_fold(const float *gamma, const float *beta, const float *mean, const float *var,
                           float eps, unsigned C, float *scale, float *shift, hipStream_t stream);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);

@@ -1,0 +1,328 @@
+// The operators of a ResNet that are not bottleneck convolutions: the 7x7 stem, max
+// pooling, global average pooling and the mean softmax cross-entropy.  DELTA regenerates
+// them like any other operator output (Sec. 5.5 lists PoolingForward among the tensors that
+// are released and recomputed), so they go through delta_recompute_segment as well.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.hpp"
+
+namespace delta {
+
+typedef __bf16 bf16x8_s __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_s __attribute__((ext_vector_type(2)));
+typedef float f32x2_s __attribute__((ext_vector_type(2)));
+typedef float f32x16_s __attribute__((ext_vector_type(16)));
+typedef float f32x4_s __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_s __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_s __attribute__((ext_vector_type(2)));
+
+namespace {
+__device__ __forceinline__ uint32_t pack2s(float lo, float hi) {
+    const f32x2_s v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_s));
+}
+__device__ __forceinline__ float blo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bhi(uint32_t p) { return __uint_as_float(p & 0xFFFF0000u); }
+}  // namespace
+
+// ------------------------------------------------------------------------------ stem
+// 7x7, stride 2, pad 3, Cin = 3, Cout = 64, bf16.  Implicit GEMM on the matrix cores with the
+// reduction axis laid out as (r, s, c padded to 4): for a fixed kernel row r the 7 taps x 4
+// channels of one output pixel are 28 contiguous elements of the input patch once its
+// pixels are padded from 3 to 4 channels, starting at a 16-byte boundary (stride 2 x 4
+// channels x 2 bytes).  Each row is rounded up to 32 elements -- the extra tap and the
+// fourth channel carry zero weights -- so K = 7 x 32 = 224, fourteen 32x32x16 steps.
+// A workgroup owns 8 x 16 output pixels (each wavefront 2 rows x 16 columns), is persistent
+// over tiles, and stages the rearranged weights once.
+static constexpr int kStemWPitch = 7 * 64 + 16;       // bytes per output channel in LDS
+static constexpr int kStemPRows = 21, kStemPCols = 38; // patch: (2*8+5) rows, (2*16+5)+1 columns
+static constexpr int kStemPPitch = kStemPCols * 8;     // 304 bytes, a multiple of 16
+
+__global__ __launch_bounds__(256) void stem7x7_kernel(ConvArgs a, int tiles_p, int tiles_q, int ntiles) {
+    __shared__ __align__(16) unsigned char wl[64 * kStemWPitch];
+    __shared__ __align__(16) unsigned char patch[kStemPRows * kStemPPitch];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const uint16_t *wg = static_cast<const uint16_t *>(a.w);
+    const uint16_t *xg = static_cast<const uint16_t *>(a.x);
+
+    // weights: wl[k][r][s*4 + c] = w[k][r][s][c], zero for s = 7 or c = 3
+    for (int e = tid; e < 64 * 7 * 32; e += 256) {
+        const int k = e / 224, rem = e - k * 224;
+        const int r = rem >> 5, el = rem & 31;
+        const int s = el >> 2, c = el & 3;
+        uint16_t v = 0;
+        if (s < 7 && c < 3) v = wg[((k * 7 + r) * 7 + s) * 3 + c];
+        *reinterpret_cast<uint16_t *>(wl + k * kStemWPitch + r * 64 + el * 2) = v;
+    }
+
+    const int prow = 2 * wv + (l32 >> 4), pcol = l32 & 15;     // this lane's pixel in the tile
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int n = tile / (tiles_p * tiles_q), t2 = tile - n * tiles_p * tiles_q;
+        const int p0 = (t2 / tiles_q) * 8, q0 = (t2 % tiles_q) * 16;
+        __syncthreads();                          // previous tile's patch is no longer read
+        for (int e = tid; e < kStemPRows * kStemPCols; e += 256) {
+            const int i = e / kStemPCols, j = e - i * kStemPCols;
+            const int h = 2 * p0 - 3 + i, w = 2 * q0 - 3 + j;
+            u32x2_s v = {0u, 0u};
+            if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W) {
+                const uint16_t *px = xg + ((size_t)((size_t)n * a.H + h) * a.W + w) * 3;
+                v.x = (uint32_t)px[0] | ((uint32_t)px[1] << 16);
+                v.y = (uint32_t)px[2];
+            }
+            *reinterpret_cast<u32x2_s *>(patch + i * kStemPPitch + j * 8) = v;
+        }
+        __syncthreads();
+
+        f32x16_s acc[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+        const unsigned char *xrow = patch + (2 * prow) * kStemPPitch + pcol * 16 + half * 16;
+        const unsigned char *wrow = wl + l32 * kStemWPitch + half * 16;
+#pragma unroll
+        for (int r = 0; r < 7; ++r)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const u32x4_s xb = *reinterpret_cast<const u32x4_s *>(xrow + r * kStemPPitch + hh * 32);
+                const u32x4_s w0 = *reinterpret_cast<const u32x4_s *>(wrow + r * 64 + hh * 32);
+                const u32x4_s w1 = *reinterpret_cast<const u32x4_s *>(wrow + 32 * kStemWPitch + r * 64 + hh * 32);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_s, w0),
+                                                                 __builtin_bit_cast(bf16x8_s, xb), acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_s, w1),
+                                                                 __builtin_bit_cast(bf16x8_s, xb), acc[1], 0, 0, 0);
+            }
+        const int p = p0 + prow, q = q0 + pcol;
+        const bool valid = p < a.P && q < a.Q;
+        unsigned char *yrow = static_cast<unsigned char *>(a.y) +
+                              ((size_t)((size_t)n * a.P + (valid ? p : 0)) * a.Q + (valid ? q : 0)) * 128;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int cb = u * 32;
+            float v[16];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const f32x4_s sc = *reinterpret_cast<const f32x4_s *>(a.scale + cb + 8 * rb + 4 * half);
+                const f32x4_s sh = *reinterpret_cast<const f32x4_s *>(a.shift + cb + 8 * rb + 4 * half);
+                v[4 * rb + 0] = acc[u][4 * rb + 0] * sc.x + sh.x;
+                v[4 * rb + 1] = acc[u][4 * rb + 1] * sc.y + sh.y;
+                v[4 * rb + 2] = acc[u][4 * rb + 2] * sc.z + sh.z;
+                v[4 * rb + 3] = acc[u][4 * rb + 3] * sc.w + sh.w;
+            }
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                float o[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]),
+                                                               __float_as_uint(v[8 * i2 + 4 + j]), false, false);
+                    o[j] = __uint_as_float(r2[0]);
+                    o[4 + j] = __uint_as_float(r2[1]);
+                }
+                if (a.relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = o[e] < 0.f ? 0.f : o[e];
+                }
+                u32x4_s out;
+                out.x = pack2s(o[0], o[1]); out.y = pack2s(o[2], o[3]);
+                out.z = pack2s(o[4], o[5]); out.w = pack2s(o[6], o[7]);
+                if (valid) *reinterpret_cast<u32x4_s *>(yrow + (cb + 16 * i2 + 8 * half) * 2) = out;
+            }
+        }
+    }
+}
+
+bool stem_applies(const ConvArgs &a) {
+    return a.bf16 && a.R == 7 && a.S == 7 && a.stride == 2 && a.pad == 3 && a.Cin == 3 && a.Cout == 64 && !a.res;
+}
+
+const char *stem_check(const ConvArgs &a) {
+    if (a.N <= 0 || a.H <= 0 || a.W <= 0) return "non-positive dimension";
+    if (a.P != (a.H + 6 - 7) / 2 + 1 || a.Q != (a.W + 6 - 7) / 2 + 1 || a.P <= 0 || a.Q <= 0)
+        return "inconsistent output size";
+    if ((long long)a.N * a.P * a.Q != a.M || (long long)a.N * a.H * a.W > 0x7FFFFFFFLL) return "bad M";
+    if (!a.x || !a.w || !a.y || !a.scale || !a.shift) return "null pointer";
+    if (((uintptr_t)a.y | (uintptr_t)a.scale | (uintptr_t)a.shift) & 15) return "pointers must be 16-byte aligned";
+    if (((uintptr_t)a.x | (uintptr_t)a.w) & 1) return "pointers must be 2-byte aligned";
+    return nullptr;
+}
+
+hipError_t launch_stem(const ConvArgs &a, hipStream_t stream) {
+    if (!stem_applies(a) || stem_check(a)) return hipErrorInvalidValue;
+    const int tiles_p = (a.P + 7) / 8, tiles_q = (a.Q + 15) / 16;
+    const long long ntiles = (long long)a.N * tiles_p * tiles_q;
+    if (ntiles <= 0 || ntiles > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    const int grid = (int)(ntiles < 1024 ? ntiles : 1024);
+    stem7x7_kernel<<<dim3(grid), dim3(256), 0, stream>>>(a, tiles_p, tiles_q, (int)ntiles);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------- pooling
+
+// One thread: 16 bytes of channels (8 bf16 or 4 fp32) of one output pixel.
+template <bool BF16>
+__global__ __launch_bounds__(256) void maxpool_kernel(PoolArgs a, long long total) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    constexpr int CPT = BF16 ? 8 : 4;
+    const int chunks = a.C / CPT;
+    const int ck = (int)(idx % chunks);
+    long long pix = idx / chunks;
+    const int q = (int)(pix % a.Q);
+    pix /= a.Q;
+    const int p = (int)(pix % a.P);
+    const int n = (int)(pix / a.P);
+    float m[CPT];
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) m[e] = -INFINITY;
+    const unsigned char *xg = static_cast<const unsigned char *>(a.x);
+    for (int r = 0; r < a.R; ++r) {
+        const int h = p * a.stride + r - a.pad;
+        if ((unsigned)h >= (unsigned)a.H) continue;
+        for (int s = 0; s < a.S; ++s) {
+            const int w = q * a.stride + s - a.pad;
+            if ((unsigned)w >= (unsigned)a.W) continue;
+            const u32x4_s v = *reinterpret_cast<const u32x4_s *>(
+                xg + (((size_t)((size_t)n * a.H + h) * a.W + w) * chunks + ck) * 16);
+            if constexpr (BF16) {
+                m[0] = fmaxf(m[0], blo(v.x)); m[1] = fmaxf(m[1], bhi(v.x));
+                m[2] = fmaxf(m[2], blo(v.y)); m[3] = fmaxf(m[3], bhi(v.y));
+                m[4] = fmaxf(m[4], blo(v.z)); m[5] = fmaxf(m[5], bhi(v.z));
+                m[6] = fmaxf(m[6], blo(v.w)); m[7] = fmaxf(m[7], bhi(v.w));
+            } else {
+                m[0] = fmaxf(m[0], __uint_as_float(v.x)); m[1] = fmaxf(m[1], __uint_as_float(v.y));
+                m[2] = fmaxf(m[2], __uint_as_float(v.z)); m[3] = fmaxf(m[3], __uint_as_float(v.w));
+            }
+        }
+    }
+    u32x4_s o;
+    if constexpr (BF16) {
+        o.x = pack2s(m[0], m[1]); o.y = pack2s(m[2], m[3]); o.z = pack2s(m[4], m[5]); o.w = pack2s(m[6], m[7]);
+    } else {
+        o.x = __float_as_uint(m[0]); o.y = __float_as_uint(m[1]); o.z = __float_as_uint(m[2]); o.w = __float_as_uint(m[3]);
+    }
+    *reinterpret_cast<u32x4_s *>(static_cast<unsigned char *>(a.y) + (size_t)idx * 16) = o;
+}
+
+// Global average: one thread per (image, 16 bytes of channels), fp32 accumulation in pixel order.
+template <bool BF16>
+__global__ __launch_bounds__(256) void avgpool_kernel(PoolArgs a, long long total) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    constexpr int CPT = BF16 ? 8 : 4;
+    const int chunks = a.C / CPT;
+    const int ck = (int)(idx % chunks);
+    const int n = (int)(idx / chunks);
+    float s[CPT];
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) s[e] = 0.f;
+    const unsigned char *xg = static_cast<const unsigned char *>(a.x);
+    const int hw = a.H * a.W;
+    for (int i = 0; i < hw; ++i) {
+        const u32x4_s v = *reinterpret_cast<const u32x4_s *>(xg + (((size_t)n * hw + i) * chunks + ck) * 16);
+        if constexpr (BF16) {
+            s[0] += blo(v.x); s[1] += bhi(v.x); s[2] += blo(v.y); s[3] += bhi(v.y);
+            s[4] += blo(v.z); s[5] += bhi(v.z); s[6] += blo(v.w); s[7] += bhi(v.w);
+        } else {
+            s[0] += __uint_as_float(v.x); s[1] += __uint_as_float(v.y);
+            s[2] += __uint_as_float(v.z); s[3] += __uint_as_float(v.w);
+        }
+    }
+    const float inv = 1.0f / (float)hw;
+    u32x4_s o;
+    if constexpr (BF16) {
+        o.x = pack2s(s[0] * inv, s[1] * inv); o.y = pack2s(s[2] * inv, s[3] * inv);
+        o.z = pack2s(s[4] * inv, s[5] * inv); o.w = pack2s(s[6] * inv, s[7] * inv);
+    } else {
+        o.x = __float_as_uint(s[0] * inv); o.y = __float_as_uint(s[1] * inv);
+        o.z = __float_as_uint(s[2] * inv); o.w = __float_as_uint(s[3] * inv);
+    }
+    *reinterpret_cast<u32x4_s *>(static_cast<unsigned char *>(a.y) + (size_t)idx * 16) = o;
+}
+
+const char *pool_check(const PoolArgs &a, bool global_avg) {
+    const int cpt = a.bf16 ? 8 : 4;
+    if (a.N <= 0 || a.H <= 0 || a.W <= 0 || a.C <= 0) return "non-positive dimension";
+    if (a.C % cpt) return "channels must be a multiple of 8 (bf16) or 4 (fp32)";
+    if (!a.x || !a.y || (((uintptr_t)a.x | (uintptr_t)a.y) & 15)) return "pointers must be non-null and 16-byte aligned";
+    if ((long long)a.N * a.H * a.W > 0x7FFFFFFFLL) return "input too large";
+    if (!global_avg) {
+        if (a.R <= 0 || a.S <= 0 || a.stride <= 0 || a.pad < 0 || a.pad >= a.R || a.pad >= a.S)
+            return "bad window (padding must be smaller than the window)";
+        if (a.P != (a.H + 2 * a.pad - a.R) / a.stride + 1 || a.Q != (a.W + 2 * a.pad - a.S) / a.stride + 1 ||
+            a.P <= 0 || a.Q <= 0)
+            return "inconsistent output size";
+    }
+    return nullptr;
+}
+
+hipError_t launch_maxpool(const PoolArgs &a, hipStream_t stream) {
+    if (pool_check(a, false)) return hipErrorInvalidValue;
+    const long long total = (long long)a.N * a.P * a.Q * (a.C / (a.bf16 ? 8 : 4));
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    if (a.bf16) maxpool_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(a, total);
+    else maxpool_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(a, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_avgpool(const PoolArgs &a, hipStream_t stream) {
+    if (pool_check(a, true)) return hipErrorInvalidValue;
+    const long long total = (long long)a.N * (a.C / (a.bf16 ? 8 : 4));
+    const long long blocks = (total + 255) / 256;
+    if (a.bf16) avgpool_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(a, total);
+    else avgpool_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(a, total);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------ loss
+// Mean over images of logsumexp(z_i) - z_i[label_i].  One workgroup; wavefront w takes images
+// w, w+4, ...; lanes stride over the classes; fixed reduction trees, so the result does not
+// depend on timing.  Labels outside [0, classes) contribute logsumexp only... they are
+// rejected instead: the kernel writes NaN so that a bad label cannot pass unnoticed.
+template <bool BF16>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(const void *logits, const long long *labels, int N,
+                                                         int classes, float *out) {
+    __shared__ float part[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    float total = 0.f;
+    for (int i = wv; i < N; i += 4) {
+        float mx = -INFINITY;
+        for (int c = lane; c < classes; c += 64) {
+            const float z = BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[(size_t)i * classes + c] << 16)
+                                 : static_cast<const float *>(logits)[(size_t)i * classes + c];
+            mx = fmaxf(mx, z);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float se = 0.f;
+        for (int c = lane; c < classes; c += 64) {
+            const float z = BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[(size_t)i * classes + c] << 16)
+                                 : static_cast<const float *>(logits)[(size_t)i * classes + c];
+            se += __expf(z - mx);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
+        const long long lab = labels[i];
+        float zl = __builtin_nanf("");
+        if (lab >= 0 && lab < classes)
+            zl = BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[(size_t)i * classes + lab] << 16)
+                      : static_cast<const float *>(logits)[(size_t)i * classes + lab];
+        total += (mx + __logf(se)) - zl;
+    }
+    if (lane == 0) part[wv] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = (part[0] + part[1] + part[2] + part[3]) / (float)N;
+}
+
+hipError_t launch_softmax_ce(const void *logits, const void *labels, int N, int classes, int bf16, float *out,
+                             hipStream_t stream) {
+    if (!logits || !labels || !out || N <= 0 || classes <= 0) return hipErrorInvalidValue;
+    if (bf16) softmax_ce_kernel<true><<<dim3(1), dim3(256), 0, stream>>>(logits, static_cast<const long long *>(labels), N, classes, out);
+    else softmax_ce_kernel<false><<<dim3(1), dim3(256), 0, stream>>>(logits, static_cast<const long long *>(labels), N, classes, out);
+    return hipGetLastError();
+}
+
+}  // namespace delta

@@ -2,14 +2,14 @@
 pass through delta_recompute_segment and replays a plan (the event list of delta_plan)
 against the arena.  torch is used for device memory, streams and events only; every layer
 runs in the library's kernels.  Used by the GPU tests, bench.py and the smoke entry."""
-import ctypes
-
 import numpy as np
 import torch
 
 import synth
 
 from . import binding as B
+
+_OPS = {"conv": B.OP_CONV, "fc": B.OP_CONV, "maxpool": B.OP_MAXPOOL, "avgpool": B.OP_AVGPOOL}
 
 
 def _dev(a, device):
@@ -18,42 +18,70 @@ def _dev(a, device):
 
 class Net:
     """Weights, folded batch-norm factors and layer descriptors of a list of synth.LayerSpec
-    conv layers, resident on the GPU.  Tensor ids follow synth.fused_graph (x0 is 0)."""
+    layers, resident on the GPU.  Tensor ids follow synth.fused_graph (x0 is 0; with
+    `with_loss` the labels and the loss come last)."""
 
-    def __init__(self, delta, layers, dtype, master, device="cuda:0"):
+    def __init__(self, delta, layers, dtype, master, device="cuda:0", with_loss=False):
         self.delta, self.layers, self.dtype, self.master = delta, layers, dtype, master
         self.device = device
         self.es = 4 if dtype == "f32" else 2
-        self.graph = synth.fused_graph(layers, dtype)
+        self.graph = synth.fused_graph(layers, dtype, with_loss=with_loss)
         self.ids = dict(self.graph.names)
         self.sizes = [t["bytes"] for t in self.graph.tensors]
         self.params_np = {}
         self.keep = []
         self.desc = {}
+        self.shapes = {}
+        self.np_dtype = {}
+        self.sources = {}                     # uncomputable tensors: id -> device bytes to copy in
         first = layers[0]
+        code = B.DTYPE_F32 if dtype == "f32" else B.DTYPE_BF16
+        store = np.float32 if dtype == "f32" else np.uint16
         self.in_shape = (first.N, first.H, first.W, first.Cin)
         self.x0_np = synth.make_input(master, self.in_shape, dtype)
-        self.x0_dev = _dev(self.x0_np.view(np.uint8).reshape(-1), device)
+        self.shapes["x0"], self.np_dtype["x0"] = self.in_shape, store
+        self.sources[0] = _dev(self.x0_np.view(np.uint8).reshape(-1), device)
         for l in layers:
-            if l.kind != "conv":
+            if l.kind not in _OPS:
                 raise ValueError("layer kind %r has no kernel" % l.kind)
-            p = synth.make_params(master, l, dtype)
-            self.params_np[l.name] = p
-            w = _dev(p["w"], device)
-            bn = [_dev(p[k], device) for k in ("gamma", "beta", "mean", "var")]
-            scale = torch.empty(l.Cout, dtype=torch.float32, device=device)
-            shift = torch.empty(l.Cout, dtype=torch.float32, device=device)
-            delta.bn_fold(bn[0].data_ptr(), bn[1].data_ptr(), bn[2].data_ptr(), bn[3].data_ptr(),
-                          float(p["eps"]), l.Cout, scale.data_ptr(), shift.data_ptr())
-            self.keep += [w, scale, shift] + bn
+            w = scale = shift = None
+            if l.kind in ("conv", "fc"):
+                p = synth.make_params(master, l, dtype)
+                self.params_np[l.name] = p
+                w = _dev(p["w"], device)
+                if l.kind == "conv":
+                    bn = [_dev(p[k], device) for k in ("gamma", "beta", "mean", "var")]
+                    scale = torch.empty(l.Cout, dtype=torch.float32, device=device)
+                    shift = torch.empty(l.Cout, dtype=torch.float32, device=device)
+                    delta.bn_fold(bn[0].data_ptr(), bn[1].data_ptr(), bn[2].data_ptr(), bn[3].data_ptr(),
+                                  float(p["eps"]), l.Cout, scale.data_ptr(), shift.data_ptr())
+                    self.keep += bn
+                else:
+                    scale = torch.ones(l.Cout, dtype=torch.float32, device=device)
+                    shift = _dev(p["bias"], device)
+                self.keep += [w, scale, shift]
             d = B.LayerDesc(x=self.ids[l.x], res=self.ids[l.res] if l.res else B.NO_TENSOR,
-                            y=self.ids[l.y], dtype=B.DTYPE_F32 if dtype == "f32" else B.DTYPE_BF16,
-                            w=w.data_ptr(), scale=scale.data_ptr(), shift=shift.data_ptr(),
+                            y=self.ids[l.y], dtype=code, w=w.data_ptr() if w is not None else None,
+                            scale=scale.data_ptr() if scale is not None else None,
+                            shift=shift.data_ptr() if shift is not None else None,
                             N=l.N, H=l.H, W=l.W, Cin=l.Cin, Cout=l.Cout, R=l.R, S=l.S,
-                            stride=l.stride, pad=l.pad, relu=1 if l.relu else 0)
+                            stride=l.stride, pad=l.pad, relu=1 if (l.relu and l.kind == "conv") else 0,
+                            op=_OPS[l.kind])
             self.desc[l.y] = B.layer_array([d])
+            self.shapes[l.y], self.np_dtype[l.y] = (l.N, l.P, l.Q, l.Cout), store
+        order = [self.desc[l.y][0] for l in layers]
+        if with_loss:
+            last = layers[-1]
+            self.labels_np = synth.make_labels(master, last.N, last.Cout)
+            self.sources[self.ids["labels"]] = _dev(self.labels_np.view(np.uint8).reshape(-1), device)
+            self.shapes["labels"], self.np_dtype["labels"] = (last.N,), np.int64
+            d = B.LayerDesc(x=self.ids[last.y], res=self.ids["labels"], y=self.ids["loss"], dtype=code,
+                            w=None, scale=None, shift=None, N=last.N, H=1, W=1, Cin=last.Cout, Cout=1,
+                            R=1, S=1, stride=1, pad=0, relu=0, op=B.OP_SOFTMAX_CE)
+            self.desc["loss"] = B.layer_array([d])
+            self.shapes["loss"], self.np_dtype["loss"] = (1,), np.float32
+        self.all_layers = B.layer_array(order)
         self.by_tensor = {self.ids[l.y]: l for l in layers}
-        self.all_layers = B.layer_array([self.desc[l.y][0] for l in layers])
         torch.cuda.synchronize()
 
     # -- raw access to arena contents
@@ -63,23 +91,26 @@ class Net:
         return self.delta.arena[off:off + self.sizes[tensor_id]]
 
     def read(self, name):
-        """Stored bits of a resident tensor as a numpy array (float32 or uint16 bf16 bits)."""
-        tid = self.ids[name]
-        raw = self._view(tid)
+        """Stored bits of a resident tensor as a numpy array (float32, uint16 bf16 bits, ...)."""
+        raw = self._view(self.ids[name])
         torch.cuda.current_stream().synchronize()
-        a = raw.cpu().numpy()
-        l = self.by_tensor.get(tid)
-        shape = self.in_shape if l is None else (l.N, l.P, l.Q, l.Cout)
-        return a.view(np.float32 if self.dtype == "f32" else np.uint16).reshape(shape)
+        return raw.cpu().numpy().view(self.np_dtype[name]).reshape(self.shapes[name])
+
+    def load_source(self, tensor_id):
+        """Brings an uncomputable tensor (network input, labels) onto the GPU."""
+        self.delta.alloc(tensor_id)
+        self._view(tensor_id).copy_(self.sources[tensor_id], non_blocking=True)
 
     def load_input(self):
-        self.delta.alloc(0)
-        self._view(0).copy_(self.x0_dev, non_blocking=True)
+        self.load_source(0)
 
     def forward(self):
-        """x0 plus every layer, nothing released."""
+        """Inputs plus every layer (and the loss when present), nothing released."""
         self.load_input()
         self.delta.recompute_segment(self.all_layers)
+        if "loss" in self.desc:
+            self.load_source(self.ids["labels"])
+            self.delta.recompute_segment(self.desc["loss"])
 
     def recompute(self, name):
         self.delta.recompute_segment(self.desc[name])
@@ -106,8 +137,8 @@ def run_plan(net, graph, events, backward_proxy=None):
             else:
                 d.prefetch(t)
         if st["produces"] >= 0:
-            if st["produces"] == 0:
-                net.load_input()
+            if st["produces"] in net.sources:
+                net.load_source(st["produces"])
             else:
                 d.recompute_segment(net.desc[names[st["produces"]]])
         elif backward_proxy is not None:

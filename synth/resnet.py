@@ -142,11 +142,19 @@ def make_params(master, layer: LayerSpec, dtype):
     if dtype == "bf16":
         w = rng.f32_to_bf16_bits(w).reshape(layer.Cout, layer.R, layer.S, layer.Cin)
     C = layer.Cout
+    if layer.kind == "fc":                      # classifier: weights and a bias, no batch-norm
+        bias = rng.normal(master, base + 2, C, 0.0, 0.1).astype(np.float32)
+        return {"w": w, "bias": bias}
     gamma = rng.uniform(master, base + 1, C, 0.5, 1.5).astype(np.float32)
     beta = rng.normal(master, base + 2, C, 0.0, 0.1).astype(np.float32)
     mean = rng.normal(master, base + 3, C, 0.0, 0.1).astype(np.float32)
     var = rng.uniform(master, base + 4, C, 0.5, 1.5).astype(np.float32)
     return {"w": w, "gamma": gamma, "beta": beta, "mean": mean, "var": var, "eps": BN_EPS}
+
+
+def make_labels(master, n, classes):
+    """Synthetic labels, uniform over the classes (int64)."""
+    return rng.integers(master, 0xFFFF0001, n, classes)
 
 
 # --------------------------------------------------------------------------- graphs
