@@ -171,9 +171,20 @@ class Delta:
         return (self.lib.delta_last_error(self.ctx) or b"").decode()
 
     # -- planning
+    def prepare_graph(self, tensors, steps):
+        """Marshals a graph once; pass the result to plan() in place of (tensors, steps)."""
+        td, sd, _, keep = _marshal_graph(tensors, steps, dict.fromkeys([k for k, _ in PlanParams._fields_], 0))
+        return ("prepared", td, sd, keep, len(tensors), len(steps))
+
     def plan(self, tensors, steps, params):
-        """Returns (events, peak): events as (step, action, tensor) tuples."""
-        td, sd, pp, keep = _marshal_graph(tensors, steps, params)
+        """Returns (events, peak): events as (step, action, tensor) tuples.  `tensors` may be
+        the result of prepare_graph() (then `steps` is ignored)."""
+        if isinstance(tensors, tuple) and tensors and tensors[0] == "prepared":
+            _, td, sd, keep, nt, ns = tensors
+            pp = PlanParams(**{k: int(params[k]) for k, _ in PlanParams._fields_})
+            tensors, steps = range(nt), range(ns)
+        else:
+            td, sd, pp, keep = _marshal_graph(tensors, steps, params)
         cap = 64 + 8 * (len(tensors) + len(steps))
         while True:
             ev = (Event * cap)()
