@@ -79,7 +79,7 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool BF16, int BM, int BN, int WM, int WN>
+template <bool BF16, int BM, int BN, int WM, int WN, int NSL>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     using E = Elem<BF16>;
     constexpr int ES = E::size;
@@ -91,23 +91,34 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     constexpr int XL = BM / 32;                // 16-byte loads per thread and slice, activations
     constexpr int WL = BN / 32;                // same, weights
     constexpr int STG_PITCH = CW * 4 + 16;
-    constexpr int TILE_BYTES = (BM + BN) * kRowPitch;
+    // NSL slices of 128 bytes are staged together; the pitch keeps rows 4 banks apart
+    constexpr int PITCH = NSL * kRowBytes + 16;
+    constexpr int TILE_BYTES = (BM + BN) * PITCH;
     constexpr int STG_BYTES = 4 * 32 * STG_PITCH;
     constexpr int SMEM = TILE_BYTES > STG_BYTES ? TILE_BYTES : STG_BYTES;
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && TN % TG == 0, "bad tiling");
 
     __shared__ __align__(16) unsigned char smem[SMEM];
     unsigned char *xs = smem;
-    unsigned char *ws = smem + BM * kRowPitch;
+    unsigned char *ws = smem + BM * PITCH;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
     const int wm = wv % WM, wn = wv / WM;
     const int l32 = lane & 31, half = lane >> 5;
 
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
+    // contiguous run of logical tiles (channel tile fastest), so that the channel tiles of one
+    // pixel tile, and neighbouring pixel tiles with their shared halo, meet in the same L2.
+    unsigned logical;
+    {
+        const unsigned nb = gridDim.x, per = nb >> 3, rem = nb & 7u;
+        const unsigned xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
+        logical = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    }
     const int tiles_n = (a.Cout + BN - 1) / BN;
-    const int m0 = (blockIdx.x / tiles_n) * BM;
-    const int n0 = (blockIdx.x % tiles_n) * BN;
+    const int m0 = (int)(logical / tiles_n) * BM;
+    const int n0 = (int)(logical % tiles_n) * BN;
 
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const unsigned char *wg = static_cast<const unsigned char *>(a.w);
@@ -135,29 +146,39 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     const int cslices = a.Cin / KC;
     const int nslices = a.R * a.S * cslices;
 
-    u32x4 xr[XL], wr[WL];
-#define DELTA_FETCH(IT)                                                                          \
-    {                                                                                            \
-        const int tap_ = (IT) / cslices, cs_ = (IT) - tap_ * cslices;                            \
-        const int r_ = tap_ / a.S, s_ = tap_ - r_ * a.S;                                         \
-        const size_t coff_ = (size_t)cs_ * kRowBytes + seg * 16;                                 \
-        _Pragma("unroll") for (int i = 0; i < XL; ++i) {                                         \
-            const int h_ = h0[i] + r_, w_ = w0[i] + s_;                                          \
-            const bool ok_ = nrow[i] >= 0 && (unsigned)h_ < (unsigned)a.H &&                     \
-                             (unsigned)w_ < (unsigned)a.W;                                       \
-            if (ok_) {                                                                           \
-                const size_t pix_ = (size_t)(nrow[i] + h_) * a.W + w_;                           \
-                xr[i] = *reinterpret_cast<const u32x4 *>(xg + pix_ * cin_bytes + coff_);         \
-            } else {                                                                             \
-                xr[i] = u32x4{0u, 0u, 0u, 0u}; /* zero padding / rows past M */                 \
+    const int nstages = (nslices + NSL - 1) / NSL;
+
+    u32x4 xr[NSL][XL], wr[NSL][WL];
+    // global -> registers for stage ST (slices ST*NSL ...); slices past the end load zeros
+#define DELTA_FETCH(ST)                                                                          \
+    _Pragma("unroll") for (int sl_ = 0; sl_ < NSL; ++sl_) {                                      \
+        const int it_ = (ST) * NSL + sl_;                                                        \
+        if (it_ < nslices) {                                                                     \
+            const int tap_ = it_ / cslices, cs_ = it_ - tap_ * cslices;                          \
+            const int r_ = tap_ / a.S, s_ = tap_ - r_ * a.S;                                     \
+            const size_t coff_ = (size_t)cs_ * kRowBytes + seg * 16;                             \
+            _Pragma("unroll") for (int i = 0; i < XL; ++i) {                                     \
+                const int h_ = h0[i] + r_, w_ = w0[i] + s_;                                      \
+                const bool ok_ = nrow[i] >= 0 && (unsigned)h_ < (unsigned)a.H &&                 \
+                                 (unsigned)w_ < (unsigned)a.W;                                   \
+                if (ok_) {                                                                       \
+                    const size_t pix_ = (size_t)(nrow[i] + h_) * a.W + w_;                       \
+                    xr[sl_][i] = *reinterpret_cast<const u32x4 *>(xg + pix_ * cin_bytes + coff_); \
+                } else {                                                                         \
+                    xr[sl_][i] = u32x4{0u, 0u, 0u, 0u}; /* zero padding / rows past M */         \
+                }                                                                                \
             }                                                                                    \
-        }                                                                                        \
-        _Pragma("unroll") for (int j = 0; j < WL; ++j) {                                         \
-            const size_t k_ = (size_t)(n0 + lrow + 32 * j);                                      \
-            if (k_ < (size_t)a.Cout)                                                             \
-                wr[j] = *reinterpret_cast<const u32x4 *>(wg + ((k_ * a.R + r_) * a.S + s_) * cin_bytes + coff_); \
-            else                                                                                 \
-                wr[j] = u32x4{0u, 0u, 0u, 0u}; /* channel rows past Cout */                      \
+            _Pragma("unroll") for (int j = 0; j < WL; ++j) {                                     \
+                const size_t k_ = (size_t)(n0 + lrow + 32 * j);                                  \
+                if (k_ < (size_t)a.Cout)                                                         \
+                    wr[sl_][j] = *reinterpret_cast<const u32x4 *>(                               \
+                        wg + ((k_ * a.R + r_) * a.S + s_) * cin_bytes + coff_);                  \
+                else                                                                             \
+                    wr[sl_][j] = u32x4{0u, 0u, 0u, 0u}; /* channel rows past Cout */             \
+            }                                                                                    \
+        } else {                                                                                 \
+            _Pragma("unroll") for (int i = 0; i < XL; ++i) xr[sl_][i] = u32x4{0u, 0u, 0u, 0u};   \
+            _Pragma("unroll") for (int j = 0; j < WL; ++j) wr[sl_][j] = u32x4{0u, 0u, 0u, 0u};   \
         }                                                                                        \
     }
 
@@ -171,29 +192,32 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 
 #define DELTA_STAGE()                                                                             \
     {                                                                                            \
-        __syncthreads(); /* previous slice fully consumed */                                     \
-        _Pragma("unroll") for (int i = 0; i < XL; ++i)                                           \
-            *reinterpret_cast<u32x4 *>(xs + (lrow + 32 * i) * kRowPitch + seg * 16) = xr[i];     \
-        _Pragma("unroll") for (int j = 0; j < WL; ++j)                                           \
-            *reinterpret_cast<u32x4 *>(ws + (lrow + 32 * j) * kRowPitch + seg * 16) = wr[j];     \
+        __syncthreads(); /* previous stage fully consumed */                                     \
+        _Pragma("unroll") for (int sl_ = 0; sl_ < NSL; ++sl_) {                                  \
+            _Pragma("unroll") for (int i = 0; i < XL; ++i)                                       \
+                *reinterpret_cast<u32x4 *>(xs + (lrow + 32 * i) * PITCH + sl_ * kRowBytes + seg * 16) = xr[sl_][i]; \
+            _Pragma("unroll") for (int j = 0; j < WL; ++j)                                       \
+                *reinterpret_cast<u32x4 *>(ws + (lrow + 32 * j) * PITCH + sl_ * kRowBytes + seg * 16) = wr[sl_][j]; \
+        }                                                                                        \
         __syncthreads();                                                                         \
     }
 #define DELTA_MMA()                                                                               \
+    _Pragma("unroll") for (int sl_ = 0; sl_ < NSL; ++sl_)                                        \
     _Pragma("unroll") for (int j16 = 0; j16 < 4; ++j16) {                                        \
-        const int koff = half * 64 + j16 * 16;                                                   \
+        const int koff = sl_ * kRowBytes + half * 64 + j16 * 16;                                 \
         u32x4 xf[TM], wf[TN];                                                                    \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-            xf[i] = *reinterpret_cast<const u32x4 *>(xs + ((wm * TM + i) * 32 + l32) * kRowPitch + koff); \
+            xf[i] = *reinterpret_cast<const u32x4 *>(xs + ((wm * TM + i) * 32 + l32) * PITCH + koff); \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
-            wf[j] = *reinterpret_cast<const u32x4 *>(ws + ((wn * TN + j) * 32 + l32) * kRowPitch + koff); \
+            wf[j] = *reinterpret_cast<const u32x4 *>(ws + ((wn * TN + j) * 32 + l32) * PITCH + koff); \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
             _Pragma("unroll") for (int j = 0; j < TN; ++j) mma16<BF16>(wf[j], xf[i], acc[i][j]); \
     }
 
     DELTA_FETCH(0)
-    for (int it = 0; it + 1 < nslices; ++it) {
+    for (int st = 0; st + 1 < nstages; ++st) {
         DELTA_STAGE()
-        DELTA_FETCH(it + 1)                       // in flight while the MFMAs below run
+        DELTA_FETCH(st + 1)                       // in flight while the MFMAs below run
         DELTA_MMA()
     }
     DELTA_STAGE()
@@ -287,29 +311,30 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     }
 }
 
-template <bool BF16, int BM, int BN, int WM, int WN>
+template <bool BF16, int BM, int BN, int WM, int WN, int NSL = 1>
 static hipError_t launch(const ConvArgs &a, hipStream_t stream) {
     const long long tiles_m = ((long long)a.M + BM - 1) / BM;
     const long long blocks = tiles_m * ((a.Cout + BN - 1) / BN);
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    conv_igemm_kernel<BF16, BM, BN, WM, WN><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
+    conv_igemm_kernel<BF16, BM, BN, WM, WN, NSL><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
     return hipGetLastError();
 }
 
-// Channel tile: the widest of 256/128/64 that divides Cout, else the one wasting least.
+// Channel tile: 128 when it divides Cout or wastes little, else 64.  Measured on MI355X,
+// 128 pixels x 128 channels with 2 x 2 wavefronts (64 x 64 each) and two reduction slices
+// per stage beats the wider tiles: the loop is bound by the latency of the global -> LDS
+// path, and the smaller register footprint lets two workgroups share a CU.
 static int conv_tile_n(const ConvArgs &a) {
-    if (a.Cout % 256 == 0) return 256;
     if (a.Cout % 128 == 0) return 128;
     if (a.Cout % 64 == 0) return 64;
-    return a.Cout > 512 ? 256 : (a.Cout > 64 ? 128 : 64);
+    return a.Cout > 64 ? 128 : 64;
 }
 
 const char *conv_kernel_name(const ConvArgs &a) {
     if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
     const int bn = conv_tile_n(a);
-    static const char *names[2][3] = {{"conv_igemm f32 128x64", "conv_igemm f32 128x128", "conv_igemm f32 128x256"},
-                                      {"conv_igemm bf16 128x64", "conv_igemm bf16 128x128", "conv_igemm bf16 128x256"}};
-    return names[a.bf16 ? 1 : 0][bn == 64 ? 0 : (bn == 128 ? 1 : 2)];
+    if (a.bf16) return bn == 128 ? "conv_igemm bf16 128x128 (2x2 waves, 2 slices)" : "conv_igemm bf16 128x64 (4x1 waves, 2 slices)";
+    return bn == 128 ? "conv_igemm f32 128x128 (2x2 waves)" : "conv_igemm f32 128x64 (4x1 waves)";
 }
 
 // Host-side shape check; the kernel assumes exactly this.
@@ -336,13 +361,11 @@ hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
     if (conv1x1_stream_applies(a)) return launch_conv1x1_stream(a, stream);
     const int bn = conv_tile_n(a);
     if (a.bf16) {
-        if (bn == 256) return launch<true, 128, 256, 4, 1>(a, stream);
-        if (bn == 128) return launch<true, 128, 128, 4, 1>(a, stream);
-        return launch<true, 128, 64, 4, 1>(a, stream);
+        if (bn == 128) return launch<true, 128, 128, 2, 2, 2>(a, stream);
+        return launch<true, 128, 64, 4, 1, 2>(a, stream);
     }
-    if (bn == 256) return launch<false, 128, 256, 4, 1>(a, stream);
-    if (bn == 128) return launch<false, 128, 128, 4, 1>(a, stream);
-    return launch<false, 128, 64, 4, 1>(a, stream);
+    if (bn == 128) return launch<false, 128, 128, 2, 2, 1>(a, stream);
+    return launch<false, 128, 64, 4, 1, 1>(a, stream);
 }
 
 // ---------------------------------------------------------------- small helpers
