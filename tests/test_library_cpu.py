@@ -128,3 +128,14 @@ def test_plan_rejects_malformed_graphs():
     with pytest.raises(dl.DeltaError) as e:
         dl.plan(g.tensors, g.steps, dict(p, trigger_den=0))
     assert e.value.status == dl.ERR_INVALID
+
+
+def test_heuristic_sweep_reproduces_the_papers_ordering():
+    """Sec. 5.7 / Fig. 7-8 (qualitative): at small budgets base and LRU get by with less memory
+    than GREEDY on ResNet-50, and LRU moves more tensors than base."""
+    from paper_2203_15980_amd import sweep
+    res = sweep.run(configs=(3,), fracs=(0.5,))["config3"]
+    assert res["base"]["min_budget_frac"] <= res["greedy"]["min_budget_frac"]
+    assert res["lru"]["min_budget_frac"] <= res["greedy"]["min_budget_frac"]
+    moved = lambda r: r["at"]["0.5"]["evict"] + r["at"]["0.5"]["offload"]
+    assert moved(res["lru"]) >= moved(res["base"])
