@@ -79,6 +79,13 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime.  It must be the one already mapped when libdelta.so is
+    # loaded, so that the arena pointers and streams torch hands over belong to the same
+    # runtime instance as the library's own HIP calls.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("%s is missing: build it with `python -m paper_2203_15980_amd.build` "
                            "(there is no CPU fallback)" % LIB_PATH)

@@ -185,3 +185,34 @@ def test_softmax_ce_matches_oracle(torch_mod):
         got = float(d.arena[ptr - base:ptr - base + 4].cpu().numpy().view(np.float32)[0])
         assert abs(got - ref) <= 1e-5 * abs(ref), (dtype, got, ref)
         d.close()
+
+
+def test_config3_full_size_sampled_image(torch_mod):
+    """Config 3 at full size (ResNet-50, batch 128, 224x224x3: the launch shapes bench.py
+    replays).  Frozen batch-norm makes images independent, so the oracle runs the last image
+    alone and is compared with that image of the full-batch GPU forward, layer by layer."""
+    from paper_2203_15980_amd.harness import Net
+    torch = torch_mod
+    N = 128
+    layers = synth.resnet_layers(N)
+    g = synth.fused_graph(layers, "bf16", with_loss=True)
+    d = make_delta(torch, g.total_bytes() + (64 << 20))
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", synth.master_seed(3), with_loss=True)
+    net.forward()
+    d.sync()
+    one = synth.resnet_layers(1)
+    x1 = np.ascontiguousarray(net.x0_np[N - 1:N])
+    print("oracle on one 224x224 image ...", flush=True)
+    ref = on.run_layers(one, net.params_np, x1, "bf16")
+    worst = 0.0
+    for l in layers:
+        got = net.read(l.y)[N - 1:N]
+        e = rel_err(got, ref[l.y], "bf16")
+        worst = max(worst, e)
+        assert e <= 2e-2, (l.y, e)
+    print("worst layer error %.3g" % worst, flush=True)
+    loss = float(net.read("loss")[0])
+    want = float(on.softmax_ce(net.read("logits"), net.labels_np, "bf16")[0])    # all 128 images
+    assert np.isfinite(loss) and abs(loss - want) <= 1e-4 * abs(want), (loss, want)
+    d.close()
