@@ -132,6 +132,7 @@ typedef struct {
     uint64_t recompute_launches, recompute_flops;
     uint64_t releases_evict, releases_offload, releases_free;
     uint64_t pinned_bytes;
+    uint64_t arena_extent_high_water;      /* highest arena offset ever handed out (fragmentation) */
 } delta_stats_t;
 
 /* Creates a context on the current HIP device.  arena_dev: device, 256-byte aligned,

@@ -58,7 +58,8 @@ class Stats(C.Structure):
                 ("h2d_copies", C.c_uint64), ("d2h_ms", C.c_double), ("h2d_ms", C.c_double),
                 ("recompute_launches", C.c_uint64), ("recompute_flops", C.c_uint64),
                 ("releases_evict", C.c_uint64), ("releases_offload", C.c_uint64),
-                ("releases_free", C.c_uint64), ("pinned_bytes", C.c_uint64)]
+                ("releases_free", C.c_uint64), ("pinned_bytes", C.c_uint64),
+                ("arena_extent_high_water", C.c_uint64)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -177,31 +177,51 @@ delta_status sync_all(delta_ctx *c) {
 
 Ev later(const Ev &a, const Ev &b) { return a.seq > b.seq ? a : b; }
 
+// Best fit, preferring blocks nobody is still touching: a block whose fences of the other
+// streams have all completed can be written at once, while a block that an Offload copy is
+// still reading would stall the stream that receives it (the 1/4 of the budget that the
+// early start of Sec. 4.3 keeps free is what makes such a choice possible).
 delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t *off) {
     const uint64_t need = (bytes + kAlign - 1) / kAlign * kAlign;
+    std::map<uint64_t, Block>::iterator pick = c->free_blocks.end();
+    bool pick_idle = false;
     for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it) {
         if (it->second.size < need) continue;
-        const uint64_t o = it->first;
-        Block b = it->second;
-        c->free_blocks.erase(it);
-        if (b.size > need) {
-            Block rest;
-            rest.size = b.size - need;
-            rest.fence = b.fence;
-            c->free_blocks[o + need] = rest;
+        bool idle = true;
+        for (int s = 0; s < N_STREAMS; ++s) {
+            Ev &f = it->second.fence.ev[s];
+            if (s == for_stream || !f) continue;
+            if (hipEventQuery(f.e) == hipSuccess) f = Ev();     // done: forget the fence
+            else { idle = false; (void)hipGetLastError(); }    // hipErrorNotReady is not an error here
         }
-        for (int s = 0; s < N_STREAMS; ++s)
-            if (s != for_stream && b.fence.ev[s])
-                HIP_TRY(c, hipStreamWaitEvent(c->stream[for_stream], b.fence.ev[s].e, 0));
-        c->used[o] = need;
-        c->st.arena_in_use += need;
-        if (c->st.arena_in_use > c->st.arena_high_water) c->st.arena_high_water = c->st.arena_in_use;
-        *off = o;
-        return DELTA_OK;
+        if (pick == c->free_blocks.end() || (idle && !pick_idle) ||
+            (idle == pick_idle && it->second.size < pick->second.size)) {
+            pick = it;
+            pick_idle = idle;
+        }
     }
-    return fail(c, DELTA_ERR_OOM_ARENA, "no arena block of %llu bytes (in use %llu of %llu)",
-                (unsigned long long)need, (unsigned long long)c->st.arena_in_use,
-                (unsigned long long)c->arena_bytes);
+    if (pick == c->free_blocks.end())
+        return fail(c, DELTA_ERR_OOM_ARENA, "no arena block of %llu bytes (in use %llu of %llu)",
+                    (unsigned long long)need, (unsigned long long)c->st.arena_in_use,
+                    (unsigned long long)c->arena_bytes);
+    const uint64_t o = pick->first;
+    Block b = pick->second;
+    c->free_blocks.erase(pick);
+    if (b.size > need) {
+        Block rest;
+        rest.size = b.size - need;
+        rest.fence = b.fence;
+        c->free_blocks[o + need] = rest;
+    }
+    for (int s = 0; s < N_STREAMS; ++s)
+        if (s != for_stream && b.fence.ev[s])
+            HIP_TRY(c, hipStreamWaitEvent(c->stream[for_stream], b.fence.ev[s].e, 0));
+    c->used[o] = need;
+    c->st.arena_in_use += need;
+    if (c->st.arena_in_use > c->st.arena_high_water) c->st.arena_high_water = c->st.arena_in_use;
+    if (o + need > c->st.arena_extent_high_water) c->st.arena_extent_high_water = o + need;
+    *off = o;
+    return DELTA_OK;
 }
 
 void arena_free(delta_ctx *c, uint64_t off, const Fence &f) {
@@ -661,6 +681,8 @@ delta_status delta_stats_reset(delta_ctx *c) {
     memset(&c->st, 0, sizeof c->st);
     c->st.arena_bytes = ab;
     c->st.arena_in_use = c->st.arena_high_water = iu;
+    for (std::map<uint64_t, uint64_t>::iterator u = c->used.begin(); u != c->used.end(); ++u)
+        if (u->first + u->second > c->st.arena_extent_high_water) c->st.arena_extent_high_water = u->first + u->second;
     c->st.pinned_bytes = pb;
     return DELTA_OK;
 }
