@@ -171,8 +171,8 @@ def test_recompute_is_bit_identical_to_forward(torch_mod):
         old_ptr = {n: d.tensor_ptr(net.ids[n]) for n in ("b1.a1", "b1.a2", "b2.a1")}
         for n in ("b1.a1", "b1.a2", "b1.sc", "b2.a1", "b2.a2", "b3.a1"):
             d.release(net.ids[n], dl.EV_EVICT)
-        # occupy the first hole so that recomputed tensors land at different addresses
-        for n in ("b3.a1", "b2.a1", "b2.a2", "b1.a1", "b1.a2", "b1.sc"):
+        # best fit sends b1.a1 into the hole b3.a1 left and b1.a2 into b2's: new addresses
+        for n in ("b1.a1", "b1.a2", "b1.sc", "b2.a1", "b2.a2", "b3.a1"):
             net.recompute(n)
         moved = sum(d.tensor_ptr(net.ids[n]) != old_ptr[n] for n in old_ptr)
         for n in ("b1.a1", "b1.a2", "b1.sc", "b2.a1", "b2.a2", "b3.a1"):
