@@ -188,3 +188,35 @@ def test_rejects_bad_arguments():
     w = np.zeros((1, 5, 5, 1), np.float32)
     with pytest.raises(ValueError):
         on.conv_bn_act(x, w, None)      # kernel larger than the unpadded image
+
+
+def test_softmax_cross_entropy_closed_forms():
+    # uniform logits: every class has probability 1/C, the loss is ln C whatever the labels
+    C, N = 37, 5
+    z = np.full((N, C), 2.5, np.float32)
+    labels = np.arange(N) % C
+    np.testing.assert_allclose(on.softmax_ce(z, labels)[0], np.log(C), rtol=1e-6)
+    # two classes: loss = log(1 + exp(-(z_label - z_other)))
+    z = np.array([[3.0, 1.0], [0.5, 2.0]], np.float32)
+    want = np.mean([np.log1p(np.exp(-2.0)), np.log1p(np.exp(1.5))])
+    np.testing.assert_allclose(on.softmax_ce(z, np.array([0, 0]))[0], want, rtol=1e-6)
+    # shift invariance and a dominant correct class
+    z = rs.randn(4, 9).astype(np.float32)
+    lab = np.array([1, 2, 3, 4])
+    np.testing.assert_allclose(on.softmax_ce(z + 100.0, lab)[0], on.softmax_ce(z, lab)[0], rtol=1e-4)
+    z[np.arange(4), lab] = 60.0
+    assert on.softmax_ce(z, lab)[0] < 1e-12 + 1e-6
+    # bf16 logits are read at their stored value
+    zb = synth.f32_to_bf16_bits(z).reshape(z.shape)
+    np.testing.assert_allclose(on.softmax_ce(zb, lab, "bf16")[0],
+                               on.softmax_ce(synth.bf16_bits_to_f32(zb).reshape(z.shape), lab)[0], rtol=1e-7)
+
+
+def test_classifier_is_matmul_plus_bias():
+    l = synth.LayerSpec("fc", "fc", "x0", None, "logits", 3, 1, 1, 16, 24, 1, 1, 1, 0, False)
+    l.index = 1
+    p = {"fc": synth.make_params(9, l, "f32")}
+    x = synth.make_input(9, (3, 1, 1, 16), "f32")
+    got = on.run_layers([l], p, x, "f32")["logits"].reshape(3, 24)
+    ref = x.reshape(3, 16).astype(np.float64) @ p["fc"]["w"].reshape(24, 16).astype(np.float64).T + p["fc"]["bias"]
+    np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-6)
