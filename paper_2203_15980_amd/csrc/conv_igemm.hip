@@ -332,6 +332,7 @@ static int conv_tile_n(const ConvArgs &a) {
 
 const char *conv_kernel_name(const ConvArgs &a) {
     if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
+    if (conv3x3_halo_applies(a)) return "conv3x3_halo bf16 256x64 (4x1 waves)";
     const int bn = conv_tile_n(a);
     if (a.bf16) return bn == 128 ? "conv_igemm bf16 128x128 (2x2 waves, 2 slices)" : "conv_igemm bf16 128x64 (4x1 waves, 2 slices)";
     return bn == 128 ? "conv_igemm f32 128x128 (2x2 waves)" : "conv_igemm f32 128x64 (4x1 waves)";
@@ -359,6 +360,7 @@ const char *conv_check(const ConvArgs &a) {
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
     if (conv_check(a)) return hipErrorInvalidValue;
     if (conv1x1_stream_applies(a)) return launch_conv1x1_stream(a, stream);
+    if (conv3x3_halo_applies(a)) return launch_conv3x3_halo(a, stream);
     const int bn = conv_tile_n(a);
     if (a.bf16) {
         if (bn == 128) return launch<true, 128, 128, 2, 2, 2>(a, stream);

@@ -24,6 +24,9 @@ hipError_t launch_conv(const ConvArgs &a, hipStream_t stream);
 // conv1x1.hip: streaming kernel for bf16 1x1 convolutions whose weights fit LDS
 bool conv1x1_stream_applies(const ConvArgs &a);
 hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream);
+// conv3x3_halo.hip: bf16 3x3 stride-1 kernel that keeps the input halo of a pixel tile in LDS
+bool conv3x3_halo_applies(const ConvArgs &a);
+hipError_t launch_conv3x3_halo(const ConvArgs &a, hipStream_t stream);
 // net_ops.hip: ResNet stem (7x7, stride 2, pad 3, 3 -> 64 channels, bf16), pooling, loss
 bool stem_applies(const ConvArgs &a);
 const char *stem_check(const ConvArgs &a);

@@ -51,6 +51,13 @@ CASES = [
     ("3x3_128",       1,  9,  9, 128, 128, 3, 1, 1, True, True),
     ("tiny",          1,  1,  1,  64,  64, 1, 1, 0, True, False),   # one pixel
     ("5x5_pad2",      1,  8,  8,  64,  64, 5, 1, 2, False, False),
+    # 3x3 stride 1 (bf16: the LDS-halo kernel): image borders inside a pixel tile, ragged tail,
+    # odd step count, non-square images, wide rows
+    ("3x3_halo_res",  3, 13, 13, 128,  64, 3, 1, 1, True, True),    # M = 507: two tiles, ragged
+    ("3x3_halo_192",  5, 16, 16, 192, 128, 3, 1, 1, True, False),   # three channel blocks: 27 steps
+    ("3x3_halo_5x7",  1,  5,  7,  64, 128, 3, 1, 1, False, False),  # one small non-square image
+    ("3x3_halo_wide", 2,  4, 60,  64,  64, 3, 1, 1, True, False),   # W = 60: longest halo variant
+    ("3x3_halo_1px",  3,  1,  1,  64,  64, 3, 1, 1, False, False),  # only the centre tap is valid
 ]
 
 
