@@ -4,7 +4,10 @@
 // These are the HBM-bound layers of a bottleneck (28-51 flop per byte against a ridge of
 // about 310 on MI355X): the job is to keep as many bytes in flight as possible, not to
 // feed the matrix cores.  So, unlike the tiled kernel in conv_igemm.hip:
-//   - the whole weight matrix (plus scale/shift) is staged once per workgroup in LDS;
+//   - the weight rows of a slice of NG * 64 output channels (plus their scale/shift) are staged
+//     once per workgroup in LDS; a layer with more channels than one slice holds runs one
+//     workgroup per (pixel group, slice), the slices of a pixel group on the same XCD so that
+//     they share the activations in its L2;
 //   - after that single barrier every wavefront works alone on its own 32 pixels: it
 //     loads its activation operand straight from global memory into registers (each lane
 //     64 contiguous bytes per 128-byte slice of Cin, issued before the staging so that the
@@ -57,14 +60,31 @@ __device__ __forceinline__ void wave_fence() {
 
 static constexpr int kTPitch = 144;
 
-// NS = Cin / 64 (128-byte slices of the reduction axis), NG = Cout / 64.  Dynamic LDS:
-// weights [Cout][Cin*2 + 16 bytes], scale[Cout], shift[Cout] (fp32), then one transposition
-// tile per wavefront.
-template <int NS, int NG, int WAVES, bool HAS_RES>
+// NS = Cin / 64 (128-byte slices of the reduction axis), NG = channels of one slice / 64.
+// Dynamic LDS: weights [NG*64][Cin*2 + 16 bytes], scale, shift (fp32) of the slice, then one
+// transposition tile per wavefront.  Grid: 8 * ceil(pixel groups / 8) * slices workgroups.
+template <int NS, int NG, int WAVES, bool HAS_RES, bool SLICED>
 __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) {
     constexpr int THREADS = WAVES * 64;
-    constexpr int Cout = NG * 64;
+    constexpr int Cout = NG * 64;               // channels of this workgroup's slice
     extern __shared__ __align__(16) unsigned char lds[];
+    // workgroup -> (pixel group, channel slice): consecutive workgroups go to consecutive XCDs,
+    // so the slices of pixel group g all land on XCD g % 8.  A layer that is one slice keeps
+    // the channel count a compile-time constant (cheaper addressing, fewer registers).
+    long long group;
+    int n0;
+    if constexpr (SLICED) {
+        const int nslices = a.Cout / Cout;
+        const long long groups = ((long long)a.M + WAVES * 32 - 1) / (WAVES * 32);
+        const unsigned xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3;
+        group = (long long)(rest / (unsigned)nslices) * 8 + xcd;
+        if (group >= groups) return;             // whole workgroup, before the barrier
+        n0 = (int)(rest % (unsigned)nslices) * Cout;
+    } else {
+        group = blockIdx.x;
+        n0 = 0;
+    }
+    const int Ctot = SLICED ? a.Cout : Cout;
     constexpr int WPITCH = NS * 128 + 16;       // rows 4 banks apart: conflict-free b128 reads
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -76,7 +96,7 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
     // ---- this wavefront's 32 output pixels.  Everything it reads from HBM (its activation
     // operand and, if present, its residual rows) goes into flight first, so that the
     // latency overlaps the staging of the weights and the wavefront never waits twice.
-    const long long tile = (long long)blockIdx.x * WAVES + wv;
+    const long long tile = group * WAVES + wv;
     const long long m = tile * 32 + l32;
     const bool active = tile * 32 < a.M;         // wavefronts past the end only help staging
     const bool valid = m < a.M;
@@ -103,13 +123,14 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
     const long long mbase = tile * 32;
     const int trow = lane >> 3, tseg = lane & 7;
 
-    unsigned char *yg = static_cast<unsigned char *>(a.y);
-    const unsigned char *rg = static_cast<const unsigned char *>(a.res);
+    // the slice offset is folded into the (uniform) base pointers
+    unsigned char *yg = static_cast<unsigned char *>(a.y) + (size_t)n0 * 2;
+    const unsigned char *rg = static_cast<const unsigned char *>(a.res) + (size_t)n0 * 2;
     // residual in the post-swap layout, straight into registers: piece (u, i2) of group g
     // covers channels g*64 + u*32 + 16*i2 + 8*half .. +8 of this lane's pixel (32-byte runs per
     // pixel; routing the reads through the LDS tile as well measured slower).  Two groups are
     // held: the one being finished and the next one, already in flight.
-    const size_t orow = (size_t)mm * Cout * 2;
+    const size_t orow = (size_t)mm * Ctot * 2;
     u32x4_t rv[2][2][2];
     auto load_res = [&](int g, u32x4_t (&dst)[2][2]) {
 #pragma unroll
@@ -123,8 +144,8 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
 
     // ---- stage weights and batch-norm factors (once per workgroup)
     {
-        const unsigned char *wg = static_cast<const unsigned char *>(a.w);
         constexpr int SEGS = NS * 8;             // 16-byte pieces per weight row
+        const unsigned char *wg = static_cast<const unsigned char *>(a.w) + (size_t)n0 * SEGS * 16;
         constexpr int pieces = Cout * SEGS;
         for (int c = tid; c < pieces; c += THREADS) {
             const int row = c / SEGS, seg = c - row * SEGS;
@@ -132,8 +153,8 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
                 *reinterpret_cast<const u32x4_t *>(wg + ((size_t)row * SEGS + seg) * 16);
         }
         for (int c = tid; c < Cout; c += THREADS) {
-            lscale[c] = a.scale[c];
-            lshift[c] = a.shift[c];
+            lscale[c] = a.scale[n0 + c];
+            lshift[c] = a.shift[n0 + c];
         }
     }
     __syncthreads();                             // the only barrier
@@ -210,55 +231,82 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
             const int pr = trow + 8 * t;
             const u32x4_t o4 = *reinterpret_cast<const u32x4_t *>(ttile + pr * kTPitch + tseg * 16);
             if (mbase + pr < a.M)
-                *reinterpret_cast<u32x4_t *>(yg + ((size_t)(mbase + pr) * Cout + g * 64) * 2 + tseg * 16) = o4;
+                *reinterpret_cast<u32x4_t *>(yg + ((size_t)(mbase + pr) * Ctot + g * 64) * 2 + tseg * 16) = o4;
         }
         wave_fence();
     }
 }
 
-// LDS without the transposition tiles
-size_t conv1x1_stream_lds_bytes(const ConvArgs &a) {
-    return (size_t)a.Cout * ((size_t)a.Cin * 2 + 16) + (size_t)a.Cout * 8;
+// Channels per slice: the most 64-channel groups (4, 2 or 1) that divide Cout and whose weight
+// rows fit next to the transposition tiles.
+static int slice_groups(const ConvArgs &a) {
+    const int groups = a.Cout / 64;
+    for (int ng = 4; ng >= 1; ng >>= 1)
+        if (groups % ng == 0 && (size_t)ng * 64 * ((size_t)a.Cin * 2 + 16 + 8) <= 72 * 1024) return ng;
+    return 0;
 }
 
-// The streaming kernel applies to bf16 1x1 convolutions without padding whose weights fit LDS.
+// The streaming kernel applies to bf16 1x1 convolutions without padding with a short reduction
+// axis.  Measured on MI355X (batch 128): with 64 or 128 input channels it beats the tiled kernel
+// for any number of output slices (128 -> 512 at 28 x 28: 49 against 62 us); with 256 input
+// channels only while all output channels fit one slice of 64 (each further slice re-reads a
+// 512-byte activation row that the tiled kernel shares through LDS), and never with 512.
 bool conv1x1_stream_applies(const ConvArgs &a) {
-    return a.bf16 && a.R == 1 && a.S == 1 && a.pad == 0 && (a.Cin == 64 || a.Cin == 128 || a.Cin == 256) &&
-           (a.Cout == 64 || a.Cout == 128 || a.Cout == 256) && conv1x1_stream_lds_bytes(a) <= 56 * 1024;
+    if (!a.bf16 || a.R != 1 || a.S != 1 || a.pad != 0 || a.Cout % 64) return false;
+    if (a.Cin == 256) return a.Cout == 64;
+    if (a.Cin != 64 && a.Cin != 128) return false;
+    return slice_groups(a) != 0;
 }
 
-template <int NS, int NG, int WAVES>
-static hipError_t launch_stream(const ConvArgs &a, hipStream_t stream) {
+template <int NS, int NG, int WAVES, bool SLICED>
+static hipError_t launch_stream_s(const ConvArgs &a, hipStream_t stream) {
     const long long tiles = ((long long)a.M + 31) / 32;
-    const long long blocks = (tiles + WAVES - 1) / WAVES;
+    const long long groups = (tiles + WAVES - 1) / WAVES;
+    const long long blocks = SLICED ? (groups + 7) / 8 * 8 * (a.Cout / (NG * 64)) : groups;
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(WAVES * 64);
-    const size_t lds = conv1x1_stream_lds_bytes(a) + (size_t)WAVES * 32 * kTPitch;
+    const size_t lds = (size_t)NG * 64 * ((size_t)NS * 128 + 16 + 8) + (size_t)WAVES * 32 * kTPitch;
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
     static bool raised = false;                  // more than the default 64 KB of dynamic LDS
     if (lds > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            e = hipFuncSetAttribute(
+                reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true><<<grid, block, lds, stream>>>(a);
-    else conv1x1_stream_kernel<NS, NG, WAVES, false><<<grid, block, lds, stream>>>(a);
+    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED><<<grid, block, lds, stream>>>(a);
+    else conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED><<<grid, block, lds, stream>>>(a);
     return hipGetLastError();
+}
+
+// The larger slices need more than the 128 registers that 16 wavefronts per CU leave a lane:
+// those run 12 wavefronts (170 registers).
+template <int NS, int NG, int WAVES>
+static hipError_t launch_stream(const ConvArgs &a, hipStream_t stream) {
+    if (a.Cout == NG * 64) {
+        constexpr int WV = NS * NG <= 4 ? WAVES : (WAVES > 12 ? 12 : WAVES);
+        return launch_stream_s<NS, NG, WV, false>(a, stream);
+    }
+    constexpr int WV = NS * NG <= 2 ? WAVES : (WAVES > 12 ? 12 : WAVES);
+    return launch_stream_s<NS, NG, WV, true>(a, stream);
 }
 
 template <int WAVES>
 hipError_t launch_conv1x1_stream_t(const ConvArgs &a, hipStream_t stream) {
     if (conv_check(a) || !conv1x1_stream_applies(a)) return hipErrorInvalidValue;
-    const int key = (a.Cin / 64) * 10 + a.Cout / 64;
+    const int key = (a.Cin / 64) * 10 + slice_groups(a);
     switch (key) {
     case 11: return launch_stream<1, 1, WAVES>(a, stream);
     case 12: return launch_stream<1, 2, WAVES>(a, stream);
     case 14: return launch_stream<1, 4, WAVES>(a, stream);
     case 21: return launch_stream<2, 1, WAVES>(a, stream);
     case 22: return launch_stream<2, 2, WAVES>(a, stream);
+    case 24: return launch_stream<2, 4, WAVES>(a, stream);
     case 41: return launch_stream<4, 1, WAVES>(a, stream);
     default: return hipErrorInvalidValue;
     }

@@ -51,6 +51,14 @@ CASES = [
     ("3x3_128",       1,  9,  9, 128, 128, 3, 1, 1, True, True),
     ("tiny",          1,  1,  1,  64,  64, 1, 1, 0, True, False),   # one pixel
     ("5x5_pad2",      1,  8,  8,  64,  64, 5, 1, 2, False, False),
+    # 1x1 with more output channels than one LDS-resident weight slice (bf16: sliced streaming)
+    ("1x1_sl_64_512",  2, 12, 12,  64,  512, 1, 1, 0, True, False),  # 2 slices of 256
+    ("1x1_sl_128_512", 2, 13, 11, 128,  512, 1, 1, 0, True, True),   # residual, ragged
+    ("1x1_sl_128_768", 2, 14, 14, 128,  768, 1, 2, 0, False, False), # stride 2, 3 slices of 256
+    ("1x1_sl_64_1k",   1, 14, 14,  64, 1024, 1, 1, 0, True, True),   # 4 slices
+    ("1x1_sl_128_192", 2, 10, 10, 128,  192, 1, 1, 0, False, False), # 3 slices of 64
+    ("1x1_256_1k",     1, 14, 14, 256, 1024, 1, 1, 0, True, True),   # tiled kernel, 8 channel tiles
+    ("1x1_512_128",    3,  9,  9, 512,  128, 1, 1, 0, True, False),
     # 3x3 stride 1 (bf16: the LDS-halo kernel): image borders inside a pixel tile, ragged tail,
     # odd step count, non-square images, wide rows
     ("3x3_halo_res",  3, 13, 13, 128,  64, 3, 1, 1, True, True),    # M = 507: two tiles, ragged
