@@ -209,6 +209,12 @@ delta_status delta_stats_reset(delta_ctx *ctx);
  * but move no bytes: the replay then shows what the step costs without the link. */
 delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
 
+/* Name of the kernel variant that delta_recompute_segment would launch for this layer (the
+ * operator DELTA re-runs, Sec. 3 / Table 1), written NUL-terminated into out[0..cap).  Validates
+ * the descriptor exactly as delta_recompute_segment does; launches nothing.  Needs a context
+ * with an arena and the tensors bound (delta_bind), since the descriptor names tensor ids. */
+delta_status delta_layer_kernel(delta_ctx *ctx, const delta_layer_desc *layer, char *out, uint64_t cap);
+
 /* Measurement probes (rooflines the hot path is reported against). */
 /* Pinned host <-> device hipMemcpyAsync throughput for `bytes` per copy, `iters` copies,
  * direction DELTA_DIR_*; BOTH runs the two directions concurrently and reports their sum. */

@@ -21,7 +21,7 @@ EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "d
            "delta_alloc", "delta_tensor_ptr", "delta_release", "delta_swap_out", "delta_prefetch",
            "delta_recompute_segment", "delta_sync", "delta_bn_fold", "delta_stats",
            "delta_stats_reset", "delta_set_skip_copies", "delta_probe_hostlink",
-           "delta_probe_hbm", "delta_probe_mfma"]
+           "delta_probe_hbm", "delta_probe_mfma", "delta_layer_kernel"]
 
 
 class TensorDesc(C.Structure):
@@ -114,6 +114,7 @@ def load_library():
         "delta_probe_hostlink": (i32, [vp, u64, u32, u32, C.POINTER(C.c_double)]),
         "delta_probe_hbm": (i32, [vp, u64, u32, C.POINTER(C.c_double)]),
         "delta_probe_mfma": (i32, [vp, u32, C.POINTER(C.c_double)]),
+        "delta_layer_kernel": (i32, [vp, C.POINTER(LayerDesc), C.c_char_p, u64]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -261,6 +262,13 @@ class Delta:
         v = C.c_double()
         self._check(self.lib.delta_probe_hbm(self.ctx, nbytes, iters, C.byref(v)))
         return v.value
+
+    def layer_kernel(self, desc):
+        """Name of the kernel variant a layer descriptor dispatches to."""
+        arr = layer_array([desc])
+        buf = C.create_string_buffer(128)
+        self._check(self.lib.delta_layer_kernel(self.ctx, arr, buf, 128))
+        return buf.value.decode()
 
     def probe_mfma(self, iters):
         v = C.c_double()

@@ -763,6 +763,27 @@ delta_status delta_probe_hbm(delta_ctx *c, uint64_t bytes, uint32_t iters, doubl
     return rc;
 }
 
+delta_status delta_layer_kernel(delta_ctx *c, const delta_layer_desc *layer, char *out, uint64_t cap) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!layer || !out || cap == 0) return fail(c, DELTA_ERR_INVALID, "null argument");
+    delta::ConvArgs a;
+    delta::PoolArgs pa;
+    uint64_t flops = 0;
+    r = prepare_layer(c, *layer, 0, a, pa, flops);
+    if (r != DELTA_OK) return r;
+    const char *name = "?";
+    switch (layer->op) {
+    case DELTA_OP_CONV: name = delta::stem_applies(a) ? "stem7x7 bf16" : delta::conv_kernel_name(a); break;
+    case DELTA_OP_MAXPOOL: name = "maxpool"; break;
+    case DELTA_OP_AVGPOOL: name = "avgpool"; break;
+    case DELTA_OP_SOFTMAX_CE: name = "softmax_ce"; break;
+    default: break;
+    }
+    snprintf(out, (size_t)cap, "%s", name);
+    return DELTA_OK;
+}
+
 delta_status delta_probe_mfma(delta_ctx *c, uint32_t iters, double *out) {
     delta_status r = need_gpu(c);
     if (r != DELTA_OK) return r;

@@ -278,50 +278,91 @@ hipError_t launch_avgpool(const PoolArgs &a, hipStream_t stream) {
 }
 
 // ------------------------------------------------------------------------------ loss
-// Mean over images of logsumexp(z_i) - z_i[label_i].  One workgroup; wavefront w takes images
-// w, w+4, ...; lanes stride over the classes; fixed reduction trees, so the result does not
-// depend on timing.  Labels outside [0, classes) contribute logsumexp only... they are
-// rejected instead: the kernel writes NaN so that a bad label cannot pass unnoticed.
+// Mean over images of logsumexp(z_i) - z_i[label_i].  One workgroup of 16 wavefronts (the
+// result is one float, so there is nothing to spread over the chip; what matters is that the
+// loads of a wavefront are all in flight together).  A wavefront takes two images per round;
+// a lane owns classes lane, lane + 64, ... and holds up to 16 of them per image in registers,
+// so each logit is read once; more than 1024 classes fall back to re-reading loops.  Fixed
+// reduction trees and a fixed image -> wavefront map: the result does not depend on timing.
+// A label outside [0, classes) makes the result NaN, so that it cannot pass unnoticed.
 template <bool BF16>
-__global__ __launch_bounds__(256) void softmax_ce_kernel(const void *logits, const long long *labels, int N,
-                                                         int classes, float *out) {
-    __shared__ float part[4];
+__device__ __forceinline__ float logit_at(const void *logits, size_t idx) {
+    return BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[idx] << 16)
+                : static_cast<const float *>(logits)[idx];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(1024) void softmax_ce_kernel(const void *logits, const long long *labels, int N,
+                                                          int classes, float *out) {
+    constexpr int WAVES = 16, IMGS = 2, KMAX = 16;
+    __shared__ float part[WAVES];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     float total = 0.f;
-    for (int i = wv; i < N; i += 4) {
-        float mx = -INFINITY;
-        for (int c = lane; c < classes; c += 64) {
-            const float z = BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[(size_t)i * classes + c] << 16)
-                                 : static_cast<const float *>(logits)[(size_t)i * classes + c];
-            mx = fmaxf(mx, z);
-        }
+    if (classes <= 64 * KMAX) {
+        for (int i0 = wv * IMGS; i0 < N; i0 += WAVES * IMGS) {
+            float z[IMGS][KMAX], zl[IMGS];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        float se = 0.f;
-        for (int c = lane; c < classes; c += 64) {
-            const float z = BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[(size_t)i * classes + c] << 16)
-                                 : static_cast<const float *>(logits)[(size_t)i * classes + c];
-            se += __expf(z - mx);
-        }
+            for (int u = 0; u < IMGS; ++u) {
+                const int i = i0 + u;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
-        const long long lab = labels[i];
-        float zl = __builtin_nanf("");
-        if (lab >= 0 && lab < classes)
-            zl = BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[(size_t)i * classes + lab] << 16)
-                      : static_cast<const float *>(logits)[(size_t)i * classes + lab];
-        total += (mx + __logf(se)) - zl;
+                for (int k = 0; k < KMAX; ++k) {
+                    const int c = lane + 64 * k;
+                    z[u][k] = (i < N && c < classes) ? logit_at<BF16>(logits, (size_t)i * classes + c) : -INFINITY;
+                }
+                zl[u] = __builtin_nanf("");
+                if (i < N) {
+                    const long long lab = labels[i];
+                    if (lab >= 0 && lab < classes) zl[u] = logit_at<BF16>(logits, (size_t)i * classes + lab);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < IMGS; ++u) {
+                if (i0 + u >= N) break;                       // uniform over the wavefront
+                float mx = -INFINITY;
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k) mx = fmaxf(mx, z[u][k]);
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                float se = 0.f;
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k)
+                    if (lane + 64 * k < classes) se += __expf(z[u][k] - mx);
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
+                total += (mx + __logf(se)) - zl[u];
+            }
+        }
+    } else {
+        for (int i = wv; i < N; i += WAVES) {
+            float mx = -INFINITY;
+            for (int c = lane; c < classes; c += 64) mx = fmaxf(mx, logit_at<BF16>(logits, (size_t)i * classes + c));
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            float se = 0.f;
+            for (int c = lane; c < classes; c += 64) se += __expf(logit_at<BF16>(logits, (size_t)i * classes + c) - mx);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
+            const long long lab = labels[i];
+            float zl = __builtin_nanf("");
+            if (lab >= 0 && lab < classes) zl = logit_at<BF16>(logits, (size_t)i * classes + lab);
+            total += (mx + __logf(se)) - zl;
+        }
     }
     if (lane == 0) part[wv] = total;
     __syncthreads();
-    if (threadIdx.x == 0) out[0] = (part[0] + part[1] + part[2] + part[3]) / (float)N;
+    if (threadIdx.x == 0) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += part[w];
+        out[0] = sum / (float)N;
+    }
 }
 
 hipError_t launch_softmax_ce(const void *logits, const void *labels, int N, int classes, int bf16, float *out,
                              hipStream_t stream) {
     if (!logits || !labels || !out || N <= 0 || classes <= 0) return hipErrorInvalidValue;
-    if (bf16) softmax_ce_kernel<true><<<dim3(1), dim3(256), 0, stream>>>(logits, static_cast<const long long *>(labels), N, classes, out);
-    else softmax_ce_kernel<false><<<dim3(1), dim3(256), 0, stream>>>(logits, static_cast<const long long *>(labels), N, classes, out);
+    if (bf16) softmax_ce_kernel<true><<<dim3(1), dim3(1024), 0, stream>>>(logits, static_cast<const long long *>(labels), N, classes, out);
+    else softmax_ce_kernel<false><<<dim3(1), dim3(1024), 0, stream>>>(logits, static_cast<const long long *>(labels), N, classes, out);
     return hipGetLastError();
 }
 

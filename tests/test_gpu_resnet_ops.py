@@ -164,7 +164,8 @@ def test_small_resnet_plan_replay_with_loss(torch_mod):
 def test_softmax_ce_matches_oracle(torch_mod):
     import paper_2203_15980_amd as dl
     torch = torch_mod
-    for dtype, N, classes in (("bf16", 7, 1000), ("f32", 130, 10)):
+    for dtype, N, classes in (("bf16", 7, 1000), ("f32", 130, 10), ("bf16", 128, 1000), ("f32", 33, 1024),
+                              ("bf16", 5, 1500)):       # 1500 classes: the re-reading path
         z = (synth.normal(5, 1, N * classes) * 3.0).astype(np.float32).reshape(N, classes)
         zs = z if dtype == "f32" else synth.f32_to_bf16_bits(z).reshape(N, classes)
         labels = synth.make_labels(5, N, classes)
