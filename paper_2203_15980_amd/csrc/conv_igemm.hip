@@ -12,13 +12,18 @@
 // pixel, which is what NHWC wants.
 //
 // Per workgroup (256 threads = 4 wavefronts of 64): BM output pixels x BN output channels.
-// The reduction runs over (tap, 128-byte slice of Cin).  Each slice of the BM gathered
-// input rows and of the BN weight rows is fetched with 16-byte loads (8 lanes cover one
-// 128-byte row), staged in LDS with rows padded to 144 bytes (conflict-free ds_read_b128),
-// and the next slice is already in flight in registers while the MFMAs of the current one
-// run.  Within a slice, lane half h owns bytes [64h, 64h+64) of every row for both
-// operands, so the pairing of products is the same for w and x whatever the hardware's
-// internal k order is.
+// The reduction runs over (tap, 128-byte slice of Cin).  Each slice of the BM gathered input
+// rows and of the BN weight rows is fetched with 16-byte buffer loads (8 lanes cover one
+// 128-byte row) and staged in LDS with rows padded to 144 bytes (conflict-free ds_read_b128).
+// Pipeline, one barrier per slice: slice t is multiplied out of LDS buffer t % 2 while slice
+// t+1 moves from registers into the other buffer and slice t+3 is requested from memory.
+// The fetches go through buffer descriptors: padding taps, rows past the last pixel, channel
+// rows past Cout and slices past the last one are given an offset outside the descriptor, which
+// loads zeros.  Nothing in a step is conditional, so the compiler knows how many loads are in
+// flight at each wait and waits only for the slice it is about to store (with branches around
+// the loads it waited for all of them, which halved the speed).
+// Within a slice, lane half h owns bytes [64h, 64h+64) of every row for both operands, so the
+// pairing of products is the same for w and x whatever the hardware's internal k order is.
 //
 // Epilogue: fp32 scale/shift in the accumulator layout, then through a wavefront-private
 // fp32 LDS tile into row-major order, so that the residual is read and y is written with
@@ -79,7 +84,10 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool BF16, int BM, int BN, int WM, int WN, int NSL>
+// offset that lies outside every buffer descriptor used here (their sizes stay below 2 GiB)
+static constexpr int kOutOfRange = (int)0x80000000;
+
+template <bool BF16, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     using E = Elem<BF16>;
     constexpr int ES = E::size;
@@ -91,16 +99,13 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     constexpr int XL = BM / 32;                // 16-byte loads per thread and slice, activations
     constexpr int WL = BN / 32;                // same, weights
     constexpr int STG_PITCH = CW * 4 + 16;
-    // NSL slices of 128 bytes are staged together; the pitch keeps rows 4 banks apart
-    constexpr int PITCH = NSL * kRowBytes + 16;
-    constexpr int TILE_BYTES = (BM + BN) * PITCH;
+    constexpr int PITCH = kRowPitch;           // rows 4 banks apart
+    constexpr int TILE_BYTES = 2 * (BM + BN) * PITCH;   // two buffers
     constexpr int STG_BYTES = 4 * 32 * STG_PITCH;
     constexpr int SMEM = TILE_BYTES > STG_BYTES ? TILE_BYTES : STG_BYTES;
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && TN % TG == 0, "bad tiling");
 
     __shared__ __align__(16) unsigned char smem[SMEM];
-    unsigned char *xs = smem;
-    unsigned char *ws = smem + BM * PITCH;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -123,64 +128,86 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const unsigned char *wg = static_cast<const unsigned char *>(a.w);
 
-    // ---- per-thread gather coordinates: row = tid/8 + 32 i, 16-byte segment = tid%8
+    // ---- per-thread gather coordinates: row = tid/8 + 32 i, 16-byte segment = tid%8.
+    // Both operands are read through buffer descriptors with 32-bit offsets.  The activation
+    // descriptor starts at the first input pixel this tile can touch (input pixel indices grow
+    // with the output pixel index and with the tap), so offsets stay small whatever the tensor
+    // size; an offset of kOutOfRange lies outside every descriptor and loads zeros.
     const int lrow = tid >> 3, seg = tid & 7;
-    int h0[XL], w0[XL];
-    long long nrow[XL];            // n * H, or -1 for rows past the end of the image batch
+    const size_t cin_bytes = (size_t)a.Cin * ES;
     const int PQ = a.P * a.Q;
+    long long base_pix;
+    {
+        const int n = m0 / PQ, pq = m0 - n * PQ;
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        base_pix = ((long long)n * a.H + (p * a.stride - a.pad)) * a.W + (q * a.stride - a.pad);
+        if (base_pix < 0) base_pix = 0;
+    }
+    const unsigned long long xbytes = (unsigned long long)a.N * a.H * a.W * cin_bytes - (unsigned long long)base_pix * cin_bytes;
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(xg) + (size_t)base_pix * cin_bytes, 0,
+        (int)(xbytes < 0x7FFFFFFFull ? xbytes : 0x7FFFFFFFull), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(wg), 0, (int)((size_t)a.Cout * a.R * a.S * cin_bytes), 0x00020000);
+    int h0[XL], w0[XL];
+    int xoff[XL];                  // byte offset of the row's tap (0,0) pixel, or kOutOfRange past M
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
         const int m = m0 + lrow + 32 * i;
         if (m < a.M) {
             const int n = m / PQ, pq = m - n * PQ;
             const int p = pq / a.Q, q = pq - p * a.Q;
-            nrow[i] = (long long)n * a.H;
             h0[i] = p * a.stride - a.pad;
             w0[i] = q * a.stride - a.pad;
+            const long long pix = ((long long)n * a.H + h0[i]) * a.W + w0[i];
+            xoff[i] = (int)((pix - base_pix) * (long long)cin_bytes) + seg * 16;
         } else {
-            nrow[i] = -1;
             h0[i] = w0[i] = 0;
+            xoff[i] = kOutOfRange;
         }
     }
-    const size_t cin_bytes = (size_t)a.Cin * ES;
+    int woff[WL];
+#pragma unroll
+    for (int j = 0; j < WL; ++j) {
+        const int k = n0 + lrow + 32 * j;
+        woff[j] = k < a.Cout ? (int)((size_t)k * a.R * a.S * cin_bytes) + seg * 16 : kOutOfRange;
+    }
     const int cslices = a.Cin / KC;
     const int nslices = a.R * a.S * cslices;
 
-    const int nstages = (nslices + NSL - 1) / NSL;
 
-    u32x4 xr[NSL][XL], wr[NSL][WL];
-    // global -> registers for stage ST (slices ST*NSL ...); slices past the end load zeros
-#define DELTA_FETCH(ST)                                                                          \
-    _Pragma("unroll") for (int sl_ = 0; sl_ < NSL; ++sl_) {                                      \
-        const int it_ = (ST) * NSL + sl_;                                                        \
-        if (it_ < nslices) {                                                                     \
-            const int tap_ = it_ / cslices, cs_ = it_ - tap_ * cslices;                          \
-            const int r_ = tap_ / a.S, s_ = tap_ - r_ * a.S;                                     \
-            const size_t coff_ = (size_t)cs_ * kRowBytes + seg * 16;                             \
-            _Pragma("unroll") for (int i = 0; i < XL; ++i) {                                     \
-                const int h_ = h0[i] + r_, w_ = w0[i] + s_;                                      \
-                const bool ok_ = nrow[i] >= 0 && (unsigned)h_ < (unsigned)a.H &&                 \
-                                 (unsigned)w_ < (unsigned)a.W;                                   \
-                if (ok_) {                                                                       \
-                    const size_t pix_ = (size_t)(nrow[i] + h_) * a.W + w_;                       \
-                    xr[sl_][i] = *reinterpret_cast<const u32x4 *>(xg + pix_ * cin_bytes + coff_); \
-                } else {                                                                         \
-                    xr[sl_][i] = u32x4{0u, 0u, 0u, 0u}; /* zero padding / rows past M */         \
-                }                                                                                \
-            }                                                                                    \
-            _Pragma("unroll") for (int j = 0; j < WL; ++j) {                                     \
-                const size_t k_ = (size_t)(n0 + lrow + 32 * j);                                  \
-                if (k_ < (size_t)a.Cout)                                                         \
-                    wr[sl_][j] = *reinterpret_cast<const u32x4 *>(                               \
-                        wg + ((k_ * a.R + r_) * a.S + s_) * cin_bytes + coff_);                  \
-                else                                                                             \
-                    wr[sl_][j] = u32x4{0u, 0u, 0u, 0u}; /* channel rows past Cout */             \
-            }                                                                                    \
-        } else {                                                                                 \
-            _Pragma("unroll") for (int i = 0; i < XL; ++i) xr[sl_][i] = u32x4{0u, 0u, 0u, 0u};   \
-            _Pragma("unroll") for (int j = 0; j < WL; ++j) wr[sl_][j] = u32x4{0u, 0u, 0u, 0u};   \
-        }                                                                                        \
-    }
+    constexpr int TILE1 = (BM + BN) * PITCH;     // one buffer: x rows then w rows
+    constexpr int D = 2;                          // slices in flight in registers
+    constexpr int U = (D % 2 == 0) ? D : 2 * D;   // steps per unrolled round: buffer and register indices static
+    u32x4 xr[D][XL], wr[D][WL];                   // register ring: set s holds a slice t with t % D == s
+
+    // global -> registers for slice `it`.  Unconditional: a slice index past the end, padding,
+    // rows past M and channel rows past Cout turn into out-of-range offsets, i.e. zeros, so the
+    // number of loads in flight at every wait is a compile-time constant.
+    auto fetch = [&](int it, u32x4 (&xd)[XL], u32x4 (&wd)[WL]) {
+        const bool live = it < nslices;
+        const int tap = it / cslices, cs = it - tap * cslices;
+        const int r = tap / a.S, sx = tap - r * a.S;
+        const int xadd = (r * a.W + sx) * (int)cin_bytes + cs * kRowBytes;
+        const int wadd = (r * a.S + sx) * (int)cin_bytes + cs * kRowBytes;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int h = h0[i] + r, w = w0[i] + sx;
+            const bool ok = live && xoff[i] != kOutOfRange && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+            xd[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, ok ? xoff[i] + xadd : kOutOfRange, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < WL; ++j)
+            wd[j] = __builtin_amdgcn_raw_buffer_load_b128(
+                wrsrc, live && woff[j] != kOutOfRange ? woff[j] + wadd : kOutOfRange, 0, 0);
+    };
+    auto store = [&](int buf, const u32x4 (&xd)[XL], const u32x4 (&wd)[WL]) {
+        unsigned char *xb = smem + buf * TILE1, *wb = xb + BM * PITCH;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) *reinterpret_cast<u32x4 *>(xb + (lrow + 32 * i) * PITCH + seg * 16) = xd[i];
+#pragma unroll
+        for (int j = 0; j < WL; ++j) *reinterpret_cast<u32x4 *>(wb + (lrow + 32 * j) * PITCH + seg * 16) = wd[j];
+    };
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -190,41 +217,42 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#define DELTA_STAGE()                                                                             \
-    {                                                                                            \
-        __syncthreads(); /* previous stage fully consumed */                                     \
-        _Pragma("unroll") for (int sl_ = 0; sl_ < NSL; ++sl_) {                                  \
-            _Pragma("unroll") for (int i = 0; i < XL; ++i)                                       \
-                *reinterpret_cast<u32x4 *>(xs + (lrow + 32 * i) * PITCH + sl_ * kRowBytes + seg * 16) = xr[sl_][i]; \
-            _Pragma("unroll") for (int j = 0; j < WL; ++j)                                       \
-                *reinterpret_cast<u32x4 *>(ws + (lrow + 32 * j) * PITCH + sl_ * kRowBytes + seg * 16) = wr[sl_][j]; \
-        }                                                                                        \
-        __syncthreads();                                                                         \
-    }
-#define DELTA_MMA()                                                                               \
-    _Pragma("unroll") for (int sl_ = 0; sl_ < NSL; ++sl_)                                        \
-    _Pragma("unroll") for (int j16 = 0; j16 < 4; ++j16) {                                        \
-        const int koff = sl_ * kRowBytes + half * 64 + j16 * 16;                                 \
-        u32x4 xf[TM], wf[TN];                                                                    \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-            xf[i] = *reinterpret_cast<const u32x4 *>(xs + ((wm * TM + i) * 32 + l32) * PITCH + koff); \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
-            wf[j] = *reinterpret_cast<const u32x4 *>(ws + ((wn * TN + j) * 32 + l32) * PITCH + koff); \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-            _Pragma("unroll") for (int j = 0; j < TN; ++j) mma16<BF16>(wf[j], xf[i], acc[i][j]); \
-    }
+    auto mma = [&](int buf) {
+        const unsigned char *xb = smem + buf * TILE1, *wb = xb + BM * PITCH;
+#pragma unroll
+        for (int j16 = 0; j16 < 4; ++j16) {
+            const int koff = half * 64 + j16 * 16;
+            u32x4 xf[TM], wf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                xf[i] = *reinterpret_cast<const u32x4 *>(xb + ((wm * TM + i) * 32 + l32) * PITCH + koff);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                wf[j] = *reinterpret_cast<const u32x4 *>(wb + ((wn * TN + j) * 32 + l32) * PITCH + koff);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) mma16<BF16>(wf[j], xf[i], acc[i][j]);
+        }
+    };
 
-    DELTA_FETCH(0)
-    for (int st = 0; st + 1 < nstages; ++st) {
-        DELTA_STAGE()
-        DELTA_FETCH(st + 1)                       // in flight while the MFMAs below run
-        DELTA_MMA()
+    // Pipeline, one barrier per slice: slice t is multiplied out of LDS buffer t % 2 while slice
+    // t+1 moves from registers to the other buffer and slice t+1+D is requested into the
+    // registers that frees.
+#pragma unroll
+    for (int i = 0; i < D; ++i) fetch(i, xr[i], wr[i]);
+    store(0, xr[0], wr[0]);
+    fetch(D, xr[0], wr[0]);
+    for (int t0 = 0; t0 < nslices; t0 += U) {     // a last partial round runs on tiles of zeros
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            const int t = t0 + i;
+            __syncthreads();                      // buffer t % 2 holds slice t; the other one is free
+            store((i + 1) & 1, xr[(i + 1) % D], wr[(i + 1) % D]);
+            fetch(t + 1 + D, xr[(i + 1) % D], wr[(i + 1) % D]);
+            mma(i & 1);
+        }
     }
-    DELTA_STAGE()
-    DELTA_MMA()
-#undef DELTA_STAGE
-#undef DELTA_MMA
-#undef DELTA_FETCH
     // ---- epilogue
     __syncthreads();                              // tiles are dead, LDS becomes staging space
     unsigned char *stg = smem + wv * (32 * STG_PITCH);
@@ -311,19 +339,19 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     }
 }
 
-template <bool BF16, int BM, int BN, int WM, int WN, int NSL = 1>
+template <bool BF16, int BM, int BN, int WM, int WN>
 static hipError_t launch(const ConvArgs &a, hipStream_t stream) {
     const long long tiles_m = ((long long)a.M + BM - 1) / BM;
     const long long blocks = tiles_m * ((a.Cout + BN - 1) / BN);
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    conv_igemm_kernel<BF16, BM, BN, WM, WN, NSL><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
+    conv_igemm_kernel<BF16, BM, BN, WM, WN><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
     return hipGetLastError();
 }
 
 // Channel tile: 128 when it divides Cout or wastes little, else 64.  Measured on MI355X,
-// 128 pixels x 128 channels with 2 x 2 wavefronts (64 x 64 each) and two reduction slices
-// per stage beats the wider tiles: the loop is bound by the latency of the global -> LDS
-// path, and the smaller register footprint lets two workgroups share a CU.
+// 128 pixels x 128 channels with 2 x 2 wavefronts (64 x 64 each) beats the wider tiles
+// (256 x 128 and 128 x 256 with 8 wavefronts were level or slower on every ResNet-50 shape):
+// two workgroups share a CU and cover each other's barriers.
 static int conv_tile_n(const ConvArgs &a) {
     if (a.Cout % 128 == 0) return 128;
     if (a.Cout % 64 == 0) return 64;
@@ -334,7 +362,7 @@ const char *conv_kernel_name(const ConvArgs &a) {
     if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
     if (conv3x3_halo_applies(a)) return "conv3x3_halo bf16 256x64 (4x1 waves)";
     const int bn = conv_tile_n(a);
-    if (a.bf16) return bn == 128 ? "conv_igemm bf16 128x128 (2x2 waves, 2 slices)" : "conv_igemm bf16 128x64 (4x1 waves, 2 slices)";
+    if (a.bf16) return bn == 128 ? "conv_igemm bf16 128x128 (2x2 waves)" : "conv_igemm bf16 128x64 (4x1 waves)";
     return bn == 128 ? "conv_igemm f32 128x128 (2x2 waves)" : "conv_igemm f32 128x64 (4x1 waves)";
 }
 
@@ -343,6 +371,9 @@ const char *conv_check(const ConvArgs &a) {
     const int kc = a.bf16 ? 64 : 32;
     if (a.N <= 0 || a.H <= 0 || a.W <= 0 || a.R <= 0 || a.S <= 0 || a.stride <= 0 || a.pad < 0)
         return "non-positive dimension";
+    // with more padding than half a window, input pixel indices would no longer grow with the
+    // output pixel index, which the tiled kernel's tile-relative offsets rely on
+    if (2 * a.pad > a.R - 1 || 2 * a.pad > a.S - 1) return "padding larger than half the window";
     if (a.Cin <= 0 || a.Cin % kc) return "Cin must be a multiple of 64 (bf16) or 32 (fp32)";
     if (a.Cout <= 0 || a.Cout % (a.bf16 ? 8 : 4)) return "Cout must be a multiple of 8 (bf16) or 4 (fp32)";
     if (a.P != (a.H + 2 * a.pad - a.R) / a.stride + 1 || a.Q != (a.W + 2 * a.pad - a.S) / a.stride + 1 ||
@@ -350,6 +381,15 @@ const char *conv_check(const ConvArgs &a) {
         return "inconsistent output size";
     if ((long long)a.N * a.P * a.Q != a.M || (long long)a.N * a.P * a.Q > 0x7FFFFFFFLL) return "bad M";
     if ((long long)a.N * a.H * a.W > 0x7FFFFFFFLL) return "input too large";
+    {
+        // 32-bit offsets of the tiled kernel: the weights as a whole, and the input pixels one
+        // tile of 128 output pixels can touch, relative to the first of them (a loose bound:
+        // the images the tile can reach into, plus two more for partial rows and the taps)
+        const long long es = a.bf16 ? 2 : 4;
+        if ((long long)a.Cout * a.R * a.S * a.Cin * es > 0x7FFFFFFFLL) return "weights exceed 2 GiB";
+        const long long images = 127 / ((long long)a.P * a.Q) + 3;
+        if (images * a.H * a.W * a.Cin * es + 256 > 0x7FFFFFFFLL) return "image too large for 32-bit tile offsets";
+    }
     if (!a.x || !a.w || !a.y || !a.scale || !a.shift) return "null pointer";
     if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y | (uintptr_t)a.res | (uintptr_t)a.scale |
          (uintptr_t)a.shift) & 15)
@@ -363,11 +403,11 @@ hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
     if (conv3x3_halo_applies(a)) return launch_conv3x3_halo(a, stream);
     const int bn = conv_tile_n(a);
     if (a.bf16) {
-        if (bn == 128) return launch<true, 128, 128, 2, 2, 2>(a, stream);
-        return launch<true, 128, 64, 4, 1, 2>(a, stream);
+        if (bn == 128) return launch<true, 128, 128, 2, 2>(a, stream);
+        return launch<true, 128, 64, 4, 1>(a, stream);
     }
-    if (bn == 128) return launch<false, 128, 128, 2, 2, 1>(a, stream);
-    return launch<false, 128, 64, 4, 1, 1>(a, stream);
+    if (bn == 128) return launch<false, 128, 128, 2, 2>(a, stream);
+    return launch<false, 128, 64, 4, 1>(a, stream);
 }
 
 // ---------------------------------------------------------------- small helpers
