@@ -302,6 +302,14 @@ def test_error_paths(torch_mod):
     with pytest.raises(dl.DeltaError) as e:
         d.recompute_segment([bad])
     assert e.value.status == dl.ERR_INVALID
+    wide = dl.LayerDesc.from_buffer_copy(net.desc["b1.a1"][0])
+    wide.pad = 1                                             # 1x1 window with padding 1: rejected
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment([wide])
+    assert e.value.status == dl.ERR_INVALID
+    # the kernel a layer dispatches to, by name
+    assert "conv1x1_stream" in d.layer_kernel(net.desc["b1.a1"][0])
+    assert "conv3x3_halo" in d.layer_kernel(net.desc["b1.a2"][0])
     d.close()
     # arena too small for the second tensor
     small = make_delta(torch_mod, 4096)
