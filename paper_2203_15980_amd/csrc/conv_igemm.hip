@@ -87,7 +87,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 // offset that lies outside every buffer descriptor used here (their sizes stay below 2 GiB)
 static constexpr int kOutOfRange = (int)0x80000000;
 
-template <bool BF16, int BM, int BN, int WM, int WN>
+template <bool BF16, int BM, int BN, int WM, int WN, bool HAS_RES>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     using E = Elem<BF16>;
     constexpr int ES = E::size;
@@ -241,6 +241,32 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     // registers that frees.
 #pragma unroll
     for (int i = 0; i < D; ++i) fetch(i, xr[i], wr[i]);
+    // The residual rows of this wavefront's outputs are requested now, in the layout the
+    // row-major phase of the epilogue uses, so that their latency hides behind the main loop
+    // (a layer with few slices otherwise pays it again after its last MFMA).  Tile-relative
+    // descriptor: rows past M lie past the end of the tensor, i.e. outside it.
+    constexpr int CPL = CW / 8;                   // channels per lane in the row-major phase
+    const int prow = lane >> 3, cseg = lane & 7;
+    u32x4 rres[HAS_RES ? TN / TG : 1][HAS_RES ? TM : 1][4];
+    if constexpr (HAS_RES) {
+        const size_t row_bytes = (size_t)a.Cout * ES;
+        const unsigned long long rbytes = (unsigned long long)(a.M - m0) * row_bytes;
+        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<unsigned char *>(static_cast<const unsigned char *>(a.res)) + (size_t)m0 * row_bytes, 0,
+            (int)(rbytes < 0x7FFFFFFFull ? rbytes : 0x7FFFFFFFull), 0x00020000);
+#pragma unroll
+        for (int g = 0; g < TN / TG; ++g) {
+            const int chan = n0 + (wn * TN + g * TG) * 32 + cseg * CPL;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int row = (wm * TM + i) * 32 + prow + 8 * t;
+                    rres[g][i][t] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rrsrc, chan < a.Cout ? (int)(row * row_bytes + (size_t)chan * ES) : kOutOfRange, 0, 0);
+                }
+        }
+    }
     store(0, xr[0], wr[0]);
     fetch(D, xr[0], wr[0]);
     for (int t0 = 0; t0 < nslices; t0 += U) {     // a last partial round runs on tiles of zeros
@@ -257,9 +283,6 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     __syncthreads();                              // tiles are dead, LDS becomes staging space
     unsigned char *stg = smem + wv * (32 * STG_PITCH);
     unsigned char *yg = static_cast<unsigned char *>(a.y);
-    const unsigned char *rg = static_cast<const unsigned char *>(a.res);
-    const int prow = lane >> 3, cseg = lane & 7;
-    constexpr int CPL = CW / 8;                   // channels per lane in the row-major phase
 
 #pragma unroll
     for (int g = 0; g < TN / TG; ++g) {
@@ -307,8 +330,8 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
                     v[e] = f.x; v[e + 1] = f.y; v[e + 2] = f.z; v[e + 3] = f.w;
                 }
                 const size_t off = ((size_t)m * a.Cout + chan) * ES;
-                if (rg) {
-                    const u32x4 rv = *reinterpret_cast<const u32x4 *>(rg + off);
+                if constexpr (HAS_RES) {
+                    const u32x4 rv = rres[g][i][t];
                     if constexpr (BF16) {
                         v[0] += bf16_lo(rv.x); v[1] += bf16_hi(rv.x);
                         v[2] += bf16_lo(rv.y); v[3] += bf16_hi(rv.y);
@@ -341,10 +364,13 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 
 template <bool BF16, int BM, int BN, int WM, int WN>
 static hipError_t launch(const ConvArgs &a, hipStream_t stream) {
+    constexpr long long kMaxRowBytes = 0x7FFFFFFFLL / BM;   // residual offsets inside one tile
+    if (a.res && (long long)a.Cout * (BF16 ? 2 : 4) > kMaxRowBytes) return hipErrorInvalidValue;
     const long long tiles_m = ((long long)a.M + BM - 1) / BM;
     const long long blocks = tiles_m * ((a.Cout + BN - 1) / BN);
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    conv_igemm_kernel<BF16, BM, BN, WM, WN><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
+    if (a.res) conv_igemm_kernel<BF16, BM, BN, WM, WN, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
+    else conv_igemm_kernel<BF16, BM, BN, WM, WN, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
     return hipGetLastError();
 }
 
