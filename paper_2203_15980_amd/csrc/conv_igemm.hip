@@ -106,6 +106,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && TN % TG == 0, "bad tiling");
 
     __shared__ __align__(16) unsigned char smem[SMEM];
+    __shared__ __align__(16) float sbn[2][BN];   // scale, shift of this tile's channels
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -127,6 +128,13 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const unsigned char *wg = static_cast<const unsigned char *>(a.w);
+    // folded batch-norm factors: fetched now, read in the epilogue (the barriers of the main
+    // loop make them visible); channels past Cout get zeros
+    if (tid < BN) {
+        const int ch = n0 + tid;
+        sbn[0][tid] = ch < a.Cout ? a.scale[ch] : 0.f;
+        sbn[1][tid] = ch < a.Cout ? a.shift[ch] : 0.f;
+    }
 
     // ---- per-thread gather coordinates: row = tid/8 + 32 i, 16-byte segment = tid%8.
     // Both operands are read through buffer descriptors with 32-bit offsets.  The activation
@@ -292,14 +300,9 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
         for (int u = 0; u < TG; ++u)
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
-                const int ch = n0 + (wn * TN + g * TG + u) * 32 + 8 * rb + 4 * half;
-                if (ch < a.Cout) {                // Cout is a multiple of 4: all four or none
-                    sc[u][rb] = *reinterpret_cast<const f32x4 *>(a.scale + ch);
-                    sh[u][rb] = *reinterpret_cast<const f32x4 *>(a.shift + ch);
-                } else {
-                    sc[u][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    sh[u][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
+                const int cl = (wn * TN + g * TG + u) * 32 + 8 * rb + 4 * half;   // channel within the tile
+                sc[u][rb] = *reinterpret_cast<const f32x4 *>(&sbn[0][cl]);
+                sh[u][rb] = *reinterpret_cast<const f32x4 *>(&sbn[1][cl]);
             }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
