@@ -23,6 +23,14 @@
  * Pins (tests/test_oracle_numeric.py): 1x1 case equals a matrix product,
  * centre-tap identity, all-ones padding counts, linearity, stride subsampling,
  * BN identity and closed forms, bf16 rounding on hand-picked bit patterns.
+ *
+ * Backward of the same layer (oracle_conv_bn_act_bwd): the backward half of the
+ * training iteration whose tensor accesses DELTA's planner follows (Sec. 3,
+ * Assumptions 1-3: the backward pass reads the stored forward activations).  It is
+ * the chain rule of the four lines above, written out; all in fp64, nothing rounded.
+ * Pins (tests/test_oracle_backward.py): central finite differences of the forward
+ * function, the adjoint identity <g, conv(x')> = <conv^T(g), x'>, the 1x1 case as
+ * two matrix products, and the mask/scale factors on hand-made cases.
  */
 #include <math.h>
 #include <stdint.h>
@@ -189,5 +197,94 @@ int oracle_avgpool(int dtype, const void *x, int N, int H, int W, int C, void *y
             else ((uint16_t *)y)[(size_t)n * C + c] = oracle_double_to_bf16(a);
         }
     free(xd);
+    return 0;
+}
+
+/*
+ * Backward of one fused layer with frozen batch-norm statistics.  Given gy = dL/dy:
+ *
+ *   gpre[n,p,q,k] = gy[n,p,q,k] * [y[n,p,q,k] > 0]     (if relu; the subgradient at 0 is 0;
+ *                                                        y is the STORED forward output)
+ *                 = gy[n,p,q,k]                         (otherwise)
+ *   dL/dres = gpre                                      (the residual enters v with weight 1)
+ *   gz[n,p,q,k] = gpre[n,p,q,k] * gamma_k / sqrt(var_k + eps)          (gz = gpre without BN)
+ *   gx[n,h,w,c]  = sum over (p,q,k,r,s) with h = p*stride + r - pad, w = q*stride + s - pad
+ *                  of gz[n,p,q,k] * w[k,r,s,c]
+ *   gw[k,r,s,c]  = sum over (n,p,q) with that (h,w) inside the image of gz[n,p,q,k] * x[n,h,w,c]
+ *
+ * x, w, y, gy at storage precision; gx64 [N,H,W,Cin], gw64 [Cout,R,S,Cin], gpre64 [N,P,Q,Cout]
+ * in fp64 (any of the three may be NULL).  gamma == NULL: no batch-norm.  y may be NULL when
+ * relu == 0.  Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int oracle_conv_bn_act_bwd(int dtype, const void *x, const void *w, const void *y, const void *gy,
+                           const float *gamma, const float *var, double eps,
+                           int N, int H, int W, int Cin, int Cout, int R, int S,
+                           int stride, int pad, int relu,
+                           double *gx64, double *gw64, double *gpre64)
+{
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || N < 0 || H <= 0 || W <= 0 ||
+        Cin <= 0 || Cout <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 || !gy || (relu && !y))
+        return -1;
+    const int P = (H + 2 * pad - R) / stride + 1;
+    const int Q = (W + 2 * pad - S) / stride + 1;
+    if (P <= 0 || Q <= 0) return -1;
+    const size_t nx = (size_t)N * H * W * Cin, nw = (size_t)Cout * R * S * Cin;
+    const size_t ny = (size_t)N * P * Q * Cout;
+    double *xd = widen(dtype, x, nx), *wd = widen(dtype, w, nw), *gd = widen(dtype, gy, ny);
+    double *yd = relu ? widen(dtype, y, ny) : NULL;
+    double *gz = (double *)malloc((ny ? ny : 1) * sizeof(double));
+    if (!xd || !wd || !gd || (relu && !yd) || !gz) { free(xd); free(wd); free(gd); free(yd); free(gz); return -1; }
+
+    for (size_t o = 0; o < ny; ++o) {
+        const int k = (int)(o % (size_t)Cout);
+        double g = gd[o];
+        if (relu && !(yd[o] > 0.0)) g = 0.0;
+        if (gpre64) gpre64[o] = g;
+        if (gamma) g *= (double)gamma[k] / sqrt((double)var[k] + eps);
+        gz[o] = g;
+    }
+    if (gx64) {
+        memset(gx64, 0, nx * sizeof(double));
+#pragma omp parallel for schedule(static)
+        for (int n = 0; n < N; ++n)                      /* images are independent */
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q)
+                    for (int k = 0; k < Cout; ++k) {
+                        const double g = gz[(((size_t)n * P + p) * Q + q) * Cout + k];
+                        for (int r = 0; r < R; ++r) {
+                            const int h = p * stride + r - pad;
+                            if (h < 0 || h >= H) continue;
+                            for (int s = 0; s < S; ++s) {
+                                const int ww = q * stride + s - pad;
+                                if (ww < 0 || ww >= W) continue;
+                                double *gp = gx64 + (((size_t)n * H + h) * W + ww) * Cin;
+                                const double *wp = wd + (((size_t)k * R + r) * S + s) * Cin;
+                                for (int c = 0; c < Cin; ++c) gp[c] += g * wp[c];
+                            }
+                        }
+                    }
+    }
+    if (gw64) {
+        memset(gw64, 0, nw * sizeof(double));
+#pragma omp parallel for schedule(static)
+        for (int k = 0; k < Cout; ++k)                   /* output channels are independent */
+            for (int n = 0; n < N; ++n)
+                for (int p = 0; p < P; ++p)
+                    for (int q = 0; q < Q; ++q) {
+                        const double g = gz[(((size_t)n * P + p) * Q + q) * Cout + k];
+                        for (int r = 0; r < R; ++r) {
+                            const int h = p * stride + r - pad;
+                            if (h < 0 || h >= H) continue;
+                            for (int s = 0; s < S; ++s) {
+                                const int ww = q * stride + s - pad;
+                                if (ww < 0 || ww >= W) continue;
+                                const double *xp = xd + (((size_t)n * H + h) * W + ww) * Cin;
+                                double *gp = gw64 + (((size_t)k * R + r) * S + s) * Cin;
+                                for (int c = 0; c < Cin; ++c) gp[c] += g * xp[c];
+                            }
+                        }
+                    }
+    }
+    free(xd); free(wd); free(gd); free(yd); free(gz);
     return 0;
 }

@@ -21,6 +21,9 @@ def lib():
         L.oracle_conv_bn_act.argtypes = ([ctypes.c_int] + [ctypes.c_void_p] * 7 + [ctypes.c_double]
                                          + [ctypes.c_int] * 10 + [ctypes.c_void_p] * 2)
         L.oracle_maxpool.restype = ctypes.c_int
+        L.oracle_conv_bn_act_bwd.argtypes = ([ctypes.c_int] + [ctypes.c_void_p] * 6 + [ctypes.c_double]
+                                             + [ctypes.c_int] * 10 + [ctypes.c_void_p] * 3)
+        L.oracle_conv_bn_act_bwd.restype = ctypes.c_int
         L.oracle_maxpool.argtypes = [ctypes.c_int, ctypes.c_void_p] + [ctypes.c_int] * 8 + [ctypes.c_void_p]
         L.oracle_avgpool.restype = ctypes.c_int
         L.oracle_avgpool.argtypes = [ctypes.c_int, ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
@@ -93,6 +96,41 @@ def conv_bn_act(x, w, bn, res=None, stride=1, pad=0, relu=True, dtype="f32", wan
     if rc != 0:
         raise ValueError("oracle_conv_bn_act rejected its arguments")
     return (y, y64) if want_f64 else y
+
+
+def conv_bn_act_bwd(x, w, bn, y, gy, stride=1, pad=0, relu=True, dtype="f32"):
+    """Backward of one fused layer (frozen batch-norm statistics).  x, w, y (stored forward
+    output; only read when relu) and gy = dL/dy at storage precision.  Returns float64 arrays
+    (gx, gw, gpre): dL/dx, dL/dw and dL/d(pre-activation), which is also dL/dres."""
+    x = np.ascontiguousarray(x, dtype=_np(dtype))
+    w = np.ascontiguousarray(w, dtype=_np(dtype))
+    gy = np.ascontiguousarray(gy, dtype=_np(dtype))
+    N, H, W, Cin = x.shape
+    Cout, R, S, Cin2 = w.shape
+    assert Cin == Cin2
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    assert gy.shape == (N, P, Q, Cout)
+    if relu:
+        y = np.ascontiguousarray(y, dtype=_np(dtype))
+        assert y.shape == gy.shape
+    else:
+        y = None
+    if bn is not None:
+        g, v = (np.ascontiguousarray(bn[k], dtype=np.float32) for k in ("gamma", "var"))
+        eps = float(bn["eps"])
+    else:
+        g = v = None
+        eps = 0.0
+    gx = np.empty(x.shape, dtype=np.float64)
+    gw = np.empty(w.shape, dtype=np.float64)
+    gpre = np.empty(gy.shape, dtype=np.float64)
+    rc = lib().oracle_conv_bn_act_bwd(_code(dtype), _ptr(x), _ptr(w), _ptr(y), _ptr(gy), _ptr(g), _ptr(v),
+                                      eps, N, H, W, Cin, Cout, R, S, stride, pad, 1 if relu else 0,
+                                      _ptr(gx), _ptr(gw), _ptr(gpre))
+    if rc != 0:
+        raise ValueError("oracle_conv_bn_act_bwd rejected its arguments")
+    return gx, gw, gpre
 
 
 def maxpool(x, R, S, stride, pad, dtype="f32"):
