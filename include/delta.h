@@ -209,6 +209,42 @@ delta_status delta_stats_reset(delta_ctx *ctx);
  * but move no bytes: the replay then shows what the step costs without the link. */
 delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
 
+/* ---- Backward of a fused convolution layer (frozen batch-norm statistics).
+ * The backward half of the training iteration whose tensor accesses the planner follows
+ * (DELTA Sec. 3, Assumptions 1-3: the backward pass reads the stored forward activations).
+ * For y = relu?(scale_k * conv(x, w) + shift_k (+ res)) and gy = dL/dy:
+ *     gpre = gy * [y > 0]  (gy itself without ReLU)      - also dL/dres
+ *     gx   = conv^T(gpre * scale, w) (+ gx_add)           - dL/dx
+ *     gw[k,r,s,c] = scale_k * sum_m gpre[m,k] * x[m+(r,s),c]   - dL/dw, fp32
+ * Supported: DELTA_OP_CONV with stride 1 and 2*pad == R-1 == S-1; gx for bf16 and fp32, gw for bf16
+ * with R in {1,3} and channel counts that are multiples of 64.  Anything else: DELTA_ERR_INVALID. */
+typedef struct delta_bwd_desc {
+    delta_layer_desc fwd;      /* the forward layer; fwd.x must be resident when gw is asked for,
+                                  fwd.y when fwd.relu != 0; fwd.res only says whether a residual exists */
+    uint32_t gy;               /* tensor id of dL/dy, resident, bytes of y */
+    uint32_t gpre;             /* tensor id that receives gpre (bytes of y; allocated if not resident).
+                                  Must equal gy when fwd.relu == 0 (nothing is written then) */
+    uint32_t gx;               /* tensor id that receives dL/dx (bytes of x), or DELTA_NO_TENSOR */
+    uint32_t gx_add;           /* resident tensor (bytes of x) added to dL/dx before it is stored: the
+                                  contribution of another consumer of x; or DELTA_NO_TENSOR */
+    const void *wt;            /* device: weights prepared by delta_bwd_weights (needed when gx is set) */
+    void *gw;                  /* device, fp32 [Cout][R][S][Cin]: receives dL/dw (overwritten), or NULL */
+    void *workspace;           /* device scratch for the weight gradient's partial sums, 16-byte aligned */
+    uint64_t workspace_bytes;  /* at least what delta_backward_workspace reports */
+} delta_bwd_desc;
+
+/* wt[c][R-1-r][S-1-s][k] = w[k][r][s][c] * scale[k] in the layer's storage type (same byte count as
+ * w): with these weights the data gradient is a forward convolution of gpre.  Device pointers;
+ * runs on the compute stream. */
+delta_status delta_bwd_weights(delta_ctx *ctx, const delta_layer_desc *layer, void *wt);
+/* Bytes of workspace delta_backward_segment needs for this layer's weight gradient (0 if the
+ * weight gradient is not supported for it). */
+delta_status delta_backward_workspace(delta_ctx *ctx, const delta_layer_desc *layer, uint64_t *out_bytes);
+/* Runs the descriptors in order on the compute stream.  Everything is validated before the first
+ * launch.  Output tensors are allocated from the arena when not resident (DELTA_ERR_OOM_ARENA);
+ * a non-resident input is DELTA_ERR_STATE. */
+delta_status delta_backward_segment(delta_ctx *ctx, const delta_bwd_desc *descs, uint32_t n);
+
 /* Name of the kernel variant that delta_recompute_segment would launch for this layer (the
  * operator DELTA re-runs, Sec. 3 / Table 1), written NUL-terminated into out[0..cap).  Validates
  * the descriptor exactly as delta_recompute_segment does; launches nothing.  Needs a context

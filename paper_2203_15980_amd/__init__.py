@@ -4,7 +4,7 @@ Everything here is argument marshalling; planning, recomputation and swapping al
 inside the library (include/delta.h).  There is no CPU fallback: importing works without
 a GPU, calling anything but `plan` needs one, and a missing library raises at load time.
 """
-from .binding import (Delta, DeltaError, LayerDesc, load_library, plan, layer_array,  # noqa: F401
+from .binding import (Delta, DeltaError, LayerDesc, BwdDesc, load_library, plan, layer_array,  # noqa: F401
                       OK, ERR_INVALID, ERR_INFEASIBLE, ERR_OOM_ARENA, ERR_OOM_PINNED, ERR_STATE,
                       ERR_BUFFER, ERR_HIP, F_UNCOMPUTABLE, F_EVICT_PINNED, F_OFFLOAD_PINNED,
                       FILTER_BASE, FILTER_LRU, FILTER_GREEDY, EV_EVICT, EV_OFFLOAD, EV_RECOMPUTE,

@@ -21,7 +21,8 @@ EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "d
            "delta_alloc", "delta_tensor_ptr", "delta_release", "delta_swap_out", "delta_prefetch",
            "delta_recompute_segment", "delta_sync", "delta_bn_fold", "delta_stats",
            "delta_stats_reset", "delta_set_skip_copies", "delta_probe_hostlink",
-           "delta_probe_hbm", "delta_probe_mfma", "delta_layer_kernel"]
+           "delta_probe_hbm", "delta_probe_mfma", "delta_layer_kernel", "delta_bwd_weights",
+           "delta_backward_workspace", "delta_backward_segment"]
 
 
 class TensorDesc(C.Structure):
@@ -50,6 +51,12 @@ class LayerDesc(C.Structure):
                 ("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("Cin", C.c_int32),
                 ("Cout", C.c_int32), ("R", C.c_int32), ("S", C.c_int32), ("stride", C.c_int32),
                 ("pad", C.c_int32), ("relu", C.c_uint32), ("op", C.c_uint32)]
+
+
+class BwdDesc(C.Structure):
+    _fields_ = [("fwd", LayerDesc), ("gy", C.c_uint32), ("gpre", C.c_uint32), ("gx", C.c_uint32),
+                ("gx_add", C.c_uint32), ("wt", C.c_void_p), ("gw", C.c_void_p), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_uint64)]
 
 
 class Stats(C.Structure):
@@ -115,6 +122,9 @@ def load_library():
         "delta_probe_hbm": (i32, [vp, u64, u32, C.POINTER(C.c_double)]),
         "delta_probe_mfma": (i32, [vp, u32, C.POINTER(C.c_double)]),
         "delta_layer_kernel": (i32, [vp, C.POINTER(LayerDesc), C.c_char_p, u64]),
+        "delta_bwd_weights": (i32, [vp, C.POINTER(LayerDesc), vp]),
+        "delta_backward_workspace": (i32, [vp, C.POINTER(LayerDesc), C.POINTER(u64)]),
+        "delta_backward_segment": (i32, [vp, C.POINTER(BwdDesc), u32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -235,6 +245,20 @@ class Delta:
         if isinstance(layers, (list, tuple)):
             layers = layer_array(layers)
         self._check(self.lib.delta_recompute_segment(self.ctx, layers, len(layers) if n is None else n))
+
+    def bwd_weights(self, layer, wt_ptr):
+        """Writes the data-gradient weights of `layer` (a LayerDesc) to device memory at wt_ptr."""
+        self._check(self.lib.delta_bwd_weights(self.ctx, layer_array([layer]), wt_ptr))
+
+    def backward_workspace(self, layer):
+        v = C.c_uint64()
+        self._check(self.lib.delta_backward_workspace(self.ctx, layer_array([layer]), C.byref(v)))
+        return v.value
+
+    def backward_segment(self, descs):
+        """`descs`: a list of BwdDesc."""
+        arr = (BwdDesc * len(descs))(*descs)
+        self._check(self.lib.delta_backward_segment(self.ctx, arr, len(descs)))
 
     def sync(self, which=SYNC_ALL):
         self._check(self.lib.delta_sync(self.ctx, which))

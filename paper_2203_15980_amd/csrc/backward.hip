@@ -1,0 +1,412 @@
+// Backward of the fused layer y = relu?(scale_k * conv(x, w) + shift_k (+ res)) for gfx950, bf16.
+//
+// DELTA's planner follows the tensor accesses of a whole training iteration (Sec. 3,
+// Assumptions 1-3: the backward pass reads the stored forward activations, which is why
+// released ones must be regenerated or reloaded).  These kernels are that backward pass for the
+// bottleneck layers, with frozen batch-norm statistics:
+//
+//   gpre = gy * [y > 0]                       relu_mask_kernel (also dL/dres)
+//   gx   = conv^T(gpre * scale, w)            the forward kernels, run on gpre with the weights
+//                                             transposed, flipped and pre-multiplied by scale
+//                                             (bwd_weights_kernel)
+//   gw[k,r,s,c] = scale_k * sum_m gpre[m,k] * x[m + (r,s), c]      wgrad_kernel + wgrad_reduce_kernel
+//
+// wgrad.  The reduction index is the pixel, and both operands are stored pixel-major (NHWC), so
+// neither has its reduction axis contiguous per lane the way an MFMA operand wants it.  gfx950's
+// LDS transpose read (ds_read_b64_tr_b16) does exactly that turn: 16 lanes each point at 4
+// consecutive 16-bit values (four rows of 16 channels) and each lane gets one channel's 4 values
+// along the rows.  So tiles are staged in LDS as they lie in memory (position rows x channels) and
+// both operands are read with two transpose reads per MFMA.
+// Image borders without masks: a chunk is RH image rows, laid out in LDS with the padding columns
+// and rows of the convolution made explicit (row length W + 2 for 3x3), zeros there.  A tap is
+// then a constant row offset, gpre is zero at the padding positions, and the reduction simply
+// runs over all positions of the padded layout (a few percent more MFMAs, no per-element mask).
+// One wavefront per (tap, 64 x 64 tile of [k, c]); the wavefronts of a workgroup share the staged
+// tiles.  Workgroups are persistent over chunks (split s takes chunks s, s + nsplit, ...) and
+// write their accumulators, in accumulator-register order, to a partial buffer; a second kernel
+// adds the partials in split order and applies scale_k.  No atomics: the result is a fixed
+// function of the inputs.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.hpp"
+
+namespace delta {
+namespace bwd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+static constexpr int kOutOfRange = (int)0x80000000;   // outside every buffer descriptor used here
+
+// ---------------------------------------------------------------- gpre = gy * [y > 0]
+// 16 bytes per thread, grid-stride.  bf16: y > 0 <=> sign bit clear and not zero (NaN counts as
+// "not greater": the forward's ReLU passes NaN through, its gradient is taken as 0).
+template <bool BF16>
+__global__ __launch_bounds__(256) void relu_mask_kernel(const u32x4 *__restrict__ y, const u32x4 *__restrict__ gy,
+                                                        u32x4 *__restrict__ out, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const u32x4 a = y[i], g = gy[i];
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if constexpr (BF16) {
+                const uint32_t lo = a[e] & 0xFFFFu, hi = a[e] >> 16;
+                const bool plo = lo != 0 && lo < 0x7F81u;      // positive, finite or +inf
+                const bool phi = hi != 0 && hi < 0x7F81u;
+                o[e] = (plo ? (g[e] & 0xFFFFu) : 0u) | (phi ? (g[e] & 0xFFFF0000u) : 0u);
+            } else {
+                o[e] = __uint_as_float(a[e]) > 0.f ? g[e] : 0u;
+            }
+        }
+        out[i] = o;
+    }
+}
+
+// ---------------------------------------------------------------- weights for the data gradient
+// wt[c][R-1-r][S-1-s][k] = round(w[k][r][s][c] * scale_k): the data gradient is then the forward
+// convolution of gpre with wt (stride 1, padding R-1-pad).  One thread per element of wt.
+template <bool BF16>
+__global__ __launch_bounds__(256) void bwd_weights_kernel(const void *w, const float *scale, void *wt, int K, int R,
+                                                          int S, int C) {
+    const size_t total = (size_t)K * R * S * C;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int k = (int)(i % K);
+    size_t rest = i / K;
+    const int s2 = (int)(rest % S); rest /= S;
+    const int r2 = (int)(rest % R);
+    const int c = (int)(rest / R);
+    const size_t src = (((size_t)k * R + (R - 1 - r2)) * S + (S - 1 - s2)) * C + c;
+    if constexpr (BF16) {
+        const float v = __uint_as_float((uint32_t)static_cast<const uint16_t *>(w)[src] << 16) * scale[k];
+        static_cast<__bf16 *>(wt)[i] = (__bf16)v;             // round to nearest even
+    } else {
+        static_cast<float *>(wt)[i] = static_cast<const float *>(w)[src] * scale[k];
+    }
+}
+
+// ---------------------------------------------------------------- weight gradient
+struct WgradArgs {
+    const void *x;       // [N,H,W,C] bf16
+    const void *g;       // [N,H,W,K] bf16 (gpre)
+    float *partial;      // [nsplit][tiles_y][waves][4 tiles][4][64 lanes] f32x4
+    int N, H, W, C, K, R;            // R = S in {1, 3}, stride 1, pad (R-1)/2
+    int RH;              // image rows per chunk
+    int QN;              // positions per chunk: RH * (W + R - 1), rounded up to 16
+    int XN;              // staged activation positions: QN + (R - 1) * (W + R - 1) + (R - 1)
+    int nsplit;
+};
+
+// KTW x CTW tiles of 64 x 64 [k, c] per workgroup and tap; TAPS = R * R.
+template <int KTW, int CTW, int TAPS>
+__global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs a) {
+    constexpr int NW = KTW * CTW * TAPS, NT = NW * 64;
+    constexpr int GP = KTW * 128 + 16, XP = CTW * 128 + 16;     // LDS row pitches (bytes)
+    constexpr int GSEG = KTW * 8, XSEG = CTW * 8;               // 16-byte segments per row
+    constexpr int MAXL = NT >= 512 ? 4 : 8;                      // staged 16-byte pieces per thread, each operand
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *gs = smem;                                    // [QN][GP]
+    unsigned char *xs = smem + (size_t)a.QN * GP;                // [XN][XP]
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tap = wv % TAPS, kw = (wv / TAPS) % KTW, cw = wv / (TAPS * KTW);
+    const int B = (a.R - 1) / 2, Wp = a.W + 2 * B;
+    const int r = tap / a.R, s = tap - r * a.R;
+    const int tapoff = a.R == 1 ? 0 : r * Wp + s;               // activation row of position q is q + tapoff
+    const int ktiles = a.K / (64 * KTW);
+    const int ty = blockIdx.y, ct = ty / ktiles, kt = ty - ct * ktiles;   // channel tile groups of this workgroup
+    const int HB = (a.H + a.RH - 1) / a.RH;
+    const int nchunks = a.N * HB;
+
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.x), 0, (int)((size_t)a.N * a.H * a.W * a.C * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.g), 0, (int)((size_t)a.N * a.H * a.W * a.K * 2), 0x00020000);
+
+    // ---- what this thread stages: piece p covers LDS row (tid + p NT) / SEG, segment % SEG.
+    // Per piece: image row relative to the chunk's first row, image column (or -1: a padding
+    // position, always zero), and the byte offset of the channel segment.
+    int g_row[MAXL], g_col[MAXL], x_row[MAXL], x_col[MAXL];
+#pragma unroll
+    for (int p = 0; p < MAXL; ++p) {
+        const int idx = tid + p * NT;
+        {
+            const int q = idx / GSEG;                            // position
+            const int pr = q / Wp, pc = q - pr * Wp;
+            const bool ok = q < a.RH * Wp && pc >= B && pc < B + a.W;
+            g_row[p] = q < a.QN ? pr : -2;                       // -2: this thread has no such piece
+            g_col[p] = ok ? pc - B : -1;
+        }
+        {
+            const int j = idx / XSEG;                            // staged activation row
+            // row j holds padded coordinate f = j - B: padded row f / Wp - B, padded column f % Wp
+            const int f = j - B;
+            const int pr = f >= 0 ? f / Wp : 0, pc = f >= 0 ? f - pr * Wp : 0;
+            const bool ok = f >= 0 && pc >= B && pc < B + a.W;
+            x_row[p] = j < a.XN ? pr - B : -1000000;             // relative image row (may be -1 or RH)
+            x_col[p] = ok ? pc - B : -1;
+        }
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    u32x4 rg[MAXL], rx[MAXL];
+    auto fetch = [&](int chunk) {                                // chunk >= nchunks: zeros
+        const bool live = chunk < nchunks;
+        const int n = chunk / HB, h0 = (chunk - n * HB) * a.RH;
+#pragma unroll
+        for (int p = 0; p < MAXL; ++p) {
+            const int idx = tid + p * NT;
+            {
+                const int h = h0 + g_row[p];
+                const bool ok = live && g_row[p] >= 0 && g_col[p] >= 0 && h < a.H;
+                const int off = (int)((((size_t)n * a.H + h) * a.W + g_col[p]) * a.K * 2) + kt * (KTW * 128) + (idx % GSEG) * 16;
+                rg[p] = __builtin_amdgcn_raw_buffer_load_b128(grsrc, ok ? off : kOutOfRange, 0, 0);
+            }
+            {
+                const int h = h0 + x_row[p];
+                const bool ok = live && x_col[p] >= 0 && h >= 0 && h < a.H && x_row[p] > -1000;
+                const int off = (int)((((size_t)n * a.H + h) * a.W + x_col[p]) * a.C * 2) + ct * (CTW * 128) + (idx % XSEG) * 16;
+                rx[p] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, ok ? off : kOutOfRange, 0, 0);
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int p = 0; p < MAXL; ++p) {
+            const int idx = tid + p * NT;
+            if (g_row[p] != -2) *reinterpret_cast<u32x4 *>(gs + (idx / GSEG) * GP + (idx % GSEG) * 16) = rg[p];
+            if (x_row[p] > -1000) *reinterpret_cast<u32x4 *>(xs + (idx / XSEG) * XP + (idx % XSEG) * 16) = rx[p];
+        }
+    };
+
+    // transpose-read addressing: lane supplies row (lane % 16) / 4 of a 4-row group and columns
+    // 16 * ((lane / 16) % 2) + 4 * (lane % 4) .. +3 of a 32-channel tile; it receives channel
+    // lane % 32 of the tile, rows 0..3 of the group.  Lanes 32..63 take positions 8..15 of a step.
+    const int srow = (lane & 15) >> 2;
+    const int scol = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int kgrp = lane >> 5;
+    const unsigned char *gbase = gs + (size_t)(8 * kgrp + srow) * GP + (kw * 64 + scol) * 2;
+    const unsigned char *xbase = xs + (size_t)(8 * kgrp + srow + tapoff) * XP + (cw * 64 + scol) * 2;
+    typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+    auto tr_read = [&](const unsigned char *p) {
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+    };
+
+    int chunk = blockIdx.x;
+    fetch(chunk);
+    for (; chunk < nchunks; chunk += a.nsplit) {
+        __syncthreads();                                         // every wavefront is done with the tiles
+        stage();
+        fetch(chunk + a.nsplit);                                 // next chunk of this split in flight
+        __syncthreads();
+        for (int q0 = 0; q0 < a.QN; q0 += 16) {
+            s16x8 af[2], bf[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const s16x4 a0 = tr_read(gbase + (size_t)q0 * GP + t * 64);
+                const s16x4 a1 = tr_read(gbase + (size_t)(q0 + 4) * GP + t * 64);
+                af[t] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+                const s16x4 b0 = tr_read(xbase + (size_t)q0 * XP + t * 64);
+                const s16x4 b1 = tr_read(xbase + (size_t)(q0 + 4) * XP + t * 64);
+                bf[t] = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // ---- partial sums, accumulator-register order: [split][ty][wave][i][j][e4][lane] x f32x4
+    float *out = a.partial + ((((size_t)blockIdx.x * gridDim.y + ty) * NW + wv) * 4) * (4 * 64 * 4);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const f32x4 v = {acc[i][j][4 * e4], acc[i][j][4 * e4 + 1], acc[i][j][4 * e4 + 2], acc[i][j][4 * e4 + 3]};
+                *reinterpret_cast<f32x4 *>(out + ((((i * 2 + j) * 4 + e4) * 64 + lane) * 4)) = v;
+            }
+}
+
+// gw[k][tap][c] = scale_k * sum over splits (in order) of the partial sums.  One thread per
+// output element; the accumulator layout of a 32x32 tile is: lane l holds column l % 32 and rows
+// 8 e4 + 4 (l / 32) + e of the tile in register 4 e4 + e.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int K,
+                                                           int C, int taps, int KTW, int CTW, int nsplit) {
+    const size_t total = (size_t)K * taps * C;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx % C);
+    const int tap = (int)((idx / C) % taps);
+    const int k = (int)(idx / ((size_t)C * taps));
+    const int ktiles = K / (64 * KTW), tiles_y = (C / (64 * CTW)) * ktiles;
+    const int kt = k / (64 * KTW), kw = (k / 64) % KTW, ct = c / (64 * CTW), cw = (c / 64) % CTW;
+    const int ty = ct * ktiles + kt;
+    const int NW = KTW * CTW * taps;
+    const int wv = (cw * KTW + kw) * taps + tap;
+    const int i = (k % 64) / 32, j = (c % 64) / 32;          // 32x32 tile inside the wavefront's 64x64
+    const int row = k % 32, col = c % 32;
+    const int e4 = row / 8, half = (row % 8) / 4, e = row % 4;
+    const int lane = col + 32 * half;
+    const size_t within = ((((size_t)(i * 2 + j) * 4 + e4) * 64 + lane) * 4) + e;
+    const size_t per_wave = 4 * (4 * 64 * 4);
+    float sum = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp)
+        sum += partial[(((size_t)sp * tiles_y + ty) * NW + wv) * per_wave + within];
+    gw[idx] = sum * scale[k];
+}
+
+}  // namespace bwd
+
+// ---------------------------------------------------------------- host side
+
+hipError_t launch_relu_mask(const void *y, const void *gy, void *out, size_t bytes, int bf16, hipStream_t stream) {
+    if (bytes % 16) return hipErrorInvalidValue;
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (bf16)
+        bwd::relu_mask_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+            static_cast<const bwd::u32x4 *>(y), static_cast<const bwd::u32x4 *>(gy), static_cast<bwd::u32x4 *>(out), n16);
+    else
+        bwd::relu_mask_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+            static_cast<const bwd::u32x4 *>(y), static_cast<const bwd::u32x4 *>(gy), static_cast<bwd::u32x4 *>(out), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_weights(const void *w, const float *scale, void *wt, int K, int R, int S, int C, int bf16,
+                              hipStream_t stream) {
+    const size_t total = (size_t)K * R * S * C;
+    if (total == 0 || total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (bf16) bwd::bwd_weights_kernel<true><<<dim3(blocks), dim3(256), 0, stream>>>(w, scale, wt, K, R, S, C);
+    else bwd::bwd_weights_kernel<false><<<dim3(blocks), dim3(256), 0, stream>>>(w, scale, wt, K, R, S, C);
+    return hipGetLastError();
+}
+
+namespace {
+
+struct WgradPlan {
+    int ktw, ctw, taps, rh, qn, xn, nsplit, tiles_y, waves;
+    size_t lds, partial_bytes;
+};
+
+// nullptr and a filled plan, or the reason the weight-gradient kernel does not apply.
+const char *wgrad_plan(const ConvArgs &a, WgradPlan &p) {
+    if (!a.bf16) return "weight gradient: bf16 only";
+    if (a.R != a.S || (a.R != 1 && a.R != 3) || a.stride != 1 || a.pad != (a.R - 1) / 2)
+        return "weight gradient: 1x1 or 3x3, stride 1, same padding only";
+    if (a.Cin % 64 || a.Cout % 64) return "weight gradient: channel counts must be multiples of 64";
+    if ((unsigned long long)a.M * a.Cin * 2ull >= 0x7FFFFFFFull || (unsigned long long)a.M * a.Cout * 2ull >= 0x7FFFFFFFull)
+        return "weight gradient: tensors of 2 GiB or more";
+    p.taps = a.R * a.S;
+    if (p.taps == 9) { p.ktw = 1; p.ctw = 1; }
+    else {
+        p.ktw = a.Cout % 256 == 0 ? 4 : (a.Cout % 128 == 0 ? 2 : 1);
+        p.ctw = 1;
+        if (p.ktw == 1) p.ctw = a.Cin % 256 == 0 ? 4 : (a.Cin % 128 == 0 ? 2 : 1);
+        else if (p.ktw == 2) p.ctw = a.Cin % 128 == 0 ? 2 : 1;
+    }
+    p.waves = p.ktw * p.ctw * p.taps;
+    const int Wp = a.W + (a.R - 1);
+    // image rows per chunk: about 128-256 positions, and at most maxl staged pieces per thread
+    int rh = (192 + Wp - 1) / Wp;
+    if (rh < 1) rh = 1;
+    if (rh > a.H) rh = a.H;
+    const int nt = p.waves * 64;
+    const long long maxl = nt >= 512 ? 4 : 8;      // as in the kernel
+    for (;; --rh) {
+        p.rh = rh;
+        p.qn = (rh * Wp + 15) / 16 * 16;
+        p.xn = p.qn + (a.R - 1) * Wp + (a.R - 1);
+        const long long gpieces = (long long)p.qn * p.ktw * 8, xpieces = (long long)p.xn * p.ctw * 8;
+        p.lds = (size_t)p.qn * (p.ktw * 128 + 16) + (size_t)p.xn * (p.ctw * 128 + 16);
+        if (gpieces <= maxl * nt && xpieces <= maxl * nt && p.lds <= 160 * 1024) break;
+        if (rh == 1) return "weight gradient: image row too wide for one chunk";
+    }
+    p.tiles_y = (a.Cin / (64 * p.ctw)) * (a.Cout / (64 * p.ktw));
+    const int chunks = a.N * ((a.H + p.rh - 1) / p.rh);
+    int ns = 512 / p.tiles_y;
+    if (ns < 1) ns = 1;
+    if (ns > 256) ns = 256;
+    if (ns > chunks) ns = chunks;
+    p.nsplit = ns;
+    p.partial_bytes = (size_t)p.nsplit * p.tiles_y * p.waves * 4 * (4 * 64 * 4) * sizeof(float);
+    return nullptr;
+}
+
+template <int KTW, int CTW, int TAPS>
+hipError_t launch_wgrad_t(const bwd::WgradArgs &wa, const WgradPlan &p, hipStream_t stream) {
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd::wgrad_kernel<KTW, CTW, TAPS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    bwd::wgrad_kernel<KTW, CTW, TAPS><<<dim3(p.nsplit, p.tiles_y), dim3(KTW * CTW * TAPS * 64), p.lds, stream>>>(wa);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+const char *wgrad_check(const ConvArgs &a) {
+    WgradPlan p;
+    return wgrad_plan(a, p);
+}
+
+size_t wgrad_workspace_bytes(const ConvArgs &a) {
+    WgradPlan p;
+    return wgrad_plan(a, p) ? 0 : p.partial_bytes;
+}
+
+// a: the forward layer's geometry with a.x = x, a.scale = scale; g = gpre [N,P,Q,Cout]; gw fp32
+// [Cout][R][S][Cin]; workspace of at least wgrad_workspace_bytes(a), 16-byte aligned.
+hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
+                        hipStream_t stream) {
+    WgradPlan p;
+    if (wgrad_plan(a, p) || !g || !gw || !workspace || workspace_bytes < p.partial_bytes ||
+        ((uintptr_t)workspace | (uintptr_t)g | (uintptr_t)a.x) & 15)
+        return hipErrorInvalidValue;
+    bwd::WgradArgs wa;
+    wa.x = a.x; wa.g = g; wa.partial = static_cast<float *>(workspace);
+    wa.N = a.N; wa.H = a.H; wa.W = a.W; wa.C = a.Cin; wa.K = a.Cout; wa.R = a.R;
+    wa.RH = p.rh; wa.QN = p.qn; wa.XN = p.xn; wa.nsplit = p.nsplit;
+    hipError_t e;
+    const int key = p.taps * 100 + p.ktw * 10 + p.ctw;
+    switch (key) {
+    case 911: e = launch_wgrad_t<1, 1, 9>(wa, p, stream); break;
+    case 111: e = launch_wgrad_t<1, 1, 1>(wa, p, stream); break;
+    case 112: e = launch_wgrad_t<1, 2, 1>(wa, p, stream); break;
+    case 114: e = launch_wgrad_t<1, 4, 1>(wa, p, stream); break;
+    case 121: e = launch_wgrad_t<2, 1, 1>(wa, p, stream); break;
+    case 122: e = launch_wgrad_t<2, 2, 1>(wa, p, stream); break;
+    case 141: e = launch_wgrad_t<4, 1, 1>(wa, p, stream); break;
+    default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    const size_t total = (size_t)a.Cout * p.taps * a.Cin;
+    bwd::wgrad_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(
+        wa.partial, a.scale, gw, a.Cout, a.Cin, p.taps, p.ktw, p.ctw, p.nsplit);
+    return hipGetLastError();
+}
+
+}  // namespace delta

@@ -82,6 +82,7 @@ struct delta_ctx {
     std::vector<Timed> timed;
     delta_stats_t st;
     bool skip_copies = false;
+    float *ones = nullptr, *zeros = nullptr;       // kMaxChannels floats each (identity scale/shift of the data gradient)
     uint64_t ev_seq = 0;
     std::string err;
 
@@ -369,6 +370,8 @@ void delta_destroy(delta_ctx *c) {
             (void)hipEventDestroy(c->timed[i].start);
             (void)hipEventDestroy(c->timed[i].stop);
         }
+        if (c->ones) (void)hipFree(c->ones);
+        if (c->zeros) (void)hipFree(c->zeros);
         (void)hipStreamDestroy(c->stream[S_D2H]);
         (void)hipStreamDestroy(c->stream[S_H2D]);
     }
@@ -761,6 +764,173 @@ delta_status delta_probe_hbm(delta_ctx *c, uint64_t bytes, uint32_t iters, doubl
     if (a) (void)hipFree(a);
     if (b) (void)hipFree(b);
     return rc;
+}
+
+// ---------------------------------------------------------------- backward of a layer
+namespace {
+
+constexpr uint32_t kMaxChannels = 8192;
+
+delta_status need_identity_factors(delta_ctx *c) {
+    if (c->ones) return DELTA_OK;
+    HIP_TRY(c, hipMalloc((void **)&c->ones, kMaxChannels * sizeof(float)));
+    HIP_TRY(c, hipMalloc((void **)&c->zeros, kMaxChannels * sizeof(float)));
+    std::vector<float> one(kMaxChannels, 1.0f);
+    HIP_TRY(c, hipMemcpy(c->ones, one.data(), kMaxChannels * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemset(c->zeros, 0, kMaxChannels * sizeof(float)));
+    return DELTA_OK;
+}
+
+// Validates one backward descriptor; fills the forward geometry (fa) and, if gx is asked for, the
+// convolution that computes the data gradient (da).  Pointers in fa/da are placeholders.
+delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, delta::ConvArgs &fa,
+                              delta::ConvArgs &da) {
+    delta::PoolArgs pa;
+    uint64_t flops = 0;
+    const delta_layer_desc &L = D.fwd;
+    delta_status r = prepare_layer(c, L, i, fa, pa, flops);
+    if (r != DELTA_OK) return r;
+    if (L.op != DELTA_OP_CONV || delta::stem_applies(fa))
+        return fail(c, DELTA_ERR_INVALID, "backward %u: only the tiled convolution layers have a backward", i);
+    if (L.stride != 1 || 2 * L.pad != L.R - 1 || 2 * L.pad != L.S - 1)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: needs stride 1 and 2*pad == R-1 == S-1", i);
+    const size_t nt = c->tensors.size();
+    const uint64_t ybytes = c->tensors[L.y].bytes, xbytes = c->tensors[L.x].bytes;
+    if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != ybytes)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gy/gpre must be tensors with the bytes of y", i);
+    if (!L.relu && D.gpre != D.gy)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: without ReLU gpre must be gy itself", i);
+    if (L.relu && (D.gpre == D.gy || D.gpre == L.y || D.gpre == L.x))
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gpre aliases another operand", i);
+    if (D.gx != DELTA_NO_TENSOR) {
+        if (D.gx >= nt || c->tensors[D.gx].bytes != xbytes)
+            return fail(c, DELTA_ERR_INVALID, "backward %u: gx must be a tensor with the bytes of x", i);
+        if (D.gx == D.gy || D.gx == D.gpre || D.gx == L.x || D.gx == L.y)
+            return fail(c, DELTA_ERR_INVALID, "backward %u: gx aliases another operand", i);
+        if (D.gx_add != DELTA_NO_TENSOR && (D.gx_add >= nt || c->tensors[D.gx_add].bytes != xbytes || D.gx_add == D.gx))
+            return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add must be another tensor with the bytes of x", i);
+        if (!D.wt || ((uintptr_t)D.wt & 15)) return fail(c, DELTA_ERR_INVALID, "backward %u: wt missing or misaligned", i);
+        if ((uint32_t)L.Cin > kMaxChannels) return fail(c, DELTA_ERR_INVALID, "backward %u: too many channels", i);
+        memset(&da, 0, sizeof da);
+        da.N = L.N; da.H = fa.P; da.W = fa.Q; da.Cin = L.Cout; da.Cout = L.Cin; da.R = L.R; da.S = L.S;
+        da.stride = 1; da.pad = L.R - 1 - L.pad; da.P = L.H; da.Q = L.W; da.M = L.N * L.H * L.W;
+        da.relu = 0; da.bf16 = fa.bf16;
+        da.x = da.y = c->arena; da.w = D.wt; da.scale = da.shift = reinterpret_cast<const float *>(c->arena);
+        const char *why = delta::conv_check(da);
+        if (why) return fail(c, DELTA_ERR_INVALID, "backward %u: data gradient: %s", i, why);
+    } else if (D.gx_add != DELTA_NO_TENSOR) {
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add without gx", i);
+    }
+    if (D.gw) {
+        const char *why = delta::wgrad_check(fa);
+        if (why) return fail(c, DELTA_ERR_INVALID, "backward %u: %s", i, why);
+        if (((uintptr_t)D.gw & 15) || !D.workspace || ((uintptr_t)D.workspace & 15) ||
+            D.workspace_bytes < delta::wgrad_workspace_bytes(fa))
+            return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned or workspace missing / too small", i);
+    }
+    return DELTA_OK;
+}
+
+// An output tensor of a launch on the compute stream: allocate it, or order the launch after
+// whatever still touches its block.
+delta_status compute_writes(delta_ctx *c, Tensor &t) {
+    delta_status r;
+    if (!t.resident) {
+        if ((r = arena_alloc(c, t.bytes, S_COMPUTE, &t.offset)) != DELTA_OK) return r;
+        t.resident = true;
+    } else {
+        if ((r = compute_uses(c, t)) != DELTA_OK) return r;
+        if (t.d2h_done) HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], t.d2h_done.e, 0));
+    }
+    t.host_valid = false;
+    return DELTA_OK;
+}
+
+}  // namespace
+
+delta_status delta_bwd_weights(delta_ctx *c, const delta_layer_desc *layer, void *wt) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!layer || !wt || ((uintptr_t)wt & 15)) return fail(c, DELTA_ERR_INVALID, "null or misaligned argument");
+    const delta_layer_desc &L = *layer;
+    if (L.op != DELTA_OP_CONV || !L.w || !L.scale || L.Cout <= 0 || L.Cin <= 0 || L.R <= 0 || L.S <= 0 ||
+        (L.dtype != DELTA_DTYPE_F32 && L.dtype != DELTA_DTYPE_BF16))
+        return fail(c, DELTA_ERR_INVALID, "not a convolution layer with weights and scale");
+    HIP_TRY(c, delta::launch_bwd_weights(L.w, L.scale, wt, L.Cout, L.R, L.S, L.Cin, L.dtype == DELTA_DTYPE_BF16,
+                                         c->stream[S_COMPUTE]));
+    return DELTA_OK;
+}
+
+delta_status delta_backward_workspace(delta_ctx *c, const delta_layer_desc *layer, uint64_t *out_bytes) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!layer || !out_bytes) return fail(c, DELTA_ERR_INVALID, "null argument");
+    delta::ConvArgs a;
+    delta::PoolArgs pa;
+    uint64_t flops = 0;
+    if ((r = prepare_layer(c, *layer, 0, a, pa, flops)) != DELTA_OK) return r;
+    *out_bytes = layer->op == DELTA_OP_CONV ? delta::wgrad_workspace_bytes(a) : 0;
+    return DELTA_OK;
+}
+
+delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, uint32_t n) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (!descs && n) return fail(c, DELTA_ERR_INVALID, "null descriptors");
+    delta::ConvArgs fa, da;
+    // Pass 1: validate everything, including residency as it will be when each step runs.
+    std::vector<uint8_t> will_exist(c->tensors.size(), 0);
+    auto there = [&](uint32_t t) { return c->tensors[t].resident || will_exist[t]; };
+    for (uint32_t i = 0; i < n; ++i) {
+        const delta_bwd_desc &D = descs[i];
+        if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
+        if (!there(D.gy)) return fail(c, DELTA_ERR_STATE, "backward %u: gy tensor %u is not resident", i, D.gy);
+        if (D.fwd.relu && !there(D.fwd.y)) return fail(c, DELTA_ERR_STATE, "backward %u: y tensor %u is not resident", i, D.fwd.y);
+        if (D.gw && !there(D.fwd.x)) return fail(c, DELTA_ERR_STATE, "backward %u: x tensor %u is not resident", i, D.fwd.x);
+        if (D.gx_add != DELTA_NO_TENSOR && !there(D.gx_add))
+            return fail(c, DELTA_ERR_STATE, "backward %u: gx_add tensor %u is not resident", i, D.gx_add);
+        will_exist[D.gpre] = 1;
+        if (D.gx != DELTA_NO_TENSOR) will_exist[D.gx] = 1;
+    }
+    if ((r = need_identity_factors(c)) != DELTA_OK) return r;
+    hipStream_t s = c->stream[S_COMPUTE];
+    for (uint32_t i = 0; i < n; ++i) {
+        const delta_bwd_desc &D = descs[i];
+        const delta_layer_desc &L = D.fwd;
+        if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
+        Tensor &tgy = c->tensors[D.gy];
+        if ((r = compute_uses(c, tgy)) != DELTA_OK) return r;
+        if (L.relu) {
+            Tensor &ty = c->tensors[L.y], &tgp = c->tensors[D.gpre];
+            if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+            if ((r = compute_writes(c, tgp)) != DELTA_OK) return r;
+            HIP_TRY(c, delta::launch_relu_mask(c->arena + ty.offset, c->arena + tgy.offset, c->arena + tgp.offset,
+                                               tgp.bytes, fa.bf16, s));
+        }
+        const unsigned char *gp = c->arena + c->tensors[D.gpre].offset;
+        if (D.gx != DELTA_NO_TENSOR) {
+            Tensor &tgx = c->tensors[D.gx];
+            const unsigned char *addp = nullptr;
+            if (D.gx_add != DELTA_NO_TENSOR) {
+                if ((r = compute_uses(c, c->tensors[D.gx_add])) != DELTA_OK) return r;
+                addp = c->arena + c->tensors[D.gx_add].offset;
+            }
+            if ((r = compute_writes(c, tgx)) != DELTA_OK) return r;
+            da.x = gp; da.w = D.wt; da.res = addp; da.y = c->arena + tgx.offset;
+            da.scale = c->ones; da.shift = c->zeros;
+            HIP_TRY(c, delta::launch_conv(da, s));
+            c->st.recompute_flops += 2ull * (uint64_t)da.M * da.R * da.S * da.Cin * da.Cout;
+        }
+        if (D.gw) {
+            Tensor &tx = c->tensors[L.x];
+            if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
+            fa.x = c->arena + tx.offset;
+            HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, D.workspace_bytes, s));
+            c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
+        }
+        c->st.recompute_launches += 1;
+    }
+    return DELTA_OK;
 }
 
 delta_status delta_layer_kernel(delta_ctx *c, const delta_layer_desc *layer, char *out, uint64_t cap) {

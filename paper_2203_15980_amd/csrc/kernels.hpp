@@ -44,6 +44,16 @@ hipError_t launch_avgpool(const PoolArgs &a, hipStream_t stream);
 hipError_t launch_softmax_ce(const void *logits, const void *labels, int N, int classes, int bf16, float *out,
                              hipStream_t stream);
 
+// backward.hip: backward of the fused layer (bf16 weight gradient; data gradient through the
+// forward kernels with transformed weights)
+hipError_t launch_relu_mask(const void *y, const void *gy, void *out, size_t bytes, int bf16, hipStream_t stream);
+hipError_t launch_bwd_weights(const void *w, const float *scale, void *wt, int K, int R, int S, int C, int bf16,
+                              hipStream_t stream);
+const char *wgrad_check(const ConvArgs &a);            // nullptr when the weight-gradient kernel applies
+size_t wgrad_workspace_bytes(const ConvArgs &a);
+hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
+                        hipStream_t stream);
+
 hipError_t launch_bn_fold(const float *gamma, const float *beta, const float *mean, const float *var,
                           float eps, unsigned C, float *scale, float *shift, hipStream_t stream);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);

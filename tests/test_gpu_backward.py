@@ -1,0 +1,145 @@
+"""GPU parity of the backward kernels (through the C ABI) against the CPU oracle.
+
+The ReLU mask is decided from the *stored* forward output, so the oracle is given the GPU's own y
+(both sides then take that decision on the same bits) and gpre must match bit for bit.  dL/dx is
+stored in bf16 from fp32 sums of bf16 products, with weights that carry one extra bf16 rounding
+(w * scale): 2e-2 of the tensor's maximum, as for the forward.  dL/dw is fp32 sums of exact
+products: 2e-4 of its maximum."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import numeric as on
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+CASES = [
+    # name        N   H   W  Cin Cout R relu res  add
+    ("1x1_64_256", 2, 12, 12,  64, 256, 1, True, True, False),
+    ("1x1_256_64", 3,  9, 11, 256,  64, 1, True, False, True),
+    ("1x1_norelu", 2,  7,  7,  64,  64, 1, False, False, False),
+    ("3x3_64",     2, 14, 14,  64,  64, 3, True, False, False),
+    ("3x3_128",    1,  9, 11, 128, 128, 3, True, False, True),     # non-square, accumulate into gx
+    ("3x3_wide",   1,  3, 56,  64,  64, 3, True, False, False),    # config 2's row length
+    ("1x1_128_128", 2, 10, 10, 128, 128, 1, True, False, False),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_layer_backward_matches_oracle(torch_mod, case):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    name, N, H, W, Cin, Cout, R, relu, has_res, has_add = case
+    print("case", name, flush=True)
+    pad = (R - 1) // 2
+    l = synth.LayerSpec(name, "conv", "x0", "r0" if has_res else None, name, N, H, W, Cin, Cout, R, R, 1, pad, relu)
+    l.index = 1
+    master = 91
+    x = synth.make_input(master, (N, H, W, Cin), "bf16")
+    p = synth.make_params(master, l, "bf16")
+    yshape = (N, H, W, Cout)
+    bits = lambda aid, shape: synth.f32_to_bf16_bits(
+        synth.normal(master, aid, int(np.prod(shape))).astype(np.float32)).reshape(shape)
+    res = bits(901, yshape) if has_res else None
+    gy = bits(902, yshape)
+    add = bits(903, x.shape) if has_add else None
+
+    arena = torch.empty(96 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    ysz, xsz = int(np.prod(yshape)) * 2, x.nbytes
+    # tensors: 0 x, 1 res, 2 y, 3 gy, 4 gpre, 5 gx, 6 gx_add
+    d.bind([xsz, ysz, ysz, ysz, ysz, xsz, xsz])
+    base = d.arena.data_ptr()
+
+    def put(tid, a):
+        ptr = d.alloc(tid)
+        d.arena[ptr - base:ptr - base + a.nbytes].copy_(_dev(torch, a.view(np.uint8).reshape(-1)))
+
+    def get(tid, shape, dtype=np.uint16):
+        ptr = d.tensor_ptr(tid)
+        n = int(np.prod(shape)) * np.dtype(dtype).itemsize
+        return d.arena[ptr - base:ptr - base + n].cpu().numpy().view(dtype).reshape(shape)
+
+    put(0, x)
+    if has_res:
+        put(1, res)
+    put(3, gy)
+    if has_add:
+        put(6, add)
+    w = _dev(torch, p["w"])
+    bn = [_dev(torch, p[k]) for k in ("gamma", "beta", "mean", "var")]
+    scale = torch.empty(Cout, dtype=torch.float32, device="cuda:0")
+    shift = torch.empty(Cout, dtype=torch.float32, device="cuda:0")
+    d.bn_fold(bn[0].data_ptr(), bn[1].data_ptr(), bn[2].data_ptr(), bn[3].data_ptr(), float(p["eps"]),
+              Cout, scale.data_ptr(), shift.data_ptr())
+    fwd = dl.LayerDesc(x=0, res=1 if has_res else dl.NO_TENSOR, y=2, dtype=dl.DTYPE_BF16, w=w.data_ptr(),
+                       scale=scale.data_ptr(), shift=shift.data_ptr(), N=N, H=H, W=W, Cin=Cin, Cout=Cout,
+                       R=R, S=R, stride=1, pad=pad, relu=1 if relu else 0)
+    d.recompute_segment([fwd])                           # the forward, so that y is the GPU's own
+    wt = torch.empty(Cout * R * R * Cin, dtype=torch.uint16, device="cuda:0")
+    d.bwd_weights(fwd, wt.data_ptr())
+    ws_bytes = d.backward_workspace(fwd)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
+    desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if relu else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
+                      wt=wt.data_ptr(), gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
+    d.backward_segment([desc])
+    d.sync()
+
+    y_gpu = get(2, yshape)
+    ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(x, p["w"], p, y_gpu, gy, stride=1, pad=pad, relu=relu, dtype="bf16")
+    if has_add:
+        ref_gx = ref_gx + on.to_f64(add, "bf16")
+    # gpre: pure masking, bit for bit
+    gpre_gpu = get(4 if relu else 3, yshape)
+    assert np.array_equal(on.to_f64(gpre_gpu, "bf16"), ref_gpre)
+    if relu:
+        assert (ref_gpre == 0).any() and (ref_gpre != 0).any()
+    # the transformed weights: w[k][r][s][c] * scale[k], flipped and transposed, one bf16 rounding
+    s64 = p["gamma"].astype(np.float64) / np.sqrt(p["var"].astype(np.float64) + p["eps"])
+    want_wt = (on.to_f64(p["w"], "bf16") * s64[:, None, None, None])[:, ::-1, ::-1, :].transpose(3, 1, 2, 0)
+    got_wt = on.to_f64(wt.cpu().numpy().reshape(Cin, R, R, Cout), "bf16")
+    assert np.max(np.abs(got_wt - want_wt)) <= 2.0 ** -8 * np.max(np.abs(want_wt))
+    gx_gpu = on.to_f64(get(5, x.shape), "bf16")
+    err_x = float(np.max(np.abs(gx_gpu - ref_gx)) / np.max(np.abs(ref_gx)))
+    gw_gpu = gw.cpu().numpy().astype(np.float64)
+    assert np.isfinite(gw_gpu).all()
+    err_w = float(np.max(np.abs(gw_gpu - ref_gw)) / np.max(np.abs(ref_gw)))
+    print("  gx err %.2e  gw err %.2e" % (err_x, err_w), flush=True)
+    assert err_x <= 2e-2, (name, err_x)
+    assert err_w <= 2e-4, (name, err_w)
+    d.close()
+
+
+def test_backward_rejects_what_it_does_not_support(torch_mod):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    arena = torch.empty(8 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    N, H, W, C = 1, 8, 8, 64
+    xs, ys = N * H * W * C * 2, N * 4 * 4 * C * 2
+    d.bind([xs, ys, ys, ys, xs])
+    for t in (0, 2):
+        d.alloc(t)
+    dummy = torch.zeros(C * 9 * C + 64, dtype=torch.uint16, device="cuda:0")
+    f32 = torch.zeros(C, dtype=torch.float32, device="cuda:0")
+    s2 = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=dummy.data_ptr(), scale=f32.data_ptr(),
+                      shift=f32.data_ptr(), N=N, H=H, W=W, Cin=C, Cout=C, R=3, S=3, stride=2, pad=1, relu=0)
+    with pytest.raises(dl.DeltaError) as e:              # stride 2 has no backward yet
+        d.backward_segment([dl.BwdDesc(fwd=s2, gy=2, gpre=2, gx=4, gx_add=dl.NO_TENSOR, wt=dummy.data_ptr(),
+                                       gw=None, workspace=None, workspace_bytes=0)])
+    assert e.value.status == dl.ERR_INVALID
+    d.close()
