@@ -115,6 +115,106 @@ class Net:
     def recompute(self, name):
         self.delta.recompute_segment(self.desc[name])
 
+    # -- backward pass (convolution layers with stride 1 and "same" padding)
+    def enable_backward(self, input_gradient=False):
+        """Adds the gradient tensors to the tensor table (re-binds: call while nothing is
+        resident), prepares the data-gradient weights, the fp32 weight-gradient buffers and the
+        shared workspace.  Gradient tensors are transient: allocated when written, released
+        after their last use; they are not part of the planned graph.  `input_gradient`: also
+        compute dL/dx0."""
+        d, dev = self.delta, self.device
+        self.n_graph = len(self.sizes)
+        self.bwd_ids, self.bwd_layers = {}, []
+        extra = []
+
+        def new_tensor(name, nbytes, shape):
+            self.bwd_ids[name] = self.n_graph + len(extra)
+            extra.append(nbytes)
+            self.shapes[name], self.np_dtype[name] = shape, (np.float32 if self.dtype == "f32" else np.uint16)
+            return self.bwd_ids[name]
+
+        top = self.layers[-1]
+        new_tensor("g:" + top.y, self.sizes[self.ids[top.y]], self.shapes[top.y])
+        for l in self.layers:
+            if l.kind != "conv":
+                raise ValueError("backward: layer kind %r has no backward kernel" % l.kind)
+            if l.relu:
+                new_tensor("gp:" + l.name, self.sizes[self.ids[l.y]], self.shapes[l.y])
+            if l.x != "x0" or input_gradient:
+                new_tensor("g:" + l.x + ":" + l.name, self.sizes[self.ids[l.x]], self.shapes[l.x])
+        self.all_sizes = self.sizes + extra
+        for name, tid in self.bwd_ids.items():
+            self.ids[name] = tid
+        self.sizes = self.all_sizes
+        d.bind(self.all_sizes)
+        self.wt, self.gw = {}, {}
+        ws_bytes = 16
+        for l in self.layers:
+            fwd = self.desc[l.y][0]
+            n = l.Cout * l.R * l.S * l.Cin
+            self.wt[l.name] = torch.empty(n * self.es, dtype=torch.uint8, device=dev)
+            d.bwd_weights(fwd, self.wt[l.name].data_ptr())
+            self.gw[l.name] = torch.zeros(n, dtype=torch.float32, device=dev)
+            ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
+        self.bwd_workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.input_gradient = input_gradient
+        self.top_gradient_np = synth.f32_to_bf16_bits(
+            synth.normal(self.master, 7001, int(np.prod(self.shapes[top.y]))).astype(np.float32)
+        ).reshape(self.shapes[top.y]) if self.dtype == "bf16" else synth.normal(
+            self.master, 7001, int(np.prod(self.shapes[top.y]))).astype(np.float32).reshape(self.shapes[top.y])
+        self.sources[self.ids["g:" + top.y]] = _dev(self.top_gradient_np.view(np.uint8).reshape(-1), dev)
+        self.pending = {}
+        torch.cuda.synchronize()
+
+    def backward_begin(self):
+        """Loads the gradient of the last layer's output (seeded, synthetic: it stands in for the
+        loss's gradient)."""
+        top = self.layers[-1]
+        self.load_source(self.ids["g:" + top.y])
+        self.pending = {top.y: "g:" + top.y}
+        self.bwd_trace = []
+
+    def backward_layer(self, l, keep=False):
+        """Backward of layer `l`; every consumer of l.y must have run its backward already.
+        Frees gradient tensors after their last use unless `keep` (tests read them back)."""
+        d = self.delta
+        fwd = self.desc[l.y][0]
+        gy_name = self.pending.pop(l.y)
+        gpre_name = "gp:" + l.name if l.relu else gy_name
+        want_gx = l.x != "x0" or self.input_gradient
+        gx_name = "g:" + l.x + ":" + l.name if want_gx else None
+        add_name = self.pending.get(l.x) if want_gx else None
+        desc = B.BwdDesc(fwd=fwd, gy=self.ids[gy_name], gpre=self.ids[gpre_name],
+                         gx=self.ids[gx_name] if gx_name else B.NO_TENSOR,
+                         gx_add=self.ids[add_name] if add_name else B.NO_TENSOR,
+                         wt=self.wt[l.name].data_ptr(),
+                         gw=self.gw[l.name].data_ptr() if self.dtype == "bf16" else None,   # weight gradient: bf16 only
+                         workspace=self.bwd_workspace.data_ptr(), workspace_bytes=self.bwd_workspace.numel())
+        d.backward_segment([desc])
+        self.bwd_trace.append((l.name, gy_name, gpre_name, gx_name, add_name))
+        dead = []
+        if gx_name:
+            self.pending[l.x] = gx_name
+            if add_name:
+                dead.append(add_name)
+        if l.res:
+            # the residual branch receives gpre; in a ResNet this is its first contribution
+            assert l.res not in self.pending, "residual gradient would need an add kernel"
+            self.pending[l.res] = gpre_name
+        elif gpre_name != gy_name:
+            dead.append(gpre_name)
+        if gpre_name != gy_name or not l.res:
+            dead.append(gy_name)
+        if not keep:
+            for name in dict.fromkeys(dead):
+                d.release(self.ids[name], B.EV_FREE)
+
+    def backward(self, keep=False):
+        """Whole backward pass, last layer first (forward activations must be resident)."""
+        self.backward_begin()
+        for l in reversed(self.layers):
+            self.backward_layer(l, keep=keep)
+
 
 def run_plan(net, graph, events, backward_proxy=None):
     """One training-step replay.  Forward steps run their layer, backward steps call

@@ -143,3 +143,61 @@ def test_backward_rejects_what_it_does_not_support(torch_mod):
                                        gw=None, workspace=None, workspace_bytes=0)])
     assert e.value.status == dl.ERR_INVALID
     d.close()
+
+
+def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod):
+    """Three bottleneck blocks (config 2's layer shapes at 2 x 16 x 16): the whole backward pass
+    through the harness.  Layer by layer, the oracle is given exactly what the GPU's layer was
+    given (its stored x, y and incoming gradient) and must reproduce what the layer wrote; end
+    to end, the oracle runs its own chain and dL/dx0 must agree within the bf16 tolerance."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    layers = synth.bottleneck_stack(2, 16, 16)
+    g = synth.fused_graph(layers, "bf16")
+    arena = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", synth.master_seed(2))
+    net.enable_backward(input_gradient=True)
+    net.forward()
+    net.backward(keep=True)
+    d.sync()
+    acts = {"x0": net.x0_np}
+    for l in layers:
+        acts[l.y] = net.read(l.y)
+    by_name = {l.name: l for l in layers}
+    for (lname, gy_name, gpre_name, gx_name, add_name) in net.bwd_trace:
+        l = by_name[lname]
+        p = net.params_np[lname]
+        gy = net.read(gy_name)
+        ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(acts[l.x], p["w"], p, acts[l.y], gy, stride=l.stride,
+                                                      pad=l.pad, relu=l.relu, dtype="bf16")
+        assert np.array_equal(on.to_f64(net.read(gpre_name), "bf16"), ref_gpre), lname
+        if add_name:
+            ref_gx = ref_gx + on.to_f64(net.read(add_name), "bf16")
+        got_gx = on.to_f64(net.read(gx_name), "bf16")
+        ex = float(np.max(np.abs(got_gx - ref_gx)) / np.max(np.abs(ref_gx)))
+        got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
+        ew = float(np.max(np.abs(got_gw - ref_gw)) / np.max(np.abs(ref_gw)))
+        print("  %-8s gx %.2e gw %.2e" % (lname, ex, ew), flush=True)
+        assert ex <= 2e-2 and ew <= 2e-4, (lname, ex, ew)
+    # end to end: the oracle's own forward (bf16 storage) and backward chain
+    ref = on.run_layers(layers, net.params_np, net.x0_np, "bf16")
+    grads = {layers[-1].y: on.to_f64(net.top_gradient_np, "bf16")}
+    rnd = lambda a: on.to_f64(synth.f32_to_bf16_bits(a.astype(np.float32)), "bf16")   # gradients are stored in bf16
+    for l in reversed(layers):
+        p = net.params_np[l.name]
+        gy_bits = synth.f32_to_bf16_bits(grads.pop(l.y).astype(np.float32)).reshape(ref[l.y].shape)
+        x_in = net.x0_np if l.x == "x0" else ref[l.x]
+        gx, gw, gpre = on.conv_bn_act_bwd(x_in, p["w"], p, ref[l.y], gy_bits, stride=l.stride, pad=l.pad,
+                                          relu=l.relu, dtype="bf16")
+        if l.res:
+            grads[l.res] = grads.get(l.res, 0) + gpre
+        grads[l.x] = rnd(grads.get(l.x, 0) + gx)
+    last = net.bwd_trace[-1]
+    got = on.to_f64(net.read(last[3]), "bf16")
+    err = float(np.max(np.abs(got - grads["x0"])) / np.max(np.abs(grads["x0"])))
+    print("  end to end dL/dx0 err %.2e" % err, flush=True)
+    assert err <= 5e-2, err
+    d.close()
