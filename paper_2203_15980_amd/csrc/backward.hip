@@ -245,32 +245,48 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
             }
 }
 
-// gw[k][tap][c] = scale_k * sum over splits (in order) of the partial sums.  One thread per
-// output element; the accumulator layout of a 32x32 tile is: lane l holds column l % 32 and rows
-// 8 e4 + 4 (l / 32) + e of the tile in register 4 e4 + e.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int K,
+// gw[k][tap][c] = scale_k * sum over splits of the partial sums, in a fixed order.  A workgroup
+// takes 64 consecutive f32x4 of the blob (one per lane) and spreads the splits over its 8
+// wavefronts (wavefront g adds splits g, g + 8, ...), which keeps enough loads in flight for a
+// reduction that is pure HBM traffic; the 8 sums are then added in wavefront order.  The
+// accumulator layout of a 32x32 tile is: lane l holds column l % 32 and rows 8 e4 + 4 (l / 32) + e
+// in register 4 e4 + e, so a thread's four sums go to four k rows of one c, and consecutive lanes
+// write consecutive c.
+__global__ __launch_bounds__(512) void wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int K,
                                                            int C, int taps, int KTW, int CTW, int nsplit) {
-    const size_t total = (size_t)K * taps * C;
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int c = (int)(idx % C);
-    const int tap = (int)((idx / C) % taps);
-    const int k = (int)(idx / ((size_t)C * taps));
+    __shared__ f32x4 part[8][64];
     const int ktiles = K / (64 * KTW), tiles_y = (C / (64 * CTW)) * ktiles;
-    const int kt = k / (64 * KTW), kw = (k / 64) % KTW, ct = c / (64 * CTW), cw = (c / 64) % CTW;
-    const int ty = ct * ktiles + kt;
     const int NW = KTW * CTW * taps;
-    const int wv = (cw * KTW + kw) * taps + tap;
-    const int i = (k % 64) / 32, j = (c % 64) / 32;          // 32x32 tile inside the wavefront's 64x64
-    const int row = k % 32, col = c % 32;
-    const int e4 = row / 8, half = (row % 8) / 4, e = row % 4;
-    const int lane = col + 32 * half;
-    const size_t within = ((((size_t)(i * 2 + j) * 4 + e4) * 64 + lane) * 4) + e;
-    const size_t per_wave = 4 * (4 * 64 * 4);
-    float sum = 0.f;
-    for (int sp = 0; sp < nsplit; ++sp)
-        sum += partial[(((size_t)sp * tiles_y + ty) * NW + wv) * per_wave + within];
-    gw[idx] = sum * scale[k];
+    const size_t per_split = (size_t)tiles_y * NW * 1024;      // f32x4 elements per split (a multiple of 64)
+    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const size_t idx = (size_t)blockIdx.x * 64 + lane;
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(partial) + idx;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    int sp = grp;
+    for (; sp + 24 < nsplit; sp += 32) {                       // four independent loads in flight
+        const f32x4 v0 = src[(size_t)sp * per_split], v1 = src[(size_t)(sp + 8) * per_split];
+        const f32x4 v2 = src[(size_t)(sp + 16) * per_split], v3 = src[(size_t)(sp + 24) * per_split];
+        sum += v0; sum += v1; sum += v2; sum += v3;
+    }
+    for (; sp < nsplit; sp += 8) sum += src[(size_t)sp * per_split];
+    part[grp][lane] = sum;
+    __syncthreads();
+    if (grp != 0) return;
+#pragma unroll
+    for (int g = 1; g < 8; ++g) sum += part[g][lane];
+    // idx = (((ty * NW + wv) * 4 + tile) * 4 + e4) * 64 + lane
+    const int e4 = (int)((idx >> 6) & 3), tile = (int)((idx >> 8) & 3);
+    const int wv = (int)((idx >> 10) % NW), ty = (int)((idx >> 10) / NW);
+    const int tap = wv % taps, kw = (wv / taps) % KTW, cw = wv / (taps * KTW);
+    const int ct = ty / ktiles, kt = ty - ct * ktiles;
+    const int i = tile >> 1, j = tile & 1;
+    const int c = (ct * CTW + cw) * 64 + j * 32 + (lane & 31);
+    const int k0 = (kt * KTW + kw) * 64 + i * 32 + 8 * e4 + 4 * (lane >> 5);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int k = k0 + e;
+        gw[((size_t)k * taps + tap) * C + c] = sum[e] * scale[k];
+    }
 }
 
 }  // namespace bwd
@@ -403,8 +419,8 @@ hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *works
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    const size_t total = (size_t)a.Cout * p.taps * a.Cin;
-    bwd::wgrad_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(
+    const size_t quads = (size_t)p.tiles_y * p.waves * 1024;   // f32x4 elements of one split
+    bwd::wgrad_reduce_kernel<<<dim3((unsigned)(quads / 64)), dim3(512), 0, stream>>>(
         wa.partial, a.scale, gw, a.Cout, a.Cin, p.taps, p.ktw, p.ctw, p.nsplit);
     return hipGetLastError();
 }
