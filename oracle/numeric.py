@@ -162,6 +162,52 @@ def softmax_ce(logits, labels, dtype="f32"):
     return np.array([np.mean(lse - picked)], dtype=np.float32)
 
 
+def maxpool_bwd(x, gy, R, S, stride, pad, dtype="f32"):
+    """Backward of max pooling: the gradient of an output pixel goes to the maximal element of its
+    window; among equal maxima to the first in scan order (r, then s) - the element the forward's
+    scan `if v > m` keeps.  Padding never receives anything.  float64 [N,H,W,C]."""
+    xd, gd = to_f64(x, dtype), to_f64(gy, dtype)
+    N, H, W, C = xd.shape
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    assert gd.shape == (N, P, Q, C)
+    gx = np.zeros_like(xd)
+    n_idx, c_idx = np.meshgrid(np.arange(N), np.arange(C), indexing="ij")
+    for p in range(P):
+        for q in range(Q):
+            hs = [p * stride + r - pad for r in range(R)]
+            ws = [q * stride + s_ - pad for s_ in range(S)]
+            cand = [(h, w) for h in hs for w in ws if 0 <= h < H and 0 <= w < W]   # scan order
+            vals = np.stack([xd[:, h, w, :] for (h, w) in cand], axis=0)            # [cand, N, C]
+            first = np.argmax(vals, axis=0)                                         # first maximum
+            for i, (h, w) in enumerate(cand):
+                gx[:, h, w, :] += np.where(first == i, gd[:, p, q, :], 0.0)
+    return gx
+
+
+def avgpool_bwd(gy, H, W, dtype="f32"):
+    """Backward of the global average: every pixel receives gy / (H W).  float64 [N,H,W,C]."""
+    gd = to_f64(gy, dtype)
+    N, C = gd.shape[0], gd.shape[-1]
+    return np.broadcast_to(gd.reshape(N, 1, 1, C) / float(H * W), (N, H, W, C)).copy()
+
+
+def softmax_ce_bwd(logits, labels, dtype="f32"):
+    """Gradient of the mean cross-entropy with respect to the logits:
+    (softmax(z_i) - onehot(label_i)) / N.  float64 [N, classes]."""
+    z = to_f64(logits, dtype).reshape(len(labels), -1)
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    g = e / e.sum(axis=1, keepdims=True)
+    g[np.arange(len(labels)), np.asarray(labels, dtype=np.int64)] -= 1.0
+    return g / float(len(labels))
+
+
+def fc_bwd(x, w, gy, dtype="f32"):
+    """Backward of z = x w^T + bias (the classifier): returns float64 (gx, gw, gbias)."""
+    gx, gw, _ = conv_bn_act_bwd(x, w, None, None, gy, stride=1, pad=0, relu=False, dtype=dtype)
+    return gx, gw, to_f64(gy, dtype).reshape(-1, gy.shape[-1]).sum(axis=0)
+
+
 def run_layers(layers, params, x0, dtype, labels=None):
     """Forward of a list of synth.LayerSpec layers; returns {tensor name: stored array}.  With
     `labels`, the mean cross-entropy of the last layer's output is added as "loss"."""

@@ -172,3 +172,77 @@ def test_bf16_operands_are_taken_at_their_stored_values():
     b = on.conv_bn_act_bwd(f(xb), f(wb), bn, f(yb), f(gb), stride=1, pad=1, relu=True, dtype="f32")
     for u, v in zip(a, b):
         assert np.array_equal(u, v)
+
+
+def test_maxpool_backward_routes_to_the_first_maximum():
+    """Finite differences of the (pinned) forward on tie-free data; conservation of the gradient
+    sum; and the tie rule on a hand-made window."""
+    N, H, W, C = 2, 7, 6, 3
+    n = N * H * W * C
+    order = np.argsort(synth.normal(71, 7, n))              # a seeded permutation
+    x = ((order.astype(np.float64) - n / 2) / 256.0).astype(np.float32).reshape(N, H, W, C)
+    assert len(np.unique(x)) == x.size                      # distinct values, gaps of 2^-8
+    y = on.maxpool(x, 3, 3, 2, 1, "f32")
+    g = _rand(y.shape, 72)
+    gx = on.maxpool_bwd(x, g, 3, 3, 2, 1, "f32")
+    assert abs(gx.sum() - g.astype(np.float64).sum()) < 1e-9
+    h = 2.0 ** -12                                           # far below the smallest gap (2^-8)
+    rng = np.random.default_rng(7)
+    for _ in range(20):
+        idx = tuple(int(rng.integers(0, s)) for s in x.shape)
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        fd = (np.sum(on.maxpool(xp, 3, 3, 2, 1, "f32").astype(np.float64) * g)
+              - np.sum(on.maxpool(xm, 3, 3, 2, 1, "f32").astype(np.float64) * g)) / (2 * h)
+        assert abs(fd - gx[idx]) <= 1e-6 * max(1.0, abs(fd))
+    # ties: a constant image; window (p,q) scans rows r then columns s, padding skipped, so its
+    # first maximum is its top-left valid pixel
+    xc = np.ones((1, 4, 4, 1), np.float32)
+    gc = np.arange(1, 5, dtype=np.float32).reshape(1, 2, 2, 1)
+    gxc = on.maxpool_bwd(xc, gc, 3, 3, 2, 1, "f32")[0, :, :, 0]
+    want = np.zeros((4, 4))
+    want[0, 0], want[0, 1], want[1, 0], want[1, 1] = 1, 2, 3, 4   # windows start at (-1,-1),(-1,1),(1,-1),(1,1)
+    assert np.array_equal(gxc, want)
+
+
+def test_avgpool_and_softmax_backward():
+    g = _rand((3, 1, 1, 5), 81)
+    gx = on.avgpool_bwd(g, 4, 6, "f32")
+    assert gx.shape == (3, 4, 6, 5)
+    np.testing.assert_allclose(gx[1, 2, 3, :], g[1, 0, 0, :].astype(np.float64) / 24.0, rtol=1e-15)
+    # cross-entropy: finite differences of the pinned forward formula, rows sum to zero
+    N, C = 4, 7
+    z = _rand((N, C), 82, 2.0)
+    labels = synth.make_labels(83, N, C)
+    gz = on.softmax_ce_bwd(z, labels, "f32")
+    np.testing.assert_allclose(gz.sum(axis=1), 0.0, atol=1e-15)
+
+    def loss64(zz):
+        zz = zz.astype(np.float64)
+        mx = zz.max(axis=1)
+        return float(np.mean(mx + np.log(np.exp(zz - mx[:, None]).sum(axis=1)) - zz[np.arange(N), labels]))
+    assert abs(loss64(z) - float(on.softmax_ce(z, labels, "f32")[0])) < 1e-6   # the same function as the forward
+    h = 2.0 ** -10
+    for i in range(N):
+        for k in (0, 3, int(labels[i])):
+            zp, zm = z.copy(), z.copy()
+            zp[i, k] += h
+            zm[i, k] -= h
+            fd = (loss64(zp) - loss64(zm)) / (2 * h)
+            assert abs(fd - gz[i, k]) <= 1e-6
+    # uniform logits: (1/C - onehot) / N
+    gu = on.softmax_ce_bwd(np.zeros((2, 4), np.float32), np.array([1, 3]), "f32")
+    assert np.allclose(gu[0], np.array([0.25, -0.75, 0.25, 0.25]) / 2)
+
+
+def test_classifier_backward_is_three_matrix_products():
+    N, Cin, Cout = 5, 8, 6
+    x = _rand((N, 1, 1, Cin), 91)
+    w = _rand((Cout, 1, 1, Cin), 92)
+    g = _rand((N, 1, 1, Cout), 93)
+    gx, gw, gb = on.fc_bwd(x, w, g, "f32")
+    G, X, Wm = (a.astype(np.float64) for a in (g.reshape(N, Cout), x.reshape(N, Cin), w.reshape(Cout, Cin)))
+    np.testing.assert_allclose(gx.reshape(N, Cin), G @ Wm, rtol=1e-13)
+    np.testing.assert_allclose(gw.reshape(Cout, Cin), G.T @ X, rtol=1e-13)
+    np.testing.assert_allclose(gb, G.sum(axis=0), rtol=1e-13)
