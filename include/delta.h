@@ -216,14 +216,18 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  *     gpre = gy * [y > 0]  (gy itself without ReLU)      - also dL/dres
  *     gx   = conv^T(gpre * scale, w) (+ gx_add)           - dL/dx
  *     gw[k,r,s,c] = scale_k * sum_m gpre[m,k] * x[m+(r,s),c]   - dL/dw, fp32
- * Supported: DELTA_OP_CONV with stride 1 and 2*pad == R-1 == S-1; gx for bf16 and fp32, gw for bf16
- * with R in {1,3} and channel counts that are multiples of 64.  Anything else: DELTA_ERR_INVALID. */
+ * Supported: DELTA_OP_CONV with 2*pad == R-1 == S-1; gx for bf16 and fp32, gw for bf16 with R in
+ * {1,3} and channel counts that are multiples of 64.  A layer with stride > 1 (no residual allowed)
+ * gets gpre at the INPUT's resolution: gpre[n, stride*p, stride*q, :] = gy[n,p,q,:] * [y > 0], zero
+ * elsewhere, so that both gradients are stride-1 operations on it (stride^2 times the arithmetic).
+ * Anything else: DELTA_ERR_INVALID. */
 typedef struct delta_bwd_desc {
     delta_layer_desc fwd;      /* the forward layer; fwd.x must be resident when gw is asked for,
                                   fwd.y when fwd.relu != 0; fwd.res only says whether a residual exists */
     uint32_t gy;               /* tensor id of dL/dy, resident, bytes of y */
-    uint32_t gpre;             /* tensor id that receives gpre (bytes of y; allocated if not resident).
-                                  Must equal gy when fwd.relu == 0 (nothing is written then) */
+    uint32_t gpre;             /* tensor id that receives gpre: N*H*W*Cout elements (the bytes of y when
+                                  stride == 1); allocated if not resident.  Must equal gy when
+                                  fwd.relu == 0 and stride == 1 (nothing is written then) */
     uint32_t gx;               /* tensor id that receives dL/dx (bytes of x), or DELTA_NO_TENSOR */
     uint32_t gx_add;           /* resident tensor (bytes of x) added to dL/dx before it is stored: the
                                   contribution of another consumer of x; or DELTA_NO_TENSOR */

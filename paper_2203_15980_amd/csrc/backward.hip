@@ -68,6 +68,47 @@ __global__ __launch_bounds__(256) void relu_mask_kernel(const u32x4 *__restrict_
     }
 }
 
+// Strided layers: the masked gradient is written at the input's resolution, out[n, s p, s q, :] =
+// gy[n, p, q, :] * [y > 0] and zero everywhere else.  With that tensor the data gradient is again a
+// stride-1 convolution and the weight gradient the stride-1 reduction (the zeros contribute
+// nothing), at the price of stride^2 times the arithmetic.  One 16-byte piece per thread.
+template <bool BF16>
+__global__ __launch_bounds__(256) void relu_mask_dilate_kernel(const u32x4 *__restrict__ y, const u32x4 *__restrict__ gy,
+                                                               u32x4 *__restrict__ out, int H, int W, int P, int Q,
+                                                               int vec_per_pixel, int stride, size_t n16) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const size_t pix = i / vec_per_pixel;
+        const int v = (int)(i - pix * vec_per_pixel);
+        const int w = (int)(pix % W);
+        const size_t rest = pix / W;
+        const int h = (int)(rest % H);
+        const size_t n = rest / H;
+        u32x4 o = {0u, 0u, 0u, 0u};
+        const int p = h / stride, q = w / stride;
+        if (p * stride == h && q * stride == w && p < P && q < Q) {
+            const size_t src = ((n * P + p) * Q + q) * vec_per_pixel + v;
+            const u32x4 g = gy[src];
+            if (y) {
+                const u32x4 a = y[src];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (BF16) {
+                        const uint32_t lo = a[e] & 0xFFFFu, hi = a[e] >> 16;
+                        const bool plo = lo != 0 && lo < 0x7F81u, phi = hi != 0 && hi < 0x7F81u;
+                        o[e] = (plo ? (g[e] & 0xFFFFu) : 0u) | (phi ? (g[e] & 0xFFFF0000u) : 0u);
+                    } else {
+                        o[e] = __uint_as_float(a[e]) > 0.f ? g[e] : 0u;
+                    }
+                }
+            } else {
+                o = g;
+            }
+        }
+        out[i] = o;
+    }
+}
+
 // ---------------------------------------------------------------- weights for the data gradient
 // wt[c][R-1-r][S-1-s][k] = round(w[k][r][s][c] * scale_k): the data gradient is then the forward
 // convolution of gpre with wt (stride 1, padding R-1-pad).  One thread per element of wt.
@@ -305,6 +346,26 @@ hipError_t launch_relu_mask(const void *y, const void *gy, void *out, size_t byt
     else
         bwd::relu_mask_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
             static_cast<const bwd::u32x4 *>(y), static_cast<const bwd::u32x4 *>(gy), static_cast<bwd::u32x4 *>(out), n16);
+    return hipGetLastError();
+}
+
+// y may be null (no ReLU).  out: [N,H,W,K]; gy, y: [N,P,Q,K].
+hipError_t launch_relu_mask_dilate(const void *y, const void *gy, void *out, int N, int H, int W, int P, int Q, int K,
+                                   int stride, int bf16, hipStream_t stream) {
+    const size_t row_bytes = (size_t)K * (bf16 ? 2 : 4);
+    if (row_bytes % 16 || stride < 1) return hipErrorInvalidValue;
+    const size_t n16 = (size_t)N * H * W * (row_bytes / 16);
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (bf16)
+        bwd::relu_mask_dilate_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+            static_cast<const bwd::u32x4 *>(y), static_cast<const bwd::u32x4 *>(gy), static_cast<bwd::u32x4 *>(out), H, W,
+            P, Q, (int)(row_bytes / 16), stride, n16);
+    else
+        bwd::relu_mask_dilate_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+            static_cast<const bwd::u32x4 *>(y), static_cast<const bwd::u32x4 *>(gy), static_cast<bwd::u32x4 *>(out), H, W,
+            P, Q, (int)(row_bytes / 16), stride, n16);
     return hipGetLastError();
 }
 

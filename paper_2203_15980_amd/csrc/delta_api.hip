@@ -792,15 +792,20 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     if (r != DELTA_OK) return r;
     if (L.op != DELTA_OP_CONV || delta::stem_applies(fa))
         return fail(c, DELTA_ERR_INVALID, "backward %u: only the tiled convolution layers have a backward", i);
-    if (L.stride != 1 || 2 * L.pad != L.R - 1 || 2 * L.pad != L.S - 1)
-        return fail(c, DELTA_ERR_INVALID, "backward %u: needs stride 1 and 2*pad == R-1 == S-1", i);
+    if (2 * L.pad != L.R - 1 || 2 * L.pad != L.S - 1)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: needs 2*pad == R-1 == S-1", i);
+    if (L.stride > 1 && L.res != DELTA_NO_TENSOR)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: a strided layer with a residual has no backward here", i);
     const size_t nt = c->tensors.size();
     const uint64_t ybytes = c->tensors[L.y].bytes, xbytes = c->tensors[L.x].bytes;
-    if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != ybytes)
-        return fail(c, DELTA_ERR_INVALID, "backward %u: gy/gpre must be tensors with the bytes of y", i);
-    if (!L.relu && D.gpre != D.gy)
-        return fail(c, DELTA_ERR_INVALID, "backward %u: without ReLU gpre must be gy itself", i);
-    if (L.relu && (D.gpre == D.gy || D.gpre == L.y || D.gpre == L.x))
+    // gpre lives at the input's resolution (for stride 1 that is y's)
+    const uint64_t gpbytes = (uint64_t)L.N * L.H * L.W * L.Cout * (fa.bf16 ? 2 : 4);
+    if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != gpbytes)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gy must have the bytes of y, gpre N*H*W*Cout elements", i);
+    const bool writes_gpre = L.relu || L.stride > 1;
+    if (!writes_gpre && D.gpre != D.gy)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: without ReLU and stride gpre must be gy itself", i);
+    if (writes_gpre && (D.gpre == D.gy || D.gpre == L.y || D.gpre == L.x))
         return fail(c, DELTA_ERR_INVALID, "backward %u: gpre aliases another operand", i);
     if (D.gx != DELTA_NO_TENSOR) {
         if (D.gx >= nt || c->tensors[D.gx].bytes != xbytes)
@@ -812,7 +817,7 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
         if (!D.wt || ((uintptr_t)D.wt & 15)) return fail(c, DELTA_ERR_INVALID, "backward %u: wt missing or misaligned", i);
         if ((uint32_t)L.Cin > kMaxChannels) return fail(c, DELTA_ERR_INVALID, "backward %u: too many channels", i);
         memset(&da, 0, sizeof da);
-        da.N = L.N; da.H = fa.P; da.W = fa.Q; da.Cin = L.Cout; da.Cout = L.Cin; da.R = L.R; da.S = L.S;
+        da.N = L.N; da.H = L.H; da.W = L.W; da.Cin = L.Cout; da.Cout = L.Cin; da.R = L.R; da.S = L.S;
         da.stride = 1; da.pad = L.R - 1 - L.pad; da.P = L.H; da.Q = L.W; da.M = L.N * L.H * L.W;
         da.relu = 0; da.bf16 = fa.bf16;
         da.x = da.y = c->arena; da.w = D.wt; da.scale = da.shift = reinterpret_cast<const float *>(c->arena);
@@ -821,6 +826,8 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     } else if (D.gx_add != DELTA_NO_TENSOR) {
         return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add without gx", i);
     }
+    // the weight gradient sees the layer at stride 1 (gpre is at the input's resolution)
+    fa.stride = 1; fa.P = L.H; fa.Q = L.W; fa.M = L.N * L.H * L.W;
     if (D.gw) {
         const char *why = delta::wgrad_check(fa);
         if (why) return fail(c, DELTA_ERR_INVALID, "backward %u: %s", i, why);
@@ -869,6 +876,7 @@ delta_status delta_backward_workspace(delta_ctx *c, const delta_layer_desc *laye
     delta::PoolArgs pa;
     uint64_t flops = 0;
     if ((r = prepare_layer(c, *layer, 0, a, pa, flops)) != DELTA_OK) return r;
+    a.stride = 1; a.P = layer->H; a.Q = layer->W; a.M = layer->N * layer->H * layer->W;   // as the weight gradient sees it
     *out_bytes = layer->op == DELTA_OP_CONV ? delta::wgrad_workspace_bytes(a) : 0;
     return DELTA_OK;
 }
@@ -900,12 +908,23 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
         Tensor &tgy = c->tensors[D.gy];
         if ((r = compute_uses(c, tgy)) != DELTA_OK) return r;
-        if (L.relu) {
-            Tensor &ty = c->tensors[L.y], &tgp = c->tensors[D.gpre];
-            if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+        if (L.relu || L.stride > 1) {
+            Tensor &tgp = c->tensors[D.gpre];
+            const unsigned char *yp = nullptr;
+            if (L.relu) {
+                Tensor &ty = c->tensors[L.y];
+                if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+                yp = c->arena + ty.offset;
+            }
             if ((r = compute_writes(c, tgp)) != DELTA_OK) return r;
-            HIP_TRY(c, delta::launch_relu_mask(c->arena + ty.offset, c->arena + tgy.offset, c->arena + tgp.offset,
-                                               tgp.bytes, fa.bf16, s));
+            if (L.stride == 1)
+                HIP_TRY(c, delta::launch_relu_mask(yp, c->arena + tgy.offset, c->arena + tgp.offset, tgp.bytes,
+                                                   fa.bf16, s));
+            else
+                HIP_TRY(c, delta::launch_relu_mask_dilate(yp, c->arena + tgy.offset, c->arena + tgp.offset, L.N, L.H,
+                                                          L.W, (L.H + 2 * L.pad - L.R) / L.stride + 1,
+                                                          (L.W + 2 * L.pad - L.S) / L.stride + 1, L.Cout, L.stride,
+                                                          fa.bf16, s));
         }
         const unsigned char *gp = c->arena + c->tensors[D.gpre].offset;
         if (D.gx != DELTA_NO_TENSOR) {

@@ -26,14 +26,17 @@ def _dev(torch, a):
 
 
 CASES = [
-    # name        N   H   W  Cin Cout R relu res  add
-    ("1x1_64_256", 2, 12, 12,  64, 256, 1, True, True, False),
-    ("1x1_256_64", 3,  9, 11, 256,  64, 1, True, False, True),
-    ("1x1_norelu", 2,  7,  7,  64,  64, 1, False, False, False),
-    ("3x3_64",     2, 14, 14,  64,  64, 3, True, False, False),
-    ("3x3_128",    1,  9, 11, 128, 128, 3, True, False, True),     # non-square, accumulate into gx
-    ("3x3_wide",   1,  3, 56,  64,  64, 3, True, False, False),    # config 2's row length
-    ("1x1_128_128", 2, 10, 10, 128, 128, 1, True, False, False),
+    # name        N   H   W  Cin Cout R relu res  add  stride
+    ("1x1_64_256", 2, 12, 12,  64, 256, 1, True, True, False, 1),
+    ("1x1_256_64", 3,  9, 11, 256,  64, 1, True, False, True, 1),
+    ("1x1_norelu", 2,  7,  7,  64,  64, 1, False, False, False, 1),
+    ("3x3_64",     2, 14, 14,  64,  64, 3, True, False, False, 1),
+    ("3x3_128",    1,  9, 11, 128, 128, 3, True, False, True, 1),     # non-square, accumulate into gx
+    ("3x3_wide",   1,  3, 56,  64,  64, 3, True, False, False, 1),    # config 2's row length
+    ("1x1_128_128", 2, 10, 10, 128, 128, 1, True, False, False, 1),
+    ("3x3_s2",     2, 14, 14,  64, 128, 3, True, False, False, 2),    # strided: gpre at the input's resolution
+    ("3x3_s2_odd", 1,  9, 13, 128,  64, 3, True, False, True, 2),     # odd image sizes
+    ("1x1_s2",     2, 12, 12, 128, 256, 1, False, False, False, 2),   # the projection shortcut
 ]
 
 
@@ -41,15 +44,17 @@ CASES = [
 def test_layer_backward_matches_oracle(torch_mod, case):
     torch = torch_mod
     import paper_2203_15980_amd as dl
-    name, N, H, W, Cin, Cout, R, relu, has_res, has_add = case
+    name, N, H, W, Cin, Cout, R, relu, has_res, has_add, stride = case
     print("case", name, flush=True)
     pad = (R - 1) // 2
-    l = synth.LayerSpec(name, "conv", "x0", "r0" if has_res else None, name, N, H, W, Cin, Cout, R, R, 1, pad, relu)
+    l = synth.LayerSpec(name, "conv", "x0", "r0" if has_res else None, name, N, H, W, Cin, Cout, R, R, stride, pad, relu)
+    P, Q = l.P, l.Q
     l.index = 1
     master = 91
     x = synth.make_input(master, (N, H, W, Cin), "bf16")
     p = synth.make_params(master, l, "bf16")
-    yshape = (N, H, W, Cout)
+    yshape = (N, P, Q, Cout)
+    gpshape = (N, H, W, Cout)
     bits = lambda aid, shape: synth.f32_to_bf16_bits(
         synth.normal(master, aid, int(np.prod(shape))).astype(np.float32)).reshape(shape)
     res = bits(901, yshape) if has_res else None
@@ -58,9 +63,9 @@ def test_layer_backward_matches_oracle(torch_mod, case):
 
     arena = torch.empty(96 << 20, dtype=torch.uint8, device="cuda:0")
     d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
-    ysz, xsz = int(np.prod(yshape)) * 2, x.nbytes
+    ysz, xsz, gpsz = int(np.prod(yshape)) * 2, x.nbytes, int(np.prod(gpshape)) * 2
     # tensors: 0 x, 1 res, 2 y, 3 gy, 4 gpre, 5 gx, 6 gx_add
-    d.bind([xsz, ysz, ysz, ysz, ysz, xsz, xsz])
+    d.bind([xsz, ysz, ysz, ysz, gpsz, xsz, xsz])
     base = d.arena.data_ptr()
 
     def put(tid, a):
@@ -86,7 +91,7 @@ def test_layer_backward_matches_oracle(torch_mod, case):
               Cout, scale.data_ptr(), shift.data_ptr())
     fwd = dl.LayerDesc(x=0, res=1 if has_res else dl.NO_TENSOR, y=2, dtype=dl.DTYPE_BF16, w=w.data_ptr(),
                        scale=scale.data_ptr(), shift=shift.data_ptr(), N=N, H=H, W=W, Cin=Cin, Cout=Cout,
-                       R=R, S=R, stride=1, pad=pad, relu=1 if relu else 0)
+                       R=R, S=R, stride=stride, pad=pad, relu=1 if relu else 0)
     d.recompute_segment([fwd])                           # the forward, so that y is the GPU's own
     wt = torch.empty(Cout * R * R * Cin, dtype=torch.uint16, device="cuda:0")
     d.bwd_weights(fwd, wt.data_ptr())
@@ -94,18 +99,22 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     assert ws_bytes > 0
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
-    desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if relu else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
+    own_gpre = relu or stride > 1
+    desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if own_gpre else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
                       wt=wt.data_ptr(), gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
     d.backward_segment([desc])
     d.sync()
 
     y_gpu = get(2, yshape)
-    ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(x, p["w"], p, y_gpu, gy, stride=1, pad=pad, relu=relu, dtype="bf16")
+    ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(x, p["w"], p, y_gpu, gy, stride=stride, pad=pad, relu=relu,
+                                                  dtype="bf16")
     if has_add:
         ref_gx = ref_gx + on.to_f64(add, "bf16")
     # gpre: pure masking, bit for bit
-    gpre_gpu = get(4 if relu else 3, yshape)
-    assert np.array_equal(on.to_f64(gpre_gpu, "bf16"), ref_gpre)
+    gpre_gpu = on.to_f64(get(4 if own_gpre else 3, gpshape), "bf16")
+    want_gpre = np.zeros(gpshape)
+    want_gpre[:, 0:stride * P:stride, 0:stride * Q:stride, :] = ref_gpre     # at the input's resolution
+    assert np.array_equal(gpre_gpu, want_gpre)
     if relu:
         assert (ref_gpre == 0).any() and (ref_gpre != 0).any()
     # the transformed weights: w[k][r][s][c] * scale[k], flipped and transposed, one bf16 rounding
@@ -138,8 +147,20 @@ def test_backward_rejects_what_it_does_not_support(torch_mod):
     f32 = torch.zeros(C, dtype=torch.float32, device="cuda:0")
     s2 = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=dummy.data_ptr(), scale=f32.data_ptr(),
                       shift=f32.data_ptr(), N=N, H=H, W=W, Cin=C, Cout=C, R=3, S=3, stride=2, pad=1, relu=0)
-    with pytest.raises(dl.DeltaError) as e:              # stride 2 has no backward yet
+    with pytest.raises(dl.DeltaError) as e:              # a strided layer needs its own gpre tensor
         d.backward_segment([dl.BwdDesc(fwd=s2, gy=2, gpre=2, gx=4, gx_add=dl.NO_TENSOR, wt=dummy.data_ptr(),
+                                       gw=None, workspace=None, workspace_bytes=0)])
+    assert e.value.status == dl.ERR_INVALID
+    d.close()
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    ys = N * 6 * 6 * C * 2
+    d.bind([xs, ys, ys, ys, xs])
+    for t in (0, 2):
+        d.alloc(t)
+    p0 = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=dummy.data_ptr(), scale=f32.data_ptr(),
+                      shift=f32.data_ptr(), N=N, H=H, W=W, Cin=C, Cout=C, R=3, S=3, stride=1, pad=0, relu=0)
+    with pytest.raises(dl.DeltaError) as e:              # 3x3 without padding: 2*pad != R-1
+        d.backward_segment([dl.BwdDesc(fwd=p0, gy=2, gpre=2, gx=4, gx_add=dl.NO_TENSOR, wt=dummy.data_ptr(),
                                        gw=None, workspace=None, workspace_bytes=0)])
     assert e.value.status == dl.ERR_INVALID
     d.close()
