@@ -220,7 +220,16 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  * {1,3} and channel counts that are multiples of 64.  A layer with stride > 1 (no residual allowed)
  * gets gpre at the INPUT's resolution: gpre[n, stride*p, stride*q, :] = gy[n,p,q,:] * [y > 0], zero
  * elsewhere, so that both gradients are stride-1 operations on it (stride^2 times the arithmetic).
- * Anything else: DELTA_ERR_INVALID. */
+ * Other operators (bf16 only; gpre must be gy, gx_add unused):
+ *   DELTA_OP_MAXPOOL   gx receives gy routed to the first maximal element of each window (scan order
+ *                      r, then s); needs fwd.x resident.
+ *   DELTA_OP_AVGPOOL   gx = gy / (H W) at every pixel.
+ *   the classifier     (DELTA_OP_CONV with H = W = R = S = 1 and Cout not a multiple of 64):
+ *                      gx = gy . (scale * w); gw (optional, fp32) receives Cout*Cin weight gradients
+ *                      followed by Cout bias gradients (sum of gy over the images).
+ *   DELTA_OP_SOFTMAX_CE  gx (bytes of the logits) = (softmax(z) - onehot(label)) / N; gy and gpre
+ *                      must be DELTA_NO_TENSOR; needs fwd.x (logits) and fwd.res (labels) resident.
+ * Anything else (the 7x7 stem among it): DELTA_ERR_INVALID. */
 typedef struct delta_bwd_desc {
     delta_layer_desc fwd;      /* the forward layer; fwd.x must be resident when gw is asked for,
                                   fwd.y when fwd.relu != 0; fwd.res only says whether a residual exists */

@@ -781,6 +781,49 @@ delta_status need_identity_factors(delta_ctx *c) {
     return DELTA_OK;
 }
 
+enum BwdKind { BK_CONV, BK_DENSE, BK_MAXPOOL, BK_AVGPOOL, BK_LOSS };
+
+// The classifier (one pixel per image, a channel count the matrix-core kernels do not take) has its
+// own small kernels; every other convolution goes through the convolution backward.
+BwdKind bwd_kind(const delta_layer_desc &L) {
+    if (L.op == DELTA_OP_MAXPOOL) return BK_MAXPOOL;
+    if (L.op == DELTA_OP_AVGPOOL) return BK_AVGPOOL;
+    if (L.op == DELTA_OP_SOFTMAX_CE) return BK_LOSS;
+    if (L.H == 1 && L.W == 1 && L.R == 1 && L.S == 1 && L.stride == 1 && L.pad == 0 && L.Cout % 64 != 0) return BK_DENSE;
+    return BK_CONV;
+}
+
+// Pooling, classifier and loss: validation only (bf16).  gx is required; gpre must be gy; no gx_add.
+delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, BwdKind kind,
+                                    delta::ConvArgs &fa, delta::PoolArgs &pa) {
+    uint64_t flops = 0;
+    const delta_layer_desc &L = D.fwd;
+    delta_status r = prepare_layer(c, L, i, fa, pa, flops);
+    if (r != DELTA_OK) return r;
+    if (L.dtype != DELTA_DTYPE_BF16) return fail(c, DELTA_ERR_INVALID, "backward %u: this operator's backward is bf16 only", i);
+    const size_t nt = c->tensors.size();
+    if (D.gx == DELTA_NO_TENSOR && !(kind == BK_DENSE && D.gw))
+        return fail(c, DELTA_ERR_INVALID, "backward %u: nothing to compute", i);
+    if (D.gx != DELTA_NO_TENSOR &&
+        (D.gx >= nt || c->tensors[D.gx].bytes != c->tensors[L.x].bytes || D.gx == L.x || D.gx == L.y || D.gx == D.gy))
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gx must be another tensor with the bytes of x", i);
+    if (D.gx_add != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add is for convolutions only", i);
+    if (kind == BK_LOSS) {
+        if (D.gy != DELTA_NO_TENSOR || D.gpre != DELTA_NO_TENSOR || D.gw)
+            return fail(c, DELTA_ERR_INVALID, "backward %u: the loss takes no incoming gradient and has no weights", i);
+        return DELTA_OK;
+    }
+    if (D.gy >= nt || c->tensors[D.gy].bytes != c->tensors[L.y].bytes || D.gpre != D.gy)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gy must have the bytes of y and gpre must be gy", i);
+    if (kind == BK_DENSE) {
+        if (L.relu || L.res != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "backward %u: classifier with ReLU or residual", i);
+        if (D.gw && ((uintptr_t)D.gw & 15)) return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned", i);
+    } else if (D.gw) {
+        return fail(c, DELTA_ERR_INVALID, "backward %u: pooling has no weights", i);
+    }
+    return DELTA_OK;
+}
+
 // Validates one backward descriptor; fills the forward geometry (fa) and, if gx is asked for, the
 // convolution that computes the data gradient (da).  Pointers in fa/da are placeholders.
 delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, delta::ConvArgs &fa,
@@ -791,7 +834,7 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     delta_status r = prepare_layer(c, L, i, fa, pa, flops);
     if (r != DELTA_OK) return r;
     if (L.op != DELTA_OP_CONV || delta::stem_applies(fa))
-        return fail(c, DELTA_ERR_INVALID, "backward %u: only the tiled convolution layers have a backward", i);
+        return fail(c, DELTA_ERR_INVALID, "backward %u: the stem convolution has no backward here", i);
     if (2 * L.pad != L.R - 1 || 2 * L.pad != L.S - 1)
         return fail(c, DELTA_ERR_INVALID, "backward %u: needs 2*pad == R-1 == S-1", i);
     if (L.stride > 1 && L.res != DELTA_NO_TENSOR)
@@ -891,6 +934,17 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
     auto there = [&](uint32_t t) { return c->tensors[t].resident || will_exist[t]; };
     for (uint32_t i = 0; i < n; ++i) {
         const delta_bwd_desc &D = descs[i];
+        const BwdKind kind = bwd_kind(D.fwd);
+        if (kind != BK_CONV) {
+            delta::PoolArgs pa;
+            if ((r = prepare_backward_other(c, D, i, kind, fa, pa)) != DELTA_OK) return r;
+            if (kind != BK_LOSS && !there(D.gy)) return fail(c, DELTA_ERR_STATE, "backward %u: gy tensor %u is not resident", i, D.gy);
+            const bool needs_x = kind == BK_MAXPOOL || kind == BK_LOSS || (kind == BK_DENSE && D.gw);
+            if (needs_x && !there(D.fwd.x)) return fail(c, DELTA_ERR_STATE, "backward %u: x tensor %u is not resident", i, D.fwd.x);
+            if (kind == BK_LOSS && !there(D.fwd.res)) return fail(c, DELTA_ERR_STATE, "backward %u: labels are not resident", i);
+            if (D.gx != DELTA_NO_TENSOR) will_exist[D.gx] = 1;
+            continue;
+        }
         if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
         if (!there(D.gy)) return fail(c, DELTA_ERR_STATE, "backward %u: gy tensor %u is not resident", i, D.gy);
         if (D.fwd.relu && !there(D.fwd.y)) return fail(c, DELTA_ERR_STATE, "backward %u: y tensor %u is not resident", i, D.fwd.y);
@@ -905,6 +959,46 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
     for (uint32_t i = 0; i < n; ++i) {
         const delta_bwd_desc &D = descs[i];
         const delta_layer_desc &L = D.fwd;
+        const BwdKind kind = bwd_kind(L);
+        if (kind != BK_CONV) {
+            delta::PoolArgs pa;
+            if ((r = prepare_backward_other(c, D, i, kind, fa, pa)) != DELTA_OK) return r;
+            const unsigned char *gyp = nullptr, *xp = nullptr;
+            if (kind != BK_LOSS) {
+                if ((r = compute_uses(c, c->tensors[D.gy])) != DELTA_OK) return r;
+                gyp = c->arena + c->tensors[D.gy].offset;
+            }
+            if (c->tensors[L.x].resident) {
+                if ((r = compute_uses(c, c->tensors[L.x])) != DELTA_OK) return r;
+                xp = c->arena + c->tensors[L.x].offset;
+            }
+            unsigned char *gxp = nullptr;
+            if (D.gx != DELTA_NO_TENSOR) {
+                if ((r = compute_writes(c, c->tensors[D.gx])) != DELTA_OK) return r;
+                gxp = c->arena + c->tensors[D.gx].offset;
+            }
+            switch (kind) {
+            case BK_MAXPOOL:
+                pa.x = xp;
+                HIP_TRY(c, delta::launch_maxpool_bwd(pa, gyp, gxp, s));
+                break;
+            case BK_AVGPOOL:
+                HIP_TRY(c, delta::launch_avgpool_bwd(pa, gyp, gxp, s));
+                break;
+            case BK_LOSS: {
+                Tensor &tl = c->tensors[L.res];
+                if ((r = compute_uses(c, tl)) != DELTA_OK) return r;
+                HIP_TRY(c, delta::launch_softmax_ce_bwd(xp, c->arena + tl.offset, L.N, L.Cin, gxp, s));
+                break;
+            }
+            default:
+                HIP_TRY(c, delta::launch_dense_bwd(xp, L.w, L.scale, gyp, gxp, static_cast<float *>(D.gw), L.N, L.Cin,
+                                                   L.Cout, s));
+                break;
+            }
+            c->st.recompute_launches += 1;
+            continue;
+        }
         if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
         Tensor &tgy = c->tensors[D.gy];
         if ((r = compute_uses(c, tgy)) != DELTA_OK) return r;

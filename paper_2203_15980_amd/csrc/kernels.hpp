@@ -56,6 +56,13 @@ size_t wgrad_workspace_bytes(const ConvArgs &a);
 hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
                         hipStream_t stream);
 
+// backward_ops.hip: backward of pooling, the classifier and the loss (bf16)
+hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipStream_t stream);
+hipError_t launch_avgpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipStream_t stream);
+hipError_t launch_softmax_ce_bwd(const void *logits, const void *labels, int N, int classes, void *gz, hipStream_t stream);
+hipError_t launch_dense_bwd(const void *x, const void *w, const float *scale, const void *gy, void *gx, float *gw,
+                            int N, int Cin, int Cout, hipStream_t stream);
+
 hipError_t launch_bn_fold(const float *gamma, const float *beta, const float *mean, const float *var,
                           float eps, unsigned C, float *scale, float *shift, hipStream_t stream);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);

@@ -222,3 +222,104 @@ def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod):
     print("  end to end dL/dx0 err %.2e" % err, flush=True)
     assert err <= 5e-2, err
     d.close()
+
+
+def _small_ctx(torch, sizes, mb=32):
+    import paper_2203_15980_amd as dl
+    arena = torch.empty(mb << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind(sizes)
+    base = d.arena.data_ptr()
+
+    def put(tid, a):
+        ptr = d.alloc(tid)
+        d.arena[ptr - base:ptr - base + a.nbytes].copy_(_dev(torch, np.ascontiguousarray(a).view(np.uint8).reshape(-1)))
+
+    def get(tid, shape, dtype=np.uint16):
+        ptr = d.tensor_ptr(tid)
+        n = int(np.prod(shape)) * np.dtype(dtype).itemsize
+        return d.arena[ptr - base:ptr - base + n].cpu().numpy().view(dtype).reshape(shape)
+    return d, put, get
+
+
+def _bits(master, aid, shape, scale=1.0):
+    return synth.f32_to_bf16_bits((synth.normal(master, aid, int(np.prod(shape))) * scale).astype(np.float32)).reshape(shape)
+
+
+def test_pooling_backward_matches_oracle(torch_mod):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    # max pooling 3x3 / 2 / 1 on a ReLU-like input (many exact ties at 0): the routing must be the
+    # oracle's (same zero pattern), the sums agree to bf16 rounding
+    N, H, W, C = 2, 12, 10, 64
+    x = _bits(5, 1, (N, H, W, C))
+    x = np.where(on.to_f64(x, "bf16") > 0, x, 0).astype(np.uint16)           # zeros tie
+    P, Q = (H + 2 - 3) // 2 + 1, (W + 2 - 3) // 2 + 1
+    gy = _bits(5, 2, (N, P, Q, C))
+    xs, ys = x.nbytes, gy.nbytes
+    d, put, get = _small_ctx(torch, [xs, ys, ys, xs])
+    put(0, x)
+    put(2, gy)
+    fwd = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=None, scale=None, shift=None, N=N, H=H, W=W,
+                       Cin=C, Cout=C, R=3, S=3, stride=2, pad=1, relu=0, op=dl.OP_MAXPOOL)
+    d.backward_segment([dl.BwdDesc(fwd=fwd, gy=2, gpre=2, gx=3, gx_add=dl.NO_TENSOR, wt=None, gw=None,
+                                   workspace=None, workspace_bytes=0)])
+    d.sync()
+    got = on.to_f64(get(3, x.shape), "bf16")
+    ref = on.maxpool_bwd(x, gy, 3, 3, 2, 1, "bf16")
+    assert np.array_equal(got == 0, ref == 0)
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref))
+    d.close()
+    # global average
+    N, H, W, C = 3, 7, 7, 128
+    gy = _bits(6, 1, (N, 1, 1, C))
+    d, put, get = _small_ctx(torch, [N * H * W * C * 2, gy.nbytes, gy.nbytes, N * H * W * C * 2])
+    put(2, gy)
+    fwd = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=None, scale=None, shift=None, N=N, H=H, W=W,
+                       Cin=C, Cout=C, R=H, S=W, stride=1, pad=0, relu=0, op=dl.OP_AVGPOOL)
+    d.backward_segment([dl.BwdDesc(fwd=fwd, gy=2, gpre=2, gx=3, gx_add=dl.NO_TENSOR, wt=None, gw=None,
+                                   workspace=None, workspace_bytes=0)])
+    d.sync()
+    got = on.to_f64(get(3, (N, H, W, C)), "bf16")
+    ref = on.avgpool_bwd(gy, H, W, "bf16")
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref))
+    d.close()
+
+
+def test_classifier_and_loss_backward_match_oracle(torch_mod):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    N, Cin, Cout = 8, 128, 1000
+    x = _bits(7, 1, (N, 1, 1, Cin))
+    w = _bits(7, 2, (Cout, 1, 1, Cin), 0.05)
+    bias = (synth.normal(7, 3, Cout) * 0.1).astype(np.float32)
+    labels = synth.make_labels(7, N, Cout)
+    zs, xs = N * Cout * 2, x.nbytes
+    # tensors: 0 x, 1 logits, 2 labels, 3 loss, 4 glogits, 5 gx
+    d, put, get = _small_ctx(torch, [xs, zs, N * 8, 4, zs, xs])
+    put(0, x)
+    put(2, labels)
+    wd, ones, bd = _dev(torch, w), torch.ones(Cout, dtype=torch.float32, device="cuda:0"), _dev(torch, bias)
+    fc = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=wd.data_ptr(), scale=ones.data_ptr(),
+                      shift=bd.data_ptr(), N=N, H=1, W=1, Cin=Cin, Cout=Cout, R=1, S=1, stride=1, pad=0, relu=0)
+    loss = dl.LayerDesc(x=1, res=2, y=3, dtype=dl.DTYPE_BF16, w=None, scale=None, shift=None, N=N, H=1, W=1,
+                        Cin=Cout, Cout=1, R=1, S=1, stride=1, pad=0, relu=0, op=dl.OP_SOFTMAX_CE)
+    d.recompute_segment([fc, loss])
+    gw = torch.full((Cout * Cin + Cout,), float("nan"), dtype=torch.float32, device="cuda:0")
+    d.backward_segment([
+        dl.BwdDesc(fwd=loss, gy=dl.NO_TENSOR, gpre=dl.NO_TENSOR, gx=4, gx_add=dl.NO_TENSOR, wt=None, gw=None,
+                   workspace=None, workspace_bytes=0),
+        dl.BwdDesc(fwd=fc, gy=4, gpre=4, gx=5, gx_add=dl.NO_TENSOR, wt=None, gw=gw.data_ptr(), workspace=None,
+                   workspace_bytes=0)])
+    d.sync()
+    logits = get(1, (N, Cout))
+    gz_gpu = get(4, (N, Cout))
+    ref_gz = on.softmax_ce_bwd(logits, labels, "bf16")                 # from the GPU's own logits
+    assert np.max(np.abs(on.to_f64(gz_gpu, "bf16") - ref_gz)) <= 2.0 ** -8 * np.max(np.abs(ref_gz)) + 1e-7
+    ref_gx, ref_gw, ref_gb = on.fc_bwd(x, w, gz_gpu.reshape(N, 1, 1, Cout), "bf16")
+    got_gx = on.to_f64(get(5, (N, 1, 1, Cin)), "bf16")
+    assert np.max(np.abs(got_gx - ref_gx)) <= 2e-2 * np.max(np.abs(ref_gx))
+    g = gw.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(g[:Cout * Cin].reshape(ref_gw.shape) - ref_gw)) <= 2e-4 * np.max(np.abs(ref_gw))
+    assert np.max(np.abs(g[Cout * Cin:] - ref_gb)) <= 2e-4 * np.max(np.abs(ref_gb))
+    d.close()
