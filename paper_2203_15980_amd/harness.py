@@ -115,31 +115,45 @@ class Net:
     def recompute(self, name):
         self.delta.recompute_segment(self.desc[name])
 
-    # -- backward pass (convolution layers with stride 1 and "same" padding)
+    # -- backward pass
+    def _is_stem(self, l):
+        return l.kind == "conv" and l.R == 7 and l.Cin == 3
+
+    def _own_gpre(self, l):
+        return l.kind == "conv" and (l.relu or l.stride > 1)
+
     def enable_backward(self, input_gradient=False):
         """Adds the gradient tensors to the tensor table (re-binds: call while nothing is
         resident), prepares the data-gradient weights, the fp32 weight-gradient buffers and the
         shared workspace.  Gradient tensors are transient: allocated when written, released
         after their last use; they are not part of the planned graph.  `input_gradient`: also
-        compute dL/dx0."""
+        compute dL/dx0.  The 7x7 stem has no backward kernel: its step runs `stem_proxy`
+        (its forward kernel twice into a scratch tensor), as the replays did for every layer
+        before the backward kernels existed."""
         d, dev = self.delta, self.device
+        if self.dtype != "bf16" and any(l.kind != "conv" for l in self.layers):
+            raise ValueError("backward of pooling, classifier and loss is bf16 only")
         self.n_graph = len(self.sizes)
-        self.bwd_ids, self.bwd_layers = {}, []
+        self.bwd_ids = {}
         extra = []
+        store = np.float32 if self.dtype == "f32" else np.uint16
 
         def new_tensor(name, nbytes, shape):
             self.bwd_ids[name] = self.n_graph + len(extra)
             extra.append(nbytes)
-            self.shapes[name], self.np_dtype[name] = shape, (np.float32 if self.dtype == "f32" else np.uint16)
+            self.shapes[name], self.np_dtype[name] = shape, store
             return self.bwd_ids[name]
 
         top = self.layers[-1]
+        self.has_loss = "loss" in self.desc
         new_tensor("g:" + top.y, self.sizes[self.ids[top.y]], self.shapes[top.y])
         for l in self.layers:
-            if l.kind != "conv":
-                raise ValueError("backward: layer kind %r has no backward kernel" % l.kind)
-            if l.relu:
-                new_tensor("gp:" + l.name, self.sizes[self.ids[l.y]], self.shapes[l.y])
+            if self._is_stem(l):
+                new_tensor("scratch:" + l.name, self.sizes[self.ids[l.y]], self.shapes[l.y])
+                continue
+            if self._own_gpre(l):
+                shape = (l.N, l.H, l.W, l.Cout)          # at the input's resolution
+                new_tensor("gp:" + l.name, int(np.prod(shape)) * self.es, shape)
             if l.x != "x0" or input_gradient:
                 new_tensor("g:" + l.x + ":" + l.name, self.sizes[self.ids[l.x]], self.shapes[l.x])
         self.all_sizes = self.sizes + extra
@@ -147,66 +161,127 @@ class Net:
             self.ids[name] = tid
         self.sizes = self.all_sizes
         d.bind(self.all_sizes)
-        self.wt, self.gw = {}, {}
+        self.wt, self.gw, self.stem_proxy_desc = {}, {}, {}
         ws_bytes = 16
         for l in self.layers:
             fwd = self.desc[l.y][0]
-            n = l.Cout * l.R * l.S * l.Cin
-            self.wt[l.name] = torch.empty(n * self.es, dtype=torch.uint8, device=dev)
-            d.bwd_weights(fwd, self.wt[l.name].data_ptr())
-            self.gw[l.name] = torch.zeros(n, dtype=torch.float32, device=dev)
-            ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
+            if l.kind == "fc":
+                self.gw[l.name] = torch.zeros(l.Cout * l.Cin + l.Cout, dtype=torch.float32, device=dev)
+            elif l.kind == "conv" and self._is_stem(l):
+                dsc = B.LayerDesc.from_buffer_copy(fwd)
+                dsc.y = self.ids["scratch:" + l.name]
+                self.stem_proxy_desc[l.name] = B.layer_array([dsc])
+            elif l.kind == "conv":
+                n = l.Cout * l.R * l.S * l.Cin
+                self.wt[l.name] = torch.empty(n * self.es, dtype=torch.uint8, device=dev)
+                d.bwd_weights(fwd, self.wt[l.name].data_ptr())
+                self.gw[l.name] = torch.zeros(n, dtype=torch.float32, device=dev)
+                ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
         self.bwd_workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self.input_gradient = input_gradient
-        self.top_gradient_np = synth.f32_to_bf16_bits(
-            synth.normal(self.master, 7001, int(np.prod(self.shapes[top.y]))).astype(np.float32)
-        ).reshape(self.shapes[top.y]) if self.dtype == "bf16" else synth.normal(
-            self.master, 7001, int(np.prod(self.shapes[top.y]))).astype(np.float32).reshape(self.shapes[top.y])
-        self.sources[self.ids["g:" + top.y]] = _dev(self.top_gradient_np.view(np.uint8).reshape(-1), dev)
+        if not self.has_loss:
+            n = int(np.prod(self.shapes[top.y]))
+            g = synth.normal(self.master, 7001, n).astype(np.float32)
+            self.top_gradient_np = (synth.f32_to_bf16_bits(g) if self.dtype == "bf16" else g).reshape(self.shapes[top.y])
+            self.sources[self.ids["g:" + top.y]] = _dev(self.top_gradient_np.view(np.uint8).reshape(-1), dev)
         self.pending = {}
+        self.by_name = {l.name: l for l in self.layers}
         torch.cuda.synchronize()
 
-    def backward_begin(self):
-        """Loads the gradient of the last layer's output (seeded, synthetic: it stands in for the
-        loss's gradient)."""
+    def rebind(self, delta):
+        """Moves the net to another context (same tensor table); nothing may be resident."""
+        self.delta = delta
+        delta.bind(self.sizes)
+
+    def _bwd_plan(self, l, pending):
+        """What the backward of layer `l` reads, writes and frees, given the partial gradients
+        `pending` (tensor name -> gradient tensor name).  Pure bookkeeping (no GPU call):
+        returns (gy, gpre, gx, add, dead, new_pending_entries)."""
+        gy = pending[l.y]
+        if self._is_stem(l):
+            return gy, None, None, None, [gy], {}
+        gpre = "gp:" + l.name if self._own_gpre(l) else gy
+        want_gx = l.x != "x0" or self.input_gradient
+        gx = "g:" + l.x + ":" + l.name if want_gx else None
+        add = pending.get(l.x) if want_gx else None
+        if add is not None and l.kind != "conv":
+            raise ValueError("gradient accumulation at the input of a %s layer needs an add kernel" % l.kind)
+        dead, new = [], {}
+        if gx:
+            new[l.x] = gx
+            if add:
+                dead.append(add)
+        if l.res:
+            if l.res in pending:
+                raise ValueError("residual gradient would need an add kernel")
+            new[l.res] = gpre                     # the shortcut receives gpre; first contribution
+        elif gpre != gy:
+            dead.append(gpre)
+        if gpre != gy or not l.res:
+            dead.append(gy)
+        return gy, gpre, gx, add, list(dict.fromkeys(dead)), new
+
+    def backward_peak_bytes(self):
+        """Largest sum of gradient-tensor bytes alive at once during `backward` (a dry run of the
+        bookkeeping): what the arena must hold beyond the activations."""
         top = self.layers[-1]
-        self.load_source(self.ids["g:" + top.y])
-        self.pending = {top.y: "g:" + top.y}
+        first = "g:" + top.y
+        live = {first: self.sizes[self.ids[first]]}
+        pending = {top.y: first}
+        peak = sum(live.values())
+        for l in reversed(self.layers):
+            gy, gpre, gx, add, dead, new = self._bwd_plan(l, pending)
+            for nm in (gpre, gx):
+                if nm and nm not in live:
+                    live[nm] = self.sizes[self.ids[nm]]
+            if self._is_stem(l):
+                live["scratch:" + l.name] = self.sizes[self.ids["scratch:" + l.name]]
+            peak = max(peak, sum(live.values()))
+            pending.pop(l.y)
+            pending.update(new)
+            for nm in dead:
+                live.pop(nm, None)
+            live.pop("scratch:" + l.name, None)
+        return peak
+
+    def backward_begin(self):
+        """The gradient of the last layer's output: from the loss's backward when the net has a
+        loss (logits and labels must be resident), else a seeded synthetic tensor."""
+        top = self.layers[-1]
+        first = "g:" + top.y
+        if self.has_loss:
+            desc = B.BwdDesc(fwd=self.desc["loss"][0], gy=B.NO_TENSOR, gpre=B.NO_TENSOR, gx=self.ids[first],
+                             gx_add=B.NO_TENSOR, wt=None, gw=None, workspace=None, workspace_bytes=0)
+            self.delta.backward_segment([desc])
+        else:
+            self.load_source(self.ids[first])
+        self.pending = {top.y: first}
         self.bwd_trace = []
 
     def backward_layer(self, l, keep=False):
         """Backward of layer `l`; every consumer of l.y must have run its backward already.
         Frees gradient tensors after their last use unless `keep` (tests read them back)."""
         d = self.delta
-        fwd = self.desc[l.y][0]
-        gy_name = self.pending.pop(l.y)
-        gpre_name = "gp:" + l.name if l.relu else gy_name
-        want_gx = l.x != "x0" or self.input_gradient
-        gx_name = "g:" + l.x + ":" + l.name if want_gx else None
-        add_name = self.pending.get(l.x) if want_gx else None
-        desc = B.BwdDesc(fwd=fwd, gy=self.ids[gy_name], gpre=self.ids[gpre_name],
-                         gx=self.ids[gx_name] if gx_name else B.NO_TENSOR,
-                         gx_add=self.ids[add_name] if add_name else B.NO_TENSOR,
-                         wt=self.wt[l.name].data_ptr(),
-                         gw=self.gw[l.name].data_ptr() if self.dtype == "bf16" else None,   # weight gradient: bf16 only
-                         workspace=self.bwd_workspace.data_ptr(), workspace_bytes=self.bwd_workspace.numel())
-        d.backward_segment([desc])
-        self.bwd_trace.append((l.name, gy_name, gpre_name, gx_name, add_name))
-        dead = []
-        if gx_name:
-            self.pending[l.x] = gx_name
-            if add_name:
-                dead.append(add_name)
-        if l.res:
-            # the residual branch receives gpre; in a ResNet this is its first contribution
-            assert l.res not in self.pending, "residual gradient would need an add kernel"
-            self.pending[l.res] = gpre_name
-        elif gpre_name != gy_name:
-            dead.append(gpre_name)
-        if gpre_name != gy_name or not l.res:
-            dead.append(gy_name)
+        gy, gpre, gx, add, dead, new = self._bwd_plan(l, self.pending)
+        self.pending.pop(l.y)
+        if self._is_stem(l):
+            arr = self.stem_proxy_desc[l.name]
+            d.recompute_segment(arr)
+            d.recompute_segment(arr)
+            d.release(self.ids["scratch:" + l.name], B.EV_FREE)
+        else:
+            conv = l.kind == "conv"
+            desc = B.BwdDesc(fwd=self.desc[l.y][0], gy=self.ids[gy], gpre=self.ids[gpre],
+                             gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
+                             wt=self.wt[l.name].data_ptr() if conv else None,
+                             gw=self.gw[l.name].data_ptr() if (l.name in self.gw and self.dtype == "bf16") else None,
+                             workspace=self.bwd_workspace.data_ptr() if conv else None,
+                             workspace_bytes=self.bwd_workspace.numel() if conv else 0)
+            d.backward_segment([desc])
+        self.bwd_trace.append((l.name, gy, gpre, gx, add))
+        self.pending.update(new)
         if not keep:
-            for name in dict.fromkeys(dead):
+            for name in dead:
                 d.release(self.ids[name], B.EV_FREE)
 
     def backward(self, keep=False):
@@ -214,6 +289,19 @@ class Net:
         self.backward_begin()
         for l in reversed(self.layers):
             self.backward_layer(l, keep=keep)
+
+    def backward_step(self, graph, k):
+        """Backward step `k` of synth.fused_graph's step list: the loss first (when present),
+        then the layers in reverse order.  For use as run_plan's `backward` callback."""
+        j = k - graph.n_fwd
+        if self.has_loss:
+            if j == 0:
+                self.backward_begin()
+                return
+            j -= 1
+        elif j == 0:
+            self.backward_begin()
+        self.backward_layer(self.layers[len(self.layers) - 1 - j])
 
 
 def run_plan(net, graph, events, backward_proxy=None):

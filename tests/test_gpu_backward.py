@@ -323,3 +323,67 @@ def test_classifier_and_loss_backward_match_oracle(torch_mod):
     assert np.max(np.abs(g[:Cout * Cin].reshape(ref_gw.shape) - ref_gw)) <= 2e-4 * np.max(np.abs(ref_gw))
     assert np.max(np.abs(g[Cout * Cin:] - ref_gb)) <= 2e-4 * np.max(np.abs(ref_gb))
     d.close()
+
+
+def test_small_resnet_whole_backward_layer_by_layer(torch_mod):
+    """ResNet with one bottleneck per stage on 2 x 64 x 64 x 3 with the loss: the whole backward
+    pass through the harness (loss, classifier, average pool, strided and projection blocks,
+    max-pool; the stem has no backward kernel and runs its proxy).  Every layer is checked against
+    the oracle on exactly the tensors the GPU's layer was given."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    layers = synth.resnet_layers(2, (1, 1, 1, 1), image=64, classes=40)
+    g = synth.fused_graph(layers, "bf16", with_loss=True)
+    arena = torch.empty(96 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", 41, with_loss=True)
+    net.enable_backward()
+    assert net.backward_peak_bytes() > 0
+    net.forward()
+    net.backward(keep=True)
+    d.sync()
+    acts = {"x0": net.x0_np}
+    for l in layers:
+        acts[l.y] = net.read(l.y)
+    # the loss's gradient from the GPU's own logits
+    top = layers[-1]
+    gz = on.to_f64(net.read("g:" + top.y), "bf16").reshape(top.N, top.Cout)
+    ref_gz = on.softmax_ce_bwd(acts[top.y], net.labels_np, "bf16")
+    assert np.max(np.abs(gz - ref_gz)) <= 2.0 ** -8 * np.max(np.abs(ref_gz)) + 1e-7
+    by_name = {l.name: l for l in layers}
+    checked = set()
+    for (lname, gy_name, gpre_name, gx_name, add_name) in net.bwd_trace:
+        l = by_name[lname]
+        if gx_name is None:
+            continue                                        # the stem
+        gy = net.read(gy_name)
+        got = on.to_f64(net.read(gx_name), "bf16")
+        if l.kind == "conv":
+            p = net.params_np[lname]
+            ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(acts[l.x], p["w"], p, acts[l.y], gy, stride=l.stride,
+                                                          pad=l.pad, relu=l.relu, dtype="bf16")
+            if add_name:
+                ref_gx = ref_gx + on.to_f64(net.read(add_name), "bf16")
+            got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
+            ew = float(np.max(np.abs(got_gw - ref_gw)) / np.max(np.abs(ref_gw)))
+            assert ew <= 2e-4, (lname, ew)
+        elif l.kind == "maxpool":
+            ref_gx = on.maxpool_bwd(acts[l.x], gy, l.R, l.S, l.stride, l.pad, "bf16")
+            assert np.array_equal(got == 0, ref_gx == 0)
+        elif l.kind == "avgpool":
+            ref_gx = on.avgpool_bwd(gy, l.H, l.W, "bf16")
+        else:
+            ref_gx, ref_gw, ref_gb = on.fc_bwd(acts[l.x], net.params_np[lname]["w"], gy, "bf16")
+            gwb = net.gw[lname].cpu().numpy().astype(np.float64)
+            n = l.Cout * l.Cin
+            assert np.max(np.abs(gwb[:n].reshape(ref_gw.shape) - ref_gw)) <= 2e-4 * np.max(np.abs(ref_gw))
+            assert np.max(np.abs(gwb[n:] - ref_gb)) <= 2e-4 * np.max(np.abs(ref_gb))
+        ex = float(np.max(np.abs(got - ref_gx)) / np.max(np.abs(ref_gx)))
+        print("  %-10s %-8s gx %.2e" % (lname, l.kind, ex), flush=True)
+        assert ex <= 2e-2, (lname, ex)
+        checked.add(l.kind)
+    assert checked == {"conv", "maxpool", "avgpool", "fc"}
+    assert any(by_name[t[0]].stride == 2 for t in net.bwd_trace)
+    d.close()
