@@ -15,6 +15,7 @@ namespace delta {
 namespace bops {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -35,63 +36,132 @@ __device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
 }
 
 // ---------------------------------------------------------------- max pooling
-// One thread: 8 channels of one INPUT pixel.  For every window that contains the pixel, the
-// window is scanned in the forward's order (r, then s, padding skipped); the pixel receives the
-// window's gradient where it is the first maximal element.  Sums in window order (p, then q), fp32.
-__global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void *gy, void *gx, long long total) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int chunks = a.C / 8;
-    const int ck = (int)(idx % chunks);
-    long long pix = idx / chunks;
-    const int w = (int)(pix % a.W);
-    pix /= a.W;
-    const int h = (int)(pix % a.H);
-    const int n = (int)(pix / a.H);
+// A workgroup owns an 8 x 8 tile of INPUT pixels and 64 channels (8 chunks of 8), in three steps:
+//  1. copy every pixel that a window touching the tile can reach (the tile plus R-1 / S-1 pixels
+//     on each side) into LDS;
+//  2. one thread per (window, chunk): scan the window in the forward's order (r, then s, padding
+//     skipped) and record, per channel, the position r*S + s of the first maximal element as
+//     one byte (255: none) - each window is scanned once, not once per pixel it covers;
+//  3. one thread per (pixel, chunk): for each of the at most ceil(R/stride) x ceil(S/stride)
+//     windows containing the pixel, add the window's gradient where the recorded position is
+//     the pixel's.  Sums in window order (p, then q), fp32.
+// Every loop has a uniform trip count and selects instead of branches: a per-element `if`
+// compiled to a branch per element and ran ten times slower.
+static constexpr int kPoolTile = 8, kPoolChunks = 8;
+
+__host__ __device__ inline int pool_windows_max(int R, int stride) { return (kPoolTile + R - 2) / stride + 2; }
+
+// FIXED: the ResNet pool (3 x 3, stride 2, padding 1) with every loop unrolled.
+template <bool FIXED>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void *gy, void *gx, int tiles_w, int tiles_h) {
+    if constexpr (FIXED) { a.R = 3; a.S = 3; a.stride = 2; a.pad = 1; }
+    extern __shared__ __align__(16) unsigned char plds[];
+    const int chunks = a.C / 8, cgroups = (chunks + kPoolChunks - 1) / kPoolChunks;
+    int blk = blockIdx.x;
+    const int cg = blk % cgroups; blk /= cgroups;
+    const int tw = blk % tiles_w; blk /= tiles_w;
+    const int th = blk % tiles_h;
+    const int n = blk / tiles_h;
+    const int h0 = th * kPoolTile, w0 = tw * kPoolTile;
+    const int LH = kPoolTile + 2 * (a.R - 1), LW = kPoolTile + 2 * (a.S - 1);
+    const int NWH = pool_windows_max(a.R, a.stride), NWW = pool_windows_max(a.S, a.stride);
+    unsigned char *arg = plds + (size_t)LH * LW * kPoolChunks * 16;      // [NWH][NWW][chunk] x 8 bytes
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const unsigned char *gg = static_cast<const unsigned char *>(gy);
-    float mine[8], acc[8];
-    unpack8(*reinterpret_cast<const u32x4 *>(xg + (size_t)idx * 16), mine);
+    // step 1: LDS pixel (lh, lw) = image pixel (h0 - (R-1) + lh, w0 - (S-1) + lw); outside the image: zeros, unused
+    for (int i = threadIdx.x; i < LH * LW * kPoolChunks; i += 256) {
+        const int c = i % kPoolChunks, pix = i / kPoolChunks;
+        const int lh = pix / LW, lw = pix - lh * LW;
+        const int hh = h0 - (a.R - 1) + lh, ww = w0 - (a.S - 1) + lw, ck = cg * kPoolChunks + c;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if ((unsigned)hh < (unsigned)a.H && (unsigned)ww < (unsigned)a.W && ck < chunks)
+            v = *reinterpret_cast<const u32x4 *>(xg + ((((size_t)n * a.H + hh) * a.W + ww) * chunks + ck) * 16);
+        *reinterpret_cast<u32x4 *>(plds + (size_t)i * 16) = v;
+    }
+    __syncthreads();
+    // windows that contain a pixel of the tile: p in [pw0, pw0 + NWH) clipped to the image (likewise q)
+    int pw0 = h0 + a.pad - a.R + 1;
+    pw0 = pw0 <= 0 ? 0 : (pw0 + a.stride - 1) / a.stride;
+    int qw0 = w0 + a.pad - a.S + 1;
+    qw0 = qw0 <= 0 ? 0 : (qw0 + a.stride - 1) / a.stride;
+    // step 2
+    for (int i = threadIdx.x; i < NWH * NWW * kPoolChunks; i += 256) {
+        const int c = i % kPoolChunks, win = i / kPoolChunks;
+        const int wp = win / NWW, wq = win - wp * NWW;
+        const int hb = (pw0 + wp) * a.stride - a.pad, wb = (qw0 + wq) * a.stride - a.pad;
+        float m[8];
+        uint32_t idx[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    // windows (p, q) with p*stride - pad <= h <= p*stride - pad + R - 1
-    int p_lo = h + a.pad - a.R + 1;
-    p_lo = p_lo <= 0 ? 0 : (p_lo + a.stride - 1) / a.stride;
-    int p_hi = (h + a.pad) / a.stride;
-    if (p_hi > a.P - 1) p_hi = a.P - 1;
-    int q_lo = w + a.pad - a.S + 1;
-    q_lo = q_lo <= 0 ? 0 : (q_lo + a.stride - 1) / a.stride;
-    int q_hi = (w + a.pad) / a.stride;
-    if (q_hi > a.Q - 1) q_hi = a.Q - 1;
-    for (int p = p_lo; p <= p_hi; ++p)
-        for (int q = q_lo; q <= q_hi; ++q) {
-            // is (h, w) the first maximum of window (p, q)?  An element before it in scan order
-            // beats it when it is >=, one after it only when it is >.
-            bool first[8];
+        for (int e = 0; e < 8; ++e) { m[e] = -INFINITY; idx[e] = 255u; }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) first[e] = true;
-            for (int r = 0; r < a.R; ++r) {
-                const int hh = p * a.stride + r - a.pad;
-                if ((unsigned)hh >= (unsigned)a.H) continue;
-                for (int s = 0; s < a.S; ++s) {
-                    const int ww = q * a.stride + s - a.pad;
-                    if ((unsigned)ww >= (unsigned)a.W || (hh == h && ww == w)) continue;
-                    float v[8];
-                    unpack8(*reinterpret_cast<const u32x4 *>(
-                                xg + ((((size_t)n * a.H + hh) * a.W + ww) * chunks + ck) * 16), v);
-                    const bool before = hh < h || (hh == h && ww < w);
+        for (int r = 0; r < a.R; ++r)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (before ? v[e] >= mine[e] : v[e] > mine[e]) first[e] = false;
+            for (int s = 0; s < a.S; ++s) {
+                const int hh = hb + r, ww = wb + s;
+                const bool inside = (unsigned)hh < (unsigned)a.H && (unsigned)ww < (unsigned)a.W;
+                // windows beyond the tile's reach (or the image) are never consulted: clamp their reads
+                int lh = hh - h0 + a.R - 1, lw = ww - w0 + a.S - 1;
+                lh = lh < 0 ? 0 : (lh > LH - 1 ? LH - 1 : lh);
+                lw = lw < 0 ? 0 : (lw > LW - 1 ? LW - 1 : lw);
+                float v[8];
+                unpack8(*reinterpret_cast<const u32x4 *>(plds + ((size_t)(lh * LW + lw) * kPoolChunks + c) * 16), v);
+                const uint32_t pos = (uint32_t)(r * a.S + s);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool take = inside && v[e] > m[e];
+                    m[e] = take ? v[e] : m[e];
+                    idx[e] = take ? pos : idx[e];
                 }
             }
-            float g[8];
-            unpack8(*reinterpret_cast<const u32x4 *>(gg + ((((size_t)n * a.P + p) * a.Q + q) * chunks + ck) * 16), g);
+        u32x2 o;
+        o.x = idx[0] | (idx[1] << 8) | (idx[2] << 16) | (idx[3] << 24);
+        o.y = idx[4] | (idx[5] << 8) | (idx[6] << 16) | (idx[7] << 24);
+        *reinterpret_cast<u32x2 *>(arg + (size_t)i * 8) = o;
+    }
+    __syncthreads();
+    // step 3
+    const int np = (a.R + a.stride - 1) / a.stride, nq = (a.S + a.stride - 1) / a.stride;
+    for (int i = threadIdx.x; i < kPoolTile * kPoolTile * kPoolChunks; i += 256) {
+        const int c = i % kPoolChunks, pix = i / kPoolChunks;
+        const int h = h0 + pix / kPoolTile, w = w0 + pix % kPoolTile, ck = cg * kPoolChunks + c;
+        const bool owned = h < a.H && w < a.W && ck < chunks;
+        int p_lo = h + a.pad - a.R + 1;
+        p_lo = p_lo <= 0 ? 0 : (p_lo + a.stride - 1) / a.stride;
+        int p_hi = (h + a.pad) / a.stride;
+        if (p_hi > a.P - 1) p_hi = a.P - 1;
+        int q_lo = w + a.pad - a.S + 1;
+        q_lo = q_lo <= 0 ? 0 : (q_lo + a.stride - 1) / a.stride;
+        int q_hi = (w + a.pad) / a.stride;
+        if (q_hi > a.Q - 1) q_hi = a.Q - 1;
+        float acc[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (first[e]) acc[e] += g[e];
-        }
-    *reinterpret_cast<u32x4 *>(static_cast<unsigned char *>(gx) + (size_t)idx * 16) = pack8(acc);
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int dp = np - 1; dp >= 0; --dp)                       // ascending p, then q: the order of the sums
+#pragma unroll
+            for (int dq = nq - 1; dq >= 0; --dq) {
+                const int p = p_hi - dp, q = q_hi - dq;
+                const bool live = owned && p >= p_lo && q >= q_lo;  // this pixel lies in window (p, q)
+                // clamped to the windows step 2 covered and to the image: the loads stay in bounds
+                const int pc = p < pw0 ? pw0 : (p > pw0 + NWH - 1 ? pw0 + NWH - 1 : p);
+                const int qc = q < qw0 ? qw0 : (q > qw0 + NWW - 1 ? qw0 + NWW - 1 : q);
+                const int pg = pc > a.P - 1 ? a.P - 1 : pc, qg = qc > a.Q - 1 ? a.Q - 1 : qc;
+                const int ckc = ck < chunks ? ck : chunks - 1;
+                const u32x2 am = *reinterpret_cast<const u32x2 *>(
+                    arg + ((size_t)((pc - pw0) * NWW + (qc - qw0)) * kPoolChunks + c) * 8);
+                float g[8];
+                unpack8(*reinterpret_cast<const u32x4 *>(gg + ((((size_t)n * a.P + pg) * a.Q + qg) * chunks + ckc) * 16), g);
+                const uint32_t my = (uint32_t)((h - (p * a.stride - a.pad)) * a.S + (w - (q * a.stride - a.pad)));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t pos = ((e < 4 ? am.x : am.y) >> (8 * (e & 3))) & 0xFFu;
+                    acc[e] += (live && pos == my) ? g[e] : 0.f;
+                }
+            }
+        if (owned)
+            *reinterpret_cast<u32x4 *>(static_cast<unsigned char *>(gx) +
+                                       ((((size_t)n * a.H + h) * a.W + w) * chunks + ck) * 16) = pack8(acc);
+    }
 }
 
 // ---------------------------------------------------------------- global average pooling
@@ -137,25 +207,39 @@ __global__ __launch_bounds__(256) void softmax_ce_bwd_kernel(const uint16_t *log
 }
 
 // ---------------------------------------------------------------- classifier z = x w^T + bias
-// gx[n][c] = sum_k gy[n][k] * scale_k * w[k][c]: one thread per (image, 8 input channels); k ascending.
+// gx[n][c] = sum_k gy[n][k] * scale_k * w[k][c].  A workgroup: one image, 32 x 8 input channels; its
+// 8 wavefront-halves split the classes (group g takes k = g, g + 8, ...), then the 8 partial sums
+// are added in group order.
 __global__ __launch_bounds__(256) void dense_bwd_data_kernel(const uint16_t *gy, const void *w, const float *scale,
                                                              void *gx, int N, int Cin, int Cout) {
-    const int chunks = Cin / 8;
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)N * chunks) return;
-    const int ck = (int)(idx % chunks), n = (int)(idx / chunks);
+    __shared__ float part[8][32][8];
+    const int chunks = Cin / 8, cblocks = (chunks + 31) / 32;
+    const int n = blockIdx.x / cblocks, cb = blockIdx.x % cblocks;
+    const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const int ck = cb * 32 + lane;
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     const unsigned char *wg = static_cast<const unsigned char *>(w);
-    for (int k = 0; k < Cout; ++k) {
-        const float g = __uint_as_float((uint32_t)gy[(size_t)n * Cout + k] << 16) * scale[k];
-        float v[8];
-        unpack8(*reinterpret_cast<const u32x4 *>(wg + ((size_t)k * chunks + ck) * 16), v);
+    if (ck < chunks) {
+#pragma unroll 4
+        for (int k = grp; k < Cout; k += 8) {
+            const float g = __uint_as_float((uint32_t)gy[(size_t)n * Cout + k] << 16) * scale[k];
+            float v[8];
+            unpack8(*reinterpret_cast<const u32x4 *>(wg + ((size_t)k * chunks + ck) * 16), v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += g * v[e];
+            for (int e = 0; e < 8; ++e) acc[e] += g * v[e];
+        }
     }
-    *reinterpret_cast<u32x4 *>(static_cast<unsigned char *>(gx) + (size_t)idx * 16) = pack8(acc);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[grp][lane][e] = acc[e];
+    __syncthreads();
+    if (grp != 0 || ck >= chunks) return;
+#pragma unroll
+    for (int g = 1; g < 8; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += part[g][lane][e];
+    *reinterpret_cast<u32x4 *>(static_cast<unsigned char *>(gx) + ((size_t)n * chunks + ck) * 16) = pack8(acc);
 }
 
 // gw[k][c] = scale_k * sum_n gy[n][k] * x[n][c] (fp32): one thread per (k, 8 input channels); n ascending.
@@ -188,10 +272,17 @@ __global__ __launch_bounds__(256) void dense_bwd_weight_kernel(const uint16_t *g
 
 hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipStream_t stream) {
     if (pool_check(a, false) || !a.bf16 || !gy || !gx) return hipErrorInvalidValue;
-    const long long total = (long long)a.N * a.H * a.W * (a.C / 8);
-    const long long blocks = (total + 255) / 256;
-    if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    bops::maxpool_bwd_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(a, gy, gx, total);
+    const int tiles_h = (a.H + bops::kPoolTile - 1) / bops::kPoolTile, tiles_w = (a.W + bops::kPoolTile - 1) / bops::kPoolTile;
+    const int cgroups = (a.C / 8 + bops::kPoolChunks - 1) / bops::kPoolChunks;
+    const long long blocks = (long long)a.N * tiles_h * tiles_w * cgroups;
+    if (a.R * a.S > 255) return hipErrorInvalidValue;                   // window positions are recorded as bytes
+    const size_t lds = (size_t)(bops::kPoolTile + 2 * (a.R - 1)) * (bops::kPoolTile + 2 * (a.S - 1)) * bops::kPoolChunks * 16 +
+                       (size_t)bops::pool_windows_max(a.R, a.stride) * bops::pool_windows_max(a.S, a.stride) * bops::kPoolChunks * 8;
+    if (blocks <= 0 || blocks > 0x7FFFFFFFLL || lds > 64 * 1024) return hipErrorInvalidValue;
+    if (a.R == 3 && a.S == 3 && a.stride == 2 && a.pad == 1)
+        bops::maxpool_bwd_kernel<true><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h);
+    else
+        bops::maxpool_bwd_kernel<false><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h);
     return hipGetLastError();
 }
 
@@ -218,8 +309,8 @@ hipError_t launch_dense_bwd(const void *x, const void *w, const float *scale, co
                             int N, int Cin, int Cout, hipStream_t stream) {
     if (!w || !scale || !gy || N <= 0 || Cin <= 0 || Cout <= 0 || Cin % 8) return hipErrorInvalidValue;
     if (gx) {
-        const long long t = (long long)N * (Cin / 8);
-        bops::dense_bwd_data_kernel<<<dim3((unsigned)((t + 255) / 256)), dim3(256), 0, stream>>>(
+        const long long t = (long long)N * ((Cin / 8 + 31) / 32);
+        bops::dense_bwd_data_kernel<<<dim3((unsigned)t), dim3(256), 0, stream>>>(
             static_cast<const uint16_t *>(gy), w, scale, gx, N, Cin, Cout);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
