@@ -240,6 +240,13 @@ typedef struct delta_bwd_desc {
     uint32_t gx;               /* tensor id that receives dL/dx (bytes of x), or DELTA_NO_TENSOR */
     uint32_t gx_add;           /* resident tensor (bytes of x) added to dL/dx before it is stored: the
                                   contribution of another consumer of x; or DELTA_NO_TENSOR */
+    uint32_t mask_gx;          /* convolutions only.  Non-zero: gx is stored as (dL/dx + gx_add) * [x > 0],
+                                  i.e. this layer also applies the ReLU mask of the layer that produced x
+                                  (x is that layer's y), in the epilogue of the data-gradient kernel;
+                                  the caller sets it on the LAST consumer of x to run.  Needs fwd.x resident */
+    uint32_t gy_masked;        /* convolutions only.  Non-zero: gy already carries this layer's ReLU mask
+                                  (a consumer ran with mask_gx): fwd.y is not read; with stride 1 gpre must
+                                  be gy, with stride > 1 gpre receives gy spread to the input's resolution */
     const void *wt;            /* device: weights prepared by delta_bwd_weights (needed when gx is set) */
     void *gw;                  /* device, fp32 [Cout][R][S][Cin]: receives dL/dw (overwritten), or NULL */
     void *workspace;           /* device scratch for the weight gradient's partial sums, 16-byte aligned */

@@ -55,7 +55,7 @@ class LayerDesc(C.Structure):
 
 class BwdDesc(C.Structure):
     _fields_ = [("fwd", LayerDesc), ("gy", C.c_uint32), ("gpre", C.c_uint32), ("gx", C.c_uint32),
-                ("gx_add", C.c_uint32), ("wt", C.c_void_p), ("gw", C.c_void_p), ("workspace", C.c_void_p),
+                ("gx_add", C.c_uint32), ("mask_gx", C.c_uint32), ("gy_masked", C.c_uint32), ("wt", C.c_void_p), ("gw", C.c_void_p), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_uint64)]
 
 

@@ -55,14 +55,8 @@ __global__ __launch_bounds__(256) void relu_mask_kernel(const u32x4 *__restrict_
         u32x4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if constexpr (BF16) {
-                const uint32_t lo = a[e] & 0xFFFFu, hi = a[e] >> 16;
-                const bool plo = lo != 0 && lo < 0x7F81u;      // positive, finite or +inf
-                const bool phi = hi != 0 && hi < 0x7F81u;
-                o[e] = (plo ? (g[e] & 0xFFFFu) : 0u) | (phi ? (g[e] & 0xFFFF0000u) : 0u);
-            } else {
-                o[e] = __uint_as_float(a[e]) > 0.f ? g[e] : 0u;
-            }
+            if constexpr (BF16) o[e] = keep_where_positive_bf16(g[e], a[e]);
+            else o[e] = keep_where_positive_f32(g[e], a[e]);
         }
         out[i] = o;
     }

@@ -63,7 +63,7 @@ static constexpr int kTPitch = 144;
 // NS = Cin / 64 (128-byte slices of the reduction axis), NG = channels of one slice / 64.
 // Dynamic LDS: weights [NG*64][Cin*2 + 16 bytes], scale, shift (fp32) of the slice, then one
 // transposition tile per wavefront.  Grid: 8 * ceil(pixel groups / 8) * slices workgroups.
-template <int NS, int NG, int WAVES, bool HAS_RES, bool SLICED>
+template <int NS, int NG, int WAVES, bool HAS_RES, bool SLICED, bool HAS_MASK = false>
 __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) {
     constexpr int THREADS = WAVES * 64;
     constexpr int Cout = NG * 64;               // channels of this workgroup's slice
@@ -126,6 +126,7 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
     // the slice offset is folded into the (uniform) base pointers
     unsigned char *yg = static_cast<unsigned char *>(a.y) + (size_t)n0 * 2;
     const unsigned char *rg = static_cast<const unsigned char *>(a.res) + (size_t)n0 * 2;
+    const unsigned char *mg = static_cast<const unsigned char *>(a.mask) + (size_t)n0 * 2;   // HAS_MASK only
     // residual in the post-swap layout, straight into registers: piece (u, i2) of group g
     // covers channels g*64 + u*32 + 16*i2 + 8*half .. +8 of this lane's pixel (32-byte runs per
     // pixel; routing the reads through the LDS tile as well measured slower).  Two groups are
@@ -229,9 +230,16 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int pr = trow + 8 * t;
-            const u32x4_t o4 = *reinterpret_cast<const u32x4_t *>(ttile + pr * kTPitch + tseg * 16);
-            if (mbase + pr < a.M)
-                *reinterpret_cast<u32x4_t *>(yg + ((size_t)(mbase + pr) * Ctot + g * 64) * 2 + tseg * 16) = o4;
+            u32x4_t o4 = *reinterpret_cast<const u32x4_t *>(ttile + pr * kTPitch + tseg * 16);
+            if (mbase + pr < a.M) {
+                const size_t off = ((size_t)(mbase + pr) * Ctot + g * 64) * 2 + tseg * 16;
+                if constexpr (HAS_MASK) {
+                    const u32x4_t mv = *reinterpret_cast<const u32x4_t *>(mg + off);
+                    o4.x = keep_where_positive_bf16(o4.x, mv.x); o4.y = keep_where_positive_bf16(o4.y, mv.y);
+                    o4.z = keep_where_positive_bf16(o4.z, mv.z); o4.w = keep_where_positive_bf16(o4.w, mv.w);
+                }
+                *reinterpret_cast<u32x4_t *>(yg + off) = o4;
+            }
         }
         wave_fence();
     }
@@ -258,7 +266,7 @@ bool conv1x1_stream_applies(const ConvArgs &a) {
     return slice_groups(a) != 0;
 }
 
-template <int NS, int NG, int WAVES, bool SLICED>
+template <int NS, int NG, int WAVES, bool SLICED, bool HAS_MASK>
 static hipError_t launch_stream_s(const ConvArgs &a, hipStream_t stream) {
     const long long tiles = ((long long)a.M + 31) / 32;
     const long long groups = (tiles + WAVES - 1) / WAVES;
@@ -270,17 +278,17 @@ static hipError_t launch_stream_s(const ConvArgs &a, hipStream_t stream) {
     static bool raised = false;                  // more than the default 64 KB of dynamic LDS
     if (lds > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED>),
+            reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED, HAS_MASK>),
             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(
-                reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED>),
+                reinterpret_cast<const void *>(conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED, HAS_MASK>),
                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED><<<grid, block, lds, stream>>>(a);
-    else conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED><<<grid, block, lds, stream>>>(a);
+    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED, HAS_MASK><<<grid, block, lds, stream>>>(a);
+    else conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED, HAS_MASK><<<grid, block, lds, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -288,12 +296,17 @@ static hipError_t launch_stream_s(const ConvArgs &a, hipStream_t stream) {
 // those run 12 wavefronts (170 registers).
 template <int NS, int NG, int WAVES>
 static hipError_t launch_stream(const ConvArgs &a, hipStream_t stream) {
+    // the variants that also apply a mask (the backward pass's data gradients) always take the
+    // 12-wavefront budget: the 16-wavefront ones have no register to spare
+    constexpr int W12 = WAVES > 12 ? 12 : WAVES;
     if (a.Cout == NG * 64) {
-        constexpr int WV = NS * NG <= 4 ? WAVES : (WAVES > 12 ? 12 : WAVES);
-        return launch_stream_s<NS, NG, WV, false>(a, stream);
+        constexpr int WV = NS * NG <= 4 ? WAVES : W12;
+        if (a.mask) return launch_stream_s<NS, NG, W12, false, true>(a, stream);
+        return launch_stream_s<NS, NG, WV, false, false>(a, stream);
     }
-    constexpr int WV = NS * NG <= 2 ? WAVES : (WAVES > 12 ? 12 : WAVES);
-    return launch_stream_s<NS, NG, WV, true>(a, stream);
+    constexpr int WV = NS * NG <= 2 ? WAVES : W12;
+    if (a.mask) return launch_stream_s<NS, NG, W12, true, true>(a, stream);
+    return launch_stream_s<NS, NG, WV, true, false>(a, stream);
 }
 
 template <int WAVES>

@@ -285,6 +285,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
             o.y = pack_bf16(v[2], v[3]);
             o.z = pack_bf16(v[4], v[5]);
             o.w = pack_bf16(v[6], v[7]);
+            if (a.mask) {
+                const u32x4 mv = *reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(a.mask) + off);
+                o.x = keep_where_positive_bf16(o.x, mv.x); o.y = keep_where_positive_bf16(o.y, mv.y);
+                o.z = keep_where_positive_bf16(o.z, mv.z); o.w = keep_where_positive_bf16(o.w, mv.w);
+            }
             *reinterpret_cast<u32x4 *>(yg + off) = o;
         }
     }

@@ -359,6 +359,16 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
                     o.x = __float_as_uint(v[0]); o.y = __float_as_uint(v[1]);
                     o.z = __float_as_uint(v[2]); o.w = __float_as_uint(v[3]);
                 }
+                if (a.mask) {
+                    const u32x4 mv = *reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(a.mask) + off);
+                    if constexpr (BF16) {
+                        o.x = keep_where_positive_bf16(o.x, mv.x); o.y = keep_where_positive_bf16(o.y, mv.y);
+                        o.z = keep_where_positive_bf16(o.z, mv.z); o.w = keep_where_positive_bf16(o.w, mv.w);
+                    } else {
+                        o.x = keep_where_positive_f32(o.x, mv.x); o.y = keep_where_positive_f32(o.y, mv.y);
+                        o.z = keep_where_positive_f32(o.z, mv.z); o.w = keep_where_positive_f32(o.w, mv.w);
+                    }
+                }
                 *reinterpret_cast<u32x4 *>(yg + off) = o;
             }
         }
@@ -420,7 +430,7 @@ const char *conv_check(const ConvArgs &a) {
         if (images * a.H * a.W * a.Cin * es + 256 > 0x7FFFFFFFLL) return "image too large for 32-bit tile offsets";
     }
     if (!a.x || !a.w || !a.y || !a.scale || !a.shift) return "null pointer";
-    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y | (uintptr_t)a.res | (uintptr_t)a.scale |
+    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y | (uintptr_t)a.res | (uintptr_t)a.mask | (uintptr_t)a.scale |
          (uintptr_t)a.shift) & 15)
         return "pointers must be 16-byte aligned";
     return nullptr;

@@ -807,7 +807,8 @@ delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint3
     if (D.gx != DELTA_NO_TENSOR &&
         (D.gx >= nt || c->tensors[D.gx].bytes != c->tensors[L.x].bytes || D.gx == L.x || D.gx == L.y || D.gx == D.gy))
         return fail(c, DELTA_ERR_INVALID, "backward %u: gx must be another tensor with the bytes of x", i);
-    if (D.gx_add != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add is for convolutions only", i);
+    if (D.gx_add != DELTA_NO_TENSOR || D.mask_gx || D.gy_masked)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add, mask_gx and gy_masked are for convolutions only", i);
     if (kind == BK_LOSS) {
         if (D.gy != DELTA_NO_TENSOR || D.gpre != DELTA_NO_TENSOR || D.gw)
             return fail(c, DELTA_ERR_INVALID, "backward %u: the loss takes no incoming gradient and has no weights", i);
@@ -845,9 +846,11 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     const uint64_t gpbytes = (uint64_t)L.N * L.H * L.W * L.Cout * (fa.bf16 ? 2 : 4);
     if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != gpbytes)
         return fail(c, DELTA_ERR_INVALID, "backward %u: gy must have the bytes of y, gpre N*H*W*Cout elements", i);
-    const bool writes_gpre = L.relu || L.stride > 1;
+    const bool writes_gpre = (L.relu && !D.gy_masked) || L.stride > 1;
     if (!writes_gpre && D.gpre != D.gy)
-        return fail(c, DELTA_ERR_INVALID, "backward %u: without ReLU and stride gpre must be gy itself", i);
+        return fail(c, DELTA_ERR_INVALID, "backward %u: without a ReLU mask to apply and stride gpre must be gy itself", i);
+    if (D.mask_gx && D.gx == DELTA_NO_TENSOR)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: mask_gx without gx", i);
     if (writes_gpre && (D.gpre == D.gy || D.gpre == L.y || D.gpre == L.x))
         return fail(c, DELTA_ERR_INVALID, "backward %u: gpre aliases another operand", i);
     if (D.gx != DELTA_NO_TENSOR) {
@@ -947,8 +950,10 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         }
         if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
         if (!there(D.gy)) return fail(c, DELTA_ERR_STATE, "backward %u: gy tensor %u is not resident", i, D.gy);
-        if (D.fwd.relu && !there(D.fwd.y)) return fail(c, DELTA_ERR_STATE, "backward %u: y tensor %u is not resident", i, D.fwd.y);
-        if (D.gw && !there(D.fwd.x)) return fail(c, DELTA_ERR_STATE, "backward %u: x tensor %u is not resident", i, D.fwd.x);
+        if (D.fwd.relu && !D.gy_masked && !there(D.fwd.y))
+            return fail(c, DELTA_ERR_STATE, "backward %u: y tensor %u is not resident", i, D.fwd.y);
+        if ((D.gw || D.mask_gx) && !there(D.fwd.x))
+            return fail(c, DELTA_ERR_STATE, "backward %u: x tensor %u is not resident", i, D.fwd.x);
         if (D.gx_add != DELTA_NO_TENSOR && !there(D.gx_add))
             return fail(c, DELTA_ERR_STATE, "backward %u: gx_add tensor %u is not resident", i, D.gx_add);
         will_exist[D.gpre] = 1;
@@ -1002,10 +1007,11 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         if ((r = prepare_backward(c, D, i, fa, da)) != DELTA_OK) return r;
         Tensor &tgy = c->tensors[D.gy];
         if ((r = compute_uses(c, tgy)) != DELTA_OK) return r;
-        if (L.relu || L.stride > 1) {
+        const bool own_mask = L.relu && !D.gy_masked;
+        if (own_mask || L.stride > 1) {
             Tensor &tgp = c->tensors[D.gpre];
             const unsigned char *yp = nullptr;
-            if (L.relu) {
+            if (own_mask) {
                 Tensor &ty = c->tensors[L.y];
                 if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
                 yp = c->arena + ty.offset;
@@ -1028,8 +1034,13 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 if ((r = compute_uses(c, c->tensors[D.gx_add])) != DELTA_OK) return r;
                 addp = c->arena + c->tensors[D.gx_add].offset;
             }
+            const unsigned char *maskp = nullptr;
+            if (D.mask_gx) {
+                if ((r = compute_uses(c, c->tensors[L.x])) != DELTA_OK) return r;
+                maskp = c->arena + c->tensors[L.x].offset;
+            }
             if ((r = compute_writes(c, tgx)) != DELTA_OK) return r;
-            da.x = gp; da.w = D.wt; da.res = addp; da.y = c->arena + tgx.offset;
+            da.x = gp; da.w = D.wt; da.res = addp; da.mask = maskp; da.y = c->arena + tgx.offset;
             da.scale = c->ones; da.shift = c->zeros;
             HIP_TRY(c, delta::launch_conv(da, s));
             c->st.recompute_flops += 2ull * (uint64_t)da.M * da.R * da.S * da.Cin * da.Cout;

@@ -9,6 +9,7 @@ struct ConvArgs {
     const void *x;        // [N,H,W,Cin]
     const void *w;        // [Cout,R,S,Cin]
     const void *res;      // [N,P,Q,Cout] or nullptr
+    const void *mask;     // [N,P,Q,Cout] or nullptr: y is stored as 0 where mask is not > 0 (after residual and ReLU)
     void *y;              // [N,P,Q,Cout]
     const float *scale;   // [Cout]
     const float *shift;   // [Cout]
@@ -16,6 +17,19 @@ struct ConvArgs {
     int relu;
     int bf16;             // 1: bf16 storage, fp32 accumulate; 0: fp32
 };
+
+// The test behind every ReLU mask of the backward pass.  bf16: greater than zero <=> sign bit clear,
+// not zero and not NaN.  Returns the bits of `v` (two bf16 values) with the halves cleared whose
+// half of `m` fails it.
+__device__ __forceinline__ uint32_t keep_where_positive_bf16(uint32_t v, uint32_t m) {
+    const uint32_t lo = m & 0xFFFFu, hi = m >> 16;
+    const bool plo = lo != 0 && lo < 0x7F81u;          // positive, finite or +inf
+    const bool phi = hi != 0 && hi < 0x7F81u;
+    return (plo ? (v & 0xFFFFu) : 0u) | (phi ? (v & 0xFFFF0000u) : 0u);
+}
+__device__ __forceinline__ uint32_t keep_where_positive_f32(uint32_t v, uint32_t m) {
+    return __uint_as_float(m) > 0.f ? v : 0u;
+}
 
 // nullptr when the kernel supports the shape, else the reason.
 const char *conv_check(const ConvArgs &a);

@@ -119,21 +119,41 @@ class Net:
     def _is_stem(self, l):
         return l.kind == "conv" and l.R == 7 and l.Cin == 3
 
-    def _own_gpre(self, l):
-        return l.kind == "conv" and (l.relu or l.stride > 1)
+    def _gy_masked(self, l):
+        return bool(l.relu) and l.y in self.masked_by
 
-    def enable_backward(self, input_gradient=False):
+    def _own_gpre(self, l):
+        return l.kind == "conv" and ((l.relu and not self._gy_masked(l)) or l.stride > 1)
+
+    def _plan_mask_fusion(self):
+        """tensor name -> the layer that applies the ReLU mask of the tensor's producer while it
+        writes the tensor's gradient: the consumer whose backward runs last (the first in forward
+        order), if it is a convolution reading the tensor as its input.  Its data gradient
+        already holds every other consumer's contribution (gx_add) at that point."""
+        masked_by = {}
+        for prod in self.layers:
+            if prod.kind != "conv" or not prod.relu or self._is_stem(prod):
+                continue
+            users = [l for l in self.layers if l.x == prod.y or l.res == prod.y]
+            if users and users[0].kind == "conv" and users[0].x == prod.y and not self._is_stem(users[0]):
+                masked_by[prod.y] = users[0].name
+        return masked_by
+
+    def enable_backward(self, input_gradient=False, fuse_masks=True):
         """Adds the gradient tensors to the tensor table (re-binds: call while nothing is
         resident), prepares the data-gradient weights, the fp32 weight-gradient buffers and the
         shared workspace.  Gradient tensors are transient: allocated when written, released
         after their last use; they are not part of the planned graph.  `input_gradient`: also
-        compute dL/dx0.  The 7x7 stem has no backward kernel: its step runs `stem_proxy`
+        compute dL/dx0.  `fuse_masks`: a ReLU layer's mask is applied by the data-gradient
+        kernel of its output's last consumer where that is a convolution (no separate mask
+        kernel, no unmasked gradient tensor).  The 7x7 stem has no backward kernel: its step runs `stem_proxy`
         (its forward kernel twice into a scratch tensor), as the replays did for every layer
         before the backward kernels existed."""
         d, dev = self.delta, self.device
         if self.dtype != "bf16" and any(l.kind != "conv" for l in self.layers):
             raise ValueError("backward of pooling, classifier and loss is bf16 only")
         self.n_graph = len(self.sizes)
+        self.masked_by = self._plan_mask_fusion() if fuse_masks else {}
         self.bwd_ids = {}
         extra = []
         store = np.float32 if self.dtype == "f32" else np.uint16
@@ -271,14 +291,17 @@ class Net:
             d.release(self.ids["scratch:" + l.name], B.EV_FREE)
         else:
             conv = l.kind == "conv"
+            mask_gx = conv and gx is not None and self.masked_by.get(l.x) == l.name
             desc = B.BwdDesc(fwd=self.desc[l.y][0], gy=self.ids[gy], gpre=self.ids[gpre],
                              gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
+                             mask_gx=int(mask_gx), gy_masked=int(conv and self._gy_masked(l)),
                              wt=self.wt[l.name].data_ptr() if conv else None,
                              gw=self.gw[l.name].data_ptr() if (l.name in self.gw and self.dtype == "bf16") else None,
                              workspace=self.bwd_workspace.data_ptr() if conv else None,
                              workspace_bytes=self.bwd_workspace.numel() if conv else 0)
             d.backward_segment([desc])
-        self.bwd_trace.append((l.name, gy, gpre, gx, add))
+        self.bwd_trace.append((l.name, gy, gpre, gx, add, bool(not self._is_stem(l) and l.kind == "conv" and gx is not None
+                                                                and self.masked_by.get(l.x) == l.name)))
         self.pending.update(new)
         if not keep:
             for name in dead:

@@ -37,6 +37,12 @@ CASES = [
     ("3x3_s2",     2, 14, 14,  64, 128, 3, True, False, False, 2),    # strided: gpre at the input's resolution
     ("3x3_s2_odd", 1,  9, 13, 128,  64, 3, True, False, True, 2),     # odd image sizes
     ("1x1_s2",     2, 12, 12, 128, 256, 1, False, False, False, 2),   # the projection shortcut
+    # fused masks ("x": this layer masks gx with [x > 0]; "y": gy arrives already masked)
+    ("1x1_64_256_fx",  2, 12, 12,  64, 256, 1, True, True, False, 1, "x"),    # data gradient: streaming kernel
+    ("1x1_256_64_fxy", 3,  9, 11, 256,  64, 1, True, False, True, 1, "xy"),   # streaming kernel, sliced, with gx_add
+    ("1x1_128_256_fx", 2, 10, 10, 128, 256, 1, True, False, True, 1, "x"),    # tiled kernel
+    ("3x3_64_fxy",     2, 14, 14,  64,  64, 3, True, False, False, 1, "xy"),  # halo kernel
+    ("3x3_s2_fy",      2, 14, 14,  64, 128, 3, True, False, False, 2, "y"),   # strided: masked gy is only spread out
 ]
 
 
@@ -44,7 +50,9 @@ CASES = [
 def test_layer_backward_matches_oracle(torch_mod, case):
     torch = torch_mod
     import paper_2203_15980_amd as dl
-    name, N, H, W, Cin, Cout, R, relu, has_res, has_add, stride = case
+    name, N, H, W, Cin, Cout, R, relu, has_res, has_add, stride = case[:11]
+    fuse = case[11] if len(case) > 11 else ""
+    mask_gx, gy_masked = "x" in fuse, "y" in fuse
     print("case", name, flush=True)
     pad = (R - 1) // 2
     l = synth.LayerSpec(name, "conv", "x0", "r0" if has_res else None, name, N, H, W, Cin, Cout, R, R, stride, pad, relu)
@@ -93,14 +101,20 @@ def test_layer_backward_matches_oracle(torch_mod, case):
                        scale=scale.data_ptr(), shift=shift.data_ptr(), N=N, H=H, W=W, Cin=Cin, Cout=Cout,
                        R=R, S=R, stride=stride, pad=pad, relu=1 if relu else 0)
     d.recompute_segment([fwd])                           # the forward, so that y is the GPU's own
+    if gy_masked:                                        # what a consumer running with mask_gx would have left
+        d.sync()
+        gy = np.where(on.to_f64(get(2, yshape), "bf16") > 0, gy, np.uint16(0)).astype(np.uint16)
+        put_again = d.tensor_ptr(3)
+        d.arena[put_again - base:put_again - base + gy.nbytes].copy_(_dev(torch, gy.view(np.uint8).reshape(-1)))
     wt = torch.empty(Cout * R * R * Cin, dtype=torch.uint16, device="cuda:0")
     d.bwd_weights(fwd, wt.data_ptr())
     ws_bytes = d.backward_workspace(fwd)
     assert ws_bytes > 0
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
-    own_gpre = relu or stride > 1
+    own_gpre = (relu and not gy_masked) or stride > 1
     desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if own_gpre else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
+                      mask_gx=int(mask_gx), gy_masked=int(gy_masked),
                       wt=wt.data_ptr(), gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
     d.backward_segment([desc])
     d.sync()
@@ -110,6 +124,10 @@ def test_layer_backward_matches_oracle(torch_mod, case):
                                                   dtype="bf16")
     if has_add:
         ref_gx = ref_gx + on.to_f64(add, "bf16")
+    if mask_gx:                                          # the producer's ReLU mask: x is its output
+        keep = on.to_f64(x, "bf16") > 0
+        assert keep.any() and not keep.all()
+        ref_gx = np.where(keep, ref_gx, 0.0)
     # gpre: pure masking, bit for bit
     gpre_gpu = on.to_f64(get(4 if own_gpre else 3, gpshape), "bf16")
     want_gpre = np.zeros(gpshape)
@@ -127,6 +145,8 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     gw_gpu = gw.cpu().numpy().astype(np.float64)
     assert np.isfinite(gw_gpu).all()
     err_w = float(np.max(np.abs(gw_gpu - ref_gw)) / np.max(np.abs(ref_gw)))
+    if mask_gx:
+        assert np.array_equal(gx_gpu[~keep], np.zeros(int((~keep).sum())))
     print("  gx err %.2e  gw err %.2e" % (err_x, err_w), flush=True)
     assert err_x <= 2e-2, (name, err_x)
     assert err_w <= 2e-4, (name, err_w)
@@ -166,7 +186,8 @@ def test_backward_rejects_what_it_does_not_support(torch_mod):
     d.close()
 
 
-def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod):
+@pytest.mark.parametrize("fuse", [False, True], ids=["separate_masks", "fused_masks"])
+def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod, fuse):
     """Three bottleneck blocks (config 2's layer shapes at 2 x 16 x 16): the whole backward pass
     through the harness.  Layer by layer, the oracle is given exactly what the GPU's layer was
     given (its stored x, y and incoming gradient) and must reproduce what the layer wrote; end
@@ -180,7 +201,8 @@ def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod):
     d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
     d.bind([t["bytes"] for t in g.tensors])
     net = Net(d, layers, "bf16", synth.master_seed(2))
-    net.enable_backward(input_gradient=True)
+    net.enable_backward(input_gradient=True, fuse_masks=fuse)
+    assert bool(net.masked_by) == fuse
     net.forward()
     net.backward(keep=True)
     d.sync()
@@ -188,15 +210,18 @@ def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod):
     for l in layers:
         acts[l.y] = net.read(l.y)
     by_name = {l.name: l for l in layers}
-    for (lname, gy_name, gpre_name, gx_name, add_name) in net.bwd_trace:
+    for (lname, gy_name, gpre_name, gx_name, add_name, masks_gx) in net.bwd_trace:
         l = by_name[lname]
         p = net.params_np[lname]
         gy = net.read(gy_name)
+        # a gy that arrives masked is unchanged by the oracle's own mask (same y, same test)
         ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(acts[l.x], p["w"], p, acts[l.y], gy, stride=l.stride,
                                                       pad=l.pad, relu=l.relu, dtype="bf16")
         assert np.array_equal(on.to_f64(net.read(gpre_name), "bf16"), ref_gpre), lname
         if add_name:
             ref_gx = ref_gx + on.to_f64(net.read(add_name), "bf16")
+        if masks_gx:
+            ref_gx = np.where(on.to_f64(acts[l.x], "bf16") > 0, ref_gx, 0.0)
         got_gx = on.to_f64(net.read(gx_name), "bf16")
         ex = float(np.max(np.abs(got_gx - ref_gx)) / np.max(np.abs(ref_gx)))
         got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
@@ -216,6 +241,7 @@ def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod):
         if l.res:
             grads[l.res] = grads.get(l.res, 0) + gpre
         grads[l.x] = rnd(grads.get(l.x, 0) + gx)
+    assert any(t[5] for t in net.bwd_trace) == fuse
     last = net.bwd_trace[-1]
     got = on.to_f64(net.read(last[3]), "bf16")
     err = float(np.max(np.abs(got - grads["x0"])) / np.max(np.abs(grads["x0"])))
@@ -325,7 +351,8 @@ def test_classifier_and_loss_backward_match_oracle(torch_mod):
     d.close()
 
 
-def test_small_resnet_whole_backward_layer_by_layer(torch_mod):
+@pytest.mark.parametrize("fuse", [False, True], ids=["separate_masks", "fused_masks"])
+def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
     """ResNet with one bottleneck per stage on 2 x 64 x 64 x 3 with the loss: the whole backward
     pass through the harness (loss, classifier, average pool, strided and projection blocks,
     max-pool; the stem has no backward kernel and runs its proxy).  Every layer is checked against
@@ -339,7 +366,7 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod):
     d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
     d.bind([t["bytes"] for t in g.tensors])
     net = Net(d, layers, "bf16", 41, with_loss=True)
-    net.enable_backward()
+    net.enable_backward(fuse_masks=fuse)
     assert net.backward_peak_bytes() > 0
     net.forward()
     net.backward(keep=True)
@@ -354,7 +381,7 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod):
     assert np.max(np.abs(gz - ref_gz)) <= 2.0 ** -8 * np.max(np.abs(ref_gz)) + 1e-7
     by_name = {l.name: l for l in layers}
     checked = set()
-    for (lname, gy_name, gpre_name, gx_name, add_name) in net.bwd_trace:
+    for (lname, gy_name, gpre_name, gx_name, add_name, masks_gx) in net.bwd_trace:
         l = by_name[lname]
         if gx_name is None:
             continue                                        # the stem
@@ -366,6 +393,9 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod):
                                                           pad=l.pad, relu=l.relu, dtype="bf16")
             if add_name:
                 ref_gx = ref_gx + on.to_f64(net.read(add_name), "bf16")
+            if masks_gx:
+                ref_gx = np.where(on.to_f64(acts[l.x], "bf16") > 0, ref_gx, 0.0)
+            assert np.array_equal(on.to_f64(net.read(gpre_name), "bf16")[:, ::l.stride, ::l.stride, :][:, :l.P, :l.Q, :], ref_gpre), lname
             got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
             ew = float(np.max(np.abs(got_gw - ref_gw)) / np.max(np.abs(ref_gw)))
             assert ew <= 2e-4, (lname, ew)
