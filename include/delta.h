@@ -218,8 +218,12 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  *     gw[k,r,s,c] = scale_k * sum_m gpre[m,k] * x[m+(r,s),c]   - dL/dw, fp32
  * Supported: DELTA_OP_CONV with 2*pad == R-1 == S-1; gx for bf16 and fp32, gw for bf16 with R in
  * {1,3} and channel counts that are multiples of 64.  A layer with stride > 1 (no residual allowed)
- * gets gpre at the INPUT's resolution: gpre[n, stride*p, stride*q, :] = gy[n,p,q,:] * [y > 0], zero
- * elsewhere, so that both gradients are stride-1 operations on it (stride^2 times the arithmetic).
+ * and a window larger than 1x1 gets gpre at the INPUT's resolution: gpre[n, stride*p, stride*q, :] =
+ * gy[n,p,q,:] * [y > 0], zero elsewhere, so that both gradients are stride-1 operations on it
+ * (stride^2 times the arithmetic).  A 1x1 layer with stride > 1 only reads the input pixels
+ * (stride*p, stride*q): gpre keeps the bytes of y, those pixels are gathered into the workspace for
+ * the weight gradient, and the data gradient is computed at the output's resolution into the
+ * workspace and then spread out (zeros between), gx_add added in a second bf16 rounding.
  * Other operators (bf16 only; gpre must be gy, gx_add unused):
  *   DELTA_OP_MAXPOOL   gx receives gy routed to the first maximal element of each window (scan order
  *                      r, then s); needs fwd.x resident.
@@ -235,8 +239,9 @@ typedef struct delta_bwd_desc {
                                   fwd.y when fwd.relu != 0; fwd.res only says whether a residual exists */
     uint32_t gy;               /* tensor id of dL/dy, resident, bytes of y */
     uint32_t gpre;             /* tensor id that receives gpre: N*H*W*Cout elements (the bytes of y when
-                                  stride == 1); allocated if not resident.  Must equal gy when
-                                  fwd.relu == 0 and stride == 1 (nothing is written then) */
+                                  stride == 1 or the layer is 1x1); allocated if not resident.  Must equal
+                                  gy when there is nothing to write: no ReLU mask to apply (fwd.relu == 0
+                                  or gy_masked) and stride == 1 or a 1x1 layer */
     uint32_t gx;               /* tensor id that receives dL/dx (bytes of x), or DELTA_NO_TENSOR */
     uint32_t gx_add;           /* resident tensor (bytes of x) added to dL/dx before it is stored: the
                                   contribution of another consumer of x; or DELTA_NO_TENSOR */
@@ -249,7 +254,9 @@ typedef struct delta_bwd_desc {
                                   be gy, with stride > 1 gpre receives gy spread to the input's resolution */
     const void *wt;            /* device: weights prepared by delta_bwd_weights (needed when gx is set) */
     void *gw;                  /* device, fp32 [Cout][R][S][Cin]: receives dL/dw (overwritten), or NULL */
-    void *workspace;           /* device scratch for the weight gradient's partial sums, 16-byte aligned */
+    void *workspace;           /* device scratch, 256-byte aligned: the weight gradient's partial sums and,
+                                  for a strided 1x1 layer, its staging tensor; needed when gw is set or
+                                  (strided 1x1) gx is set */
     uint64_t workspace_bytes;  /* at least what delta_backward_workspace reports */
 } delta_bwd_desc;
 
@@ -257,8 +264,7 @@ typedef struct delta_bwd_desc {
  * w): with these weights the data gradient is a forward convolution of gpre.  Device pointers;
  * runs on the compute stream. */
 delta_status delta_bwd_weights(delta_ctx *ctx, const delta_layer_desc *layer, void *wt);
-/* Bytes of workspace delta_backward_segment needs for this layer's weight gradient (0 if the
- * weight gradient is not supported for it). */
+/* Bytes of workspace delta_backward_segment needs for this layer (0 for operators that need none). */
 delta_status delta_backward_workspace(delta_ctx *ctx, const delta_layer_desc *layer, uint64_t *out_bytes);
 /* Runs the descriptors in order on the compute stream.  Everything is validated before the first
  * launch.  Output tensors are allocated from the arena when not resident (DELTA_ERR_OOM_ARENA);

@@ -40,6 +40,8 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 static constexpr int kOutOfRange = (int)0x80000000;   // outside every buffer descriptor used here
 
@@ -97,6 +99,73 @@ __global__ __launch_bounds__(256) void relu_mask_dilate_kernel(const u32x4 *__re
                 }
             } else {
                 o = g;
+            }
+        }
+        out[i] = o;
+    }
+}
+
+// ---------------------------------------------------------------- strided 1x1 layers, directly
+// A 1x1 layer with stride s reads only the pixels (s p, s q) of its input, so both of its
+// gradients are stride-1 operations at the OUTPUT's resolution once those pixels are gathered:
+//   xs[n,p,q,:] = x[n, s p, s q, :]                          subsample_kernel (for dL/dw)
+//   t = 1x1 data gradient of gpre at P x Q
+//   gx[n,h,w,:] = (t[n,h/s,w/s,:] on the grid, else 0) + gx_add, optionally * [x > 0]   spread_add_kernel
+// One 16-byte piece per thread in both.
+__global__ __launch_bounds__(256) void subsample_kernel(const u32x4 *__restrict__ x, u32x4 *__restrict__ xs, int H, int W,
+                                                        int P, int Q, int vec_per_pixel, int stride, size_t n16) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const size_t pix = i / vec_per_pixel;
+        const int v = (int)(i - pix * vec_per_pixel);
+        const int q = (int)(pix % Q);
+        const size_t rest = pix / Q;
+        const int p = (int)(rest % P);
+        const size_t n = rest / P;
+        xs[i] = x[((n * H + (size_t)p * stride) * W + (size_t)q * stride) * vec_per_pixel + v];
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void spread_add_kernel(const u32x4 *__restrict__ t, const u32x4 *__restrict__ add,
+                                                         const u32x4 *__restrict__ mask, u32x4 *__restrict__ out, int H,
+                                                         int W, int P, int Q, int vec_per_pixel, int stride, size_t n16) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const size_t pix = i / vec_per_pixel;
+        const int v = (int)(i - pix * vec_per_pixel);
+        const int w = (int)(pix % W);
+        const size_t rest = pix / W;
+        const int h = (int)(rest % H);
+        const size_t n = rest / H;
+        const int p = h / stride, q = w / stride;
+        const bool on_grid = p * stride == h && q * stride == w && p < P && q < Q;
+        u32x4 o = {0u, 0u, 0u, 0u};
+        if (on_grid) o = t[((n * P + p) * Q + q) * vec_per_pixel + v];
+        if (add) {
+            const u32x4 a = add[i];
+            if (!on_grid) {
+                o = a;                                   // nothing to add to: the bits pass through
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (BF16) {
+                        const float lo = __uint_as_float(o[e] << 16) + __uint_as_float(a[e] << 16);
+                        const float hi = __uint_as_float(o[e] & 0xFFFF0000u) + __uint_as_float(a[e] & 0xFFFF0000u);
+                        const f32x2 pr = {lo, hi};
+                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                    } else {
+                        o[e] = __float_as_uint(__uint_as_float(o[e]) + __uint_as_float(a[e]));
+                    }
+                }
+            }
+        }
+        if (mask) {
+            const u32x4 m = mask[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (BF16) o[e] = keep_where_positive_bf16(o[e], m[e]);
+                else o[e] = keep_where_positive_f32(o[e], m[e]);
             }
         }
         out[i] = o;
@@ -360,6 +429,43 @@ hipError_t launch_relu_mask_dilate(const void *y, const void *gy, void *out, int
         bwd::relu_mask_dilate_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
             static_cast<const bwd::u32x4 *>(y), static_cast<const bwd::u32x4 *>(gy), static_cast<bwd::u32x4 *>(out), H, W,
             P, Q, (int)(row_bytes / 16), stride, n16);
+    return hipGetLastError();
+}
+
+// xs: [N,P,Q,C] = x[N,H,W,C] at the pixels (stride p, stride q).
+hipError_t launch_subsample(const void *x, void *xs, int N, int H, int W, int P, int Q, int C, int stride, int bf16,
+                            hipStream_t stream) {
+    const size_t row_bytes = (size_t)C * (bf16 ? 2 : 4);
+    if (row_bytes % 16 || stride < 1 || (P - 1) * stride >= H || (Q - 1) * stride >= W) return hipErrorInvalidValue;
+    const size_t n16 = (size_t)N * P * Q * (row_bytes / 16);
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    bwd::subsample_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+        static_cast<const bwd::u32x4 *>(x), static_cast<bwd::u32x4 *>(xs), H, W, P, Q, (int)(row_bytes / 16), stride, n16);
+    return hipGetLastError();
+}
+
+// out[N,H,W,C] = t[N,P,Q,C] spread to the pixels (stride p, stride q), zero elsewhere, + add (may
+// be null), then zero where mask (may be null) is not > 0.
+hipError_t launch_spread_add(const void *t, const void *add, const void *mask, void *out, int N, int H, int W, int P,
+                             int Q, int C, int stride, int bf16, hipStream_t stream) {
+    const size_t row_bytes = (size_t)C * (bf16 ? 2 : 4);
+    if (row_bytes % 16 || stride < 1 || (P - 1) * stride >= H || (Q - 1) * stride >= W) return hipErrorInvalidValue;
+    const size_t n16 = (size_t)N * H * W * (row_bytes / 16);
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    const auto *tp = static_cast<const bwd::u32x4 *>(t);
+    const auto *ap = static_cast<const bwd::u32x4 *>(add);
+    const auto *mp = static_cast<const bwd::u32x4 *>(mask);
+    auto *op = static_cast<bwd::u32x4 *>(out);
+    if (bf16)
+        bwd::spread_add_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(tp, ap, mp, op, H, W, P, Q,
+                                                                                        (int)(row_bytes / 16), stride, n16);
+    else
+        bwd::spread_add_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(tp, ap, mp, op, H, W, P, Q,
+                                                                                         (int)(row_bytes / 16), stride, n16);
     return hipGetLastError();
 }
 

@@ -827,6 +827,32 @@ delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint3
 
 // Validates one backward descriptor; fills the forward geometry (fa) and, if gx is asked for, the
 // convolution that computes the data gradient (da).  Pointers in fa/da are placeholders.
+// A 1x1 layer with stride > 1 touches only the input pixels (stride p, stride q): its gradients are
+// computed at the output's resolution (input pixels gathered, data gradient spread back out).
+bool strided_1x1(const delta_layer_desc &L) { return L.stride > 1 && L.R == 1 && L.S == 1 && L.pad == 0; }
+
+// `fa` (the forward layer's arguments) as the weight gradient sees the layer: stride 1.
+void as_stride_1(const delta_layer_desc &L, delta::ConvArgs &fa) {
+    if (strided_1x1(L)) { fa.H = fa.P; fa.W = fa.Q; }
+    else { fa.P = L.H; fa.Q = L.W; }
+    fa.stride = 1;
+    fa.M = L.N * fa.P * fa.Q;
+}
+
+// Bytes of the staging tensor of a strided 1x1 layer (the gathered input pixels, and before that
+// the data gradient at the output's resolution): N*P*Q*Cin elements, after the weight gradient's
+// partial sums in the workspace.
+uint64_t staging_bytes(const delta_layer_desc &L, const delta::ConvArgs &fa) {
+    if (!strided_1x1(L)) return 0;
+    const uint64_t b = (uint64_t)L.N * fa.P * fa.Q * L.Cin * (fa.bf16 ? 2 : 4);
+    return (b + 255) / 256 * 256;
+}
+uint64_t partials_bytes(const delta::ConvArgs &fa) { return ((uint64_t)delta::wgrad_workspace_bytes(fa) + 255) / 256 * 256; }
+// `fa` after as_stride_1
+uint64_t backward_workspace_bytes(const delta_layer_desc &L, const delta::ConvArgs &fa) {
+    return partials_bytes(fa) + staging_bytes(L, fa);
+}
+
 delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, delta::ConvArgs &fa,
                               delta::ConvArgs &da) {
     delta::PoolArgs pa;
@@ -842,11 +868,14 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
         return fail(c, DELTA_ERR_INVALID, "backward %u: a strided layer with a residual has no backward here", i);
     const size_t nt = c->tensors.size();
     const uint64_t ybytes = c->tensors[L.y].bytes, xbytes = c->tensors[L.x].bytes;
-    // gpre lives at the input's resolution (for stride 1 that is y's)
-    const uint64_t gpbytes = (uint64_t)L.N * L.H * L.W * L.Cout * (fa.bf16 ? 2 : 4);
+    // gpre lives at the input's resolution (for stride 1 that is y's), except for strided 1x1
+    // layers, which are handled at the output's resolution
+    const bool direct = strided_1x1(L);
+    const uint64_t gpbytes = direct ? ybytes : (uint64_t)L.N * L.H * L.W * L.Cout * (fa.bf16 ? 2 : 4);
     if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != gpbytes)
-        return fail(c, DELTA_ERR_INVALID, "backward %u: gy must have the bytes of y, gpre N*H*W*Cout elements", i);
-    const bool writes_gpre = (L.relu && !D.gy_masked) || L.stride > 1;
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gy must have the bytes of y, gpre N*H*W*Cout elements "
+                    "(the bytes of y for a 1x1 layer)", i);
+    const bool writes_gpre = (L.relu && !D.gy_masked) || (L.stride > 1 && !direct);
     if (!writes_gpre && D.gpre != D.gy)
         return fail(c, DELTA_ERR_INVALID, "backward %u: without a ReLU mask to apply and stride gpre must be gy itself", i);
     if (D.mask_gx && D.gx == DELTA_NO_TENSOR)
@@ -864,7 +893,8 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
         if ((uint32_t)L.Cin > kMaxChannels) return fail(c, DELTA_ERR_INVALID, "backward %u: too many channels", i);
         memset(&da, 0, sizeof da);
         da.N = L.N; da.H = L.H; da.W = L.W; da.Cin = L.Cout; da.Cout = L.Cin; da.R = L.R; da.S = L.S;
-        da.stride = 1; da.pad = L.R - 1 - L.pad; da.P = L.H; da.Q = L.W; da.M = L.N * L.H * L.W;
+        if (direct) { da.H = fa.P; da.W = fa.Q; }
+        da.stride = 1; da.pad = L.R - 1 - L.pad; da.P = da.H; da.Q = da.W; da.M = L.N * da.H * da.W;
         da.relu = 0; da.bf16 = fa.bf16;
         da.x = da.y = c->arena; da.w = D.wt; da.scale = da.shift = reinterpret_cast<const float *>(c->arena);
         const char *why = delta::conv_check(da);
@@ -872,14 +902,17 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     } else if (D.gx_add != DELTA_NO_TENSOR) {
         return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add without gx", i);
     }
-    // the weight gradient sees the layer at stride 1 (gpre is at the input's resolution)
-    fa.stride = 1; fa.P = L.H; fa.Q = L.W; fa.M = L.N * L.H * L.W;
+    // the weight gradient sees the layer at stride 1 (gpre is at the input's resolution; a strided
+    // 1x1 layer at the output's, on the gathered input pixels)
+    as_stride_1(L, fa);
     if (D.gw) {
         const char *why = delta::wgrad_check(fa);
         if (why) return fail(c, DELTA_ERR_INVALID, "backward %u: %s", i, why);
-        if (((uintptr_t)D.gw & 15) || !D.workspace || ((uintptr_t)D.workspace & 15) ||
-            D.workspace_bytes < delta::wgrad_workspace_bytes(fa))
-            return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned or workspace missing / too small", i);
+        if ((uintptr_t)D.gw & 15) return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned", i);
+    }
+    if (D.gw || (direct && D.gx != DELTA_NO_TENSOR)) {
+        if (!D.workspace || ((uintptr_t)D.workspace & 255) || D.workspace_bytes < backward_workspace_bytes(L, fa))
+            return fail(c, DELTA_ERR_INVALID, "backward %u: workspace missing, not 256-byte aligned or too small", i);
     }
     return DELTA_OK;
 }
@@ -922,8 +955,9 @@ delta_status delta_backward_workspace(delta_ctx *c, const delta_layer_desc *laye
     delta::PoolArgs pa;
     uint64_t flops = 0;
     if ((r = prepare_layer(c, *layer, 0, a, pa, flops)) != DELTA_OK) return r;
-    a.stride = 1; a.P = layer->H; a.Q = layer->W; a.M = layer->N * layer->H * layer->W;   // as the weight gradient sees it
-    *out_bytes = layer->op == DELTA_OP_CONV ? delta::wgrad_workspace_bytes(a) : 0;
+    if (layer->op != DELTA_OP_CONV) { *out_bytes = 0; return DELTA_OK; }
+    as_stride_1(*layer, a);
+    *out_bytes = backward_workspace_bytes(*layer, a);
     return DELTA_OK;
 }
 
@@ -1008,7 +1042,10 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         Tensor &tgy = c->tensors[D.gy];
         if ((r = compute_uses(c, tgy)) != DELTA_OK) return r;
         const bool own_mask = L.relu && !D.gy_masked;
-        if (own_mask || L.stride > 1) {
+        const bool direct = strided_1x1(L);
+        const int outP = (L.H + 2 * L.pad - L.R) / L.stride + 1, outQ = (L.W + 2 * L.pad - L.S) / L.stride + 1;
+        unsigned char *staging = direct ? static_cast<unsigned char *>(D.workspace) + partials_bytes(fa) : nullptr;
+        if (own_mask || (L.stride > 1 && !direct)) {
             Tensor &tgp = c->tensors[D.gpre];
             const unsigned char *yp = nullptr;
             if (own_mask) {
@@ -1017,14 +1054,12 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 yp = c->arena + ty.offset;
             }
             if ((r = compute_writes(c, tgp)) != DELTA_OK) return r;
-            if (L.stride == 1)
+            if (L.stride == 1 || direct)
                 HIP_TRY(c, delta::launch_relu_mask(yp, c->arena + tgy.offset, c->arena + tgp.offset, tgp.bytes,
                                                    fa.bf16, s));
             else
                 HIP_TRY(c, delta::launch_relu_mask_dilate(yp, c->arena + tgy.offset, c->arena + tgp.offset, L.N, L.H,
-                                                          L.W, (L.H + 2 * L.pad - L.R) / L.stride + 1,
-                                                          (L.W + 2 * L.pad - L.S) / L.stride + 1, L.Cout, L.stride,
-                                                          fa.bf16, s));
+                                                          L.W, outP, outQ, L.Cout, L.stride, fa.bf16, s));
         }
         const unsigned char *gp = c->arena + c->tensors[D.gpre].offset;
         if (D.gx != DELTA_NO_TENSOR) {
@@ -1042,14 +1077,22 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
             if ((r = compute_writes(c, tgx)) != DELTA_OK) return r;
             da.x = gp; da.w = D.wt; da.res = addp; da.mask = maskp; da.y = c->arena + tgx.offset;
             da.scale = c->ones; da.shift = c->zeros;
+            if (direct) { da.res = nullptr; da.mask = nullptr; da.y = staging; }
             HIP_TRY(c, delta::launch_conv(da, s));
+            if (direct)
+                HIP_TRY(c, delta::launch_spread_add(staging, addp, maskp, c->arena + tgx.offset, L.N, L.H, L.W, outP, outQ,
+                                                    L.Cin, L.stride, fa.bf16, s));
             c->st.recompute_flops += 2ull * (uint64_t)da.M * da.R * da.S * da.Cin * da.Cout;
         }
         if (D.gw) {
             Tensor &tx = c->tensors[L.x];
             if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
             fa.x = c->arena + tx.offset;
-            HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, D.workspace_bytes, s));
+            if (direct) {
+                HIP_TRY(c, delta::launch_subsample(fa.x, staging, L.N, L.H, L.W, outP, outQ, L.Cin, L.stride, fa.bf16, s));
+                fa.x = staging;
+            }
+            HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa), s));
             c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
         }
         c->st.recompute_launches += 1;

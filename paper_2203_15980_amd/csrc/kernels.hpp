@@ -63,6 +63,10 @@ hipError_t launch_softmax_ce(const void *logits, const void *labels, int N, int 
 hipError_t launch_relu_mask(const void *y, const void *gy, void *out, size_t bytes, int bf16, hipStream_t stream);
 hipError_t launch_relu_mask_dilate(const void *y, const void *gy, void *out, int N, int H, int W, int P, int Q, int K,
                                    int stride, int bf16, hipStream_t stream);
+hipError_t launch_subsample(const void *x, void *xs, int N, int H, int W, int P, int Q, int C, int stride, int bf16,
+                            hipStream_t stream);
+hipError_t launch_spread_add(const void *t, const void *add, const void *mask, void *out, int N, int H, int W, int P,
+                             int Q, int C, int stride, int bf16, hipStream_t stream);
 hipError_t launch_bwd_weights(const void *w, const float *scale, void *wt, int K, int R, int S, int C, int bf16,
                               hipStream_t stream);
 const char *wgrad_check(const ConvArgs &a);            // nullptr when the weight-gradient kernel applies

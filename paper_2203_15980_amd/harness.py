@@ -123,7 +123,7 @@ class Net:
         return bool(l.relu) and l.y in self.masked_by
 
     def _own_gpre(self, l):
-        return l.kind == "conv" and ((l.relu and not self._gy_masked(l)) or l.stride > 1)
+        return l.kind == "conv" and ((l.relu and not self._gy_masked(l)) or (l.stride > 1 and l.R > 1))
 
     def _plan_mask_fusion(self):
         """tensor name -> the layer that applies the ReLU mask of the tensor's producer while it
@@ -172,7 +172,8 @@ class Net:
                 new_tensor("scratch:" + l.name, self.sizes[self.ids[l.y]], self.shapes[l.y])
                 continue
             if self._own_gpre(l):
-                shape = (l.N, l.H, l.W, l.Cout)          # at the input's resolution
+                # at the input's resolution; a 1x1 layer's at the output's
+                shape = (l.N, l.H, l.W, l.Cout) if l.R > 1 else self.shapes[l.y]
                 new_tensor("gp:" + l.name, int(np.prod(shape)) * self.es, shape)
             if l.x != "x0" or input_gradient:
                 new_tensor("g:" + l.x + ":" + l.name, self.sizes[self.ids[l.x]], self.shapes[l.x])

@@ -36,7 +36,9 @@ CASES = [
     ("1x1_128_128", 2, 10, 10, 128, 128, 1, True, False, False, 1),
     ("3x3_s2",     2, 14, 14,  64, 128, 3, True, False, False, 2),    # strided: gpre at the input's resolution
     ("3x3_s2_odd", 1,  9, 13, 128,  64, 3, True, False, True, 2),     # odd image sizes
-    ("1x1_s2",     2, 12, 12, 128, 256, 1, False, False, False, 2),   # the projection shortcut
+    ("1x1_s2",     2, 12, 12, 128, 256, 1, False, False, False, 2),   # the projection shortcut: at the output's resolution
+    ("1x1_s2_odd", 2,  9, 13, 128,  64, 1, True, False, True, 2),     # with ReLU, gx_add, odd image sizes
+    ("1x1_s2_fx",  1, 10, 10,  64, 128, 1, False, False, True, 2, "x"),
     # fused masks ("x": this layer masks gx with [x > 0]; "y": gy arrives already masked)
     ("1x1_64_256_fx",  2, 12, 12,  64, 256, 1, True, True, False, 1, "x"),    # data gradient: streaming kernel
     ("1x1_256_64_fxy", 3,  9, 11, 256,  64, 1, True, False, True, 1, "xy"),   # streaming kernel, sliced, with gx_add
@@ -62,7 +64,8 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     x = synth.make_input(master, (N, H, W, Cin), "bf16")
     p = synth.make_params(master, l, "bf16")
     yshape = (N, P, Q, Cout)
-    gpshape = (N, H, W, Cout)
+    direct = R == 1 and stride > 1                        # handled at the output's resolution
+    gpshape = yshape if direct else (N, H, W, Cout)
     bits = lambda aid, shape: synth.f32_to_bf16_bits(
         synth.normal(master, aid, int(np.prod(shape))).astype(np.float32)).reshape(shape)
     res = bits(901, yshape) if has_res else None
@@ -112,7 +115,7 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     assert ws_bytes > 0
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
-    own_gpre = (relu and not gy_masked) or stride > 1
+    own_gpre = (relu and not gy_masked) or (stride > 1 and not direct)
     desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if own_gpre else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
                       mask_gx=int(mask_gx), gy_masked=int(gy_masked),
                       wt=wt.data_ptr(), gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
@@ -131,7 +134,10 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     # gpre: pure masking, bit for bit
     gpre_gpu = on.to_f64(get(4 if own_gpre else 3, gpshape), "bf16")
     want_gpre = np.zeros(gpshape)
-    want_gpre[:, 0:stride * P:stride, 0:stride * Q:stride, :] = ref_gpre     # at the input's resolution
+    if direct:
+        want_gpre = ref_gpre
+    else:
+        want_gpre[:, 0:stride * P:stride, 0:stride * Q:stride, :] = ref_gpre     # at the input's resolution
     assert np.array_equal(gpre_gpu, want_gpre)
     if relu:
         assert (ref_gpre == 0).any() and (ref_gpre != 0).any()
@@ -395,7 +401,10 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
                 ref_gx = ref_gx + on.to_f64(net.read(add_name), "bf16")
             if masks_gx:
                 ref_gx = np.where(on.to_f64(acts[l.x], "bf16") > 0, ref_gx, 0.0)
-            assert np.array_equal(on.to_f64(net.read(gpre_name), "bf16")[:, ::l.stride, ::l.stride, :][:, :l.P, :l.Q, :], ref_gpre), lname
+            got_gpre = on.to_f64(net.read(gpre_name), "bf16")
+            if l.R > 1:                                     # at the input's resolution
+                got_gpre = got_gpre[:, ::l.stride, ::l.stride, :][:, :l.P, :l.Q, :]
+            assert np.array_equal(got_gpre, ref_gpre), lname
             got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
             ew = float(np.max(np.abs(got_gw - ref_gw)) / np.max(np.abs(ref_gw)))
             assert ew <= 2e-4, (lname, ew)
