@@ -10,3 +10,4 @@ from .rng import (splitmix64, stream_seed, uniform01, normal, uniform,  # noqa: 
 from .resnet import (LayerSpec, bottleneck_stack, resnet_layers, make_params,  # noqa: F401
                      make_input, make_labels, fused_graph, opgranular_graph, config_graph,
                      transformer_graph, Graph, master_seed, cost_model_ns)
+from .transformer import encoder_layers, make_layer_params, make_encoder_params, LN_EPS  # noqa: F401

@@ -25,7 +25,7 @@ def master_seed(cfg: int) -> int:
 class LayerSpec:
     """One fused layer: y = relu?(bn(conv(x, w)) + res?), NHWC activations, KRSC weights."""
     name: str
-    kind: str               # 'conv' | 'maxpool' | 'avgpool' | 'fc' | 'input' | 'loss'
+    kind: str               # 'conv' | 'maxpool' | 'avgpool' | 'fc' | 'input' | 'loss' | transformer.py's kinds
     x: Optional[str]
     res: Optional[str]
     y: str
@@ -40,6 +40,7 @@ class LayerSpec:
     pad: int = 0
     relu: bool = True
     index: int = 0          # position in the network, used to derive array ids
+    act: str = ""           # 'gelu' for a linear layer that ends in GELU
 
     @property
     def P(self):
@@ -55,8 +56,12 @@ class LayerSpec:
 
     @property
     def flops(self):
-        if self.kind in ("conv", "fc"):
+        if self.kind in ("conv", "fc", "linear"):
             return 2 * self.M * self.R * self.S * self.Cin * self.Cout
+        if self.kind == "attention":                 # q k^T and p v: 2 * 2 * N * S^2 * hidden
+            return 4 * self.N * self.H * self.H * self.Cout
+        if self.kind == "layernorm":
+            return 8 * self.N * self.H * self.W * self.Cin
         if self.kind == "maxpool":
             return self.M * self.R * self.S * self.Cout
         if self.kind == "avgpool":
@@ -227,9 +232,9 @@ def fused_graph(layers: List[LayerSpec], dtype, with_loss=False, costs=None) -> 
         g.add_bwd([logits, lab], 2000)
     for l in reversed(layers):
         reads = []
-        if l.kind in ("conv", "fc", "maxpool"):
+        if l.kind in ("conv", "fc", "maxpool", "linear", "attention", "layernorm"):
             reads.append(g.names[l.x])
-        if (l.kind == "conv" and l.relu) or l.kind == "maxpool":
+        if (l.kind == "conv" and l.relu) or l.kind in ("maxpool", "attention") or (l.kind == "linear" and l.act):
             reads.append(g.names[l.y])
         g.add_bwd(reads, 2 * g.tensors[g.names[l.y]]["cost_ns"])
     return g
