@@ -68,7 +68,9 @@ enum {
     DELTA_OP_CONV = 0,       /* fused conv + BN affine (+ residual) (+ ReLU); also the classifier */
     DELTA_OP_MAXPOOL = 1,    /* R x S window, stride, pad; padding never wins the maximum */
     DELTA_OP_AVGPOOL = 2,    /* global average over H x W */
-    DELTA_OP_SOFTMAX_CE = 3  /* mean cross-entropy of logits x [N, Cin] against labels `res` */
+    DELTA_OP_SOFTMAX_CE = 3, /* mean cross-entropy of logits x [N, Cin] against labels `res` */
+    DELTA_OP_ATTENTION = 4,  /* fused multi-head self-attention of a transformer layer (bf16, heads of 64) */
+    DELTA_OP_LAYERNORM = 5   /* layer normalisation over the channel axis (bf16) */
 };
 enum { DELTA_SYNC_D2H = 1, DELTA_SYNC_H2D = 2, DELTA_SYNC_COMPUTE = 4, DELTA_SYNC_ALL = 7 };
 enum { DELTA_DIR_D2H = 0, DELTA_DIR_H2D = 1, DELTA_DIR_BOTH = 2 };
@@ -106,13 +108,26 @@ typedef struct {
 
 typedef struct { uint32_t step, action, tensor, pad; } delta_event;
 
-/* One layer.  DELTA_OP_CONV: y = relu?(scale_k * conv(x, w) + shift_k (+ res)), activations
+/* Activation of a DELTA_OP_CONV layer (field `relu`). */
+enum { DELTA_ACT_NONE = 0, DELTA_ACT_RELU = 1, DELTA_ACT_GELU = 2 /* x/2 (1 + erf(x / sqrt 2)) */ };
+
+/* One layer.  DELTA_OP_CONV: y = act(scale_k * conv(x, w) + shift_k (+ res)), activations
  * NHWC, weights KRSC (w[k][r][s][c]), scale/shift fp32 per output channel (folded batch-norm
  * with frozen statistics; scale = 1, shift = bias for the classifier).  The pooling
  * operators use x, y, N, H, W, Cin (= Cout), R, S, stride, pad and ignore w/scale/shift/res.
  * DELTA_OP_SOFTMAX_CE reads logits x [N, Cin] (storage dtype) and int64 labels in tensor
  * `res` [N], and writes one fp32 (the mean loss) to y.  x, res, y are tensor ids of the
- * bound table. */
+ * bound table.
+ * Transformer encoder layers (the paper's BERT-base workload, Sec. 5.2; the layer itself is the
+ * published post-LN encoder): a linear layer y = act(x w^T + bias + res) is DELTA_OP_CONV with
+ * H = sequence length, W = R = S = stride = 1, pad = 0, w [Cout][Cin], scale = ones, shift = bias.
+ * DELTA_OP_ATTENTION: x = qkv [N, H, Cin] with Cin = 3 * Cout (q | k | v, head h in columns
+ * [64 h, 64 h + 64) of each), y = ctx [N, H, Cout] = concat_h softmax(q_h k_h^T / 8) v_h over all H
+ * positions, no mask; R = number of heads, Cout = 64 * R; the scores never reach memory (fp32 on
+ * chip, probabilities rounded to bf16 before they multiply v).  W = S = stride = 1, pad = 0.
+ * DELTA_OP_LAYERNORM: y = (x - mean) / sqrt(var + eps) * scale + shift over the Cin (= Cout,
+ * multiple of 8, <= 2048) channels of each of the N*H*W rows; scale = gamma, shift = beta.
+ * Both are bf16 only and ignore w and res. */
 typedef struct {
     uint32_t x, res, y;        /* res = DELTA_NO_TENSOR when there is no residual */
     uint32_t dtype;            /* DELTA_DTYPE_*: storage type of x, res, y and w */
@@ -120,8 +135,9 @@ typedef struct {
     const float *scale;        /* device */
     const float *shift;        /* device */
     int32_t N, H, W, Cin, Cout, R, S, stride, pad;
-    uint32_t relu;
+    uint32_t relu;             /* DELTA_ACT_* (convolution / linear layers) */
     uint32_t op;               /* DELTA_OP_* */
+    float eps;                 /* DELTA_OP_LAYERNORM only */
 } delta_layer_desc;
 
 typedef struct {

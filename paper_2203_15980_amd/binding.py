@@ -15,7 +15,8 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 SYNC_D2H, SYNC_H2D, SYNC_COMPUTE, SYNC_ALL = 1, 2, 4, 7
 DIR_D2H, DIR_H2D, DIR_BOTH = 0, 1, 2
 NO_TENSOR = 0xFFFFFFFF
-OP_CONV, OP_MAXPOOL, OP_AVGPOOL, OP_SOFTMAX_CE = 0, 1, 2, 3
+OP_CONV, OP_MAXPOOL, OP_AVGPOOL, OP_SOFTMAX_CE, OP_ATTENTION, OP_LAYERNORM = 0, 1, 2, 3, 4, 5
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
 EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "delta_bind",
            "delta_alloc", "delta_tensor_ptr", "delta_release", "delta_swap_out", "delta_prefetch",
@@ -50,7 +51,7 @@ class LayerDesc(C.Structure):
                 ("w", C.c_void_p), ("scale", C.c_void_p), ("shift", C.c_void_p),
                 ("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("Cin", C.c_int32),
                 ("Cout", C.c_int32), ("R", C.c_int32), ("S", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("relu", C.c_uint32), ("op", C.c_uint32)]
+                ("pad", C.c_int32), ("relu", C.c_uint32), ("op", C.c_uint32), ("eps", C.c_float)]
 
 
 class BwdDesc(C.Structure):

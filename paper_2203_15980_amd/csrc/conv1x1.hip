@@ -260,7 +260,7 @@ static int slice_groups(const ConvArgs &a) {
 // channels only while all output channels fit one slice of 64 (each further slice re-reads a
 // 512-byte activation row that the tiled kernel shares through LDS), and never with 512.
 bool conv1x1_stream_applies(const ConvArgs &a) {
-    if (!a.bf16 || a.R != 1 || a.S != 1 || a.pad != 0 || a.Cout % 64) return false;
+    if (!a.bf16 || a.R != 1 || a.S != 1 || a.pad != 0 || a.Cout % 64 || a.relu > 1) return false;
     if (a.Cin == 256) return a.Cout == 64;
     if (a.Cin != 64 && a.Cin != 128) return false;
     return slice_groups(a) != 0;

@@ -345,9 +345,12 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
                         v[2] += __uint_as_float(rv.z); v[3] += __uint_as_float(rv.w);
                     }
                 }
-                if (a.relu) {
+                if (a.relu == 1) {
 #pragma unroll
                     for (int e = 0; e < CPL; ++e) v[e] = v[e] < 0.f ? 0.f : v[e];   // NaN stays NaN
+                } else if (a.relu == 2) {
+#pragma unroll
+                    for (int e = 0; e < CPL; ++e) v[e] = 0.5f * v[e] * (1.0f + erff(v[e] * 0.70710678118654752f));
                 }
                 u32x4 o;
                 if constexpr (BF16) {
@@ -410,6 +413,7 @@ const char *conv_check(const ConvArgs &a) {
     const int kc = a.bf16 ? 64 : 32;
     if (a.N <= 0 || a.H <= 0 || a.W <= 0 || a.R <= 0 || a.S <= 0 || a.stride <= 0 || a.pad < 0)
         return "non-positive dimension";
+    if (a.relu < 0 || a.relu > 2) return "unknown activation";
     // with more padding than half a window, input pixel indices would no longer grow with the
     // output pixel index, which the tiled kernel's tile-relative offsets rely on
     if (2 * a.pad > a.R - 1 || 2 * a.pad > a.S - 1) return "padding larger than half the window";

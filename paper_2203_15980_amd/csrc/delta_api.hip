@@ -528,7 +528,8 @@ static delta_status prepare_layer(delta_ctx *c, const delta_layer_desc &L, uint3
         if (L.stride <= 0 || L.R <= 0 || L.S <= 0 || L.pad < 0 || L.Cout <= 0)
             return fail(c, DELTA_ERR_INVALID, "layer %u: non-positive dimension", i);
         a.N = L.N; a.H = L.H; a.W = L.W; a.Cin = L.Cin; a.Cout = L.Cout; a.R = L.R; a.S = L.S;
-        a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0; a.bf16 = bf16;
+        if (L.relu > DELTA_ACT_GELU) return fail(c, DELTA_ERR_INVALID, "layer %u: unknown activation %u", i, L.relu);
+        a.stride = L.stride; a.pad = L.pad; a.relu = (int)L.relu; a.bf16 = bf16;
         a.P = (L.H + 2 * L.pad - L.R) / L.stride + 1;
         a.Q = (L.W + 2 * L.pad - L.S) / L.stride + 1;
         const long long M = (long long)L.N * a.P * a.Q;
@@ -572,6 +573,25 @@ static delta_status prepare_layer(delta_ctx *c, const delta_layer_desc &L, uint3
             return fail(c, DELTA_ERR_INVALID, "layer %u: labels tensor must hold N int64 values", i);
         ybytes = 4;
         break;
+    case DELTA_OP_ATTENTION: {
+        if (L.W != 1 || L.R <= 0 || L.Cout != 64 * L.R || L.Cin != 3 * L.Cout)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: attention needs W = 1, R heads of 64, Cout = 64 R, Cin = 3 Cout", i);
+        if (L.res != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "layer %u: attention takes no second input", i);
+        const char *why = delta::attention_check(c->arena, c->arena, L.N, L.H, L.R, bf16);
+        if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
+        ybytes = (uint64_t)L.N * L.H * L.Cout * es;
+        flops = 4ull * (uint64_t)L.N * L.H * L.H * L.Cout;
+        break;
+    }
+    case DELTA_OP_LAYERNORM: {
+        if (L.Cout != L.Cin) return fail(c, DELTA_ERR_INVALID, "layer %u: layer normalisation keeps the shape", i);
+        if (L.res != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "layer %u: layer normalisation takes no second input", i);
+        if (!(L.eps >= 0.f)) return fail(c, DELTA_ERR_INVALID, "layer %u: eps must be >= 0", i);
+        const char *why = delta::layernorm_check(c->arena, c->arena, L.scale, L.shift, (long long)L.N * L.H * L.W, L.Cin, bf16);
+        if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
+        ybytes = xbytes;
+        break;
+    }
     default:
         return fail(c, DELTA_ERR_INVALID, "layer %u: unknown operator %u", i, L.op);
     }
@@ -631,6 +651,13 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
         case DELTA_OP_AVGPOOL:
             pa.x = xp; pa.y = yp;
             HIP_TRY(c, delta::launch_avgpool(pa, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_ATTENTION:
+            HIP_TRY(c, delta::launch_attention(xp, yp, L.N, L.H, L.R, L.dtype == DELTA_DTYPE_BF16, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_LAYERNORM:
+            HIP_TRY(c, delta::launch_layernorm(xp, yp, L.scale, L.shift, (long long)L.N * L.H * L.W, L.Cin, L.eps,
+                                               L.dtype == DELTA_DTYPE_BF16, c->stream[S_COMPUTE]));
             break;
         default:
             HIP_TRY(c, delta::launch_softmax_ce(xp, rp, L.N, L.Cin, L.dtype == DELTA_DTYPE_BF16,
@@ -860,8 +887,9 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     const delta_layer_desc &L = D.fwd;
     delta_status r = prepare_layer(c, L, i, fa, pa, flops);
     if (r != DELTA_OK) return r;
-    if (L.op != DELTA_OP_CONV || delta::stem_applies(fa))
-        return fail(c, DELTA_ERR_INVALID, "backward %u: the stem convolution has no backward here", i);
+    if (L.op != DELTA_OP_CONV) return fail(c, DELTA_ERR_INVALID, "backward %u: operator %u has no backward here", i, L.op);
+    if (delta::stem_applies(fa)) return fail(c, DELTA_ERR_INVALID, "backward %u: the stem convolution has no backward here", i);
+    if (L.relu > DELTA_ACT_RELU) return fail(c, DELTA_ERR_INVALID, "backward %u: only ReLU layers have a backward here", i);
     if (2 * L.pad != L.R - 1 || 2 * L.pad != L.S - 1)
         return fail(c, DELTA_ERR_INVALID, "backward %u: needs 2*pad == R-1 == S-1", i);
     if (L.stride > 1 && L.res != DELTA_NO_TENSOR)
@@ -1115,6 +1143,8 @@ delta_status delta_layer_kernel(delta_ctx *c, const delta_layer_desc *layer, cha
     case DELTA_OP_MAXPOOL: name = "maxpool"; break;
     case DELTA_OP_AVGPOOL: name = "avgpool"; break;
     case DELTA_OP_SOFTMAX_CE: name = "softmax_ce"; break;
+    case DELTA_OP_ATTENTION: name = "attention bf16 (256 queries x 8 waves, K/V in LDS)"; break;
+    case DELTA_OP_LAYERNORM: name = "layernorm bf16"; break;
     default: break;
     }
     snprintf(out, (size_t)cap, "%s", name);

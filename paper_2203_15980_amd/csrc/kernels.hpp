@@ -14,7 +14,7 @@ struct ConvArgs {
     const float *scale;   // [Cout]
     const float *shift;   // [Cout]
     int N, H, W, Cin, Cout, R, S, stride, pad, P, Q, M;
-    int relu;
+    int relu;             // 0: none, 1: ReLU, 2: GELU (erf form; tiled kernel only)
     int bf16;             // 1: bf16 storage, fp32 accumulate; 0: fp32
 };
 
@@ -41,6 +41,14 @@ hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream);
 // conv3x3_halo.hip: bf16 3x3 stride-1 kernel that keeps the input halo of a pixel tile in LDS
 bool conv3x3_halo_applies(const ConvArgs &a);
 hipError_t launch_conv3x3_halo(const ConvArgs &a, hipStream_t stream);
+// attention.hip: fused multi-head self-attention, head dimension 64, bf16.  qkv [N,S,3*64*heads], ctx [N,S,64*heads]
+const char *attention_check(const void *qkv, const void *ctx, int N, int S, int heads, int bf16);
+hipError_t launch_attention(const void *qkv, void *ctx, int N, int S, int heads, int bf16, hipStream_t stream);
+// transformer_ops.hip: layer normalisation over the last axis of [rows, C], bf16
+const char *layernorm_check(const void *x, const void *y, const float *gamma, const float *beta, long long rows, int C,
+                            int bf16);
+hipError_t launch_layernorm(const void *x, void *y, const float *gamma, const float *beta, long long rows, int C,
+                            float eps, int bf16, hipStream_t stream);
 // net_ops.hip: ResNet stem (7x7, stride 2, pad 3, 3 -> 64 channels, bf16), pooling, loss
 bool stem_applies(const ConvArgs &a);
 const char *stem_check(const ConvArgs &a);

@@ -9,7 +9,8 @@ import synth
 
 from . import binding as B
 
-_OPS = {"conv": B.OP_CONV, "fc": B.OP_CONV, "maxpool": B.OP_MAXPOOL, "avgpool": B.OP_AVGPOOL}
+_OPS = {"conv": B.OP_CONV, "fc": B.OP_CONV, "maxpool": B.OP_MAXPOOL, "avgpool": B.OP_AVGPOOL,
+        "linear": B.OP_CONV, "attention": B.OP_ATTENTION, "layernorm": B.OP_LAYERNORM}
 
 
 def _dev(a, device):
@@ -60,13 +61,25 @@ class Net:
                     scale = torch.ones(l.Cout, dtype=torch.float32, device=device)
                     shift = _dev(p["bias"], device)
                 self.keep += [w, scale, shift]
+            elif l.kind in ("linear", "layernorm"):
+                p = synth.make_layer_params(master, l, dtype)
+                self.params_np[l.name] = p
+                if l.kind == "linear":
+                    w = _dev(p["w"], device)
+                    scale = torch.ones(l.Cout, dtype=torch.float32, device=device)
+                    shift = _dev(p["bias"], device)
+                    self.keep += [w, scale, shift]
+                else:
+                    scale, shift = _dev(p["gamma"], device), _dev(p["beta"], device)
+                    self.keep += [scale, shift]
+            act = 1 if (l.relu and l.kind == "conv") else (B.ACT_GELU if l.act == "gelu" else 0)
             d = B.LayerDesc(x=self.ids[l.x], res=self.ids[l.res] if l.res else B.NO_TENSOR,
                             y=self.ids[l.y], dtype=code, w=w.data_ptr() if w is not None else None,
                             scale=scale.data_ptr() if scale is not None else None,
                             shift=shift.data_ptr() if shift is not None else None,
                             N=l.N, H=l.H, W=l.W, Cin=l.Cin, Cout=l.Cout, R=l.R, S=l.S,
-                            stride=l.stride, pad=l.pad, relu=1 if (l.relu and l.kind == "conv") else 0,
-                            op=_OPS[l.kind])
+                            stride=l.stride, pad=l.pad, relu=act, op=_OPS[l.kind],
+                            eps=float(self.params_np[l.name]["eps"]) if l.kind == "layernorm" else 0.0)
             self.desc[l.y] = B.layer_array([d])
             self.shapes[l.y], self.np_dtype[l.y] = (l.N, l.P, l.Q, l.Cout), store
         order = [self.desc[l.y][0] for l in layers]

@@ -44,10 +44,14 @@ class LayerSpec:
 
     @property
     def P(self):
+        if self.kind in ("attention", "layernorm"):          # R is the number of heads there
+            return self.H
         return (self.H + 2 * self.pad - self.R) // self.stride + 1
 
     @property
     def Q(self):
+        if self.kind in ("attention", "layernorm"):
+            return self.W
         return (self.W + 2 * self.pad - self.S) // self.stride + 1
 
     @property
