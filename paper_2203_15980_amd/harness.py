@@ -222,6 +222,35 @@ class Net:
         self.by_name = {l.name: l for l in self.layers}
         torch.cuda.synchronize()
 
+    def enable_backward_proxy(self):
+        """For networks whose layers have no backward kernels (the transformer encoder): each
+        backward step then runs a compute PROXY - the layer's forward kernel twice, without its
+        residual operand, into a scratch tensor - which reads what the access trace says the
+        backward reads and costs about what a backward costs.  Adds one scratch tensor per
+        output size to the tensor table (re-binds: call while nothing is resident)."""
+        self.n_graph = len(self.sizes)
+        self.proxy_desc = {}
+        scratch = {}
+        extra = []
+        for l in self.layers:
+            nbytes = self.sizes[self.ids[l.y]]
+            if nbytes not in scratch:
+                scratch[nbytes] = self.n_graph + len(extra)
+                extra.append(nbytes)
+            dsc = B.LayerDesc.from_buffer_copy(self.desc[l.y][0])
+            dsc.y, dsc.res = scratch[nbytes], B.NO_TENSOR
+            self.proxy_desc[l.name] = (B.layer_array([dsc]), scratch[nbytes])
+        self.sizes = self.sizes + extra
+        self.delta.bind(self.sizes)
+
+    def backward_proxy_step(self, graph, k):
+        """Backward step `k` of synth.fused_graph's step list, as the compute proxy."""
+        l = self.layers[len(self.layers) - 1 - (k - graph.n_fwd)]
+        arr, sid = self.proxy_desc[l.name]
+        self.delta.recompute_segment(arr)
+        self.delta.recompute_segment(arr)
+        self.delta.release(sid, B.EV_FREE)
+
     def rebind(self, delta):
         """Moves the net to another context (same tensor table); nothing may be resident."""
         self.delta = delta
