@@ -87,6 +87,18 @@ __device__ __forceinline__ void wave_lds_fence() {
 // offset that lies outside every buffer descriptor used here (their sizes stay below 2 GiB)
 static constexpr int kOutOfRange = (int)0x80000000;
 
+// GELU in its erf form, v/2 (1 + erf(v / sqrt 2)).  1 + erf(x) = erfc(-x): for x < 0 it is
+// erfc(|x|), for x >= 0 it is 2 - erfc(x), and erfc(|x|) = poly(t) exp(-x^2), t = 1/(1 + p |x|)
+// (Abramowitz & Stegun 7.1.26, absolute error 1.5e-7) - no cancellation in the negative tail, one
+// exp and one reciprocal per element instead of the library erff's branches.
+__device__ __forceinline__ float gelu_erf(float v) {
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float c = poly * __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);   // erfc(|x|)
+    return 0.5f * v * (v < 0.f ? c : 2.0f - c);
+}
+
 template <bool BF16, int BM, int BN, int WM, int WN, bool HAS_RES>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     using E = Elem<BF16>;
@@ -350,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
                     for (int e = 0; e < CPL; ++e) v[e] = v[e] < 0.f ? 0.f : v[e];   // NaN stays NaN
                 } else if (a.relu == 2) {
 #pragma unroll
-                    for (int e = 0; e < CPL; ++e) v[e] = 0.5f * v[e] * (1.0f + erff(v[e] * 0.70710678118654752f));
+                    for (int e = 0; e < CPL; ++e) v[e] = gelu_erf(v[e]);
                 }
                 u32x4 o;
                 if constexpr (BF16) {

@@ -238,3 +238,55 @@ def test_attention_at_config5_size_on_sampled_heads(torch_mod):
         print("  image %d head %d err %.2e" % (n, h, err), flush=True)
         assert err <= 2e-2, (n, h, err)
     d.close()
+
+
+def test_encoder_plan_replay_restores_every_backward_operand(torch_mod):
+    """Plan three small encoder layers at 40 % of their activation bytes (library plan = oracle plan),
+    replay it, and compare every tensor a backward step reads with the unconstrained forward's, bit
+    for bit: evicted tensors are rebuilt by the attention / linear / LayerNorm kernels, offloaded
+    ones come back over the link.  Then the same plan once more with the compute-proxy backward."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from oracle import planner as opl
+    from paper_2203_15980_amd.harness import Net, run_plan
+    N, S, H, heads, FF = 2, 150, 128, 2, 256
+    layers = synth.encoder_layers(N, S, H, heads, FF, nlayers=3)
+    g = synth.fused_graph(layers, "bf16")
+    sizes = [t["bytes"] for t in g.tensors]
+
+    def make(arena_bytes):
+        arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda:0")
+        d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+        d.bind(sizes)
+        return d, Net(d, layers, "bf16", 73)
+
+    d0, net0 = make(g.total_bytes() + (1 << 20))
+    net0.forward()
+    want = {t["name"]: net0.read(t["name"]).copy() for t in g.tensors}
+    d0.close()
+    budget = int(g.total_bytes() * 0.4)
+    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9)
+    ev, peak = dl.plan(g.tensors, g.steps, p)
+    assert (ev, peak) == opl.plan(g.tensors, g.steps, p)
+    d, net = make(int(budget * 1.5) + (1 << 20))
+    seen = set()
+
+    def check(k):
+        for t in g.steps[k]["reads"]:
+            n = g.tensors[t]["name"]
+            assert net.read(n).tobytes() == want[n].tobytes(), (k, n)
+            seen.add(n)
+
+    run_plan(net, g, ev, backward_proxy=check)
+    d.sync()
+    st = d.stats()
+    kinds = {a for (_, a, _) in ev}
+    print("events", sorted(kinds), "peak", peak, "budget", budget, "recompute launches", st["recompute_launches"], flush=True)
+    assert st["arena_in_use"] == 0 and st["arena_high_water"] <= budget
+    assert dl.EV_RECOMPUTE in kinds and any(n.endswith("ctx") for n in seen)
+    # the proxy backward: same plan, every backward step runs its operator's forward kernel twice
+    net.enable_backward_proxy()
+    run_plan(net, g, ev, backward_proxy=lambda k: net.backward_proxy_step(g, k))
+    d.sync()
+    assert d.stats()["arena_in_use"] == 0
+    d.close()
