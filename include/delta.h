@@ -70,7 +70,10 @@ enum {
     DELTA_OP_AVGPOOL = 2,    /* global average over H x W */
     DELTA_OP_SOFTMAX_CE = 3, /* mean cross-entropy of logits x [N, Cin] against labels `res` */
     DELTA_OP_ATTENTION = 4,  /* fused multi-head self-attention of a transformer layer (bf16, heads of 64) */
-    DELTA_OP_LAYERNORM = 5   /* layer normalisation over the channel axis (bf16) */
+    DELTA_OP_LAYERNORM = 5,  /* layer normalisation over the channel axis (bf16) */
+    DELTA_OP_BATCHNORM = 6,  /* batch normalisation with the statistics of the batch (bf16) */
+    DELTA_OP_RELU = 7,       /* y = max(x, 0) (bf16) */
+    DELTA_OP_ADD = 8         /* y = x + res (bf16) */
 };
 enum { DELTA_SYNC_D2H = 1, DELTA_SYNC_H2D = 2, DELTA_SYNC_COMPUTE = 4, DELTA_SYNC_ALL = 7 };
 enum { DELTA_DIR_D2H = 0, DELTA_DIR_H2D = 1, DELTA_DIR_BOTH = 2 };
@@ -127,7 +130,14 @@ enum { DELTA_ACT_NONE = 0, DELTA_ACT_RELU = 1, DELTA_ACT_GELU = 2 /* x/2 (1 + er
  * chip, probabilities rounded to bf16 before they multiply v).  W = S = stride = 1, pad = 0.
  * DELTA_OP_LAYERNORM: y = (x - mean) / sqrt(var + eps) * scale + shift over the Cin (= Cout,
  * multiple of 8, <= 2048) channels of each of the N*H*W rows; scale = gamma, shift = beta.
- * Both are bf16 only and ignore w and res. */
+ * Both are bf16 only and ignore w and res.
+ * Operator granularity (the separate ConvForward / BNForward tensors of the paper's cost table,
+ * Sec. 5.5; bf16 only, any N, H, W, Cin = Cout a multiple of 8): a bare convolution is
+ * DELTA_OP_CONV with scale = ones, shift = zeros, relu = 0, no res.  DELTA_OP_BATCHNORM:
+ * y = scale_c (x - mu_c) / sqrt(var_c + eps) + shift_c with mu_c, var_c (biased) the mean and
+ * variance of channel c over the N*H*W positions of THIS batch; scale = gamma, shift = beta;
+ * Cin <= 8192; running statistics are not kept.  DELTA_OP_RELU: y = max(x, 0).  DELTA_OP_ADD:
+ * y = x + res (res required).  All are deterministic: recomputation gives the same bits. */
 typedef struct {
     uint32_t x, res, y;        /* res = DELTA_NO_TENSOR when there is no residual */
     uint32_t dtype;            /* DELTA_DTYPE_*: storage type of x, res, y and w */
@@ -137,7 +147,7 @@ typedef struct {
     int32_t N, H, W, Cin, Cout, R, S, stride, pad;
     uint32_t relu;             /* DELTA_ACT_* (convolution / linear layers) */
     uint32_t op;               /* DELTA_OP_* */
-    float eps;                 /* DELTA_OP_LAYERNORM only */
+    float eps;                 /* DELTA_OP_LAYERNORM and DELTA_OP_BATCHNORM */
 } delta_layer_desc;
 
 typedef struct {

@@ -46,7 +46,8 @@ def to_storage(v, dtype):
     trunc = bits >> 16
     # which side of the float32 value the float64 one lies on (by magnitude): breaks what would
     # otherwise look like a tie after the first rounding
-    resid = (np.abs(v) - np.abs(f.astype(np.float64)))
+    with np.errstate(invalid="ignore"):            # inf - inf for infinite inputs: their low bits are 0 anyway
+        resid = (np.abs(v) - np.abs(f.astype(np.float64)))
     up = (low > 0x8000) | ((low == 0x8000) & ((resid > 0) | ((resid == 0) & ((trunc & 1) == 1))))
     out = (trunc + up.astype(np.uint64)).astype(np.uint16)
     nan = np.isnan(v)

@@ -16,6 +16,7 @@ SYNC_D2H, SYNC_H2D, SYNC_COMPUTE, SYNC_ALL = 1, 2, 4, 7
 DIR_D2H, DIR_H2D, DIR_BOTH = 0, 1, 2
 NO_TENSOR = 0xFFFFFFFF
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL, OP_SOFTMAX_CE, OP_ATTENTION, OP_LAYERNORM = 0, 1, 2, 3, 4, 5
+OP_BATCHNORM, OP_RELU, OP_ADD = 6, 7, 8
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
 EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "delta_bind",

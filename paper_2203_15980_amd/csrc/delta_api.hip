@@ -82,6 +82,7 @@ struct delta_ctx {
     std::vector<Timed> timed;
     delta_stats_t st;
     bool skip_copies = false;
+    void *bn_scratch = nullptr;                    // partial sums of DELTA_OP_BATCHNORM, allocated on first use
     float *ones = nullptr, *zeros = nullptr;       // kMaxChannels floats each (identity scale/shift of the data gradient)
     uint64_t ev_seq = 0;
     std::string err;
@@ -370,6 +371,7 @@ void delta_destroy(delta_ctx *c) {
             (void)hipEventDestroy(c->timed[i].start);
             (void)hipEventDestroy(c->timed[i].stop);
         }
+        if (c->bn_scratch) (void)hipFree(c->bn_scratch);
         if (c->ones) (void)hipFree(c->ones);
         if (c->zeros) (void)hipFree(c->zeros);
         (void)hipStreamDestroy(c->stream[S_D2H]);
@@ -592,6 +594,23 @@ static delta_status prepare_layer(delta_ctx *c, const delta_layer_desc &L, uint3
         ybytes = xbytes;
         break;
     }
+    case DELTA_OP_BATCHNORM:
+    case DELTA_OP_RELU:
+    case DELTA_OP_ADD: {
+        if (!bf16) return fail(c, DELTA_ERR_INVALID, "layer %u: this operator is bf16 only", i);
+        if (L.Cout != L.Cin || L.Cin % 8) return fail(c, DELTA_ERR_INVALID, "layer %u: Cout = Cin, a multiple of 8", i);
+        if ((L.op == DELTA_OP_ADD) != (L.res != DELTA_NO_TENSOR))
+            return fail(c, DELTA_ERR_INVALID, "layer %u: add needs a second input, the others take none", i);
+        if (L.op == DELTA_OP_ADD && c->tensors[L.res].bytes != xbytes)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: second input tensor %u has the wrong size", i, L.res);
+        if (L.op == DELTA_OP_BATCHNORM) {
+            if (!(L.eps >= 0.f)) return fail(c, DELTA_ERR_INVALID, "layer %u: eps must be >= 0", i);
+            const char *why = delta::bn_train_check(c->arena, c->arena, L.scale, L.shift, (long long)L.N * L.H * L.W, L.Cin, bf16);
+            if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
+        }
+        ybytes = xbytes;
+        break;
+    }
     default:
         return fail(c, DELTA_ERR_INVALID, "layer %u: unknown operator %u", i, L.op);
     }
@@ -654,6 +673,17 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
             break;
         case DELTA_OP_ATTENTION:
             HIP_TRY(c, delta::launch_attention(xp, yp, L.N, L.H, L.R, L.dtype == DELTA_DTYPE_BF16, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_BATCHNORM:
+            if (!c->bn_scratch) HIP_TRY(c, hipMalloc(&c->bn_scratch, delta::bn_train_scratch_bytes()));
+            HIP_TRY(c, delta::launch_bn_train(xp, yp, L.scale, L.shift, (long long)L.N * L.H * L.W, L.Cin, L.eps, 1,
+                                              c->bn_scratch, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_RELU:
+            HIP_TRY(c, delta::launch_relu(xp, yp, ty.bytes, 1, c->stream[S_COMPUTE]));
+            break;
+        case DELTA_OP_ADD:
+            HIP_TRY(c, delta::launch_add(xp, rp, yp, ty.bytes, 1, c->stream[S_COMPUTE]));
             break;
         case DELTA_OP_LAYERNORM:
             HIP_TRY(c, delta::launch_layernorm(xp, yp, L.scale, L.shift, (long long)L.N * L.H * L.W, L.Cin, L.eps,
@@ -1145,6 +1175,9 @@ delta_status delta_layer_kernel(delta_ctx *c, const delta_layer_desc *layer, cha
     case DELTA_OP_SOFTMAX_CE: name = "softmax_ce"; break;
     case DELTA_OP_ATTENTION: name = "attention bf16 (256 queries x 8 waves, K/V in LDS)"; break;
     case DELTA_OP_LAYERNORM: name = "layernorm bf16"; break;
+    case DELTA_OP_BATCHNORM: name = "batchnorm (batch statistics) bf16: stats + finalize + apply"; break;
+    case DELTA_OP_RELU: name = "relu bf16"; break;
+    case DELTA_OP_ADD: name = "add bf16"; break;
     default: break;
     }
     snprintf(out, (size_t)cap, "%s", name);

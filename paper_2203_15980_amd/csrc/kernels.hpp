@@ -49,6 +49,14 @@ const char *layernorm_check(const void *x, const void *y, const float *gamma, co
                             int bf16);
 hipError_t launch_layernorm(const void *x, void *y, const float *gamma, const float *beta, long long rows, int C,
                             float eps, int bf16, hipStream_t stream);
+// opgranular_ops.hip: training-mode batch normalisation over [M, C] (bf16), ReLU, residual add
+const char *bn_train_check(const void *x, const void *y, const float *gamma, const float *beta, long long M, int C,
+                           int bf16);
+size_t bn_train_scratch_bytes();
+hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const float *beta, long long M, int C, float eps,
+                           int bf16, void *scratch, hipStream_t stream);
+hipError_t launch_relu(const void *x, void *y, size_t bytes, int bf16, hipStream_t stream);
+hipError_t launch_add(const void *x, const void *r, void *y, size_t bytes, int bf16, hipStream_t stream);
 // net_ops.hip: ResNet stem (7x7, stride 2, pad 3, 3 -> 64 channels, bf16), pooling, loss
 bool stem_applies(const ConvArgs &a);
 const char *stem_check(const ConvArgs &a);

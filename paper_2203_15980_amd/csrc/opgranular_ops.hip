@@ -1,0 +1,264 @@
+// Operators of the operator-granular graph (the granularity of the paper's cost table, Sec. 5.5:
+// ConvForward, BNForward, ... are separate managed tensors) for gfx950, bf16 NHWC:
+//   training-mode batch normalisation   y = gamma (x - mu_B) / sqrt(var_B + eps) + beta
+//   ReLU                                y = max(x, 0)
+//   residual add                        y = x + r
+// All three are HBM-bound (16 bytes per lane).  Batch normalisation reads x twice (statistics,
+// then normalise) and writes y once:
+//   bn_stats_kernel     each workgroup sums (x - K_c) and (x - K_c)^2 over its block of rows, per
+//                       channel, fp32, K_c = x[0, c] (shifted data: no cancellation when the mean is
+//                       far from 0); lanes own 8 channels, the row-parallel lanes of a workgroup are
+//                       combined through LDS in a fixed order; partial sums to a scratch buffer
+//   bn_finalize_kernel  one thread per channel adds the partials in block order (double), forms
+//                       mean, biased variance and a = gamma / sqrt(var + eps)
+//   bn_apply_kernel     y = a_c (x - mean_c) + beta_c   (centred first: no cancellation of two large products)
+// No atomics: the result is a fixed function of the input (recomputation is bit-identical).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.hpp"
+
+namespace delta {
+namespace ops {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float lo16(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float hi16(uint32_t p) { return __uint_as_float(p & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
+    f[0] = lo16(v.x); f[1] = hi16(v.x); f[2] = lo16(v.y); f[3] = hi16(v.y);
+    f[4] = lo16(v.z); f[5] = hi16(v.z); f[6] = lo16(v.w); f[7] = hi16(v.w);
+}
+
+// CH = min(chunks, 256) chunk columns per pass, RS = 256 / CH rows in parallel.
+// partial: [gridDim.x][2][C] floats.
+__global__ __launch_bounds__(256) void bn_stats_kernel(const unsigned char *x, float *partial, long long M, int C,
+                                                       long long rows_per_block, int CH, int RS) {
+    extern __shared__ __align__(16) float red[];                 // [RS][CH][16]
+    const int chunks = C / 8;
+    const int t = threadIdx.x;
+    const int ck0 = t % CH, rsub = t / CH;
+    const long long r0 = (long long)blockIdx.x * rows_per_block;
+    long long r1 = r0 + rows_per_block;
+    if (r1 > M) r1 = M;
+    for (int cg = 0; cg < chunks; cg += CH) {
+        const int ck = cg + ck0;
+        const bool live = ck < chunks && rsub < RS;
+        float s1[8], s2[8], k[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s1[e] = s2[e] = 0.f;
+        if (live) {
+            unpack8(*reinterpret_cast<const u32x4 *>(x + (size_t)ck * 16), k);      // row 0: the shift
+            long long r = r0 + rsub;
+            for (; r + 3LL * RS < r1; r += 4LL * RS) {            // four rows in flight per lane
+                u32x4 raw[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    raw[u] = *reinterpret_cast<const u32x4 *>(x + ((size_t)(r + (long long)u * RS) * chunks + ck) * 16);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float v[8];
+                    unpack8(raw[u], v);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float d = v[e] - k[e];
+                        s1[e] += d;
+                        s2[e] += d * d;
+                    }
+                }
+            }
+            for (; r < r1; r += RS) {
+                float v[8];
+                unpack8(*reinterpret_cast<const u32x4 *>(x + ((size_t)r * chunks + ck) * 16), v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float d = v[e] - k[e];
+                    s1[e] += d;
+                    s2[e] += d * d;
+                }
+            }
+        }
+        if (cg) __syncthreads();                                 // the previous pass's reads are done
+        if (rsub < RS) {
+            float *p = red + ((size_t)rsub * CH + ck0) * 16;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { p[e] = s1[e]; p[8 + e] = s2[e]; }
+        }
+        __syncthreads();
+        if (rsub == 0 && ck < chunks) {
+            float a1[8], a2[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a1[e] = a2[e] = 0.f;
+            for (int j = 0; j < RS; ++j) {                       // fixed order
+                const float *p = red + ((size_t)j * CH + ck0) * 16;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { a1[e] += p[e]; a2[e] += p[8 + e]; }
+            }
+            float *o = partial + (size_t)blockIdx.x * 2 * C + ck * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { o[e] = a1[e]; o[C + e] = a2[e]; }
+        }
+    }
+}
+
+// ab: [2][C]: a, then the mean.  A workgroup of 1024 threads takes 64 channels: thread (channel
+// lane, group g of 16) adds the partials of blocks g, g + 16, ... (coalesced over the channels,
+// eight loads in flight), the 16 groups are then added in order through LDS.
+__global__ __launch_bounds__(1024) void bn_finalize_kernel(const unsigned char *x, const float *partial, const float *gamma,
+                                                           const float *beta, float *ab, long long M, int C, int blocks,
+                                                           float eps) {
+    __shared__ double red[2][16][64];
+    const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cl;
+    double s1 = 0.0, s2 = 0.0;
+    if (c < C) {
+        int b = grp;
+        for (; b + 7 * 16 < blocks; b += 8 * 16) {
+            float p1[8], p2[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                p1[u] = partial[(size_t)(b + 16 * u) * 2 * C + c];
+                p2[u] = partial[(size_t)(b + 16 * u) * 2 * C + C + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s1 += (double)p1[u]; s2 += (double)p2[u]; }
+        }
+        for (; b < blocks; b += 16) {
+            s1 += (double)partial[(size_t)b * 2 * C + c];
+            s2 += (double)partial[(size_t)b * 2 * C + C + c];
+        }
+    }
+    red[0][grp][cl] = s1;
+    red[1][grp][cl] = s2;
+    __syncthreads();
+    if (grp != 0 || c >= C) return;
+    s1 = s2 = 0.0;
+    for (int g = 0; g < 16; ++g) { s1 += red[0][g][cl]; s2 += red[1][g][cl]; }
+    const double k = (double)__uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(x)[c] << 16);
+    const double md = s1 / (double)M;
+    double var = s2 / (double)M - md * md;
+    if (var < 0.0) var = 0.0;
+    const double mean = k + md;
+    ab[c] = (float)((double)gamma[c] / sqrt(var + (double)eps));
+    ab[C + c] = (float)mean;
+    (void)beta;
+}
+
+__global__ __launch_bounds__(256) void bn_apply_kernel(const u32x4 *__restrict__ x, u32x4 *__restrict__ y,
+                                                       const float *__restrict__ ab, const float *__restrict__ beta, int C,
+                                                       size_t n16) {
+    const int chunks = C / 8;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const int ck = (int)(i % chunks);
+        float v[8];
+        unpack8(x[i], v);
+        const f32x4 a0 = *reinterpret_cast<const f32x4 *>(ab + ck * 8), a1 = *reinterpret_cast<const f32x4 *>(ab + ck * 8 + 4);
+        const f32x4 m0 = *reinterpret_cast<const f32x4 *>(ab + C + ck * 8), m1 = *reinterpret_cast<const f32x4 *>(ab + C + ck * 8 + 4);
+        const f32x4 b0 = *reinterpret_cast<const f32x4 *>(beta + ck * 8), b1 = *reinterpret_cast<const f32x4 *>(beta + ck * 8 + 4);
+        u32x4 o;
+        o.x = pack2((v[0] - m0.x) * a0.x + b0.x, (v[1] - m0.y) * a0.y + b0.y);
+        o.y = pack2((v[2] - m0.z) * a0.z + b0.z, (v[3] - m0.w) * a0.w + b0.w);
+        o.z = pack2((v[4] - m1.x) * a1.x + b1.x, (v[5] - m1.y) * a1.y + b1.y);
+        o.w = pack2((v[6] - m1.z) * a1.z + b1.z, (v[7] - m1.w) * a1.w + b1.w);
+        y[i] = o;
+    }
+}
+
+// y = max(x, 0): a negative bf16 has its sign bit set (NaN passes through, as in the fused epilogue)
+__global__ __launch_bounds__(256) void relu_kernel(const u32x4 *__restrict__ x, u32x4 *__restrict__ y, size_t n16) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        u32x4 v = x[i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lo = v[e] & 0xFFFFu, hi = v[e] >> 16;
+            const bool nlo = (lo & 0x8000u) && (lo & 0x7FFFu) <= 0x7F80u;    // negative, not NaN
+            const bool nhi = (hi & 0x8000u) && (hi & 0x7FFFu) <= 0x7F80u;
+            v[e] = (nlo ? 0u : lo) | ((nhi ? 0u : hi) << 16);
+        }
+        y[i] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void add_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ r,
+                                                  u32x4 *__restrict__ y, size_t n16) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const u32x4 a = x[i], b = r[i];
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = pack2(lo16(a[e]) + lo16(b[e]), hi16(a[e]) + hi16(b[e]));
+        y[i] = o;
+    }
+}
+
+static unsigned stream_blocks(size_t n16) {
+    size_t blocks = (n16 + 255) / 256;
+    return (unsigned)(blocks > 256 * 16 ? 256 * 16 : blocks);
+}
+
+}  // namespace ops
+
+const char *bn_train_check(const void *x, const void *y, const float *gamma, const float *beta, long long M, int C,
+                           int bf16) {
+    if (!bf16) return "batch normalisation with batch statistics is bf16 only";
+    if (M <= 0 || C <= 0 || C % 8 || C > 8192) return "channels must be a multiple of 8, at most 8192";
+    if (!x || !y || !gamma || !beta || (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta) & 15))
+        return "pointers must be non-null and 16-byte aligned";
+    return nullptr;
+}
+
+size_t bn_train_scratch_bytes() { return (size_t)16 << 20; }     // partial sums + the 2 x C factors
+
+// scratch: device, bn_train_scratch_bytes() bytes, 16-byte aligned.
+hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const float *beta, long long M, int C, float eps,
+                           int bf16, void *scratch, hipStream_t stream) {
+    if (bn_train_check(x, y, gamma, beta, M, C, bf16) || !scratch || ((uintptr_t)scratch & 15)) return hipErrorInvalidValue;
+    const int chunks = C / 8;
+    const int CH = chunks < 256 ? chunks : 256;
+    const int RS = 256 / CH;
+    float *ab = static_cast<float *>(scratch);                   // [2][C]
+    float *partial = ab + 2 * (size_t)C;
+    const size_t room = (bn_train_scratch_bytes() - 2 * (size_t)C * 4) / ((size_t)2 * C * 4);
+    long long blocks = (M + (long long)RS * 4 - 1) / ((long long)RS * 4);    // at least 4 rows per lane
+    if (blocks > 2048) blocks = 2048;
+    if (blocks > (long long)room) blocks = (long long)room;
+    if (blocks < 1) return hipErrorInvalidValue;
+    const long long rpb = (M + blocks - 1) / blocks;
+    blocks = (M + rpb - 1) / rpb;
+    const size_t lds = (size_t)RS * CH * 16 * 4;
+    ops::bn_stats_kernel<<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(static_cast<const unsigned char *>(x), partial,
+                                                                            M, C, rpb, CH, RS);
+    ops::bn_finalize_kernel<<<dim3((unsigned)((C + 63) / 64)), dim3(1024), 0, stream>>>(
+        static_cast<const unsigned char *>(x), partial, gamma, beta, ab, M, C, (int)blocks, eps);
+    const size_t n16 = (size_t)M * chunks;
+    ops::bn_apply_kernel<<<dim3(ops::stream_blocks(n16)), dim3(256), 0, stream>>>(
+        static_cast<const ops::u32x4 *>(x), static_cast<ops::u32x4 *>(y), ab, beta, C, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_relu(const void *x, void *y, size_t bytes, int bf16, hipStream_t stream) {
+    if (!bf16 || !x || !y || bytes % 16 || (((uintptr_t)x | (uintptr_t)y) & 15)) return hipErrorInvalidValue;
+    if (bytes == 0) return hipSuccess;
+    ops::relu_kernel<<<dim3(ops::stream_blocks(bytes / 16)), dim3(256), 0, stream>>>(
+        static_cast<const ops::u32x4 *>(x), static_cast<ops::u32x4 *>(y), bytes / 16);
+    return hipGetLastError();
+}
+
+hipError_t launch_add(const void *x, const void *r, void *y, size_t bytes, int bf16, hipStream_t stream) {
+    if (!bf16 || !x || !r || !y || bytes % 16 || (((uintptr_t)x | (uintptr_t)r | (uintptr_t)y) & 15)) return hipErrorInvalidValue;
+    if (bytes == 0) return hipSuccess;
+    ops::add_kernel<<<dim3(ops::stream_blocks(bytes / 16)), dim3(256), 0, stream>>>(
+        static_cast<const ops::u32x4 *>(x), static_cast<const ops::u32x4 *>(r), static_cast<ops::u32x4 *>(y), bytes / 16);
+    return hipGetLastError();
+}
+
+}  // namespace delta

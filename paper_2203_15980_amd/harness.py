@@ -399,3 +399,137 @@ def run_plan(net, graph, events, backward_proxy=None):
             backward_proxy(k)
         for t in post:
             d.release(t, B.EV_FREE)
+
+
+class OpNet:
+    """A ResNet at OPERATOR granularity (synth.opgranular_graph): convolution, batch normalisation
+    with the statistics of the batch, residual add and ReLU are separate launches and separate
+    tensors (bf16).  Same interface as Net towards run_plan (delta, desc, sources, load_source).
+    There are no backward kernels at this granularity: a backward step runs the compute proxy
+    (the operator's forward kernel twice into a scratch tensor) where the access trace gives it
+    its input, and nothing for the operators whose backward reads no activation (add, average
+    pool) or for the loss."""
+
+    def __init__(self, delta, layers, master, device="cuda:0", with_loss=True):
+        self.delta, self.layers, self.master, self.device = delta, layers, master, device
+        self.dtype, self.es = "bf16", 2
+        self.graph = g = synth.opgranular_graph(layers, "bf16", with_loss=with_loss)
+        self.ids = dict(g.names)
+        self.sizes = [t["bytes"] for t in g.tensors]
+        self.params_np, self.keep, self.desc, self.shapes, self.np_dtype, self.sources = {}, [], {}, {}, {}, {}
+        first = layers[0]
+        code = B.DTYPE_BF16
+        self.x0_np = synth.make_input(master, (first.N, first.H, first.W, first.Cin), "bf16")
+        self.shapes["x0"], self.np_dtype["x0"] = self.x0_np.shape, np.uint16
+        self.sources[0] = _dev(self.x0_np.view(np.uint8).reshape(-1), device)
+        cmax = max(l.Cout for l in layers)
+        ones = torch.ones(cmax, dtype=torch.float32, device=device)
+        zeros = torch.zeros(cmax, dtype=torch.float32, device=device)
+        self.keep += [ones, zeros]
+        self.op_names = []                        # in production order
+        self.proxy_src = {}                       # op tensor -> the tensor its proxy reads (None: no proxy)
+        alias = {"x0": "x0"}
+
+        def emit(name, shape, proxy_x, **kw):
+            self.desc[name] = B.layer_array([B.LayerDesc(y=self.ids[name], dtype=code, **kw)])
+            self.shapes[name], self.np_dtype[name] = shape, np.uint16
+            self.op_names.append(name)
+            self.proxy_src[name] = proxy_x
+
+        for l in layers:
+            xin = alias[l.x]
+            geo = dict(N=l.N, H=l.H, W=l.W, Cin=l.Cin, Cout=l.Cout, R=l.R, S=l.S, stride=l.stride, pad=l.pad)
+            oshape = (l.N, l.P, l.Q, l.Cout)
+            same = dict(N=l.N, H=l.P, W=l.Q, Cin=l.Cout, Cout=l.Cout, R=1, S=1, stride=1, pad=0)
+            if l.kind == "conv":
+                p = synth.make_params(master, l, "bf16")
+                self.params_np[l.name] = p
+                w, gamma, beta = _dev(p["w"], device), _dev(p["gamma"], device), _dev(p["beta"], device)
+                self.keep += [w, gamma, beta]
+                t = l.name + ".conv"
+                emit(t, oshape, xin, x=self.ids[xin], res=B.NO_TENSOR, w=w.data_ptr(), scale=ones.data_ptr(),
+                     shift=zeros.data_ptr(), relu=0, op=B.OP_CONV, **geo)
+                emit(l.name + ".bn", oshape, t, x=self.ids[t], res=B.NO_TENSOR, w=None, scale=gamma.data_ptr(),
+                     shift=beta.data_ptr(), relu=0, op=B.OP_BATCHNORM, eps=float(p["eps"]), **same)
+                t = l.name + ".bn"
+                if l.res:
+                    emit(l.name + ".add", oshape, None, x=self.ids[t], res=self.ids[alias[l.res]], w=None, scale=None,
+                         shift=None, relu=0, op=B.OP_ADD, **same)
+                    t = l.name + ".add"
+                if l.relu:
+                    emit(l.name + ".relu", oshape, l.name + ".relu", x=self.ids[t], res=B.NO_TENSOR, w=None, scale=None,
+                         shift=None, relu=0, op=B.OP_RELU, **same)
+                    t = l.name + ".relu"
+            elif l.kind in ("maxpool", "avgpool"):
+                t = l.name
+                emit(t, oshape, xin if l.kind == "maxpool" else None, x=self.ids[xin], res=B.NO_TENSOR, w=None, scale=None,
+                     shift=None, relu=0, op=_OPS[l.kind], **geo)
+            elif l.kind == "fc":
+                p = synth.make_params(master, l, "bf16")
+                self.params_np[l.name] = p
+                w, bias = _dev(p["w"], device), _dev(p["bias"], device)
+                self.keep += [w, bias]
+                t = l.name
+                emit(t, oshape, xin, x=self.ids[xin], res=B.NO_TENSOR, w=w.data_ptr(), scale=ones.data_ptr(),
+                     shift=bias.data_ptr(), relu=0, op=B.OP_CONV, **geo)
+            else:
+                raise ValueError("layer kind %r has no operator-granular form" % l.kind)
+            alias[l.y] = t
+        self.alias = alias
+        self.with_loss = with_loss
+        if with_loss:
+            last = layers[-1]
+            self.labels_np = synth.make_labels(master, last.N, last.Cout)
+            self.sources[self.ids["labels"]] = _dev(self.labels_np.view(np.uint8).reshape(-1), device)
+            self.shapes["labels"], self.np_dtype["labels"] = (last.N,), np.int64
+            d = B.LayerDesc(x=self.ids[alias[last.y]], res=self.ids["labels"], y=self.ids["loss"], dtype=code,
+                            w=None, scale=None, shift=None, N=last.N, H=1, W=1, Cin=last.Cout, Cout=1,
+                            R=1, S=1, stride=1, pad=0, relu=0, op=B.OP_SOFTMAX_CE)
+            self.desc["loss"] = B.layer_array([d])
+            self.shapes["loss"], self.np_dtype["loss"] = (1,), np.float32
+        self.all_ops = B.layer_array([self.desc[n][0] for n in self.op_names])
+        torch.cuda.synchronize()
+
+    _view = Net._view
+    read = Net.read
+    load_source = Net.load_source
+    rebind = Net.rebind
+
+    def forward(self):
+        self.load_source(0)
+        self.delta.recompute_segment(self.all_ops)
+        if self.with_loss:
+            self.load_source(self.ids["labels"])
+            self.delta.recompute_segment(self.desc["loss"])
+
+    def enable_backward_proxy(self):
+        """Adds one scratch tensor per output size (re-binds: call while nothing is resident)."""
+        n_graph = len(self.sizes)
+        scratch, extra, self.proxy_desc = {}, [], {}
+        for name in self.op_names:
+            src = self.proxy_src[name]
+            if src is None:
+                continue
+            nbytes = self.sizes[self.ids[name]]
+            if nbytes not in scratch:
+                scratch[nbytes] = n_graph + len(extra)
+                extra.append(nbytes)
+            dsc = B.LayerDesc.from_buffer_copy(self.desc[name][0])
+            dsc.x, dsc.y = self.ids[src], scratch[nbytes]
+            self.proxy_desc[name] = (B.layer_array([dsc]), scratch[nbytes])
+        self.sizes = self.sizes + extra
+        self.delta.bind(self.sizes)
+
+    def backward_proxy_step(self, graph, k):
+        j = k - graph.n_fwd
+        if self.with_loss:
+            if j == 0:
+                return                            # the loss's backward: one tiny kernel, not modelled
+            j -= 1
+        name = self.op_names[len(self.op_names) - 1 - j]
+        if name not in self.proxy_desc:
+            return
+        arr, sid = self.proxy_desc[name]
+        self.delta.recompute_segment(arr)
+        self.delta.recompute_segment(arr)
+        self.delta.release(sid, B.EV_FREE)

@@ -244,9 +244,9 @@ def fused_graph(layers: List[LayerSpec], dtype, with_loss=False, costs=None) -> 
     return g
 
 
-def opgranular_graph(layers: List[LayerSpec], dtype, with_loss=True) -> Graph:
-    """Planner-only variant at operator granularity: convolution, batch-norm, residual add
-    and ReLU outputs are separate tensors (about 160 for ResNet-50)."""
+def opgranular_graph(layers: List[LayerSpec], dtype, with_loss=True, costs=None) -> Graph:
+    """Operator granularity: convolution, batch-norm, residual add and ReLU outputs are separate
+    tensors (about 177 for ResNet-50).  `costs` optionally maps tensor name -> measured ns."""
     g = Graph()
     es = _esize(dtype)
     first = layers[0]
@@ -256,7 +256,7 @@ def opgranular_graph(layers: List[LayerSpec], dtype, with_loss=True) -> Graph:
     bwd = []
 
     def emit(name, nbytes, flops, traffic, parents, bwd_reads):
-        c = cost_model_ns(flops, traffic)
+        c = costs[name] if costs and name in costs else cost_model_ns(flops, traffic)
         t = g.add_tensor(name, nbytes, c, flops, 0, parents)
         g.add_fwd(t, parents, c)
         bwd.append((bwd_reads, 2 * c))
