@@ -1,0 +1,317 @@
+// y[M, N] = act(scale_n * (x[M, K] . w[N, K]^T) + shift_n (+ res)) (* [mask > 0]) for gfx950, bf16.
+//
+// The dense layers of a recomputation segment whose reduction axis is long: the linear layers of a
+// transformer encoder (the paper's BERT-base workload, Sec. 5.2) and the 1x1 stride-1 convolutions
+// with many input channels - both are plain "NT" GEMMs (both operands contiguous along K), bound
+// by the matrix cores.  The tiled convolution kernel treats them as a convolution (64 x 64 tiles
+// per wavefront, slices staged through registers); this kernel is built for the GEMM:
+//  * workgroup tile 256 x 256 (8 wavefronts as 2 x 4) or 256 x 192 (6 wavefronts), 128 x 64 per
+//    wavefront: 6 operand reads feed 8 MFMAs (32x32x16) per k-step, against 4 for 4; the width is
+//    the one that leaves fewer CUs idle (768 output channels: 4 tiles of 192 fill the chip at
+//    16384 rows, 3 tiles of 256 leave a quarter of it idle);
+//  * K slices of 32 go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+//    no registers, no LDS store instructions) through FOUR buffers of 32 KB: a slice is requested
+//    three slices (>= 3000 cycles of MFMA work per SIMD) before it is multiplied - with two buffers
+//    of 64 the memory latency (about 2 us under load) was longer than a slice's arithmetic and the
+//    kernel ran no faster than the convolution kernel; one barrier per slice, and the wait before
+//    it is for the oldest slice only (vmcnt counts the younger loads);
+//  * a tile row is 64 bytes = 4 pieces of 16; piece p of row r lives in slot p ^ ((r >> 2) & 3):
+//    the direct loads fix where a LANE's 16 bytes land, so the swizzle is applied to the global
+//    address each lane fetches; 16 lanes reading one piece of 16 consecutive rows then touch all
+//    64 banks once;
+//  * workgroups are numbered so that each XCD (blockIdx % 8) walks a contiguous range of x-row
+//    tiles with all their w tiles: x rows and the whole of w stay in that XCD's L2;
+//  * epilogue as in the convolution kernels: scale/shift in the accumulator layout, a
+//    wavefront-private fp32 tile in LDS turns channel-major accumulators into 128-byte pixel rows,
+//    residual, activation (none / ReLU / GELU), optional mask, one rounding.
+// Rows past M or N are fetched from the last valid row (never stored).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.hpp"
+
+namespace delta {
+namespace gemm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+static constexpr int kBM = 256, kBK = 32, kStages = 4;
+static constexpr int kWM = 2;                                           // wavefront rows: 128 rows of x each
+static constexpr int kTM = 4, kTN = 2;                                  // 4 x 2 tiles of 32 x 32 per wavefront (128 x 64)
+static constexpr int kXBytes = kBM * kBK * 2;                           // 16 KB of x per buffer
+static constexpr int kStgPitch = 64 * 4 + 16;                          // fp32 staging row: 64 channels + pad
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float lo16(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float hi16(uint32_t p) { return __uint_as_float(p & 0xFFFF0000u); }
+
+__device__ __forceinline__ void wave_lds_fence() {
+    // LDS instructions of one wavefront execute in order; this only stops the compiler from moving
+    // accesses across the point where lanes exchange data through LDS.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float gelu_erf(float v) {     // v/2 (1 + erf(v / sqrt 2)); see conv_igemm.hip
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float c = poly * __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
+    return 0.5f * v * (v < 0.f ? c : 2.0f - c);
+}
+
+// BN: rows of w (output channels) per workgroup, 256 or 192; BN / 64 wavefront columns.
+template <int BN>
+__global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs a, int tiles_n, int tiles_total) {
+    constexpr int kBN = BN, kWN = BN / 64, kWaves = kWM * kWN;
+    constexpr int kStageBytes = kXBytes + BN * kBK * 2;
+    constexpr int XI = (kBM / 16 + kWaves - 1) / kWaves, WI = (BN / 16 + kWaves - 1) / kWaves;   // direct loads per wavefront and slice
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wv / kWN, wn = wv % kWN;
+    const int M = a.M, N = a.Cout, K = a.Cin;
+    // XCD-aware numbering: XCD x (= blockIdx % 8) takes logical tiles x * per .. (x + 1) * per
+    const int per = (tiles_total + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    if (logical >= tiles_total) return;
+    const int m0 = (logical / tiles_n) * kBM, n0 = (logical % tiles_n) * kBN;
+
+    // ---- direct loads: one instruction fills 16 tile rows (1 KB); per slice a wavefront issues XI for
+    // x and WI for w (when the rows do not divide evenly the last wavefronts repeat a neighbour's rows:
+    // every wavefront must issue the same number, the waits below count them)
+    const unsigned char *xg = static_cast<const unsigned char *>(a.x);
+    const unsigned char *wg = static_cast<const unsigned char *>(a.w);
+    const size_t krow = (size_t)K * 2;
+    const unsigned char *xsrc[XI], *wsrc[WI];
+    uint32_t xdst[XI], wdst[WI];
+#pragma unroll
+    for (int q = 0; q < XI; ++q) {
+        int g = wv * XI + q;
+        g = g < kBM / 16 ? g : kBM / 16 - 1;
+        const int r = 16 * g + (lane >> 2);                             // row of the tile this lane fills
+        const int piece = (lane & 3) ^ ((r >> 2) & 3);                 // which 16 bytes of the row land in this lane's slot
+        int xr = m0 + r;
+        xr = xr < M ? xr : M - 1;
+        xsrc[q] = xg + (size_t)xr * krow + piece * 16;
+        xdst[q] = (uint32_t)g * 1024u;
+    }
+#pragma unroll
+    for (int q = 0; q < WI; ++q) {
+        int g = wv * WI + q;
+        g = g < BN / 16 ? g : BN / 16 - 1;
+        const int r = 16 * g + (lane >> 2);
+        const int piece = (lane & 3) ^ ((r >> 2) & 3);
+        int wr = n0 + r;
+        wr = wr < N ? wr : N - 1;
+        wsrc[q] = wg + (size_t)wr * krow + piece * 16;
+        wdst[q] = (uint32_t)kXBytes + (uint32_t)g * 1024u;
+    }
+    // The direct loads and the waits for them are written as inline assembly: through the builtin
+    // the compiler, which cannot tell the four buffers apart, waits for ALL outstanding direct loads
+    // (vmcnt(0)) before every barrier, i.e. for the slice requested a moment ago, and the deep
+    // pipeline is gone.  Loads return in order, so "at most 8 outstanding" means the oldest slice is in.
+    typedef __attribute__((address_space(3))) unsigned char *lptr_t;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+    const int nslices = K / kBK;
+    auto fetch = [&](int t, int buf) {           // t past the end: the last slice again (keeps the load count uniform)
+        t = t < nslices ? t : nslices - 1;
+        const uint32_t sb = lds0 + (uint32_t)buf * kStageBytes;
+#pragma unroll
+        for (int q = 0; q < XI; ++q)
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                         :: "v"(xsrc[q] + (size_t)t * 64), "s"(__builtin_amdgcn_readfirstlane(sb + xdst[q])) : "memory", "m0");
+#pragma unroll
+        for (int q = 0; q < WI; ++q)
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                         :: "v"(wsrc[q] + (size_t)t * 64), "s"(__builtin_amdgcn_readfirstlane(sb + wdst[q])) : "memory", "m0");
+    };
+    // "at most 2 slices' worth outstanding": the oldest slice is in
+    auto wait_oldest = [&]() {
+        if constexpr (2 * (XI + WI) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if constexpr (2 * (XI + WI) == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+
+    f32x16 acc[kTM][kTN];
+#pragma unroll
+    for (int i = 0; i < kTM; ++i)
+#pragma unroll
+        for (int j = 0; j < kTN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // operand reads: row (tile row of this lane), piece 2 * k2 + half, swizzled
+    int xoff[kTM], woff[kTN], xsw[kTM], wsw[kTN];
+#pragma unroll
+    for (int i = 0; i < kTM; ++i) {
+        const int r = wm * 128 + i * 32 + l32;
+        xoff[i] = r * 64;
+        xsw[i] = (r >> 2) & 3;
+    }
+#pragma unroll
+    for (int j = 0; j < kTN; ++j) {
+        const int r = wn * 64 + j * 32 + l32;
+        woff[j] = kXBytes + r * 64;
+        wsw[j] = (r >> 2) & 3;
+    }
+
+    fetch(0, 0);
+    fetch(1, 1);
+    fetch(2, 2);
+    wait_oldest();
+    __syncthreads();
+    for (int t = 0; t < nslices; ++t) {
+        const int buf = t % kStages;
+        fetch(t + 3, (t + 3) % kStages);           // into the buffer that slice t - 1 has just left
+        const unsigned char *base = smem + (size_t)buf * kStageBytes;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            bf16x8 xf[kTM], wf[kTN];
+#pragma unroll
+            for (int i = 0; i < kTM; ++i)
+                xf[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + xoff[i] + (((2 * k2 + half) ^ xsw[i]) << 4)));
+#pragma unroll
+            for (int j = 0; j < kTN; ++j)
+                wf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + woff[j] + (((2 * k2 + half) ^ wsw[j]) << 4)));
+#pragma unroll
+            for (int i = 0; i < kTM; ++i)
+#pragma unroll
+                for (int j = 0; j < kTN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+        }
+        wait_oldest();                             // this wavefront's loads of slice t + 1 have landed
+        __syncthreads();                           // everyone's have, and everyone is done reading buffer `buf`
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the surplus loads of the last rounds ...
+    __syncthreads();                               // ... of every wavefront, before LDS becomes staging space
+
+    // ---- epilogue.  acc[i][j]: lane holds pixel (x row) l32 of tile i and channels 8*rb + 4*half + e of tile j
+    unsigned char *stg = smem + (size_t)wv * (32 * kStgPitch);
+    unsigned char *yg = static_cast<unsigned char *>(a.y);
+    const unsigned char *rg = static_cast<const unsigned char *>(a.res);
+    const unsigned char *mg = static_cast<const unsigned char *>(a.mask);
+    const int prow = lane >> 3, cseg = lane & 7;
+    f32x4 sc[kTN][4], sh[kTN][4];
+#pragma unroll
+    for (int j = 0; j < kTN; ++j)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            int ch = n0 + wn * 64 + j * 32 + 8 * rb + 4 * half;
+            ch = ch + 4 <= N ? ch : 0;              // N is a multiple of 8: a group of 4 is inside or outside
+            sc[j][rb] = *reinterpret_cast<const f32x4 *>(a.scale + ch);
+            sh[j][rb] = *reinterpret_cast<const f32x4 *>(a.shift + ch);
+        }
+    const int chan = n0 + wn * 64 + cseg * 8;
+#pragma unroll
+    for (int i = 0; i < kTM; ++i) {
+        wave_lds_fence();
+#pragma unroll
+        for (int j = 0; j < kTN; ++j)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const f32x16 &c = acc[i][j];
+                f32x4 v;
+                v.x = c[4 * rb + 0] * sc[j][rb].x + sh[j][rb].x;
+                v.y = c[4 * rb + 1] * sc[j][rb].y + sh[j][rb].y;
+                v.z = c[4 * rb + 2] * sc[j][rb].z + sh[j][rb].z;
+                v.w = c[4 * rb + 3] * sc[j][rb].w + sh[j][rb].w;
+                *reinterpret_cast<f32x4 *>(stg + l32 * kStgPitch + (j * 32 + 8 * rb + 4 * half) * 4) = v;
+            }
+        wave_lds_fence();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int pr = prow + 8 * t;
+            const int m = m0 + wm * 128 + i * 32 + pr;
+            if (m >= M || chan >= N) continue;
+            const f32x4 f0 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32);
+            const f32x4 f1 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32 + 16);
+            float v[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+            const size_t off = ((size_t)m * N + chan) * 2;
+            if (rg) {
+                const u32x4 rv = *reinterpret_cast<const u32x4 *>(rg + off);
+                v[0] += lo16(rv.x); v[1] += hi16(rv.x); v[2] += lo16(rv.y); v[3] += hi16(rv.y);
+                v[4] += lo16(rv.z); v[5] += hi16(rv.z); v[6] += lo16(rv.w); v[7] += hi16(rv.w);
+            }
+            if (a.relu == 1) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = v[e] < 0.f ? 0.f : v[e];
+            } else if (a.relu == 2) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
+            }
+            u32x4 o;
+            o.x = pack2(v[0], v[1]); o.y = pack2(v[2], v[3]); o.z = pack2(v[4], v[5]); o.w = pack2(v[6], v[7]);
+            if (mg) {
+                const u32x4 mv = *reinterpret_cast<const u32x4 *>(mg + off);
+                o.x = keep_where_positive_bf16(o.x, mv.x); o.y = keep_where_positive_bf16(o.y, mv.y);
+                o.z = keep_where_positive_bf16(o.z, mv.z); o.w = keep_where_positive_bf16(o.w, mv.w);
+            }
+            *reinterpret_cast<u32x4 *>(yg + off) = o;
+        }
+    }
+}
+
+}  // namespace gemm
+
+namespace {
+
+// Width of the w tile: the one whose number of rounds over the 256 CUs (one workgroup per CU) times
+// its cost per tile is smaller; e.g. 768 output channels are 3 tiles of 256 (192 workgroups at
+// batch 32 x 512: a quarter of the chip idle) but 4 tiles of 192 (256 workgroups, one full round).
+int pick_bn(const ConvArgs &a) {
+    const long long tiles_m = ((long long)a.M + gemm::kBM - 1) / gemm::kBM;
+    long long best_cost = -1;
+    int best = 256;
+    for (int bn : {256, 192}) {
+        const long long tiles = tiles_m * ((a.Cout + bn - 1) / bn);
+        const long long cost = ((tiles + 255) / 256) * bn;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = bn; }
+    }
+    return best;
+}
+
+template <int BN>
+hipError_t launch_bn(const ConvArgs &a, hipStream_t stream) {
+    constexpr size_t lds = (size_t)gemm::kStages * (gemm::kXBytes + BN * gemm::kBK * 2);
+    constexpr int threads = gemm::kWM * (BN / 64) * 64;
+    const int tiles_m = (a.M + gemm::kBM - 1) / gemm::kBM, tiles_n = (a.Cout + BN - 1) / BN;
+    const long long total = (long long)tiles_m * tiles_n;
+    const long long blocks = (total + 7) / 8 * 8;
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm::gemm_nt_kernel<BN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    gemm::gemm_nt_kernel<BN><<<dim3((unsigned)blocks), dim3(threads), lds, stream>>>(a, tiles_n, (int)total);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// bf16 1x1 stride-1 layers (rows of x contiguous) with a reduction axis of at least 256 and enough
+// output to fill the chip with 256-row tiles.
+bool gemm_nt_applies(const ConvArgs &a) {
+    if (!a.bf16 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0) return false;
+    if (a.Cin % 64 || a.Cin < 256 || a.Cout % 8 || a.Cout < 192) return false;
+    const long long tiles = (((long long)a.M + gemm::kBM - 1) / gemm::kBM) * ((a.Cout + 255) / 256);
+    return tiles >= 128 && tiles <= 0x3FFFFFF0LL;
+}
+
+hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream) {
+    if (conv_check(a) || !gemm_nt_applies(a)) return hipErrorInvalidValue;
+    return pick_bn(a) == 192 ? launch_bn<192>(a, stream) : launch_bn<256>(a, stream);
+}
+
+}  // namespace delta

@@ -112,7 +112,11 @@ def test_layernorm_matches_oracle(torch_mod, rows, C):
 
 
 @pytest.mark.parametrize("case", [("gelu", 2, 70, 128, 192, "gelu", False), ("res", 1, 45, 768, 64, None, True),
-                                  ("ffn2", 1, 40, 512, 128, None, True), ("plain", 3, 33, 64, 256, None, False)],
+                                  ("ffn2", 1, 40, 512, 128, None, True), ("plain", 3, 33, 64, 256, None, False),
+                                  # large enough for the 256 x 256-tiled GEMM kernel; ragged rows and channels
+                                  ("gemm_gelu", 1, 8465, 256, 1024, "gelu", False),
+                                  ("gemm_res_ragged_n", 1, 8300, 768, 776, None, True),
+                                  ("gemm_one_column_of_tiles", 1, 32800, 256, 256, "relu", False)],
                          ids=lambda c: c[0])
 def test_linear_layers_match_oracle(torch_mod, case):
     torch = torch_mod
@@ -124,14 +128,15 @@ def test_linear_layers_match_oracle(torch_mod, case):
     w = _bits(63, 2, (Cout, Cin), 1.0 / np.sqrt(Cin) * 1.5)
     bias = synth.normal(63, 3, Cout, 0.0, 0.5).astype(np.float32)
     res = _bits(63, 4, (M, Cout)) if has_res else None
-    d, put, get = _ctx(torch, [x.nbytes, M * Cout * 2, M * Cout * 2], 16)
+    d, put, get = _ctx(torch, [x.nbytes, M * Cout * 2, M * Cout * 2], 96)
     put(0, x)
     if has_res:
         put(1, res)
     wd, ones, bd = _dev(torch, w), torch.ones(Cout, dtype=torch.float32, device="cuda:0"), _dev(torch, bias)
     desc = dl.LayerDesc(x=0, res=1 if has_res else dl.NO_TENSOR, y=2, dtype=dl.DTYPE_BF16, w=wd.data_ptr(),
                         scale=ones.data_ptr(), shift=bd.data_ptr(), N=N, H=S, W=1, Cin=Cin, Cout=Cout, R=1, S=1,
-                        stride=1, pad=0, relu=dl.ACT_GELU if act == "gelu" else dl.ACT_NONE, op=dl.OP_CONV)
+                        stride=1, pad=0, relu={"gelu": dl.ACT_GELU, "relu": dl.ACT_RELU, None: dl.ACT_NONE}[act], op=dl.OP_CONV)
+    assert ("gemm_nt" in d.layer_kernel(desc)) == name.startswith("gemm"), d.layer_kernel(desc)
     d.recompute_segment([desc])
     d.sync()
     got = ot.to_f64(get(2, (M, Cout)), "bf16")
