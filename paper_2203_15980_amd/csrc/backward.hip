@@ -499,6 +499,7 @@ const char *wgrad_plan(const ConvArgs &a, WgradPlan &p) {
     else {
         p.ktw = a.Cout % 256 == 0 ? 4 : (a.Cout % 128 == 0 ? 2 : 1);
         p.ctw = 1;
+        // (256 x 128 tiles with 8 wavefronts measured 2-3 % slower on ResNet-50's stage 4/5 layers)
         if (p.ktw == 1) p.ctw = a.Cin % 256 == 0 ? 4 : (a.Cin % 128 == 0 ? 2 : 1);
         else if (p.ktw == 2) p.ctw = a.Cin % 128 == 0 ? 2 : 1;
     }
