@@ -10,8 +10,10 @@
 // [64h, 64h+64) of each (d = 64).  ctx [N, S, H] bf16.
 //
 // A workgroup (8 wavefronts) takes one (image, head) and a block of 256 queries; a wavefront owns
-// 32 queries.  K and V of the head - up to 512 keys at a time - are staged in LDS once per
-// workgroup.  Everything is computed TRANSPOSED so that a lane owns one query:
+// 32 queries.  K and V of the head stream through LDS in blocks of 128 keys, two buffers; block
+// b + 1 waits in registers (requested a block earlier) while block b is multiplied, so only the
+// first block's latency is exposed (staging all 512 keys up front cost 20 of 68 us at batch 32 x
+// 512).  Everything is computed TRANSPOSED so that a lane owns one query:
 //   S^T tile (32 keys x 32 queries) = K tile . Q^T        A = K rows from LDS (b128), B = Q from registers
 //   lane l holds query l % 32 and keys 8*e4 + 4*(l/32) + e of the tile: the softmax statistics of
 //   a query (running maximum, running sum) are per-lane scalars; the two half-waves see disjoint
@@ -21,7 +23,8 @@
 //   accumulators rounded to bf16: accumulator registers (e4 in {2j, 2j+1}) of a lane are exactly
 //   the 8 reduction slots of step j, if the A operand enumerates the keys in the same order
 //   (keys 16j + 4*(l/32) + e and 16j + 8 + 4*(l/32) + e) - the order of a reduction is free.
-// Online softmax over chunks of 128 keys (fp32; exp2 with the scale folded in).  P is rounded to
+// Online softmax over the 128-key blocks (fp32; the maximum is taken of the raw scores, the scale
+// and the subtraction are one fma in front of exp2).  P is rounded to
 // bf16 before it multiplies V (the only rounding besides the output's).
 // Keys >= S are masked to -inf (their K/V rows in LDS are zeros); query rows >= S are computed on
 // a clamped row and not stored.
@@ -42,10 +45,11 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 static constexpr int kD = 64;                    // head dimension
-static constexpr int kWaves = 8, kQB = kWaves * 32;   // queries per workgroup
-static constexpr int kChunk = 128;               // keys per online-softmax step
-static constexpr int kMaxKeys = 512;             // keys staged at once
+static constexpr int kChunk = 128;               // keys per block (one online-softmax step)
+static constexpr int kWaves = 8, kQB = kWaves * 32;   // queries per workgroup (4 wavefronts, two workgroups per CU: 4 % slower)
+static constexpr int kPieces = kChunk * 8 / (kWaves * 64);   // 16-byte pieces of K (and of V) per thread and block
 static constexpr int kPitch = kD * 2 + 16;       // LDS row pitch in bytes (144: conflict-free b128 rows)
+static constexpr int kBufBytes = 2 * kChunk * kPitch;   // K and V of one block of 128 keys: 36 KB
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     const f32x2 v = {lo, hi};
@@ -56,14 +60,11 @@ struct AttnArgs {
     const unsigned char *qkv;
     unsigned char *ctx;
     int N, S, heads;
-    int keys_alloc;                              // LDS rows per operand: multiple of kChunk, <= kMaxKeys
     float scale_log2e;                           // log2(e) / sqrt(d)
 };
 
 __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *ks = smem;
-    unsigned char *vs = smem + (size_t)a.keys_alloc * kPitch;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int qblocks = (a.S + kQB - 1) / kQB;
@@ -98,70 +99,92 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
     typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
     auto tr_read = [&](const unsigned char *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p)); };
 
-    for (int kb0 = 0; kb0 < a.S; kb0 += a.keys_alloc) {
-        if (kb0) __syncthreads();                // every wavefront is done with the previous block
-        // ---- stage K and V rows kb0 .. kb0 + keys_alloc (zeros past S): 8 lanes per 128-byte row
-        for (int i = tid; i < a.keys_alloc * 8; i += kWaves * 64) {
-            const int r = i >> 3, seg = i & 7;
-            u32x4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-            if (kb0 + r < a.S) {
-                const unsigned char *p = base + (size_t)(kb0 + r) * row_bytes + seg * 16;
-                kv = *reinterpret_cast<const u32x4 *>(p + (size_t)H * 2);
-                vv = *reinterpret_cast<const u32x4 *>(p + (size_t)H * 4);
+    // ---- K/V blocks of 128 keys move global -> registers -> LDS one block ahead of the arithmetic:
+    // while block b is multiplied out of buffer b % 2, block b + 1 sits in registers (requested a
+    // whole block earlier) and is stored into the other buffer at the start of the next round.
+    // 128 rows x 8 pieces x 2 operands / 512 threads = 4 pieces per thread.
+    const int nblocks = (a.S + kChunk - 1) / kChunk;
+    u32x4 rk[kPieces], rv[kPieces];
+    auto fetch = [&](int blk) {                  // rows past S (or blocks past the end): zeros
+#pragma unroll
+        for (int p = 0; p < kPieces; ++p) {
+            const int i = tid + p * (kWaves * 64);
+            const int r = blk * kChunk + (i >> 3), seg = i & 7;
+            rk[p] = u32x4{0u, 0u, 0u, 0u};
+            rv[p] = u32x4{0u, 0u, 0u, 0u};
+            if (r < a.S) {
+                const unsigned char *src = base + (size_t)r * row_bytes + seg * 16;
+                rk[p] = *reinterpret_cast<const u32x4 *>(src + (size_t)H * 2);
+                rv[p] = *reinterpret_cast<const u32x4 *>(src + (size_t)H * 4);
             }
-            *reinterpret_cast<u32x4 *>(ks + (size_t)r * kPitch + seg * 16) = kv;
-            *reinterpret_cast<u32x4 *>(vs + (size_t)r * kPitch + seg * 16) = vv;
         }
-        __syncthreads();
-        const int kend = a.S - kb0 < a.keys_alloc ? a.S - kb0 : a.keys_alloc;   // valid keys in this block
-        for (int c0 = 0; c0 < kend; c0 += kChunk) {
+    };
+    auto stage = [&](int buf) {
+        unsigned char *kb = smem + (size_t)buf * kBufBytes, *vb = kb + kChunk * kPitch;
+#pragma unroll
+        for (int p = 0; p < kPieces; ++p) {
+            const int i = tid + p * (kWaves * 64);
+            *reinterpret_cast<u32x4 *>(kb + (size_t)(i >> 3) * kPitch + (i & 7) * 16) = rk[p];
+            *reinterpret_cast<u32x4 *>(vb + (size_t)(i >> 3) * kPitch + (i & 7) * 16) = rv[p];
+        }
+    };
+    fetch(0);
+    stage(0);
+    fetch(1);
+    __syncthreads();
+    for (int blk = 0; blk < nblocks; ++blk) {
+        if (blk + 1 < nblocks) stage((blk + 1) & 1);      // that buffer's last readers passed the barrier below
+        fetch(blk + 2);
+        const unsigned char *ks = smem + (size_t)(blk & 1) * kBufBytes, *vs = ks + kChunk * kPitch;
+        const int kend = a.S - blk * kChunk;              // valid keys in this block (>= 1)
+        {
             // ---- S^T for 128 keys: 4 tiles of 32 keys x 32 queries
             f32x16 s[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) s[t][e] = 0.f;
-                const unsigned char *krow = ks + (size_t)(c0 + 32 * t + l32) * kPitch + half * 16;
+                const unsigned char *krow = ks + (size_t)(32 * t + l32) * kPitch + half * 16;
 #pragma unroll
                 for (int k4 = 0; k4 < 4; ++k4) {
                     const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(krow + k4 * 32));
                     s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[k4], s[t], 0, 0, 0);
                 }
             }
-            // ---- scale, mask, running maximum
-            const bool ragged = c0 + kChunk > kend;
+            // ---- mask, running maximum (of the raw scores: the scale is positive)
             float mx = -INFINITY;
+            if (kend < kChunk) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = 32 * t + 8 * (e >> 2) + 4 * half + (e & 3);
+                        s[t][e] = key < kend ? s[t][e] : -INFINITY;
+                    }
+            }
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float v = s[t][e] * a.scale_log2e;
-                    if (ragged) {
-                        const int key = c0 + 32 * t + 8 * (e >> 2) + 4 * half + (e & 3);
-                        v = key < kend ? v : -INFINITY;
-                    }
-                    s[t][e] = v;
-                    mx = fmaxf(mx, v);
-                }
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
             {
                 const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                 mx = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));   // both half-waves' keys
             }
-            const float m_new = fmaxf(m_run, mx);       // finite: every chunk starts at a valid key
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first chunk (m_run = -inf)
+            const float m_new = fmaxf(m_run, mx * a.scale_log2e);   // finite: every block starts at a valid key
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
-            // ---- p = exp2(s - m), O^T += V^T P^T
+            // ---- p = exp2(s * scale - m), O^T += V^T P^T
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 float psum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    s[t][e] = __builtin_amdgcn_exp2f(s[t][e] - m_new);
+                    s[t][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e], a.scale_log2e, -m_new));
                     psum += s[t][e];
                 }
                 l_run += psum;
@@ -173,7 +196,7 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
                     pb.z = pack2(s[t][8 * j + 4], s[t][8 * j + 5]);
                     pb.w = pack2(s[t][8 * j + 6], s[t][8 * j + 7]);
                     const bf16x8 pf = __builtin_bit_cast(bf16x8, pb);
-                    const unsigned char *vrow = vs + (size_t)(c0 + 32 * t + 16 * j + 4 * half + srow) * kPitch + scol * 2;
+                    const unsigned char *vrow = vs + (size_t)(32 * t + 16 * j + 4 * half + srow) * kPitch + scol * 2;
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
                         const s16x4 v0 = tr_read(vrow + dt * 64);
@@ -184,6 +207,7 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
                 }
             }
         }
+        __syncthreads();                         // buffer blk % 2 is free; block blk + 1 is visible
     }
     // ---- normalise and store: lane holds query l32, d = 32*dt + 8*e4 + 4*half + e
     {
@@ -221,12 +245,10 @@ hipError_t launch_attention(const void *qkv, void *ctx, int N, int S, int heads,
     a.qkv = static_cast<const unsigned char *>(qkv);
     a.ctx = static_cast<unsigned char *>(ctx);
     a.N = N; a.S = S; a.heads = heads;
-    const int want = (S + attn::kChunk - 1) / attn::kChunk * attn::kChunk;
-    a.keys_alloc = want < attn::kMaxKeys ? want : attn::kMaxKeys;
     a.scale_log2e = 1.4426950408889634f / 8.0f;          // log2(e) / sqrt(64)
-    const size_t lds = (size_t)2 * a.keys_alloc * attn::kPitch;
+    const size_t lds = (size_t)2 * attn::kBufBytes;      // two buffers of one 128-key block: 72 KB
     static bool raised = false;
-    if (lds > 64 * 1024 && !raised) {
+    if (!raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn::attention_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
