@@ -259,7 +259,10 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  *                      followed by Cout bias gradients (sum of gy over the images).
  *   DELTA_OP_SOFTMAX_CE  gx (bytes of the logits) = (softmax(z) - onehot(label)) / N; gy and gpre
  *                      must be DELTA_NO_TENSOR; needs fwd.x (logits) and fwd.res (labels) resident.
- * Anything else (the 7x7 stem among it): DELTA_ERR_INVALID. */
+ *   the stem           (DELTA_OP_CONV, 7x7, stride 2, pad 3, 3 -> 64 channels, bf16): weight gradient only
+ *                      (gw required, fp32 [64][7][7][3]; gx, gx_add must be unset); gpre (bytes of y) receives
+ *                      gy * [y > 0] when fwd.relu, else gpre must be gy; needs fwd.x resident and a workspace.
+ * Anything else: DELTA_ERR_INVALID. */
 typedef struct delta_bwd_desc {
     delta_layer_desc fwd;      /* the forward layer; fwd.x must be resident when gw is asked for,
                                   fwd.y when fwd.relu != 0; fwd.res only says whether a residual exists */

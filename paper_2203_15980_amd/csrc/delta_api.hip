@@ -838,7 +838,12 @@ delta_status need_identity_factors(delta_ctx *c) {
     return DELTA_OK;
 }
 
-enum BwdKind { BK_CONV, BK_DENSE, BK_MAXPOOL, BK_AVGPOOL, BK_LOSS };
+enum BwdKind { BK_CONV, BK_DENSE, BK_MAXPOOL, BK_AVGPOOL, BK_LOSS, BK_STEM };
+
+bool is_stem(const delta_layer_desc &L) {
+    return L.op == DELTA_OP_CONV && L.dtype == DELTA_DTYPE_BF16 && L.R == 7 && L.S == 7 && L.stride == 2 && L.pad == 3 &&
+           L.Cin == 3 && L.Cout == 64 && L.res == DELTA_NO_TENSOR;
+}
 
 // The classifier (one pixel per image, a channel count the matrix-core kernels do not take) has its
 // own small kernels; every other convolution goes through the convolution backward.
@@ -846,8 +851,31 @@ BwdKind bwd_kind(const delta_layer_desc &L) {
     if (L.op == DELTA_OP_MAXPOOL) return BK_MAXPOOL;
     if (L.op == DELTA_OP_AVGPOOL) return BK_AVGPOOL;
     if (L.op == DELTA_OP_SOFTMAX_CE) return BK_LOSS;
+    if (is_stem(L)) return BK_STEM;
     if (L.H == 1 && L.W == 1 && L.R == 1 && L.S == 1 && L.stride == 1 && L.pad == 0 && L.Cout % 64 != 0) return BK_DENSE;
     return BK_CONV;
+}
+
+// The stem: weight gradient only (its input is the network's input).
+delta_status prepare_backward_stem(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, delta::ConvArgs &fa) {
+    delta::PoolArgs pa;
+    uint64_t flops = 0;
+    const delta_layer_desc &L = D.fwd;
+    delta_status r = prepare_layer(c, L, i, fa, pa, flops);
+    if (r != DELTA_OK) return r;
+    const size_t nt = c->tensors.size();
+    if (D.gx != DELTA_NO_TENSOR || D.gx_add != DELTA_NO_TENSOR || D.mask_gx)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: the stem has a weight gradient only (gx, gx_add, mask_gx unused)", i);
+    if (!D.gw || ((uintptr_t)D.gw & 15)) return fail(c, DELTA_ERR_INVALID, "backward %u: gw missing or misaligned", i);
+    const uint64_t ybytes = c->tensors[L.y].bytes;
+    if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != ybytes)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gy and gpre must have the bytes of y", i);
+    const bool own_mask = L.relu && !D.gy_masked;
+    if (own_mask ? (D.gpre == D.gy || D.gpre == L.y || D.gpre == L.x) : D.gpre != D.gy)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gpre must be a separate tensor exactly when a ReLU mask is applied", i);
+    if (!D.workspace || ((uintptr_t)D.workspace & 255) || D.workspace_bytes < delta::stem_wgrad_workspace_bytes(fa))
+        return fail(c, DELTA_ERR_INVALID, "backward %u: workspace missing, not 256-byte aligned or too small", i);
+    return DELTA_OK;
 }
 
 // Pooling, classifier and loss: validation only (bf16).  gx is required; gpre must be gy; no gx_add.
@@ -1014,6 +1042,7 @@ delta_status delta_backward_workspace(delta_ctx *c, const delta_layer_desc *laye
     uint64_t flops = 0;
     if ((r = prepare_layer(c, *layer, 0, a, pa, flops)) != DELTA_OK) return r;
     if (layer->op != DELTA_OP_CONV) { *out_bytes = 0; return DELTA_OK; }
+    if (is_stem(*layer)) { *out_bytes = delta::stem_wgrad_workspace_bytes(a); return DELTA_OK; }
     as_stride_1(*layer, a);
     *out_bytes = backward_workspace_bytes(*layer, a);
     return DELTA_OK;
@@ -1030,6 +1059,15 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
     for (uint32_t i = 0; i < n; ++i) {
         const delta_bwd_desc &D = descs[i];
         const BwdKind kind = bwd_kind(D.fwd);
+        if (kind == BK_STEM) {
+            if ((r = prepare_backward_stem(c, D, i, fa)) != DELTA_OK) return r;
+            if (!there(D.gy)) return fail(c, DELTA_ERR_STATE, "backward %u: gy tensor %u is not resident", i, D.gy);
+            if (!there(D.fwd.x)) return fail(c, DELTA_ERR_STATE, "backward %u: x tensor %u is not resident", i, D.fwd.x);
+            if (D.fwd.relu && !D.gy_masked && !there(D.fwd.y))
+                return fail(c, DELTA_ERR_STATE, "backward %u: y tensor %u is not resident", i, D.fwd.y);
+            will_exist[D.gpre] = 1;
+            continue;
+        }
         if (kind != BK_CONV) {
             delta::PoolArgs pa;
             if ((r = prepare_backward_other(c, D, i, kind, fa, pa)) != DELTA_OK) return r;
@@ -1057,6 +1095,26 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         const delta_bwd_desc &D = descs[i];
         const delta_layer_desc &L = D.fwd;
         const BwdKind kind = bwd_kind(L);
+        if (kind == BK_STEM) {
+            if ((r = prepare_backward_stem(c, D, i, fa)) != DELTA_OK) return r;
+            Tensor &tgy = c->tensors[D.gy];
+            if ((r = compute_uses(c, tgy)) != DELTA_OK) return r;
+            if (L.relu && !D.gy_masked) {
+                Tensor &ty = c->tensors[L.y];
+                if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+                if ((r = compute_writes(c, c->tensors[D.gpre])) != DELTA_OK) return r;
+                HIP_TRY(c, delta::launch_relu_mask(c->arena + ty.offset, c->arena + tgy.offset,
+                                                   c->arena + c->tensors[D.gpre].offset, tgy.bytes, 1, s));
+            }
+            Tensor &tx = c->tensors[L.x];
+            if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
+            fa.x = c->arena + tx.offset;
+            HIP_TRY(c, delta::launch_stem_wgrad(fa, c->arena + c->tensors[D.gpre].offset, static_cast<float *>(D.gw),
+                                                D.workspace, D.workspace_bytes, s));
+            c->st.recompute_flops += 2ull * (uint64_t)fa.M * 7 * 7 * 3 * 64;
+            c->st.recompute_launches += 1;
+            continue;
+        }
         if (kind != BK_CONV) {
             delta::PoolArgs pa;
             if ((r = prepare_backward_other(c, D, i, kind, fa, pa)) != DELTA_OK) return r;

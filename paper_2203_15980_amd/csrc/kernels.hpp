@@ -64,6 +64,10 @@ hipError_t launch_add(const void *x, const void *r, void *y, size_t bytes, int b
 bool stem_applies(const ConvArgs &a);
 const char *stem_check(const ConvArgs &a);
 hipError_t launch_stem(const ConvArgs &a, hipStream_t stream);
+// stem_wgrad.hip: weight gradient of the stem
+size_t stem_wgrad_workspace_bytes(const ConvArgs &a);
+hipError_t launch_stem_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
+                             hipStream_t stream);
 
 struct PoolArgs {
     const void *x;   // [N,H,W,C]

@@ -136,7 +136,11 @@ class Net:
         return bool(l.relu) and l.y in self.masked_by
 
     def _own_gpre(self, l):
-        return l.kind == "conv" and ((l.relu and not self._gy_masked(l)) or (l.stride > 1 and l.R > 1))
+        if l.kind != "conv":
+            return False
+        if self._is_stem(l):
+            return bool(l.relu) and not self._gy_masked(l)
+        return (l.relu and not self._gy_masked(l)) or (l.stride > 1 and l.R > 1)
 
     def _plan_mask_fusion(self):
         """tensor name -> the layer that applies the ReLU mask of the tensor's producer while it
@@ -159,9 +163,7 @@ class Net:
         after their last use; they are not part of the planned graph.  `input_gradient`: also
         compute dL/dx0.  `fuse_masks`: a ReLU layer's mask is applied by the data-gradient
         kernel of its output's last consumer where that is a convolution (no separate mask
-        kernel, no unmasked gradient tensor).  The 7x7 stem has no backward kernel: its step runs `stem_proxy`
-        (its forward kernel twice into a scratch tensor), as the replays did for every layer
-        before the backward kernels existed."""
+        kernel, no unmasked gradient tensor).  The 7x7 stem (bf16) has a weight gradient only."""
         d, dev = self.delta, self.device
         if self.dtype != "bf16" and any(l.kind != "conv" for l in self.layers):
             raise ValueError("backward of pooling, classifier and loss is bf16 only")
@@ -181,12 +183,11 @@ class Net:
         self.has_loss = "loss" in self.desc
         new_tensor("g:" + top.y, self.sizes[self.ids[top.y]], self.shapes[top.y])
         for l in self.layers:
-            if self._is_stem(l):
-                new_tensor("scratch:" + l.name, self.sizes[self.ids[l.y]], self.shapes[l.y])
-                continue
+            if self._is_stem(l) and (input_gradient or self.dtype != "bf16"):
+                raise ValueError("the stem's backward is its bf16 weight gradient only")
             if self._own_gpre(l):
-                # at the input's resolution; a 1x1 layer's at the output's
-                shape = (l.N, l.H, l.W, l.Cout) if l.R > 1 else self.shapes[l.y]
+                # at the input's resolution; a 1x1 layer's and the stem's at the output's
+                shape = (l.N, l.H, l.W, l.Cout) if (l.R > 1 and not self._is_stem(l)) else self.shapes[l.y]
                 new_tensor("gp:" + l.name, int(np.prod(shape)) * self.es, shape)
             if l.x != "x0" or input_gradient:
                 new_tensor("g:" + l.x + ":" + l.name, self.sizes[self.ids[l.x]], self.shapes[l.x])
@@ -195,20 +196,17 @@ class Net:
             self.ids[name] = tid
         self.sizes = self.all_sizes
         d.bind(self.all_sizes)
-        self.wt, self.gw, self.stem_proxy_desc = {}, {}, {}
+        self.wt, self.gw = {}, {}
         ws_bytes = 16
         for l in self.layers:
             fwd = self.desc[l.y][0]
             if l.kind == "fc":
                 self.gw[l.name] = torch.zeros(l.Cout * l.Cin + l.Cout, dtype=torch.float32, device=dev)
-            elif l.kind == "conv" and self._is_stem(l):
-                dsc = B.LayerDesc.from_buffer_copy(fwd)
-                dsc.y = self.ids["scratch:" + l.name]
-                self.stem_proxy_desc[l.name] = B.layer_array([dsc])
             elif l.kind == "conv":
                 n = l.Cout * l.R * l.S * l.Cin
-                self.wt[l.name] = torch.empty(n * self.es, dtype=torch.uint8, device=dev)
-                d.bwd_weights(fwd, self.wt[l.name].data_ptr())
+                if not self._is_stem(l):                  # the data gradient's weights
+                    self.wt[l.name] = torch.empty(n * self.es, dtype=torch.uint8, device=dev)
+                    d.bwd_weights(fwd, self.wt[l.name].data_ptr())
                 self.gw[l.name] = torch.zeros(n, dtype=torch.float32, device=dev)
                 ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
         self.bwd_workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
@@ -261,8 +259,6 @@ class Net:
         `pending` (tensor name -> gradient tensor name).  Pure bookkeeping (no GPU call):
         returns (gy, gpre, gx, add, dead, new_pending_entries)."""
         gy = pending[l.y]
-        if self._is_stem(l):
-            return gy, None, None, None, [gy], {}
         gpre = "gp:" + l.name if self._own_gpre(l) else gy
         want_gx = l.x != "x0" or self.input_gradient
         gx = "g:" + l.x + ":" + l.name if want_gx else None
@@ -297,14 +293,11 @@ class Net:
             for nm in (gpre, gx):
                 if nm and nm not in live:
                     live[nm] = self.sizes[self.ids[nm]]
-            if self._is_stem(l):
-                live["scratch:" + l.name] = self.sizes[self.ids["scratch:" + l.name]]
             peak = max(peak, sum(live.values()))
             pending.pop(l.y)
             pending.update(new)
             for nm in dead:
                 live.pop(nm, None)
-            live.pop("scratch:" + l.name, None)
         return peak
 
     def backward_begin(self):
@@ -327,24 +320,17 @@ class Net:
         d = self.delta
         gy, gpre, gx, add, dead, new = self._bwd_plan(l, self.pending)
         self.pending.pop(l.y)
-        if self._is_stem(l):
-            arr = self.stem_proxy_desc[l.name]
-            d.recompute_segment(arr)
-            d.recompute_segment(arr)
-            d.release(self.ids["scratch:" + l.name], B.EV_FREE)
-        else:
-            conv = l.kind == "conv"
-            mask_gx = conv and gx is not None and self.masked_by.get(l.x) == l.name
-            desc = B.BwdDesc(fwd=self.desc[l.y][0], gy=self.ids[gy], gpre=self.ids[gpre],
-                             gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
-                             mask_gx=int(mask_gx), gy_masked=int(conv and self._gy_masked(l)),
-                             wt=self.wt[l.name].data_ptr() if conv else None,
-                             gw=self.gw[l.name].data_ptr() if (l.name in self.gw and self.dtype == "bf16") else None,
-                             workspace=self.bwd_workspace.data_ptr() if conv else None,
-                             workspace_bytes=self.bwd_workspace.numel() if conv else 0)
-            d.backward_segment([desc])
-        self.bwd_trace.append((l.name, gy, gpre, gx, add, bool(not self._is_stem(l) and l.kind == "conv" and gx is not None
-                                                                and self.masked_by.get(l.x) == l.name)))
+        conv = l.kind == "conv"
+        mask_gx = conv and gx is not None and self.masked_by.get(l.x) == l.name
+        desc = B.BwdDesc(fwd=self.desc[l.y][0], gy=self.ids[gy], gpre=self.ids[gpre],
+                         gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
+                         mask_gx=int(mask_gx), gy_masked=int(conv and self._gy_masked(l)),
+                         wt=self.wt[l.name].data_ptr() if l.name in self.wt else None,
+                         gw=self.gw[l.name].data_ptr() if (l.name in self.gw and self.dtype == "bf16") else None,
+                         workspace=self.bwd_workspace.data_ptr() if conv else None,
+                         workspace_bytes=self.bwd_workspace.numel() if conv else 0)
+        d.backward_segment([desc])
+        self.bwd_trace.append((l.name, gy, gpre, gx, add, bool(mask_gx)))
         self.pending.update(new)
         if not keep:
             for name in dead:

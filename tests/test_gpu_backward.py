@@ -159,6 +159,68 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     d.close()
 
 
+@pytest.mark.parametrize("N,H,W,relu", [(2, 32, 32, True), (1, 37, 45, True), (3, 64, 48, False)])
+def test_stem_weight_gradient_matches_oracle(torch_mod, N, H, W, relu):
+    """7x7 stride-2 stem: gpre bit-exact, dL/dw against the oracle (fp32 sums of exact bf16 products).
+    Odd image sizes give partial tiles and padding on every side."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    print("stem", N, H, W, relu, flush=True)
+    l = synth.LayerSpec("stem", "conv", "x0", None, "stem", N, H, W, 3, 64, 7, 7, 2, 3, relu)
+    l.index = 1
+    P, Q = l.P, l.Q
+    master = 97
+    x = synth.make_input(master, (N, H, W, 3), "bf16")
+    p = synth.make_params(master, l, "bf16")
+    gy = synth.f32_to_bf16_bits(synth.normal(master, 902, N * P * Q * 64).astype(np.float32)).reshape(N, P, Q, 64)
+    ysz = gy.nbytes
+    arena = torch.empty(32 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([x.nbytes, ysz, ysz, ysz])               # 0 x, 1 y, 2 gy, 3 gpre
+    base = d.arena.data_ptr()
+
+    def put(tid, a):
+        ptr = d.alloc(tid)
+        d.arena[ptr - base:ptr - base + a.nbytes].copy_(_dev(torch, a.view(np.uint8).reshape(-1)))
+
+    def get(tid, shape):
+        ptr = d.tensor_ptr(tid)
+        n = int(np.prod(shape)) * 2
+        return d.arena[ptr - base:ptr - base + n].cpu().numpy().view(np.uint16).reshape(shape)
+
+    put(0, x)
+    put(2, gy)
+    w = _dev(torch, p["w"])
+    bn = [_dev(torch, p[k]) for k in ("gamma", "beta", "mean", "var")]
+    scale = torch.empty(64, dtype=torch.float32, device="cuda:0")
+    shift = torch.empty(64, dtype=torch.float32, device="cuda:0")
+    d.bn_fold(bn[0].data_ptr(), bn[1].data_ptr(), bn[2].data_ptr(), bn[3].data_ptr(), float(p["eps"]), 64,
+              scale.data_ptr(), shift.data_ptr())
+    fwd = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=w.data_ptr(), scale=scale.data_ptr(),
+                       shift=shift.data_ptr(), N=N, H=H, W=W, Cin=3, Cout=64, R=7, S=7, stride=2, pad=3, relu=1 if relu else 0)
+    d.recompute_segment([fwd])
+    ws_bytes = d.backward_workspace(fwd)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    gw = torch.full((64, 7, 7, 3), float("nan"), dtype=torch.float32, device="cuda:0")
+    desc = dl.BwdDesc(fwd=fwd, gy=2, gpre=3 if relu else 2, gx=dl.NO_TENSOR, gx_add=dl.NO_TENSOR, wt=None,
+                      gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
+    d.backward_segment([desc])
+    d.sync()
+    y_gpu = get(1, (N, P, Q, 64))
+    _, ref_gw, ref_gpre = on.conv_bn_act_bwd(x, p["w"], p, y_gpu, gy, stride=2, pad=3, relu=relu, dtype="bf16")
+    assert np.array_equal(on.to_f64(get(3 if relu else 2, (N, P, Q, 64)), "bf16"), ref_gpre)
+    got = gw.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err = float(np.max(np.abs(got - ref_gw)) / np.max(np.abs(ref_gw)))
+    print("  gw err %.2e" % err, flush=True)
+    assert err <= 2e-4, err
+    with pytest.raises(dl.DeltaError):                      # the stem has no data gradient
+        d.backward_segment([dl.BwdDesc(fwd=fwd, gy=2, gpre=3 if relu else 2, gx=0, gx_add=dl.NO_TENSOR, wt=None,
+                                       gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)])
+    d.close()
+
+
 def test_backward_rejects_what_it_does_not_support(torch_mod):
     torch = torch_mod
     import paper_2203_15980_amd as dl
@@ -361,7 +423,7 @@ def test_classifier_and_loss_backward_match_oracle(torch_mod):
 def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
     """ResNet with one bottleneck per stage on 2 x 64 x 64 x 3 with the loss: the whole backward
     pass through the harness (loss, classifier, average pool, strided and projection blocks,
-    max-pool; the stem has no backward kernel and runs its proxy).  Every layer is checked against
+    max-pool, the stem's weight gradient).  Every layer is checked against
     the oracle on exactly the tensors the GPU's layer was given."""
     torch = torch_mod
     import paper_2203_15980_amd as dl
@@ -389,8 +451,17 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
     checked = set()
     for (lname, gy_name, gpre_name, gx_name, add_name, masks_gx) in net.bwd_trace:
         l = by_name[lname]
-        if gx_name is None:
-            continue                                        # the stem
+        if gx_name is None:                                 # the stem: weight gradient only
+            p = net.params_np[lname]
+            _, ref_gw, ref_gpre = on.conv_bn_act_bwd(acts[l.x], p["w"], p, acts[l.y], net.read(gy_name), stride=l.stride,
+                                                     pad=l.pad, relu=l.relu, dtype="bf16")
+            assert np.array_equal(on.to_f64(net.read(gpre_name), "bf16"), ref_gpre)
+            got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
+            ew = float(np.max(np.abs(got_gw - ref_gw)) / np.max(np.abs(ref_gw)))
+            print("  %-10s stem     gw %.2e" % (lname, ew), flush=True)
+            assert ew <= 2e-4, (lname, ew)
+            checked.add("stem")
+            continue
         gy = net.read(gy_name)
         got = on.to_f64(net.read(gx_name), "bf16")
         if l.kind == "conv":
@@ -423,6 +494,6 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
         print("  %-10s %-8s gx %.2e" % (lname, l.kind, ex), flush=True)
         assert ex <= 2e-2, (lname, ex)
         checked.add(l.kind)
-    assert checked == {"conv", "maxpool", "avgpool", "fc"}
+    assert checked == {"conv", "maxpool", "avgpool", "fc", "stem"}
     assert any(by_name[t[0]].stride == 2 for t in net.bwd_trace)
     d.close()
