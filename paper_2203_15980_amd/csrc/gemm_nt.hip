@@ -21,9 +21,9 @@
 //    64 banks once;
 //  * workgroups are numbered so that each XCD (blockIdx % 8) walks a contiguous range of x-row
 //    tiles with all their w tiles: x rows and the whole of w stay in that XCD's L2;
-//  * epilogue as in the convolution kernels: scale/shift in the accumulator layout, a
-//    wavefront-private fp32 tile in LDS turns channel-major accumulators into 128-byte pixel rows,
-//    residual, activation (none / ReLU / GELU), optional mask, one rounding.
+//  * epilogue: a wavefront-private fp32 tile in LDS turns channel-major accumulators into 128-byte
+//    pixel rows; scale/shift, residual, activation (none / ReLU / GELU), optional mask, one rounding;
+//    the residual and mask rows of the next 32 pixels are requested while the current ones are finished.
 // Rows past M or N are fetched from the last valid row (never stored).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -201,30 +201,40 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
     const unsigned char *rg = static_cast<const unsigned char *>(a.res);
     const unsigned char *mg = static_cast<const unsigned char *>(a.mask);
     const int prow = lane >> 3, cseg = lane & 7;
-    f32x4 sc[kTN][4], sh[kTN][4];
-#pragma unroll
-    for (int j = 0; j < kTN; ++j)
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            int ch = n0 + wn * 64 + j * 32 + 8 * rb + 4 * half;
-            ch = ch + 4 <= N ? ch : 0;              // N is a multiple of 8: a group of 4 is inside or outside
-            sc[j][rb] = *reinterpret_cast<const f32x4 *>(a.scale + ch);
-            sh[j][rb] = *reinterpret_cast<const f32x4 *>(a.shift + ch);
-        }
     const int chan = n0 + wn * 64 + cseg * 8;
+    // scale / shift of this lane's 8 channels in the row-major phase (the same for every row)
+    float sc[8], sh[8];
+    {
+        const int ch = chan < N ? chan : 0;          // N is a multiple of 8: the 8 channels are inside or outside together
+        const f32x4 s0 = *reinterpret_cast<const f32x4 *>(a.scale + ch), s1 = *reinterpret_cast<const f32x4 *>(a.scale + ch + 4);
+        const f32x4 h0 = *reinterpret_cast<const f32x4 *>(a.shift + ch), h1 = *reinterpret_cast<const f32x4 *>(a.shift + ch + 4);
+        sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w; sc[4] = s1.x; sc[5] = s1.y; sc[6] = s1.z; sc[7] = s1.w;
+        sh[0] = h0.x; sh[1] = h0.y; sh[2] = h0.z; sh[3] = h0.w; sh[4] = h1.x; sh[5] = h1.y; sh[6] = h1.z; sh[7] = h1.w;
+    }
+    // residual and mask rows of tile i + 1 are requested while tile i is finished (a workgroup is
+    // alone on its CU: nothing else would cover their latency; it was most of a short-K layer's time)
+    u32x4 rres[2][4], rmsk[2][4];
+    auto request = [&](int i, u32x4 (&rr)[4], u32x4 (&rm)[4]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int m = m0 + wm * 128 + i * 32 + prow + 8 * t;
+            const bool ok = m < M && chan < N;
+            const size_t off = ((size_t)(ok ? m : 0) * N + (ok ? chan : 0)) * 2;
+            rr[t] = rg ? *reinterpret_cast<const u32x4 *>(rg + off) : u32x4{0u, 0u, 0u, 0u};
+            rm[t] = mg ? *reinterpret_cast<const u32x4 *>(mg + off) : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    request(0, rres[0], rmsk[0]);
 #pragma unroll
     for (int i = 0; i < kTM; ++i) {
+        if (i + 1 < kTM) request(i + 1, rres[(i + 1) & 1], rmsk[(i + 1) & 1]);
         wave_lds_fence();
 #pragma unroll
         for (int j = 0; j < kTN; ++j)
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
                 const f32x16 &c = acc[i][j];
-                f32x4 v;
-                v.x = c[4 * rb + 0] * sc[j][rb].x + sh[j][rb].x;
-                v.y = c[4 * rb + 1] * sc[j][rb].y + sh[j][rb].y;
-                v.z = c[4 * rb + 2] * sc[j][rb].z + sh[j][rb].z;
-                v.w = c[4 * rb + 3] * sc[j][rb].w + sh[j][rb].w;
+                const f32x4 v = {c[4 * rb + 0], c[4 * rb + 1], c[4 * rb + 2], c[4 * rb + 3]};
                 *reinterpret_cast<f32x4 *>(stg + l32 * kStgPitch + (j * 32 + 8 * rb + 4 * half) * 4) = v;
             }
         wave_lds_fence();
@@ -236,9 +246,11 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
             const f32x4 f0 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32);
             const f32x4 f1 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32 + 16);
             float v[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] * sc[e] + sh[e];
             const size_t off = ((size_t)m * N + chan) * 2;
             if (rg) {
-                const u32x4 rv = *reinterpret_cast<const u32x4 *>(rg + off);
+                const u32x4 rv = rres[i & 1][t];
                 v[0] += lo16(rv.x); v[1] += hi16(rv.x); v[2] += lo16(rv.y); v[3] += hi16(rv.y);
                 v[4] += lo16(rv.z); v[5] += hi16(rv.z); v[6] += lo16(rv.w); v[7] += hi16(rv.w);
             }
@@ -252,7 +264,7 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
             u32x4 o;
             o.x = pack2(v[0], v[1]); o.y = pack2(v[2], v[3]); o.z = pack2(v[4], v[5]); o.w = pack2(v[6], v[7]);
             if (mg) {
-                const u32x4 mv = *reinterpret_cast<const u32x4 *>(mg + off);
+                const u32x4 mv = rmsk[i & 1][t];
                 o.x = keep_where_positive_bf16(o.x, mv.x); o.y = keep_where_positive_bf16(o.y, mv.y);
                 o.z = keep_where_positive_bf16(o.z, mv.z); o.w = keep_where_positive_bf16(o.w, mv.w);
             }
