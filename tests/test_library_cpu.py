@@ -139,3 +139,55 @@ def test_heuristic_sweep_reproduces_the_papers_ordering():
     assert res["lru"]["min_budget_frac"] <= res["greedy"]["min_budget_frac"]
     moved = lambda r: r["at"]["0.5"]["evict"] + r["at"]["0.5"]["offload"]
     assert moved(res["lru"]) >= moved(res["base"])
+
+
+def test_binding_structs_have_the_headers_layout(tmp_path):
+    """The ctypes structures must match include/delta.h field for field: a C program built against
+    the header prints sizes and offsets, the binding is compared with it."""
+    import ctypes as C
+    from paper_2203_15980_amd import binding as B
+    fields = {"delta_layer_desc": [f for f, _ in B.LayerDesc._fields_],
+              "delta_bwd_desc": [f for f, _ in B.BwdDesc._fields_],
+              "delta_stats_t": [f for f, _ in B.Stats._fields_]}
+    src = ["#include <stdio.h>", "#include <stddef.h>", '#include "delta.h"', "int main(void) {"]
+    for st, fs in fields.items():
+        src.append('printf("%s %%zu\\n", sizeof(%s));' % (st, st))
+        for f in fs:
+            src.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (st, f, st, f))
+    src += ["return 0;", "}"]
+    c_file = tmp_path / "layout.c"
+    c_file.write_text("\n".join(src))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(c_file), "-o", str(exe)])
+    want = dict(line.split() for line in subprocess.check_output([str(exe)]).decode().splitlines())
+    classes = {"delta_layer_desc": B.LayerDesc, "delta_bwd_desc": B.BwdDesc, "delta_stats_t": B.Stats}
+    for st, cls in classes.items():
+        assert C.sizeof(cls) == int(want[st]), st
+        for f in fields[st]:
+            assert getattr(cls, f).offset == int(want["%s.%s" % (st, f)]), (st, f)
+    # and the enumerators the binding restates
+    hdr = open(os.path.join(ROOT, "include", "delta.h")).read()
+    for name, val in (("OP_ATTENTION", B.OP_ATTENTION), ("OP_LAYERNORM", B.OP_LAYERNORM), ("OP_BATCHNORM", B.OP_BATCHNORM),
+                      ("OP_RELU", B.OP_RELU), ("OP_ADD", B.OP_ADD), ("OP_SOFTMAX_CE", B.OP_SOFTMAX_CE),
+                      ("ACT_GELU", B.ACT_GELU), ("ACT_RELU", B.ACT_RELU)):
+        m = re.search(r"DELTA_%s\s*=\s*(\d+)" % name, hdr)
+        assert m and int(m.group(1)) == val, name
+
+
+def test_executed_encoder_plan_matches_oracle():
+    """The graph bench.py replays for config 5 (12 BERT-base layers as 84 fused operators, no score
+    tensors): library plan = oracle plan at 30 % and 50 %, and the plans pass the checker."""
+    layers = synth.encoder_layers(32, 512, nlayers=12)
+    g = synth.fused_graph(layers, "bf16")
+    assert len(g.tensors) == 85 and g.total_bytes() == 3649044480
+    for frac in (0.3, 0.5):
+        p = pl.default_params(int(frac * g.total_bytes()), g.n_fwd, bw_d2h_Bps=55 * 10**9, bw_h2d_Bps=55 * 10**9)
+        want = pl.plan(g.tensors, g.steps, p)
+        assert dl.plan(g.tensors, g.steps, p) == want
+        st = checker.check(g.tensors, g.steps, p, want[0])
+        assert st["peak"] == want[1] <= p["budget_bytes"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run(["python", os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
