@@ -229,7 +229,10 @@ hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const flo
     float *partial = ab + 2 * (size_t)C;
     const size_t room = (bn_train_scratch_bytes() - 2 * (size_t)C * 4) / ((size_t)2 * C * 4);
     long long blocks = (M + (long long)RS * 4 - 1) / ((long long)RS * 4);    // at least 4 rows per lane
-    if (blocks > 2048) blocks = 2048;
+    // fewer partials for wide tensors: the finalize kernel reads blocks x 2 x C floats
+    long long cap = 262144 / C;
+    cap = cap < 64 ? 64 : (cap > 2048 ? 2048 : cap);
+    if (blocks > cap) blocks = cap;
     if (blocks > (long long)room) blocks = (long long)room;
     if (blocks < 1) return hipErrorInvalidValue;
     const long long rpb = (M + blocks - 1) / blocks;
