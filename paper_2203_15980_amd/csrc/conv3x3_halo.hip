@@ -227,22 +227,33 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
         }
     }
 
-    // ---- epilogue: scale/shift in the accumulator layout, row-major through a wavefront-
-    // private fp32 tile, residual + ReLU, one rounding, 128 contiguous bytes per pixel
-    __syncthreads();
-    unsigned char *stg = smem + wv * (32 * kStgPitch);
+    // ---- epilogue: row-major through a wavefront-private fp32 tile, scale/shift, residual + ReLU
+    // (+ mask), one rounding, 128 contiguous bytes per pixel.  The residual and mask rows are
+    // requested before the barrier, so that their latency overlaps it and the transposition.
     unsigned char *yg = static_cast<unsigned char *>(a.y);
     const unsigned char *rg = static_cast<const unsigned char *>(a.res);
+    const unsigned char *mg = static_cast<const unsigned char *>(a.mask);
     const int pr8 = lane >> 3, cseg = lane & 7;
-    f32x4 sc[2][4], sh[2][4];
+    const int chan = n0 + wn * 64 + cseg * 8;
+    u32x4 rres[TP][4], rmsk[TP][4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int i = 0; i < TP; ++i)
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const int ch = n0 + wn * 64 + u * 32 + 8 * rb + 4 * half;
-            sc[u][rb] = *reinterpret_cast<const f32x4 *>(a.scale + ch);
-            sh[u][rb] = *reinterpret_cast<const f32x4 *>(a.shift + ch);
+        for (int t = 0; t < 4; ++t) {
+            const int m = m0 + wm * (32 * TP) + i * 32 + pr8 + 8 * t;
+            const size_t off = ((size_t)(m < a.M ? m : 0) * a.Cout + chan) * 2;
+            rres[i][t] = rg ? *reinterpret_cast<const u32x4 *>(rg + off) : u32x4{0u, 0u, 0u, 0u};
+            rmsk[i][t] = mg ? *reinterpret_cast<const u32x4 *>(mg + off) : u32x4{0u, 0u, 0u, 0u};
         }
+    float sc[8], sh[8];                             // this lane's 8 channels in the row-major phase
+    {
+        const f32x4 s0 = *reinterpret_cast<const f32x4 *>(a.scale + chan), s1 = *reinterpret_cast<const f32x4 *>(a.scale + chan + 4);
+        const f32x4 h0 = *reinterpret_cast<const f32x4 *>(a.shift + chan), h1 = *reinterpret_cast<const f32x4 *>(a.shift + chan + 4);
+        sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w; sc[4] = s1.x; sc[5] = s1.y; sc[6] = s1.z; sc[7] = s1.w;
+        sh[0] = h0.x; sh[1] = h0.y; sh[2] = h0.z; sh[3] = h0.w; sh[4] = h1.x; sh[5] = h1.y; sh[6] = h1.z; sh[7] = h1.w;
+    }
+    __syncthreads();
+    unsigned char *stg = smem + wv * (32 * kStgPitch);
 #pragma unroll
     for (int i = 0; i < TP; ++i) {
         wave_lds_fence();
@@ -251,15 +262,10 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
                 const f32x16 &c = acc[i][u];
-                f32x4 v;
-                v.x = c[4 * rb + 0] * sc[u][rb].x + sh[u][rb].x;
-                v.y = c[4 * rb + 1] * sc[u][rb].y + sh[u][rb].y;
-                v.z = c[4 * rb + 2] * sc[u][rb].z + sh[u][rb].z;
-                v.w = c[4 * rb + 3] * sc[u][rb].w + sh[u][rb].w;
+                const f32x4 v = {c[4 * rb + 0], c[4 * rb + 1], c[4 * rb + 2], c[4 * rb + 3]};
                 *reinterpret_cast<f32x4 *>(stg + l32 * kStgPitch + (u * 32 + 8 * rb + 4 * half) * 4) = v;
             }
         wave_lds_fence();
-        const int chan = n0 + wn * 64 + cseg * 8;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int pr = pr8 + 8 * t;
@@ -268,9 +274,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
             const f32x4 f0 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32);
             const f32x4 f1 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32 + 16);
             float v[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] * sc[e] + sh[e];
             const size_t off = ((size_t)m * a.Cout + chan) * 2;
             if (rg) {
-                const u32x4 rv = *reinterpret_cast<const u32x4 *>(rg + off);
+                const u32x4 rv = rres[i][t];
                 v[0] += bf16_lo(rv.x); v[1] += bf16_hi(rv.x);
                 v[2] += bf16_lo(rv.y); v[3] += bf16_hi(rv.y);
                 v[4] += bf16_lo(rv.z); v[5] += bf16_hi(rv.z);
@@ -285,8 +293,8 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
             o.y = pack_bf16(v[2], v[3]);
             o.z = pack_bf16(v[4], v[5]);
             o.w = pack_bf16(v[6], v[7]);
-            if (a.mask) {
-                const u32x4 mv = *reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(a.mask) + off);
+            if (mg) {
+                const u32x4 mv = rmsk[i][t];
                 o.x = keep_where_positive_bf16(o.x, mv.x); o.y = keep_where_positive_bf16(o.y, mv.y);
                 o.z = keep_where_positive_bf16(o.z, mv.z); o.w = keep_where_positive_bf16(o.w, mv.w);
             }
