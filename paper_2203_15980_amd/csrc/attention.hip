@@ -10,20 +10,20 @@
 // [64h, 64h+64) of each (d = 64).  ctx [N, S, H] bf16.
 //
 // A workgroup (8 wavefronts) takes one (image, head) and a block of 256 queries; a wavefront owns
-// 32 queries.  K and V of the head stream through LDS in blocks of 128 keys, two buffers; block
+// 32 queries.  K and V of the head stream through LDS in blocks of 64 keys, two buffers; block
 // b + 1 waits in registers (requested a block earlier) while block b is multiplied, so only the
 // first block's latency is exposed (staging all 512 keys up front cost 20 of 68 us at batch 32 x
 // 512).  Everything is computed TRANSPOSED so that a lane owns one query:
 //   S^T tile (32 keys x 32 queries) = K tile . Q^T        A = K rows from LDS (b128), B = Q from registers
 //   lane l holds query l % 32 and keys 8*e4 + 4*(l/32) + e of the tile: the softmax statistics of
 //   a query (running maximum, running sum) are per-lane scalars; the two half-waves see disjoint
-//   keys and exchange their maxima with one permlane32 swap per 128 keys.
+//   keys and exchange their maxima with one permlane32 swap per block of 64 keys.
 //   O^T (64 d x 32 queries) += V^T . P^T                  A = V^T through the LDS transpose read
 //   (ds_read_b64_tr_b16: V lies [key][d] in LDS as in memory), B = P straight from the S^T
 //   accumulators rounded to bf16: accumulator registers (e4 in {2j, 2j+1}) of a lane are exactly
 //   the 8 reduction slots of step j, if the A operand enumerates the keys in the same order
 //   (keys 16j + 4*(l/32) + e and 16j + 8 + 4*(l/32) + e) - the order of a reduction is free.
-// Online softmax over the 128-key blocks (fp32; the maximum is taken of the raw scores, the scale
+// Online softmax over the 64-key blocks (fp32; the maximum is taken of the raw scores, the scale
 // and the subtraction are one fma in front of exp2).  P is rounded to
 // bf16 before it multiplies V (the only rounding besides the output's).
 // Keys >= S are masked to -inf (their K/V rows in LDS are zeros); query rows >= S are computed on
@@ -45,11 +45,12 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 static constexpr int kD = 64;                    // head dimension
-static constexpr int kChunk = 128;               // keys per block (one online-softmax step)
+static constexpr int kChunk = 64;                // keys per block (one online-softmax step)
+static constexpr int kKT = kChunk / 32;          // 32-key tiles per block
 static constexpr int kWaves = 8, kQB = kWaves * 32;   // queries per workgroup (4 wavefronts, two workgroups per CU: 4 % slower)
 static constexpr int kPieces = kChunk * 8 / (kWaves * 64);   // 16-byte pieces of K (and of V) per thread and block
 static constexpr int kPitch = kD * 2 + 16;       // LDS row pitch in bytes (144: conflict-free b128 rows)
-static constexpr int kBufBytes = 2 * kChunk * kPitch;   // K and V of one block of 128 keys: 36 KB
+static constexpr int kBufBytes = 2 * kChunk * kPitch;   // K and V of one block: 18 KB
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     const f32x2 v = {lo, hi};
@@ -63,7 +64,10 @@ struct AttnArgs {
     float scale_log2e;                           // log2(e) / sqrt(d)
 };
 
-__global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
+// Two workgroups per CU (<= 128 registers per lane, 36 KB of LDS each): four wavefronts per SIMD, so that
+// one wavefront's softmax arithmetic runs under another's MFMAs.  With 128-key blocks (172 registers,
+// one workgroup per CU) the same kernel took 54 instead of 45 us at batch 32 x 512.
+__global__ __launch_bounds__(kWaves * 64, 2) void attention_kernel(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -99,10 +103,10 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
     typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
     auto tr_read = [&](const unsigned char *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p)); };
 
-    // ---- K/V blocks of 128 keys move global -> registers -> LDS one block ahead of the arithmetic:
+    // ---- K/V blocks of 64 keys move global -> registers -> LDS one block ahead of the arithmetic:
     // while block b is multiplied out of buffer b % 2, block b + 1 sits in registers (requested a
     // whole block earlier) and is stored into the other buffer at the start of the next round.
-    // 128 rows x 8 pieces x 2 operands / 512 threads = 4 pieces per thread.
+    // 64 rows x 8 pieces x 2 operands / 512 threads = 2 pieces per thread.
     const int nblocks = (a.S + kChunk - 1) / kChunk;
     u32x4 rk[kPieces], rv[kPieces];
     auto fetch = [&](int blk) {                  // rows past S (or blocks past the end): zeros
@@ -138,10 +142,10 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
         const unsigned char *ks = smem + (size_t)(blk & 1) * kBufBytes, *vs = ks + kChunk * kPitch;
         const int kend = a.S - blk * kChunk;              // valid keys in this block (>= 1)
         {
-            // ---- S^T for 128 keys: 4 tiles of 32 keys x 32 queries
-            f32x16 s[4];
+            // ---- S^T for the block: tiles of 32 keys x 32 queries
+            f32x16 s[kKT];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < kKT; ++t) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) s[t][e] = 0.f;
                 const unsigned char *krow = ks + (size_t)(32 * t + l32) * kPitch + half * 16;
@@ -151,19 +155,20 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
                     s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[k4], s[t], 0, 0, 0);
                 }
             }
-            // ---- mask, running maximum (of the raw scores: the scale is positive)
+            // ---- mask (last block only: a real branch, the selects would otherwise run for every
+            // block), running maximum (of the raw scores: the scale is positive)
             float mx = -INFINITY;
-            if (kend < kChunk) {
+            if (__builtin_expect(kend < kChunk, 0)) {
+                const int lim = kend - 4 * half;                   // key = 32 t + 8 (e / 4) + (e % 4) + 4 half
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < kKT; ++t)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int key = 32 * t + 8 * (e >> 2) + 4 * half + (e & 3);
-                        s[t][e] = key < kend ? s[t][e] : -INFINITY;
-                    }
+                    for (int e = 0; e < 16; ++e)
+                        s[t][e] = 32 * t + 8 * (e >> 2) + (e & 3) < lim ? s[t][e] : -INFINITY;
+                asm volatile("" ::: "memory");                     // keeps the masked path a separate block
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < kKT; ++t)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
             {
@@ -180,7 +185,7 @@ __global__ __launch_bounds__(kWaves * 64) void attention_kernel(AttnArgs a) {
                 for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
             // ---- p = exp2(s * scale - m), O^T += V^T P^T
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < kKT; ++t) {
                 float psum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
@@ -246,7 +251,7 @@ hipError_t launch_attention(const void *qkv, void *ctx, int N, int S, int heads,
     a.ctx = static_cast<unsigned char *>(ctx);
     a.N = N; a.S = S; a.heads = heads;
     a.scale_log2e = 1.4426950408889634f / 8.0f;          // log2(e) / sqrt(64)
-    const size_t lds = (size_t)2 * attn::kBufBytes;      // two buffers of one 128-key block: 72 KB
+    const size_t lds = (size_t)2 * attn::kBufBytes;      // two buffers of one block: 36 KB
     static bool raised = false;
     if (!raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn::attention_kernel),
