@@ -5,10 +5,13 @@
 // with many input channels - both are plain "NT" GEMMs (both operands contiguous along K), bound
 // by the matrix cores.  The tiled convolution kernel treats them as a convolution (64 x 64 tiles
 // per wavefront, slices staged through registers); this kernel is built for the GEMM:
-//  * workgroup tile 256 x 256 (8 wavefronts as 2 x 4) or 256 x 192 (6 wavefronts), 128 x 64 per
-//    wavefront: 6 operand reads feed 8 MFMAs (32x32x16) per k-step, against 4 for 4; the width is
-//    the one that leaves fewer CUs idle (768 output channels: 4 tiles of 192 fill the chip at
-//    16384 rows, 3 tiles of 256 leave a quarter of it idle);
+//  * workgroup tile 256 x 256 (16 wavefronts as 4 x 4) or 256 x 192 (12 wavefronts), 64 x 64 per
+//    wavefront and at most 128 registers, so that four (three) wavefronts share a SIMD: with
+//    128 x 64 per wavefront (8 | 6 wavefronts, two per SIMD, fewer operand reads per MFMA) the same
+//    kernel was 5-13 % slower - a SIMD needs more than two wavefronts to keep its MFMA pipe fed
+//    across the barrier and the operand reads; the width is the one that leaves fewer CUs idle
+//    (768 output channels: 4 tiles of 192 fill the chip at 16384 rows, 3 tiles of 256 leave a
+//    quarter of it idle);
 //  * K slices of 32 go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
 //    no registers, no LDS store instructions) through FOUR buffers of 32 KB: a slice is requested
 //    three slices (>= 3000 cycles of MFMA work per SIMD) before it is multiplied - with two buffers
@@ -41,8 +44,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 static constexpr int kBM = 256, kBK = 32, kStages = 4;
-static constexpr int kWM = 2;                                           // wavefront rows: 128 rows of x each
-static constexpr int kTM = 4, kTN = 2;                                  // 4 x 2 tiles of 32 x 32 per wavefront (128 x 64)
+static constexpr int kWM = 4;                                           // wavefront rows: 256 / kWM = 64 rows of x each
+static constexpr int kTM = kBM / kWM / 32, kTN = 2;                     // kTM x 2 tiles of 32 x 32 per wavefront
 static constexpr int kXBytes = kBM * kBK * 2;                           // 16 KB of x per buffer
 static constexpr int kStgPitch = 64 * 4 + 16;                          // fp32 staging row: 64 channels + pad
 
@@ -137,8 +140,11 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
     };
     // "at most 2 slices' worth outstanding": the oldest slice is in
     auto wait_oldest = [&]() {
-        if constexpr (2 * (XI + WI) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if constexpr (2 * (XI + WI) == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        constexpr int n = 2 * (XI + WI);
+        if constexpr (n == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if constexpr (n == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else if constexpr (n == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if constexpr (n == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
 
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
     int xoff[kTM], woff[kTN], xsw[kTM], wsw[kTN];
 #pragma unroll
     for (int i = 0; i < kTM; ++i) {
-        const int r = wm * 128 + i * 32 + l32;
+        const int r = wm * (32 * kTM) + i * 32 + l32;
         xoff[i] = r * 64;
         xsw[i] = (r >> 2) & 3;
     }
@@ -213,21 +219,26 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
     }
     // residual and mask rows of tile i + 1 are requested while tile i is finished (a workgroup is
     // alone on its CU: nothing else would cover their latency; it was most of a short-K layer's time)
-    u32x4 rres[2][4], rmsk[2][4];
+    u32x4 rres[kTM > 2 ? 2 : 1][4], rmsk[kTM > 2 ? 2 : 1][4];
     auto request = [&](int i, u32x4 (&rr)[4], u32x4 (&rm)[4]) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int m = m0 + wm * 128 + i * 32 + prow + 8 * t;
+            const int m = m0 + wm * (32 * kTM) + i * 32 + prow + 8 * t;
             const bool ok = m < M && chan < N;
             const size_t off = ((size_t)(ok ? m : 0) * N + (ok ? chan : 0)) * 2;
             rr[t] = rg ? *reinterpret_cast<const u32x4 *>(rg + off) : u32x4{0u, 0u, 0u, 0u};
             rm[t] = mg ? *reinterpret_cast<const u32x4 *>(mg + off) : u32x4{0u, 0u, 0u, 0u};
         }
     };
+    constexpr bool kAhead = kTM > 2;              // the 64-row wavefront tiles have no registers for a tile ahead
     request(0, rres[0], rmsk[0]);
 #pragma unroll
     for (int i = 0; i < kTM; ++i) {
-        if (i + 1 < kTM) request(i + 1, rres[(i + 1) & 1], rmsk[(i + 1) & 1]);
+        if constexpr (kAhead) {
+            if (i + 1 < kTM) request(i + 1, rres[(i + 1) & 1], rmsk[(i + 1) & 1]);
+        } else {
+            if (i > 0) request(i, rres[0], rmsk[0]);
+        }
         wave_lds_fence();
 #pragma unroll
         for (int j = 0; j < kTN; ++j)
@@ -241,7 +252,7 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int pr = prow + 8 * t;
-            const int m = m0 + wm * 128 + i * 32 + pr;
+            const int m = m0 + wm * (32 * kTM) + i * 32 + pr;
             if (m >= M || chan >= N) continue;
             const f32x4 f0 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32);
             const f32x4 f1 = *reinterpret_cast<const f32x4 *>(stg + pr * kStgPitch + cseg * 32 + 16);
@@ -250,7 +261,7 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
             for (int e = 0; e < 8; ++e) v[e] = v[e] * sc[e] + sh[e];
             const size_t off = ((size_t)m * N + chan) * 2;
             if (rg) {
-                const u32x4 rv = rres[i & 1][t];
+                const u32x4 rv = rres[kAhead ? (i & 1) : 0][t];
                 v[0] += lo16(rv.x); v[1] += hi16(rv.x); v[2] += lo16(rv.y); v[3] += hi16(rv.y);
                 v[4] += lo16(rv.z); v[5] += hi16(rv.z); v[6] += lo16(rv.w); v[7] += hi16(rv.w);
             }
@@ -264,7 +275,7 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
             u32x4 o;
             o.x = pack2(v[0], v[1]); o.y = pack2(v[2], v[3]); o.z = pack2(v[4], v[5]); o.w = pack2(v[6], v[7]);
             if (mg) {
-                const u32x4 mv = rmsk[i & 1][t];
+                const u32x4 mv = rmsk[kAhead ? (i & 1) : 0][t];
                 o.x = keep_where_positive_bf16(o.x, mv.x); o.y = keep_where_positive_bf16(o.y, mv.y);
                 o.z = keep_where_positive_bf16(o.z, mv.z); o.w = keep_where_positive_bf16(o.w, mv.w);
             }
@@ -294,7 +305,9 @@ int pick_bn(const ConvArgs &a) {
 
 template <int BN>
 hipError_t launch_bn(const ConvArgs &a, hipStream_t stream) {
-    constexpr size_t lds = (size_t)gemm::kStages * (gemm::kXBytes + BN * gemm::kBK * 2);
+    constexpr size_t pipe = (size_t)gemm::kStages * (gemm::kXBytes + BN * gemm::kBK * 2);
+    constexpr size_t stage_out = (size_t)gemm::kWM * (BN / 64) * 32 * gemm::kStgPitch;
+    constexpr size_t lds = pipe > stage_out ? pipe : stage_out;
     constexpr int threads = gemm::kWM * (BN / 64) * 64;
     const int tiles_m = (a.M + gemm::kBM - 1) / gemm::kBM, tiles_n = (a.Cout + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n;
