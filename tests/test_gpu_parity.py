@@ -330,3 +330,65 @@ def test_probes_report_plausible_rooflines(torch_mod):
     print("probes: d2h %.1f GB/s, h2d %.1f GB/s, hbm %.0f GB/s, mfma %.0f TFLOP/s" % (d2h, h2d, hbm, mfma), flush=True)
     assert 1 < d2h < 200 and 1 < h2d < 200 and 500 < hbm < 10000 and 100 < mfma < 3000
     d.close()
+
+
+def test_degenerate_inputs(torch_mod):
+    """Empty segments are no-ops; a one-pixel image and a one-row tensor go through every operator
+    family without touching memory outside their tensors (checked by guard bytes around them)."""
+    import paper_2203_15980_amd as dl
+    from oracle import opgranular as og
+    from oracle import transformer as ot
+    torch = torch_mod
+    d = make_delta(torch, 1 << 20)
+    # guard tensors 0, 2, 4, 6, 8 of 256 bytes around the working tensors
+    C = 64
+    row = C * 2
+    d.bind([256, row, 256, row, 256, 3 * row, 256, row, 256])
+    d.recompute_segment([])                                  # nothing to do
+    d.backward_segment([])
+    base = d.arena.data_ptr()
+    for t in range(9):
+        ptr = d.alloc(t)
+        n = [256, row, 256, row, 256, 3 * row, 256, row, 256][t]
+        d.arena[ptr - base:ptr - base + n] = 0xA5 if t % 2 == 0 else 0
+    x = synth.f32_to_bf16_bits(synth.normal(7, 1, C).astype(np.float32))
+    ptr = d.tensor_ptr(1)
+    d.arena[ptr - base:ptr - base + row].copy_(torch.from_numpy(x.view(np.uint8)).to("cuda:0"))
+    g = torch.ones(C, dtype=torch.float32, device="cuda:0")
+    z = torch.zeros(C, dtype=torch.float32, device="cuda:0")
+    w = synth.f32_to_bf16_bits((synth.normal(7, 2, C * C) / 8).astype(np.float32)).reshape(C, C)
+    wd = torch.from_numpy(w.view(np.uint8).reshape(-1)).to("cuda:0")
+    geo = dict(dtype=dl.DTYPE_BF16, N=1, H=1, W=1, Cin=C, Cout=C, R=1, S=1, stride=1, pad=0)
+    d.recompute_segment([
+        dl.LayerDesc(x=1, res=dl.NO_TENSOR, y=3, w=wd.data_ptr(), scale=g.data_ptr(), shift=z.data_ptr(), relu=1,
+                     op=dl.OP_CONV, **geo),                                          # one pixel through the 1x1 kernel
+        dl.LayerDesc(x=1, res=dl.NO_TENSOR, y=7, w=None, scale=g.data_ptr(), shift=z.data_ptr(), relu=0,
+                     op=dl.OP_LAYERNORM, eps=1e-5, **geo)])                          # one row
+    d.sync()
+
+    def get(t, n):
+        p = d.tensor_ptr(t)
+        return d.arena[p - base:p - base + n].cpu().numpy()
+
+    y = get(3, row).view(np.uint16)
+    ref = ot.linear(x.reshape(1, C), w, z.cpu().numpy(), act="relu", dtype="bf16")[0]
+    assert np.max(np.abs(ot.to_f64(y, "bf16") - ot.to_f64(ref, "bf16"))) <= 2e-2 * max(1e-6, np.max(np.abs(ot.to_f64(ref, "bf16"))))
+    ln = get(7, row).view(np.uint16)
+    ref_ln = ot.layernorm(x.reshape(1, C), np.ones(C, np.float32), np.zeros(C, np.float32), 1e-5, "bf16")[0]
+    assert np.max(np.abs(ot.to_f64(ln, "bf16") - ot.to_f64(ref_ln, "bf16"))) <= 2e-2
+    # batch normalisation over a single position: variance 0, the output is beta (= 0)
+    d.recompute_segment([dl.LayerDesc(x=1, res=dl.NO_TENSOR, y=3, w=None, scale=g.data_ptr(), shift=z.data_ptr(), relu=0,
+                                      op=dl.OP_BATCHNORM, eps=1e-5, **geo)])
+    d.sync()
+    assert np.array_equal(ot.to_f64(get(3, row).view(np.uint16), "bf16"), np.zeros(C))
+    # attention over a single position: the softmax of one score is 1, ctx = v
+    qkv = synth.f32_to_bf16_bits(synth.normal(7, 3, 3 * C).astype(np.float32))
+    p5 = d.tensor_ptr(5)
+    d.arena[p5 - base:p5 - base + 3 * row].copy_(torch.from_numpy(qkv.view(np.uint8)).to("cuda:0"))
+    d.recompute_segment([dl.LayerDesc(x=5, res=dl.NO_TENSOR, y=3, dtype=dl.DTYPE_BF16, w=None, scale=None, shift=None, N=1, H=1,
+                                      W=1, Cin=3 * C, Cout=C, R=1, S=1, stride=1, pad=0, relu=0, op=dl.OP_ATTENTION)])
+    d.sync()
+    assert np.array_equal(get(3, row).view(np.uint16), qkv[2 * C:])
+    for t in (0, 2, 4, 6, 8):                                # nothing wrote outside its tensor
+        assert (get(t, 256) == 0xA5).all(), t
+    d.close()
