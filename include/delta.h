@@ -297,8 +297,18 @@ delta_status delta_bwd_weights(delta_ctx *ctx, const delta_layer_desc *layer, vo
 delta_status delta_backward_workspace(delta_ctx *ctx, const delta_layer_desc *layer, uint64_t *out_bytes);
 /* Runs the descriptors in order on the compute stream.  Everything is validated before the first
  * launch.  Output tensors are allocated from the arena when not resident (DELTA_ERR_OOM_ARENA);
- * a non-resident input is DELTA_ERR_STATE. */
+ * a non-resident input is DELTA_ERR_STATE.
+ * Weight gradients of convolutions (gw) are the exception to "on the compute stream": nothing later
+ * in the backward pass reads them, so they run on a stream of the library's own, beside the
+ * data-gradient chain, each after the launches that produce its inputs.  The arena accounts for
+ * these readers when a tensor is released or rewritten.  The gw buffers and the workspace are the
+ * caller's: their contents are ordered for later work on the compute stream only after
+ * delta_backward_join (or complete after delta_sync with DELTA_SYNC_COMPUTE), and descriptors of one
+ * context must keep using the same workspace or join in between. */
 delta_status delta_backward_segment(delta_ctx *ctx, const delta_bwd_desc *descs, uint32_t n);
+/* Orders the compute stream after every weight gradient enqueued so far (no host wait): work given
+ * to the compute stream afterwards may read the gw buffers and reuse the workspace. */
+delta_status delta_backward_join(delta_ctx *ctx);
 
 /* Name of the kernel variant that delta_recompute_segment would launch for this layer (the
  * operator DELTA re-runs, Sec. 3 / Table 1), written NUL-terminated into out[0..cap).  Validates

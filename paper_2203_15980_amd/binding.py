@@ -24,7 +24,7 @@ EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "d
            "delta_recompute_segment", "delta_sync", "delta_bn_fold", "delta_stats",
            "delta_stats_reset", "delta_set_skip_copies", "delta_probe_hostlink",
            "delta_probe_hbm", "delta_probe_mfma", "delta_layer_kernel", "delta_bwd_weights",
-           "delta_backward_workspace", "delta_backward_segment"]
+           "delta_backward_workspace", "delta_backward_segment", "delta_backward_join"]
 
 
 class TensorDesc(C.Structure):
@@ -127,6 +127,7 @@ def load_library():
         "delta_bwd_weights": (i32, [vp, C.POINTER(LayerDesc), vp]),
         "delta_backward_workspace": (i32, [vp, C.POINTER(LayerDesc), C.POINTER(u64)]),
         "delta_backward_segment": (i32, [vp, C.POINTER(BwdDesc), u32]),
+        "delta_backward_join": (i32, [vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -261,6 +262,9 @@ class Delta:
         """`descs`: a list of BwdDesc."""
         arr = (BwdDesc * len(descs))(*descs)
         self._check(self.lib.delta_backward_segment(self.ctx, arr, len(descs)))
+
+    def backward_join(self):
+        self._check(self.lib.delta_backward_join(self.ctx))
 
     def sync(self, which=SYNC_ALL):
         self._check(self.lib.delta_sync(self.ctx, which))

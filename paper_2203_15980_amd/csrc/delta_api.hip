@@ -31,7 +31,9 @@
 
 namespace {
 
-enum { S_COMPUTE = 0, S_D2H = 1, S_H2D = 2, N_STREAMS = 3 };
+// S_AUX carries the weight gradients of convolutions: nothing later in the backward pass reads
+// them, so they run beside the data-gradient chain instead of inside it.
+enum { S_COMPUTE = 0, S_D2H = 1, S_H2D = 2, S_AUX = 3, N_STREAMS = 4 };
 const uint64_t kAlign = 256;
 
 // An ordering event plus its position in the order of recording: of two events recorded on
@@ -60,6 +62,7 @@ struct Tensor {
     bool host_valid = false;
     Ev d2h_done;                    // last Offload copy of this tensor
     Ev h2d_done;                    // pending Reload the compute stream has not waited for
+    Ev aux_done;                    // last weight-gradient launch on S_AUX that reads this tensor
 };
 
 struct Timed {
@@ -73,7 +76,8 @@ struct delta_ctx {
     unsigned char *arena = nullptr;
     uint64_t arena_bytes = 0;
     int device = -1;
-    hipStream_t stream[N_STREAMS] = {nullptr, nullptr, nullptr};
+    hipStream_t stream[N_STREAMS] = {nullptr, nullptr, nullptr, nullptr};
+    Ev aux_tail;                                   // last launch on S_AUX the compute stream has not joined
     std::map<uint64_t, Block> free_blocks;         // offset -> block, coalesced
     std::map<uint64_t, uint64_t> used;             // offset -> size
     std::vector<Tensor> tensors;
@@ -158,11 +162,13 @@ delta_status harvest_timings(delta_ctx *c) {
     return DELTA_OK;
 }
 
-// After all three streams are idle every fence is satisfied: recycle the events.
+// After all streams are idle every fence is satisfied: recycle the events.
 void retire_events(delta_ctx *c) {
     for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it)
         it->second.fence = Fence();
-    for (size_t i = 0; i < c->tensors.size(); ++i) c->tensors[i].d2h_done = c->tensors[i].h2d_done = Ev();
+    for (size_t i = 0; i < c->tensors.size(); ++i)
+        c->tensors[i].d2h_done = c->tensors[i].h2d_done = c->tensors[i].aux_done = Ev();
+    c->aux_tail = Ev();
     c->ev_pool.insert(c->ev_pool.end(), c->ev_live.begin(), c->ev_live.end());
     c->ev_live.clear();
 }
@@ -277,7 +283,8 @@ delta_status drop_block(delta_ctx *c, Tensor &t) {
     if (r != DELTA_OK) return r;
     f.ev[S_D2H] = t.d2h_done;
     f.ev[S_H2D] = t.h2d_done;
-    t.h2d_done = Ev();
+    f.ev[S_AUX] = t.aux_done;
+    t.h2d_done = t.aux_done = Ev();
     arena_free(c, t.offset, f);
     t.resident = false;
     return DELTA_OK;
@@ -347,7 +354,8 @@ delta_status delta_create(void *arena_dev, uint64_t arena_bytes, void *compute_s
         c->st.arena_bytes = c->arena_bytes;
         c->stream[S_COMPUTE] = static_cast<hipStream_t>(compute_stream);
         if (hipStreamCreateWithFlags(&c->stream[S_D2H], hipStreamNonBlocking) != hipSuccess ||
-            hipStreamCreateWithFlags(&c->stream[S_H2D], hipStreamNonBlocking) != hipSuccess) {
+            hipStreamCreateWithFlags(&c->stream[S_H2D], hipStreamNonBlocking) != hipSuccess ||
+            hipStreamCreateWithFlags(&c->stream[S_AUX], hipStreamNonBlocking) != hipSuccess) {
             delete c;
             return DELTA_ERR_HIP;
         }
@@ -376,6 +384,7 @@ void delta_destroy(delta_ctx *c) {
         if (c->zeros) (void)hipFree(c->zeros);
         (void)hipStreamDestroy(c->stream[S_D2H]);
         (void)hipStreamDestroy(c->stream[S_H2D]);
+        (void)hipStreamDestroy(c->stream[S_AUX]);
     }
     delete c;
 }
@@ -653,6 +662,8 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
             if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
             if (ty.d2h_done)                        // an Offload copy may still be reading it
                 HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.d2h_done.e, 0));
+            if (ty.aux_done)                        // and so may a weight gradient
+                HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.aux_done.e, 0));
         }
         ty.host_valid = false;                      // the host copy, if any, is of older contents
         unsigned char *xp = c->arena + tx.offset, *yp = c->arena + ty.offset;
@@ -705,7 +716,10 @@ delta_status delta_sync(delta_ctx *c, uint32_t which) {
     if (r != DELTA_OK) return r;
     if (which == 0 || (which & ~(uint32_t)DELTA_SYNC_ALL)) return fail(c, DELTA_ERR_INVALID, "bad sync mask %u", which);
     if (which == DELTA_SYNC_ALL) return sync_all(c);
-    if (which & DELTA_SYNC_COMPUTE) HIP_TRY(c, hipStreamSynchronize(c->stream[S_COMPUTE]));
+    if (which & DELTA_SYNC_COMPUTE) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream[S_COMPUTE]));
+        HIP_TRY(c, hipStreamSynchronize(c->stream[S_AUX]));
+    }
     if (which & DELTA_SYNC_D2H) HIP_TRY(c, hipStreamSynchronize(c->stream[S_D2H]));
     if (which & DELTA_SYNC_H2D) HIP_TRY(c, hipStreamSynchronize(c->stream[S_H2D]));
     return DELTA_OK;
@@ -1013,8 +1027,18 @@ delta_status compute_writes(delta_ctx *c, Tensor &t) {
     } else {
         if ((r = compute_uses(c, t)) != DELTA_OK) return r;
         if (t.d2h_done) HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], t.d2h_done.e, 0));
+        if (t.aux_done) HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], t.aux_done.e, 0));
     }
     t.host_valid = false;
+    return DELTA_OK;
+}
+
+// Orders the compute stream after every weight gradient launched so far.
+delta_status join_aux(delta_ctx *c) {
+    if (c->aux_tail) {
+        HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], c->aux_tail.e, 0));
+        c->aux_tail = Ev();
+    }
     return DELTA_OK;
 }
 
@@ -1109,6 +1133,7 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
             Tensor &tx = c->tensors[L.x];
             if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
             fa.x = c->arena + tx.offset;
+            if ((r = join_aux(c)) != DELTA_OK) return r;          // the workspace is shared with the layers before
             HIP_TRY(c, delta::launch_stem_wgrad(fa, c->arena + c->tensors[D.gpre].offset, static_cast<float *>(D.gw),
                                                 D.workspace, D.workspace_bytes, s));
             c->st.recompute_flops += 2ull * (uint64_t)fa.M * 7 * 7 * 3 * 64;
@@ -1161,6 +1186,9 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         const bool direct = strided_1x1(L);
         const int outP = (L.H + 2 * L.pad - L.R) / L.stride + 1, outQ = (L.W + 2 * L.pad - L.S) / L.stride + 1;
         unsigned char *staging = direct ? static_cast<unsigned char *>(D.workspace) + partials_bytes(fa) : nullptr;
+        // A strided 1x1 layer stages both of its gradients in the workspace, which weight gradients
+        // still running on the other stream may be using: it waits for them and stays in line.
+        if (direct && (r = join_aux(c)) != DELTA_OK) return r;
         if (own_mask || (L.stride > 1 && !direct)) {
             Tensor &tgp = c->tensors[D.gpre];
             const unsigned char *yp = nullptr;
@@ -1178,6 +1206,11 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                                                           L.W, outP, outQ, L.Cout, L.stride, fa.bf16, s));
         }
         const unsigned char *gp = c->arena + c->tensors[D.gpre].offset;
+        Ev ready;
+        if (D.gw && !direct) {
+            if ((r = compute_uses(c, c->tensors[L.x])) != DELTA_OK) return r;
+            if ((r = new_event(c, s, &ready)) != DELTA_OK) return r;
+        }
         if (D.gx != DELTA_NO_TENSOR) {
             Tensor &tgx = c->tensors[D.gx];
             const unsigned char *addp = nullptr;
@@ -1207,13 +1240,27 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
             if (direct) {
                 HIP_TRY(c, delta::launch_subsample(fa.x, staging, L.N, L.H, L.W, outP, outQ, L.Cin, L.stride, fa.bf16, s));
                 fa.x = staging;
+                HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa), s));
+            } else {
+                // gpre and x are complete once the compute stream reaches `ready`; from there the
+                // weight gradient runs on its own stream, and both tensors remember that reader.
+                HIP_TRY(c, hipStreamWaitEvent(c->stream[S_AUX], ready.e, 0));
+                HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa),
+                                               c->stream[S_AUX]));
+                if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
+                tx.aux_done = c->tensors[D.gpre].aux_done = c->aux_tail;
             }
-            HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa), s));
             c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
         }
         c->st.recompute_launches += 1;
     }
     return DELTA_OK;
+}
+
+delta_status delta_backward_join(delta_ctx *c) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    return join_aux(c);
 }
 
 delta_status delta_layer_kernel(delta_ctx *c, const delta_layer_desc *layer, char *out, uint64_t cap) {

@@ -341,6 +341,7 @@ class Net:
         self.backward_begin()
         for l in reversed(self.layers):
             self.backward_layer(l, keep=keep)
+        self.delta.backward_join()                 # weight gradients are visible to the compute stream from here
 
     def backward_step(self, graph, k):
         """Backward step `k` of synth.fused_graph's step list: the loss first (when present),
@@ -354,6 +355,8 @@ class Net:
         elif j == 0:
             self.backward_begin()
         self.backward_layer(self.layers[len(self.layers) - 1 - j])
+        if j == len(self.layers) - 1:
+            self.delta.backward_join()
 
 
 def run_plan(net, graph, events, backward_proxy=None):
