@@ -497,3 +497,68 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
     assert checked == {"conv", "maxpool", "avgpool", "fc", "stem"}
     assert any(by_name[t[0]].stride == 2 for t in net.bwd_trace)
     d.close()
+
+
+def test_weight_gradient_survives_release_of_its_inputs(torch_mod):
+    """The weight gradient runs beside the compute stream.  Its inputs are released straight after
+    the launch and their blocks are handed to new tensors that the compute stream fills at once:
+    the arena must hold those writers back until the weight gradient has read.  Weight gradients
+    are a fixed function of the inputs, so the result must equal, bit for bit, that of a run
+    that waits before releasing anything."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    N, H, W, Cin, Cout, R = 16, 56, 56, 64, 64, 3         # a long weight gradient: 50k positions, 9 taps
+    l = synth.LayerSpec("wg", "conv", "x0", None, "wg", N, H, W, Cin, Cout, R, R, 1, 1, True)
+    l.index = 1
+    master = 17
+    x = synth.make_input(master, (N, H, W, Cin), "bf16")
+    p = synth.make_params(master, l, "bf16")
+    gy = synth.f32_to_bf16_bits(synth.normal(master, 902, x.size).astype(np.float32)).reshape(x.shape)
+    sz = x.nbytes
+    arena = torch.empty(6 * sz + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    # tensors: 0 x, 1 y, 2 gy, 3 gpre, 4 gx, 5..8 the tensors that take the four freed blocks
+    d.bind([sz] * 9)
+    base = d.arena.data_ptr()
+    view = lambda ptr: d.arena[ptr - base:ptr - base + sz]
+    w = _dev(torch, p["w"])
+    scale = torch.ones(Cout, dtype=torch.float32, device="cuda:0")
+    shift = torch.zeros(Cout, dtype=torch.float32, device="cuda:0")
+    fwd = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, dtype=dl.DTYPE_BF16, w=w.data_ptr(), scale=scale.data_ptr(),
+                       shift=shift.data_ptr(), N=N, H=H, W=W, Cin=Cin, Cout=Cout, R=R, S=R, stride=1, pad=1, relu=1)
+    wt = torch.empty(Cout * R * R * Cin, dtype=torch.uint16, device="cuda:0")
+    d.bwd_weights(fwd, wt.data_ptr())
+    ws_bytes = d.backward_workspace(fwd)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    xd, gyd = _dev(torch, x.view(np.uint8).reshape(-1)), _dev(torch, gy.view(np.uint8).reshape(-1))
+
+    def run(release_at_once):
+        for t, a in ((0, xd), (2, gyd)):
+            view(d.alloc(t)).copy_(a)
+        d.recompute_segment([fwd])
+        gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
+        desc = dl.BwdDesc(fwd=fwd, gy=2, gpre=3, gx=4, gx_add=dl.NO_TENSOR, mask_gx=0, gy_masked=0, wt=wt.data_ptr(),
+                          gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
+        d.backward_segment([desc])
+        if not release_at_once:
+            d.sync()
+        for t in (0, 3, 1, 2):                            # x and gpre are what the weight gradient reads
+            d.release(t, dl.EV_FREE)
+        if release_at_once:
+            for t in (5, 6, 7, 8):                        # best fit hands out the blocks just freed
+                view(d.alloc(t)).fill_(0x7F)              # bf16 3.4e38 / NaN patterns: any early write shows
+        d.backward_join()
+        out = gw.clone()                                  # on the compute stream, after the join
+        d.sync()
+        for t in (4, 5, 6, 7, 8):
+            if release_at_once or t == 4:
+                d.release(t, dl.EV_FREE)
+        d.sync()
+        return out.cpu().numpy()
+
+    ref = run(False)
+    assert np.isfinite(ref).all() and np.abs(ref).max() > 0
+    for rep in range(3):
+        got = run(True)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "repeat %d" % rep
+    d.close()
