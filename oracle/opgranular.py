@@ -12,9 +12,19 @@ float64 numpy, one plain step after the other:
     var_c = mean over (n, h, w) of (x[n,h,w,c] - mu_c)^2            (biased)
     y     = gamma_c (x - mu_c) / sqrt(var_c + eps) + beta_c
 
-Running statistics are not part of the activations the memory manager handles and are not
-modelled.  ReLU and the residual add are separate operators at this granularity; every stored
-tensor is rounded to the storage type where it is produced.
+Its backward is the chain rule through those three lines, in the order the same publication
+lists it (its Sec. 3): with xhat = (x - mu) / sqrt(var + eps), M = N H W positions per channel,
+
+    dxhat  = gy gamma_c
+    dvar_c = sum dxhat (x - mu_c) * (-1/2) (var_c + eps)^(-3/2)
+    dmu_c  = -sum dxhat / sqrt(var_c + eps)  +  dvar_c * (-2/M) sum (x - mu_c)
+    gx     = dxhat / sqrt(var_c + eps) + dvar_c * 2 (x - mu_c) / M + dmu_c / M
+    dgamma_c = sum gy xhat            dbeta_c = sum gy
+
+ReLU's backward passes gy where the stored output is positive.  Running statistics are not part
+of the activations the memory manager handles and are not modelled.  ReLU and the residual add
+are separate operators at this granularity; every stored tensor is rounded to the storage type
+where it is produced.
 
 Pins: tests/test_oracle_opgranular.py.
 """
@@ -24,18 +34,45 @@ from . import numeric as on
 from .transformer import to_storage
 
 
-def bn_train(x, gamma, beta, eps, dtype="bf16"):
-    """x [N,H,W,C] (storage); gamma, beta float32 [C].  Returns y (storage)."""
-    v = on.to_f64(x, dtype)
+def bn_train_f64(v, gamma, beta, eps):
+    """The operator on float64 values v [N,H,W,C], unrounded."""
     mu = v.mean(axis=(0, 1, 2), keepdims=True)
     var = ((v - mu) ** 2).mean(axis=(0, 1, 2), keepdims=True)
     g = np.asarray(gamma, dtype=np.float32).astype(np.float64)
     b = np.asarray(beta, dtype=np.float32).astype(np.float64)
-    return to_storage(g * (v - mu) / np.sqrt(var + float(eps)) + b, dtype)
+    return g * (v - mu) / np.sqrt(var + float(eps)) + b
+
+
+def bn_train(x, gamma, beta, eps, dtype="bf16"):
+    """x [N,H,W,C] (storage); gamma, beta float32 [C].  Returns y (storage)."""
+    return to_storage(bn_train_f64(on.to_f64(x, dtype), gamma, beta, eps), dtype)
+
+
+def bn_train_bwd(x, gamma, gy, eps, dtype="bf16"):
+    """Backward of bn_train.  x, gy [N,H,W,C] (storage); gamma float32 [C].
+    Returns (gx storage, dgamma float64 [C], dbeta float64 [C])."""
+    v, g = on.to_f64(x, dtype), on.to_f64(gy, dtype)
+    M = v.shape[0] * v.shape[1] * v.shape[2]
+    ax = (0, 1, 2)
+    gam = np.asarray(gamma, dtype=np.float32).astype(np.float64)
+    mu = v.mean(axis=ax, keepdims=True)
+    var = ((v - mu) ** 2).mean(axis=ax, keepdims=True)
+    ve = var + float(eps)
+    xhat = (v - mu) / np.sqrt(ve)
+    dxhat = g * gam
+    dvar = (dxhat * (v - mu)).sum(axis=ax, keepdims=True) * (-0.5) * ve ** (-1.5)
+    dmu = -(dxhat.sum(axis=ax, keepdims=True)) / np.sqrt(ve) + dvar * (-2.0 / M) * (v - mu).sum(axis=ax, keepdims=True)
+    gx = dxhat / np.sqrt(ve) + dvar * 2.0 * (v - mu) / M + dmu / M
+    return to_storage(gx, dtype), (g * xhat).sum(axis=ax), g.sum(axis=ax)
 
 
 def relu(x, dtype="bf16"):
     return to_storage(np.maximum(on.to_f64(x, dtype), 0.0), dtype)
+
+
+def relu_bwd(y, gy, dtype="bf16"):
+    """gx = gy where the stored output y is positive, else 0 (storage in, storage out)."""
+    return to_storage(np.where(on.to_f64(y, dtype) > 0, on.to_f64(gy, dtype), 0.0), dtype)
 
 
 def add(x, r, dtype="bf16"):

@@ -83,3 +83,67 @@ def test_chain_equals_the_fused_layer_when_the_statistics_are_given():
         assert err < 1e-4, (l.name, err)
     names = set(acts)
     assert {"b1.out.conv", "b1.out.bn", "b1.out.add", "b1.out.relu"} <= names or any(n.endswith(".add") for n in names)
+
+
+def test_bn_train_bwd_hand_computed():
+    # one channel, two positions x = [0, 2]: mu 1, var 1, eps 0 -> xhat = [-1, 1]; y does not change when
+    # x moves (two points always normalise to -1, +1), so gx = 0 whatever gy is
+    x = np.array([0, 2], np.float32).reshape(2, 1, 1, 1)
+    gy = np.array([3, -5], np.float32).reshape(2, 1, 1, 1)
+    gx, dg, db = og.bn_train_bwd(x, np.array([2], np.float32), gy, 0.0, "f32")
+    assert np.max(np.abs(on.to_f64(gx, "f32"))) < 1e-12
+    assert abs(dg[0] - (3 * -1 + -5 * 1)) < 1e-12 and abs(db[0] - (-2)) < 1e-12
+    # with eps = 3 the two points sit at -1/2, +1/2 and do move: y_i = gamma (x_i - mu) / sqrt(var + 3),
+    # var = d^2/4 with d = x1 - x0 = 2; y1 = gamma (d/2) / sqrt(d^2/4 + 3) -> dy1/dd = gamma * (3/2) / (d^2/4+3)^(3/2)
+    # = 2 * 1.5 / 8 = 0.375; dy0/dd = -0.375; dL/dd = gy1 * .375 - gy0 * .375 = -3; gx = [-dL/dd, dL/dd] = [3, -3]
+    gx, dg, db = og.bn_train_bwd(x, np.array([2], np.float32), gy, 3.0, "f32")
+    assert np.allclose(on.to_f64(gx, "f32").reshape(2), [3.0, -3.0], rtol=0, atol=1e-6)
+    assert abs(dg[0] - (3 * -0.5 + -5 * 0.5)) < 1e-12
+
+
+def test_bn_train_bwd_finite_differences_invariants_and_torch():
+    torch = pytest.importorskip("torch")
+    N, H, W, C = 2, 3, 4, 5
+    x = (synth.normal(83, 1, N * H * W * C).reshape(N, H, W, C) * 1.5 + 0.4).astype(np.float32)
+    gy = synth.normal(83, 2, N * H * W * C).reshape(N, H, W, C).astype(np.float32)
+    g = synth.uniform(83, 3, C, 0.5, 1.5).astype(np.float32)
+    b = synth.normal(83, 4, C, 0.0, 0.1).astype(np.float32)
+    eps = 1e-3
+    gx, dg, db = og.bn_train_bwd(x, g, gy, eps, "f32")
+    gx = on.to_f64(gx, "f32")
+    # central differences of L = sum gy * bn(x) on the unrounded forward, every element of x
+    v = x.astype(np.float64)
+    w = gy.astype(np.float64)
+    h = 1e-5
+    num = np.empty_like(v)
+    for i in np.ndindex(*v.shape):
+        vp, vm = v.copy(), v.copy()
+        vp[i] += h
+        vm[i] -= h
+        num[i] = ((w * og.bn_train_f64(vp, g, b, eps)).sum() - (w * og.bn_train_f64(vm, g, b, eps)).sum()) / (2 * h)
+    assert np.max(np.abs(gx - num)) < 1e-6
+    # gamma and beta by differences too (the forward is linear in both: exact up to the float32 rounding of g + 1, b + 1)
+    for c in range(C):
+        e = np.zeros(C, np.float32)
+        e[c] = 1
+        assert abs((w * (og.bn_train_f64(v, g + e, b, eps) - og.bn_train_f64(v, g, b, eps))).sum() - dg[c]) < 1e-5
+        assert abs((w * (og.bn_train_f64(v, g, b + e, eps) - og.bn_train_f64(v, g, b, eps))).sum() - db[c]) < 1e-5
+    # the output is unchanged by a shift or (eps = 0) a rescaling of a channel, so gx has no component along 1 or x - mu
+    gx0 = on.to_f64(og.bn_train_bwd(x, g, gy, 0.0, "f32")[0], "f32")
+    assert np.max(np.abs(gx.sum(axis=(0, 1, 2)))) < 1e-5
+    assert np.max(np.abs((gx0 * (v - v.mean(axis=(0, 1, 2)))).sum(axis=(0, 1, 2)))) < 1e-5
+    # PyTorch's CPU float64 autograd through its own batch-norm routine
+    xt = torch.from_numpy(x).double().permute(0, 3, 1, 2).requires_grad_(True)
+    gt = torch.from_numpy(g).double().requires_grad_(True)
+    bt = torch.from_numpy(b).double().requires_grad_(True)
+    yt = torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=eps)
+    (yt * torch.from_numpy(gy).double().permute(0, 3, 1, 2)).sum().backward()
+    assert np.max(np.abs(gx - xt.grad.permute(0, 2, 3, 1).numpy())) < 1e-6
+    assert np.max(np.abs(dg - gt.grad.numpy())) < 1e-9 and np.max(np.abs(db - bt.grad.numpy())) < 1e-9
+
+
+def test_relu_bwd_masks_on_the_stored_output():
+    y = synth.f32_to_bf16_bits(np.array([1.5, 0.0, -0.0, -2.0, 3e-39, 7.0], np.float32))
+    gy = synth.f32_to_bf16_bits(np.array([1, 2, 3, 4, 5, -6], np.float32))
+    got = on.to_f64(og.relu_bwd(y, gy, "bf16"), "bf16")
+    assert np.array_equal(got[[0, 1, 2, 3, 5]], [1, 0, 0, 0, -6])
