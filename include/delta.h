@@ -259,6 +259,11 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  *                      followed by Cout bias gradients (sum of gy over the images).
  *   DELTA_OP_SOFTMAX_CE  gx (bytes of the logits) = (softmax(z) - onehot(label)) / N; gy and gpre
  *                      must be DELTA_NO_TENSOR; needs fwd.x (logits) and fwd.res (labels) resident.
+ *   DELTA_OP_BATCHNORM (batch statistics, bf16) gx = a (gy - mean(gy) - (x - mu) S / ((var + eps) M)) per channel,
+ *                      a = gamma / sqrt(var + eps), S = sum gy (x - mu), M = N*H*W, mu and var recomputed
+ *                      from x; gw (optional, fp32) receives C values dgamma = S / sqrt(var + eps), then
+ *                      C values dbeta = sum gy.  Needs fwd.x resident; fwd.scale = gamma; gpre = gy.
+ *   DELTA_OP_RELU      (bf16) gx = gy * [y > 0] on the stored output; needs fwd.y resident; gpre = gy.
  *   the stem           (DELTA_OP_CONV, 7x7, stride 2, pad 3, 3 -> 64 channels, bf16): weight gradient only
  *                      (gw required, fp32 [64][7][7][3]; gx, gx_add must be unset); gpre (bytes of y) receives
  *                      gy * [y > 0] when fwd.relu, else gpre must be gy; needs fwd.x resident and a workspace.

@@ -852,7 +852,7 @@ delta_status need_identity_factors(delta_ctx *c) {
     return DELTA_OK;
 }
 
-enum BwdKind { BK_CONV, BK_DENSE, BK_MAXPOOL, BK_AVGPOOL, BK_LOSS, BK_STEM };
+enum BwdKind { BK_CONV, BK_DENSE, BK_MAXPOOL, BK_AVGPOOL, BK_LOSS, BK_STEM, BK_BATCHNORM, BK_RELU };
 
 bool is_stem(const delta_layer_desc &L) {
     return L.op == DELTA_OP_CONV && L.dtype == DELTA_DTYPE_BF16 && L.R == 7 && L.S == 7 && L.stride == 2 && L.pad == 3 &&
@@ -865,6 +865,8 @@ BwdKind bwd_kind(const delta_layer_desc &L) {
     if (L.op == DELTA_OP_MAXPOOL) return BK_MAXPOOL;
     if (L.op == DELTA_OP_AVGPOOL) return BK_AVGPOOL;
     if (L.op == DELTA_OP_SOFTMAX_CE) return BK_LOSS;
+    if (L.op == DELTA_OP_BATCHNORM) return BK_BATCHNORM;
+    if (L.op == DELTA_OP_RELU) return BK_RELU;
     if (is_stem(L)) return BK_STEM;
     if (L.H == 1 && L.W == 1 && L.R == 1 && L.S == 1 && L.stride == 1 && L.pad == 0 && L.Cout % 64 != 0) return BK_DENSE;
     return BK_CONV;
@@ -892,7 +894,8 @@ delta_status prepare_backward_stem(delta_ctx *c, const delta_bwd_desc &D, uint32
     return DELTA_OK;
 }
 
-// Pooling, classifier and loss: validation only (bf16).  gx is required; gpre must be gy; no gx_add.
+// Pooling, classifier, loss, batch normalisation with batch statistics and ReLU: validation only
+// (bf16).  gx is required; gpre must be gy; no gx_add.
 delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, BwdKind kind,
                                     delta::ConvArgs &fa, delta::PoolArgs &pa) {
     uint64_t flops = 0;
@@ -918,8 +921,10 @@ delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint3
     if (kind == BK_DENSE) {
         if (L.relu || L.res != DELTA_NO_TENSOR) return fail(c, DELTA_ERR_INVALID, "backward %u: classifier with ReLU or residual", i);
         if (D.gw && ((uintptr_t)D.gw & 15)) return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned", i);
+    } else if (kind == BK_BATCHNORM) {
+        if (D.gw && ((uintptr_t)D.gw & 15)) return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned", i);
     } else if (D.gw) {
-        return fail(c, DELTA_ERR_INVALID, "backward %u: pooling has no weights", i);
+        return fail(c, DELTA_ERR_INVALID, "backward %u: this operator has no weights", i);
     }
     return DELTA_OK;
 }
@@ -1096,8 +1101,9 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
             delta::PoolArgs pa;
             if ((r = prepare_backward_other(c, D, i, kind, fa, pa)) != DELTA_OK) return r;
             if (kind != BK_LOSS && !there(D.gy)) return fail(c, DELTA_ERR_STATE, "backward %u: gy tensor %u is not resident", i, D.gy);
-            const bool needs_x = kind == BK_MAXPOOL || kind == BK_LOSS || (kind == BK_DENSE && D.gw);
+            const bool needs_x = kind == BK_MAXPOOL || kind == BK_LOSS || kind == BK_BATCHNORM || (kind == BK_DENSE && D.gw);
             if (needs_x && !there(D.fwd.x)) return fail(c, DELTA_ERR_STATE, "backward %u: x tensor %u is not resident", i, D.fwd.x);
+            if (kind == BK_RELU && !there(D.fwd.y)) return fail(c, DELTA_ERR_STATE, "backward %u: y tensor %u is not resident", i, D.fwd.y);
             if (kind == BK_LOSS && !there(D.fwd.res)) return fail(c, DELTA_ERR_STATE, "backward %u: labels are not resident", i);
             if (D.gx != DELTA_NO_TENSOR) will_exist[D.gx] = 1;
             continue;
@@ -1169,6 +1175,17 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 Tensor &tl = c->tensors[L.res];
                 if ((r = compute_uses(c, tl)) != DELTA_OK) return r;
                 HIP_TRY(c, delta::launch_softmax_ce_bwd(xp, c->arena + tl.offset, L.N, L.Cin, gxp, s));
+                break;
+            }
+            case BK_BATCHNORM:
+                if (!c->bn_scratch) HIP_TRY(c, hipMalloc(&c->bn_scratch, delta::bn_train_scratch_bytes()));
+                HIP_TRY(c, delta::launch_bn_train_bwd(xp, gyp, gxp, L.scale, static_cast<float *>(D.gw),
+                                                      (long long)L.N * L.H * L.W, L.Cin, L.eps, 1, c->bn_scratch, s));
+                break;
+            case BK_RELU: {
+                Tensor &ty = c->tensors[L.y];
+                if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+                HIP_TRY(c, delta::launch_relu_mask(c->arena + ty.offset, gyp, gxp, c->tensors[D.gy].bytes, 1, s));
                 break;
             }
             default:

@@ -58,6 +58,8 @@ const char *bn_train_check(const void *x, const void *y, const float *gamma, con
 size_t bn_train_scratch_bytes();
 hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const float *beta, long long M, int C, float eps,
                            int bf16, void *scratch, hipStream_t stream);
+hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const float *gamma, float *gw, long long M, int C,
+                               float eps, int bf16, void *scratch, hipStream_t stream);
 hipError_t launch_relu(const void *x, void *y, size_t bytes, int bf16, hipStream_t stream);
 hipError_t launch_add(const void *x, const void *r, void *y, size_t bytes, int bf16, hipStream_t stream);
 // net_ops.hip: ResNet stem (7x7, stride 2, pad 3, 3 -> 64 channels, bf16), pooling, loss

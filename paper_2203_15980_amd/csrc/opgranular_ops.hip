@@ -13,6 +13,15 @@
 //                       mean, biased variance and a = gamma / sqrt(var + eps)
 //   bn_apply_kernel     y = a_c (x - mean_c) + beta_c   (centred first: no cancellation of two large products)
 // No atomics: the result is a fixed function of the input (recomputation is bit-identical).
+// Backward of the batch normalisation (chain rule through the three lines above, collapsed):
+//   gx = a_c (gy - mean(gy)_c - (x - mu_c) S_c / ((var_c + eps) M)),   S_c = sum gy (x - mu_c)
+//   dgamma_c = S_c / sqrt(var_c + eps),   dbeta_c = sum gy
+// reads x and gy twice and writes gx once, the floor without stored statistics (x has to be read
+// for S_c in any case):
+//   bn_bwd_stats_kernel     sums of (x - K_c), (x - K_c)^2, gy, gy (x - K_c) per channel and workgroup
+//   bn_bwd_finalize_kernel  adds the partials (double), forms a, mu, mean(gy), S/((var + eps) M) and
+//                           the two parameter gradients
+//   bn_bwd_apply_kernel     gx from x, gy and the four per-channel factors
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -172,6 +181,169 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const u32x4 *__restrict__
     }
 }
 
+
+// Backward statistics.  Same decomposition as bn_stats_kernel; partial: [gridDim.x][4][C] floats
+// (sum d, sum d^2, sum g, sum g d with d = x - K_c).  red: [RS][CH][32].
+__global__ __launch_bounds__(256) void bn_bwd_stats_kernel(const unsigned char *x, const unsigned char *g, float *partial,
+                                                           long long M, int C, long long rows_per_block, int CH, int RS) {
+    extern __shared__ __align__(16) float red[];
+    const int chunks = C / 8;
+    const int t = threadIdx.x;
+    const int ck0 = t % CH, rsub = t / CH;
+    const long long r0 = (long long)blockIdx.x * rows_per_block;
+    long long r1 = r0 + rows_per_block;
+    if (r1 > M) r1 = M;
+    for (int cg = 0; cg < chunks; cg += CH) {
+        const int ck = cg + ck0;
+        const bool live = ck < chunks && rsub < RS;
+        float s1[8], s2[8], s3[8], s4[8], k[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s1[e] = s2[e] = s3[e] = s4[e] = 0.f;
+        if (live) {
+            unpack8(*reinterpret_cast<const u32x4 *>(x + (size_t)ck * 16), k);
+            long long r = r0 + rsub;
+            for (; r + (long long)RS < r1; r += 2LL * RS) {       // two rows of both tensors in flight per lane
+                u32x4 rx[2], rg[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const size_t at = ((size_t)(r + (long long)u * RS) * chunks + ck) * 16;
+                    rx[u] = *reinterpret_cast<const u32x4 *>(x + at);
+                    rg[u] = *reinterpret_cast<const u32x4 *>(g + at);
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    float v[8], w[8];
+                    unpack8(rx[u], v);
+                    unpack8(rg[u], w);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float d = v[e] - k[e];
+                        s1[e] += d;
+                        s2[e] += d * d;
+                        s3[e] += w[e];
+                        s4[e] += w[e] * d;
+                    }
+                }
+            }
+            for (; r < r1; r += RS) {
+                const size_t at = ((size_t)r * chunks + ck) * 16;
+                float v[8], w[8];
+                unpack8(*reinterpret_cast<const u32x4 *>(x + at), v);
+                unpack8(*reinterpret_cast<const u32x4 *>(g + at), w);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float d = v[e] - k[e];
+                    s1[e] += d;
+                    s2[e] += d * d;
+                    s3[e] += w[e];
+                    s4[e] += w[e] * d;
+                }
+            }
+        }
+        if (cg) __syncthreads();
+        if (rsub < RS) {
+            float *p = red + ((size_t)rsub * CH + ck0) * 32;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { p[e] = s1[e]; p[8 + e] = s2[e]; p[16 + e] = s3[e]; p[24 + e] = s4[e]; }
+        }
+        __syncthreads();
+        if (rsub == 0 && ck < chunks) {
+            float a[4][8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[q][e] = 0.f;
+            for (int j = 0; j < RS; ++j) {                       // fixed order
+                const float *p = red + ((size_t)j * CH + ck0) * 32;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) a[q][e] += p[q * 8 + e];
+            }
+            float *o = partial + (size_t)blockIdx.x * 4 * C + ck * 8;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[(size_t)q * C + e] = a[q][e];
+        }
+    }
+}
+
+// coef: [4][C]: a, mean, mean(gy), S / ((var + eps) M).  gw (may be null): dgamma [C], then dbeta [C].
+__global__ __launch_bounds__(1024) void bn_bwd_finalize_kernel(const unsigned char *x, const float *partial,
+                                                               const float *gamma, float *coef, float *gw, long long M,
+                                                               int C, int blocks, float eps) {
+    __shared__ double red[4][16][64];
+    const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cl;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    if (c < C) {
+        int b = grp;
+        for (; b + 3 * 16 < blocks; b += 4 * 16) {
+            float p[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) p[u][q] = partial[((size_t)(b + 16 * u) * 4 + q) * C + c];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s[q] += (double)p[u][q];
+        }
+        for (; b < blocks; b += 16)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) s[q] += (double)partial[((size_t)b * 4 + q) * C + c];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[q][grp][cl] = s[q];
+    __syncthreads();
+    if (grp != 0 || c >= C) return;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        s[q] = 0.0;
+        for (int g = 0; g < 16; ++g) s[q] += red[q][g][cl];
+    }
+    const double k = (double)__uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(x)[c] << 16);
+    const double md = s[0] / (double)M;
+    double var = s[1] / (double)M - md * md;
+    if (var < 0.0) var = 0.0;
+    const double ve = var + (double)eps;
+    const double S = s[3] - md * s[2];                           // sum gy (x - mean)
+    coef[c] = (float)((double)gamma[c] / sqrt(ve));
+    coef[C + c] = (float)(k + md);
+    coef[2 * C + c] = (float)(s[2] / (double)M);
+    coef[3 * C + c] = (float)(S / (ve * (double)M));
+    if (gw) {
+        gw[c] = (float)(S / sqrt(ve));
+        gw[C + c] = (float)s[2];
+    }
+}
+
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ g,
+                                                           u32x4 *__restrict__ gx, const float *__restrict__ coef, int C,
+                                                           size_t n16) {
+    const int chunks = C / 8;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const int ck = (int)(i % chunks);
+        float v[8], w[8], o[8];
+        unpack8(x[i], v);
+        unpack8(g[i], w);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const f32x4 a = *reinterpret_cast<const f32x4 *>(coef + ck * 8 + 4 * h);
+            const f32x4 m = *reinterpret_cast<const f32x4 *>(coef + C + ck * 8 + 4 * h);
+            const f32x4 c1 = *reinterpret_cast<const f32x4 *>(coef + 2 * C + ck * 8 + 4 * h);
+            const f32x4 c2 = *reinterpret_cast<const f32x4 *>(coef + 3 * C + ck * 8 + 4 * h);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[4 * h + e] = a[e] * (w[4 * h + e] - c1[e] - (v[4 * h + e] - m[e]) * c2[e]);
+        }
+        u32x4 r;
+        r.x = pack2(o[0], o[1]); r.y = pack2(o[2], o[3]); r.z = pack2(o[4], o[5]); r.w = pack2(o[6], o[7]);
+        gx[i] = r;
+    }
+}
+
 // y = max(x, 0): a negative bf16 has its sign bit set (NaN passes through, as in the fused epilogue)
 __global__ __launch_bounds__(256) void relu_kernel(const u32x4 *__restrict__ x, u32x4 *__restrict__ y, size_t n16) {
     const size_t step = (size_t)gridDim.x * blockDim.x;
@@ -245,6 +417,37 @@ hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const flo
     const size_t n16 = (size_t)M * chunks;
     ops::bn_apply_kernel<<<dim3(ops::stream_blocks(n16)), dim3(256), 0, stream>>>(
         static_cast<const ops::u32x4 *>(x), static_cast<ops::u32x4 *>(y), ab, beta, C, n16);
+    return hipGetLastError();
+}
+
+// Backward of launch_bn_train.  gw: device fp32 [2][C] (dgamma, dbeta) or null.  Same scratch.
+hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const float *gamma, float *gw, long long M, int C,
+                               float eps, int bf16, void *scratch, hipStream_t stream) {
+    if (bn_train_check(x, gx, gamma, gamma, M, C, bf16) || !gy || ((uintptr_t)gy & 15) || ((uintptr_t)gw & 15) || !scratch ||
+        ((uintptr_t)scratch & 15))
+        return hipErrorInvalidValue;
+    const int chunks = C / 8;
+    const int CH = chunks < 256 ? chunks : 256;
+    const int RS = 256 / CH;
+    float *coef = static_cast<float *>(scratch);                 // [4][C]
+    float *partial = coef + 4 * (size_t)C;
+    const size_t room = (bn_train_scratch_bytes() - 4 * (size_t)C * 4) / ((size_t)4 * C * 4);
+    long long blocks = (M + (long long)RS * 4 - 1) / ((long long)RS * 4);
+    long long cap = 131072 / C;
+    cap = cap < 64 ? 64 : (cap > 2048 ? 2048 : cap);
+    if (blocks > cap) blocks = cap;
+    if (blocks > (long long)room) blocks = (long long)room;
+    if (blocks < 1) return hipErrorInvalidValue;
+    const long long rpb = (M + blocks - 1) / blocks;
+    blocks = (M + rpb - 1) / rpb;
+    const size_t lds = (size_t)RS * CH * 32 * 4;
+    ops::bn_bwd_stats_kernel<<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(
+        static_cast<const unsigned char *>(x), static_cast<const unsigned char *>(gy), partial, M, C, rpb, CH, RS);
+    ops::bn_bwd_finalize_kernel<<<dim3((unsigned)((C + 63) / 64)), dim3(1024), 0, stream>>>(
+        static_cast<const unsigned char *>(x), partial, gamma, coef, gw, M, C, (int)blocks, eps);
+    const size_t n16 = (size_t)M * chunks;
+    ops::bn_bwd_apply_kernel<<<dim3(ops::stream_blocks(n16)), dim3(256), 0, stream>>>(
+        static_cast<const ops::u32x4 *>(x), static_cast<const ops::u32x4 *>(gy), static_cast<ops::u32x4 *>(gx), coef, C, n16);
     return hipGetLastError();
 }
 

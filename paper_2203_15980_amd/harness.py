@@ -394,10 +394,11 @@ class OpNet:
     """A ResNet at OPERATOR granularity (synth.opgranular_graph): convolution, batch normalisation
     with the statistics of the batch, residual add and ReLU are separate launches and separate
     tensors (bf16).  Same interface as Net towards run_plan (delta, desc, sources, load_source).
-    There are no backward kernels at this granularity: a backward step runs the compute proxy
-    (the operator's forward kernel twice into a scratch tensor) where the access trace gives it
-    its input, and nothing for the operators whose backward reads no activation (add, average
-    pool) or for the loss."""
+    Backward, either of two: `enable_backward` - every operator's own backward kernel (convolution
+    data and weight gradients, batch normalisation through its batch statistics, ReLU mask,
+    pooling, classifier, loss; the add only hands its gradient to both inputs), reading exactly the
+    activations the access trace of synth.opgranular_graph names; or `enable_backward_proxy` - the
+    operator's forward kernel twice into a scratch tensor where the trace gives it an input."""
 
     def __init__(self, delta, layers, master, device="cuda:0", with_loss=True):
         self.delta, self.layers, self.master, self.device = delta, layers, master, device
@@ -417,13 +418,18 @@ class OpNet:
         self.keep += [ones, zeros]
         self.op_names = []                        # in production order
         self.proxy_src = {}                       # op tensor -> the tensor its proxy reads (None: no proxy)
+        self.op_inputs = {}                       # op tensor -> (x tensor name, second input's name or None)
+        self.op_layer = {}                        # op tensor -> the LayerSpec it comes from
         alias = {"x0": "x0"}
+        names_by_id = {v: k for k, v in self.ids.items()}
 
         def emit(name, shape, proxy_x, **kw):
             self.desc[name] = B.layer_array([B.LayerDesc(y=self.ids[name], dtype=code, **kw)])
             self.shapes[name], self.np_dtype[name] = shape, np.uint16
             self.op_names.append(name)
             self.proxy_src[name] = proxy_x
+            self.op_inputs[name] = (names_by_id[kw["x"]], names_by_id[kw["res"]] if kw["res"] != B.NO_TENSOR else None)
+            self.op_layer[name] = l
 
         for l in layers:
             xin = alias[l.x]
@@ -522,3 +528,157 @@ class OpNet:
         self.delta.recompute_segment(arr)
         self.delta.recompute_segment(arr)
         self.delta.release(sid, B.EV_FREE)
+
+    # ---------------------------------------------------------------- true backward
+    def _kind(self, name):
+        op = self.desc[name][0].op
+        if op == B.OP_CONV:
+            return "fc" if self.op_layer[name].kind == "fc" else "conv"
+        return {B.OP_BATCHNORM: "bn", B.OP_RELU: "relu", B.OP_ADD: "add", B.OP_MAXPOOL: "maxpool",
+                B.OP_AVGPOOL: "avgpool"}[op]
+
+    def _dilated(self, name):
+        """A strided convolution wider than 1x1 (the stem aside, which has no data gradient)."""
+        l = self.op_layer[name]
+        return self._kind(name) == "conv" and l.stride > 1 and l.R > 1 and self.op_inputs[name][0] != "x0"
+
+    def enable_backward(self):
+        """Adds the gradient tensors to the tensor table (re-binds: call while nothing is
+        resident), prepares the data gradients' weights and allocates the parameter gradients
+        (outside the arena, fp32) and the workspace.  The network's input gets no gradient."""
+        d, dev = self.delta, self.device
+        self.n_graph = len(self.sizes)
+        extra = []
+
+        def new_tensor(name, like):
+            self.ids[name] = self.n_graph + len(extra)
+            extra.append(self.sizes[self.ids[like]])
+            self.shapes[name], self.np_dtype[name] = self.shapes[like], np.uint16
+
+        top = self.op_names[-1]
+        if not self.with_loss:
+            raise ValueError("the operator-granular backward starts from the loss")
+        new_tensor("g:" + top, top)
+        for name in self.op_names:
+            x, res = self.op_inputs[name]
+            if self._kind(name) != "add" and x != "x0":
+                new_tensor("g:" + x + ":" + name, x)
+            if self._dilated(name):               # dL/dy spread to the input's resolution
+                l = self.op_layer[name]
+                self.ids["gp:" + name] = self.n_graph + len(extra)
+                extra.append(l.N * l.H * l.W * l.Cout * 2)
+                self.shapes["gp:" + name], self.np_dtype["gp:" + name] = (l.N, l.H, l.W, l.Cout), np.uint16
+        self.sizes = self.sizes + extra
+        d.bind(self.sizes)
+        self.wt, self.gw = {}, {}
+        ws_bytes = 16
+        for name in self.op_names:
+            kind, fwd, l = self._kind(name), self.desc[name][0], self.op_layer[name]
+            if kind == "fc":
+                self.gw[name] = torch.zeros(l.Cout * l.Cin + l.Cout, dtype=torch.float32, device=dev)
+            elif kind == "bn":
+                self.gw[name] = torch.zeros(2 * l.Cout, dtype=torch.float32, device=dev)
+            elif kind == "conv":
+                n = l.Cout * l.R * l.S * l.Cin
+                if self.op_inputs[name][0] != "x0":
+                    self.wt[name] = torch.empty(n * 2, dtype=torch.uint8, device=dev)
+                    d.bwd_weights(fwd, self.wt[name].data_ptr())
+                self.gw[name] = torch.zeros(n, dtype=torch.float32, device=dev)
+                ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
+        self.bwd_workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+
+    def _bwd_plan(self, name, pending, refs):
+        """Bookkeeping of one operator's backward given `pending` (tensor -> name of the gradient
+        accumulated so far) and `refs` (gradient tensor -> readers left).  No GPU call.
+        Returns (gy, gx, add, dead gradient tensors)."""
+        kind = self._kind(name)
+        x, res = self.op_inputs[name]
+        gy = pending.pop(name)
+        dead = []
+        if kind == "add":                          # both inputs receive gy itself
+            for t in (x, res):
+                if t in pending:
+                    raise ValueError("gradient accumulation at %s would need an add kernel" % t)
+                pending[t] = gy
+            refs[gy] += 1                          # one reader became two
+            return gy, None, None, dead
+        gx = add = None
+        if x != "x0":
+            gx = "g:" + x + ":" + name
+            add = pending.get(x)
+            if add is not None and kind != "conv":
+                raise ValueError("gradient accumulation at the input of %s needs an add kernel" % name)
+            pending[x] = gx
+            refs[gx] = 1
+            if add is not None:
+                refs[add] -= 1
+                if refs[add] == 0:
+                    dead.append(add)
+        refs[gy] -= 1
+        if refs[gy] == 0:
+            dead.append(gy)
+        return gy, gx, add, dead
+
+    def backward_peak_bytes(self):
+        """Largest sum of gradient-tensor bytes alive at once during the backward pass (dry run)."""
+        first = "g:" + self.op_names[-1]
+        pending, refs = {self.op_names[-1]: first}, {first: 1}
+        live = {first}
+        size = lambda n: self.sizes[self.ids[n]]
+        peak = size(first)
+        for name in reversed(self.op_names):
+            gy, gx, add, dead = self._bwd_plan(name, pending, refs)
+            if gx:
+                live.add(gx)
+            peak = max(peak, sum(size(n) for n in live) + (size("gp:" + name) if self._dilated(name) else 0))
+            live.difference_update(dead)
+        return peak
+
+    def backward_begin(self):
+        first = "g:" + self.op_names[-1]
+        desc = B.BwdDesc(fwd=self.desc["loss"][0], gy=B.NO_TENSOR, gpre=B.NO_TENSOR, gx=self.ids[first],
+                         gx_add=B.NO_TENSOR, wt=None, gw=None, workspace=None, workspace_bytes=0)
+        self.delta.backward_segment([desc])
+        self.pending, self.refs = {self.op_names[-1]: first}, {first: 1}
+        self.bwd_trace = []
+
+    def backward_op(self, name, keep=False):
+        """Backward of the operator that produces `name` (all its consumers have run theirs)."""
+        d = self.delta
+        gy, gx, add, dead = self._bwd_plan(name, self.pending, self.refs)
+        kind = self._kind(name)
+        self.bwd_trace.append((name, kind, gy, gx, add))
+        if kind != "add":
+            conv = kind == "conv"
+            gpre = "gp:" + name if self._dilated(name) else gy
+            if gpre != gy:
+                dead = dead + [gpre]
+            desc = B.BwdDesc(fwd=self.desc[name][0], gy=self.ids[gy], gpre=self.ids[gpre],
+                             gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
+                             mask_gx=0, gy_masked=0,
+                             wt=self.wt[name].data_ptr() if name in self.wt else None,
+                             gw=self.gw[name].data_ptr() if name in self.gw else None,
+                             workspace=self.bwd_workspace.data_ptr() if conv else None,
+                             workspace_bytes=self.bwd_workspace.numel() if conv else 0)
+            d.backward_segment([desc])
+        if not keep:
+            for g in dead:
+                d.release(self.ids[g], B.EV_FREE)
+
+    def backward(self, keep=False):
+        self.backward_begin()
+        for name in reversed(self.op_names):
+            self.backward_op(name, keep=keep)
+        self.delta.backward_join()
+
+    def backward_step(self, graph, k):
+        """Backward step `k` of synth.opgranular_graph's step list: the loss, then the operators in
+        reverse order.  For use as run_plan's backward callback."""
+        j = k - graph.n_fwd
+        if j == 0:
+            self.backward_begin()
+            return
+        self.backward_op(self.op_names[len(self.op_names) - j])
+        if j == len(self.op_names):
+            self.delta.backward_join()

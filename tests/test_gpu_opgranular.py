@@ -196,3 +196,158 @@ def test_operator_granular_plan_replay(torch_mod):
     d.sync()
     assert d.stats()["arena_in_use"] == 0
     d.close()
+
+
+# ------------------------------------------------------------------------------- backward
+
+BN_BWD = [(2, 7, 7, 64), (3, 5, 9, 24), (1, 1, 2, 8), (4, 30, 30, 256), (2, 3, 3, 2048), (16, 56, 56, 64)]
+
+
+@pytest.mark.parametrize("shape", BN_BWD, ids=lambda s: "x".join(map(str, s)))
+def test_batchnorm_backward_matches_oracle(torch_mod, shape):
+    """gx stored in bf16 from fp32 arithmetic on double-precision channel factors: 2e-2 / 4 of its
+    maximum; dgamma, dbeta fp32 from fp32 partial sums combined in double: 2e-4 of their maximum
+    (plus 1e-6 of sum |gy|, the rounding floor of a sum that nearly cancels)."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    print("shape", shape, flush=True)
+    N, H, W, C = shape
+    x = _bits(94, 1, shape, 2.0, 3.0)
+    gy = _bits(94, 4, shape, 0.5, 0.1)
+    gamma = synth.uniform(94, 2, C, 0.5, 1.5).astype(np.float32)
+    d, put, get = _ctx(torch, [x.nbytes] * 4, 64)
+    put(0, x)
+    put(1, gy)
+    g = _dev(torch, gamma)
+    gw = torch.full((2 * C,), float("nan"), dtype=torch.float32, device="cuda:0")
+    fwd = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=3, dtype=dl.DTYPE_BF16, w=None, scale=g.data_ptr(), shift=g.data_ptr(),
+                       N=N, H=H, W=W, Cin=C, Cout=C, R=1, S=1, stride=1, pad=0, relu=0, op=dl.OP_BATCHNORM, eps=1e-5)
+    desc = dl.BwdDesc(fwd=fwd, gy=1, gpre=1, gx=2, gx_add=dl.NO_TENSOR, mask_gx=0, gy_masked=0, wt=None,
+                      gw=gw.data_ptr(), workspace=None, workspace_bytes=0)
+    d.backward_segment([desc])
+    d.sync()
+    first = get(2, shape).copy()
+    ref_gx, ref_dg, ref_db = og.bn_train_bwd(x, gamma, gy, 1e-5, "bf16")
+    err = _relerr(on.to_f64(first, "bf16"), on.to_f64(ref_gx, "bf16"))
+    got_w = gw.cpu().numpy().astype(np.float64)
+    floor = 1e-6 * np.abs(on.to_f64(gy, "bf16")).sum(axis=(0, 1, 2)).max()
+    eg = np.max(np.abs(got_w[:C] - ref_dg)) / (np.max(np.abs(ref_dg)) + floor)
+    eb = np.max(np.abs(got_w[C:] - ref_db)) / (np.max(np.abs(ref_db)) + floor)
+    print("  gx %.2e dgamma %.2e dbeta %.2e" % (err, eg, eb), flush=True)
+    assert err <= 2e-2 / 4 and eg <= 2e-4 and eb <= 2e-4, (shape, err, eg, eb)
+    d.backward_segment([desc])                             # fixed reduction order: the same bits again
+    d.sync()
+    assert np.array_equal(get(2, shape), first) and np.array_equal(gw.cpu().numpy().astype(np.float64), got_w)
+    d.close()
+
+
+def test_relu_backward_and_rejects(torch_mod):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    shape = (3, 5, 7, 24)
+    y = og.relu(_bits(95, 1, shape), "bf16")
+    y.reshape(-1)[:3] = [0x8000, 0x7FC0, 0x0001]           # -0, NaN, the smallest positive value
+    gy = _bits(95, 2, shape)
+    d, put, get = _ctx(torch, [y.nbytes] * 4, 16)
+    put(1, y)
+    put(2, gy)
+    geo = dict(dtype=dl.DTYPE_BF16, w=None, scale=None, shift=None, N=3, H=5, W=7, Cin=24, Cout=24, R=1, S=1, stride=1,
+               pad=0, relu=0)
+    fwd = dl.LayerDesc(x=0, res=dl.NO_TENSOR, y=1, op=dl.OP_RELU, **geo)     # x is not resident: not read
+    mk = lambda **kw: dl.BwdDesc(**{**dict(fwd=fwd, gy=2, gpre=2, gx=3, gx_add=dl.NO_TENSOR, mask_gx=0, gy_masked=0, wt=None,
+                                           gw=None, workspace=None, workspace_bytes=0), **kw})
+    d.backward_segment([mk()])
+    d.sync()
+    got, ref = get(3, shape), og.relu_bwd(y, gy, "bf16")
+    assert np.array_equal(got.reshape(-1)[3:], ref.reshape(-1)[3:])
+    assert list(got.reshape(-1)[:3]) == [0, 0, gy.reshape(-1)[2]]
+    g = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    bn = dl.LayerDesc(x=1, res=dl.NO_TENSOR, y=0, op=dl.OP_BATCHNORM, eps=1e-5,
+                      **{**geo, "scale": g.data_ptr(), "shift": g.data_ptr()})
+    for bad in (mk(gx=2), mk(gx=1), mk(gpre=3), mk(gx_add=1), mk(mask_gx=1), mk(gw=g.data_ptr()),
+                mk(fwd=bn, gw=g.data_ptr() + 4),
+                mk(fwd=dl.LayerDesc(x=0, res=1, y=3, op=dl.OP_ADD, **geo))):
+        with pytest.raises(dl.DeltaError):
+            d.backward_segment([bad])
+    d.release(1, dl.EV_FREE)
+    with pytest.raises(dl.DeltaError):                     # the stored output is what the mask is read from
+        d.backward_segment([mk()])
+    d.close()
+
+
+def test_small_resnet_operator_granular_backward(torch_mod):
+    """Loss to stem through every operator's own backward kernel; each operator is checked against
+    the oracle on the GPU's own tensors (activations and incoming gradient), parameter gradients
+    included.  Then a replay under half the activation budget with this backward: the parameter
+    gradients are bit-identical to the unconstrained run's (recomputation returns the same bits and
+    every reduction has a fixed order)."""
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import run_plan
+    torch = torch_mod
+    d0, net, layers, g = _mini(torch, None)
+    d0.close()
+    net.delta = None
+    arena = torch.empty(3 * g.total_bytes() + (8 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    net.rebind(d)
+    net.enable_backward()
+    net.forward()
+    net.backward(keep=True)
+    d.sync()
+    acts = {n: net.read(n) for n in ["x0"] + net.op_names}
+    f64 = lambda a: on.to_f64(a, "bf16")
+    worst = {}
+    for (name, kind, gy, gx, add) in net.bwd_trace:
+        l = net.op_layer[name]
+        x, res = net.op_inputs[name]
+        if kind == "add":
+            continue
+        gyv = net.read(gy)
+        p = net.params_np.get(l.name)
+        ref_w = None
+        if kind == "conv":
+            ref, ref_w, _ = on.conv_bn_act_bwd(acts[x], p["w"], None, None, gyv, stride=l.stride, pad=l.pad, relu=False,
+                                               dtype="bf16")
+        elif kind == "bn":
+            r, dg, db = og.bn_train_bwd(acts[x], p["gamma"], gyv, p["eps"], "bf16")
+            ref, ref_w = f64(r), np.concatenate([dg, db])
+        elif kind == "relu":
+            ref = f64(og.relu_bwd(acts[name], gyv, "bf16"))
+        elif kind == "maxpool":
+            ref = on.maxpool_bwd(acts[x], gyv, l.R, l.S, l.stride, l.pad, "bf16")
+        elif kind == "avgpool":
+            ref = on.avgpool_bwd(gyv, l.H, l.W, "bf16")
+        else:
+            ref, w_, b_ = on.fc_bwd(acts[x], p["w"], gyv, "bf16")
+            ref_w = np.concatenate([w_.reshape(-1), b_])
+        if gx is not None:
+            if add is not None:
+                ref = ref + f64(net.read(add)).reshape(ref.shape)
+            e = _relerr(f64(net.read(gx)).reshape(ref.shape), ref)
+            worst[kind] = max(worst.get(kind, 0.0), e)
+            assert e <= 2e-2, (name, e)
+        if ref_w is not None:
+            got_w = net.gw[name].cpu().numpy().astype(np.float64).reshape(-1)
+            e = _relerr(got_w, ref_w.reshape(-1))
+            worst[kind + ".w"] = max(worst.get(kind + ".w", 0.0), e)
+            assert e <= 2e-4, (name, e)
+    print("  worst", {k: "%.1e" % v for k, v in sorted(worst.items())}, flush=True)
+    kinds = [t[1] for t in net.bwd_trace]
+    assert kinds.count("bn") == 17 and kinds.count("add") == 4 and kinds.count("conv") == 17
+    assert sum(1 for t in net.bwd_trace if t[4] is not None) == 4          # one accumulation per block input
+    want = {n: t.clone() for n, t in net.gw.items()}
+    d.close()                                              # kept tensors go with the context
+    budget = g.total_bytes() // 2
+    arena = torch.empty(int(budget * 1.5) + net.backward_peak_bytes() * 2 + (8 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    net.rebind(d)
+    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9)
+    ev, peak = dl.plan(g.tensors, g.steps, p)
+    for t in net.gw.values():
+        t.fill_(float("nan"))
+    run_plan(net, g, ev, backward_proxy=lambda k: net.backward_step(g, k))
+    d.sync()
+    assert d.stats()["arena_in_use"] == 0
+    for n, t in net.gw.items():
+        assert torch.equal(t.view(torch.int32), want[n].view(torch.int32)), n
+    d.close()
