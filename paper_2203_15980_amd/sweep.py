@@ -1,7 +1,11 @@
 """Planner-only sweep over Filter heuristics and budgets (DELTA Sec. 5.7, Fig. 7-8): for each
 synthetic graph and each of base / LRU / GREEDY, plan at a grid of budgets with the library's
 delta_plan and report what the plan does, plus the smallest budget each heuristic can still
-plan for (bisection).  Needs no GPU.  Run: python -m paper_2203_15980_amd.sweep"""
+plan for (bisection).  Then the analogue of the paper's maximum-batch tables (Sec. 5.3): under a
+fixed number of bytes for activations, the largest batch whose whole-ResNet graph still fits
+without any release, and the largest one the planner still finds a plan for (bisection over the
+batch; every tensor and every cost grows linearly with it).  Needs no GPU.
+Run: python -m paper_2203_15980_amd.sweep"""
 import json
 import sys
 
@@ -51,6 +55,49 @@ def min_budget(delta, graph, prepared, filt):
     return hi / 256.0
 
 
+def max_batch(delta, depths, arena_bytes, filt=B.FILTER_BASE, hi=1 << 14):
+    """Largest batch of the fused ResNet graph (bf16, 224 x 224, with loss) that fits `arena_bytes`
+    of activations: (without releasing anything, with a plan).  A batch "fits" without releases when
+    the peak of the unconstrained plan is within the arena; with releases when delta_plan succeeds
+    at budget = arena."""
+    def fits(n, release):
+        g = synth.fused_graph(synth.resnet_layers(n, depths), "bf16", with_loss=True)
+        try:
+            _, peak = delta.plan(g.tensors, g.steps, _params(arena_bytes if release else 10**15, g.n_fwd, filt))
+        except B.DeltaError as e:
+            if e.status != B.ERR_INFEASIBLE:
+                raise
+            return False
+        return peak <= arena_bytes
+
+    out = []
+    for release in (False, True):
+        lo, top = 0, hi                            # lo fits (0 = nothing), top does not
+        if fits(top, release):
+            out.append(top)
+            continue
+        while top - lo > 1:
+            mid = (lo + top) // 2
+            if fits(mid, release):
+                lo = mid
+            else:
+                top = mid
+        out.append(lo)
+    return tuple(out)
+
+
+def run_max_batch(arenas_gib=(8, 16, 32), nets=(("resnet50", (3, 4, 6, 3)), ("resnet101", (3, 4, 23, 3)))):
+    delta = B.Delta()
+    out = {}
+    for name, depths in nets:
+        for gib in arenas_gib:
+            plain, planned = max_batch(delta, depths, gib << 30)
+            out["%s@%dGiB" % (name, gib)] = {"no_release": plain, "planned": planned,
+                                            "ratio": planned / plain if plain else None}
+    delta.close()
+    return out
+
+
 def run(configs=(3, 4, 5), fracs=(0.8, 0.6, 0.5, 0.4, 0.3, 0.25)):
     delta = B.Delta()
     out = {}
@@ -80,8 +127,12 @@ def main():
                           "recompute cost %.3f of step  offloaded %.2f GB"
                           % (f, dsc["peak_frac"], dsc["evict"], dsc["offload"], dsc["recompute"], dsc["reload"],
                              dsc["recompute_cost_frac"], dsc["offload_bytes"] / 1e9))
+    mb = run_max_batch()
+    print("largest batch under a fixed number of activation bytes (fused graph, bf16, base Filter)")
+    for key, r in mb.items():
+        print("  %-18s no release %5d   planned %5d   x%.2f" % (key, r["no_release"], r["planned"], r["ratio"]))
     if "--json" in sys.argv:
-        print(json.dumps(res))
+        print(json.dumps({"sweep": res, "max_batch": mb}))
 
 
 if __name__ == "__main__":

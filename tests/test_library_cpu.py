@@ -191,3 +191,27 @@ def test_executed_encoder_plan_matches_oracle():
 def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run(["python", os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_max_batch_search_brackets_feasibility():
+    """Sec. 5.3's question on synthetic graphs: under a fixed number of activation bytes the planner
+    admits a larger batch than keeping everything; the returned batches are exactly the last that fit."""
+    import synth
+    from paper_2203_15980_amd import sweep
+    from paper_2203_15980_amd import binding as B
+    arena = 1 << 30
+    depths = (3, 4, 6, 3)
+    d = B.Delta()
+    plain, planned = sweep.max_batch(d, depths, arena)
+    assert 0 < plain < planned
+
+    def plan(n, budget):
+        g = synth.fused_graph(synth.resnet_layers(n, depths), "bf16", with_loss=True)
+        return d.plan(g.tensors, g.steps, sweep._params(budget, g.n_fwd, B.FILTER_BASE))
+
+    assert plan(plain, 10**15)[1] <= arena < plan(plain + 1, 10**15)[1]
+    assert plan(planned, arena)[1] <= arena
+    with pytest.raises(B.DeltaError) as e:
+        plan(planned + 1, arena)
+    assert e.value.status == B.ERR_INFEASIBLE
+    d.close()
