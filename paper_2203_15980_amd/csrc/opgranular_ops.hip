@@ -8,7 +8,8 @@
 //   bn_stats_kernel     each workgroup sums (x - K_c) and (x - K_c)^2 over its block of rows, per
 //                       channel, fp32, K_c = x[0, c] (shifted data: no cancellation when the mean is
 //                       far from 0); lanes own 8 channels, the row-parallel lanes of a workgroup are
-//                       combined through LDS in a fixed order; partial sums to a scratch buffer
+//                       combined through LDS in row order (all lanes share that work); partial sums to a
+//                       scratch buffer
 //   bn_finalize_kernel  one thread per channel adds the partials in block order (double), forms
 //                       mean, biased variance and a = gamma / sqrt(var + eps)
 //   bn_apply_kernel     y = a_c (x - mean_c) + beta_c   (centred first: no cancellation of two large products)
@@ -101,55 +102,53 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const unsigned char *x, f
             for (int e = 0; e < 8; ++e) { p[e] = s1[e]; p[8 + e] = s2[e]; }
         }
         __syncthreads();
-        if (rsub == 0 && ck < chunks) {
-            float a1[8], a2[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) a1[e] = a2[e] = 0.f;
-            for (int j = 0; j < RS; ++j) {                       // fixed order
-                const float *p = red + ((size_t)j * CH + ck0) * 16;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { a1[e] += p[e]; a2[e] += p[8 + e]; }
-            }
-            float *o = partial + (size_t)blockIdx.x * 2 * C + ck * 8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { o[e] = a1[e]; o[C + e] = a2[e]; }
+        // every thread adds the RS row-parallel contributions of some of the CH x 16 sums, in row order
+        for (int o = t; o < CH * 16; o += 256) {
+            const int c0 = o >> 4, q = o & 15;
+            if (cg + c0 >= chunks) continue;
+            float a = 0.f;
+            for (int j = 0; j < RS; ++j) a += red[(size_t)j * CH * 16 + o];
+            partial[((size_t)blockIdx.x * 2 + (q >> 3)) * C + (cg + c0) * 8 + (q & 7)] = a;
         }
     }
 }
 
-// ab: [2][C]: a, then the mean.  A workgroup of 1024 threads takes 64 channels: thread (channel
-// lane, group g of 16) adds the partials of blocks g, g + 16, ... (coalesced over the channels,
-// eight loads in flight), the 16 groups are then added in order through LDS.
+// ab: [2][C]: a, then the mean.  A workgroup of 1024 threads takes CL = 1 << cl_bits channels (64, or
+// 16 when there are few channels, so that more workgroups and shorter chains share the partials):
+// thread (channel lane, group g of G = 1024 / CL) adds the partials of blocks g, g + G, ...
+// (coalesced over the channels, eight loads in flight), the G groups are then added in order
+// through LDS.
 __global__ __launch_bounds__(1024) void bn_finalize_kernel(const unsigned char *x, const float *partial, const float *gamma,
                                                            const float *beta, float *ab, long long M, int C, int blocks,
-                                                           float eps) {
-    __shared__ double red[2][16][64];
-    const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + cl;
+                                                           float eps, int cl_bits) {
+    __shared__ double red[2][1024];                              // [sum][group][channel lane]
+    const int CL = 1 << cl_bits, G = 1024 >> cl_bits;
+    const int cl = threadIdx.x & (CL - 1), grp = threadIdx.x >> cl_bits;
+    const int c = blockIdx.x * CL + cl;
     double s1 = 0.0, s2 = 0.0;
     if (c < C) {
         int b = grp;
-        for (; b + 7 * 16 < blocks; b += 8 * 16) {
+        for (; b + 7 * G < blocks; b += 8 * G) {
             float p1[8], p2[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                p1[u] = partial[(size_t)(b + 16 * u) * 2 * C + c];
-                p2[u] = partial[(size_t)(b + 16 * u) * 2 * C + C + c];
+                p1[u] = partial[(size_t)(b + G * u) * 2 * C + c];
+                p2[u] = partial[(size_t)(b + G * u) * 2 * C + C + c];
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) { s1 += (double)p1[u]; s2 += (double)p2[u]; }
         }
-        for (; b < blocks; b += 16) {
+        for (; b < blocks; b += G) {
             s1 += (double)partial[(size_t)b * 2 * C + c];
             s2 += (double)partial[(size_t)b * 2 * C + C + c];
         }
     }
-    red[0][grp][cl] = s1;
-    red[1][grp][cl] = s2;
+    red[0][threadIdx.x] = s1;
+    red[1][threadIdx.x] = s2;
     __syncthreads();
     if (grp != 0 || c >= C) return;
     s1 = s2 = 0.0;
-    for (int g = 0; g < 16; ++g) { s1 += red[0][g][cl]; s2 += red[1][g][cl]; }
+    for (int g = 0; g < G; ++g) { s1 += red[0][g * CL + cl]; s2 += red[1][g * CL + cl]; }
     const double k = (double)__uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(x)[c] << 16);
     const double md = s1 / (double)M;
     double var = s2 / (double)M - md * md;
@@ -202,16 +201,16 @@ __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(const unsigned char *
         if (live) {
             unpack8(*reinterpret_cast<const u32x4 *>(x + (size_t)ck * 16), k);
             long long r = r0 + rsub;
-            for (; r + (long long)RS < r1; r += 2LL * RS) {       // two rows of both tensors in flight per lane
-                u32x4 rx[2], rg[2];
+            for (; r + 3LL * RS < r1; r += 4LL * RS) {            // four rows of both tensors in flight per lane
+                u32x4 rx[4], rg[4];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < 4; ++u) {
                     const size_t at = ((size_t)(r + (long long)u * RS) * chunks + ck) * 16;
                     rx[u] = *reinterpret_cast<const u32x4 *>(x + at);
                     rg[u] = *reinterpret_cast<const u32x4 *>(g + at);
                 }
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < 4; ++u) {
                     float v[8], w[8];
                     unpack8(rx[u], v);
                     unpack8(rg[u], w);
@@ -247,61 +246,51 @@ __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(const unsigned char *
             for (int e = 0; e < 8; ++e) { p[e] = s1[e]; p[8 + e] = s2[e]; p[16 + e] = s3[e]; p[24 + e] = s4[e]; }
         }
         __syncthreads();
-        if (rsub == 0 && ck < chunks) {
-            float a[4][8];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) a[q][e] = 0.f;
-            for (int j = 0; j < RS; ++j) {                       // fixed order
-                const float *p = red + ((size_t)j * CH + ck0) * 32;
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) a[q][e] += p[q * 8 + e];
-            }
-            float *o = partial + (size_t)blockIdx.x * 4 * C + ck * 8;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[(size_t)q * C + e] = a[q][e];
+        for (int o = t; o < CH * 32; o += 256) {                 // as in bn_stats_kernel
+            const int c0 = o >> 5, q = o & 31;
+            if (cg + c0 >= chunks) continue;
+            float a = 0.f;
+            for (int j = 0; j < RS; ++j) a += red[(size_t)j * CH * 32 + o];
+            partial[((size_t)blockIdx.x * 4 + (q >> 3)) * C + (cg + c0) * 8 + (q & 7)] = a;
         }
     }
 }
 
 // coef: [4][C]: a, mean, mean(gy), S / ((var + eps) M).  gw (may be null): dgamma [C], then dbeta [C].
+// Decomposition as in bn_finalize_kernel.
 __global__ __launch_bounds__(1024) void bn_bwd_finalize_kernel(const unsigned char *x, const float *partial,
                                                                const float *gamma, float *coef, float *gw, long long M,
-                                                               int C, int blocks, float eps) {
-    __shared__ double red[4][16][64];
-    const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + cl;
+                                                               int C, int blocks, float eps, int cl_bits) {
+    __shared__ double red[4][1024];
+    const int CL = 1 << cl_bits, G = 1024 >> cl_bits;
+    const int cl = threadIdx.x & (CL - 1), grp = threadIdx.x >> cl_bits;
+    const int c = blockIdx.x * CL + cl;
     double s[4] = {0.0, 0.0, 0.0, 0.0};
     if (c < C) {
         int b = grp;
-        for (; b + 3 * 16 < blocks; b += 4 * 16) {
+        for (; b + 3 * G < blocks; b += 4 * G) {
             float p[4][4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) p[u][q] = partial[((size_t)(b + 16 * u) * 4 + q) * C + c];
+                for (int q = 0; q < 4; ++q) p[u][q] = partial[((size_t)(b + G * u) * 4 + q) * C + c];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) s[q] += (double)p[u][q];
         }
-        for (; b < blocks; b += 16)
+        for (; b < blocks; b += G)
 #pragma unroll
             for (int q = 0; q < 4; ++q) s[q] += (double)partial[((size_t)b * 4 + q) * C + c];
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) red[q][grp][cl] = s[q];
+    for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = s[q];
     __syncthreads();
     if (grp != 0 || c >= C) return;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         s[q] = 0.0;
-        for (int g = 0; g < 16; ++g) s[q] += red[q][g][cl];
+        for (int g = 0; g < G; ++g) s[q] += red[q][g * CL + cl];
     }
     const double k = (double)__uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(x)[c] << 16);
     const double md = s[0] / (double)M;
@@ -412,8 +401,9 @@ hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const flo
     const size_t lds = (size_t)RS * CH * 16 * 4;
     ops::bn_stats_kernel<<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(static_cast<const unsigned char *>(x), partial,
                                                                             M, C, rpb, CH, RS);
-    ops::bn_finalize_kernel<<<dim3((unsigned)((C + 63) / 64)), dim3(1024), 0, stream>>>(
-        static_cast<const unsigned char *>(x), partial, gamma, beta, ab, M, C, (int)blocks, eps);
+    const int cl_bits = C <= 512 ? 4 : 6;
+    ops::bn_finalize_kernel<<<dim3((unsigned)((C + (1 << cl_bits) - 1) >> cl_bits)), dim3(1024), 0, stream>>>(
+        static_cast<const unsigned char *>(x), partial, gamma, beta, ab, M, C, (int)blocks, eps, cl_bits);
     const size_t n16 = (size_t)M * chunks;
     ops::bn_apply_kernel<<<dim3(ops::stream_blocks(n16)), dim3(256), 0, stream>>>(
         static_cast<const ops::u32x4 *>(x), static_cast<ops::u32x4 *>(y), ab, beta, C, n16);
@@ -433,8 +423,8 @@ hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const fl
     float *partial = coef + 4 * (size_t)C;
     const size_t room = (bn_train_scratch_bytes() - 4 * (size_t)C * 4) / ((size_t)4 * C * 4);
     long long blocks = (M + (long long)RS * 4 - 1) / ((long long)RS * 4);
-    long long cap = 131072 / C;
-    cap = cap < 64 ? 64 : (cap > 2048 ? 2048 : cap);
+    long long cap = 262144 / C;                                  // 1024 workgroups fill the chip four wavefronts deep
+    cap = cap < 64 ? 64 : (cap > 1024 ? 1024 : cap);
     if (blocks > cap) blocks = cap;
     if (blocks > (long long)room) blocks = (long long)room;
     if (blocks < 1) return hipErrorInvalidValue;
@@ -443,8 +433,9 @@ hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const fl
     const size_t lds = (size_t)RS * CH * 32 * 4;
     ops::bn_bwd_stats_kernel<<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(
         static_cast<const unsigned char *>(x), static_cast<const unsigned char *>(gy), partial, M, C, rpb, CH, RS);
-    ops::bn_bwd_finalize_kernel<<<dim3((unsigned)((C + 63) / 64)), dim3(1024), 0, stream>>>(
-        static_cast<const unsigned char *>(x), partial, gamma, coef, gw, M, C, (int)blocks, eps);
+    const int cl_bits = C <= 512 ? 4 : 6;
+    ops::bn_bwd_finalize_kernel<<<dim3((unsigned)((C + (1 << cl_bits) - 1) >> cl_bits)), dim3(1024), 0, stream>>>(
+        static_cast<const unsigned char *>(x), partial, gamma, coef, gw, M, C, (int)blocks, eps, cl_bits);
     const size_t n16 = (size_t)M * chunks;
     ops::bn_bwd_apply_kernel<<<dim3(ops::stream_blocks(n16)), dim3(256), 0, stream>>>(
         static_cast<const ops::u32x4 *>(x), static_cast<const ops::u32x4 *>(gy), static_cast<ops::u32x4 *>(gx), coef, C, n16);
