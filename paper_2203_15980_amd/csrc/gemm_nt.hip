@@ -12,13 +12,17 @@
 //    across the barrier and the operand reads; the width is the one that leaves fewer CUs idle
 //    (768 output channels: 4 tiles of 192 fill the chip at 16384 rows, 3 tiles of 256 leave a
 //    quarter of it idle);
-//  * K slices of 32 go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
-//    no registers, no LDS store instructions) through FOUR buffers of 32 KB: a slice is requested
-//    three slices (>= 3000 cycles of MFMA work per SIMD) before it is multiplied - with two buffers
-//    of 64 the memory latency (about 2 us under load) was longer than a slice's arithmetic and the
-//    kernel ran no faster than the convolution kernel; one barrier per slice, and the wait before
-//    it is for the oldest slice only (vmcnt counts the younger loads);
-//  * a tile row is 64 bytes = 4 pieces of 16; piece p of row r lives in slot p ^ ((r >> 2) & 3):
+//  * K slices of 64 go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+//    no registers, no LDS store instructions) through TWO buffers of 64 KB (56 KB): a tile row is a
+//    whole 128-byte line of the operand, one barrier per 64 of K, and the slice after the current one
+//    is in flight while the current one is multiplied (2000 cycles of MFMA work per SIMD at full
+//    rate).  Measured against four buffers of 32 (two and three slices ahead, also with a fifth
+//    buffer, also with the next slice's first operands read before the barrier): those were all the
+//    same speed, this is 4-9 % faster on the encoder's and ResNet's shapes; with the loads switched
+//    off the loop runs at 1.3-1.5 PFLOP/s and removing the barrier changes nothing: what holds the
+//    kernel at about 1 PFLOP/s is the delivery of the operands from L2, not their latency, the
+//    barrier or LDS (LDS reads are a quarter of the cycles by the counters);
+//  * a tile row is 128 bytes = 8 pieces of 16; piece p of row r lives in slot p ^ ((r >> 1) & 7):
 //    the direct loads fix where a LANE's 16 bytes land, so the swizzle is applied to the global
 //    address each lane fetches; 16 lanes reading one piece of 16 consecutive rows then touch all
 //    64 banks once;
@@ -43,7 +47,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kBM = 256, kBK = 32, kStages = 4;
+static constexpr int kBM = 256, kBK = 64, kStages = 2;
 static constexpr int kWM = 4;                                           // wavefront rows: 256 / kWM = 64 rows of x each
 static constexpr int kTM = kBM / kWM / 32, kTN = 2;                     // kTM x 2 tiles of 32 x 32 per wavefront
 static constexpr int kXBytes = kBM * kBK * 2;                           // 16 KB of x per buffer
@@ -77,7 +81,7 @@ template <int BN>
 __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs a, int tiles_n, int tiles_total) {
     constexpr int kBN = BN, kWN = BN / 64, kWaves = kWM * kWN;
     constexpr int kStageBytes = kXBytes + BN * kBK * 2;
-    constexpr int XI = (kBM / 16 + kWaves - 1) / kWaves, WI = (BN / 16 + kWaves - 1) / kWaves;   // direct loads per wavefront and slice
+    constexpr int XI = (kBM / 8 + kWaves - 1) / kWaves, WI = (BN / 8 + kWaves - 1) / kWaves;   // direct loads per wavefront and slice
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -89,9 +93,8 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
     if (logical >= tiles_total) return;
     const int m0 = (logical / tiles_n) * kBM, n0 = (logical % tiles_n) * kBN;
 
-    // ---- direct loads: one instruction fills 16 tile rows (1 KB); per slice a wavefront issues XI for
-    // x and WI for w (when the rows do not divide evenly the last wavefronts repeat a neighbour's rows:
-    // every wavefront must issue the same number, the waits below count them)
+    // ---- direct loads: one instruction fills 8 tile rows (1 KB); per slice a wavefront issues XI for
+    // x and WI for w (when the rows do not divide evenly the last wavefronts repeat a neighbour's rows)
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const unsigned char *wg = static_cast<const unsigned char *>(a.w);
     const size_t krow = (size_t)K * 2;
@@ -100,9 +103,9 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
 #pragma unroll
     for (int q = 0; q < XI; ++q) {
         int g = wv * XI + q;
-        g = g < kBM / 16 ? g : kBM / 16 - 1;
-        const int r = 16 * g + (lane >> 2);                             // row of the tile this lane fills
-        const int piece = (lane & 3) ^ ((r >> 2) & 3);                 // which 16 bytes of the row land in this lane's slot
+        g = g < kBM / 8 ? g : kBM / 8 - 1;
+        const int r = 8 * g + (lane >> 3);                              // row of the tile this lane fills
+        const int piece = (lane & 7) ^ ((r >> 1) & 7);                 // which 16 bytes of the row land in this lane's slot
         int xr = m0 + r;
         xr = xr < M ? xr : M - 1;
         xsrc[q] = xg + (size_t)xr * krow + piece * 16;
@@ -111,43 +114,30 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
 #pragma unroll
     for (int q = 0; q < WI; ++q) {
         int g = wv * WI + q;
-        g = g < BN / 16 ? g : BN / 16 - 1;
-        const int r = 16 * g + (lane >> 2);
-        const int piece = (lane & 3) ^ ((r >> 2) & 3);
+        g = g < BN / 8 ? g : BN / 8 - 1;
+        const int r = 8 * g + (lane >> 3);
+        const int piece = (lane & 7) ^ ((r >> 1) & 7);
         int wr = n0 + r;
         wr = wr < N ? wr : N - 1;
         wsrc[q] = wg + (size_t)wr * krow + piece * 16;
         wdst[q] = (uint32_t)kXBytes + (uint32_t)g * 1024u;
     }
-    // The direct loads and the waits for them are written as inline assembly: through the builtin
-    // the compiler, which cannot tell the four buffers apart, waits for ALL outstanding direct loads
-    // (vmcnt(0)) before every barrier, i.e. for the slice requested a moment ago, and the deep
-    // pipeline is gone.  Loads return in order, so "at most 8 outstanding" means the oldest slice is in.
+    // The direct loads and the waits for them are written as inline assembly: the compiler does not
+    // track what a direct load writes, the explicit waits below do.
     typedef __attribute__((address_space(3))) unsigned char *lptr_t;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
     const int nslices = K / kBK;
-    auto fetch = [&](int t, int buf) {           // t past the end: the last slice again (keeps the load count uniform)
-        t = t < nslices ? t : nslices - 1;
+    auto fetch = [&](int t, int buf) {
         const uint32_t sb = lds0 + (uint32_t)buf * kStageBytes;
 #pragma unroll
         for (int q = 0; q < XI; ++q)
             asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-                         :: "v"(xsrc[q] + (size_t)t * 64), "s"(__builtin_amdgcn_readfirstlane(sb + xdst[q])) : "memory", "m0");
+                         :: "v"(xsrc[q] + (size_t)t * 128), "s"(__builtin_amdgcn_readfirstlane(sb + xdst[q])) : "memory", "m0");
 #pragma unroll
         for (int q = 0; q < WI; ++q)
             asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-                         :: "v"(wsrc[q] + (size_t)t * 64), "s"(__builtin_amdgcn_readfirstlane(sb + wdst[q])) : "memory", "m0");
+                         :: "v"(wsrc[q] + (size_t)t * 128), "s"(__builtin_amdgcn_readfirstlane(sb + wdst[q])) : "memory", "m0");
     };
-    // "at most 2 slices' worth outstanding": the oldest slice is in
-    auto wait_oldest = [&]() {
-        constexpr int n = 2 * (XI + WI);
-        if constexpr (n == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else if constexpr (n == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else if constexpr (n == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if constexpr (n == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    };
-
     f32x16 acc[kTM][kTN];
 #pragma unroll
     for (int i = 0; i < kTM; ++i)
@@ -161,27 +151,25 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
 #pragma unroll
     for (int i = 0; i < kTM; ++i) {
         const int r = wm * (32 * kTM) + i * 32 + l32;
-        xoff[i] = r * 64;
-        xsw[i] = (r >> 2) & 3;
+        xoff[i] = r * 128;
+        xsw[i] = (r >> 1) & 7;
     }
 #pragma unroll
     for (int j = 0; j < kTN; ++j) {
         const int r = wn * 64 + j * 32 + l32;
-        woff[j] = kXBytes + r * 64;
-        wsw[j] = (r >> 2) & 3;
+        woff[j] = kXBytes + r * 128;
+        wsw[j] = (r >> 1) & 7;
     }
 
     fetch(0, 0);
-    fetch(1, 1);
-    fetch(2, 2);
-    wait_oldest();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     for (int t = 0; t < nslices; ++t) {
-        const int buf = t % kStages;
-        fetch(t + 3, (t + 3) % kStages);           // into the buffer that slice t - 1 has just left
+        const int buf = t & 1;
+        if (t + 1 < nslices) fetch(t + 1, buf ^ 1);    // into the buffer that slice t - 1 has just left
         const unsigned char *base = smem + (size_t)buf * kStageBytes;
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
+        for (int k2 = 0; k2 < 4; ++k2) {
             bf16x8 xf[kTM], wf[kTN];
 #pragma unroll
             for (int i = 0; i < kTM; ++i)
@@ -195,11 +183,9 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
                 for (int j = 0; j < kTN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
         }
-        wait_oldest();                             // this wavefront's loads of slice t + 1 have landed
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's loads of slice t + 1 have landed
         __syncthreads();                           // everyone's have, and everyone is done reading buffer `buf`
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the surplus loads of the last rounds ...
-    __syncthreads();                               // ... of every wavefront, before LDS becomes staging space
 
     // ---- epilogue.  acc[i][j]: lane holds pixel (x row) l32 of tile i and channels 8*rb + 4*half + e of tile j
     unsigned char *stg = smem + (size_t)wv * (32 * kStgPitch);
