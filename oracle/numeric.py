@@ -133,6 +133,55 @@ def conv_bn_act_bwd(x, w, bn, y, gy, stride=1, pad=0, relu=True, dtype="f32"):
     return gx, gw, gpre
 
 
+def wgrad_entries(x, gpre, scale, entries, stride, pad, dtype="f32"):
+    """Single entries of dL/dw of one fused layer, each written out as its defining sum
+    (for checking tensors too large to differentiate whole):
+        gw[k, r, s, c] = scale_k * sum over n, p, q of gpre[n, p, q, k] * x[n, p*stride + r - pad, q*stride + s - pad, c]
+    x [N,H,W,Cin] and gpre [N,P,Q,Cout] (dL/d pre-activation at the OUTPUT's resolution) at storage
+    precision, scale float32 [Cout] or None; entries: (k, r, s, c) tuples.  float64 list."""
+    xd, gd = to_f64(x, dtype), to_f64(gpre, dtype)
+    N, H, W, _ = xd.shape
+    _, P, Q, _ = gd.shape
+    out = []
+    for (k, r, s_, c) in entries:
+        ps = [p for p in range(P) if 0 <= p * stride + r - pad < H]
+        qs = [q for q in range(Q) if 0 <= q * stride + s_ - pad < W]
+        if not ps or not qs:
+            out.append(0.0)
+            continue
+        hs = [p * stride + r - pad for p in ps]
+        ws = [q * stride + s_ - pad for q in qs]
+        a = gd[:, ps][:, :, qs][..., k]
+        b = xd[:, hs][:, :, ws][..., c]
+        v = float((a * b).sum())
+        out.append(v * (float(np.float32(scale[k])) if scale is not None else 1.0))
+    return out
+
+
+def dgrad_pixels(gpre, w, scale, pixels, stride, pad, H, W, dtype="f32"):
+    """dL/dx of one fused layer at single input pixels, each written out as its defining sum:
+        gx[n, h, w, c] = sum over k, r, s with (h + pad - r, w + pad - s) = stride * (p, q), p, q in range,
+                         of gpre[n, p, q, k] * scale_k * w[k, r, s, c]
+    gpre [N,P,Q,Cout] at the output's resolution and w [Cout,R,S,Cin] at storage precision; pixels:
+    (n, h, w) tuples; H, W: the input's size.  float64 [len(pixels), Cin]."""
+    gd, wd = to_f64(gpre, dtype), to_f64(w, dtype)
+    Cout, R, S, Cin = wd.shape
+    _, P, Q, _ = gd.shape
+    sc = np.asarray(scale, dtype=np.float32).astype(np.float64) if scale is not None else np.ones(Cout)
+    out = np.zeros((len(pixels), Cin))
+    for i, (n, h, w_) in enumerate(pixels):
+        assert 0 <= h < H and 0 <= w_ < W
+        for r in range(R):
+            for s_ in range(S):
+                hp, wq = h + pad - r, w_ + pad - s_
+                if hp % stride or wq % stride:
+                    continue
+                p, q = hp // stride, wq // stride
+                if 0 <= p < P and 0 <= q < Q:
+                    out[i] += (gd[n, p, q, :] * sc) @ wd[:, r, s_, :]
+    return out
+
+
 def maxpool(x, R, S, stride, pad, dtype="f32"):
     x = np.ascontiguousarray(x, dtype=_np(dtype))
     N, H, W, C = x.shape

@@ -562,3 +562,77 @@ def test_weight_gradient_survives_release_of_its_inputs(torch_mod):
         got = run(True)
         assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "repeat %d" % rep
     d.close()
+
+
+def test_config3_full_size_backward_sampled_entries(torch_mod):
+    """Config 3 at full size (ResNet-50, batch 128, 224x224x3: the launch shapes bench.py times):
+    forward and the whole backward pass, then for one layer of every backward code path sampled
+    entries of dL/dw and sampled pixels of dL/dx against their defining sums (oracle
+    wgrad_entries / dgrad_pixels) on the GPU's own x and gpre.  A whole gradient at this size is
+    beyond the oracle; a sum over all 128 images per entry is not."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    N = 128
+    layers = synth.resnet_layers(N)
+    g = synth.fused_graph(layers, "bf16", with_loss=True)
+    boot = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(boot, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", synth.master_seed(3), with_loss=True)
+    net.enable_backward()
+    d.close()
+    arena = torch.empty(sum(net.sizes) + (256 << 20), dtype=torch.uint8, device="cuda:0")   # everything kept
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    net.rebind(d)
+    net.forward()
+    net.backward(keep=True)
+    d.sync()
+    trace = {t[0]: t for t in net.bwd_trace}
+    by_name = {l.name: l for l in layers}
+    rng = np.random.default_rng(7)
+    f64 = lambda a: on.to_f64(a, "bf16")
+    # 3x3 | 1x1 with residual (flattened positions) | 3x3 stride 2 (dilated gpre) | 1x1 stride 2 (gathered) |
+    # 3x3 on 7x7 images | a wide 1x1 on the GEMM kernel | block inputs that accumulate a second gradient | the stem
+    seen_add = False
+    for lname in ("s2.b1.a2", "s2.b1.out", "s3.b1.a2", "s3.b1.sc", "s5.b3.a2", "s4.b2.out", "s3.b1.a1", "s2.b2.a1", "stem"):
+        l = by_name[lname]
+        _, gy_name, gpre_name, gx_name, add_name, masks_gx = trace[lname]
+        print("layer", lname, "gpre", gpre_name, "gx", gx_name, "add", add_name, "mask", masks_gx, flush=True)
+        p = net.params_np[lname]
+        scale = (p["gamma"].astype(np.float64) / np.sqrt(p["var"].astype(np.float64) + p["eps"])).astype(np.float32)
+        x = net.read(l.x) if l.x != "x0" else net.x0_np
+        gp = net.read(gpre_name)
+        if gp.shape[1] != l.P:                             # written at the input's resolution, zeros between
+            s = l.stride
+            keep = np.zeros(gp.shape[1:3], dtype=bool)
+            keep[::s, ::s] = True
+            assert not gp[:, ~keep, :].any()
+            gp = np.ascontiguousarray(gp[:, ::s, ::s, :][:, :l.P, :l.Q, :])
+        assert gp.shape == (N, l.P, l.Q, l.Cout)
+        gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(l.Cout, l.R, l.S, l.Cin)
+        entries = [(int(rng.integers(l.Cout)), int(rng.integers(l.R)), int(rng.integers(l.S)), int(rng.integers(l.Cin)))
+                   for _ in range(24)]
+        ref = np.array(on.wgrad_entries(x, gp, scale, entries, l.stride, l.pad, "bf16"))
+        got = np.array([gw[e] for e in entries])
+        ew = float(np.max(np.abs(got - ref)) / np.max(np.abs(gw)))
+        print("  dL/dw: 24 entries, max |gw| %.3g, err %.2e" % (np.max(np.abs(gw)), ew), flush=True)
+        assert np.isfinite(gw).all() and ew <= 2e-4, (lname, ew)
+        if gx_name is None:
+            continue
+        gx = net.read(gx_name)
+        pixels = [(int(rng.integers(N)), int(rng.integers(l.H)), int(rng.integers(l.W))) for _ in range(12)]
+        pixels += [(N - 1, l.H - 1, l.W - 1), (0, 0, 0), (1, 0, l.W - 1), (2, 1, 1)]        # corners, both parities
+        ref = on.dgrad_pixels(gp, p["w"], scale, pixels, l.stride, l.pad, l.H, l.W, "bf16")
+        if add_name is not None:
+            a = net.read(add_name)
+            ref = ref + np.stack([f64(a[px]) for px in pixels])
+            seen_add = True
+        if masks_gx:
+            ref = ref * np.stack([f64(x[px]) > 0 for px in pixels])
+        got = np.stack([f64(gx[px]) for px in pixels])
+        ex = float(np.max(np.abs(got - ref)) / np.max(np.abs(f64(gx))))
+        print("  dL/dx: %d pixels, err %.2e" % (len(pixels), ex), flush=True)
+        assert ex <= 2e-2, (lname, ex)
+    assert seen_add
+    d.close()

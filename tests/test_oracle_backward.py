@@ -246,3 +246,26 @@ def test_classifier_backward_is_three_matrix_products():
     np.testing.assert_allclose(gx.reshape(N, Cin), G @ Wm, rtol=1e-13)
     np.testing.assert_allclose(gw.reshape(Cout, Cin), G.T @ X, rtol=1e-13)
     np.testing.assert_allclose(gb, G.sum(axis=0), rtol=1e-13)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_single_entry_sums_agree_with_the_whole_gradients(case):
+    """wgrad_entries / dgrad_pixels (the defining sums of single gradient entries, used on tensors
+    too large to differentiate whole) against the full backward oracle, which is pinned above by
+    finite differences: every entry of dL/dw and every pixel of dL/dx on small layers, strides and
+    paddings included."""
+    N, H, W, Cin, Cout, R, stride, pad = case
+    x = _rand((N, H, W, Cin), 21)
+    w = _rand((Cout, R, R, Cin), 22, 0.5)
+    bn = _bn(Cout, 23)
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    g = _rand((N, P, Q, Cout), 24)
+    gx, gw, gpre = on.conv_bn_act_bwd(x, w, bn, None, g, stride=stride, pad=pad, relu=False, dtype="f32")
+    scale = (bn["gamma"].astype(np.float64) / np.sqrt(bn["var"].astype(np.float64) + bn["eps"])).astype(np.float32)
+    entries = [(k, r, s, c) for k in range(Cout) for r in range(R) for s in range(R) for c in range(Cin)]
+    got_w = np.array(on.wgrad_entries(x, g, scale, entries, stride, pad, "f32")).reshape(gw.shape)
+    assert np.max(np.abs(got_w - gw)) <= 1e-6 * max(1.0, np.max(np.abs(gw)))     # scale rounded to float32 here
+    pixels = [(n, h, v) for n in range(N) for h in range(H) for v in range(W)]
+    got_x = on.dgrad_pixels(g, w, scale, pixels, stride, pad, H, W, "f32").reshape(gx.shape)
+    assert np.max(np.abs(got_x - gx)) <= 1e-6 * max(1.0, np.max(np.abs(gx)))
