@@ -351,3 +351,64 @@ def test_small_resnet_operator_granular_backward(torch_mod):
     for n, t in net.gw.items():
         assert torch.equal(t.view(torch.int32), want[n].view(torch.int32)), n
     d.close()
+
+
+def test_config3_full_size_operator_granular_sampled(torch_mod):
+    """ResNet-50 at batch 128 at operator granularity (the launch shapes bench.py replays):
+    forward and the whole backward; batch normalisation is independent per channel, so the oracle
+    runs whole sampled channels (statistics over all 128 images) of a 205 MB, a 51 MB and a 13 MB
+    tensor, forward and backward; one ReLU backward whole (bit-exact); one bare convolution's
+    weight gradient on sampled entries."""
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import OpNet
+    torch = torch_mod
+    N = 128
+    layers = synth.resnet_layers(N)
+    g = synth.opgranular_graph(layers, "bf16", with_loss=True)
+    boot = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(boot, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = OpNet(d, layers, synth.master_seed(3))
+    net.enable_backward()
+    d.close()
+    arena = torch.empty(sum(net.sizes) + (256 << 20), dtype=torch.uint8, device="cuda:0")   # everything kept
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    net.rebind(d)
+    net.forward()
+    net.backward(keep=True)
+    d.sync()
+    trace = {t[0]: t for t in net.bwd_trace}
+    rng = np.random.default_rng(11)
+    f64 = lambda a: on.to_f64(a, "bf16")
+    for lname in ("stem", "s2.b1.out", "s3.b2.a1", "s5.b3.out"):
+        name = lname + ".bn"
+        _, kind, gy_name, gx_name, _ = trace[name]
+        assert kind == "bn"
+        p = net.params_np[lname]
+        x, y, gy, gx = net.read(lname + ".conv"), net.read(name), net.read(gy_name), net.read(gx_name)
+        gw = net.gw[name].cpu().numpy().astype(np.float64)
+        C = x.shape[-1]
+        print("batch-norm", name, x.shape, flush=True)
+        for c in sorted({0, C - 1, int(rng.integers(C))}):
+            one = lambda a: np.ascontiguousarray(a[..., c:c + 1])
+            ref_y = og.bn_train(one(x), p["gamma"][c:c + 1], p["beta"][c:c + 1], p["eps"], "bf16")
+            ey = _relerr(f64(one(y)), f64(ref_y))
+            ref_gx, dg, db = og.bn_train_bwd(one(x), p["gamma"][c:c + 1], one(gy), p["eps"], "bf16")
+            ex = _relerr(f64(one(gx)), f64(ref_gx))
+            floor = 1e-6 * np.abs(f64(one(gy))).sum()
+            eg, eb = abs(gw[c] - dg[0]) / (abs(dg[0]) + floor), abs(gw[C + c] - db[0]) / (abs(db[0]) + floor)
+            print("  channel %4d: y %.2e gx %.2e dgamma %.2e dbeta %.2e" % (c, ey, ex, eg, eb), flush=True)
+            assert ey <= 2e-2 / 4 and ex <= 2e-2 / 4 and eg <= 2e-4 and eb <= 2e-4, (name, c, ey, ex, eg, eb)
+    name = "s2.b1.out.relu"
+    _, kind, gy_name, gx_name, _ = trace[name]
+    assert kind == "relu" and np.array_equal(net.read(gx_name), og.relu_bwd(net.read(name), net.read(gy_name), "bf16"))
+    name = "s2.b1.a2.conv"
+    _, kind, gy_name, gx_name, add = trace[name]
+    l = net.op_layer[name]
+    gwc = net.gw[name].cpu().numpy().astype(np.float64).reshape(l.Cout, l.R, l.S, l.Cin)
+    entries = [(int(rng.integers(l.Cout)), int(rng.integers(3)), int(rng.integers(3)), int(rng.integers(l.Cin))) for _ in range(16)]
+    ref = np.array(on.wgrad_entries(net.read(net.op_inputs[name][0]), net.read(gy_name), None, entries, 1, 1, "bf16"))
+    ew = float(np.max(np.abs(np.array([gwc[e] for e in entries]) - ref)) / np.max(np.abs(gwc)))
+    print("bare convolution dL/dw: 16 entries, err %.2e" % ew, flush=True)
+    assert ew <= 2e-4
+    d.close()
