@@ -252,7 +252,7 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  * workspace and then spread out (zeros between), gx_add added in a second bf16 rounding.
  * Other operators (bf16 only; gpre must be gy, gx_add unused):
  *   DELTA_OP_MAXPOOL   gx receives gy routed to the first maximal element of each window (scan order
- *                      r, then s); needs fwd.x resident.
+ *                      r, then s); needs fwd.x resident.  With mask_gx, gx is also multiplied by [x > 0].
  *   DELTA_OP_AVGPOOL   gx = gy / (H W) at every pixel.
  *   the classifier     (DELTA_OP_CONV with H = W = R = S = 1 and Cout not a multiple of 64):
  *                      gx = gy . (scale * w); gw (optional, fp32) receives Cout*Cin weight gradients
@@ -279,7 +279,7 @@ typedef struct delta_bwd_desc {
     uint32_t gx;               /* tensor id that receives dL/dx (bytes of x), or DELTA_NO_TENSOR */
     uint32_t gx_add;           /* resident tensor (bytes of x) added to dL/dx before it is stored: the
                                   contribution of another consumer of x; or DELTA_NO_TENSOR */
-    uint32_t mask_gx;          /* convolutions only.  Non-zero: gx is stored as (dL/dx + gx_add) * [x > 0],
+    uint32_t mask_gx;          /* convolutions and max pooling.  Non-zero: gx is stored as (dL/dx + gx_add) * [x > 0],
                                   i.e. this layer also applies the ReLU mask of the layer that produced x
                                   (x is that layer's y), in the epilogue of the data-gradient kernel;
                                   the caller sets it on the LAST consumer of x to run.  Needs fwd.x resident */

@@ -53,7 +53,8 @@ __host__ __device__ inline int pool_windows_max(int R, int stride) { return (kPo
 
 // FIXED: the ResNet pool (3 x 3, stride 2, padding 1) with every loop unrolled.
 template <bool FIXED>
-__global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void *gy, void *gx, int tiles_w, int tiles_h) {
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void *gy, void *gx, int tiles_w, int tiles_h,
+                                                          int mask_x) {
     if constexpr (FIXED) { a.R = 3; a.S = 3; a.stride = 2; a.pad = 1; }
     extern __shared__ __align__(16) unsigned char plds[];
     const int chunks = a.C / 8, cgroups = (chunks + kPoolChunks - 1) / kPoolChunks;
@@ -158,9 +159,17 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void
                     acc[e] += (live && pos == my) ? g[e] : 0.f;
                 }
             }
-        if (owned)
+        if (owned) {
+            u32x4 o = pack8(acc);
+            if (mask_x) {                                           // also the ReLU mask of x's producer: x is its output
+                const int lh = h - h0 + a.R - 1, lw = w - w0 + a.S - 1;
+                const u32x4 xv = *reinterpret_cast<const u32x4 *>(plds + ((size_t)(lh * LW + lw) * kPoolChunks + c) * 16);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = keep_where_positive_bf16(o[e], xv[e]);
+            }
             *reinterpret_cast<u32x4 *>(static_cast<unsigned char *>(gx) +
-                                       ((((size_t)n * a.H + h) * a.W + w) * chunks + ck) * 16) = pack8(acc);
+                                       ((((size_t)n * a.H + h) * a.W + w) * chunks + ck) * 16) = o;
+        }
     }
 }
 
@@ -270,7 +279,7 @@ __global__ __launch_bounds__(256) void dense_bwd_weight_kernel(const uint16_t *g
 
 }  // namespace bops
 
-hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipStream_t stream) {
+hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, int mask_x, hipStream_t stream) {
     if (pool_check(a, false) || !a.bf16 || !gy || !gx) return hipErrorInvalidValue;
     const int tiles_h = (a.H + bops::kPoolTile - 1) / bops::kPoolTile, tiles_w = (a.W + bops::kPoolTile - 1) / bops::kPoolTile;
     const int cgroups = (a.C / 8 + bops::kPoolChunks - 1) / bops::kPoolChunks;
@@ -280,9 +289,9 @@ hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipSt
                        (size_t)bops::pool_windows_max(a.R, a.stride) * bops::pool_windows_max(a.S, a.stride) * bops::kPoolChunks * 8;
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL || lds > 64 * 1024) return hipErrorInvalidValue;
     if (a.R == 3 && a.S == 3 && a.stride == 2 && a.pad == 1)
-        bops::maxpool_bwd_kernel<true><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h);
+        bops::maxpool_bwd_kernel<true><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h, mask_x);
     else
-        bops::maxpool_bwd_kernel<false><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h);
+        bops::maxpool_bwd_kernel<false><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h, mask_x);
     return hipGetLastError();
 }
 

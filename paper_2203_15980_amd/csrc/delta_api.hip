@@ -909,8 +909,9 @@ delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint3
     if (D.gx != DELTA_NO_TENSOR &&
         (D.gx >= nt || c->tensors[D.gx].bytes != c->tensors[L.x].bytes || D.gx == L.x || D.gx == L.y || D.gx == D.gy))
         return fail(c, DELTA_ERR_INVALID, "backward %u: gx must be another tensor with the bytes of x", i);
-    if (D.gx_add != DELTA_NO_TENSOR || D.mask_gx || D.gy_masked)
-        return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add, mask_gx and gy_masked are for convolutions only", i);
+    if (D.gx_add != DELTA_NO_TENSOR || (D.mask_gx && kind != BK_MAXPOOL) || D.gy_masked)
+        return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add and gy_masked are for convolutions only, mask_gx for "
+                    "convolutions and max pooling", i);
     if (kind == BK_LOSS) {
         if (D.gy != DELTA_NO_TENSOR || D.gpre != DELTA_NO_TENSOR || D.gw)
             return fail(c, DELTA_ERR_INVALID, "backward %u: the loss takes no incoming gradient and has no weights", i);
@@ -1166,7 +1167,7 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
             switch (kind) {
             case BK_MAXPOOL:
                 pa.x = xp;
-                HIP_TRY(c, delta::launch_maxpool_bwd(pa, gyp, gxp, s));
+                HIP_TRY(c, delta::launch_maxpool_bwd(pa, gyp, gxp, D.mask_gx ? 1 : 0, s));
                 break;
             case BK_AVGPOOL:
                 HIP_TRY(c, delta::launch_avgpool_bwd(pa, gyp, gxp, s));

@@ -100,7 +100,8 @@ hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *works
                         hipStream_t stream);
 
 // backward_ops.hip: backward of pooling, the classifier and the loss (bf16)
-hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipStream_t stream);
+// mask_x: gx is also multiplied by [x > 0] (the ReLU mask of the layer that produced the pool's input)
+hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, int mask_x, hipStream_t stream);
 hipError_t launch_avgpool_bwd(const PoolArgs &a, const void *gy, void *gx, hipStream_t stream);
 hipError_t launch_softmax_ce_bwd(const void *logits, const void *labels, int N, int classes, void *gz, hipStream_t stream);
 hipError_t launch_dense_bwd(const void *x, const void *w, const float *scale, const void *gy, void *gx, float *gw,

@@ -145,14 +145,19 @@ class Net:
     def _plan_mask_fusion(self):
         """tensor name -> the layer that applies the ReLU mask of the tensor's producer while it
         writes the tensor's gradient: the consumer whose backward runs last (the first in forward
-        order), if it is a convolution reading the tensor as its input.  Its data gradient
-        already holds every other consumer's contribution (gx_add) at that point."""
+        order), if it is a convolution reading the tensor as its input - its data gradient
+        already holds every other consumer's contribution (gx_add) at that point - or a max-pool
+        that is the tensor's only consumer (the stem's output in a ResNet)."""
         masked_by = {}
         for prod in self.layers:
-            if prod.kind != "conv" or not prod.relu or self._is_stem(prod):
+            if prod.kind != "conv" or not prod.relu:
                 continue
             users = [l for l in self.layers if l.x == prod.y or l.res == prod.y]
-            if users and users[0].kind == "conv" and users[0].x == prod.y and not self._is_stem(users[0]):
+            if not users or users[0].x != prod.y:
+                continue
+            if users[0].kind == "conv" and not self._is_stem(users[0]) and not self._is_stem(prod):
+                masked_by[prod.y] = users[0].name
+            elif users[0].kind == "maxpool" and len(users) == 1 and self.dtype == "bf16":
                 masked_by[prod.y] = users[0].name
         return masked_by
 
@@ -321,7 +326,7 @@ class Net:
         gy, gpre, gx, add, dead, new = self._bwd_plan(l, self.pending)
         self.pending.pop(l.y)
         conv = l.kind == "conv"
-        mask_gx = conv and gx is not None and self.masked_by.get(l.x) == l.name
+        mask_gx = gx is not None and self.masked_by.get(l.x) == l.name
         desc = B.BwdDesc(fwd=self.desc[l.y][0], gy=self.ids[gy], gpre=self.ids[gpre],
                          gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
                          mask_gx=int(mask_gx), gy_masked=int(conv and self._gy_masked(l)),

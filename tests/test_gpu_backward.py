@@ -364,6 +364,21 @@ def test_pooling_backward_matches_oracle(torch_mod):
     assert np.array_equal(got == 0, ref == 0)
     assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref))
     d.close()
+    # the same with the producer's ReLU mask applied on the way out (mask_gx), on an input of mixed
+    # signs so that maxima at or below zero exist: their gradient is dropped
+    x = _bits(5, 3, (N, H, W, C))
+    x[0, 0, 0, :8] = [0x8000, 0x0000, 0x7FC0, 0x0001, 0xBF80, 0x3F80, 0x8001, 0x7F80]     # -0, 0, NaN, tiny, -1, 1, -tiny, inf
+    d, put, get = _small_ctx(torch, [xs, ys, ys, xs])
+    put(0, x)
+    put(2, gy)
+    d.backward_segment([dl.BwdDesc(fwd=fwd, gy=2, gpre=2, gx=3, gx_add=dl.NO_TENSOR, mask_gx=1, wt=None, gw=None,
+                                   workspace=None, workspace_bytes=0)])
+    d.sync()
+    got = on.to_f64(get(3, x.shape), "bf16")
+    ref = np.where(on.to_f64(x, "bf16") > 0, on.maxpool_bwd(x, gy, 3, 3, 2, 1, "bf16"), 0.0)
+    assert np.array_equal(got == 0, ref == 0) and (ref != 0).any() and (ref == 0).any()
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref))
+    d.close()
     # global average
     N, H, W, C = 3, 7, 7, 128
     gy = _bits(6, 1, (N, 1, 1, C))
@@ -481,7 +496,9 @@ def test_small_resnet_whole_backward_layer_by_layer(torch_mod, fuse):
             assert ew <= 2e-4, (lname, ew)
         elif l.kind == "maxpool":
             ref_gx = on.maxpool_bwd(acts[l.x], gy, l.R, l.S, l.stride, l.pad, "bf16")
-            assert np.array_equal(got == 0, ref_gx == 0)
+            if masks_gx:                                    # also the stem's ReLU mask
+                ref_gx = np.where(on.to_f64(acts[l.x], "bf16") > 0, ref_gx, 0.0)
+            assert masks_gx == fuse and np.array_equal(got == 0, ref_gx == 0)
         elif l.kind == "avgpool":
             ref_gx = on.avgpool_bwd(gy, l.H, l.W, "bf16")
         else:
