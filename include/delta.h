@@ -288,9 +288,12 @@ typedef struct delta_bwd_desc {
                                   be gy, with stride > 1 gpre receives gy spread to the input's resolution */
     const void *wt;            /* device: weights prepared by delta_bwd_weights (needed when gx is set) */
     void *gw;                  /* device, fp32 [Cout][R][S][Cin]: receives dL/dw (overwritten), or NULL */
-    void *workspace;           /* device scratch, 256-byte aligned: the weight gradient's partial sums and,
-                                  for a strided 1x1 layer, its staging tensor; needed when gw is set or
-                                  (strided 1x1) gx is set */
+    void *workspace;           /* device scratch, 256-byte aligned: the weight gradient's partial sums (from
+                                  its start) and, for a strided 1x1 layer, its staging tensor (at its
+                                  end); needed when gw is set or (strided 1x1) gx is set.  A strided 1x1
+                                  layer whose staging bytes overlap what weight gradients still in flight
+                                  use makes the compute stream wait for them: one workspace of (largest
+                                  partial sums + largest staging tensor) for all layers avoids that */
     uint64_t workspace_bytes;  /* at least what delta_backward_workspace reports */
 } delta_bwd_desc;
 

@@ -99,7 +99,9 @@ __device__ __forceinline__ float gelu_erf(float v) {
     return 0.5f * v * (v < 0.f ? c : 2.0f - c);
 }
 
-template <bool BF16, int BM, int BN, int WM, int WN, bool HAS_RES>
+// SCATTER: the scattered form described at ConvArgs (strided output pixels, a strided subset of the
+// weight tensor's taps, residual read in the epilogue); HAS_RES is then false.
+template <bool BF16, int BM, int BN, int WM, int WN, bool HAS_RES, bool SCATTER = false>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     using E = Elem<BF16>;
     constexpr int ES = E::size;
@@ -167,8 +169,9 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<unsigned char *>(xg) + (size_t)base_pix * cin_bytes, 0,
         (int)(xbytes < 0x7FFFFFFFull ? xbytes : 0x7FFFFFFFull), 0x00020000);
+    const int wtaps = SCATTER ? a.wR * a.wS : a.R * a.S;       // taps per output channel in memory
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned char *>(wg), 0, (int)((size_t)a.Cout * a.R * a.S * cin_bytes), 0x00020000);
+        const_cast<unsigned char *>(wg), 0, (int)((size_t)a.Cout * wtaps * cin_bytes), 0x00020000);
     int h0[XL], w0[XL];
     int xoff[XL];                  // byte offset of the row's tap (0,0) pixel, or kOutOfRange past M
 #pragma unroll
@@ -190,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
 #pragma unroll
     for (int j = 0; j < WL; ++j) {
         const int k = n0 + lrow + 32 * j;
-        woff[j] = k < a.Cout ? (int)((size_t)k * a.R * a.S * cin_bytes) + seg * 16 : kOutOfRange;
+        woff[j] = k < a.Cout ? (int)((size_t)k * wtaps * cin_bytes) + seg * 16 : kOutOfRange;
     }
     const int cslices = a.Cin / KC;
     const int nslices = a.R * a.S * cslices;
@@ -209,7 +212,8 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
         const int tap = it / cslices, cs = it - tap * cslices;
         const int r = tap / a.S, sx = tap - r * a.S;
         const int xadd = (r * a.W + sx) * (int)cin_bytes + cs * kRowBytes;
-        const int wadd = (r * a.S + sx) * (int)cin_bytes + cs * kRowBytes;
+        const int wadd = (SCATTER ? (a.w_r0 + r * a.w_step) * a.wS + a.w_s0 + sx * a.w_step : r * a.S + sx) * (int)cin_bytes +
+                         cs * kRowBytes;
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
             const int h = h0[i] + r, w = w0[i] + sx;
@@ -344,7 +348,27 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(ConvArgs a) {
                     const f32x4 f = *reinterpret_cast<const f32x4 *>(stg + pr * STG_PITCH + (cseg * CPL + e) * 4);
                     v[e] = f.x; v[e + 1] = f.y; v[e + 2] = f.z; v[e + 3] = f.w;
                 }
-                const size_t off = ((size_t)m * a.Cout + chan) * ES;
+                size_t pixel = (size_t)m;
+                if constexpr (SCATTER) {
+                    const int n = m / PQ, pq = m - n * PQ;
+                    const int p = pq / a.Q, q = pq - p * a.Q;
+                    pixel = ((size_t)n * a.OH + (p * a.oy_s + a.oy_a)) * a.OW + (q * a.oy_s + a.oy_b);
+                }
+                const size_t off = (pixel * a.Cout + chan) * ES;
+                if constexpr (SCATTER) {
+                    if (a.res) {
+                        const u32x4 rv = *reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(a.res) + off);
+                        if constexpr (BF16) {
+                            v[0] += bf16_lo(rv.x); v[1] += bf16_hi(rv.x);
+                            v[2] += bf16_lo(rv.y); v[3] += bf16_hi(rv.y);
+                            v[4] += bf16_lo(rv.z); v[5] += bf16_hi(rv.z);
+                            v[6] += bf16_lo(rv.w); v[7] += bf16_hi(rv.w);
+                        } else {
+                            v[0] += __uint_as_float(rv.x); v[1] += __uint_as_float(rv.y);
+                            v[2] += __uint_as_float(rv.z); v[3] += __uint_as_float(rv.w);
+                        }
+                    }
+                }
                 if constexpr (HAS_RES) {
                     const u32x4 rv = rres[g][i][t];
                     if constexpr (BF16) {
@@ -397,7 +421,8 @@ static hipError_t launch(const ConvArgs &a, hipStream_t stream) {
     const long long tiles_m = ((long long)a.M + BM - 1) / BM;
     const long long blocks = tiles_m * ((a.Cout + BN - 1) / BN);
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    if (a.res) conv_igemm_kernel<BF16, BM, BN, WM, WN, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
+    if (a.oy_s) conv_igemm_kernel<BF16, BM, BN, WM, WN, false, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
+    else if (a.res) conv_igemm_kernel<BF16, BM, BN, WM, WN, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
     else conv_igemm_kernel<BF16, BM, BN, WM, WN, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(a);
     return hipGetLastError();
 }
@@ -453,8 +478,48 @@ const char *conv_check(const ConvArgs &a) {
     return nullptr;
 }
 
+// The scattered form: stride 1, no padding, windows of at most 2 x 2 starting AT the output pixel
+// (a tap past the input's last row or column reads zeros), P <= H and Q <= W given by the caller.
+const char *conv_scatter_check(const ConvArgs &a) {
+    const int kc = a.bf16 ? 64 : 32;
+    if (a.N <= 0 || a.H <= 0 || a.W <= 0 || a.R < 1 || a.R > 2 || a.S < 1 || a.S > 2 || a.stride != 1 || a.pad != 0)
+        return "scattered form: windows of 1 or 2, stride 1, no padding";
+    if (a.relu) return "scattered form: no activation";
+    if (a.Cin <= 0 || a.Cin % kc) return "Cin must be a multiple of 64 (bf16) or 32 (fp32)";
+    if (a.Cout <= 0 || a.Cout % (a.bf16 ? 8 : 4)) return "Cout must be a multiple of 8 (bf16) or 4 (fp32)";
+    if (a.P <= 0 || a.Q <= 0 || a.P > a.H || a.Q > a.W) return "output size must be within the input's";
+    if ((long long)a.N * a.P * a.Q != a.M || (long long)a.N * a.P * a.Q > 0x7FFFFFFFLL) return "bad M";
+    if (a.oy_s <= 0 || a.oy_a < 0 || a.oy_b < 0 || a.oy_a >= a.oy_s || a.oy_b >= a.oy_s ||
+        (a.P - 1) * a.oy_s + a.oy_a >= a.OH || (a.Q - 1) * a.oy_s + a.oy_b >= a.OW)
+        return "scattered output pixels leave the output tensor";
+    if (a.w_step <= 0 || a.w_r0 < 0 || a.w_s0 < 0 || a.w_r0 + (a.R - 1) * a.w_step >= a.wR ||
+        a.w_s0 + (a.S - 1) * a.w_step >= a.wS)
+        return "taps leave the weight tensor";
+    const long long es = a.bf16 ? 2 : 4;
+    if ((long long)a.N * a.H * a.W > 0x7FFFFFFFLL || (long long)a.N * a.OH * a.OW > 0x7FFFFFFFLL) return "tensor too large";
+    if ((long long)a.Cout * a.wR * a.wS * a.Cin * es > 0x7FFFFFFFLL) return "weights exceed 2 GiB";
+    const long long images = 127 / ((long long)a.P * a.Q) + 3;
+    if (images * a.H * a.W * a.Cin * es + 256 > 0x7FFFFFFFLL) return "image too large for 32-bit tile offsets";
+    if (!a.x || !a.w || !a.y || !a.scale || !a.shift) return "null pointer";
+    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y | (uintptr_t)a.res | (uintptr_t)a.mask | (uintptr_t)a.scale |
+         (uintptr_t)a.shift) & 15)
+        return "pointers must be 16-byte aligned";
+    return nullptr;
+}
+
+hipError_t launch_conv_scatter(const ConvArgs &a, hipStream_t stream) {
+    if (conv_scatter_check(a)) return hipErrorInvalidValue;
+    const int bn = conv_tile_n(a);
+    if (a.bf16) {
+        if (bn == 128) return launch<true, 128, 128, 2, 2>(a, stream);
+        return launch<true, 128, 64, 4, 1>(a, stream);
+    }
+    if (bn == 128) return launch<false, 128, 128, 2, 2>(a, stream);
+    return launch<false, 128, 64, 4, 1>(a, stream);
+}
+
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
-    if (conv_check(a)) return hipErrorInvalidValue;
+    if (conv_check(a) || a.oy_s) return hipErrorInvalidValue;
     if (conv1x1_stream_applies(a)) return launch_conv1x1_stream(a, stream);
     if (conv3x3_halo_applies(a)) return launch_conv3x3_halo(a, stream);
     if (gemm_nt_applies(a)) return launch_gemm_nt(a, stream);

@@ -78,6 +78,7 @@ struct delta_ctx {
     int device = -1;
     hipStream_t stream[N_STREAMS] = {nullptr, nullptr, nullptr, nullptr};
     Ev aux_tail;                                   // last launch on S_AUX the compute stream has not joined
+    uintptr_t aux_lo = 0, aux_hi = 0;              // caller memory (workspace) those launches use: [aux_lo, aux_hi)
     std::map<uint64_t, Block> free_blocks;         // offset -> block, coalesced
     std::map<uint64_t, uint64_t> used;             // offset -> size
     std::vector<Tensor> tensors;
@@ -936,6 +937,31 @@ delta_status prepare_backward_other(delta_ctx *c, const delta_bwd_desc &D, uint3
 // computed at the output's resolution (input pixels gathered, data gradient spread back out).
 bool strided_1x1(const delta_layer_desc &L) { return L.stride > 1 && L.R == 1 && L.S == 1 && L.pad == 0; }
 
+// A 3x3 stride-2 pad-1 layer whose incoming gradient needs no mask of its own: input pixel (2i+a, 2j+b)
+// only receives from the taps with r = a + 1 (mod 2) and s = b + 1 (mod 2), so its data gradient is four
+// small convolutions of gy at the OUTPUT's resolution (1, 2, 2 and 4 taps: the nine taps once, where
+// the stride-1 convolution of the zero-filled gradient does four times that work), each storing to
+// its own parity class of gx.
+bool class_dgrad(const delta_bwd_desc &D) {
+    const delta_layer_desc &L = D.fwd;
+    return L.stride == 2 && L.R == 3 && L.S == 3 && L.pad == 1 && D.gx != DELTA_NO_TENSOR && (!L.relu || D.gy_masked);
+}
+
+// Geometry of class (a, b): a convolution of gy [N,P,Q,Cout] with window (1+a) x (1+b) starting at
+// the output pixel; tap t along a dimension of class 1 is r = 2 - 2t, i.e. index 2t of the flipped
+// weights delta_bwd_weights prepares; class 0 uses r = 1, index 1.
+void class_args(const delta_layer_desc &L, int bf16, int a, int b, delta::ConvArgs &ca) {
+    memset(&ca, 0, sizeof ca);
+    const int P = (L.H + 2 - 3) / 2 + 1, Q = (L.W + 2 - 3) / 2 + 1;
+    ca.N = L.N; ca.H = P; ca.W = Q; ca.Cin = L.Cout; ca.Cout = L.Cin;
+    ca.R = 1 + a; ca.S = 1 + b; ca.stride = 1; ca.pad = 0;
+    ca.P = (L.H - a + 1) / 2; ca.Q = (L.W - b + 1) / 2;
+    ca.M = ca.N * ca.P * ca.Q;
+    ca.relu = 0; ca.bf16 = bf16;
+    ca.oy_s = 2; ca.oy_a = a; ca.oy_b = b; ca.OH = L.H; ca.OW = L.W;
+    ca.wR = 3; ca.wS = 3; ca.w_r0 = a ? 0 : 1; ca.w_s0 = b ? 0 : 1; ca.w_step = 2;
+}
+
 // `fa` (the forward layer's arguments) as the weight gradient sees the layer: stride 1.
 void as_stride_1(const delta_layer_desc &L, delta::ConvArgs &fa) {
     if (strided_1x1(L)) { fa.H = fa.P; fa.W = fa.Q; }
@@ -1005,6 +1031,16 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
         da.x = da.y = c->arena; da.w = D.wt; da.scale = da.shift = reinterpret_cast<const float *>(c->arena);
         const char *why = delta::conv_check(da);
         if (why) return fail(c, DELTA_ERR_INVALID, "backward %u: data gradient: %s", i, why);
+        if (class_dgrad(D)) {
+            for (int cls = 0; cls < 4; ++cls) {
+                delta::ConvArgs ca;
+                class_args(L, fa.bf16, cls >> 1, cls & 1, ca);
+                if (ca.P <= 0 || ca.Q <= 0) continue;              // a one-pixel-high or -wide input has no odd rows / columns
+                ca.x = ca.y = c->arena; ca.w = D.wt; ca.scale = ca.shift = reinterpret_cast<const float *>(c->arena);
+                if ((why = delta::conv_scatter_check(ca)) != nullptr)
+                    return fail(c, DELTA_ERR_INVALID, "backward %u: data gradient by parity class: %s", i, why);
+            }
+        }
     } else if (D.gx_add != DELTA_NO_TENSOR) {
         return fail(c, DELTA_ERR_INVALID, "backward %u: gx_add without gx", i);
     }
@@ -1045,7 +1081,20 @@ delta_status join_aux(delta_ctx *c) {
         HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], c->aux_tail.e, 0));
         c->aux_tail = Ev();
     }
+    c->aux_lo = c->aux_hi = 0;
     return DELTA_OK;
+}
+
+// Workspace bytes [p, p + n) are about to be used by a weight gradient on S_AUX / by the compute stream.
+void aux_claims(delta_ctx *c, const void *p, uint64_t n) {
+    const uintptr_t lo = (uintptr_t)p, hi = lo + n;
+    if (c->aux_lo == c->aux_hi) { c->aux_lo = lo; c->aux_hi = hi; return; }
+    if (lo < c->aux_lo) c->aux_lo = lo;
+    if (hi > c->aux_hi) c->aux_hi = hi;
+}
+bool aux_holds(const delta_ctx *c, const void *p, uint64_t n) {
+    const uintptr_t lo = (uintptr_t)p, hi = lo + n;
+    return c->aux_tail && lo < c->aux_hi && c->aux_lo < hi;
 }
 
 }  // namespace
@@ -1203,10 +1252,13 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         const bool own_mask = L.relu && !D.gy_masked;
         const bool direct = strided_1x1(L);
         const int outP = (L.H + 2 * L.pad - L.R) / L.stride + 1, outQ = (L.W + 2 * L.pad - L.S) / L.stride + 1;
-        unsigned char *staging = direct ? static_cast<unsigned char *>(D.workspace) + partials_bytes(fa) : nullptr;
-        // A strided 1x1 layer stages both of its gradients in the workspace, which weight gradients
-        // still running on the other stream may be using: it waits for them and stays in line.
-        if (direct && (r = join_aux(c)) != DELTA_OK) return r;
+        // A strided 1x1 layer stages both of its gradients at the END of the workspace; weight gradients
+        // still running on the other stream use its beginning.  Only if the two ranges meet (a
+        // workspace no larger than this layer needs) does the compute stream wait for them.
+        const uint64_t stg_bytes = direct ? staging_bytes(L, fa) : 0;
+        unsigned char *staging =
+            direct ? static_cast<unsigned char *>(D.workspace) + ((D.workspace_bytes - stg_bytes) & ~(uint64_t)255) : nullptr;
+        if (direct && aux_holds(c, staging, stg_bytes) && (r = join_aux(c)) != DELTA_OK) return r;
         if (own_mask || (L.stride > 1 && !direct)) {
             Tensor &tgp = c->tensors[D.gpre];
             const unsigned char *yp = nullptr;
@@ -1245,29 +1297,43 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
             da.x = gp; da.w = D.wt; da.res = addp; da.mask = maskp; da.y = c->arena + tgx.offset;
             da.scale = c->ones; da.shift = c->zeros;
             if (direct) { da.res = nullptr; da.mask = nullptr; da.y = staging; }
+            if (class_dgrad(D)) {
+                for (int cls = 0; cls < 4; ++cls) {
+                    delta::ConvArgs ca;
+                    class_args(L, fa.bf16, cls >> 1, cls & 1, ca);
+                    if (ca.P <= 0 || ca.Q <= 0) continue;
+                    ca.x = c->arena + tgy.offset; ca.w = D.wt; ca.res = addp; ca.mask = maskp; ca.y = c->arena + tgx.offset;
+                    ca.scale = c->ones; ca.shift = c->zeros;
+                    HIP_TRY(c, delta::launch_conv_scatter(ca, s));
+                }
+            } else
             HIP_TRY(c, delta::launch_conv(da, s));
             if (direct)
                 HIP_TRY(c, delta::launch_spread_add(staging, addp, maskp, c->arena + tgx.offset, L.N, L.H, L.W, outP, outQ,
                                                     L.Cin, L.stride, fa.bf16, s));
-            c->st.recompute_flops += 2ull * (uint64_t)da.M * da.R * da.S * da.Cin * da.Cout;
+            c->st.recompute_flops += class_dgrad(D) ? 2ull * (uint64_t)L.N * outP * outQ * 9 * L.Cin * L.Cout
+                                                    : 2ull * (uint64_t)da.M * da.R * da.S * da.Cin * da.Cout;
         }
         if (D.gw) {
             Tensor &tx = c->tensors[L.x];
             if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
             fa.x = c->arena + tx.offset;
+            // gpre and x are complete once the compute stream reaches `ready` (for a strided 1x1 layer:
+            // and the data gradient has left the staging area); from there the weight gradient runs on
+            // its own stream, and both tensors remember that reader.
+            if (direct && (r = new_event(c, s, &ready)) != DELTA_OK) return r;
+            HIP_TRY(c, hipStreamWaitEvent(c->stream[S_AUX], ready.e, 0));
             if (direct) {
-                HIP_TRY(c, delta::launch_subsample(fa.x, staging, L.N, L.H, L.W, outP, outQ, L.Cin, L.stride, fa.bf16, s));
+                HIP_TRY(c, delta::launch_subsample(fa.x, staging, L.N, L.H, L.W, outP, outQ, L.Cin, L.stride, fa.bf16,
+                                                   c->stream[S_AUX]));
                 fa.x = staging;
-                HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa), s));
-            } else {
-                // gpre and x are complete once the compute stream reaches `ready`; from there the
-                // weight gradient runs on its own stream, and both tensors remember that reader.
-                HIP_TRY(c, hipStreamWaitEvent(c->stream[S_AUX], ready.e, 0));
-                HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa),
-                                               c->stream[S_AUX]));
-                if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
-                tx.aux_done = c->tensors[D.gpre].aux_done = c->aux_tail;
+                aux_claims(c, staging, stg_bytes);
             }
+            HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa),
+                                           c->stream[S_AUX]));
+            aux_claims(c, D.workspace, partials_bytes(fa));
+            if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
+            tx.aux_done = c->tensors[D.gpre].aux_done = c->aux_tail;
             c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
         }
         c->st.recompute_launches += 1;

@@ -16,6 +16,13 @@ struct ConvArgs {
     int N, H, W, Cin, Cout, R, S, stride, pad, P, Q, M;
     int relu;             // 0: none, 1: ReLU, 2: GELU (erf form; tiled kernel only)
     int bf16;             // 1: bf16 storage, fp32 accumulate; 0: fp32
+    // Scattered form (launch_conv_scatter only; the data gradient of a strided layer, one parity
+    // class of input pixels at a time).  oy_s > 0: output pixel (n, p, q) is stored at pixel
+    // (n, p * oy_s + oy_a, q * oy_s + oy_b) of an [N, OH, OW, Cout] tensor; res and mask are read
+    // there; P and Q are the caller's (a tap that leaves the input reads zeros); the R x S taps are
+    // taps (w_r0 + r * w_step, w_s0 + s * w_step) of a weight tensor [Cout, wR, wS, Cin].
+    int oy_s = 0, oy_a = 0, oy_b = 0, OH = 0, OW = 0;
+    int wR = 0, wS = 0, w_r0 = 0, w_s0 = 0, w_step = 1;
 };
 
 // The test behind every ReLU mask of the backward pass.  bf16: greater than zero <=> sign bit clear,
@@ -35,6 +42,8 @@ __device__ __forceinline__ uint32_t keep_where_positive_f32(uint32_t v, uint32_t
 const char *conv_check(const ConvArgs &a);
 const char *conv_kernel_name(const ConvArgs &a);
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream);
+const char *conv_scatter_check(const ConvArgs &a);
+hipError_t launch_conv_scatter(const ConvArgs &a, hipStream_t stream);
 // conv1x1.hip: streaming kernel for bf16 1x1 convolutions whose weights fit LDS
 bool conv1x1_stream_applies(const ConvArgs &a);
 hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream);

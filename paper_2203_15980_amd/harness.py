@@ -214,7 +214,9 @@ class Net:
                     d.bwd_weights(fwd, self.wt[l.name].data_ptr())
                 self.gw[l.name] = torch.zeros(n, dtype=torch.float32, device=dev)
                 ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
-        self.bwd_workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # twice the largest single need: room for the largest partial sums and the largest staging
+        # tensor side by side, so that no layer has to wait for weight gradients still in flight
+        self.bwd_workspace = torch.empty(2 * ws_bytes, dtype=torch.uint8, device=dev)
         self.input_gradient = input_gradient
         if not self.has_loss:
             n = int(np.prod(self.shapes[top.y]))
@@ -590,7 +592,7 @@ class OpNet:
                     d.bwd_weights(fwd, self.wt[name].data_ptr())
                 self.gw[name] = torch.zeros(n, dtype=torch.float32, device=dev)
                 ws_bytes = max(ws_bytes, d.backward_workspace(fwd))
-        self.bwd_workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.bwd_workspace = torch.empty(2 * ws_bytes, dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
 
     def _bwd_plan(self, name, pending, refs):

@@ -44,7 +44,11 @@ CASES = [
     ("1x1_256_64_fxy", 3,  9, 11, 256,  64, 1, True, False, True, 1, "xy"),   # streaming kernel, sliced, with gx_add
     ("1x1_128_256_fx", 2, 10, 10, 128, 256, 1, True, False, True, 1, "x"),    # tiled kernel
     ("3x3_64_fxy",     2, 14, 14,  64,  64, 3, True, False, False, 1, "xy"),  # halo kernel
-    ("3x3_s2_fy",      2, 14, 14,  64, 128, 3, True, False, False, 2, "y"),   # strided: masked gy is only spread out
+    ("3x3_s2_fy",      2, 14, 14,  64, 128, 3, True, False, False, 2, "y"),   # strided: masked gy is only spread out;
+                                                                               # data gradient by parity class
+    ("3x3_s2_odd_fxy", 2,  9, 13, 128,  64, 3, True, False, True, 2, "xy"),   # the same on odd sizes, + gx_add, + mask_gx
+    ("3x3_s2_norelu",  1, 12, 10,  64,  64, 3, False, False, True, 2, "x"),   # no mask of its own either
+    ("3x3_s2_1row",    3,  1,  8,  64,  64, 3, True, False, False, 2, "y"),   # a single input row: no odd rows
 ]
 
 
