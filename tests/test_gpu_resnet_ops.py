@@ -217,3 +217,53 @@ def test_config3_full_size_sampled_image(torch_mod):
     want = float(on.softmax_ce(net.read("logits"), net.labels_np, "bf16")[0])    # all 128 images
     assert np.isfinite(loss) and abs(loss - want) <= 1e-4 * abs(want), (loss, want)
     d.close()
+
+
+def test_resnet50_training_step_replay_repeats_its_gradients_bit_for_bit(torch_mod):
+    """ResNet-50 (config 3's graph at batch 16) as a whole training step: unconstrained once, then
+    five replays of the plan for 40 % of the activation bytes in an arena with no room to spare
+    (1.25 x the budget + the gradient tensors), with swaps on both copy streams, recomputation,
+    the true backward and the weight gradients on their own stream.  Recomputation returns the
+    forward's bits and every reduction has a fixed order, so every parameter gradient of every
+    replay must equal the unconstrained step's bit for bit; any missing fence between the four
+    streams shows up as a difference."""
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net, run_plan
+    torch = torch_mod
+    N = 16
+    layers = synth.resnet_layers(N)
+    g = synth.fused_graph(layers, "bf16", with_loss=True)
+    boot = make_delta(torch, 1 << 20)
+    boot.bind([t["bytes"] for t in g.tensors])
+    net = Net(boot, layers, "bf16", synth.master_seed(3), with_loss=True)
+    net.enable_backward()
+    grad_peak = net.backward_peak_bytes()
+    boot.close()
+    d = make_delta(torch, g.total_bytes() + 2 * grad_peak + (64 << 20))
+    net.rebind(d)
+    p0 = opl.default_params(10**15, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9)
+    ev0, _ = dl.plan(g.tensors, g.steps, p0)
+    run_plan(net, g, ev0, backward_proxy=lambda k: net.backward_step(g, k))
+    d.sync()
+    assert d.stats()["arena_in_use"] == 0
+    want = {n: t.clone() for n, t in net.gw.items()}
+    assert all(torch.isfinite(t).all() and t.abs().max() > 0 for t in want.values())
+    d.close()
+    budget = int(g.total_bytes() * 0.4)
+    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9)
+    ev, peak = dl.plan(g.tensors, g.steps, p)
+    kinds = {a for (_, a, _) in ev}
+    print("events", sorted(kinds), "peak", peak, "budget", budget, flush=True)
+    assert dl.EV_RECOMPUTE in kinds and dl.EV_OFFLOAD in kinds
+    d = make_delta(torch, budget + budget // 4 + grad_peak + grad_peak // 2 + (8 << 20))
+    net.rebind(d)
+    for rep in range(5):
+        for t in net.gw.values():
+            t.fill_(float("nan"))
+        run_plan(net, g, ev, backward_proxy=lambda k: net.backward_step(g, k))
+        d.sync()
+        st = d.stats()
+        assert st["arena_in_use"] == 0 and st["d2h_copies"] > 0
+        for n, t in net.gw.items():
+            assert torch.equal(t.view(torch.int32), want[n].view(torch.int32)), (rep, n)
+    d.close()
