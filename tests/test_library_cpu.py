@@ -30,9 +30,12 @@ def test_library_exports_every_declared_symbol():
 
 def test_planner_only_context_rejects_gpu_calls():
     d = dl.Delta()
-    with pytest.raises(dl.DeltaError) as e:
-        d.bind([16])
-    assert e.value.status == dl.ERR_STATE
+    for call in (lambda: d.bind([16]), lambda: d.alloc(0), lambda: d.release(0, dl.EV_FREE), lambda: d.prefetch(0),
+                 lambda: d.swap_out(0), lambda: d.sync(), lambda: d.backward_join(), lambda: d.backward_segment([]),
+                 lambda: d.recompute_segment([])):
+        with pytest.raises(dl.DeltaError) as e:
+            call()
+        assert e.value.status == dl.ERR_STATE
     d.close()
 
 
