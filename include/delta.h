@@ -275,7 +275,10 @@ typedef struct delta_bwd_desc {
     uint32_t gpre;             /* tensor id that receives gpre: N*H*W*Cout elements (the bytes of y when
                                   stride == 1 or the layer is 1x1); allocated if not resident.  Must equal
                                   gy when there is nothing to write: no ReLU mask to apply (fwd.relu == 0
-                                  or gy_masked) and stride == 1 or a 1x1 layer */
+                                  or gy_masked) and stride == 1 or a 1x1 layer.  May equal gy with no mask
+                                  to apply on a 3x3 stride-2 pad-1 layer whose gradients both run at the
+                                  output's resolution (bf16; if gw is set, channel counts multiples of
+                                  128): gy is then not spread out and gpre not written */
     uint32_t gx;               /* tensor id that receives dL/dx (bytes of x), or DELTA_NO_TENSOR */
     uint32_t gx_add;           /* resident tensor (bytes of x) added to dL/dx before it is stored: the
                                   contribution of another consumer of x; or DELTA_NO_TENSOR */

@@ -112,8 +112,10 @@ __global__ __launch_bounds__(256) void relu_mask_dilate_kernel(const u32x4 *__re
 //   t = 1x1 data gradient of gpre at P x Q
 //   gx[n,h,w,:] = (t[n,h/s,w/s,:] on the grid, else 0) + gx_add, optionally * [x > 0]   spread_add_kernel
 // One 16-byte piece per thread in both.
+// With offsets: xs[n,p,q,:] = x[n, s p + oa, s q + ob, :], zeros where that pixel lies outside the image.
 __global__ __launch_bounds__(256) void subsample_kernel(const u32x4 *__restrict__ x, u32x4 *__restrict__ xs, int H, int W,
-                                                        int P, int Q, int vec_per_pixel, int stride, size_t n16) {
+                                                        int P, int Q, int vec_per_pixel, int stride, int oa, int ob,
+                                                        size_t n16) {
     const size_t step = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
         const size_t pix = i / vec_per_pixel;
@@ -122,7 +124,10 @@ __global__ __launch_bounds__(256) void subsample_kernel(const u32x4 *__restrict_
         const size_t rest = pix / Q;
         const int p = (int)(rest % P);
         const size_t n = rest / P;
-        xs[i] = x[((n * H + (size_t)p * stride) * W + (size_t)q * stride) * vec_per_pixel + v];
+        const int h = p * stride + oa, w = q * stride + ob;
+        u32x4 val = {0u, 0u, 0u, 0u};
+        if (h < H && w < W) val = x[((n * H + (size_t)h) * W + (size_t)w) * vec_per_pixel + v];
+        xs[i] = val;
     }
 }
 
@@ -205,9 +210,13 @@ struct WgradArgs {
     int QN;              // positions per chunk: RH * (W + R - 1), rounded up to 16
     int XN;              // staged activation positions: QN + (R - 1) * (W + R - 1) + (R - 1)
     int nsplit;
+    unsigned long long tapwin;   // 4 bits per tap: its position r * R + s in the R x R window (a subset of the
+                                 // window's taps when TAPS < R * R)
+    int XH, XW, xstep, xoa, xob; // x is [N,XH,XW,C] and position (h, w) reads its pixel (h * xstep + xoa, w * xstep + xob),
+                                 // zeros past the image (XH = H, XW = W, xstep = 1, offsets 0: x as it is)
 };
 
-// KTW x CTW tiles of 64 x 64 [k, c] per workgroup and tap; TAPS = R * R.
+// KTW x CTW tiles of 64 x 64 [k, c] per workgroup and tap; TAPS = R * R, or fewer: the taps tapwin lists.
 template <int KTW, int CTW, int TAPS>
 __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs a) {
     constexpr int NW = KTW * CTW * TAPS, NT = NW * 64;
@@ -221,7 +230,8 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int tap = wv % TAPS, kw = (wv / TAPS) % KTW, cw = wv / (TAPS * KTW);
     const int B = (a.R - 1) / 2, Wp = a.W + 2 * B;
-    const int r = tap / a.R, s = tap - r * a.R;
+    const int win = (int)((a.tapwin >> (4 * tap)) & 15);
+    const int r = win / a.R, s = win - r * a.R;
     const int tapoff = a.R == 1 ? 0 : r * Wp + s;               // activation row of position q is q + tapoff
     const int ktiles = a.K / (64 * KTW);
     const int ty = blockIdx.y, ct = ty / ktiles, kt = ty - ct * ktiles;   // channel tile groups of this workgroup
@@ -229,7 +239,7 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
     const int nchunks = a.N * HB;
 
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<void *>(a.x), 0, (int)((size_t)a.N * a.H * a.W * a.C * 2), 0x00020000);
+        const_cast<void *>(a.x), 0, (int)((size_t)a.N * a.XH * a.XW * a.C * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void *>(a.g), 0, (int)((size_t)a.N * a.H * a.W * a.K * 2), 0x00020000);
 
@@ -281,8 +291,9 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
             }
             {
                 const int h = h0 + x_row[p];
-                const bool ok = live && x_col[p] >= 0 && h >= 0 && h < a.H && x_row[p] > -1000;
-                const int off = (int)((((size_t)n * a.H + h) * a.W + x_col[p]) * a.C * 2) + ct * (CTW * 128) + (idx % XSEG) * 16;
+                const int xh = h * a.xstep + a.xoa, xw = x_col[p] * a.xstep + a.xob;
+                const bool ok = live && x_col[p] >= 0 && h >= 0 && h < a.H && x_row[p] > -1000 && xh < a.XH && xw < a.XW;
+                const int off = (int)((((size_t)n * a.XH + xh) * a.XW + xw) * a.C * 2) + ct * (CTW * 128) + (idx % XSEG) * 16;
                 rx[p] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, ok ? off : kOutOfRange, 0, 0);
             }
         }
@@ -356,8 +367,10 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
 // accumulator layout of a 32x32 tile is: lane l holds column l % 32 and rows 8 e4 + 4 (l / 32) + e
 // in register 4 e4 + e, so a thread's four sums go to four k rows of one c, and consecutive lanes
 // write consecutive c.
+// gw_taps: taps per (k, c) pair in gw; tapout: 4 bits per tap of this launch, its index among them.
 __global__ __launch_bounds__(512) void wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int K,
-                                                           int C, int taps, int KTW, int CTW, int nsplit) {
+                                                           int C, int taps, int KTW, int CTW, int nsplit, int gw_taps,
+                                                           unsigned long long tapout) {
     __shared__ f32x4 part[8][64];
     const int ktiles = K / (64 * KTW), tiles_y = (C / (64 * CTW)) * ktiles;
     const int NW = KTW * CTW * taps;
@@ -389,7 +402,7 @@ __global__ __launch_bounds__(512) void wgrad_reduce_kernel(const float *partial,
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const int k = k0 + e;
-        gw[((size_t)k * taps + tap) * C + c] = sum[e] * scale[k];
+        gw[((size_t)k * gw_taps + (int)((tapout >> (4 * tap)) & 15)) * C + c] = sum[e] * scale[k];
     }
 }
 
@@ -434,15 +447,17 @@ hipError_t launch_relu_mask_dilate(const void *y, const void *gy, void *out, int
 
 // xs: [N,P,Q,C] = x[N,H,W,C] at the pixels (stride p, stride q).
 hipError_t launch_subsample(const void *x, void *xs, int N, int H, int W, int P, int Q, int C, int stride, int bf16,
-                            hipStream_t stream) {
+                            hipStream_t stream, int oa, int ob) {
     const size_t row_bytes = (size_t)C * (bf16 ? 2 : 4);
-    if (row_bytes % 16 || stride < 1 || (P - 1) * stride >= H || (Q - 1) * stride >= W) return hipErrorInvalidValue;
+    if (row_bytes % 16 || stride < 1 || oa < 0 || ob < 0 || oa >= stride || ob >= stride) return hipErrorInvalidValue;
+    if (oa == 0 && ob == 0 && ((P - 1) * stride >= H || (Q - 1) * stride >= W)) return hipErrorInvalidValue;
     const size_t n16 = (size_t)N * P * Q * (row_bytes / 16);
     if (n16 == 0) return hipSuccess;
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     bwd::subsample_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
-        static_cast<const bwd::u32x4 *>(x), static_cast<bwd::u32x4 *>(xs), H, W, P, Q, (int)(row_bytes / 16), stride, n16);
+        static_cast<const bwd::u32x4 *>(x), static_cast<bwd::u32x4 *>(xs), H, W, P, Q, (int)(row_bytes / 16), stride, oa, ob,
+        n16);
     return hipGetLastError();
 }
 
@@ -501,7 +516,8 @@ ConvArgs flattened_1x1(const ConvArgs &a) {
     return f;
 }
 
-const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p) {
+// ntaps: 0 = all R * S taps; 1, 2 or 4 = a subset of a 3 x 3 window's taps (the strided layers' parity classes)
+const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
     const ConvArgs a = flattened_1x1(a_in);
     if (!a.bf16) return "weight gradient: bf16 only";
     if (a.R != a.S || (a.R != 1 && a.R != 3) || a.stride != 1 || a.pad != (a.R - 1) / 2)
@@ -509,8 +525,11 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p) {
     if (a.Cin % 64 || a.Cout % 64) return "weight gradient: channel counts must be multiples of 64";
     if ((unsigned long long)a.M * a.Cin * 2ull >= 0x7FFFFFFFull || (unsigned long long)a.M * a.Cout * 2ull >= 0x7FFFFFFFull)
         return "weight gradient: tensors of 2 GiB or more";
-    p.taps = a.R * a.S;
+    p.taps = ntaps ? ntaps : a.R * a.S;
+    if (ntaps && (a.R != 3 || (ntaps != 1 && ntaps != 2 && ntaps != 4) || a.Cin % 128 || a.Cout % 128))
+        return "weight gradient: a tap subset needs a 3x3 window and channel counts that are multiples of 128";
     if (p.taps == 9) { p.ktw = 1; p.ctw = 1; }
+    else if (ntaps) { p.ktw = 2; p.ctw = ntaps == 4 ? 1 : 2; }        // eight wavefronts either way
     else {
         p.ktw = a.Cout % 256 == 0 ? 4 : (a.Cout % 128 == 0 ? 2 : 1);
         // 128 x 128 tiles where both channel counts allow: the staging registers then hold chunks of
@@ -586,12 +605,17 @@ size_t wgrad_workspace_bytes(const ConvArgs &a) {
     return wgrad_plan(a, p) ? 0 : p.partial_bytes;
 }
 
-// a: the forward layer's geometry with a.x = x, a.scale = scale; g = gpre [N,P,Q,Cout]; gw fp32
-// [Cout][R][S][Cin]; workspace of at least wgrad_workspace_bytes(a), 16-byte aligned.
-hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
-                        hipStream_t stream) {
+namespace {
+
+// One weight-gradient launch + its reduction.  ntaps / tapwin: see wgrad_plan and WgradArgs; the
+// sums go to taps tapout (4 bits each) of a gw with gw_taps taps per (k, c).
+struct XView { int XH, XW, step, oa, ob; };                  // see WgradArgs; XH = 0: x as it is
+
+hipError_t run_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes, int ntaps,
+                     unsigned long long tapwin, int gw_taps, unsigned long long tapout, hipStream_t stream,
+                     XView xv = XView{0, 0, 1, 0, 0}) {
     WgradPlan p;
-    if (wgrad_plan(a, p) || !g || !gw || !workspace || workspace_bytes < p.partial_bytes ||
+    if (wgrad_plan(a, p, ntaps) || !g || !gw || !workspace || workspace_bytes < p.partial_bytes ||
         ((uintptr_t)workspace | (uintptr_t)g | (uintptr_t)a.x) & 15)
         return hipErrorInvalidValue;
     const ConvArgs f = flattened_1x1(a);
@@ -599,10 +623,15 @@ hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *works
     wa.x = a.x; wa.g = g; wa.partial = static_cast<float *>(workspace);
     wa.N = f.N; wa.H = f.H; wa.W = f.W; wa.C = a.Cin; wa.K = a.Cout; wa.R = a.R;
     wa.RH = p.rh; wa.QN = p.qn; wa.XN = p.xn; wa.nsplit = p.nsplit;
+    wa.tapwin = tapwin;
+    wa.XH = xv.XH ? xv.XH : f.H; wa.XW = xv.XH ? xv.XW : f.W; wa.xstep = xv.step; wa.xoa = xv.oa; wa.xob = xv.ob;
+    if ((unsigned long long)f.N * wa.XH * wa.XW * a.Cin * 2ull >= 0x7FFFFFFFull) return hipErrorInvalidValue;
     hipError_t e;
     const int key = p.taps * 100 + p.ktw * 10 + p.ctw;
     switch (key) {
     case 911: e = launch_wgrad_t<1, 1, 9>(wa, p, stream); break;
+    case 421: e = launch_wgrad_t<2, 1, 4>(wa, p, stream); break;
+    case 222: e = launch_wgrad_t<2, 2, 2>(wa, p, stream); break;
     case 111: e = launch_wgrad_t<1, 1, 1>(wa, p, stream); break;
     case 112: e = launch_wgrad_t<1, 2, 1>(wa, p, stream); break;
     case 114: e = launch_wgrad_t<1, 4, 1>(wa, p, stream); break;
@@ -614,8 +643,77 @@ hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *works
     if (e != hipSuccess) return e;
     const size_t quads = (size_t)p.tiles_y * p.waves * 1024;   // f32x4 elements of one split
     bwd::wgrad_reduce_kernel<<<dim3((unsigned)(quads / 64)), dim3(512), 0, stream>>>(
-        wa.partial, a.scale, gw, a.Cout, a.Cin, p.taps, p.ktw, p.ctw, p.nsplit);
+        wa.partial, a.scale, gw, a.Cout, a.Cin, p.taps, p.ktw, p.ctw, p.nsplit, gw_taps, tapout);
     return hipGetLastError();
+}
+
+const unsigned long long kAllTaps = 0x876543210ull;             // tap t of 9 is window position t and output tap t
+
+// The parity classes of a 3x3 stride-2 pad-1 layer.  x[2p + r - 1] is, for r = 1, pixel p of the even
+// rows; for r = 0 and r = 2, pixels p - 1 and p of the odd rows.  So against the class tensor
+// X_ab[n,i,j,:] = x[n, 2i + a, 2j + b, :] (zeros past the image) the layer's weight gradient is a
+// stride-1 weight gradient at the output's resolution that needs, per dimension, window position 1
+// (shift 0) for class 0 and window positions 0 and 1 (shifts -1, 0) for class 1 - these feed the
+// layer's taps 1, and 0 and 2.
+struct S2Class { int a, b, ntaps; unsigned long long tapwin, tapout; };
+const S2Class kS2Classes[4] = {
+    {0, 0, 1, 0x4ull, 0x4ull},                                   // window (1,1) -> layer tap (1,1)
+    {0, 1, 2, 0x43ull, 0x53ull},                                 // window (1,0), (1,1) -> layer taps (1,0), (1,2)
+    {1, 0, 2, 0x41ull, 0x71ull},                                 // window (0,1), (1,1) -> layer taps (0,1), (2,1)
+    {1, 1, 4, 0x4310ull, 0x8620ull},                             // window (0,0), (0,1), (1,0), (1,1) -> (0,0), (0,2), (2,0), (2,2)
+};
+
+ConvArgs s2_class_layer(const ConvArgs &a, const S2Class &, const void *cls) {
+    ConvArgs ca = a;
+    ca.H = a.P; ca.W = a.Q; ca.stride = 1;
+    ca.R = ca.S = 3;
+    ca.pad = 1;
+    ca.M = a.N * a.P * a.Q;
+    ca.x = cls;
+    return ca;
+}
+
+}  // namespace
+
+// a: the forward layer's geometry with a.x = x, a.scale = scale; g = gpre [N,P,Q,Cout]; gw fp32
+// [Cout][R][S][Cin]; workspace of at least wgrad_workspace_bytes(a), 16-byte aligned.
+hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
+                        hipStream_t stream) {
+    const int taps = a.R * a.S;
+    return run_wgrad(a, g, gw, workspace, workspace_bytes, 0, taps == 9 ? kAllTaps : 0ull, taps, taps == 9 ? kAllTaps : 0ull,
+                     stream);
+}
+
+// The weight gradient of a 3x3 stride-2 pad-1 bf16 layer by parity class, from dL/d(pre-activation)
+// at the OUTPUT's resolution: four weight gradients at that resolution, each reading its class of
+// x's pixels in place (the kernel's staging addresses pixel (2i + a, 2j + b)), each with its reduction.
+bool wgrad_s2_applies(const ConvArgs &a) {
+    return a.bf16 && a.R == 3 && a.S == 3 && a.stride == 2 && a.pad == 1 && a.Cin % 128 == 0 && a.Cout % 128 == 0 &&
+           a.P == (a.H - 1) / 2 + 1 && a.Q == (a.W - 1) / 2 + 1;
+}
+
+size_t wgrad_s2_workspace_bytes(const ConvArgs &a) {
+    if (!wgrad_s2_applies(a)) return 0;
+    size_t most = 0;
+    for (const S2Class &c : kS2Classes) {
+        WgradPlan p;
+        if (wgrad_plan(s2_class_layer(a, c, a.x), p, c.ntaps)) return 0;
+        most = p.partial_bytes > most ? p.partial_bytes : most;
+    }
+    return (most + 255) / 256 * 256;
+}
+
+hipError_t launch_wgrad_s2(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
+                           hipStream_t stream) {
+    const size_t need = wgrad_s2_workspace_bytes(a);
+    if (!need || workspace_bytes < need || !g || !gw || !workspace || !a.x || !a.scale || ((uintptr_t)workspace & 255))
+        return hipErrorInvalidValue;
+    for (const S2Class &c : kS2Classes) {
+        const hipError_t e = run_wgrad(s2_class_layer(a, c, a.x), g, gw, workspace, need, c.ntaps, c.tapwin,
+                                       9, c.tapout, stream, XView{a.H, a.W, 2, c.a, c.b});
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace delta

@@ -947,6 +947,19 @@ bool class_dgrad(const delta_bwd_desc &D) {
     return L.stride == 2 && L.R == 3 && L.S == 3 && L.pad == 1 && D.gx != DELTA_NO_TENSOR && (!L.relu || D.gy_masked);
 }
 
+// The same layers' weight gradient by parity class (delta::launch_wgrad_s2): bf16, channel counts that
+// are multiples of 128.  `fo`: the forward layer's own arguments.
+bool class_layer(const delta_bwd_desc &D) {
+    const delta_layer_desc &L = D.fwd;
+    return L.stride == 2 && L.R == 3 && L.S == 3 && L.pad == 1 && (!L.relu || D.gy_masked);
+}
+bool class_wgrad(const delta_bwd_desc &D, const delta::ConvArgs &fo) { return D.gw && class_layer(D) && delta::wgrad_s2_applies(fo); }
+// Everything such a layer was asked for runs at the output's resolution: no zero-filled copy of gy is
+// needed, and the caller may say so by passing gpre = gy.
+bool class_only(const delta_bwd_desc &D, const delta::ConvArgs &fo) {
+    return class_layer(D) && (!D.gw || delta::wgrad_s2_applies(fo));
+}
+
 // Geometry of class (a, b): a convolution of gy [N,P,Q,Cout] with window (1+a) x (1+b) starting at
 // the output pixel; tap t along a dimension of class 1 is r = 2 - 2t, i.e. index 2t of the flipped
 // weights delta_bwd_weights prepares; class 0 uses r = 1, index 1.
@@ -981,7 +994,14 @@ uint64_t staging_bytes(const delta_layer_desc &L, const delta::ConvArgs &fa) {
 uint64_t partials_bytes(const delta::ConvArgs &fa) { return ((uint64_t)delta::wgrad_workspace_bytes(fa) + 255) / 256 * 256; }
 // `fa` after as_stride_1
 uint64_t backward_workspace_bytes(const delta_layer_desc &L, const delta::ConvArgs &fa) {
-    return partials_bytes(fa) + staging_bytes(L, fa);
+    uint64_t need = partials_bytes(fa) + staging_bytes(L, fa);
+    if (L.stride == 2 && L.R == 3 && L.S == 3 && L.pad == 1) {          // whichever way the weight gradient goes
+        delta::ConvArgs fo = fa;
+        fo.stride = 2; fo.P = (L.H - 1) / 2 + 1; fo.Q = (L.W - 1) / 2 + 1; fo.M = L.N * fo.P * fo.Q;
+        const uint64_t by_class = delta::wgrad_s2_workspace_bytes(fo);
+        need = by_class > need ? by_class : need;
+    }
+    return need;
 }
 
 delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i, delta::ConvArgs &fa,
@@ -1003,11 +1023,13 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     // gpre lives at the input's resolution (for stride 1 that is y's), except for strided 1x1
     // layers, which are handled at the output's resolution
     const bool direct = strided_1x1(L);
-    const uint64_t gpbytes = direct ? ybytes : (uint64_t)L.N * L.H * L.W * L.Cout * (fa.bf16 ? 2 : 4);
+    const delta::ConvArgs fo = fa;                       // the forward layer as it is (fa becomes its stride-1 view below)
+    const bool no_spread = D.gpre == D.gy && class_only(D, fo);
+    const uint64_t gpbytes = direct || no_spread ? ybytes : (uint64_t)L.N * L.H * L.W * L.Cout * (fa.bf16 ? 2 : 4);
     if (D.gy >= nt || D.gpre >= nt || c->tensors[D.gy].bytes != ybytes || c->tensors[D.gpre].bytes != gpbytes)
         return fail(c, DELTA_ERR_INVALID, "backward %u: gy must have the bytes of y, gpre N*H*W*Cout elements "
                     "(the bytes of y for a 1x1 layer)", i);
-    const bool writes_gpre = (L.relu && !D.gy_masked) || (L.stride > 1 && !direct);
+    const bool writes_gpre = (L.relu && !D.gy_masked) || (L.stride > 1 && !direct && !no_spread);
     if (!writes_gpre && D.gpre != D.gy)
         return fail(c, DELTA_ERR_INVALID, "backward %u: without a ReLU mask to apply and stride gpre must be gy itself", i);
     if (D.mask_gx && D.gx == DELTA_NO_TENSOR)
@@ -1048,7 +1070,7 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
     // 1x1 layer at the output's, on the gathered input pixels)
     as_stride_1(L, fa);
     if (D.gw) {
-        const char *why = delta::wgrad_check(fa);
+        const char *why = class_wgrad(D, fo) ? nullptr : delta::wgrad_check(fa);
         if (why) return fail(c, DELTA_ERR_INVALID, "backward %u: %s", i, why);
         if ((uintptr_t)D.gw & 15) return fail(c, DELTA_ERR_INVALID, "backward %u: gw misaligned", i);
     }
@@ -1259,7 +1281,10 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         unsigned char *staging =
             direct ? static_cast<unsigned char *>(D.workspace) + ((D.workspace_bytes - stg_bytes) & ~(uint64_t)255) : nullptr;
         if (direct && aux_holds(c, staging, stg_bytes) && (r = join_aux(c)) != DELTA_OK) return r;
-        if (own_mask || (L.stride > 1 && !direct)) {
+        delta::ConvArgs fo = fa;                             // the forward layer's own geometry (fa is its stride-1 view)
+        fo.stride = L.stride; fo.P = outP; fo.Q = outQ; fo.M = L.N * outP * outQ;
+        const bool no_spread = D.gpre == D.gy && class_only(D, fo);
+        if (own_mask || (L.stride > 1 && !direct && !no_spread)) {
             Tensor &tgp = c->tensors[D.gpre];
             const unsigned char *yp = nullptr;
             if (own_mask) {
@@ -1329,12 +1354,24 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 fa.x = staging;
                 aux_claims(c, staging, stg_bytes);
             }
-            HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa),
-                                           c->stream[S_AUX]));
-            aux_claims(c, D.workspace, partials_bytes(fa));
-            if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
-            tx.aux_done = c->tensors[D.gpre].aux_done = c->aux_tail;
-            c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
+            if (class_wgrad(D, fo)) {
+                // by parity class, from gy itself (it needs no mask of this layer's) and x
+                fo.x = fa.x;
+                const uint64_t need = delta::wgrad_s2_workspace_bytes(fo);
+                HIP_TRY(c, delta::launch_wgrad_s2(fo, c->arena + tgy.offset, static_cast<float *>(D.gw), D.workspace, need,
+                                                  c->stream[S_AUX]));
+                aux_claims(c, D.workspace, need);
+                if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
+                tx.aux_done = tgy.aux_done = c->aux_tail;
+                c->st.recompute_flops += 2ull * (uint64_t)fo.M * 9 * fo.Cin * fo.Cout;
+            } else {
+                HIP_TRY(c, delta::launch_wgrad(fa, gp, static_cast<float *>(D.gw), D.workspace, partials_bytes(fa),
+                                               c->stream[S_AUX]));
+                aux_claims(c, D.workspace, partials_bytes(fa));
+                if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
+                tx.aux_done = c->tensors[D.gpre].aux_done = c->aux_tail;
+                c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
+            }
         }
         c->st.recompute_launches += 1;
     }

@@ -98,13 +98,19 @@ hipError_t launch_relu_mask(const void *y, const void *gy, void *out, size_t byt
 hipError_t launch_relu_mask_dilate(const void *y, const void *gy, void *out, int N, int H, int W, int P, int Q, int K,
                                    int stride, int bf16, hipStream_t stream);
 hipError_t launch_subsample(const void *x, void *xs, int N, int H, int W, int P, int Q, int C, int stride, int bf16,
-                            hipStream_t stream);
+                            hipStream_t stream, int oa = 0, int ob = 0);
 hipError_t launch_spread_add(const void *t, const void *add, const void *mask, void *out, int N, int H, int W, int P,
                              int Q, int C, int stride, int bf16, hipStream_t stream);
 hipError_t launch_bwd_weights(const void *w, const float *scale, void *wt, int K, int R, int S, int C, int bf16,
                               hipStream_t stream);
 const char *wgrad_check(const ConvArgs &a);            // nullptr when the weight-gradient kernel applies
 size_t wgrad_workspace_bytes(const ConvArgs &a);
+// 3x3 stride-2 pad-1 layers by parity class, from the gradient at the output's resolution (a.x = x at the
+// input's resolution, a.H, a.W, a.P, a.Q the layer's own)
+bool wgrad_s2_applies(const ConvArgs &a);
+size_t wgrad_s2_workspace_bytes(const ConvArgs &a);
+hipError_t launch_wgrad_s2(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
+                           hipStream_t stream);
 hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
                         hipStream_t stream);
 

@@ -135,12 +135,19 @@ class Net:
     def _gy_masked(self, l):
         return bool(l.relu) and l.y in self.masked_by
 
+    def _by_class(self, l):
+        """A 3x3 stride-2 layer whose incoming gradient needs no mask of its own and whose channel
+        counts the class-wise weight gradient takes: both gradients run at the output's resolution
+        (by parity class of the input pixels), so no zero-filled copy of dL/dy is needed."""
+        return (l.kind == "conv" and l.stride == 2 and l.R == 3 and l.S == 3 and l.pad == 1 and self.dtype == "bf16" and
+                l.Cin % 128 == 0 and l.Cout % 128 == 0 and (not l.relu or self._gy_masked(l)))
+
     def _own_gpre(self, l):
         if l.kind != "conv":
             return False
         if self._is_stem(l):
             return bool(l.relu) and not self._gy_masked(l)
-        return (l.relu and not self._gy_masked(l)) or (l.stride > 1 and l.R > 1)
+        return (l.relu and not self._gy_masked(l)) or (l.stride > 1 and l.R > 1 and not self._by_class(l))
 
     def _plan_mask_fusion(self):
         """tensor name -> the layer that applies the ReLU mask of the tensor's producer while it
@@ -547,7 +554,8 @@ class OpNet:
     def _dilated(self, name):
         """A strided convolution wider than 1x1 (the stem aside, which has no data gradient)."""
         l = self.op_layer[name]
-        return self._kind(name) == "conv" and l.stride > 1 and l.R > 1 and self.op_inputs[name][0] != "x0"
+        by_class = l.stride == 2 and l.R == 3 and l.S == 3 and l.pad == 1 and l.Cin % 128 == 0 and l.Cout % 128 == 0
+        return self._kind(name) == "conv" and l.stride > 1 and l.R > 1 and self.op_inputs[name][0] != "x0" and not by_class
 
     def enable_backward(self):
         """Adds the gradient tensors to the tensor table (re-binds: call while nothing is
