@@ -49,6 +49,11 @@ CASES = [
     ("3x3_s2_odd_fxy", 2,  9, 13, 128,  64, 3, True, False, True, 2, "xy"),   # the same on odd sizes, + gx_add, + mask_gx
     ("3x3_s2_norelu",  1, 12, 10,  64,  64, 3, False, False, True, 2, "x"),   # no mask of its own either
     ("3x3_s2_1row",    3,  1,  8,  64,  64, 3, True, False, False, 2, "y"),   # a single input row: no odd rows
+    # channel counts the class-wise weight gradient takes ("g": gpre = gy, nothing is spread out)
+    ("3x3_s2_cls",     2, 14, 14, 128, 128, 3, True, False, False, 2, "y"),   # both gradients by class, gpre still written
+    ("3x3_s2_cls_g",   2, 14, 14, 128, 128, 3, True, False, True, 2, "xyg"),
+    ("3x3_s2_cls_odd", 1,  9, 13, 128, 256, 3, False, False, True, 2, "xg"),  # odd sizes: classes of unequal size
+    ("3x3_s2_cls_1col", 3, 6,  1, 256, 128, 3, True, False, False, 2, "yg"),  # a single input column: no odd columns
 ]
 
 
@@ -119,7 +124,7 @@ def test_layer_backward_matches_oracle(torch_mod, case):
     assert ws_bytes > 0
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
-    own_gpre = (relu and not gy_masked) or (stride > 1 and not direct)
+    own_gpre = ((relu and not gy_masked) or (stride > 1 and not direct)) and "g" not in fuse
     desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if own_gpre else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
                       mask_gx=int(mask_gx), gy_masked=int(gy_masked),
                       wt=wt.data_ptr(), gw=gw.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws_bytes)
@@ -136,13 +141,16 @@ def test_layer_backward_matches_oracle(torch_mod, case):
         assert keep.any() and not keep.all()
         ref_gx = np.where(keep, ref_gx, 0.0)
     # gpre: pure masking, bit for bit
-    gpre_gpu = on.to_f64(get(4 if own_gpre else 3, gpshape), "bf16")
-    want_gpre = np.zeros(gpshape)
-    if direct:
-        want_gpre = ref_gpre
+    if "g" in fuse:                                      # not spread out: gy itself, untouched
+        assert np.array_equal(get(3, yshape), gy)
     else:
-        want_gpre[:, 0:stride * P:stride, 0:stride * Q:stride, :] = ref_gpre     # at the input's resolution
-    assert np.array_equal(gpre_gpu, want_gpre)
+        gpre_gpu = on.to_f64(get(4 if own_gpre else 3, gpshape), "bf16")
+        want_gpre = np.zeros(gpshape)
+        if direct:
+            want_gpre = ref_gpre
+        else:
+            want_gpre[:, 0:stride * P:stride, 0:stride * Q:stride, :] = ref_gpre     # at the input's resolution
+        assert np.array_equal(gpre_gpu, want_gpre)
     if relu:
         assert (ref_gpre == 0).any() and (ref_gpre != 0).any()
     # the transformed weights: w[k][r][s][c] * scale[k], flipped and transposed, one bf16 rounding
