@@ -79,6 +79,8 @@ struct delta_ctx {
     hipStream_t stream[N_STREAMS] = {nullptr, nullptr, nullptr, nullptr};
     Ev aux_tail;                                   // last launch on S_AUX the compute stream has not joined
     uintptr_t aux_lo = 0, aux_hi = 0;              // caller memory (workspace) those launches use: [aux_lo, aux_hi)
+    Ev stg_tail;                                   // last launch on S_AUX that used a staging range, and that range
+    uintptr_t stg_lo = 0, stg_hi = 0;
     std::map<uint64_t, Block> free_blocks;         // offset -> block, coalesced
     std::map<uint64_t, uint64_t> used;             // offset -> size
     std::vector<Tensor> tensors;
@@ -1104,6 +1106,8 @@ delta_status join_aux(delta_ctx *c) {
         c->aux_tail = Ev();
     }
     c->aux_lo = c->aux_hi = 0;
+    c->stg_tail = Ev();
+    c->stg_lo = c->stg_hi = 0;
     return DELTA_OK;
 }
 
@@ -1280,7 +1284,16 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
         const uint64_t stg_bytes = direct ? staging_bytes(L, fa) : 0;
         unsigned char *staging =
             direct ? static_cast<unsigned char *>(D.workspace) + ((D.workspace_bytes - stg_bytes) & ~(uint64_t)255) : nullptr;
-        if (direct && aux_holds(c, staging, stg_bytes) && (r = join_aux(c)) != DELTA_OK) return r;
+        if (direct) {
+            const uintptr_t lo = (uintptr_t)staging, hi = lo + stg_bytes;
+            if (aux_holds(c, staging, stg_bytes)) {
+                if ((r = join_aux(c)) != DELTA_OK) return r;
+            } else if (c->stg_tail && lo < c->stg_hi && c->stg_lo < hi) {
+                // only an earlier strided 1x1 layer's weight gradient used these bytes: wait for that one launch
+                HIP_TRY(c, hipStreamWaitEvent(s, c->stg_tail.e, 0));
+                c->stg_tail = Ev();
+            }
+        }
         delta::ConvArgs fo = fa;                             // the forward layer's own geometry (fa is its stride-1 view)
         fo.stride = L.stride; fo.P = outP; fo.Q = outQ; fo.M = L.N * outP * outQ;
         const bool no_spread = D.gpre == D.gy && class_only(D, fo);
@@ -1352,7 +1365,6 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 HIP_TRY(c, delta::launch_subsample(fa.x, staging, L.N, L.H, L.W, outP, outQ, L.Cin, L.stride, fa.bf16,
                                                    c->stream[S_AUX]));
                 fa.x = staging;
-                aux_claims(c, staging, stg_bytes);
             }
             if (class_wgrad(D, fo)) {
                 // by parity class, from gy itself (it needs no mask of this layer's) and x
@@ -1370,6 +1382,11 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 aux_claims(c, D.workspace, partials_bytes(fa));
                 if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
                 tx.aux_done = c->tensors[D.gpre].aux_done = c->aux_tail;
+                if (direct) {                                   // the staging range is tracked on its own
+                    c->stg_tail = c->aux_tail;
+                    c->stg_lo = (uintptr_t)staging;
+                    c->stg_hi = c->stg_lo + stg_bytes;
+                }
                 c->st.recompute_flops += 2ull * (uint64_t)fa.M * fa.R * fa.S * fa.Cin * fa.Cout;
             }
         }
