@@ -188,27 +188,34 @@ delta_status sync_all(delta_ctx *c) {
 
 Ev later(const Ev &a, const Ev &b) { return a.seq > b.seq ? a : b; }
 
-// Best fit, preferring blocks nobody is still touching: a block whose fences of the other
-// streams have all completed can be written at once, while a block that an Offload copy is
-// still reading would stall the stream that receives it (the 1/4 of the budget that the
-// early start of Sec. 4.3 keeps free is what makes such a choice possible).
+// Best fit among the blocks that cost the receiving stream the least waiting: first those nobody
+// else is still touching, then those whose youngest pending fence of another stream is oldest
+// (events are numbered in recording order, and the streams run in order, so an older fence
+// completes sooner; fences of the copy streams count as younger than any kernel's) - a block that an Offload copy or a weight gradient queued behind others is
+// still reading would stall the stream that receives it (the 1/4 of the budget that the early
+// start of Sec. 4.3 keeps free is what makes such a choice possible).
 delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t *off) {
     const uint64_t need = (bytes + kAlign - 1) / kAlign * kAlign;
     std::map<uint64_t, Block>::iterator pick = c->free_blocks.end();
-    bool pick_idle = false;
+    uint64_t pick_wait = 0;
     for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it) {
         if (it->second.size < need) continue;
-        bool idle = true;
+        uint64_t wait = 0;                                      // recording number of the youngest foreign fence still pending
         for (int s = 0; s < N_STREAMS; ++s) {
             Ev &f = it->second.fence.ev[s];
             if (s == for_stream || !f) continue;
             if (hipEventQuery(f.e) == hipSuccess) f = Ev();     // done: forget the fence
-            else { idle = false; (void)hipGetLastError(); }    // hipErrorNotReady is not an error here
+            else {
+                (void)hipGetLastError();                        // hipErrorNotReady is not an error here
+                // a pending copy outweighs any pending kernel: the link is three orders slower than HBM
+                const uint64_t w = f.seq + ((s == S_D2H || s == S_H2D) ? (1ull << 62) : 0ull);
+                if (w > wait) wait = w;
+            }
         }
-        if (pick == c->free_blocks.end() || (idle && !pick_idle) ||
-            (idle == pick_idle && it->second.size < pick->second.size)) {
+        if (pick == c->free_blocks.end() || wait < pick_wait ||
+            (wait == pick_wait && it->second.size < pick->second.size)) {
             pick = it;
-            pick_idle = idle;
+            pick_wait = wait;
         }
     }
     if (pick == c->free_blocks.end())
