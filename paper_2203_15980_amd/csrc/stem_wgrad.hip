@@ -107,18 +107,30 @@ __global__ __launch_bounds__(kWaves * 64) void stem_wgrad_kernel(ConvArgs a, con
         for (int e = 0; e < 16; ++e) out[(u * 16 + e) * 64 + lane] = acc[u][e];
 }
 
-// One workgroup per (r, k tile, register): 64 lanes x 4 groups of workgroup-partials, the groups
-// added in order.  Element (r, u, e, lane) is k = 32 u + 8 (e / 4) + 4 (lane / 32) + e % 4, j = lane % 32.
-__global__ __launch_bounds__(256) void stem_wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int nblocks) {
-    __shared__ float red[4][64];
+// One workgroup per (r, k tile, register): 64 lanes x 16 groups of workgroup-partials (group g adds
+// partials g, g + 16, ..., eight loads in flight), the groups added in order.  Element (r, u, e, lane)
+// is k = 32 u + 8 (e / 4) + 4 (lane / 32) + e % 4, j = lane % 32.
+__global__ __launch_bounds__(1024) void stem_wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int nblocks) {
+    __shared__ float red[16][64];
     const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const int idx = blockIdx.x;                   // (r * 2 + u) * 16 + e
+    const float *src = partial + (size_t)idx * 64 + lane;
     float s = 0.f;
-    for (int b = grp; b < nblocks; b += 4) s += partial[(size_t)b * kPartialFloats + (size_t)idx * 64 + lane];
+    int b = grp;
+    for (; b + 7 * 16 < nblocks; b += 8 * 16) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(b + 16 * u) * kPartialFloats];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; b < nblocks; b += 16) s += src[(size_t)b * kPartialFloats];
     red[grp][lane] = s;
     __syncthreads();
     if (grp) return;
-    s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+    s = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) s += red[g][lane];
     const int e = idx & 15, u = (idx >> 4) & 1, r = idx >> 5;
     const int k = 32 * u + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3), j = lane & 31;
     const int sx = j >> 2, c = j & 3;
@@ -147,7 +159,7 @@ hipError_t launch_stem_wgrad(const ConvArgs &a, const void *g, float *gw, void *
     const int grid = stemw::grid_for(ntiles);
     stemw::stem_wgrad_kernel<<<dim3(grid), dim3(stemw::kWaves * 64), 0, stream>>>(
         a, static_cast<const unsigned char *>(g), static_cast<float *>(workspace), tiles_p, tiles_q, (int)ntiles);
-    stemw::stem_wgrad_reduce_kernel<<<dim3(stemw::kWaves * 2 * 16), dim3(256), 0, stream>>>(
+    stemw::stem_wgrad_reduce_kernel<<<dim3(stemw::kWaves * 2 * 16), dim3(1024), 0, stream>>>(
         static_cast<const float *>(workspace), a.scale, gw, grid);
     return hipGetLastError();
 }
