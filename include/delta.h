@@ -309,7 +309,7 @@ delta_status delta_backward_workspace(delta_ctx *ctx, const delta_layer_desc *la
 /* Runs the descriptors in order on the compute stream.  Everything is validated before the first
  * launch.  Output tensors are allocated from the arena when not resident (DELTA_ERR_OOM_ARENA);
  * a non-resident input is DELTA_ERR_STATE.
- * Weight gradients of convolutions (gw) are the exception to "on the compute stream": nothing later
+ * Weight gradients of convolutions and of the classifier (gw) are the exception to "on the compute stream": nothing later
  * in the backward pass reads them, so they run on a stream of the library's own, beside the
  * data-gradient chain, each after the launches that produce its inputs.  The arena accounts for
  * these readers when a tensor is released or rewritten.  The gw buffers and the workspace are the

@@ -263,6 +263,7 @@ __global__ __launch_bounds__(256) void dense_bwd_weight_kernel(const uint16_t *g
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     const unsigned char *xg = static_cast<const unsigned char *>(x);
+#pragma unroll 8
     for (int n = 0; n < N; ++n) {
         const float g = __uint_as_float((uint32_t)gy[(size_t)n * Cout + k] << 16);
         gsum += g;

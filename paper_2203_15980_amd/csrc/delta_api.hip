@@ -1272,8 +1272,16 @@ delta_status delta_backward_segment(delta_ctx *c, const delta_bwd_desc *descs, u
                 break;
             }
             default:
-                HIP_TRY(c, delta::launch_dense_bwd(xp, L.w, L.scale, gyp, gxp, static_cast<float *>(D.gw), L.N, L.Cin,
-                                                   L.Cout, s));
+                if (gxp) HIP_TRY(c, delta::launch_dense_bwd(xp, L.w, L.scale, gyp, gxp, nullptr, L.N, L.Cin, L.Cout, s));
+                if (D.gw) {                                     // the weight gradient beside the chain, like the convolutions'
+                    Ev ready;
+                    if ((r = new_event(c, s, &ready)) != DELTA_OK) return r;
+                    HIP_TRY(c, hipStreamWaitEvent(c->stream[S_AUX], ready.e, 0));
+                    HIP_TRY(c, delta::launch_dense_bwd(xp, L.w, L.scale, gyp, nullptr, static_cast<float *>(D.gw), L.N, L.Cin,
+                                                       L.Cout, c->stream[S_AUX]));
+                    if ((r = new_event(c, c->stream[S_AUX], &c->aux_tail)) != DELTA_OK) return r;
+                    c->tensors[L.x].aux_done = c->tensors[D.gy].aux_done = c->aux_tail;
+                }
                 break;
             }
             c->st.recompute_launches += 1;
