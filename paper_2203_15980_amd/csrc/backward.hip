@@ -542,8 +542,8 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
     }
     p.waves = p.ktw * p.ctw * p.taps;
     const int Wp = a.W + (a.R - 1);
-    // image rows per chunk: about 128-256 positions, and at most maxl staged pieces per thread
-    int rh = (192 + Wp - 1) / Wp;
+    // image rows per chunk: up to about 256 positions, and at most maxl staged pieces per thread
+    int rh = (256 + Wp - 1) / Wp;
     if (rh < 1) rh = 1;
     if (rh > a.H) rh = a.H;
     const int nt = p.waves * 64;
