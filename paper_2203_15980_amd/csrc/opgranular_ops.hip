@@ -47,9 +47,9 @@ __device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
     f[4] = lo16(v.z); f[5] = hi16(v.z); f[6] = lo16(v.w); f[7] = hi16(v.w);
 }
 
-// CH = min(chunks, 256) chunk columns per pass, RS = 256 / CH rows in parallel.
-// partial: [gridDim.x][2][C] floats.
-__global__ __launch_bounds__(256) void bn_stats_kernel(const unsigned char *x, float *partial, long long M, int C,
+// NT = blockDim.x threads (256 or 1024): CH = min(chunks, NT) chunk columns per pass, RS = NT / CH rows
+// in parallel.  partial: [gridDim.x][2][C] floats.
+__global__ __launch_bounds__(1024) void bn_stats_kernel(const unsigned char *x, float *partial, long long M, int C,
                                                        long long rows_per_block, int CH, int RS) {
     extern __shared__ __align__(16) float red[];                 // [RS][CH][16]
     const int chunks = C / 8;
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const unsigned char *x, f
         }
         __syncthreads();
         // every thread adds the RS row-parallel contributions of some of the CH x 16 sums, in row order
-        for (int o = t; o < CH * 16; o += 256) {
+        for (int o = t; o < CH * 16; o += (int)blockDim.x) {
             const int c0 = o >> 4, q = o & 15;
             if (cg + c0 >= chunks) continue;
             float a = 0.f;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const u32x4 *__restrict__
 
 // Backward statistics.  Same decomposition as bn_stats_kernel; partial: [gridDim.x][4][C] floats
 // (sum d, sum d^2, sum g, sum g d with d = x - K_c).  red: [RS][CH][32].
-__global__ __launch_bounds__(256) void bn_bwd_stats_kernel(const unsigned char *x, const unsigned char *g, float *partial,
+__global__ __launch_bounds__(1024) void bn_bwd_stats_kernel(const unsigned char *x, const unsigned char *g, float *partial,
                                                            long long M, int C, long long rows_per_block, int CH, int RS) {
     extern __shared__ __align__(16) float red[];
     const int chunks = C / 8;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(const unsigned char *
             for (int e = 0; e < 8; ++e) { p[e] = s1[e]; p[8 + e] = s2[e]; p[16 + e] = s3[e]; p[24 + e] = s4[e]; }
         }
         __syncthreads();
-        for (int o = t; o < CH * 32; o += 256) {                 // as in bn_stats_kernel
+        for (int o = t; o < CH * 32; o += (int)blockDim.x) {     // as in bn_stats_kernel
             const int c0 = o >> 5, q = o & 31;
             if (cg + c0 >= chunks) continue;
             float a = 0.f;
@@ -379,13 +379,24 @@ const char *bn_train_check(const void *x, const void *y, const float *gamma, con
 
 size_t bn_train_scratch_bytes() { return (size_t)16 << 20; }     // partial sums + the 2 x C factors
 
+// Large tensors take workgroups of 1024 threads, a quarter as many: the same lanes share the rows, and
+// the finalize kernel, which runs on a nearly empty chip, reads a quarter of the partial sums.
+static void stats_shape(int chunks, long long &blocks, int &NT, int &CH, int &RS) {
+    if (blocks < 256) return;
+    NT = 1024;
+    blocks = (blocks + 3) / 4;
+    CH = chunks < NT ? chunks : NT;
+    RS = NT / CH;
+}
+
 // scratch: device, bn_train_scratch_bytes() bytes, 16-byte aligned.
 hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const float *beta, long long M, int C, float eps,
                            int bf16, void *scratch, hipStream_t stream) {
     if (bn_train_check(x, y, gamma, beta, M, C, bf16) || !scratch || ((uintptr_t)scratch & 15)) return hipErrorInvalidValue;
     const int chunks = C / 8;
-    const int CH = chunks < 256 ? chunks : 256;
-    const int RS = 256 / CH;
+    int NT = 256;
+    int CH = chunks < NT ? chunks : NT;
+    int RS = NT / CH;
     float *ab = static_cast<float *>(scratch);                   // [2][C]
     float *partial = ab + 2 * (size_t)C;
     const size_t room = (bn_train_scratch_bytes() - 2 * (size_t)C * 4) / ((size_t)2 * C * 4);
@@ -396,10 +407,14 @@ hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const flo
     if (blocks > cap) blocks = cap;
     if (blocks > (long long)room) blocks = (long long)room;
     if (blocks < 1) return hipErrorInvalidValue;
+    stats_shape(chunks, blocks, NT, CH, RS);
     const long long rpb = (M + blocks - 1) / blocks;
     blocks = (M + rpb - 1) / rpb;
     const size_t lds = (size_t)RS * CH * 16 * 4;
-    ops::bn_stats_kernel<<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(static_cast<const unsigned char *>(x), partial,
+    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(ops::bn_stats_kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 1024 * 16 * 4);
+    if (lds_ok != hipSuccess) return lds_ok;
+    ops::bn_stats_kernel<<<dim3((unsigned)blocks), dim3((unsigned)NT), lds, stream>>>(static_cast<const unsigned char *>(x), partial,
                                                                             M, C, rpb, CH, RS);
     const int cl_bits = C <= 512 ? 4 : 6;
     ops::bn_finalize_kernel<<<dim3((unsigned)((C + (1 << cl_bits) - 1) >> cl_bits)), dim3(1024), 0, stream>>>(
@@ -417,8 +432,9 @@ hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const fl
         ((uintptr_t)scratch & 15))
         return hipErrorInvalidValue;
     const int chunks = C / 8;
-    const int CH = chunks < 256 ? chunks : 256;
-    const int RS = 256 / CH;
+    int NT = 256;
+    int CH = chunks < NT ? chunks : NT;
+    int RS = NT / CH;
     float *coef = static_cast<float *>(scratch);                 // [4][C]
     float *partial = coef + 4 * (size_t)C;
     const size_t room = (bn_train_scratch_bytes() - 4 * (size_t)C * 4) / ((size_t)4 * C * 4);
@@ -428,10 +444,14 @@ hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const fl
     if (blocks > cap) blocks = cap;
     if (blocks > (long long)room) blocks = (long long)room;
     if (blocks < 1) return hipErrorInvalidValue;
+    stats_shape(chunks, blocks, NT, CH, RS);
     const long long rpb = (M + blocks - 1) / blocks;
     blocks = (M + rpb - 1) / rpb;
     const size_t lds = (size_t)RS * CH * 32 * 4;
-    ops::bn_bwd_stats_kernel<<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(
+    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(ops::bn_bwd_stats_kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 1024 * 32 * 4);
+    if (lds_ok != hipSuccess) return lds_ok;
+    ops::bn_bwd_stats_kernel<<<dim3((unsigned)blocks), dim3((unsigned)NT), lds, stream>>>(
         static_cast<const unsigned char *>(x), static_cast<const unsigned char *>(gy), partial, M, C, rpb, CH, RS);
     const int cl_bits = C <= 512 ? 4 : 6;
     ops::bn_bwd_finalize_kernel<<<dim3((unsigned)((C + (1 << cl_bits) - 1) >> cl_bits)), dim3(1024), 0, stream>>>(
