@@ -242,8 +242,9 @@ delta_status delta_set_skip_copies(delta_ctx *ctx, int32_t skip);
  *     gpre = gy * [y > 0]  (gy itself without ReLU)      - also dL/dres
  *     gx   = conv^T(gpre * scale, w) (+ gx_add)           - dL/dx
  *     gw[k,r,s,c] = scale_k * sum_m gpre[m,k] * x[m+(r,s),c]   - dL/dw, fp32
- * Supported: DELTA_OP_CONV with 2*pad == R-1 == S-1; gx for bf16 and fp32, gw for bf16 with R in
- * {1,3} and channel counts that are multiples of 64.  A layer with stride > 1 (no residual allowed)
+ * Supported: DELTA_OP_CONV with 2*pad == R-1 == S-1; gx for bf16 and fp32; gw with R in {1,3}: bf16
+ * with channel counts that are multiples of 64 (MFMA kernel), fp32 with any channel counts the
+ * forward accepts (a plain fp32 kernel, one fixed summation order, no workspace bytes).  A layer with stride > 1 (no residual allowed)
  * and a window larger than 1x1 gets gpre at the INPUT's resolution: gpre[n, stride*p, stride*q, :] =
  * gy[n,p,q,:] * [y > 0], zero elsewhere, so that both gradients are stride-1 operations on it
  * (stride^2 times the arithmetic).  A 1x1 layer with stride > 1 only reads the input pixels

@@ -406,6 +406,41 @@ __global__ __launch_bounds__(512) void wgrad_reduce_kernel(const float *partial,
     }
 }
 
+// fp32 layers (the small correctness configuration): plain fp32 multiply-adds.  One workgroup per
+// 16 x 16 tile of (k, c) and tap; thread (kk, cc) walks every position in order, 64 at a time through
+// LDS, so there are no partial sums, no workspace and one fixed order of summation.
+// g: [N,H,W,K] (dL/d(pre-activation) at the input's resolution), x: [N,H,W,C], gw: [K][R][R][C].
+__global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *x, const float *g, const float *scale, float *gw,
+                                                        int N, int H, int W, int C, int K, int R, int pad) {
+    __shared__ float gs[64][17], xs[64][17];
+    const int t = threadIdx.x, kk = t >> 4, cc = t & 15;
+    const int k0 = blockIdx.x * 16, c0 = blockIdx.y * 16, tap = blockIdx.z;
+    const int r = tap / R, s = tap % R;
+    const long long M = (long long)N * H * W;
+    float acc = 0.f;
+    for (long long m0 = 0; m0 < M; m0 += 64) {
+        for (int i = t; i < 1024; i += 256) {
+            const int p = i >> 4, ch = i & 15;
+            const long long m = m0 + p;
+            float gv = 0.f, xv = 0.f;
+            if (m < M) {
+                gv = g[(size_t)m * K + k0 + ch];
+                const int w_ = (int)(m % W), h_ = (int)((m / W) % H);
+                const long long n = m / ((long long)W * H);
+                const int ih = h_ + r - pad, iw = w_ + s - pad;
+                if (ih >= 0 && ih < H && iw >= 0 && iw < W) xv = x[((size_t)(n * H + ih) * W + iw) * C + c0 + ch];
+            }
+            gs[p][ch] = gv;
+            xs[p][ch] = xv;
+        }
+        __syncthreads();
+#pragma unroll 16
+        for (int p = 0; p < 64; ++p) acc += gs[p][kk] * xs[p][cc];
+        __syncthreads();
+    }
+    gw[((size_t)(k0 + kk) * R * R + tap) * C + c0 + cc] = acc * scale[k0 + kk];
+}
+
 }  // namespace bwd
 
 // ---------------------------------------------------------------- host side
@@ -597,7 +632,18 @@ hipError_t launch_wgrad_t(const bwd::WgradArgs &wa, const WgradPlan &p, hipStrea
 
 }  // namespace
 
+// fp32: the plain kernel
+static const char *wgrad_f32_check(const ConvArgs &a) {
+    if (a.R != a.S || (a.R != 1 && a.R != 3) || a.stride != 1 || a.pad != (a.R - 1) / 2)
+        return "weight gradient: 1x1 or 3x3, stride 1, same padding only";
+    if (a.Cin % 16 || a.Cout % 16) return "weight gradient (fp32): channel counts must be multiples of 16";
+    if (a.N < 1 || a.H < 1 || a.W < 1 || a.Cout / 16 > 65535 || a.Cin / 16 > 65535)
+        return "weight gradient (fp32): empty or oversized layer";
+    return nullptr;
+}
+
 const char *wgrad_check(const ConvArgs &a) {
+    if (!a.bf16) return wgrad_f32_check(a);
     WgradPlan p;
     return wgrad_plan(a, p);
 }
@@ -682,6 +728,13 @@ ConvArgs s2_class_layer(const ConvArgs &a, const S2Class &, const void *cls) {
 hipError_t launch_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspace, size_t workspace_bytes,
                         hipStream_t stream) {
     const int taps = a.R * a.S;
+    if (!a.bf16) {                                               // no workspace
+        if (wgrad_f32_check(a) || !a.x || !a.scale || !g || !gw) return hipErrorInvalidValue;
+        bwd::wgrad_f32_kernel<<<dim3(a.Cout / 16, a.Cin / 16, taps), dim3(256), 0, stream>>>(
+            static_cast<const float *>(a.x), static_cast<const float *>(g), a.scale, gw, a.N, a.H, a.W, a.Cin, a.Cout, a.R,
+            a.pad);
+        return hipGetLastError();
+    }
     return run_wgrad(a, g, gw, workspace, workspace_bytes, 0, taps == 9 ? kAllTaps : 0ull, taps, taps == 9 ? kAllTaps : 0ull,
                      stream);
 }

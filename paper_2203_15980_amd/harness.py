@@ -340,7 +340,7 @@ class Net:
                          gx=self.ids[gx] if gx else B.NO_TENSOR, gx_add=self.ids[add] if add else B.NO_TENSOR,
                          mask_gx=int(mask_gx), gy_masked=int(conv and self._gy_masked(l)),
                          wt=self.wt[l.name].data_ptr() if l.name in self.wt else None,
-                         gw=self.gw[l.name].data_ptr() if (l.name in self.gw and self.dtype == "bf16") else None,
+                         gw=self.gw[l.name].data_ptr() if l.name in self.gw else None,
                          workspace=self.bwd_workspace.data_ptr() if conv else None,
                          workspace_bytes=self.bwd_workspace.numel() if conv else 0)
         d.backward_segment([desc])

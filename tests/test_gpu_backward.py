@@ -352,6 +352,129 @@ def _bits(master, aid, shape, scale=1.0):
     return synth.f32_to_bf16_bits((synth.normal(master, aid, int(np.prod(shape))) * scale).astype(np.float32)).reshape(shape)
 
 
+F32_CASES = [
+    # name          N   H   W  Cin Cout R relu res  add  stride
+    ("f32_1x1_res",  2, 12, 12,  64, 256, 1, True, True, False, 1),
+    ("f32_1x1_tail", 3,  9, 11,  96,  32, 1, False, False, True, 1),    # 297 positions: a ragged last chunk of 64
+    ("f32_3x3",      2, 14, 14,  64,  64, 3, True, False, False, 1),
+    ("f32_3x3_odd",  1,  9, 11,  32,  96, 3, True, False, True, 1),
+    ("f32_3x3_s2",   2, 13, 14,  64,  32, 3, True, False, False, 2),    # strided: gpre at the input's resolution
+    ("f32_1x1_s2",   2, 12, 13,  64, 128, 1, False, False, True, 2),    # the projection shortcut
+]
+
+
+@pytest.mark.parametrize("case", F32_CASES, ids=[c[0] for c in F32_CASES])
+def test_layer_backward_fp32_matches_oracle(torch_mod, case):
+    """The fp32 storage type (config 1's): data gradient through the same kernels as bf16, weight
+    gradient through the plain fp32 kernel; both within 1e-4 of the float64 oracle."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    name, N, H, W, Cin, Cout, R, relu, has_res, has_add, stride = case
+    print("case", name, flush=True)
+    pad = (R - 1) // 2
+    l = synth.LayerSpec(name, "conv", "x0", "r0" if has_res else None, name, N, H, W, Cin, Cout, R, R, stride, pad, relu)
+    P, Q = l.P, l.Q
+    l.index = 1
+    master = 92
+    x = synth.make_input(master, (N, H, W, Cin), "f32")
+    p = synth.make_params(master, l, "f32")
+    yshape = (N, P, Q, Cout)
+    direct = R == 1 and stride > 1
+    gpshape = yshape if direct else (N, H, W, Cout)
+    rnd = lambda aid, shape: synth.normal(master, aid, int(np.prod(shape))).astype(np.float32).reshape(shape)
+    res = rnd(901, yshape) if has_res else None
+    gy = rnd(902, yshape)
+    add = rnd(903, x.shape) if has_add else None
+    ysz, xsz, gpsz = int(np.prod(yshape)) * 4, x.nbytes, int(np.prod(gpshape)) * 4
+    d, put, get = _small_ctx(torch, [xsz, ysz, ysz, ysz, gpsz, xsz, xsz])
+    put(0, x)
+    if has_res:
+        put(1, res)
+    put(3, gy)
+    if has_add:
+        put(6, add)
+    w = _dev(torch, p["w"])
+    bn = [_dev(torch, p[k]) for k in ("gamma", "beta", "mean", "var")]
+    scale = torch.empty(Cout, dtype=torch.float32, device="cuda:0")
+    shift = torch.empty(Cout, dtype=torch.float32, device="cuda:0")
+    d.bn_fold(bn[0].data_ptr(), bn[1].data_ptr(), bn[2].data_ptr(), bn[3].data_ptr(), float(p["eps"]),
+              Cout, scale.data_ptr(), shift.data_ptr())
+    fwd = dl.LayerDesc(x=0, res=1 if has_res else dl.NO_TENSOR, y=2, dtype=dl.DTYPE_F32, w=w.data_ptr(),
+                       scale=scale.data_ptr(), shift=shift.data_ptr(), N=N, H=H, W=W, Cin=Cin, Cout=Cout,
+                       R=R, S=R, stride=stride, pad=pad, relu=1 if relu else 0)
+    d.recompute_segment([fwd])
+    wt = torch.empty(Cout * R * R * Cin, dtype=torch.float32, device="cuda:0")
+    d.bwd_weights(fwd, wt.data_ptr())
+    ws_bytes = max(d.backward_workspace(fwd), 256)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    gw = torch.full((Cout, R, R, Cin), float("nan"), dtype=torch.float32, device="cuda:0")
+    own_gpre = relu or (stride > 1 and not direct)
+    desc = dl.BwdDesc(fwd=fwd, gy=3, gpre=4 if own_gpre else 3, gx=5, gx_add=6 if has_add else dl.NO_TENSOR,
+                      mask_gx=0, gy_masked=0, wt=wt.data_ptr(), gw=gw.data_ptr(), workspace=ws.data_ptr(),
+                      workspace_bytes=ws_bytes)
+    d.backward_segment([desc])
+    d.sync()
+    y_gpu = get(2, yshape, np.float32)
+    ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(x, p["w"], p, y_gpu, gy, stride=stride, pad=pad, relu=relu, dtype="f32")
+    if has_add:
+        ref_gx = ref_gx + add.astype(np.float64)
+    gpre_gpu = get(4 if own_gpre else 3, gpshape, np.float32).astype(np.float64)
+    want_gpre = np.zeros(gpshape)
+    if direct:
+        want_gpre = ref_gpre
+    else:
+        want_gpre[:, 0:stride * P:stride, 0:stride * Q:stride, :] = ref_gpre
+    assert np.array_equal(gpre_gpu, want_gpre)               # pure masking: bit for bit
+    if relu:
+        assert (ref_gpre == 0).any() and (ref_gpre != 0).any()
+    gx_gpu = get(5, x.shape, np.float32).astype(np.float64)
+    err_x = float(np.max(np.abs(gx_gpu - ref_gx)) / np.max(np.abs(ref_gx)))
+    gw_gpu = gw.cpu().numpy().astype(np.float64)
+    assert np.isfinite(gw_gpu).all()
+    err_w = float(np.max(np.abs(gw_gpu - ref_gw)) / np.max(np.abs(ref_gw)))
+    print("  gx err %.2e  gw err %.2e" % (err_x, err_w), flush=True)
+    assert err_x <= 1e-4 and err_w <= 1e-4, (name, err_x, err_w)
+    d.close()
+
+
+def test_config1_backward_fp32_layer_by_layer(torch_mod):
+    """Config 1 (three bottleneck blocks, fp32, 2 x 32 x 32 x 64): the whole backward pass through
+    the harness; every layer's gradients against the oracle given the same stored tensors."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    layers = synth.bottleneck_stack(2, 32, 32)
+    g = synth.fused_graph(layers, "f32")
+    arena = torch.empty(128 << 20, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "f32", synth.master_seed(1))
+    net.enable_backward(input_gradient=True, fuse_masks=False)
+    net.forward()
+    net.backward(keep=True)
+    d.sync()
+    acts = {"x0": net.x0_np}
+    for l in layers:
+        acts[l.y] = net.read(l.y)
+    by_name = {l.name: l for l in layers}
+    assert len(net.bwd_trace) == len(layers)
+    for (lname, gy_name, gpre_name, gx_name, add_name, masks_gx) in net.bwd_trace:
+        l = by_name[lname]
+        p = net.params_np[lname]
+        ref_gx, ref_gw, ref_gpre = on.conv_bn_act_bwd(acts[l.x], p["w"], p, acts[l.y], net.read(gy_name), stride=l.stride,
+                                                      pad=l.pad, relu=l.relu, dtype="f32")
+        assert not masks_gx
+        assert np.array_equal(net.read(gpre_name).astype(np.float64), ref_gpre), lname
+        if add_name:
+            ref_gx = ref_gx + net.read(add_name).astype(np.float64)
+        ex = float(np.max(np.abs(net.read(gx_name).astype(np.float64) - ref_gx)) / np.max(np.abs(ref_gx)))
+        got_gw = net.gw[lname].cpu().numpy().astype(np.float64).reshape(ref_gw.shape)
+        ew = float(np.max(np.abs(got_gw - ref_gw)) / np.max(np.abs(ref_gw)))
+        print("  %-8s gx %.2e gw %.2e" % (lname, ex, ew), flush=True)
+        assert ex <= 1e-4 and ew <= 1e-4, (lname, ex, ew)
+    d.close()
+
+
 def test_pooling_backward_matches_oracle(torch_mod):
     torch = torch_mod
     import paper_2203_15980_amd as dl
