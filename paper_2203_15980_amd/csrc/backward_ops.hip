@@ -38,7 +38,8 @@ __device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
 // ---------------------------------------------------------------- max pooling
 // A workgroup owns an 8 x 8 tile of INPUT pixels and 64 channels (8 chunks of 8), in three steps:
 //  1. copy every pixel that a window touching the tile can reach (the tile plus R-1 / S-1 pixels
-//     on each side) into LDS;
+//     on each side) into LDS, and the gradients of those windows with them (one global round trip
+//     for both; step 3 then reads each window's gradient from LDS instead of once per pixel);
 //  2. one thread per (window, chunk): scan the window in the forward's order (r, then s, padding
 //     skipped) and record, per channel, the position r*S + s of the first maximal element as
 //     one byte (255: none) - each window is scanned once, not once per pixel it covers;
@@ -46,10 +47,15 @@ __device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
 //     windows containing the pixel, add the window's gradient where the recorded position is
 //     the pixel's.  Sums in window order (p, then q), fp32.
 // Every loop has a uniform trip count and selects instead of branches: a per-element `if`
-// compiled to a branch per element and ran ten times slower.
+// compiled to a branch per element and ran ten times slower.  The kernel is bound by its vector
+// arithmetic (about 3300 wavefront instructions per tile): XCD-aware tile numbering and trip counts
+// made uniform per wavefront by pixel parity class both left its time unchanged; scanning only the
+// windows that can touch the tile (5 x 5 instead of 6 x 6 for the 3 x 3 stride-2 pool) took 16 % off.
 static constexpr int kPoolTile = 8, kPoolChunks = 8;
 
-__host__ __device__ inline int pool_windows_max(int R, int stride) { return (kPoolTile + R - 2) / stride + 2; }
+// windows p with a pixel in kPoolTile consecutive rows: stride * p - pad in [h0 - R + 1, h0 + kPoolTile - 1],
+// an interval of length kPoolTile + R - 2
+__host__ __device__ inline int pool_windows_max(int R, int stride) { return (kPoolTile + R - 2) / stride + 1; }
 
 // FIXED: the ResNet pool (3 x 3, stride 2, padding 1) with every loop unrolled.
 template <bool FIXED>
@@ -67,8 +73,14 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void
     const int LH = kPoolTile + 2 * (a.R - 1), LW = kPoolTile + 2 * (a.S - 1);
     const int NWH = pool_windows_max(a.R, a.stride), NWW = pool_windows_max(a.S, a.stride);
     unsigned char *arg = plds + (size_t)LH * LW * kPoolChunks * 16;      // [NWH][NWW][chunk] x 8 bytes
+    unsigned char *gys = arg + (size_t)NWH * NWW * kPoolChunks * 8;      // [NWH][NWW][chunk] x 16 bytes
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const unsigned char *gg = static_cast<const unsigned char *>(gy);
+    // windows that contain a pixel of the tile: p in [pw0, pw0 + NWH) clipped to the image (likewise q)
+    int pw0 = h0 + a.pad - a.R + 1;
+    pw0 = pw0 <= 0 ? 0 : (pw0 + a.stride - 1) / a.stride;
+    int qw0 = w0 + a.pad - a.S + 1;
+    qw0 = qw0 <= 0 ? 0 : (qw0 + a.stride - 1) / a.stride;
     // step 1: LDS pixel (lh, lw) = image pixel (h0 - (R-1) + lh, w0 - (S-1) + lw); outside the image: zeros, unused
     for (int i = threadIdx.x; i < LH * LW * kPoolChunks; i += 256) {
         const int c = i % kPoolChunks, pix = i / kPoolChunks;
@@ -79,12 +91,15 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void
             v = *reinterpret_cast<const u32x4 *>(xg + ((((size_t)n * a.H + hh) * a.W + ww) * chunks + ck) * 16);
         *reinterpret_cast<u32x4 *>(plds + (size_t)i * 16) = v;
     }
+    for (int i = threadIdx.x; i < NWH * NWW * kPoolChunks; i += 256) {
+        const int c = i % kPoolChunks, win = i / kPoolChunks;
+        const int p = pw0 + win / NWW, q = qw0 + win % NWW, ck = cg * kPoolChunks + c;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (p < a.P && q < a.Q && ck < chunks)
+            v = *reinterpret_cast<const u32x4 *>(gg + ((((size_t)n * a.P + p) * a.Q + q) * chunks + ck) * 16);
+        *reinterpret_cast<u32x4 *>(gys + (size_t)i * 16) = v;
+    }
     __syncthreads();
-    // windows that contain a pixel of the tile: p in [pw0, pw0 + NWH) clipped to the image (likewise q)
-    int pw0 = h0 + a.pad - a.R + 1;
-    pw0 = pw0 <= 0 ? 0 : (pw0 + a.stride - 1) / a.stride;
-    int qw0 = w0 + a.pad - a.S + 1;
-    qw0 = qw0 <= 0 ? 0 : (qw0 + a.stride - 1) / a.stride;
     // step 2
     for (int i = threadIdx.x; i < NWH * NWW * kPoolChunks; i += 256) {
         const int c = i % kPoolChunks, win = i / kPoolChunks;
@@ -143,15 +158,13 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolArgs a, const void
             for (int dq = nq - 1; dq >= 0; --dq) {
                 const int p = p_hi - dp, q = q_hi - dq;
                 const bool live = owned && p >= p_lo && q >= q_lo;  // this pixel lies in window (p, q)
-                // clamped to the windows step 2 covered and to the image: the loads stay in bounds
+                // clamped to the windows steps 1 and 2 covered: the LDS reads stay in bounds
                 const int pc = p < pw0 ? pw0 : (p > pw0 + NWH - 1 ? pw0 + NWH - 1 : p);
                 const int qc = q < qw0 ? qw0 : (q > qw0 + NWW - 1 ? qw0 + NWW - 1 : q);
-                const int pg = pc > a.P - 1 ? a.P - 1 : pc, qg = qc > a.Q - 1 ? a.Q - 1 : qc;
-                const int ckc = ck < chunks ? ck : chunks - 1;
-                const u32x2 am = *reinterpret_cast<const u32x2 *>(
-                    arg + ((size_t)((pc - pw0) * NWW + (qc - qw0)) * kPoolChunks + c) * 8);
+                const size_t slot = (size_t)((pc - pw0) * NWW + (qc - qw0)) * kPoolChunks + c;
+                const u32x2 am = *reinterpret_cast<const u32x2 *>(arg + slot * 8);
                 float g[8];
-                unpack8(*reinterpret_cast<const u32x4 *>(gg + ((((size_t)n * a.P + pg) * a.Q + qg) * chunks + ckc) * 16), g);
+                unpack8(*reinterpret_cast<const u32x4 *>(gys + slot * 16), g);
                 const uint32_t my = (uint32_t)((h - (p * a.stride - a.pad)) * a.S + (w - (q * a.stride - a.pad)));
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -287,7 +300,7 @@ hipError_t launch_maxpool_bwd(const PoolArgs &a, const void *gy, void *gx, int m
     const long long blocks = (long long)a.N * tiles_h * tiles_w * cgroups;
     if (a.R * a.S > 255) return hipErrorInvalidValue;                   // window positions are recorded as bytes
     const size_t lds = (size_t)(bops::kPoolTile + 2 * (a.R - 1)) * (bops::kPoolTile + 2 * (a.S - 1)) * bops::kPoolChunks * 16 +
-                       (size_t)bops::pool_windows_max(a.R, a.stride) * bops::pool_windows_max(a.S, a.stride) * bops::kPoolChunks * 8;
+                       (size_t)bops::pool_windows_max(a.R, a.stride) * bops::pool_windows_max(a.S, a.stride) * bops::kPoolChunks * (8 + 16);
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL || lds > 64 * 1024) return hipErrorInvalidValue;
     if (a.R == 3 && a.S == 3 && a.stride == 2 && a.pad == 1)
         bops::maxpool_bwd_kernel<true><<<dim3((unsigned)blocks), dim3(256), lds, stream>>>(a, gy, gx, tiles_w, tiles_h, mask_x);
