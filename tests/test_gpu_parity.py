@@ -225,6 +225,53 @@ def test_swap_round_trip_is_byte_exact(torch_mod):
     d.close()
 
 
+def test_swap_round_trip_of_tensors_larger_than_one_copy_piece(torch_mod):
+    """Tensors above 32 MiB travel as four copies: a Reload issued right behind the Offload follows it
+    piece by piece, one issued after a sync takes the plain path; both return the bytes, also with a
+    ragged last piece and with sizes at and just above the boundary."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    whole = 32 << 20
+    sizes = [2 * whole + 4096 + 256, whole, whole + 256, whole + whole // 2, 1 << 20]
+    # twice the tensors' bytes, pre-filled: the Reloads of the first round land in blocks nobody reads
+    # any more (the untouched half), so a piece that was not copied would show as the fill pattern
+    arena = torch.full((2 * sum(sizes) + (1 << 20),), 0xA5, dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind(sizes)
+    base = d.arena.data_ptr()
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(77)
+    want = []
+    for t, n in enumerate(sizes):
+        ptr = d.alloc(t)
+        v = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0", generator=gen)
+        d.arena[ptr - base:ptr - base + n].copy_(v)
+        want.append(v.cpu())
+    torch.cuda.synchronize()
+
+    def check():
+        for t, n in enumerate(sizes):
+            ptr = d.tensor_ptr(t)
+            assert torch.equal(d.arena[ptr - base:ptr - base + n].cpu(), want[t]), t
+
+    for rnd in range(2):
+        for t in range(len(sizes)):
+            d.release(t, dl.EV_OFFLOAD)
+        if rnd == 1:
+            d.sync()                                          # the Offloads are complete: no pieces to follow
+            d.arena.fill_(0x5A)                               # nothing resident, no copy in flight: wipe the device side
+            torch.cuda.synchronize()
+        for t in range(len(sizes)):
+            d.prefetch(t)
+        d.sync()
+        check()
+    st = d.stats()
+    # the second round's Offloads are free: the host copies are still valid
+    assert st["d2h_bytes"] == sum(sizes) and st["h2d_bytes"] == 2 * sum(sizes)
+    assert st["d2h_copies"] == len(sizes) and st["h2d_copies"] == 2 * len(sizes)
+    d.close()
+
+
 @pytest.mark.parametrize("dtype,N,HW", [("f32", 2, 32), ("bf16", 4, 56)])
 def test_plan_replay_hands_every_step_its_forward_bits(torch_mod, dtype, N, HW):
     """Plan with delta_plan at a 50 % budget, replay it in an arena of exactly that size, and
