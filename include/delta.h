@@ -203,10 +203,13 @@ delta_status delta_tensor_ptr(delta_ctx *ctx, uint32_t tensor, void **dev_out);
  */
 delta_status delta_release(delta_ctx *ctx, uint32_t tensor, uint32_t action);
 /* Offload without release: async copy to the tensor's pinned host buffer on the D2H
- * stream, ordered after everything enqueued so far on the compute stream (Sec. 4.2). */
+ * stream, ordered after everything enqueued so far on the compute stream (Sec. 4.2).
+ * A tensor above 32 MiB goes out as four copies with an event after each. */
 delta_status delta_swap_out(delta_ctx *ctx, uint32_t tensor);
 /* Reload (Algorithm 4): fresh arena block, async copy from the host buffer on the H2D
  * stream; later uses of the tensor on the compute stream wait for the copy's event.
+ * May be called while the tensor's Offload is still in flight: the copy back then follows
+ * it (piece by piece for a tensor that went out in pieces), never overtakes it.
  * DELTA_ERR_STATE when the tensor is resident or has no valid host copy. */
 delta_status delta_prefetch(delta_ctx *ctx, uint32_t tensor);
 /*
