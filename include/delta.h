@@ -223,6 +223,22 @@ delta_status delta_prefetch(delta_ctx *ctx, uint32_t tensor);
  */
 delta_status delta_recompute_segment(delta_ctx *ctx, const delta_layer_desc *layers,
                                      uint32_t n_layers);
+/*
+ * For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The DELTA_OP_BATCHNORM operator of delta_recompute_segment (which
+ * allocates its partial-sum buffer on first use, and an arena block for the output) on buffers the
+ * caller owns: y = gamma_c (x - mu_c) / sqrt(var_c + eps) + beta_c over x [rows, channels] bf16, with the
+ * mean and biased variance of THIS batch; same kernels, same decomposition, so the same bits.
+ * x, y, gamma, beta: device, 16-byte aligned, x != y; channels a multiple of 8 and at most 8192 (more:
+ * DELTA_ERR_INVALID); any rows >= 1.  Runs on the compute stream; calls no hipMalloc / hipFree and no
+ * other allocating routine.  Its scratch (partial sums and factors, at most 4 259 840 bytes) is a
+ * file-scope device array inside the library: every GPU the library runs on holds one copy until the
+ * process ends, and every call on a GPU shares that copy - calls that overlap on one GPU (two streams,
+ * two contexts, two threads) race; calls enqueued on one stream do not.  Nothing in it needs clearing
+ * between calls.
+ */
+delta_status delta_batchnorm_static(delta_ctx *ctx, const void *x, void *y, const float *gamma, const float *beta,
+                                    uint64_t rows, uint32_t channels, float eps);
 /* Blocks the host until the selected streams (DELTA_SYNC_* bit mask) are idle. */
 delta_status delta_sync(delta_ctx *ctx, uint32_t which);
 

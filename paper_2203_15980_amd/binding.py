@@ -24,7 +24,8 @@ EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "d
            "delta_recompute_segment", "delta_sync", "delta_bn_fold", "delta_stats",
            "delta_stats_reset", "delta_set_skip_copies", "delta_probe_hostlink",
            "delta_probe_hbm", "delta_probe_mfma", "delta_layer_kernel", "delta_bwd_weights",
-           "delta_backward_workspace", "delta_backward_segment", "delta_backward_join"]
+           "delta_backward_workspace", "delta_backward_segment", "delta_backward_join",
+           "delta_batchnorm_static"]
 
 
 class TensorDesc(C.Structure):
@@ -128,6 +129,7 @@ def load_library():
         "delta_backward_workspace": (i32, [vp, C.POINTER(LayerDesc), C.POINTER(u64)]),
         "delta_backward_segment": (i32, [vp, C.POINTER(BwdDesc), u32]),
         "delta_backward_join": (i32, [vp]),
+        "delta_batchnorm_static": (i32, [vp, vp, vp, vp, vp, u64, u32, C.c_float]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -265,6 +267,10 @@ class Delta:
 
     def backward_join(self):
         self._check(self.lib.delta_backward_join(self.ctx))
+
+    def batchnorm_static(self, x_ptr, y_ptr, gamma_ptr, beta_ptr, rows, channels, eps):
+        """Batch normalisation with batch statistics on caller-owned device buffers; allocates nothing."""
+        self._check(self.lib.delta_batchnorm_static(self.ctx, x_ptr, y_ptr, gamma_ptr, beta_ptr, rows, channels, eps))
 
     def sync(self, which=SYNC_ALL):
         self._check(self.lib.delta_sync(self.ctx, which))

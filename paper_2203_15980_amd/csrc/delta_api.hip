@@ -79,6 +79,16 @@ struct Timed {
 
 }  // namespace
 
+// Scratch of delta_batchnorm_static, the entry point that allocates nothing: the partial sums and the
+// per-channel factors of the batch-norm kernels.  One copy per GPU, at its own address, held until the
+// process ends.  In host code this name only stands for the symbol: the device address of the current
+// GPU's copy comes from hipGetSymbolAddress (static_scratch_for below) and only that pointer is ever
+// handed to a kernel.
+constexpr size_t kStaticScratchBytes = ((size_t)4 << 20) + ((size_t)64 << 10);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_static_scratch[kMaxDevices];        // per device ordinal: where that GPU keeps its copy
+
 struct delta_ctx {
     unsigned char *arena = nullptr;
     uint64_t arena_bytes = 0;
@@ -97,6 +107,7 @@ struct delta_ctx {
     delta_stats_t st;
     bool skip_copies = false;
     void *bn_scratch = nullptr;                    // partial sums of DELTA_OP_BATCHNORM, allocated on first use
+    void *static_scratch = nullptr;                // this GPU's copy of the file-scope scratch array (delta_batchnorm_static)
     float *ones = nullptr, *zeros = nullptr;       // kMaxChannels floats each (identity scale/shift of the data gradient)
     uint64_t ev_seq = 0;
     std::string err;
@@ -279,6 +290,25 @@ void arena_free(delta_ctx *c, uint64_t off, const Fence &f) {
     c->free_blocks[o] = b;
 }
 
+// Device address of the file-scope scratch array on the context's GPU, resolved once per device.
+// The context's device must be the current one: every GPU holds its own copy at its own address.
+hipError_t static_scratch_for(int device, void **out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_static_scratch[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_static_scratch[device] = p;
+    }
+    *out = g_static_scratch[device];
+    return hipSuccess;
+}
+
 delta_status check_id(delta_ctx *c, uint32_t t) {
     if (t >= c->tensors.size()) return fail(c, DELTA_ERR_INVALID, "tensor id %u out of range (%zu bound)", t, c->tensors.size());
     return DELTA_OK;
@@ -393,6 +423,10 @@ delta_status delta_create(void *arena_dev, uint64_t arena_bytes, void *compute_s
             hipStreamCreateWithFlags(&c->stream[S_AUX], hipStreamNonBlocking) != hipSuccess) {
             delete c;
             return DELTA_ERR_HIP;
+        }
+        if (static_scratch_for(c->device, &c->static_scratch) != hipSuccess) {
+            (void)hipGetLastError();
+            c->static_scratch = nullptr;            // delta_batchnorm_static reports it; everything else works
         }
         Block b;
         b.size = c->arena_bytes;
@@ -743,7 +777,7 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
         case DELTA_OP_BATCHNORM:
             if (!c->bn_scratch) HIP_TRY(c, hipMalloc(&c->bn_scratch, delta::bn_train_scratch_bytes()));
             HIP_TRY(c, delta::launch_bn_train(xp, yp, L.scale, L.shift, (long long)L.N * L.H * L.W, L.Cin, L.eps, 1,
-                                              c->bn_scratch, c->stream[S_COMPUTE]));
+                                              c->bn_scratch, delta::bn_train_scratch_bytes(), c->stream[S_COMPUTE]));
             break;
         case DELTA_OP_RELU:
             HIP_TRY(c, delta::launch_relu(xp, yp, ty.bytes, 1, c->stream[S_COMPUTE]));
@@ -763,6 +797,34 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
         c->st.recompute_launches += 1;
         c->st.recompute_flops += flops;
     }
+    return DELTA_OK;
+}
+
+delta_status delta_batchnorm_static(delta_ctx *c, const void *x, void *y, const float *gamma, const float *beta,
+                                    uint64_t rows, uint32_t channels, float eps) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    if (channels == 0 || channels % 8 || channels > 8192)
+        return fail(c, DELTA_ERR_INVALID, "batchnorm_static: %u channels: must be a multiple of 8 and at most 8192 "
+                    "(the static scratch of %zu bytes is sized for that)", channels, kStaticScratchBytes);
+    if (rows == 0 || rows > (uint64_t)1 << 40) return fail(c, DELTA_ERR_INVALID, "batchnorm_static: bad row count");
+    if (!(eps >= 0.f)) return fail(c, DELTA_ERR_INVALID, "batchnorm_static: eps must be >= 0");
+    if (x == y) return fail(c, DELTA_ERR_INVALID, "batchnorm_static: output aliases the input");
+    const char *why = delta::bn_train_check(x, y, gamma, beta, (long long)rows, (int)channels, 1);
+    if (why) return fail(c, DELTA_ERR_INVALID, "batchnorm_static: %s", why);
+    if (delta::bn_train_fwd_scratch_bytes() > kStaticScratchBytes)
+        return fail(c, DELTA_ERR_INVALID, "batchnorm_static: the kernels need more scratch than the static array holds");
+    if (!c->static_scratch) {
+        hipError_t e = static_scratch_for(c->device, &c->static_scratch);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(c, DELTA_ERR_HIP, "batchnorm_static: hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+        }
+    }
+    // Nothing in the scratch has to start at zero: every partial sum and factor the later kernels of
+    // this call read is written by an earlier kernel of this call.
+    HIP_TRY(c, delta::launch_bn_train(x, y, gamma, beta, (long long)rows, (int)channels, eps, 1, c->static_scratch,
+                                      kStaticScratchBytes, c->stream[S_COMPUTE]));
     return DELTA_OK;
 }
 

@@ -65,8 +65,9 @@ hipError_t launch_layernorm(const void *x, void *y, const float *gamma, const fl
 const char *bn_train_check(const void *x, const void *y, const float *gamma, const float *beta, long long M, int C,
                            int bf16);
 size_t bn_train_scratch_bytes();
+size_t bn_train_fwd_scratch_bytes();      // what the forward alone needs of it (any C up to 8192)
 hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const float *beta, long long M, int C, float eps,
-                           int bf16, void *scratch, hipStream_t stream);
+                           int bf16, void *scratch, size_t scratch_bytes, hipStream_t stream);
 hipError_t launch_bn_train_bwd(const void *x, const void *gy, void *gx, const float *gamma, float *gw, long long M, int C,
                                float eps, int bf16, void *scratch, hipStream_t stream);
 hipError_t launch_relu(const void *x, void *y, size_t bytes, int bf16, hipStream_t stream);

@@ -389,17 +389,24 @@ static void stats_shape(int chunks, long long &blocks, int &NT, int &CH, int &RS
     RS = NT / CH;
 }
 
-// scratch: device, bn_train_scratch_bytes() bytes, 16-byte aligned.
+// What the forward needs at most: the 2 x C factors and 64 workgroups' partial sums at C = 8192 (wider
+// tensors take fewer workgroups, see the cap below), so that a buffer of this size never changes the
+// decomposition - and with it the bits of the result - against a larger one.
+size_t bn_train_fwd_scratch_bytes() { return ((size_t)4 << 20) + ((size_t)64 << 10); }
+
+// scratch: device, scratch_bytes (>= bn_train_fwd_scratch_bytes()) bytes, 16-byte aligned.
 hipError_t launch_bn_train(const void *x, void *y, const float *gamma, const float *beta, long long M, int C, float eps,
-                           int bf16, void *scratch, hipStream_t stream) {
-    if (bn_train_check(x, y, gamma, beta, M, C, bf16) || !scratch || ((uintptr_t)scratch & 15)) return hipErrorInvalidValue;
+                           int bf16, void *scratch, size_t scratch_bytes, hipStream_t stream) {
+    if (bn_train_check(x, y, gamma, beta, M, C, bf16) || !scratch || ((uintptr_t)scratch & 15) ||
+        scratch_bytes < bn_train_fwd_scratch_bytes())
+        return hipErrorInvalidValue;
     const int chunks = C / 8;
     int NT = 256;
     int CH = chunks < NT ? chunks : NT;
     int RS = NT / CH;
     float *ab = static_cast<float *>(scratch);                   // [2][C]
     float *partial = ab + 2 * (size_t)C;
-    const size_t room = (bn_train_scratch_bytes() - 2 * (size_t)C * 4) / ((size_t)2 * C * 4);
+    const size_t room = (scratch_bytes - 2 * (size_t)C * 4) / ((size_t)2 * C * 4);
     long long blocks = (M + (long long)RS * 4 - 1) / ((long long)RS * 4);    // at least 4 rows per lane
     // fewer partials for wide tensors: the finalize kernel reads blocks x 2 x C floats
     long long cap = 262144 / C;
