@@ -7,7 +7,9 @@ it pins the planners to what the paper fixes:
   * the budget: live activation bytes never exceed B (DELTA Sec. 5.1, budget);
   * the early start: before a forward operator runs, either at most 3/4 of B is
     in use or nothing releasable was left (Algorithm 1 and Sec. 4.3);
-  * Assumption 2: no Evict/Offload once the forward pass is over;
+  * Assumption 2: no Evict/Offload once the forward pass is over -- or, when the plan was
+    made with release_when_short (Algorithm 1 taken literally), only where the allocation
+    that follows in the same step would not fit without it;
   * Table 1 semantics: Recompute needs every parent on the GPU, Reload needs a
     host copy made by an earlier Offload, Evict/Offload need a resident tensor;
   * pins (Sec. 4.3 flag meanings): evict_pinned/uncomputable tensors are never
@@ -63,12 +65,18 @@ def check(tensors, steps, params, events, check_trigger=True, check_prefetch_win
         post = [e for e in ev if e[0] == EV_FREE]
         if ev != pre + post:
             fail(k, "FREE must follow every other event of the step")
-        for (a, t) in pre:
+        for i, (a, t) in enumerate(pre):
             m = tensors[t]["bytes"]
             fl = tensors[t]["flags"]
             if a in (EV_EVICT, EV_OFFLOAD):
                 if not fwd:
-                    fail(k, "release of %d in the backward pass" % t)
+                    if not params.get("release_when_short"):
+                        fail(k, "release of %d in the backward pass" % t)
+                    nxt = [tensors[u]["bytes"] for (b, u) in pre[i + 1:]
+                           if b in (EV_RECOMPUTE, EV_RELOAD_DEMAND)]
+                    if not nxt or live + nxt[0] <= B:
+                        fail(k, "release of %d in the backward pass without an allocation "
+                                "that needs the room" % t)
                 if not resident[t] or t in locked or provisional[t]:
                     fail(k, "release of non-resident, in-use or provisional tensor %d" % t)
                 if a == EV_EVICT and fl & (EVICT_PINNED | UNCOMPUTABLE):

@@ -21,7 +21,13 @@ and notation:
     tensor's own cost plus that of its non-resident ancestors (Sec. 3, Eq. 5).
   * Prefetcher (Algorithm 4): reload the head of the offloaded queue while
     memory allows and fewer than n reloads have been issued.
-  * Assumption 2: no Evict/Offload after the last forward step.
+  * Assumption 2: no Evict/Offload after the last forward step -- unless the
+    parameter release_when_short is set: then Algorithm 1 is taken literally
+    (its release loop stands behind every access, and "memory is not enough" is
+    one of its two conditions): whenever an allocation does not fit, in either
+    pass, and no leftover of a recomputation can give way, Filter and Director
+    release resident tensors that the running step and the recomputations in
+    progress do not use.  The early 3/4 trigger stays a forward-pass rule.
 
 Readings taken where the paper is silent (each listed in the design notes):
 logical clock = sum of executed operator costs; queue ordered by next use;
@@ -50,11 +56,14 @@ U64_MAX = (1 << 64) - 1
 
 
 class Infeasible(Exception):
-    """The budget cannot hold what one step needs."""
+    """The budget cannot hold what one step needs.  `operand` is the operand of the step whose
+    way back onto the GPU (recomputation with its missing ancestors, or reload) did not fit;
+    None when the step failed elsewhere."""
 
-    def __init__(self, step, msg):
+    def __init__(self, step, msg, operand=None):
         super().__init__("step %d: %s" % (step, msg))
         self.step = step
+        self.operand = operand
 
 
 def ceil_div(a, b):
@@ -76,7 +85,7 @@ def swap_cost_ns(nbytes, bw_d2h, bw_h2d):
 def default_params(budget, n_fwd, **kw):
     p = dict(budget_bytes=int(budget), trigger_num=3, trigger_den=4, filter=FILTER_BASE,
              prefetch_distance=2, max_reloads=2, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9,
-             n_fwd_steps=int(n_fwd))
+             n_fwd_steps=int(n_fwd), release_when_short=0)
     p.update(kw)
     return p
 
@@ -120,6 +129,7 @@ class _Sim:
         self.locked = set()
         self.provisional = [False] * n
         self.held = _Held()
+        self.bringing_back = None                    # operand of the running step on its way back
 
     # -- bookkeeping -------------------------------------------------------
     def emit(self, action, t):
@@ -128,7 +138,10 @@ class _Sim:
     def grow(self, nbytes):
         """Allocate nbytes.  Tensors that sit on the GPU only as leftovers of an earlier
         recomputation (provisional) give way first: the one needed farthest in the future
-        goes first, ties to the lowest id."""
+        goes first, ties to the lowest id.  When none is left and release_when_short is
+        set, the release loop of Algorithm 1 runs ("memory is not enough"): Filter picks
+        among the resident tensors that neither the running step nor a recomputation in
+        progress uses, Director says Evict or Offload."""
         while self.live + nbytes > self.B:
             best, best_nr = None, None
             for t in range(len(self.T)):
@@ -136,12 +149,32 @@ class _Sim:
                     nr = self.next_read(t, self.k)
                     if best is None or nr > best_nr:
                         best, best_nr = t, nr
-            if best is None:
+            if best is not None:
+                self.drop(best)
+                continue
+            cands = []
+            if self.p.get("release_when_short"):
+                cands = [t for t in range(len(self.T))
+                         if self.resident[t] and not self.provisional[t] and t not in self.locked
+                         and t not in self.held and not self.doubly_pinned(t)
+                         and self.next_read(t, self.k + 1) is not None]
+            if not cands:
                 raise Infeasible(self.k, "live %d + %d exceeds budget %d"
-                                 % (self.live, nbytes, self.B))
-            self.drop(best)
+                                 % (self.live, nbytes, self.B), self.bringing_back)
+            self.release(self.filter(cands))
         self.live += nbytes
         self.peak = max(self.peak, self.live)
+
+    def release(self, v):
+        """Algorithm 1, the body of its release loop: Director decides, the tensor leaves."""
+        act = self.director(v)
+        self.emit(act, v)
+        self.live -= self.T[v]["bytes"]
+        self.resident[v] = False
+        if act == EV_EVICT:
+            self.evicted[v], self.swapout[v] = True, False
+        else:
+            self.swapout[v] = True
 
     def drop(self, t):
         self.emit(EV_DROP_TEMP, t)
@@ -267,7 +300,9 @@ class _Sim:
             self.locked.add(st["produces"])
         for t in st["reads"]:                           # ascending id
             if not self.resident[t]:
+                self.bringing_back = t
                 self.materialise(t)
+                self.bringing_back = None
             self.provisional[t] = False
             self.evicted[t] = False
         need = self.T[st["produces"]]["bytes"] if st["produces"] >= 0 else 0
@@ -286,15 +321,7 @@ class _Sim:
                     if self.live + need <= self.B:
                         break
                     raise Infeasible(k, "nothing left to release")
-                v = self.filter(cands)
-                act = self.director(v)
-                self.emit(act, v)
-                self.live -= self.T[v]["bytes"]
-                self.resident[v] = False
-                if act == EV_EVICT:
-                    self.evicted[v], self.swapout[v] = True, False
-                else:
-                    self.swapout[v] = True
+                self.release(self.filter(cands))
         if st["produces"] >= 0:
             self.grow(need)
             self.resident[st["produces"]] = True
@@ -314,8 +341,34 @@ class _Sim:
 
 def plan(tensors, steps, params):
     """Returns (events, peak_bytes); events are (step, action, tensor) in issue order.
-    Raises Infeasible when some step cannot fit into the budget."""
-    sim = _Sim(tensors, steps, params)
-    for k in range(len(steps)):
-        sim.step(k)
-    return sim.events, sim.peak
+    Raises Infeasible when some step cannot fit into the budget.
+
+    repair_rounds > 0 (our addition; the paper's manager would simply run out of memory):
+    the operator sequence repeats every iteration (Assumption 1), so an iteration that
+    fails teaches the next one.  When an operand of a step cannot be brought back because
+    rebuilding it with its missing ancestors does not fit, that operand is treated as
+    uncomputable from then on -- the Director may only offload it (Sec. 4.3, the pin flags)
+    and it comes back by reload, which needs no more than its own bytes -- and the whole
+    iteration is planned again, at most repair_rounds times.  A failure anywhere else is final."""
+    return plan_with_pins(tensors, steps, params)[:2]
+
+
+def plan_with_pins(tensors, steps, params):
+    """plan() plus the list of tensors that the repair rounds made offload-only."""
+    learned = []
+    while True:
+        T = tensors
+        if learned:
+            T = [dict(t, flags=t["flags"] | UNCOMPUTABLE) if i in learned else t
+                 for i, t in enumerate(tensors)]
+        sim = _Sim(T, steps, params)
+        try:
+            for k in range(len(steps)):
+                sim.step(k)
+            return sim.events, sim.peak, learned
+        except Infeasible as e:
+            o = e.operand
+            if (o is None or len(learned) >= params.get("repair_rounds", 0)
+                    or T[o]["flags"] & UNCOMPUTABLE):
+                raise
+            learned.append(o)

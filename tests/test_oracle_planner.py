@@ -179,6 +179,241 @@ def test_handworked_temporaries_without_a_reader_are_dropped():
     checker.check(tensors, steps, p, ev)
 
 
+def test_handworked_leftovers_give_way_farthest_next_use_first_lowest_id_on_ties():
+    """Three leftovers of a recomputation with next uses 10, 11, 10 and an allocation that
+    needs the room of two of them (reading: rebuilt parents stay while a later step reads them
+    and go farthest next use first, ties to the lowest id).
+    t0 (m 4, never releasable: both pin flags) feeds t1, t2, t3 (m 4); t4 = f(t1, t2, t3);
+    t5 = f(t0), m 8; t6 = f(t4, t5); t7 = f(t6), m 8.  B = 20, trigger 1/1, no link.
+      step 4 fills the budget (t0..t4 = 20).  step 5 (t5 needs 8): t1..t4 all have s = 0, so
+        every product m*s is 0 and the lowest ids go: Evict t1, t2.  step 6: only t3 (s = 10)
+        is free to go.  step 7 (t7 needs 8): t4 then t5 (both s = 0, lowest id first); t6 and
+        t7 die at once.
+      step 8 reads t4: t1, t2, t3 are rebuilt first (live 20); they are read again at steps
+        10, 11, 10, so they stay as leftovers.
+      step 9 reads t5 (8 bytes, live 20): the farthest leftover t2 (step 11) goes first, then
+        the tie t1/t3 (step 10) goes to the lowest id, t1.
+    One-line mutations that turn this red: `nr > best_nr` -> `nr < best_nr` in grow (drops
+    t1, t3); `nr >= best_nr` (drops t2, t3); ignoring nr altogether (drops t1, t2)."""
+    both = pl.EVICT_PINNED | pl.OFFLOAD_PINNED
+    tensors = [T(4, 1, (), both), T(4, 10, (0,)), T(4, 10, (0,)), T(4, 10, (0,)),
+               T(4, 10, (1, 2, 3)), T(8, 10, (0,)), T(4, 10, (4, 5)), T(8, 10, (6,))]
+    steps = [dict(produces=0, reads=[], cost_ns=1)]
+    steps += [dict(produces=i, reads=list(tensors[i]["parents"]), cost_ns=10) for i in range(1, 8)]
+    steps += [dict(produces=-1, reads=r, cost_ns=20) for r in ([4], [5], [1, 3], [2], [0, 4])]
+    p = pl.default_params(20, 8, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [
+        (5, "EVICT", 1), (5, "EVICT", 2), (6, "EVICT", 3), (7, "EVICT", 4), (7, "EVICT", 5),
+        (7, "FREE", 6), (7, "FREE", 7),
+        (8, "RECOMPUTE", 1), (8, "RECOMPUTE", 2), (8, "RECOMPUTE", 3), (8, "RECOMPUTE", 4),
+        (9, "DROP_TEMP", 2), (9, "DROP_TEMP", 1), (9, "RECOMPUTE", 5), (9, "FREE", 5),
+        (10, "RECOMPUTE", 1), (10, "FREE", 1), (10, "FREE", 3),
+        (11, "RECOMPUTE", 2), (11, "FREE", 2), (12, "FREE", 0), (12, "FREE", 4)]
+    assert peak == 20
+    checker.check(tensors, steps, p, ev)
+
+
+def test_handworked_leftover_goes_before_the_filter_is_asked_in_the_forward_pass():
+    """A forward operator with a skip connection reads an evicted tensor; the parent rebuilt
+    for it is a leftover and must leave (DROP_TEMP) before Filter and Director release anything.
+    Chain t0..t5 (m 4, cost 10; t0 never releasable), t6 = f(t2, t5).  B = 24, trigger 3/4
+    (release while 4 (live + need) > 72), no link.
+      step 4: 4*20 > 72; t1 (s = 10) beats t2 (s = 0): Evict t1.  step 5: Evict t2
+        (s = 10; c_r = 10 + 10 for the missing t1).
+      step 6 reads t2: rebuild t1 (live 20), t2 (live 24); t1 is read again by the backward
+        pass, so it stays as a leftover.  Then the trigger: 4*(24 + 4) > 72: the leftover t1
+        goes first; 4*24 > 72 still: now the Filter: t3 (m*s = 4*30) beats t4 (4*20): Evict
+        t3, then Evict t4 (4*20 > 72 still); 4*16 <= 72 stops it.
+      backward: 7 [2,5,6], 8 [4,5] rebuilds t3 (leftover, read at 9) and t4, 9 [3,4],
+        10 [2,3], 11 [1,2] rebuilds t1, 12 [0,1].
+    Mutation: skipping the `if prov:` branch of step() makes the Filter evict t1 (m*s = 4*50)
+    as an ordinary EVICT."""
+    both = pl.EVICT_PINNED | pl.OFFLOAD_PINNED
+    tensors = [T(4, 1, (), both)] + [T(4, 10, (i - 1,)) for i in range(1, 6)] + [T(4, 10, (2, 5))]
+    steps = [dict(produces=0, reads=[], cost_ns=1)]
+    steps += [dict(produces=i, reads=list(tensors[i]["parents"]), cost_ns=10) for i in range(1, 7)]
+    steps += [dict(produces=-1, reads=r, cost_ns=20)
+              for r in ([2, 5, 6], [4, 5], [3, 4], [2, 3], [1, 2], [0, 1])]
+    p = pl.default_params(24, 7, bw_d2h_Bps=0, bw_h2d_Bps=0)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [
+        (4, "EVICT", 1), (5, "EVICT", 2),
+        (6, "RECOMPUTE", 1), (6, "RECOMPUTE", 2), (6, "DROP_TEMP", 1), (6, "EVICT", 3), (6, "EVICT", 4),
+        (7, "FREE", 6), (8, "RECOMPUTE", 3), (8, "RECOMPUTE", 4), (8, "FREE", 5), (9, "FREE", 4),
+        (10, "FREE", 3), (11, "RECOMPUTE", 1), (11, "FREE", 2), (12, "FREE", 0), (12, "FREE", 1)]
+    assert peak == 24
+    checker.check(tensors, steps, p, ev)
+
+
+def _offloaded_chain(sizes, budget, num, den):
+    """Chain t0..t5 with the given sizes and an effectively infinite link, so that every release is
+    an Offload (c_s = 2 ns); the early trigger num/den makes the forward pass offload t0, t1, t2
+    while the budget leaves the backward pass room to bring them back."""
+    tensors, steps, n_fwd = chain(6)
+    for t, m in zip(tensors, sizes):
+        t["bytes"] = m
+    return tensors, steps, pl.default_params(budget, n_fwd, trigger_num=num, trigger_den=den,
+                                             bw_d2h_Bps=10**18, bw_h2d_Bps=10**18)
+
+
+def test_handworked_prefetcher_window_admits_two_and_n_caps():
+    """Algorithm 4 with three queued tensors.  Chain of six, m = 4, B = 24, trigger 1/2: the
+    forward pass releases while live + need > 12, exactly as with a budget of 12: t0 at step 3
+    (uncomputable), t1 at step 4 (c_r = 10 + 1 > c_s = 2), t2 at step 5 -- all Offload.
+    The queue, by next use: t2 (step 8), t1 (9), t0 (10).  Backward steps 6 [4,5], 7 [3,4],
+    8 [2,3], 9 [1,2], 10 [0,1]; live is 12 when the backward pass starts.
+      d = 3, n = 2: step 6 sees uses up to step 9: t2 and t1 come back (live 20), t0 (step 10)
+        is outside the window; step 7: t0.
+      d = 4, n = 1: the window would admit t2 and t1 at step 6 and both fit, but one reload
+        per step: t2 at 6, t1 at 7, t0 at 8.
+    Mutations: dropping `issued < n` (two reloads at step 6 of the second case); `nr > k + d`
+    -> `nr >= k + d` (t1 waits for step 7 in the first case)."""
+    tensors, steps, p = _offloaded_chain([4] * 6, 24, 1, 2)
+    fwd = [(3, "OFFLOAD", 0), (4, "OFFLOAD", 1), (5, "OFFLOAD", 2)]
+    frees = {6: 5, 7: 4, 8: 3, 9: 2}
+    ev, peak = pl.plan(tensors, steps, dict(p, prefetch_distance=3, max_reloads=2))
+    assert names(ev) == fwd + [
+        (6, "RELOAD_PREFETCH", 2), (6, "RELOAD_PREFETCH", 1), (6, "FREE", 5),
+        (7, "RELOAD_PREFETCH", 0), (7, "FREE", 4), (8, "FREE", 3), (9, "FREE", 2),
+        (10, "FREE", 0), (10, "FREE", 1)]
+    assert peak == 20
+    checker.check(tensors, steps, dict(p, prefetch_distance=3, max_reloads=2), ev)
+    ev, peak = pl.plan(tensors, steps, dict(p, prefetch_distance=4, max_reloads=1))
+    assert names(ev) == fwd + [
+        (6, "RELOAD_PREFETCH", 2), (6, "FREE", 5), (7, "RELOAD_PREFETCH", 1), (7, "FREE", 4),
+        (8, "RELOAD_PREFETCH", 0), (8, "FREE", 3), (9, "FREE", 2), (10, "FREE", 0), (10, "FREE", 1)]
+    assert peak == 16 and frees
+    checker.check(tensors, steps, dict(p, prefetch_distance=4, max_reloads=1), ev)
+
+
+def test_handworked_prefetcher_stops_at_a_head_that_does_not_fit():
+    """The head of the queue blocks what stands behind it.  Sizes 4, 4, 12, 4, 4, 4; B = 20,
+    trigger 3/5 (release while live + need > 12).  Forward: step 2 (t2 needs 12, live 8):
+    only t0 may go (Offload), then nothing is left and 16 <= 20 is allowed; step 3: Offload t1;
+    step 4: Offload t2 (c_r = 10 + 10 + 1 > 2).  Backward starts with t3, t4, t5 = 12 bytes.
+    d = 4, n = 3.  step 6: the head t2 (12 bytes, used at step 8) does not fit (24 > 20), and
+    although t1 (4 bytes, used at step 9, inside the window) would, nothing is reloaded.
+    step 7 (live 8): t2 fits exactly; t1 no longer does.  step 8: t1; step 9: t0.
+    Mutation: `break` -> skip to the next queued tensor reloads t1 at step 6."""
+    tensors, steps, p = _offloaded_chain([4, 4, 12, 4, 4, 4], 20, 3, 5)
+    p = dict(p, prefetch_distance=4, max_reloads=3)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [
+        (2, "OFFLOAD", 0), (3, "OFFLOAD", 1), (4, "OFFLOAD", 2), (6, "FREE", 5),
+        (7, "RELOAD_PREFETCH", 2), (7, "FREE", 4), (8, "RELOAD_PREFETCH", 1), (8, "FREE", 3),
+        (9, "RELOAD_PREFETCH", 0), (9, "FREE", 2), (10, "FREE", 0), (10, "FREE", 1)]
+    assert peak == 20
+    checker.check(tensors, steps, p, ev)
+
+
+def test_handworked_demand_reload_of_an_uncomputable_parent_inside_a_recomputation():
+    """The first hand-worked chain with the Prefetcher switched off (n = 0): at step 7 the
+    evicted t1 is rebuilt, its parent t0 is offloaded and cannot be recomputed, so it comes
+    back by a demand reload inside the recomputation (Algorithm 1: Reload when uncomputable),
+    and stays because step 8 reads it.  When step 8 reads t1 only, t0 is dead after step 1, is
+    freed there and never offloaded, so the rebuild of t1 at step 7 has no way to get its
+    parent: the plan fails at step 7.
+    Mutation: raising on an uncomputable parent, or recomputing it, changes event (7, ., 0)."""
+    tensors, steps, n_fwd = chain(5)
+    p = pl.default_params(12, n_fwd, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0,
+                          prefetch_distance=1, max_reloads=0)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(3, "OFFLOAD", 0), (4, "EVICT", 1), (5, "FREE", 4), (6, "FREE", 3),
+                         (7, "RELOAD_DEMAND", 0), (7, "RECOMPUTE", 1), (7, "FREE", 2),
+                         (8, "FREE", 0), (8, "FREE", 1)]
+    assert peak == 12
+    checker.check(tensors, steps, p, ev)
+    steps[8]["reads"] = [1]
+    with pytest.raises(pl.Infeasible) as e:
+        pl.plan(tensors, steps, p)
+    assert e.value.step == 7
+
+
+def test_handworked_release_when_memory_is_short_in_the_backward_pass():
+    """Algorithm 1 taken literally (release_when_short): its release loop also runs when an
+    allocation of the backward pass does not fit.  t0 (m 4, cost 5) -> t1 -> t2 -> t3 (m 8,
+    cost 10); backward steps 4 [0,2], 5 [2,3], 6 [0,3], 7 [3]; B = 16, trigger 1/1, no link.
+      step 2: t0 is the only tensor free to go: Evict; t1 dies.  step 3 fills the budget.
+      step 4 needs t0 back (4 bytes, live 16): no leftover to drop; the only resident tensor
+        that the step does not use and that is read later is t3: Evict t3, Recompute t0.
+      step 5 needs t3 back (8 bytes, live 12): t0 (read again at 6) goes: Evict, Recompute t3.
+      step 6: Recompute t0.
+    With the switch off (Assumption 2 to the letter) step 4 cannot be planned."""
+    tensors = [T(4, 5), T(8, 10, (0,)), T(8, 10, (1,)), T(8, 10, (2,))]
+    steps = [dict(produces=0, reads=[], cost_ns=5)]
+    steps += [dict(produces=i, reads=[i - 1], cost_ns=10) for i in (1, 2, 3)]
+    steps += [dict(produces=-1, reads=r, cost_ns=20) for r in ([0, 2], [2, 3], [0, 3], [3])]
+    p = pl.default_params(16, 4, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0)
+    with pytest.raises(pl.Infeasible) as e:
+        pl.plan(tensors, steps, p)
+    assert e.value.step == 4
+    p = dict(p, release_when_short=1)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(2, "EVICT", 0), (2, "FREE", 1), (4, "EVICT", 3), (4, "RECOMPUTE", 0),
+                         (5, "EVICT", 0), (5, "RECOMPUTE", 3), (5, "FREE", 2),
+                         (6, "RECOMPUTE", 0), (6, "FREE", 0), (7, "FREE", 3)]
+    assert peak == 16
+    checker.check(tensors, steps, p, ev)
+    with pytest.raises(checker.PlanError):          # the same events are no plan under Assumption 2
+        checker.check(tensors, steps, dict(p, release_when_short=0), ev)
+    # a release in the backward pass that no allocation needs is refused even with the switch on
+    big = dict(p, budget_bytes=64)
+    evb, _ = pl.plan(tensors, steps, big)
+    bad = sorted(evb + [(5, pl.EV_EVICT, 0)], key=lambda x: (x[0], x[1] == pl.EV_FREE))
+    with pytest.raises(checker.PlanError):
+        checker.check(tensors, steps, big, bad)
+
+
+def test_handworked_repair_round_makes_the_failing_operand_offload_only():
+    """repair_rounds (our addition): t0 (m 4) -> t1 (m 8) -> t2 (m 4) -> t3 (m 8); backward
+    steps 4 [1], 5 [1,3]; B = 16, trigger 1/1, no link, Prefetcher off.
+    First pass: t0 dies at step 1; step 3 evicts t1 (the only tensor free to go), t2 dies.
+    Step 4 must rebuild t1, which first rebuilds t0 (live 8 + 4), and then t1's 8 bytes do not
+    fit: the plan fails with t1 as the operand that could not be brought back.
+    Second pass: t1 counts as uncomputable, so step 3 offloads it and step 4 reloads it (8
+    bytes fit beside t3)."""
+    tensors = [T(4, 5), T(8, 10, (0,)), T(4, 10, (1,)), T(8, 10, (2,))]
+    steps = [dict(produces=0, reads=[], cost_ns=5)]
+    steps += [dict(produces=i, reads=[i - 1], cost_ns=10) for i in (1, 2, 3)]
+    steps += [dict(produces=-1, reads=r, cost_ns=20) for r in ([1], [1, 3])]
+    p = pl.default_params(16, 4, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0,
+                          max_reloads=0)
+    with pytest.raises(pl.Infeasible) as e:
+        pl.plan(tensors, steps, p)
+    assert e.value.step == 4 and e.value.operand == 1
+    p = dict(p, repair_rounds=1)
+    ev, peak, learned = pl.plan_with_pins(tensors, steps, p)
+    assert learned == [1]
+    assert names(ev) == [(1, "FREE", 0), (3, "OFFLOAD", 1), (3, "FREE", 2),
+                         (4, "RELOAD_DEMAND", 1), (5, "FREE", 1), (5, "FREE", 3)]
+    assert peak == 16
+    checker.check(tensors, steps, p, ev)
+
+
+@pytest.mark.parametrize("frac", [0.6, 0.55, 0.5, 0.45, 0.4])
+def test_config2_plans_wherever_a_static_plan_exists(frac):
+    """The conv2_x stage (config 2): the exhaustive search finds a static plan at every one of
+    these budgets.  The single greedy pass does not below 60 % (it evicts b2.a1 and b1.out, and
+    rebuilding b2.a2 then needs b1.a2 + b1.sc + b1.out next to the locked b2.out: 167 MB); with
+    repair rounds the heuristic plans all of them.  The gap to the optimum is printed."""
+    g = synth.config_graph(2)
+    B = int(frac * g.total_bytes())
+    p = pl.default_params(B, g.n_fwd, repair_rounds=8)
+    o = brute.optimum(g.tensors, g.steps, p)
+    assert o is not None
+    if frac < 0.6:
+        with pytest.raises(pl.Infeasible):
+            pl.plan(g.tensors, g.steps, dict(p, repair_rounds=0))
+        with pytest.raises(pl.Infeasible):          # the literal reading of Algorithm 1 alone does not help
+            pl.plan(g.tensors, g.steps, dict(p, repair_rounds=0, release_when_short=1))
+    ev, peak, learned = pl.plan_with_pins(g.tensors, g.steps, p)
+    st = checker.check(g.tensors, g.steps, p, ev)
+    assert st["peak"] == peak <= B
+    print("config 2 at %.0f %%: heuristic %d ns (offload-only: %s), static optimum %d ns"
+          % (100 * frac, st["cost_ns"], [g.tensors[t]["name"] for t in learned], o["cost"]))
+
+
 def test_chain_victims_leave_in_production_order():
     """Equal m and cost on a chain: the stalest resident tensor is always the oldest one,
     so base, LRU and (by the lowest-id tie-break) GREEDY all release t0, t1, t2, ..."""
