@@ -107,6 +107,19 @@ typedef struct {
     uint32_t max_reloads;                  /* n of Algorithm 4, per step */
     uint32_t n_fwd_steps;
     uint64_t bw_d2h_Bps, bw_h2d_Bps;       /* b of Eq. (6), per direction; 0 = no link */
+    uint32_t release_when_short;           /* 0: Evict/Offload only in the forward pass's release loop
+                                              (Assumption 2).  1: Algorithm 1 to the letter: the loop
+                                              also runs whenever an allocation does not fit ("memory is
+                                              not enough"), in either pass, over the tensors that the
+                                              running operator and the recomputations in progress do
+                                              not use */
+    uint32_t repair_rounds;                /* > 0: when an operand of a step cannot be brought back
+                                              because rebuilding it with its missing ancestors does not
+                                              fit, plan the iteration again with that operand treated as
+                                              uncomputable (offload-only, Sec. 4.3: it then returns by
+                                              reload), at most this many times.  The operator sequence
+                                              repeats every iteration (Assumption 1), so a failed
+                                              iteration can teach the next.  0: fail at once */
 } delta_plan_params;
 
 typedef struct { uint32_t step, action, tensor, pad; } delta_event;

@@ -41,7 +41,8 @@ class StepDesc(C.Structure):
 class PlanParams(C.Structure):
     _fields_ = [("budget_bytes", C.c_uint64), ("trigger_num", C.c_uint32), ("trigger_den", C.c_uint32),
                 ("filter", C.c_uint32), ("prefetch_distance", C.c_uint32), ("max_reloads", C.c_uint32),
-                ("n_fwd_steps", C.c_uint32), ("bw_d2h_Bps", C.c_uint64), ("bw_h2d_Bps", C.c_uint64)]
+                ("n_fwd_steps", C.c_uint32), ("bw_d2h_Bps", C.c_uint64), ("bw_h2d_Bps", C.c_uint64),
+                ("release_when_short", C.c_uint32), ("repair_rounds", C.c_uint32)]
 
 
 class Event(C.Structure):
@@ -146,6 +147,14 @@ def layer_array(descs):
     return arr
 
 
+_OPTIONAL_PLAN_PARAMS = ("release_when_short", "repair_rounds")      # 0 when the caller leaves them out
+
+
+def _plan_params(params):
+    return PlanParams(**{k: int(params.get(k, 0) if k in _OPTIONAL_PLAN_PARAMS else params[k])
+                         for k, _ in PlanParams._fields_})
+
+
 def _marshal_graph(tensors, steps, params):
     keep = []
     td = (TensorDesc * len(tensors))()
@@ -159,7 +168,7 @@ def _marshal_graph(tensors, steps, params):
         rd = (C.c_uint32 * len(s["reads"]))(*s["reads"])
         keep.append(rd)
         sd[i] = StepDesc(s["produces"], len(s["reads"]), C.cast(rd, C.POINTER(C.c_uint32)), s["cost_ns"])
-    pp = PlanParams(**{k: int(params[k]) for k, _ in PlanParams._fields_})
+    pp = _plan_params(params)
     return td, sd, pp, keep
 
 
@@ -205,7 +214,7 @@ class Delta:
         the result of prepare_graph() (then `steps` is ignored)."""
         if isinstance(tensors, tuple) and tensors and tensors[0] == "prepared":
             _, td, sd, keep, nt, ns = tensors
-            pp = PlanParams(**{k: int(params[k]) for k, _ in PlanParams._fields_})
+            pp = _plan_params(params)
             tensors, steps = range(nt), range(ns)
         else:
             td, sd, pp, keep = _marshal_graph(tensors, steps, params)

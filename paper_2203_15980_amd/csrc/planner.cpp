@@ -1,16 +1,34 @@
-// Planner behind delta_plan: DELTA's main loop (Algorithm 1) simulated over a static
-// operator trace, with the Filter (Algorithm 2, Eq. 1-3), the Director (Algorithm 3,
-// Eq. 4-6) and the Prefetcher (Algorithm 4).  Integer arithmetic only.
+// Planner behind delta_plan.
 //
-// Readings taken where the paper leaves room (all stated in the design notes):
-//   staleness s(t) runs on a logical clock that advances by the cost of every executed or
-//   recomputed operator, transfers do not advance it (Assumption 3); c_s = offload time +
-//   reload time (Sec. 3); F <= 1 evicts (Algorithm 3); the offloaded queue is ordered by
-//   next use; the Prefetcher reloads while memory allows AND fewer than n were issued; the
-//   release loop runs in the forward pass only (Assumption 2), down to trigger*B or until
-//   nothing releasable is left, and fails only above B; parents rebuilt as operands of a
-//   recomputation stay as provisional tensors while a later step reads them and go first
-//   (farthest next use first) when room is needed.
+// The paper describes DELTA as a manager that sits under a framework's executor and is called
+// once per tensor access (Algorithm 1): bring the accessed tensor back if it is gone, then,
+// while memory is tight, let the Filter (Algorithm 2, Eq. 1-3) pick a resident tensor and the
+// Director (Algorithm 3, Eq. 4-6) decide between Evict and Offload; before the backward pass's
+// operators the Prefetcher (Algorithm 4) reloads offloaded tensors.  This file is that manager
+// (class Manager: on_access, make_room, pick_victim, decide, prefetch) plus an executor stand-in
+// (run_iteration) that walks the operator sequence of one training iteration (Assumption 1) and
+// records what the manager does as plan events.  Integer arithmetic only: products of bytes and
+// time are 128-bit, costs saturate at 2^64 - 1.
+//
+// Where the paper leaves room, the choices are:
+//   * time runs on a logical clock that advances by the cost of every operator that runs,
+//     recomputations included; copies do not advance it (Assumption 3).  Staleness s(t) is the
+//     clock minus the tensor's last access by an operator of the sequence;
+//   * c_s(t) is the offload time plus the reload time (Sec. 3), each rounded up to a nanosecond;
+//     c_r(t) is t's own cost plus, once each, the cost of every missing ancestor reached through
+//     missing tensors (reload time for one that cannot be recomputed); F <= 1 evicts;
+//   * the release loop runs before a forward operator's output is allocated and stops at the
+//     early-start level (3/4 of the budget in the paper, Sec. 4.3) or when nothing releasable is
+//     left; only a step that does not fit into the whole budget fails.  After the forward pass no
+//     Evict or Offload is issued (Assumption 2), unless release_when_short asks for Algorithm 1
+//     to the letter: then the same loop also runs whenever an allocation does not fit;
+//   * parents that were rebuilt only to recompute a tensor stay on the GPU as leftovers while
+//     some later operator reads them, and are the first to give way (latest next use first, ties to
+//     the lowest id); one nobody reads again leaves at once;
+//   * the Prefetcher's queue is ordered by next use (ties: lowest id); it looks d steps ahead,
+//     issues at most n reloads per step, and stops at the first tensor that does not fit;
+//   * repair_rounds: an iteration whose operand could not be brought back is planned again with
+//     that operand offload-only (it then returns by reload, which needs only its own bytes).
 #include "planner.hpp"
 
 #include <algorithm>
@@ -19,255 +37,341 @@
 
 namespace delta {
 
-typedef unsigned __int128 u128;
-static const uint64_t kU64Max = std::numeric_limits<uint64_t>::max();
-
-static uint64_t transfer_ns(uint64_t bytes, uint64_t bw) {
-    if (bw == 0) return kU64Max;
-    u128 q = ((u128)bytes * 1000000000u + (bw - 1)) / bw;
-    return q > (u128)kU64Max ? kU64Max : (uint64_t)q;
-}
-
-static uint64_t sat_add(uint64_t a, uint64_t b) { return a > kU64Max - b ? kU64Max : a + b; }
-
 namespace {
 
-struct Sim {
-    const std::vector<PlanTensor> &T;
-    const std::vector<PlanStep> &S;
-    const delta_plan_params &P;
-    uint32_t nT;
-    std::vector<uint8_t> resident, swapout, provisional, locked, hold;
-    std::vector<uint64_t> last_access;
-    std::vector<std::vector<uint32_t>> reads_at;   // per tensor: steps that read it, ascending
-    std::vector<uint32_t> cursor;                  // per tensor: first entry of reads_at >= current step
-    uint64_t tau = 0, live = 0, peak = 0;
-    uint32_t k = 0;
-    std::vector<delta_event> ev;
-    std::string err;
-    bool failed = false;
+typedef unsigned __int128 u128;
+const uint64_t kForever = std::numeric_limits<uint64_t>::max();
+const uint32_t kNoStep = 0xFFFFFFFFu;
+const uint32_t kNoTensor = 0xFFFFFFFFu;
 
-    Sim(const std::vector<PlanTensor> &t, const std::vector<PlanStep> &s, const delta_plan_params &p)
-        : T(t), S(s), P(p), nT((uint32_t)t.size()), resident(nT, 0), swapout(nT, 0),
-          provisional(nT, 0), locked(nT, 0), hold(nT, 0), last_access(nT, 0), reads_at(nT),
-          cursor(nT, 0) {
-        for (uint32_t i = 0; i < S.size(); ++i)
-            for (uint32_t r : S[i].reads) reads_at[r].push_back(i);
+uint64_t saturating_sum(uint64_t a, uint64_t b) { return b > kForever - a ? kForever : a + b; }
+
+// ceil(bytes / bandwidth) in ns; a link of 0 B/s never finishes
+uint64_t copy_ns(uint64_t bytes, uint64_t bytes_per_s) {
+    if (!bytes_per_s) return kForever;
+    const u128 ns = ((u128)bytes * 1000000000ull + bytes_per_s - 1) / bytes_per_s;
+    return ns > (u128)kForever ? kForever : (uint64_t)ns;
+}
+
+// The fields of the paper's struct DELTATensor (Sec. 4.3) that the planner needs, plus the
+// trace knowledge a static plan has: when the tensor is used.
+struct Record {
+    uint64_t memory = 0, compute_cost = 0;
+    bool uncomputable = false, evict_pinned = false, offload_pinned = false;
+    bool on_gpu = false;
+    bool host_copy = false;        // "swapout": a valid copy sits in host memory
+    bool leftover = false;         // on the GPU only because a recomputation needed it
+    bool operand = false;          // read or produced by the operator that is running
+    uint32_t rebuilding = 0;       // number of recomputations in progress that hold it as a parent
+    uint64_t last_access = 0;
+    std::vector<uint32_t> uses;    // steps that read it, ascending
+    size_t seen = 0;               // uses[0 .. seen) lie before the running step
+    const std::vector<uint32_t> *parents = nullptr;
+
+    // first use at or after the running step / strictly after it
+    uint32_t use_from_now() const { return seen < uses.size() ? uses[seen] : kNoStep; }
+    uint32_t use_after(uint32_t now) const {
+        size_t i = seen;
+        if (i < uses.size() && uses[i] == now) ++i;
+        return i < uses.size() ? uses[i] : kNoStep;
     }
+    bool may_never_leave() const { return (evict_pinned || uncomputable) && offload_pinned; }
+};
 
-    static const uint32_t kNever = 0xFFFFFFFFu;
+struct OutOfMemory {
+    uint32_t step;
+    uint32_t operand;              // the step's operand that was on its way back, or kNoTensor
+    std::string what;
+};
 
-    // first step >= from that reads t, or kNever
-    uint32_t next_read(uint32_t t, uint32_t from) const {
-        const std::vector<uint32_t> &v = reads_at[t];
-        std::vector<uint32_t>::const_iterator it = std::lower_bound(v.begin(), v.end(), from);
-        return it == v.end() ? kNever : *it;
-    }
-
-    bool computable(uint32_t t) const { return !(T[t].flags & DELTA_F_UNCOMPUTABLE); }
-
-    void emit(uint32_t action, uint32_t t) {
-        delta_event e = {k, action, t, 0};
-        ev.push_back(e);
-    }
-
-    void fail(const char *what, uint64_t a = 0, uint64_t b = 0) {
-        if (failed) return;
-        char buf[256];
-        snprintf(buf, sizeof buf, "step %u: %s (%llu, %llu; budget %llu)", k, what,
-                 (unsigned long long)a, (unsigned long long)b, (unsigned long long)P.budget_bytes);
-        err = buf;
-        failed = true;
-    }
-
-    void drop(uint32_t t) {
-        emit(DELTA_EV_DROP_TEMP, t);
-        live -= T[t].bytes;
-        resident[t] = 0;
-        provisional[t] = 0;
-    }
-
-    // provisional tensor with the farthest next use (lowest id on ties) that is neither an
-    // operand of the running step nor of a recomputation in progress; nT when none
-    uint32_t farthest_provisional(bool respect_hold) const {
-        uint32_t best = nT, best_nr = 0;
-        for (uint32_t t = 0; t < nT; ++t) {
-            if (!provisional[t] || locked[t] || (respect_hold && hold[t])) continue;
-            uint32_t nr = next_read(t, k);
-            if (best == nT || nr > best_nr) { best = t; best_nr = nr; }
+class Manager {
+  public:
+    Manager(const std::vector<PlanTensor> &tensors, const std::vector<PlanStep> &steps,
+            const delta_plan_params &params, const std::vector<uint8_t> &offload_only)
+        : steps_(steps), cfg_(params), rec_(tensors.size()), mark_(tensors.size(), 0) {
+        for (size_t t = 0; t < tensors.size(); ++t) {
+            Record &r = rec_[t];
+            r.memory = tensors[t].bytes;
+            r.compute_cost = tensors[t].cost_ns;
+            r.uncomputable = (tensors[t].flags & DELTA_F_UNCOMPUTABLE) || offload_only[t];
+            r.evict_pinned = tensors[t].flags & DELTA_F_EVICT_PINNED;
+            r.offload_pinned = tensors[t].flags & DELTA_F_OFFLOAD_PINNED;
+            r.parents = &tensors[t].parents;
         }
-        return best;
+        for (uint32_t k = 0; k < steps.size(); ++k)
+            for (uint32_t t : steps[k].reads) rec_[t].uses.push_back(k);
     }
 
-    void grow(uint64_t bytes) {
-        while (!failed && live + bytes > P.budget_bytes) {
-            uint32_t v = farthest_provisional(true);
-            if (v == nT) { fail("allocation does not fit", live, bytes); return; }
-            drop(v);
+    // One operator of the sequence.  Throws OutOfMemory.
+    void run_step(uint32_t k) {
+        now_ = k;
+        const PlanStep &op = steps_[k];
+        const bool forward = k < cfg_.n_fwd_steps;
+        for (Record &r : rec_)
+            while (r.seen < r.uses.size() && r.uses[r.seen] < k) ++r.seen;
+        if (!forward) prefetch();
+        for (uint32_t t : op.reads) rec_[t].operand = true;
+        if (op.produces >= 0) rec_[op.produces].operand = true;
+        for (uint32_t t : op.reads) {
+            on_access(t);
+            rec_[t].leftover = false;
         }
-        live += bytes;
-        if (live > peak) peak = live;
+        if (op.produces >= 0) {
+            Record &out = rec_[op.produces];
+            if (forward) early_release(out.memory);
+            make_room(out.memory, kNoTensor);
+            occupy(out.memory);
+            out.on_gpu = true;
+        }
+        clock_ += op.cost_ns;
+        // ids in ascending order, each once: reads are ascending, the output is a new id
+        std::vector<uint32_t> touched(op.reads);
+        if (op.produces >= 0)
+            touched.insert(std::upper_bound(touched.begin(), touched.end(), (uint32_t)op.produces), (uint32_t)op.produces);
+        for (uint32_t t : touched) rec_[t].last_access = clock_;
+        for (uint32_t t : touched) {
+            Record &r = rec_[t];
+            r.operand = false;
+            if (r.use_after(k) == kNoStep) {            // its last use has passed
+                note(DELTA_EV_FREE, t);
+                vacate(r);
+            }
+        }
     }
 
-    // Algorithm 1, lines on the accessed tensor: Recompute when possible, else Reload.
-    void materialise(uint32_t t) {
-        if (failed) return;
-        if (computable(t)) {
-            const std::vector<uint32_t> &par = T[t].parents;
-            for (uint32_t p : par) ++hold[p];
-            std::vector<uint32_t> mine;
-            for (uint32_t p : par) {
-                if (!resident[p]) {
-                    materialise(p);
-                    if (failed) return;
-                    mine.push_back(p);
+    std::vector<delta_event> events;
+    uint64_t peak = 0;
+
+  private:
+    const std::vector<PlanStep> &steps_;
+    const delta_plan_params &cfg_;
+    std::vector<Record> rec_;
+    std::vector<uint32_t> mark_;       // visit stamps of the ancestor walk
+    uint32_t stamp_ = 0;
+    uint32_t now_ = 0;
+    uint64_t clock_ = 0, in_use_ = 0;
+
+    void note(uint32_t action, uint32_t t) {
+        const delta_event e = {now_, action, t, 0};
+        events.push_back(e);
+    }
+    void occupy(uint64_t bytes) {
+        in_use_ += bytes;
+        if (in_use_ > peak) peak = in_use_;
+    }
+    void vacate(Record &r) {
+        in_use_ -= r.memory;
+        r.on_gpu = false;
+        r.leftover = false;
+    }
+
+    // ---- Algorithm 1, first half: the accessed tensor must be on the GPU.
+    // A missing tensor that can be recomputed is recomputed, after its missing parents (depth
+    // first, ascending ids); one that cannot is reloaded from its host copy.  Written as a loop
+    // over an explicit stack of recomputations in progress.
+    struct Rebuild {
+        uint32_t tensor;
+        size_t next_parent;
+        std::vector<uint32_t> fetched;     // parents this recomputation had to bring back
+    };
+
+    void on_access(uint32_t wanted) {
+        if (rec_[wanted].on_gpu) return;
+        std::vector<Rebuild> stack;
+        open_rebuild(stack, wanted, wanted);
+        while (!stack.empty()) {
+            Rebuild &top = stack.back();
+            Record &r = rec_[top.tensor];
+            const std::vector<uint32_t> &parents = *r.parents;
+            if (top.next_parent < parents.size()) {
+                const uint32_t p = parents[top.next_parent++];
+                if (!rec_[p].on_gpu) {
+                    top.fetched.push_back(p);
+                    open_rebuild(stack, p, wanted);     // may invalidate `top`
+                }
+                continue;
+            }
+            // all parents are here: run the operator again
+            make_room(r.memory, wanted);
+            occupy(r.memory);
+            note(DELTA_EV_RECOMPUTE, top.tensor);
+            clock_ += r.compute_cost;
+            r.on_gpu = true;
+            for (uint32_t p : parents) --rec_[p].rebuilding;
+            for (uint32_t p : top.fetched) {
+                Record &q = rec_[p];
+                if (q.operand) continue;                // the running operator reads it anyway
+                if (q.use_after(now_) == kNoStep) {
+                    note(DELTA_EV_DROP_TEMP, p);
+                    vacate(q);
+                } else {
+                    q.leftover = true;
                 }
             }
-            grow(T[t].bytes);
-            if (failed) return;
-            emit(DELTA_EV_RECOMPUTE, t);
-            tau += T[t].cost_ns;
-            for (uint32_t p : par) --hold[p];
-            for (uint32_t p : mine) {
-                if (locked[p]) continue;
-                if (next_read(p, k + 1) == kNever) drop(p);
-                else provisional[p] = 1;
-            }
-        } else if (swapout[t]) {
-            grow(T[t].bytes);
-            if (failed) return;
-            emit(DELTA_EV_RELOAD_DEMAND, t);
-        } else {
-            fail("tensor can neither be recomputed nor reloaded", t);
-            return;
+            stack.pop_back();
         }
-        resident[t] = 1;
     }
 
-    // Algorithm 2: minimum of 1/(m*s), 1/s or 1/m == maximum of m*s, s or m.
-    uint32_t filter(const std::vector<uint32_t> &cands) const {
-        uint32_t best = cands[0];
-        u128 best_key = 0;
-        bool first = true;
-        for (uint32_t t : cands) {
-            uint64_t s = tau - last_access[t];
-            u128 key = P.filter == DELTA_FILTER_BASE ? (u128)T[t].bytes * s
-                     : P.filter == DELTA_FILTER_LRU  ? (u128)s
-                                                     : (u128)T[t].bytes;
-            if (first || key > best_key) { best = t; best_key = key; first = false; }
+    // Starts bringing `t` back: a reload completes at once, a recomputation goes on the stack.
+    void open_rebuild(std::vector<Rebuild> &stack, uint32_t t, uint32_t wanted) {
+        Record &r = rec_[t];
+        if (!r.uncomputable) {
+            for (uint32_t p : *r.parents) ++rec_[p].rebuilding;
+            Rebuild f;
+            f.tensor = t;
+            f.next_parent = 0;
+            stack.push_back(f);
+            return;
+        }
+        if (!r.host_copy) {
+            char msg[96];
+            snprintf(msg, sizeof msg, "tensor %u can neither be recomputed nor reloaded", t);
+            throw OutOfMemory{now_, kNoTensor, msg};
+        }
+        make_room(r.memory, wanted);
+        occupy(r.memory);
+        note(DELTA_EV_RELOAD_DEMAND, t);
+        r.on_gpu = true;
+    }
+
+    // ---- Algorithm 1, second half: the release loop.
+    bool idle(const Record &r) const { return !r.operand && r.rebuilding == 0; }
+
+    // the leftover to drop next: latest next use, lowest id among equals
+    uint32_t next_leftover() const {
+        uint32_t best = kNoTensor, best_use = 0;
+        for (uint32_t t = 0; t < rec_.size(); ++t) {
+            const Record &r = rec_[t];
+            if (!r.leftover || !idle(r)) continue;
+            const uint32_t u = r.use_from_now();
+            if (best == kNoTensor || u > best_use) {
+                best = t;
+                best_use = u;
+            }
         }
         return best;
     }
 
-    // c_r(t), Eq. (5): own cost plus missing ancestors reached through missing tensors.
-    uint64_t recompute_cost(uint32_t t) const {
-        uint64_t total = T[t].cost_ns;
-        std::vector<uint8_t> seen(nT, 0);
-        std::vector<uint32_t> stack(T[t].parents.begin(), T[t].parents.end());
-        while (!stack.empty()) {
-            uint32_t a = stack.back();
-            stack.pop_back();
-            if (seen[a] || resident[a]) continue;
-            seen[a] = 1;
-            if (computable(a)) {
-                total = sat_add(total, T[a].cost_ns);
-                stack.insert(stack.end(), T[a].parents.begin(), T[a].parents.end());
+    // Algorithm 2.  The minimum of H = 1/(m s), 1/s or 1/m is the maximum of m s, s or m; the
+    // first of equal scores wins; s = 0 scores lowest without a division.
+    uint32_t pick_victim() const {
+        uint32_t best = kNoTensor;
+        u128 best_score = 0;
+        for (uint32_t t = 0; t < rec_.size(); ++t) {
+            const Record &r = rec_[t];
+            if (!r.on_gpu || r.leftover || !idle(r) || r.may_never_leave() || r.use_after(now_) == kNoStep) continue;
+            const uint64_t stale = clock_ - r.last_access;
+            u128 score;
+            switch (cfg_.filter) {
+            case DELTA_FILTER_LRU: score = stale; break;
+            case DELTA_FILTER_GREEDY: score = r.memory; break;
+            default: score = (u128)r.memory * stale; break;
+            }
+            if (best == kNoTensor || score > best_score) {
+                best = t;
+                best_score = score;
+            }
+        }
+        return best;
+    }
+
+    // c_r(t) of Eq. (5)
+    uint64_t rebuild_cost(uint32_t t) {
+        ++stamp_;
+        uint64_t total = rec_[t].compute_cost;
+        std::vector<uint32_t> todo(rec_[t].parents->rbegin(), rec_[t].parents->rend());
+        while (!todo.empty()) {
+            const uint32_t a = todo.back();
+            todo.pop_back();
+            if (rec_[a].on_gpu || mark_[a] == stamp_) continue;
+            mark_[a] = stamp_;
+            if (rec_[a].uncomputable) {
+                total = saturating_sum(total, copy_ns(rec_[a].memory, cfg_.bw_h2d_Bps));
             } else {
-                total = sat_add(total, transfer_ns(T[a].bytes, P.bw_h2d_Bps));
+                total = saturating_sum(total, rec_[a].compute_cost);
+                todo.insert(todo.end(), rec_[a].parents->rbegin(), rec_[a].parents->rend());
             }
         }
         return total;
     }
 
-    // Algorithm 3.
-    uint32_t director(uint32_t t) const {
-        uint32_t f = T[t].flags;
-        if (f & (DELTA_F_EVICT_PINNED | DELTA_F_UNCOMPUTABLE)) return DELTA_EV_OFFLOAD;
-        if (f & DELTA_F_OFFLOAD_PINNED) return DELTA_EV_EVICT;
-        uint64_t c_s = sat_add(transfer_ns(T[t].bytes, P.bw_d2h_Bps),
-                               transfer_ns(T[t].bytes, P.bw_h2d_Bps));
-        return recompute_cost(t) <= c_s ? DELTA_EV_EVICT : DELTA_EV_OFFLOAD;
+    // Algorithm 3
+    uint32_t decide(uint32_t t) {
+        const Record &r = rec_[t];
+        if (r.evict_pinned || r.uncomputable) return DELTA_EV_OFFLOAD;
+        if (r.offload_pinned) return DELTA_EV_EVICT;
+        const uint64_t c_s = saturating_sum(copy_ns(r.memory, cfg_.bw_d2h_Bps), copy_ns(r.memory, cfg_.bw_h2d_Bps));
+        return rebuild_cost(t) <= c_s ? DELTA_EV_EVICT : DELTA_EV_OFFLOAD;
     }
 
-    // Algorithm 4.
+    void release(uint32_t t) {
+        const uint32_t action = decide(t);
+        note(action, t);
+        rec_[t].host_copy = action == DELTA_EV_OFFLOAD;
+        vacate(rec_[t]);
+    }
+
+    // "3/4 of the memory is used": before a forward operator's output of `incoming` bytes
+    void early_release(uint64_t incoming) {
+        while ((u128)cfg_.trigger_den * ((u128)in_use_ + incoming) > (u128)cfg_.trigger_num * cfg_.budget_bytes) {
+            uint32_t t = next_leftover();
+            if (t != kNoTensor) {
+                note(DELTA_EV_DROP_TEMP, t);
+                vacate(rec_[t]);
+                continue;
+            }
+            t = pick_victim();
+            if (t == kNoTensor) {
+                if (in_use_ + incoming <= cfg_.budget_bytes) return;
+                char msg[128];
+                snprintf(msg, sizeof msg, "nothing left to release (%llu in use + %llu; budget %llu)",
+                         (unsigned long long)in_use_, (unsigned long long)incoming, (unsigned long long)cfg_.budget_bytes);
+                throw OutOfMemory{now_, kNoTensor, msg};
+            }
+            release(t);
+        }
+    }
+
+    // "memory is not enough": `incoming` bytes must fit into the budget
+    void make_room(uint64_t incoming, uint32_t wanted) {
+        while (in_use_ + incoming > cfg_.budget_bytes) {
+            uint32_t t = next_leftover();
+            if (t != kNoTensor) {
+                note(DELTA_EV_DROP_TEMP, t);
+                vacate(rec_[t]);
+                continue;
+            }
+            t = cfg_.release_when_short ? pick_victim() : kNoTensor;
+            if (t == kNoTensor) {
+                char msg[128];
+                snprintf(msg, sizeof msg, "allocation does not fit (%llu in use + %llu; budget %llu)",
+                         (unsigned long long)in_use_, (unsigned long long)incoming, (unsigned long long)cfg_.budget_bytes);
+                throw OutOfMemory{now_, wanted, msg};
+            }
+            release(t);
+        }
+    }
+
+    // ---- Algorithm 4
     void prefetch() {
-        for (uint32_t issued = 0; issued < P.max_reloads; ++issued) {
-            uint32_t head = nT, head_nr = kNever;
-            for (uint32_t t = 0; t < nT; ++t) {
-                if (!swapout[t] || resident[t]) continue;
-                uint32_t nr = next_read(t, k);
-                if (nr != kNever && (head == nT || nr < head_nr)) { head = t; head_nr = nr; }
-            }
-            if (head == nT) return;
-            if ((uint64_t)head_nr > (uint64_t)k + P.prefetch_distance) return;
-            if (live + T[head].bytes > P.budget_bytes) return;
-            emit(DELTA_EV_RELOAD_PREFETCH, head);
-            live += T[head].bytes;
-            if (live > peak) peak = live;
-            resident[head] = 1;
-        }
-    }
-
-    bool doubly_pinned(uint32_t t) const {
-        uint32_t f = T[t].flags;
-        return (f & (DELTA_F_EVICT_PINNED | DELTA_F_UNCOMPUTABLE)) && (f & DELTA_F_OFFLOAD_PINNED);
-    }
-
-    void step(uint32_t idx) {
-        k = idx;
-        const PlanStep &st = S[k];
-        const bool fwd = k < P.n_fwd_steps;
-        if (!fwd) prefetch();
-        for (uint32_t r : st.reads) locked[r] = 1;
-        if (st.produces >= 0) locked[st.produces] = 1;
-        for (uint32_t r : st.reads) {
-            if (!resident[r]) materialise(r);
-            if (failed) return;
-            provisional[r] = 0;
-        }
-        const uint64_t need = st.produces >= 0 ? T[st.produces].bytes : 0;
-        if (fwd) {
-            while ((u128)P.trigger_den * (live + need) > (u128)P.trigger_num * P.budget_bytes) {
-                uint32_t pv = farthest_provisional(false);
-                if (pv != nT) { drop(pv); continue; }
-                std::vector<uint32_t> cands;
-                for (uint32_t t = 0; t < nT; ++t)
-                    if (resident[t] && !locked[t] && !doubly_pinned(t) &&
-                        next_read(t, k + 1) != kNever)
-                        cands.push_back(t);
-                if (cands.empty()) {
-                    if (live + need <= P.budget_bytes) break;
-                    fail("nothing left to release", live, need);
-                    return;
+        for (uint32_t issued = 0; issued < cfg_.max_reloads; ++issued) {
+            uint32_t head = kNoTensor, head_use = kNoStep;
+            for (uint32_t t = 0; t < rec_.size(); ++t) {
+                const Record &r = rec_[t];
+                if (r.on_gpu || !r.host_copy) continue;
+                const uint32_t u = r.use_from_now();
+                if (u < head_use) {                      // kNoStep (never used again) is never below
+                    head = t;
+                    head_use = u;
                 }
-                uint32_t v = filter(cands);
-                uint32_t act = director(v);
-                emit(act, v);
-                live -= T[v].bytes;
-                resident[v] = 0;
-                swapout[v] = act == DELTA_EV_OFFLOAD ? 1 : 0;
             }
+            if (head == kNoTensor) return;
+            if ((uint64_t)head_use - now_ > cfg_.prefetch_distance) return;
+            if (in_use_ + rec_[head].memory > cfg_.budget_bytes) return;
+            note(DELTA_EV_RELOAD_PREFETCH, head);
+            occupy(rec_[head].memory);
+            rec_[head].on_gpu = true;
         }
-        if (st.produces >= 0) {
-            grow(need);
-            if (failed) return;
-            resident[st.produces] = 1;
-        }
-        tau += st.cost_ns;
-        std::vector<uint32_t> touched(st.reads);
-        if (st.produces >= 0) touched.push_back((uint32_t)st.produces);
-        std::sort(touched.begin(), touched.end());
-        touched.erase(std::unique(touched.begin(), touched.end()), touched.end());
-        for (uint32_t t : touched) last_access[t] = tau;
-        for (uint32_t t : touched) {
-            if (next_read(t, k + 1) == kNever) {
-                emit(DELTA_EV_FREE, t);
-                live -= T[t].bytes;
-                resident[t] = 0;
-                provisional[t] = 0;
-            }
-        }
-        for (uint32_t t : touched) locked[t] = 0;
     }
 };
 
@@ -276,19 +380,30 @@ struct Sim {
 delta_status run_plan(const std::vector<PlanTensor> &tensors, const std::vector<PlanStep> &steps,
                       const delta_plan_params &params, std::vector<delta_event> &events,
                       uint64_t &peak, std::string &err) {
-    Sim sim(tensors, steps, params);
-    for (uint32_t i = 0; i < steps.size(); ++i) {
-        sim.step(i);
-        if (sim.failed) {
-            err = sim.err;
-            events.swap(sim.ev);
-            peak = sim.peak;
+    std::vector<uint8_t> offload_only(tensors.size(), 0);
+    for (uint32_t round = 0;; ++round) {
+        Manager m(tensors, steps, params, offload_only);
+        try {
+            for (uint32_t k = 0; k < steps.size(); ++k) m.run_step(k);
+            events.swap(m.events);
+            peak = m.peak;
+            return DELTA_OK;
+        } catch (const OutOfMemory &oom) {
+            const uint32_t o = oom.operand;
+            const bool can_learn = o != kNoTensor && round < params.repair_rounds && !offload_only[o] &&
+                                   !(tensors[o].flags & DELTA_F_UNCOMPUTABLE);
+            if (can_learn) {
+                offload_only[o] = 1;
+                continue;
+            }
+            char head[32];
+            snprintf(head, sizeof head, "step %u: ", oom.step);
+            err = head + oom.what;
+            events.swap(m.events);
+            peak = m.peak;
             return DELTA_ERR_INFEASIBLE;
         }
     }
-    events.swap(sim.ev);
-    peak = sim.peak;
-    return DELTA_OK;
 }
 
 // Validates and copies the caller's graph.
@@ -301,7 +416,8 @@ delta_status load_graph(const delta_tensor_desc *tensors, uint32_t n_tensors,
         return DELTA_ERR_INVALID;
     }
     if (params->trigger_den == 0 || params->trigger_num > params->trigger_den ||
-        params->filter > DELTA_FILTER_GREEDY || params->n_fwd_steps > n_steps) {
+        params->filter > DELTA_FILTER_GREEDY || params->n_fwd_steps > n_steps ||
+        params->release_when_short > 1) {
         err = "bad plan parameters";
         return DELTA_ERR_INVALID;
     }
