@@ -127,6 +127,17 @@ typedef struct { uint32_t step, action, tensor, pad; } delta_event;
 /* Activation of a DELTA_OP_CONV layer (field `relu`). */
 enum { DELTA_ACT_NONE = 0, DELTA_ACT_RELU = 1, DELTA_ACT_GELU = 2 /* x/2 (1 + erf(x / sqrt 2)) */ };
 
+/* Field `fuse` of a DELTA_OP_CONV layer: the block kernel.  A layer with DELTA_FUSE_BLOCK is the first
+ * of an identity bottleneck whose three layers stand next to each other in the segment and run in ONE
+ * launch: [1x1, 256 -> 64, ReLU] [3x3, 64 -> 64, stride 1, pad 1, ReLU, x = the first layer's y]
+ * [1x1, 64 -> 256, ReLU, x = the second layer's y, res = the first layer's x], bf16, rows of at most 223
+ * pixels.  Only the first layer's x has to be resident: every output is regenerated from it, and an
+ * output whose layer carries DELTA_FUSE_NO_STORE is neither allocated nor written (at least one of
+ * the three must be stored).  The arithmetic does not depend on which outputs are stored, so what
+ * the block kernel produced it reproduces bit for bit; it does not reproduce the bits of the three
+ * per-layer launches, so a tensor must always be produced by the same of the two. */
+enum { DELTA_FUSE_NONE = 0, DELTA_FUSE_BLOCK = 1, DELTA_FUSE_NO_STORE = 2 };
+
 /* One layer.  DELTA_OP_CONV: y = act(scale_k * conv(x, w) + shift_k (+ res)), activations
  * NHWC, weights KRSC (w[k][r][s][c]), scale/shift fp32 per output channel (folded batch-norm
  * with frozen statistics; scale = 1, shift = bias for the classifier).  The pooling
@@ -161,6 +172,7 @@ typedef struct {
     uint32_t relu;             /* DELTA_ACT_* (convolution / linear layers) */
     uint32_t op;               /* DELTA_OP_* */
     float eps;                 /* DELTA_OP_LAYERNORM and DELTA_OP_BATCHNORM */
+    uint32_t fuse;             /* DELTA_FUSE_* bits (convolutions only; 0 everywhere else) */
 } delta_layer_desc;
 
 typedef struct {

@@ -11,4 +11,4 @@ from .binding import (Delta, DeltaError, LayerDesc, BwdDesc, load_library, plan,
                       EV_RELOAD_PREFETCH, EV_RELOAD_DEMAND, EV_FREE, EV_DROP_TEMP, DTYPE_F32,
                       DTYPE_BF16, SYNC_D2H, SYNC_H2D, SYNC_COMPUTE, SYNC_ALL, DIR_D2H, DIR_H2D,
                       DIR_BOTH, NO_TENSOR, EXPORTS, OP_CONV, OP_MAXPOOL, OP_AVGPOOL, OP_SOFTMAX_CE, OP_ATTENTION,
-                      OP_LAYERNORM, OP_BATCHNORM, OP_RELU, OP_ADD, ACT_NONE, ACT_RELU, ACT_GELU)
+                      OP_LAYERNORM, OP_BATCHNORM, OP_RELU, OP_ADD, ACT_NONE, ACT_RELU, ACT_GELU, FUSE_NONE, FUSE_BLOCK, FUSE_NO_STORE)

@@ -18,6 +18,7 @@ NO_TENSOR = 0xFFFFFFFF
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL, OP_SOFTMAX_CE, OP_ATTENTION, OP_LAYERNORM = 0, 1, 2, 3, 4, 5
 OP_BATCHNORM, OP_RELU, OP_ADD = 6, 7, 8
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+FUSE_NONE, FUSE_BLOCK, FUSE_NO_STORE = 0, 1, 2
 
 EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "delta_bind",
            "delta_alloc", "delta_tensor_ptr", "delta_release", "delta_swap_out", "delta_prefetch",
@@ -54,7 +55,8 @@ class LayerDesc(C.Structure):
                 ("w", C.c_void_p), ("scale", C.c_void_p), ("shift", C.c_void_p),
                 ("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("Cin", C.c_int32),
                 ("Cout", C.c_int32), ("R", C.c_int32), ("S", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("relu", C.c_uint32), ("op", C.c_uint32), ("eps", C.c_float)]
+                ("pad", C.c_int32), ("relu", C.c_uint32), ("op", C.c_uint32), ("eps", C.c_float),
+                ("fuse", C.c_uint32)]
 
 
 class BwdDesc(C.Structure):

@@ -718,17 +718,89 @@ static delta_status prepare_layer(delta_ctx *c, const delta_layer_desc &L, uint3
     return DELTA_OK;
 }
 
+// The three layers of an identity bottleneck that the block kernel runs in one launch (layers[i] carries
+// DELTA_FUSE_BLOCK).  Validates the chain and fills the launch arguments except device addresses.
+static delta_status prepare_block(delta_ctx *c, const delta_layer_desc *layers, uint32_t n_layers, uint32_t i,
+                                  delta::BlockArgs &b, uint64_t (&flops)[3]) {
+    if (i + 3 > n_layers) return fail(c, DELTA_ERR_INVALID, "layer %u: a fused block needs three layers", i);
+    const delta_layer_desc &L1 = layers[i], &L2 = layers[i + 1], &L3 = layers[i + 2];
+    delta::ConvArgs a;
+    delta::PoolArgs pa;
+    for (uint32_t j = 0; j < 3; ++j) {
+        const delta_layer_desc &L = layers[i + j];
+        if (L.op != DELTA_OP_CONV || L.dtype != DELTA_DTYPE_BF16)
+            return fail(c, DELTA_ERR_INVALID, "layer %u: the block kernel takes bf16 convolutions", i + j);
+        if (L.fuse & ~(uint32_t)(DELTA_FUSE_BLOCK | DELTA_FUSE_NO_STORE) || (j && (L.fuse & DELTA_FUSE_BLOCK)))
+            return fail(c, DELTA_ERR_INVALID, "layer %u: bad fuse flags %u", i + j, L.fuse);
+        delta_status r = prepare_layer(c, L, i + j, a, pa, flops[j]);
+        if (r != DELTA_OK) return r;
+    }
+    const bool geo = L1.R == 1 && L1.S == 1 && L1.stride == 1 && L1.pad == 0 && L1.Cin == 256 && L1.Cout == 64 &&
+                     L2.R == 3 && L2.S == 3 && L2.stride == 1 && L2.pad == 1 && L2.Cin == 64 && L2.Cout == 64 &&
+                     L3.R == 1 && L3.S == 1 && L3.stride == 1 && L3.pad == 0 && L3.Cin == 64 && L3.Cout == 256 &&
+                     L2.N == L1.N && L2.H == L1.H && L2.W == L1.W && L3.N == L1.N && L3.H == L1.H && L3.W == L1.W;
+    const bool chain = L2.x == L1.y && L3.x == L2.y && L3.res == L1.x && L1.res == DELTA_NO_TENSOR &&
+                       L2.res == DELTA_NO_TENSOR && L1.relu == DELTA_ACT_RELU && L2.relu == DELTA_ACT_RELU &&
+                       L3.relu == DELTA_ACT_RELU;
+    if (!geo || !chain)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: not an identity bottleneck the block kernel takes "
+                    "(1x1 256->64, 3x3 64->64 s1 p1, 1x1 64->256 + the block's input, ReLU after each)", i);
+    if (L1.y == L1.x || L2.y == L1.x || L3.y == L1.x || L1.y == L2.y || L1.y == L3.y || L2.y == L3.y)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: the block's tensors must be distinct", i);
+    if ((L1.fuse & L2.fuse & L3.fuse) & DELTA_FUSE_NO_STORE)
+        return fail(c, DELTA_ERR_INVALID, "layer %u: the block stores nothing", i);
+    memset(&b, 0, sizeof b);
+    b.N = L1.N; b.H = L1.H; b.W = L1.W;
+    b.M = (int)((long long)L1.N * L1.H * L1.W);
+    b.w1 = L1.w; b.w2 = L2.w; b.w3 = L3.w;
+    b.s1 = L1.scale; b.h1 = L1.shift; b.s2 = L2.scale; b.h2 = L2.shift; b.s3 = L3.scale; b.h3 = L3.shift;
+    b.x = c->arena;                                  // placeholders for the checks
+    b.out = c->arena;
+    const char *why = delta::bottleneck_block_check(b);
+    if (why) return fail(c, DELTA_ERR_INVALID, "layer %u: %s", i, why);
+    return DELTA_OK;
+}
+
+// Makes tensor `y` ready to be written on the compute stream: a fresh block, or its own one once
+// nobody else is still reading it.
+static delta_status claim_output(delta_ctx *c, Tensor &ty) {
+    delta_status r;
+    if (!ty.resident) {
+        if ((r = arena_alloc(c, ty.bytes, S_COMPUTE, &ty.offset)) != DELTA_OK) return r;
+        ty.resident = true;
+    } else {
+        if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
+        if (ty.d2h_done)                            // an Offload copy may still be reading it
+            HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.d2h_done.e, 0));
+        if (ty.aux_done)                            // and so may a weight gradient
+            HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.aux_done.e, 0));
+    }
+    ty.host_valid = false;                          // the host copy, if any, is of older contents
+    return DELTA_OK;
+}
+
 delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layers, uint32_t n_layers) {
     delta_status r = need_gpu(c);
     if (r != DELTA_OK) return r;
     if (!layers && n_layers) return fail(c, DELTA_ERR_INVALID, "null layers");
     delta::ConvArgs a;
     delta::PoolArgs pa;
-    uint64_t flops;
+    delta::BlockArgs blk;
+    uint64_t flops, bflops[3];
     // Pass 1: validate everything before anything is launched or allocated.
     std::vector<uint8_t> will_exist(c->tensors.size(), 0);
     for (uint32_t i = 0; i < n_layers; ++i) {
         const delta_layer_desc &L = layers[i];
+        if (L.op == DELTA_OP_CONV && (L.fuse & DELTA_FUSE_BLOCK)) {
+            if ((r = prepare_block(c, layers, n_layers, i, blk, bflops)) != DELTA_OK) return r;
+            if (!c->tensors[L.x].resident && !will_exist[L.x])
+                return fail(c, DELTA_ERR_STATE, "layer %u: input tensor %u is not resident", i, L.x);
+            for (uint32_t j = 0; j < 3; ++j)
+                if (!(layers[i + j].fuse & DELTA_FUSE_NO_STORE)) will_exist[layers[i + j].y] = 1;
+            i += 2;
+            continue;
+        }
+        if (L.fuse) return fail(c, DELTA_ERR_INVALID, "layer %u: fuse flags %u outside a fused block", i, L.fuse);
         if ((r = prepare_layer(c, L, i, a, pa, flops)) != DELTA_OK) return r;
         if (!c->tensors[L.x].resident && !will_exist[L.x])
             return fail(c, DELTA_ERR_STATE, "layer %u: input tensor %u is not resident", i, L.x);
@@ -739,22 +811,31 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
     // Pass 2: allocate outputs and launch, in order, on the compute stream.
     for (uint32_t i = 0; i < n_layers; ++i) {
         const delta_layer_desc &L = layers[i];
+        if (L.op == DELTA_OP_CONV && (L.fuse & DELTA_FUSE_BLOCK)) {
+            if ((r = prepare_block(c, layers, n_layers, i, blk, bflops)) != DELTA_OK) return r;
+            Tensor &tx = c->tensors[L.x];
+            if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
+            void *outp[3] = {nullptr, nullptr, nullptr};
+            for (uint32_t j = 0; j < 3; ++j) {
+                if (layers[i + j].fuse & DELTA_FUSE_NO_STORE) continue;
+                Tensor &ty = c->tensors[layers[i + j].y];
+                if ((r = claim_output(c, ty)) != DELTA_OK) return r;
+                outp[j] = c->arena + ty.offset;
+            }
+            blk.x = c->arena + tx.offset;
+            blk.a1 = outp[0]; blk.a2 = outp[1]; blk.out = outp[2];
+            HIP_TRY(c, delta::launch_bottleneck_block(blk, c->stream[S_COMPUTE]));
+            c->st.recompute_launches += 1;
+            c->st.recompute_flops += bflops[0] + ((outp[1] || outp[2]) ? bflops[1] : 0) + (outp[2] ? bflops[2] : 0);
+            i += 2;
+            continue;
+        }
         if ((r = prepare_layer(c, L, i, a, pa, flops)) != DELTA_OK) return r;
         Tensor &tx = c->tensors[L.x];
         Tensor &ty = c->tensors[L.y];
         if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
         if (L.res != DELTA_NO_TENSOR && (r = compute_uses(c, c->tensors[L.res])) != DELTA_OK) return r;
-        if (!ty.resident) {
-            if ((r = arena_alloc(c, ty.bytes, S_COMPUTE, &ty.offset)) != DELTA_OK) return r;
-            ty.resident = true;
-        } else {
-            if ((r = compute_uses(c, ty)) != DELTA_OK) return r;
-            if (ty.d2h_done)                        // an Offload copy may still be reading it
-                HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.d2h_done.e, 0));
-            if (ty.aux_done)                        // and so may a weight gradient
-                HIP_TRY(c, hipStreamWaitEvent(c->stream[S_COMPUTE], ty.aux_done.e, 0));
-        }
-        ty.host_valid = false;                      // the host copy, if any, is of older contents
+        if ((r = claim_output(c, ty)) != DELTA_OK) return r;
         unsigned char *xp = c->arena + tx.offset, *yp = c->arena + ty.offset;
         unsigned char *rp = L.res != DELTA_NO_TENSOR ? c->arena + c->tensors[L.res].offset : nullptr;
         switch (L.op) {

@@ -53,6 +53,18 @@ hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream);
 // conv3x3_halo.hip: bf16 3x3 stride-1 kernel that keeps the input halo of a pixel tile in LDS
 bool conv3x3_halo_applies(const ConvArgs &a);
 hipError_t launch_conv3x3_halo(const ConvArgs &a, hipStream_t stream);
+// bottleneck_block.hip: one identity bottleneck of conv2_x (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + x,
+// ReLU after each, bf16) in a single launch; a1 / a2 / out may each be null (not stored)
+struct BlockArgs {
+    const void *x;                       // [M, 256] block input, also the shortcut
+    void *a1, *a2, *out;                 // [M, 64], [M, 64], [M, 256]
+    const void *w1, *w2, *w3;            // [64][256], [64][3][3][64], [256][64]
+    const float *s1, *h1, *s2, *h2, *s3, *h3;   // folded batch-norm scale / shift of the three layers
+    int N, H, W, M;
+};
+const char *bottleneck_block_check(const BlockArgs &a);
+int bottleneck_block_tile(const BlockArgs &a);          // pixels per workgroup the launch will use
+hipError_t launch_bottleneck_block(const BlockArgs &a, hipStream_t stream);
 // attention.hip: fused multi-head self-attention, head dimension 64, bf16.  qkv [N,S,3*64*heads], ctx [N,S,64*heads]
 const char *attention_check(const void *qkv, const void *ctx, int N, int S, int heads, int bf16);
 hipError_t launch_attention(const void *qkv, void *ctx, int N, int S, int heads, int bf16, hipStream_t stream);

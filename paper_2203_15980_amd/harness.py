@@ -128,6 +128,16 @@ class Net:
     def recompute(self, name):
         self.delta.recompute_segment(self.desc[name])
 
+    def block_desc(self, prefix, store=None):
+        """The three layers `prefix`.a1 / .a2 / .out of an identity bottleneck as one launch of the
+        block kernel; `store`: the tensor names to write (default: all three)."""
+        names = [prefix + ".a1", prefix + ".a2", prefix + ".out"]
+        store = names if store is None else store
+        arr = B.layer_array([B.LayerDesc.from_buffer_copy(self.desc[n][0]) for n in names])
+        for i, n in enumerate(names):
+            arr[i].fuse = (B.FUSE_BLOCK if i == 0 else 0) | (0 if n in store else B.FUSE_NO_STORE)
+        return arr
+
     # -- backward pass
     def _is_stem(self, l):
         return l.kind == "conv" and l.R == 7 and l.Cin == 3

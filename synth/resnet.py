@@ -108,6 +108,16 @@ def bottleneck_stack(N, H, W, cin=64, mid=64, cout=256, nblocks=3):
     return layers
 
 
+def identity_block(N, H, W, cin=256, mid=64, prefix="blk"):
+    """One bottleneck with an identity shortcut on an input of `cin` channels (blocks 2 and 3 of
+    conv2_x): a1 (1x1), a2 (3x3), out (1x1 + x0)."""
+    layers: List[LayerSpec] = []
+    _bottleneck(layers, prefix, "x0", N, H, W, cin, mid, cin, 1, False)
+    for i, l in enumerate(layers):
+        l.index = i + 1
+    return layers
+
+
 def resnet_layers(N, depths=(3, 4, 6, 3), image=224, classes=1000):
     """Full ResNet-v1 (50: 3/4/6/3, 101: 3/4/23/3) as fused layers."""
     layers: List[LayerSpec] = []

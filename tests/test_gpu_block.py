@@ -1,0 +1,138 @@
+"""GPU parity of the block kernel (one identity bottleneck 1x1 -> 3x3 -> 1x1 + shortcut in a single
+launch, selected with DELTA_FUSE_BLOCK) against the CPU oracle's layer chain, through the C ABI.
+
+Bars: every stored tensor within 2e-2 (bf16) of the oracle's; whatever subset of {a1, a2, out} a
+launch stores, the stored tensors carry the same bits; a recomputation after a release (at
+another arena address) reproduces the forward bit for bit."""
+import itertools
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import numeric as on
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("blk.a1", "blk.a2", "blk.out")
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _net(torch, N, H, W, master=61, extra=4):
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    layers = synth.identity_block(N, H, W)
+    g = synth.fused_graph(layers, "bf16")
+    arena = torch.empty(extra * g.total_bytes() + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    return d, Net(d, layers, "bf16", master), layers
+
+
+def _rel(got, ref):
+    g, r = on.to_f64(got, "bf16"), on.to_f64(ref, "bf16")
+    return float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
+
+
+SHAPES = [(2, 7, 7), (1, 14, 14), (3, 9, 11), (1, 1, 1), (2, 3, 100), (1, 5, 223), (5, 56, 56)]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_block_kernel_matches_the_oracle_chain(torch_mod, shape):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    print("shape", shape, flush=True)
+    d, net, layers = _net(torch, *shape)
+    net.load_input()
+    ref = on.run_layers(layers, net.params_np, net.x0_np, "bf16")
+    d.recompute_segment(net.block_desc("blk"))
+    d.sync()
+    first = {n: net.read(n).copy() for n in NAMES}
+    for n in NAMES:
+        err = _rel(first[n], ref[n])
+        print("  %s err %.2e" % (n, err), flush=True)
+        assert err <= 2e-2, (shape, n, err)
+    # every subset of stored outputs: same bits; what is not stored is not allocated
+    for k in (1, 2):
+        for keep in itertools.combinations(NAMES, k):
+            for n in NAMES:
+                d.release(net.ids[n], dl.EV_EVICT)
+            filler = d.alloc(net.ids["blk.a1"]) if "blk.a1" not in keep else None     # shifts the addresses
+            if filler is not None:
+                d.release(net.ids["blk.a1"], dl.EV_FREE)
+            d.recompute_segment(net.block_desc("blk", store=keep))
+            d.sync()
+            for n in NAMES:
+                if n in keep:
+                    assert np.array_equal(net.read(n), first[n]), (shape, keep, n)
+                else:
+                    with pytest.raises(dl.DeltaError) as e:
+                        d.tensor_ptr(net.ids[n])
+                    assert e.value.status == dl.ERR_STATE
+            for n in keep:
+                d.release(net.ids[n], dl.EV_EVICT)
+            d.recompute_segment(net.block_desc("blk"))                               # all three back for the next round
+    d.sync()
+    st = d.stats()
+    assert st["recompute_launches"] == 1 + 2 * 6
+    d.close()
+
+
+def test_block_kernel_at_config2_size_on_sampled_images(torch_mod):
+    """The launch shape bench.py times (batch 32, 56 x 56: one workgroup of 392 pixels per CU);
+    the oracle computes the first and the last image (frozen statistics: images are independent)."""
+    torch = torch_mod
+    d, net, layers = _net(torch, 32, 56, 56, extra=2)
+    net.load_input()
+    d.recompute_segment(net.block_desc("blk"))
+    d.sync()
+    for img in (0, 31):
+        sub = synth.identity_block(1, 56, 56)
+        ref = on.run_layers(sub, net.params_np, net.x0_np[img:img + 1], "bf16")
+        for n in NAMES:
+            err = _rel(net.read(n)[img:img + 1], ref[n])
+            print("image %d %s err %.2e" % (img, n, err), flush=True)
+            assert err <= 2e-2, (img, n, err)
+    d.close()
+
+
+def test_block_kernel_refuses_what_it_does_not_take(torch_mod):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    d, net, layers = _net(torch, 1, 4, 224)                    # rows of 224 pixels: too wide for the LDS tile
+    net.load_input()
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(net.block_desc("blk"))
+    assert e.value.status == dl.ERR_INVALID and "223" in e.value.message
+    d.recompute_segment(net.all_layers)                        # the per-layer kernels take it
+    d.close()
+    d, net, layers = _net(torch, 2, 6, 6)
+    net.load_input()
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(net.block_desc("blk", store=()))
+    assert e.value.status == dl.ERR_INVALID
+    arr = net.block_desc("blk")
+    arr[2].res = dl.NO_TENSOR                                  # the shortcut is part of the block
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(arr)
+    assert e.value.status == dl.ERR_INVALID
+    arr = net.block_desc("blk")
+    with pytest.raises(dl.DeltaError) as e:                   # a block cut short
+        d.recompute_segment(arr, 2)
+    assert e.value.status == dl.ERR_INVALID
+    lone = dl.layer_array([dl.LayerDesc.from_buffer_copy(net.desc["blk.a1"][0])])
+    lone[0].fuse = dl.FUSE_NO_STORE                            # the flag means nothing outside a block
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(lone)
+    assert e.value.status == dl.ERR_INVALID
+    net.delta.release(0, dl.EV_FREE)
+    with pytest.raises(dl.DeltaError) as e:                   # the block's input must be resident
+        d.recompute_segment(net.block_desc("blk"))
+    assert e.value.status == dl.ERR_STATE
+    d.close()
