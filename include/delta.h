@@ -18,9 +18,10 @@
  *     pointers are ordinary process memory.  The caller owns every array it
  *     passes; the library copies what it keeps before the call returns.
  *   - The caller owns the device arena and the compute stream handed to
- *     delta_create().  The library owns the context, its two copy streams, its
- *     events, its pinned host buffers, and sub-allocates the arena: the arena
- *     size is the physical activation budget.
+ *     delta_create().  The library owns the context, its copy streams, its
+ *     events, its pinned host pool, and sub-allocates the arena: the arena
+ *     size is the physical budget (planned activations from its bottom upwards,
+ *     the backward pass's gradient tensors from its end downwards).
  *   - delta_swap_out, delta_prefetch, delta_release and delta_recompute_segment
  *     only enqueue work; delta_sync (and delta_destroy) block the host.
  *   - One context is used from one host thread at a time.
@@ -183,7 +184,9 @@ typedef struct {
     uint64_t recompute_launches, recompute_flops;
     uint64_t releases_evict, releases_offload, releases_free;
     uint64_t pinned_bytes;
-    uint64_t arena_extent_high_water;      /* highest arena offset ever handed out (fragmentation) */
+    uint64_t arena_extent_high_water;      /* highest arena offset handed to a tensor placed from the bottom (fragmentation) */
+    uint64_t arena_top_extent_high_water;  /* deepest reach, measured from the arena's end, of the tensors placed from
+                                              the top (the backward pass's gradient tensors) */
 } delta_stats_t;
 
 /* Creates a context on the current HIP device.  arena_dev: device, 256-byte aligned,
@@ -212,6 +215,11 @@ delta_status delta_plan(delta_ctx *ctx, const delta_tensor_desc *tensors, uint32
 /* Declares the run-time tensor table: n tensors with the given byte sizes, none resident.
  * Drops every tensor and host copy of a previous table (after waiting for the streams). */
 delta_status delta_bind(delta_ctx *ctx, const uint64_t *bytes, uint32_t n_tensors);
+/* The pinned host pool (Offload's destination, Sec. 4.2) grows by whole slabs and keeps them until
+ * delta_destroy; a tensor gets its host buffer from it at its first Offload.  This call makes sure that
+ * `bytes` more fit without a further allocation, so that a replay whose offloaded tensors add up to at
+ * most `bytes` never reaches hipHostMalloc.  delta_bind returns every buffer to the pool. */
+delta_status delta_reserve_pinned(delta_ctx *ctx, uint64_t bytes);
 /* Makes `tensor` resident in a fresh arena block without computing it (network input).
  * The block may be written on the compute stream right away. */
 delta_status delta_alloc(delta_ctx *ctx, uint32_t tensor, void **dev_out);

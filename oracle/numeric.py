@@ -257,10 +257,11 @@ def fc_bwd(x, w, gy, dtype="f32"):
     return gx, gw, to_f64(gy, dtype).reshape(-1, gy.shape[-1]).sum(axis=0)
 
 
-def run_layers(layers, params, x0, dtype, labels=None):
+def run_layers(layers, params, x0, dtype, labels=None, acts=None):
     """Forward of a list of synth.LayerSpec layers; returns {tensor name: stored array}.  With
-    `labels`, the mean cross-entropy of the last layer's output is added as "loss"."""
-    acts = {"x0": x0}
+    `labels`, the mean cross-entropy of the last layer's output is added as "loss".  `acts`
+    (instead of x0): stored tensors the layers may read, by name."""
+    acts = dict(acts) if acts is not None else {"x0": x0}
     for l in layers:
         if l.kind == "conv":
             acts[l.y] = conv_bn_act(acts[l.x], params[l.name]["w"], params[l.name],

@@ -26,7 +26,7 @@ EXPORTS = ["delta_create", "delta_destroy", "delta_last_error", "delta_plan", "d
            "delta_stats_reset", "delta_set_skip_copies", "delta_probe_hostlink",
            "delta_probe_hbm", "delta_probe_mfma", "delta_layer_kernel", "delta_bwd_weights",
            "delta_backward_workspace", "delta_backward_segment", "delta_backward_join",
-           "delta_batchnorm_static"]
+           "delta_batchnorm_static", "delta_reserve_pinned"]
 
 
 class TensorDesc(C.Structure):
@@ -72,7 +72,7 @@ class Stats(C.Structure):
                 ("recompute_launches", C.c_uint64), ("recompute_flops", C.c_uint64),
                 ("releases_evict", C.c_uint64), ("releases_offload", C.c_uint64),
                 ("releases_free", C.c_uint64), ("pinned_bytes", C.c_uint64),
-                ("arena_extent_high_water", C.c_uint64)]
+                ("arena_extent_high_water", C.c_uint64), ("arena_top_extent_high_water", C.c_uint64)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -133,6 +133,7 @@ def load_library():
         "delta_backward_segment": (i32, [vp, C.POINTER(BwdDesc), u32]),
         "delta_backward_join": (i32, [vp]),
         "delta_batchnorm_static": (i32, [vp, vp, vp, vp, vp, u64, u32, C.c_float]),
+        "delta_reserve_pinned": (i32, [vp, u64]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -236,6 +237,9 @@ class Delta:
     def bind(self, sizes):
         arr = (C.c_uint64 * len(sizes))(*[int(s) for s in sizes])
         self._check(self.lib.delta_bind(self.ctx, arr, len(sizes)))
+
+    def reserve_pinned(self, nbytes):
+        self._check(self.lib.delta_reserve_pinned(self.ctx, int(nbytes)))
 
     def alloc(self, tensor):
         p = C.c_void_p()

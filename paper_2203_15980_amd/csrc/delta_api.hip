@@ -77,6 +77,13 @@ struct Timed {
     int dir;
 };
 
+// One allocation of pinned host memory; tensors' host buffers are carved out of slabs in order.
+struct Slab {
+    unsigned char *base;
+    uint64_t size, used;
+};
+const uint64_t kSlabMin = 64ull << 20;
+
 }  // namespace
 
 // Scratch of delta_batchnorm_static, the entry point that allocates nothing: the partial sums and the
@@ -101,6 +108,7 @@ struct delta_ctx {
     std::map<uint64_t, Block> free_blocks;         // offset -> block, coalesced
     std::map<uint64_t, uint64_t> used;             // offset -> size
     std::vector<Tensor> tensors;
+    std::vector<Slab> slabs;                       // the pinned host pool: kept across delta_bind, freed by delta_destroy
     std::vector<hipEvent_t> ev_pool, ev_live;      // ordering events (no timing)
     std::vector<hipEvent_t> tev_pool;              // timing events
     std::vector<Timed> timed;
@@ -191,7 +199,8 @@ void retire_events(delta_ctx *c) {
         c->tensors[i].d2h_done = c->tensors[i].h2d_done = c->tensors[i].aux_done = Ev();
         c->tensors[i].d2h_piece.clear();
     }
-    c->aux_tail = Ev();
+    c->aux_tail = c->stg_tail = Ev();              // every stream is idle: nothing in flight uses the caller's workspace
+    c->aux_lo = c->aux_hi = c->stg_lo = c->stg_hi = 0;
     c->ev_pool.insert(c->ev_pool.end(), c->ev_live.begin(), c->ev_live.end());
     c->ev_live.clear();
 }
@@ -208,13 +217,18 @@ delta_status sync_all(delta_ctx *c) {
 
 Ev later(const Ev &a, const Ev &b) { return a.seq > b.seq ? a : b; }
 
-// Best fit among the blocks that cost the receiving stream the least waiting: first those nobody
-// else is still touching, then those whose youngest pending fence of another stream is oldest
-// (events are numbered in recording order, and the streams run in order, so an older fence
-// completes sooner; fences of the copy streams count as younger than any kernel's) - a block that an Offload copy or a weight gradient queued behind others is
-// still reading would stall the stream that receives it (the 1/4 of the budget that the early
-// start of Sec. 4.3 keeps free is what makes such a choice possible).
-delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t *off) {
+// Placement.  Two populations share the arena: the planned activations, which live long, and the
+// gradient tensors of the backward pass, which come and go.  Activations (top = false) are placed
+// from the bottom of the arena upwards, gradients (top = true) from its end downwards, so that the
+// two do not cut up each other's free space; with that an arena of the activation budget plus the
+// gradient peak is enough (the early start of Sec. 4.3 keeps a quarter of the budget free, which
+// is what leaves a choice at all).
+// Among the blocks that fit, the one that costs the receiving stream the least waiting is taken:
+// first those nobody else is still touching, then those whose youngest pending fence of another
+// stream is oldest (events are numbered in recording order and the streams run in order, so an
+// older fence completes sooner; a pending copy counts as younger than any kernel: the link is
+// three orders slower than HBM).  Ties: best fit, then the block nearest the population's own end.
+delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t *off, bool top = false) {
     const uint64_t need = (bytes + kAlign - 1) / kAlign * kAlign;
     std::map<uint64_t, Block>::iterator pick = c->free_blocks.end();
     uint64_t pick_wait = 0;
@@ -227,13 +241,13 @@ delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t 
             if (hipEventQuery(f.e) == hipSuccess) f = Ev();     // done: forget the fence
             else {
                 (void)hipGetLastError();                        // hipErrorNotReady is not an error here
-                // a pending copy outweighs any pending kernel: the link is three orders slower than HBM
                 const uint64_t w = f.seq + ((s == S_D2H || s == S_H2D) ? (1ull << 62) : 0ull);
                 if (w > wait) wait = w;
             }
         }
+        // the map runs bottom-up: for the bottom population the first of equals stays, for the top one the last
         if (pick == c->free_blocks.end() || wait < pick_wait ||
-            (wait == pick_wait && it->second.size < pick->second.size)) {
+            (wait == pick_wait && (it->second.size < pick->second.size || (top && it->second.size == pick->second.size)))) {
             pick = it;
             pick_wait = wait;
         }
@@ -245,20 +259,25 @@ delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t 
     const uint64_t o = pick->first;
     Block b = pick->second;
     c->free_blocks.erase(pick);
+    const uint64_t at = top ? o + b.size - need : o;             // the end of the block that faces the population's side
     if (b.size > need) {
         Block rest;
         rest.size = b.size - need;
         rest.fence = b.fence;
-        c->free_blocks[o + need] = rest;
+        c->free_blocks[top ? o : o + need] = rest;
     }
     for (int s = 0; s < N_STREAMS; ++s)
         if (s != for_stream && b.fence.ev[s])
             HIP_TRY(c, hipStreamWaitEvent(c->stream[for_stream], b.fence.ev[s].e, 0));
-    c->used[o] = need;
+    c->used[at] = need;
     c->st.arena_in_use += need;
     if (c->st.arena_in_use > c->st.arena_high_water) c->st.arena_high_water = c->st.arena_in_use;
-    if (o + need > c->st.arena_extent_high_water) c->st.arena_extent_high_water = o + need;
-    *off = o;
+    if (top) {
+        if (c->arena_bytes - at > c->st.arena_top_extent_high_water) c->st.arena_top_extent_high_water = c->arena_bytes - at;
+    } else if (at + need > c->st.arena_extent_high_water) {
+        c->st.arena_extent_high_water = at + need;
+    }
+    *off = at;
     return DELTA_OK;
 }
 
@@ -339,18 +358,48 @@ delta_status drop_block(delta_ctx *c, Tensor &t) {
     return DELTA_OK;
 }
 
+// Adds a slab of at least `bytes` to the pinned pool.
+delta_status pool_grow(delta_ctx *c, uint64_t bytes) {
+    Slab sl;
+    sl.size = bytes < kSlabMin ? kSlabMin : (bytes + kAlign - 1) / kAlign * kAlign;
+    sl.used = 0;
+    void *p = nullptr;
+    hipError_t e = hipHostMalloc(&p, sl.size, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(c, DELTA_ERR_OOM_PINNED, "hipHostMalloc(%llu) failed: %s", (unsigned long long)sl.size, hipGetErrorString(e));
+    }
+    sl.base = static_cast<unsigned char *>(p);
+    c->slabs.push_back(sl);
+    c->st.pinned_bytes += sl.size;
+    return DELTA_OK;
+}
+
+// A host buffer for tensor t from the pool (first slab with room; a new slab when none has: the
+// only place where a replay can still reach hipHostMalloc, and delta_reserve_pinned avoids it).
+delta_status pool_take(delta_ctx *c, Tensor &t) {
+    const uint64_t need = ((t.bytes ? t.bytes : 1) + kAlign - 1) / kAlign * kAlign;
+    for (int pass = 0; pass < 2; ++pass) {
+        for (size_t i = 0; i < c->slabs.size(); ++i) {
+            Slab &sl = c->slabs[i];
+            if (sl.size - sl.used >= need) {
+                t.host = sl.base + sl.used;
+                sl.used += need;
+                return DELTA_OK;
+            }
+        }
+        delta_status r = pool_grow(c, need);
+        if (r != DELTA_OK) return r;
+    }
+    return fail(c, DELTA_ERR_OOM_PINNED, "pinned pool: no room for %llu bytes", (unsigned long long)need);
+}
+
 delta_status swap_out_impl(delta_ctx *c, uint32_t id) {
     Tensor &t = c->tensors[id];
     if (!t.resident) return fail(c, DELTA_ERR_STATE, "swap_out: tensor %u is not resident", id);
     if (!t.host) {
-        hipError_t e = hipHostMalloc(&t.host, t.bytes ? t.bytes : 1, hipHostMallocDefault);
-        if (e != hipSuccess) {
-            t.host = nullptr;
-            (void)hipGetLastError();
-            return fail(c, DELTA_ERR_OOM_PINNED, "hipHostMalloc(%llu) failed: %s",
-                        (unsigned long long)t.bytes, hipGetErrorString(e));
-        }
-        c->st.pinned_bytes += t.bytes;
+        delta_status pr = pool_take(c, t);
+        if (pr != DELTA_OK) return pr;
     }
     Ev produced;
     delta_status r = new_event(c, c->stream[S_COMPUTE], &produced);
@@ -388,10 +437,17 @@ delta_status swap_out_impl(delta_ctx *c, uint32_t id) {
     return DELTA_OK;
 }
 
-void free_host_buffers(delta_ctx *c) {
-    for (size_t i = 0; i < c->tensors.size(); ++i)
-        if (c->tensors[i].host) (void)hipHostFree(c->tensors[i].host);
-    c->st.pinned_bytes = 0;
+// Forgets every tensor's host buffer; the slabs stay (delta_bind) or go (delta_destroy).
+void free_host_buffers(delta_ctx *c, bool slabs_too) {
+    for (size_t i = 0; i < c->tensors.size(); ++i) c->tensors[i].host = nullptr;
+    for (size_t i = 0; i < c->slabs.size(); ++i) {
+        c->slabs[i].used = 0;
+        if (slabs_too) (void)hipHostFree(c->slabs[i].base);
+    }
+    if (slabs_too) {
+        c->slabs.clear();
+        c->st.pinned_bytes = 0;
+    }
 }
 
 }  // namespace
@@ -440,7 +496,7 @@ void delta_destroy(delta_ctx *c) {
     if (!c) return;
     if (c->arena) {
         for (int s = 0; s < N_STREAMS; ++s) (void)hipStreamSynchronize(c->stream[s]);
-        free_host_buffers(c);
+        free_host_buffers(c, true);
         for (size_t i = 0; i < c->ev_live.size(); ++i) (void)hipEventDestroy(c->ev_live[i]);
         for (size_t i = 0; i < c->ev_pool.size(); ++i) (void)hipEventDestroy(c->ev_pool[i]);
         for (size_t i = 0; i < c->tev_pool.size(); ++i) (void)hipEventDestroy(c->tev_pool[i]);
@@ -487,7 +543,7 @@ delta_status delta_bind(delta_ctx *c, const uint64_t *bytes, uint32_t n) {
     if (r != DELTA_OK) return r;
     if (!bytes && n) return fail(c, DELTA_ERR_INVALID, "null sizes");
     if ((r = sync_all(c)) != DELTA_OK) return r;
-    free_host_buffers(c);
+    free_host_buffers(c, false);
     c->tensors.assign(n, Tensor());
     for (uint32_t i = 0; i < n; ++i) c->tensors[i].bytes = bytes[i];
     c->free_blocks.clear();
@@ -497,6 +553,15 @@ delta_status delta_bind(delta_ctx *c, const uint64_t *bytes, uint32_t n) {
     c->free_blocks[0] = b;
     c->st.arena_in_use = 0;
     return DELTA_OK;
+}
+
+delta_status delta_reserve_pinned(delta_ctx *c, uint64_t bytes) {
+    delta_status r = need_gpu(c);
+    if (r != DELTA_OK) return r;
+    uint64_t room = 0;
+    for (size_t i = 0; i < c->slabs.size(); ++i) room += c->slabs[i].size - c->slabs[i].used;
+    // every tensor's buffer is rounded up to 256 bytes and must lie within one slab: one slab for the shortfall
+    return room >= bytes ? DELTA_OK : pool_grow(c, bytes - room + kAlign * (uint64_t)c->tensors.size());
 }
 
 delta_status delta_alloc(delta_ctx *c, uint32_t id, void **dev_out) {
@@ -953,6 +1018,7 @@ delta_status delta_stats_reset(delta_ctx *c) {
     memset(&c->st, 0, sizeof c->st);
     c->st.arena_bytes = ab;
     c->st.arena_in_use = c->st.arena_high_water = iu;
+    // what is resident now counts towards the bottom population's extent (a replay starts from an empty arena)
     for (std::map<uint64_t, uint64_t>::iterator u = c->used.begin(); u != c->used.end(); ++u)
         if (u->first + u->second > c->st.arena_extent_high_water) c->st.arena_extent_high_water = u->first + u->second;
     c->st.pinned_bytes = pb;
@@ -1283,7 +1349,7 @@ delta_status prepare_backward(delta_ctx *c, const delta_bwd_desc &D, uint32_t i,
 delta_status compute_writes(delta_ctx *c, Tensor &t) {
     delta_status r;
     if (!t.resident) {
-        if ((r = arena_alloc(c, t.bytes, S_COMPUTE, &t.offset)) != DELTA_OK) return r;
+        if ((r = arena_alloc(c, t.bytes, S_COMPUTE, &t.offset, /*top=*/true)) != DELTA_OK) return r;   // a gradient tensor
         t.resident = true;
     } else {
         if ((r = compute_uses(c, t)) != DELTA_OK) return r;

@@ -219,19 +219,70 @@ def test_config3_full_size_sampled_image(torch_mod):
     d.close()
 
 
-def test_resnet50_training_step_replay_repeats_its_gradients_bit_for_bit(torch_mod):
-    """ResNet-50 (config 3's graph at batch 16) as a whole training step: unconstrained once, then
-    five replays of the plan for 40 % of the activation bytes in an arena with no room to spare
-    (1.25 x the budget + the gradient tensors), with swaps on both copy streams, recomputation,
-    the true backward and the weight gradients on their own stream.  Recomputation returns the
-    forward's bits and every reduction has a fixed order, so every parameter gradient of every
-    replay must equal the unconstrained step's bit for bit; any missing fence between the four
-    streams shows up as a difference."""
+def test_config4_full_size_sampled_image(torch_mod):
+    """Config 4 at full size (ResNet-101, batch 256, 224x224x3: the launch shapes of bench.py's
+    40 % replay).  Frozen statistics make images independent, so the oracle works on the first
+    image alone.  Every layer is checked on its own: the oracle gets the GPU's stored input (and
+    shortcut) of that image and must agree with the GPU's stored output within the per-tensor bar.
+    (The oracle's own chain drifts from the GPU's over a hundred layers of bf16 storage rounding;
+    that end-to-end distance is printed, not asserted: it is no statement about any one kernel.)"""
+    from paper_2203_15980_amd.harness import Net
+    torch = torch_mod
+    N, depths = 256, (3, 4, 23, 3)
+    layers = synth.resnet_layers(N, depths)
+    g = synth.fused_graph(layers, "bf16", with_loss=True)
+    d = make_delta(torch, g.total_bytes() + (64 << 20))
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", synth.master_seed(4), with_loss=True)
+    net.forward()
+    d.sync()
+    one = synth.resnet_layers(1, depths)
+    print("oracle on one 224x224 image, 101 layers, each on the GPU's own input ...", flush=True)
+    gpu = {"x0": np.ascontiguousarray(net.x0_np[0:1])}
+    for l in layers:
+        gpu[l.y] = np.ascontiguousarray(net.read(l.y)[0:1])
+    chain = {"x0": gpu["x0"]}
+    worst = drift = 0.0
+    for l in one:
+        for acts, own in ((gpu, True), (chain, False)):
+            ref = on.run_layers([l], net.params_np, None, "bf16", acts={k: acts[k] for k in (l.x, l.res) if k})[l.y]
+            if own:
+                e = rel_err(gpu[l.y], ref, "bf16")
+                worst = max(worst, e)
+                assert e <= 2e-2, (l.y, e)
+            else:
+                chain[l.y] = ref
+                drift = max(drift, rel_err(gpu[l.y], ref, "bf16"))
+    print("worst layer error %.3g; worst distance to the oracle's own chain %.3g" % (worst, drift), flush=True)
+    d.close()
+
+
+REPLAYS = [
+    # name                      batch  depths         budget                reps  arena = a x budget + g x gradient peak
+    ("resnet50_b16_40pct",         16, (3, 4, 6, 3),  ("frac", 0.4),         5,   (1.10, 1.0)),
+    ("config3_b128_50pct",        128, (3, 4, 6, 3),  ("frac", 0.5),         2,   (1.10, 1.0)),   # the replay bench.py times
+    ("config4_b256_40pct",        256, (3, 4, 23, 3), ("frac", 0.4),         1,   (1.10, 1.0)),   # ResNet-101, as bench.py times it
+    # near the largest plannable batch: single tensors of up to 29 % of the budget, whose holes no
+    # 10 % allowance absorbs (the arena cannot compact): the allowance bench.py gives this replay
+    ("max_batch_b384_2GiB",       384, (3, 4, 6, 3),  ("bytes", 2 << 30),    1,   (1.25, 1.5)),
+]
+
+
+@pytest.mark.parametrize("case", REPLAYS, ids=[c[0] for c in REPLAYS])
+def test_training_step_replay_repeats_its_gradients_bit_for_bit(torch_mod, case):
+    """A whole ResNet training step: unconstrained once, then replays of the plan for the given
+    activation budget in an arena that IS the physical budget - 1.10 x the planned activation bytes
+    (the allowance for fragmentation) plus the gradient tensors' peak, one case aside - with swaps on both copy
+    streams, recomputation, the true backward and the weight gradients on their own stream.
+    Recomputation returns the forward's bits and every reduction has a fixed order, so every
+    parameter gradient of every replay must equal the unconstrained step's bit for bit; a missing
+    fence between the four streams, or a block handed out twice, shows up as a difference."""
     import paper_2203_15980_amd as dl
     from paper_2203_15980_amd.harness import Net, run_plan
     torch = torch_mod
-    N = 16
-    layers = synth.resnet_layers(N)
+    name, N, depths, (how, amount), reps, (act_mult, grad_mult) = case
+    print("case", name, flush=True)
+    layers = synth.resnet_layers(N, depths)
     g = synth.fused_graph(layers, "bf16", with_loss=True)
     boot = make_delta(torch, 1 << 20)
     boot.bind([t["bytes"] for t in g.tensors])
@@ -245,25 +296,36 @@ def test_resnet50_training_step_replay_repeats_its_gradients_bit_for_bit(torch_m
     ev0, _ = dl.plan(g.tensors, g.steps, p0)
     run_plan(net, g, ev0, backward_proxy=lambda k: net.backward_step(g, k))
     d.sync()
-    assert d.stats()["arena_in_use"] == 0
+    st0 = d.stats()
+    assert st0["arena_in_use"] == 0
     want = {n: t.clone() for n, t in net.gw.items()}
     assert all(torch.isfinite(t).all() and t.abs().max() > 0 for t in want.values())
     d.close()
-    budget = int(g.total_bytes() * 0.4)
-    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9)
+    del d
+    torch.cuda.empty_cache()
+    budget = int(g.total_bytes() * amount) if how == "frac" else amount
+    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9, repair_rounds=8)
     ev, peak = dl.plan(g.tensors, g.steps, p)
     kinds = {a for (_, a, _) in ev}
-    print("events", sorted(kinds), "peak", peak, "budget", budget, flush=True)
-    assert dl.EV_RECOMPUTE in kinds and dl.EV_OFFLOAD in kinds
-    d = make_delta(torch, budget + budget // 4 + grad_peak + grad_peak // 2 + (8 << 20))
+    arena_bytes = (int(act_mult * budget) + int(grad_mult * grad_peak) + 255) // 256 * 256
+    print("events", sorted(kinds), "peak", peak, "budget", budget, "arena", arena_bytes, flush=True)
+    assert dl.EV_RECOMPUTE in kinds and peak <= budget
+    d = make_delta(torch, arena_bytes)
     net.rebind(d)
-    for rep in range(5):
+    d.reserve_pinned(sum(g.tensors[t]["bytes"] for t in {t for (_, a, t) in ev if a == dl.EV_OFFLOAD}))
+    pinned = d.stats()["pinned_bytes"]
+    for rep in range(reps):
         for t in net.gw.values():
             t.fill_(float("nan"))
         run_plan(net, g, ev, backward_proxy=lambda k: net.backward_step(g, k))
         d.sync()
         st = d.stats()
-        assert st["arena_in_use"] == 0 and st["d2h_copies"] > 0
+        assert st["arena_in_use"] == 0
+        assert st["pinned_bytes"] == pinned            # the replay never reached hipHostMalloc
+        if dl.EV_OFFLOAD in kinds:
+            assert st["d2h_copies"] > 0
         for n, t in net.gw.items():
             assert torch.equal(t.view(torch.int32), want[n].view(torch.int32)), (rep, n)
+    print("arena %.3f GB against %.3f GB in use at the unconstrained step's peak: %.3f" %
+          (arena_bytes / 1e9, st0["arena_high_water"] / 1e9, arena_bytes / st0["arena_high_water"]), flush=True)
     d.close()
