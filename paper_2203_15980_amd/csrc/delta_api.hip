@@ -20,6 +20,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <map>
 #include <new>
 #include <string>
@@ -58,6 +59,12 @@ struct Fence {
 struct Block {
     uint64_t size;
     Fence fence;
+};
+
+// A freed block that stays out of the free list for a while (see arena_free).
+struct Resting {
+    uint64_t offset, order;         // order: its place in the sequence of all frees
+    Block block;
 };
 
 struct Tensor {
@@ -106,6 +113,9 @@ struct delta_ctx {
     Ev stg_tail;                                   // last launch on S_AUX that used a staging range, and that range
     uintptr_t stg_lo = 0, stg_hi = 0;
     std::map<uint64_t, Block> free_blocks;         // offset -> block, coalesced
+    std::deque<Resting> cooling;                   // freed blocks the weight-gradient stream may still read, oldest first
+    std::deque<Resting> copying;                   // freed blocks a copy may still touch, oldest first
+    uint64_t free_seq = 0;                         // blocks freed so far
     std::map<uint64_t, uint64_t> used;             // offset -> size
     std::vector<Tensor> tensors;
     std::vector<Slab> slabs;                       // the pinned host pool: kept across delta_bind, freed by delta_destroy
@@ -191,8 +201,12 @@ delta_status harvest_timings(delta_ctx *c) {
     return DELTA_OK;
 }
 
+void flush_cooling(delta_ctx *c);
+
 // After all streams are idle every fence is satisfied: recycle the events.
 void retire_events(delta_ctx *c) {
+    for (size_t i = 0; i < c->cooling.size(); ++i) c->cooling[i].block.fence = Fence();
+    for (size_t i = 0; i < c->copying.size(); ++i) c->copying[i].block.fence = Fence();
     for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it)
         it->second.fence = Fence();
     for (size_t i = 0; i < c->tensors.size(); ++i) {
@@ -210,6 +224,7 @@ delta_status sync_all(delta_ctx *c) {
     delta_status r = harvest_timings(c);
     if (r != DELTA_OK) return r;
     retire_events(c);
+    flush_cooling(c);                              // nothing is in flight: resting blocks rejoin the free list
     return DELTA_OK;
 }
 
@@ -220,37 +235,79 @@ Ev later(const Ev &a, const Ev &b) { return a.seq > b.seq ? a : b; }
 // Placement.  Two populations share the arena: the planned activations, which live long, and the
 // gradient tensors of the backward pass, which come and go.  Activations (top = false) are placed
 // from the bottom of the arena upwards, gradients (top = true) from its end downwards, so that the
-// two do not cut up each other's free space; with that an arena of the activation budget plus the
-// gradient peak is enough (the early start of Sec. 4.3 keeps a quarter of the budget free, which
-// is what leaves a choice at all).
-// Among the blocks that fit, the one that costs the receiving stream the least waiting is taken:
-// first those nobody else is still touching, then those whose youngest pending fence of another
-// stream is oldest (events are numbered in recording order and the streams run in order, so an
-// older fence completes sooner; a pending copy counts as younger than any kernel: the link is
-// three orders slower than HBM).  Ties: best fit, then the block nearest the population's own end.
+// two do not cut up each other's free space; with that an arena of little more than the activation
+// budget plus the gradient peak is enough (the early start of Sec. 4.3 keeps a quarter of the
+// budget free, which is what leaves a choice at all).  Best fit; among equals the block nearest
+// the population's own end.
+// A freed block that a copy or a weight gradient of another stream may still be touching would
+// stall the stream that receives it.  Such blocks rest outside the free list first: one that a
+// weight gradient reads, in a short queue (kCooling blocks, in order of release), by which time
+// that stream has usually passed it; one that an Offload or Reload copy still touches - the link
+// is three orders slower than HBM - until nothing else fits.  When nothing in the free list fits,
+// the blocks that rest rejoin it one by one, the longest-resting first, until something fits, so
+// the arena never fails while a fitting block exists (at the price of some fragmentation: resting
+// blocks do not merge with their neighbours).  Which block a tensor gets depends on the order of
+// calls only, never on timing: a replay that fits once fits every time.
+const size_t kCooling = 4;
+
+void insert_free(delta_ctx *c, uint64_t off, Block b) {
+    // Fences that have completed by now are dropped before they can spread to the neighbours the block
+    // merges with (this only spares later waits; it has no part in where anything is placed).
+    for (int s = 0; s < N_STREAMS; ++s)
+        if (b.fence.ev[s] && s != S_COMPUTE) {
+            if (hipEventQuery(b.fence.ev[s].e) == hipSuccess) b.fence.ev[s] = Ev();
+            else (void)hipGetLastError();                       // hipErrorNotReady is not an error here
+        }
+    uint64_t o = off;
+    std::map<uint64_t, Block>::iterator nx = c->free_blocks.lower_bound(off);   // first block above
+    if (nx != c->free_blocks.begin()) {
+        std::map<uint64_t, Block>::iterator pv = nx;
+        --pv;
+        if (pv->first + pv->second.size == off) {                               // merge downwards
+            o = pv->first;
+            b.size += pv->second.size;
+            for (int s = 0; s < N_STREAMS; ++s) b.fence.ev[s] = later(pv->second.fence.ev[s], b.fence.ev[s]);
+            c->free_blocks.erase(pv);
+        }
+    }
+    if (nx != c->free_blocks.end() && o + b.size == nx->first) {                // merge upwards
+        b.size += nx->second.size;
+        for (int s = 0; s < N_STREAMS; ++s) b.fence.ev[s] = later(nx->second.fence.ev[s], b.fence.ev[s]);
+        c->free_blocks.erase(nx);
+    }
+    c->free_blocks[o] = b;
+}
+
+// The streams are drained: nothing needs to rest any more.
+void flush_cooling(delta_ctx *c) {
+    for (size_t i = 0; i < c->cooling.size(); ++i) insert_free(c, c->cooling[i].offset, c->cooling[i].block);
+    c->cooling.clear();
+    for (size_t i = 0; i < c->copying.size(); ++i) insert_free(c, c->copying[i].offset, c->copying[i].block);
+    c->copying.clear();
+}
+
+// The block that has rested longest joins the free list; false when nothing rests.
+bool wake_oldest(delta_ctx *c) {
+    const bool a = !c->cooling.empty(), b = !c->copying.empty();
+    if (!a && !b) return false;
+    std::deque<Resting> &q = (a && (!b || c->cooling.front().order < c->copying.front().order)) ? c->cooling : c->copying;
+    insert_free(c, q.front().offset, q.front().block);
+    q.pop_front();
+    return true;
+}
+
 delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t *off, bool top = false) {
     const uint64_t need = (bytes + kAlign - 1) / kAlign * kAlign;
     std::map<uint64_t, Block>::iterator pick = c->free_blocks.end();
-    uint64_t pick_wait = 0;
-    for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it) {
-        if (it->second.size < need) continue;
-        uint64_t wait = 0;                                      // recording number of the youngest foreign fence still pending
-        for (int s = 0; s < N_STREAMS; ++s) {
-            Ev &f = it->second.fence.ev[s];
-            if (s == for_stream || !f) continue;
-            if (hipEventQuery(f.e) == hipSuccess) f = Ev();     // done: forget the fence
-            else {
-                (void)hipGetLastError();                        // hipErrorNotReady is not an error here
-                const uint64_t w = f.seq + ((s == S_D2H || s == S_H2D) ? (1ull << 62) : 0ull);
-                if (w > wait) wait = w;
-            }
-        }
+    for (;;) {
         // the map runs bottom-up: for the bottom population the first of equals stays, for the top one the last
-        if (pick == c->free_blocks.end() || wait < pick_wait ||
-            (wait == pick_wait && (it->second.size < pick->second.size || (top && it->second.size == pick->second.size)))) {
-            pick = it;
-            pick_wait = wait;
+        for (std::map<uint64_t, Block>::iterator it = c->free_blocks.begin(); it != c->free_blocks.end(); ++it) {
+            if (it->second.size < need) continue;
+            if (pick == c->free_blocks.end() || it->second.size < pick->second.size ||
+                (top && it->second.size == pick->second.size))
+                pick = it;
         }
+        if (pick != c->free_blocks.end() || !wake_oldest(c)) break;   // nothing fits: the longest-resting block returns
     }
     if (pick == c->free_blocks.end())
         return fail(c, DELTA_ERR_OOM_ARENA, "no arena block of %llu bytes (in use %llu of %llu)",
@@ -284,29 +341,24 @@ delta_status arena_alloc(delta_ctx *c, uint64_t bytes, int for_stream, uint64_t 
 void arena_free(delta_ctx *c, uint64_t off, const Fence &f) {
     std::map<uint64_t, uint64_t>::iterator u = c->used.find(off);
     if (u == c->used.end()) return;
-    Block b;
-    b.size = u->second;
-    b.fence = f;
-    c->st.arena_in_use -= b.size;
+    Resting r;
+    r.offset = off;
+    r.block.size = u->second;
+    r.block.fence = f;
+    r.order = ++c->free_seq;
+    c->st.arena_in_use -= r.block.size;
     c->used.erase(u);
-    uint64_t o = off;
-    std::map<uint64_t, Block>::iterator nx = c->free_blocks.lower_bound(off);   // first block above
-    if (nx != c->free_blocks.begin()) {
-        std::map<uint64_t, Block>::iterator pv = nx;
-        --pv;
-        if (pv->first + pv->second.size == off) {                               // merge downwards
-            o = pv->first;
-            b.size += pv->second.size;
-            for (int s = 0; s < N_STREAMS; ++s) b.fence.ev[s] = later(pv->second.fence.ev[s], b.fence.ev[s]);
-            c->free_blocks.erase(pv);
+    if (f.ev[S_D2H] || f.ev[S_H2D]) {                           // a copy may still be at it: rest until needed
+        c->copying.push_back(r);
+    } else if (f.ev[S_AUX]) {                                    // a weight gradient may still read it: rest a while
+        c->cooling.push_back(r);
+        if (c->cooling.size() > kCooling) {
+            insert_free(c, c->cooling.front().offset, c->cooling.front().block);
+            c->cooling.pop_front();
         }
+    } else {
+        insert_free(c, off, r.block);
     }
-    if (nx != c->free_blocks.end() && o + b.size == nx->first) {                // merge upwards
-        b.size += nx->second.size;
-        for (int s = 0; s < N_STREAMS; ++s) b.fence.ev[s] = later(nx->second.fence.ev[s], b.fence.ev[s]);
-        c->free_blocks.erase(nx);
-    }
-    c->free_blocks[o] = b;
 }
 
 // Device address of the file-scope scratch array on the context's GPU, resolved once per device.
@@ -548,6 +600,8 @@ delta_status delta_bind(delta_ctx *c, const uint64_t *bytes, uint32_t n) {
     for (uint32_t i = 0; i < n; ++i) c->tensors[i].bytes = bytes[i];
     c->free_blocks.clear();
     c->used.clear();
+    c->cooling.clear();
+    c->copying.clear();
     Block b;
     b.size = c->arena_bytes;
     c->free_blocks[0] = b;

@@ -326,6 +326,11 @@ def test_bottleneck_stack_backward_layer_by_layer_and_end_to_end(torch_mod, fuse
     got = on.to_f64(net.read(last[3]), "bf16")
     err = float(np.max(np.abs(got - grads["x0"])) / np.max(np.abs(grads["x0"])))
     print("  end to end dL/dx0 err %.2e" % err, flush=True)
+    # Not the per-tensor parity bar (that is the 2e-2 asserted layer by layer above, each layer on
+    # the GPU's own inputs): here the oracle walks its OWN chain, ten stored activations and ten
+    # stored gradients deep, each rounded to bf16 independently of the GPU's (up to 2^-9 of the
+    # tensor's maximum per rounding: 20 x 2^-9 = 3.9e-2), and ReLU masks taken on those
+    # independently rounded activations may differ at activations next to zero.  5e-2 bounds that drift.
     assert err <= 5e-2, err
     d.close()
 

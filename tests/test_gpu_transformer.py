@@ -212,7 +212,7 @@ def test_encoder_layers_through_the_harness(torch_mod):
         out = ot.encoder_layer(x, synth.make_encoder_params(71, i, H, FF, "bf16", heads), heads, synth.LN_EPS, "bf16")
         for k, v in out.items():                              # the harness and the oracle drew the same parameters
             err = _relerr(ot.to_f64(acts["l%d.%s" % (i, k)], "bf16"), ot.to_f64(v, "bf16"))
-            assert err <= 5e-2, (i, k, err)
+            assert err <= 2e-2, (i, k, err)
         x = out["ln2"].reshape(N, S, H)
     print("  end to end err %.2e" % err, flush=True)
     d.close()
