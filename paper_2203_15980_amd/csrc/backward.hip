@@ -216,11 +216,21 @@ struct WgradArgs {
                                  // zeros past the image (XH = H, XW = W, xstep = 1, offsets 0: x as it is)
 };
 
+// Which way the 64-byte groups of LDS row `row` are permuted (see wgrad_kernel): rows of 128 bytes lie two to
+// a 256-byte bank line, so the line's half already separates neighbours and bit 1 of the row number flips
+// the group; wider rows start a bank line each and the low two bits of the row number flip it.
+template <int TW>
+__device__ __forceinline__ int lds_swizzle(int row) { return TW == 1 ? (row >> 1) & 1 : row & 3; }
+
 // KTW x CTW tiles of 64 x 64 [k, c] per workgroup and tap; TAPS = R * R, or fewer: the taps tapwin lists.
 template <int KTW, int CTW, int TAPS>
 __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs a) {
     constexpr int NW = KTW * CTW * TAPS, NT = NW * 64;
-    constexpr int GP = KTW * 128 + 16, XP = CTW * 128 + 16;     // LDS row pitches (bytes)
+    // LDS rows without padding; the 64-byte groups of a row are permuted by the row number instead
+    // (group ^ swizzle(row)), so that the four consecutive rows a transposing read touches at one
+    // column lie in four different quarters of the 64 banks (with padded rows of 144 / 272 bytes half
+    // of the LDS-active cycles of this kernel were bank conflicts)
+    constexpr int GP = KTW * 128, XP = CTW * 128;               // LDS row pitches (bytes)
     constexpr int GSEG = KTW * 8, XSEG = CTW * 8;               // 16-byte segments per row
     constexpr int MAXL = NT >= 512 ? 4 : 8;                      // staged 16-byte pieces per thread, each operand
     extern __shared__ __align__(16) unsigned char smem[];
@@ -302,8 +312,14 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
 #pragma unroll
         for (int p = 0; p < MAXL; ++p) {
             const int idx = tid + p * NT;
-            if (g_row[p] != -2) *reinterpret_cast<u32x4 *>(gs + (idx / GSEG) * GP + (idx % GSEG) * 16) = rg[p];
-            if (x_row[p] > -1000) *reinterpret_cast<u32x4 *>(xs + (idx / XSEG) * XP + (idx % XSEG) * 16) = rx[p];
+            if (g_row[p] != -2) {
+                const int row = idx / GSEG, seg = idx % GSEG;
+                *reinterpret_cast<u32x4 *>(gs + row * GP + (((seg >> 2) ^ lds_swizzle<KTW>(row)) << 6) + (seg & 3) * 16) = rg[p];
+            }
+            if (x_row[p] > -1000) {
+                const int row = idx / XSEG, seg = idx % XSEG;
+                *reinterpret_cast<u32x4 *>(xs + row * XP + (((seg >> 2) ^ lds_swizzle<CTW>(row)) << 6) + (seg & 3) * 16) = rx[p];
+            }
         }
     };
 
@@ -313,8 +329,17 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
     const int srow = (lane & 15) >> 2;
     const int scol = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
     const int kgrp = lane >> 5;
-    const unsigned char *gbase = gs + (size_t)(8 * kgrp + srow) * GP + (kw * 64 + scol) * 2;
-    const unsigned char *xbase = xs + (size_t)(8 * kgrp + srow + tapoff) * XP + (cw * 64 + scol) * 2;
+    // the rows a lane reads are its first row plus multiples of 4 (q0 and the second half of a step), so the
+    // swizzle of all of them is that of the first; the two 32-channel halves t of the tile are groups 2 w + t
+    const int grow = 8 * kgrp + srow, xrow = 8 * kgrp + srow + tapoff;
+    const unsigned char *gbase = gs + (size_t)grow * GP + scol * 2;
+    const unsigned char *xbase = xs + (size_t)xrow * XP + scol * 2;
+    int goff[2], xoff[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        goff[t] = ((kw * 2 + t) ^ lds_swizzle<KTW>(grow)) << 6;
+        xoff[t] = ((cw * 2 + t) ^ lds_swizzle<CTW>(xrow)) << 6;
+    }
     typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
     auto tr_read = [&](const unsigned char *p) {
         return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
@@ -331,11 +356,11 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
             s16x8 af[2], bf[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const s16x4 a0 = tr_read(gbase + (size_t)q0 * GP + t * 64);
-                const s16x4 a1 = tr_read(gbase + (size_t)(q0 + 4) * GP + t * 64);
+                const s16x4 a0 = tr_read(gbase + (size_t)q0 * GP + goff[t]);
+                const s16x4 a1 = tr_read(gbase + (size_t)(q0 + 4) * GP + goff[t]);
                 af[t] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-                const s16x4 b0 = tr_read(xbase + (size_t)q0 * XP + t * 64);
-                const s16x4 b1 = tr_read(xbase + (size_t)(q0 + 4) * XP + t * 64);
+                const s16x4 b0 = tr_read(xbase + (size_t)q0 * XP + xoff[t]);
+                const s16x4 b1 = tr_read(xbase + (size_t)(q0 + 4) * XP + xoff[t]);
                 bf[t] = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
 #pragma unroll
@@ -588,7 +613,7 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
         p.qn = (rh * Wp + 15) / 16 * 16;
         p.xn = p.qn + (a.R - 1) * Wp + (a.R - 1);
         const long long gpieces = (long long)p.qn * p.ktw * 8, xpieces = (long long)p.xn * p.ctw * 8;
-        p.lds = (size_t)p.qn * (p.ktw * 128 + 16) + (size_t)p.xn * (p.ctw * 128 + 16);
+        p.lds = (size_t)p.qn * (p.ktw * 128) + (size_t)p.xn * (p.ctw * 128);
         if (gpieces <= maxl * nt && xpieces <= maxl * nt && p.lds <= 160 * 1024) break;
         if (rh == 1) return "weight gradient: image row too wide for one chunk";
     }
@@ -601,7 +626,7 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
             p.rh = even;
             p.qn = (even * Wp + 15) / 16 * 16;
             p.xn = p.qn + (a.R - 1) * Wp + (a.R - 1);
-            p.lds = (size_t)p.qn * (p.ktw * 128 + 16) + (size_t)p.xn * (p.ctw * 128 + 16);
+            p.lds = (size_t)p.qn * (p.ktw * 128) + (size_t)p.xn * (p.ctw * 128);
         }
     }
     p.tiles_y = (a.Cin / (64 * p.ctw)) * (a.Cout / (64 * p.ktw));
