@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdelta.so")
-SOURCES = ["delta_api.hip", "conv_igemm.hip", "conv1x1.hip", "conv3x3_halo.hip", "bottleneck_block.hip", "gemm_nt.hip", "backward.hip", "backward_ops.hip", "stem_wgrad.hip", "net_ops.hip", "attention.hip", "transformer_ops.hip", "opgranular_ops.hip", "planner.cpp"]
+SOURCES = ["delta_api.hip", "conv_igemm.hip", "conv1x1.hip", "conv3x3_halo.hip", "conv3x3_c64.hip", "bottleneck_block.hip", "gemm_nt.hip", "backward.hip", "backward_ops.hip", "stem_wgrad.hip", "net_ops.hip", "attention.hip", "transformer_ops.hip", "opgranular_ops.hip", "planner.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

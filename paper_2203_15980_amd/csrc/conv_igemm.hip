@@ -439,6 +439,7 @@ static int conv_tile_n(const ConvArgs &a) {
 
 const char *conv_kernel_name(const ConvArgs &a) {
     if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
+    if (conv3x3_c64_applies(a)) return "conv3x3_c64 bf16 (persistent, nine taps resident in LDS)";
     if (conv3x3_halo_applies(a)) return "conv3x3_halo bf16 256x64 (4x1 waves)";
     if (gemm_nt_applies(a)) return "gemm_nt bf16 256x256|192 (64x64 per wave, direct-to-LDS)";
     const int bn = conv_tile_n(a);
@@ -521,6 +522,7 @@ hipError_t launch_conv_scatter(const ConvArgs &a, hipStream_t stream) {
 hipError_t launch_conv(const ConvArgs &a, hipStream_t stream) {
     if (conv_check(a) || a.oy_s) return hipErrorInvalidValue;
     if (conv1x1_stream_applies(a)) return launch_conv1x1_stream(a, stream);
+    if (conv3x3_c64_applies(a)) return launch_conv3x3_c64(a, stream);
     if (conv3x3_halo_applies(a)) return launch_conv3x3_halo(a, stream);
     if (gemm_nt_applies(a)) return launch_gemm_nt(a, stream);
     const int bn = conv_tile_n(a);

@@ -53,6 +53,9 @@ hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream);
 // conv3x3_halo.hip: bf16 3x3 stride-1 kernel that keeps the input halo of a pixel tile in LDS
 bool conv3x3_halo_applies(const ConvArgs &a);
 hipError_t launch_conv3x3_halo(const ConvArgs &a, hipStream_t stream);
+// conv3x3_c64.hip: bf16 3x3 stride-1 64 -> 64 channels, persistent workgroups with all nine taps resident in LDS
+bool conv3x3_c64_applies(const ConvArgs &a);
+hipError_t launch_conv3x3_c64(const ConvArgs &a, hipStream_t stream);
 // bottleneck_block.hip: one identity bottleneck of conv2_x (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + x,
 // ReLU after each, bf16) in a single launch; a1 / a2 / out may each be null (not stored)
 struct BlockArgs {

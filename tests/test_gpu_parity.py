@@ -121,6 +121,54 @@ def test_single_layer_matches_oracle(torch_mod, dtype, case):
     d.close()
 
 
+def test_conv3x3_c64_persistent_workgroups_on_sampled_images(torch_mod):
+    """The 64 -> 64 channel 3x3 kernel keeps its workgroups alive over several tiles once there are more
+    than 256 tiles: 40 images of 56 x 56 make 506 tiles of 248 pixels (two rounds, the second ragged).
+    With residual and ReLU; the oracle computes the first and the last image (a convolution with frozen
+    statistics treats images independently).  Recomputation gives the same bits."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    N, H, W, C = 40, 56, 56, 64
+    l = single("c64_rounds", N, H, W, C, C, 3, 1, 1, True, True)
+    x = synth.make_input(78, (N, H, W, C), "bf16")
+    p = synth.make_params(78, l, "bf16")
+    r = synth.f32_to_bf16_bits(synth.normal(78, 999, N * H * W * C).astype(np.float32)).reshape(N, H, W, C)
+    d = make_delta(torch, 64 << 20)
+    d.bind([x.nbytes] * 3)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    w = dev(p["w"])
+    bn = [dev(p[k]) for k in ("gamma", "beta", "mean", "var")]
+    scale = torch.empty(C, dtype=torch.float32, device="cuda:0")
+    shift = torch.empty(C, dtype=torch.float32, device="cuda:0")
+    d.bn_fold(bn[0].data_ptr(), bn[1].data_ptr(), bn[2].data_ptr(), bn[3].data_ptr(), float(p["eps"]), C,
+              scale.data_ptr(), shift.data_ptr())
+    base = d.arena.data_ptr()
+    for tid, a in ((0, x), (1, r)):
+        ptr = d.alloc(tid)
+        d.arena[ptr - base:ptr - base + a.nbytes].copy_(dev(a.view(np.uint8).reshape(-1)))
+    desc = dl.LayerDesc(x=0, res=1, y=2, dtype=dl.DTYPE_BF16, w=w.data_ptr(), scale=scale.data_ptr(),
+                        shift=shift.data_ptr(), N=N, H=H, W=W, Cin=C, Cout=C, R=3, S=3, stride=1, pad=1, relu=1)
+    assert "c64" in d.layer_kernel(desc)
+    d.recompute_segment([desc])
+    py = d.tensor_ptr(2)
+    d.sync()
+    got = d.arena[py - base:py - base + x.nbytes].cpu().numpy().view(np.uint16).reshape(N, H, W, C).copy()
+    for img in (0, N - 1):
+        ref = on.conv_bn_act(x[img:img + 1], p["w"], p, res=r[img:img + 1], stride=1, pad=1, relu=True, dtype="bf16")
+        err = rel_err(got[img:img + 1], ref, "bf16")
+        print("image %d err %.2e" % (img, err), flush=True)
+        assert err <= TOL["bf16"], (img, err)
+    d.release(2, dl.EV_EVICT)
+    filler = d.alloc(2)                                       # a recomputation at another address
+    d.release(2, dl.EV_FREE)
+    d.recompute_segment([desc])
+    py2 = d.tensor_ptr(2)
+    d.sync()
+    again = d.arena[py2 - base:py2 - base + x.nbytes].cpu().numpy().view(np.uint16).reshape(N, H, W, C)
+    assert np.array_equal(again, got)
+    d.close()
+
+
 def _stack(torch, N, HW, dtype, master, arena_mult=1.0):
     from paper_2203_15980_amd.harness import Net
     layers = synth.bottleneck_stack(N, HW, HW)
@@ -356,7 +404,7 @@ def test_error_paths(torch_mod):
     assert e.value.status == dl.ERR_INVALID
     # the kernel a layer dispatches to, by name
     assert "conv1x1_stream" in d.layer_kernel(net.desc["b1.a1"][0])
-    assert "conv3x3_halo" in d.layer_kernel(net.desc["b1.a2"][0])
+    assert "conv3x3_c64" in d.layer_kernel(net.desc["b1.a2"][0])           # 64 -> 64 channels: the weights stay in LDS
     d.close()
     # arena too small for the second tensor
     small = make_delta(torch_mod, 4096)
