@@ -62,26 +62,36 @@ static constexpr int kTPitch = 144;
 
 // NS = Cin / 64 (128-byte slices of the reduction axis), NG = channels of one slice / 64.
 // Dynamic LDS: weights [NG*64][Cin*2 + 16 bytes], scale, shift (fp32) of the slice, then one
-// transposition tile per wavefront.  Grid: 8 * ceil(pixel groups / 8) * slices workgroups.
+// transposition tile per wavefront.
+// Persistent workgroups: the grid is `nworkers` workgroups per channel slice (about one per CU),
+// each stages its weights once and its wavefronts then walk the 32-pixel tiles
+// worker + nworkers * (wavefront + WAVES * k): consecutive tiles go to different CUs, so that
+// whatever number of tiles there is, every CU gets its share to within one tile per wavefront
+// (one workgroup per 512 pixels left 60 of 256 CUs idle at batch 32 and ran 3.06 rounds as 4 at
+// batch 128).  While a tile's last channel group is finished the next tile's rows are already in flight.
+// Grid: 8 * ceil(nworkers / 8) * slices workgroups.
 template <int NS, int NG, int WAVES, bool HAS_RES, bool SLICED, bool HAS_MASK = false>
-__global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) {
+__global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a, int nworkers) {
     constexpr int THREADS = WAVES * 64;
     constexpr int Cout = NG * 64;               // channels of this workgroup's slice
+    // The next tile's rows are requested while the current tile's last group is finished - where a
+    // lane has the registers for them to wait in: not with a residual at 16 wavefronts (128
+    // registers) or with residual and mask, and not with four operand slices.
+    constexpr bool AHEAD = !(HAS_RES && (WAVES > 12 || HAS_MASK)) && NS <= 2;
     extern __shared__ __align__(16) unsigned char lds[];
-    // workgroup -> (pixel group, channel slice): consecutive workgroups go to consecutive XCDs,
-    // so the slices of pixel group g all land on XCD g % 8.  A layer that is one slice keeps
-    // the channel count a compile-time constant (cheaper addressing, fewer registers).
-    long long group;
-    int n0;
+    // workgroup -> (worker, channel slice): consecutive workgroups go to consecutive XCDs,
+    // so the slices of worker g all land on XCD g % 8 and share the activations in its L2.
+    // A layer that is one slice keeps the channel count a compile-time constant (cheaper
+    // addressing, fewer registers).
+    int worker, n0;
     if constexpr (SLICED) {
         const int nslices = a.Cout / Cout;
-        const long long groups = ((long long)a.M + WAVES * 32 - 1) / (WAVES * 32);
         const unsigned xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3;
-        group = (long long)(rest / (unsigned)nslices) * 8 + xcd;
-        if (group >= groups) return;             // whole workgroup, before the barrier
+        worker = (int)(rest / (unsigned)nslices) * 8 + (int)xcd;
+        if (worker >= nworkers) return;          // whole workgroup, before the barrier
         n0 = (int)(rest % (unsigned)nslices) * Cout;
     } else {
-        group = blockIdx.x;
+        worker = blockIdx.x;
         n0 = 0;
     }
     const int Ctot = SLICED ? a.Cout : Cout;
@@ -93,36 +103,37 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
     // wavefront-private transposition tile: 32 pixel rows of 128 bytes, pitch 144
     unsigned char *ttile = reinterpret_cast<unsigned char *>(lshift + Cout) + wv * (32 * kTPitch);
 
-    // ---- this wavefront's 32 output pixels.  Everything it reads from HBM (its activation
-    // operand and, if present, its residual rows) goes into flight first, so that the
-    // latency overlaps the staging of the weights and the wavefront never waits twice.
-    const long long tile = group * WAVES + wv;
-    const long long m = tile * 32 + l32;
-    const bool active = tile * 32 < a.M;         // wavefronts past the end only help staging
-    const bool valid = m < a.M;
-    const long long mm = valid ? m : (long long)a.M - 1;      // clamp: loads stay in bounds
-    size_t xpix;
-    if (a.stride == 1) {
-        xpix = (size_t)mm;
-    } else {
-        const int PQ = a.P * a.Q;
-        const int n = (int)(mm / PQ), pq = (int)(mm - (long long)n * PQ);
-        const int p = pq / a.Q, q = pq - p * a.Q;
-        xpix = ((size_t)n * a.H + (size_t)p * a.stride) * a.W + (size_t)q * a.stride;
-    }
+    // tile numbers fit 32 bits with room to spare (M < 2^31, at most 2^26 tiles, step <= 4096)
+    const int ntiles = (int)(((long long)a.M + 31) / 32);
+    const int step = nworkers * WAVES;
+    int tile = worker + nworkers * wv;
+    const bool active = tile < ntiles;           // wavefronts without a tile only help staging
+
+    // This lane's pixel of a tile (clamped: loads stay in bounds, such rows are never stored)
+    auto pixel = [&](int t) -> long long {
+        const long long m = (long long)t * 32 + l32;
+        return m < a.M ? m : (long long)a.M - 1;
+    };
     // operand straight into registers: lane (pixel l32, half) takes bytes [64*half, 64*half + 64)
     // of each 128-byte slice of its pixel (routing these loads through the LDS tile as rows
     // helped the smallest layer only and cost registers everywhere else)
-    const unsigned char *xp = static_cast<const unsigned char *>(a.x) + xpix * (NS * 128) + half * 64;
-    u32x4_t xf[NS][4];
+    auto load_x = [&](int t, u32x4_t (&dst)[NS][4]) {
+        const long long mm = pixel(t);
+        size_t xpix;
+        if (a.stride == 1) {
+            xpix = (size_t)mm;
+        } else {
+            const int PQ = a.P * a.Q;
+            const int n = (int)(mm / PQ), pq = (int)(mm - (long long)n * PQ);
+            const int p = pq / a.Q, q = pq - p * a.Q;
+            xpix = ((size_t)n * a.H + (size_t)p * a.stride) * a.W + (size_t)q * a.stride;
+        }
+        const unsigned char *xp = static_cast<const unsigned char *>(a.x) + xpix * (NS * 128) + half * 64;
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            xf[s][j] = *reinterpret_cast<const u32x4_t *>(xp + s * 128 + j * 16);
-    const long long mbase = tile * 32;
-    const int trow = lane >> 3, tseg = lane & 7;
-
+            for (int j = 0; j < 4; ++j) dst[s][j] = *reinterpret_cast<const u32x4_t *>(xp + s * 128 + j * 16);
+    };
     // the slice offset is folded into the (uniform) base pointers
     unsigned char *yg = static_cast<unsigned char *>(a.y) + (size_t)n0 * 2;
     const unsigned char *rg = static_cast<const unsigned char *>(a.res) + (size_t)n0 * 2;
@@ -130,10 +141,10 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
     // residual in the post-swap layout, straight into registers: piece (u, i2) of group g
     // covers channels g*64 + u*32 + 16*i2 + 8*half .. +8 of this lane's pixel (32-byte runs per
     // pixel; routing the reads through the LDS tile as well measured slower).  Two groups are
-    // held: the one being finished and the next one, already in flight.
-    const size_t orow = (size_t)mm * Ctot * 2;
+    // held: the one being finished and the next one (of this tile or the next), already in flight.
     u32x4_t rv[2][2][2];
-    auto load_res = [&](int g, u32x4_t (&dst)[2][2]) {
+    auto load_res = [&](int t, int g, u32x4_t (&dst)[2][2]) {
+        const size_t orow = (size_t)pixel(t) * Ctot * 2;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -141,7 +152,11 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
                 dst[u][i2] = *reinterpret_cast<const u32x4_t *>(
                     rg + orow + (size_t)(g * 64 + u * 32 + 16 * i2 + 8 * half) * 2);
     };
-    if constexpr (HAS_RES) load_res(0, rv[0]);
+    // Everything the first tile reads from HBM goes into flight before the staging, so that the
+    // latency overlaps it.
+    u32x4_t xf[NS][4];
+    load_x(tile, xf);
+    if constexpr (HAS_RES) load_res(tile, 0, rv[0]);
 
     // ---- stage weights and batch-norm factors (once per workgroup)
     {
@@ -162,86 +177,114 @@ __global__ __launch_bounds__(WAVES * 64) void conv1x1_stream_kernel(ConvArgs a) 
     if (!active) return;
     const int relu = a.relu;
 
+    for (;;) {
+        const int next = tile + step;
+        const bool more = next < ntiles;         // the same for the whole wavefront
+        // with a mask operand the lane-derived offsets are recomputed per tile (a handful of integer
+        // operations) instead of being carried across the loop: those variants have no register to spare
+        int lz = lane;
+        if constexpr (HAS_MASK) asm volatile("" : "+v"(lz));
+        const int l32 = lz & 31, half = lz >> 5, trow = lz >> 3, tseg = lz & 7;
+        const long long mbase = (long long)tile * 32;
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        if constexpr (HAS_RES) {
-            if (g + 1 < NG) load_res(g + 1, rv[(g + 1) & 1]);
-        }
-        f32x16_t acc[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-        const unsigned char *wrow = lds + (size_t)(g * 64 + l32) * WPITCH + half * 64;
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4_t w0 = *reinterpret_cast<const u32x4_t *>(wrow + s * 128 + j * 16);
-                const u32x4_t w1 = *reinterpret_cast<const u32x4_t *>(wrow + 32 * WPITCH + s * 128 + j * 16);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w0),
-                                                                 __builtin_bit_cast(bf16x8_t, xf[s][j]), acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w1),
-                                                                 __builtin_bit_cast(bf16x8_t, xf[s][j]), acc[1], 0, 0, 0);
+        for (int g = 0; g < NG; ++g) {
+            if constexpr (HAS_RES) {
+                if (g + 1 < NG) load_res(tile, g + 1, rv[(g + 1) & 1]);
+                else if (AHEAD && more) load_res(next, 0, rv[NG & 1]);
             }
-        // ---- epilogue of the two 32-channel tiles
+            f32x16_t acc[2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int cb = g * 64 + u * 32;
-            float v[16];
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const f32x4_t sc = *reinterpret_cast<const f32x4_t *>(lscale + cb + 8 * rb + 4 * half);
-                const f32x4_t sh = *reinterpret_cast<const f32x4_t *>(lshift + cb + 8 * rb + 4 * half);
-                v[4 * rb + 0] = acc[u][4 * rb + 0] * sc.x + sh.x;
-                v[4 * rb + 1] = acc[u][4 * rb + 1] * sc.y + sh.y;
-                v[4 * rb + 2] = acc[u][4 * rb + 2] * sc.z + sh.z;
-                v[4 * rb + 3] = acc[u][4 * rb + 3] * sc.w + sh.w;
-            }
+                for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+            const unsigned char *wrow = lds + (size_t)(g * 64 + l32) * WPITCH + half * 64;
 #pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2) {
-                // blocks 2*i2 and 2*i2+1: after the swap the lower half-wave holds channels
-                // cb + 16*i2 .. +8 and the upper half-wave the next eight, in order
-                float o[8];
+            for (int s = 0; s < NS; ++s)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]),
-                                                              __float_as_uint(v[8 * i2 + 4 + j]), false, false);
-                    o[j] = __uint_as_float(r[0]);
-                    o[4 + j] = __uint_as_float(r[1]);
+                    const u32x4_t w0 = *reinterpret_cast<const u32x4_t *>(wrow + s * 128 + j * 16);
+                    const u32x4_t w1 = *reinterpret_cast<const u32x4_t *>(wrow + 32 * WPITCH + s * 128 + j * 16);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w0),
+                                                                     __builtin_bit_cast(bf16x8_t, xf[s][j]), acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w1),
+                                                                     __builtin_bit_cast(bf16x8_t, xf[s][j]), acc[1], 0, 0, 0);
                 }
-                if constexpr (HAS_RES) {
-                    const u32x4_t r4 = rv[g & 1][u][i2];
-                    o[0] += lo16(r4.x); o[1] += hi16(r4.x); o[2] += lo16(r4.y); o[3] += hi16(r4.y);
-                    o[4] += lo16(r4.z); o[5] += hi16(r4.z); o[6] += lo16(r4.w); o[7] += hi16(r4.w);
-                }
-                if (relu) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
-                }
-                u32x4_t out;
-                out.x = pack2(o[0], o[1]); out.y = pack2(o[2], o[3]);
-                out.z = pack2(o[4], o[5]); out.w = pack2(o[6], o[7]);
-                *reinterpret_cast<u32x4_t *>(ttile + l32 * kTPitch + (u * 32 + 16 * i2 + 8 * half) * 2) = out;
+            // the operand registers are free after the last group's products: the next tile's rows
+            // go into flight under this group's epilogue and stores
+            if constexpr (AHEAD) {
+                if (g == NG - 1 && more) load_x(next, xf);
             }
-        }
-        // pieces -> rows: 8 lanes store 128 contiguous bytes of one pixel
-        wave_fence();
+            // ---- epilogue of the two 32-channel tiles
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int pr = trow + 8 * t;
-            u32x4_t o4 = *reinterpret_cast<const u32x4_t *>(ttile + pr * kTPitch + tseg * 16);
-            if (mbase + pr < a.M) {
-                const size_t off = ((size_t)(mbase + pr) * Ctot + g * 64) * 2 + tseg * 16;
-                if constexpr (HAS_MASK) {
-                    const u32x4_t mv = *reinterpret_cast<const u32x4_t *>(mg + off);
-                    o4.x = keep_where_positive_bf16(o4.x, mv.x); o4.y = keep_where_positive_bf16(o4.y, mv.y);
-                    o4.z = keep_where_positive_bf16(o4.z, mv.z); o4.w = keep_where_positive_bf16(o4.w, mv.w);
+            for (int u = 0; u < 2; ++u) {
+                const int cb = g * 64 + u * 32;
+                float v[16];
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const f32x4_t sc = *reinterpret_cast<const f32x4_t *>(lscale + cb + 8 * rb + 4 * half);
+                    const f32x4_t sh = *reinterpret_cast<const f32x4_t *>(lshift + cb + 8 * rb + 4 * half);
+                    v[4 * rb + 0] = acc[u][4 * rb + 0] * sc.x + sh.x;
+                    v[4 * rb + 1] = acc[u][4 * rb + 1] * sc.y + sh.y;
+                    v[4 * rb + 2] = acc[u][4 * rb + 2] * sc.z + sh.z;
+                    v[4 * rb + 3] = acc[u][4 * rb + 3] * sc.w + sh.w;
                 }
-                *reinterpret_cast<u32x4_t *>(yg + off) = o4;
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2) {
+                    // blocks 2*i2 and 2*i2+1: after the swap the lower half-wave holds channels
+                    // cb + 16*i2 .. +8 and the upper half-wave the next eight, in order
+                    float o[8];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]),
+                                                                  __float_as_uint(v[8 * i2 + 4 + j]), false, false);
+                        o[j] = __uint_as_float(r[0]);
+                        o[4 + j] = __uint_as_float(r[1]);
+                    }
+                    if constexpr (HAS_RES) {
+                        const u32x4_t r4 = rv[g & 1][u][i2];
+                        o[0] += lo16(r4.x); o[1] += hi16(r4.x); o[2] += lo16(r4.y); o[3] += hi16(r4.y);
+                        o[4] += lo16(r4.z); o[5] += hi16(r4.z); o[6] += lo16(r4.w); o[7] += hi16(r4.w);
+                    }
+                    if (relu) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
+                    }
+                    u32x4_t out;
+                    out.x = pack2(o[0], o[1]); out.y = pack2(o[2], o[3]);
+                    out.z = pack2(o[4], o[5]); out.w = pack2(o[6], o[7]);
+                    *reinterpret_cast<u32x4_t *>(ttile + l32 * kTPitch + (u * 32 + 16 * i2 + 8 * half) * 2) = out;
+                }
             }
+            // pieces -> rows: 8 lanes store 128 contiguous bytes of one pixel
+            wave_fence();
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int pr = trow + 8 * t;
+                u32x4_t o4 = *reinterpret_cast<const u32x4_t *>(ttile + pr * kTPitch + tseg * 16);
+                if (mbase + pr < a.M) {
+                    const size_t off = ((size_t)(mbase + pr) * Ctot + g * 64) * 2 + tseg * 16;
+                    if constexpr (HAS_MASK) {
+                        const u32x4_t mv = *reinterpret_cast<const u32x4_t *>(mg + off);
+                        o4.x = keep_where_positive_bf16(o4.x, mv.x); o4.y = keep_where_positive_bf16(o4.y, mv.y);
+                        o4.z = keep_where_positive_bf16(o4.z, mv.z); o4.w = keep_where_positive_bf16(o4.w, mv.w);
+                    }
+                    *reinterpret_cast<u32x4_t *>(yg + off) = o4;
+                }
+            }
+            wave_fence();
         }
-        wave_fence();
+        if (!more) break;
+        tile = next;
+        if constexpr (!AHEAD) {
+            load_x(tile, xf);
+            if constexpr (HAS_RES) load_res(tile, 0, rv[0]);
+        }
+        if constexpr (AHEAD && HAS_RES && (NG & 1)) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2) rv[0][u][i2] = rv[1][u][i2];
+        }
     }
 }
 
@@ -270,7 +313,15 @@ template <int NS, int NG, int WAVES, bool SLICED, bool HAS_MASK>
 static hipError_t launch_stream_s(const ConvArgs &a, hipStream_t stream) {
     const long long tiles = ((long long)a.M + 31) / 32;
     const long long groups = (tiles + WAVES - 1) / WAVES;
-    const long long blocks = SLICED ? (groups + 7) / 8 * 8 * (a.Cout / (NG * 64)) : groups;
+    const int nslices = SLICED ? a.Cout / (NG * 64) : 1;
+    // one workgroup per CU and slice set; fewer when there are not enough tiles for that.  The masked
+    // variants are the backward pass's data gradients, which share the GPU with the weight-gradient
+    // stream: workgroups that hold their CU for the whole launch were 1.5 % slower there than one
+    // workgroup per WAVES tiles, which leaves and lets the other stream's workgroups in.
+    long long cap = HAS_MASK ? groups : 256 / nslices;
+    if (cap < 8) cap = 8;
+    const long long nworkers = groups < cap ? groups : cap;
+    const long long blocks = SLICED ? (nworkers + 7) / 8 * 8 * nslices : nworkers;
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(WAVES * 64);
     const size_t lds = (size_t)NG * 64 * ((size_t)NS * 128 + 16 + 8) + (size_t)WAVES * 32 * kTPitch;
@@ -287,8 +338,8 @@ static hipError_t launch_stream_s(const ConvArgs &a, hipStream_t stream) {
         if (e != hipSuccess) return e;
         raised = true;
     }
-    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED, HAS_MASK><<<grid, block, lds, stream>>>(a);
-    else conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED, HAS_MASK><<<grid, block, lds, stream>>>(a);
+    if (a.res) conv1x1_stream_kernel<NS, NG, WAVES, true, SLICED, HAS_MASK><<<grid, block, lds, stream>>>(a, (int)nworkers);
+    else conv1x1_stream_kernel<NS, NG, WAVES, false, SLICED, HAS_MASK><<<grid, block, lds, stream>>>(a, (int)nworkers);
     return hipGetLastError();
 }
 
@@ -302,6 +353,8 @@ static hipError_t launch_stream(const ConvArgs &a, hipStream_t stream) {
     if (a.Cout == NG * 64) {
         constexpr int WV = NS * NG <= 4 ? WAVES : W12;
         if (a.mask) return launch_stream_s<NS, NG, W12, false, true>(a, stream);
+        // two or four operand slices and a residual do not fit 128 registers
+        if (NS > 1 && a.res) return launch_stream_s<NS, NG, W12, false, false>(a, stream);
         return launch_stream_s<NS, NG, WV, false, false>(a, stream);
     }
     constexpr int WV = NS * NG <= 2 ? WAVES : W12;
