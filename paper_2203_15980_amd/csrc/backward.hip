@@ -223,9 +223,13 @@ template <int TW>
 __device__ __forceinline__ int lds_swizzle(int row) { return TW == 1 ? (row >> 1) & 1 : row & 3; }
 
 // KTW x CTW tiles of 64 x 64 [k, c] per workgroup and tap; TAPS = R * R, or fewer: the taps tapwin lists.
-template <int KTW, int CTW, int TAPS>
-__global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs a) {
-    constexpr int NW = KTW * CTW * TAPS, NT = NW * 64;
+// QS wavefronts share each (tap, tile): wavefront qs of them takes the 16-position steps qs, qs + QS, ...
+// of every chunk, and when the workgroup has walked all its chunks their sums are added in the order
+// of qs (through LDS).  A tile's wavefront alone on its SIMD left the matrix pipe idle whenever it
+// waited for its own operand reads or at the two barriers of a chunk.
+template <int KTW, int CTW, int TAPS, int QS>
+__global__ __launch_bounds__(KTW * CTW * TAPS * QS * 64) void wgrad_kernel(WgradArgs a) {
+    constexpr int NB = KTW * CTW * TAPS, NW = NB * QS, NT = NW * 64;
     // LDS rows without padding; the 64-byte groups of a row are permuted by the row number instead
     // (group ^ swizzle(row)), so that the four consecutive rows a transposing read touches at one
     // column lie in four different quarters of the 64 banks (with padded rows of 144 / 272 bytes half
@@ -238,7 +242,8 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
     unsigned char *xs = smem + (size_t)a.QN * GP;                // [XN][XP]
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int tap = wv % TAPS, kw = (wv / TAPS) % KTW, cw = wv / (TAPS * KTW);
+    const int base = wv % NB, qs = wv / NB;
+    const int tap = base % TAPS, kw = (base / TAPS) % KTW, cw = base / (TAPS * KTW);
     const int B = (a.R - 1) / 2, Wp = a.W + 2 * B;
     const int win = (int)((a.tapwin >> (4 * tap)) & 15);
     const int r = win / a.R, s = win - r * a.R;
@@ -352,7 +357,7 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
         stage();
         fetch(chunk + a.nsplit);                                 // next chunk of this split in flight
         __syncthreads();
-        for (int q0 = 0; q0 < a.QN; q0 += 16) {
+        for (int q0 = 16 * qs; q0 < a.QN; q0 += 16 * QS) {
             s16x8 af[2], bf[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -372,8 +377,41 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * 64) void wgrad_kernel(WgradArgs 
         }
     }
 
+    // ---- the QS sums of a tile, added in the order of qs
+    if constexpr (QS > 1) {
+        __syncthreads();                                         // the staged tiles are dead
+        float *red = reinterpret_cast<float *>(smem);            // [QS - 1][NB][i][j][e4][lane] x f32x4
+        if (qs > 0) {
+            float *dst = red + (size_t)((qs - 1) * NB + base) * 4096;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const f32x4 v = {acc[i][j][4 * e4], acc[i][j][4 * e4 + 1], acc[i][j][4 * e4 + 2], acc[i][j][4 * e4 + 3]};
+                        *reinterpret_cast<f32x4 *>(dst + ((((i * 2 + j) * 4 + e4) * 64 + lane) * 4)) = v;
+                    }
+        }
+        __syncthreads();
+        if (qs > 0) return;
+#pragma unroll
+        for (int g = 1; g < QS; ++g) {
+            const float *src = red + (size_t)((g - 1) * NB + base) * 4096;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const f32x4 v = *reinterpret_cast<const f32x4 *>(src + ((((i * 2 + j) * 4 + e4) * 64 + lane) * 4));
+                        acc[i][j][4 * e4] += v.x; acc[i][j][4 * e4 + 1] += v.y;
+                        acc[i][j][4 * e4 + 2] += v.z; acc[i][j][4 * e4 + 3] += v.w;
+                    }
+        }
+    }
     // ---- partial sums, accumulator-register order: [split][ty][wave][i][j][e4][lane] x f32x4
-    float *out = a.partial + ((((size_t)blockIdx.x * gridDim.y + ty) * NW + wv) * 4) * (4 * 64 * 4);
+    float *out = a.partial + ((((size_t)blockIdx.x * gridDim.y + ty) * NB + base) * 4) * (4 * 64 * 4);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -557,7 +595,7 @@ hipError_t launch_bwd_weights(const void *w, const float *scale, void *wt, int K
 namespace {
 
 struct WgradPlan {
-    int ktw, ctw, taps, rh, qn, xn, nsplit, tiles_y, waves;
+    int ktw, ctw, taps, rh, qn, xn, nsplit, tiles_y, waves, qs;   // waves: (tap, tile) pairs; qs wavefronts on each
     size_t lds, partial_bytes;
 };
 
@@ -574,6 +612,16 @@ ConvArgs flattened_1x1(const ConvArgs &a) {
             break;
         }
     return f;
+}
+
+// Wavefronts per (tap, tile) pair: as many as make a workgroup of 8 (two per SIMD; with 16 the kernel
+// spills at 128 registers).  ResNet-50's backward pass at batch 128: 5.76 -> 5.69 ms.
+int wgrad_qs(int pairs) {
+    int qs = 8 / pairs;
+    if (qs < 1) qs = 1;
+    if (qs > 8) qs = 8;
+    while (qs & (qs - 1)) --qs;                    // 1, 2, 4, 8
+    return qs;
 }
 
 // ntaps: 0 = all R * S taps; 1, 2 or 4 = a subset of a 3 x 3 window's taps (the strided layers' parity classes)
@@ -601,13 +649,16 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
         else if (p.ktw == 2) p.ctw = a.Cin % 128 == 0 ? 2 : 1;
     }
     p.waves = p.ktw * p.ctw * p.taps;
+    p.qs = wgrad_qs(p.waves);
+    while ((size_t)(p.qs - 1) * p.waves * 4096 * sizeof(float) > 160 * 1024) p.qs >>= 1;   // their sums meet in LDS
     const int Wp = a.W + (a.R - 1);
     // image rows per chunk: up to about 256 positions, and at most maxl staged pieces per thread
     int rh = (256 + Wp - 1) / Wp;
     if (rh < 1) rh = 1;
     if (rh > a.H) rh = a.H;
-    const int nt = p.waves * 64;
+    const int nt = p.waves * p.qs * 64;
     const long long maxl = nt >= 512 ? 4 : 8;      // as in the kernel
+    const size_t red = (size_t)(p.qs - 1) * p.waves * 4096 * sizeof(float);   // the sums of the extra wavefronts
     for (;; --rh) {
         p.rh = rh;
         p.qn = (rh * Wp + 15) / 16 * 16;
@@ -629,6 +680,7 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
             p.lds = (size_t)p.qn * (p.ktw * 128) + (size_t)p.xn * (p.ctw * 128);
         }
     }
+    if (p.lds < red) p.lds = red;
     p.tiles_y = (a.Cin / (64 * p.ctw)) * (a.Cout / (64 * p.ktw));
     const int chunks = a.N * ((a.H + p.rh - 1) / p.rh);
     // one workgroup per CU in all: with two (512) the partial sums double and a ResNet-50 backward pass was
@@ -642,17 +694,32 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
     return nullptr;
 }
 
+template <int KTW, int CTW, int TAPS, int QS>
+hipError_t launch_wgrad_q(const bwd::WgradArgs &wa, const WgradPlan &p, hipStream_t stream) {
+    if constexpr (KTW * CTW * TAPS * QS > 16) {
+        return hipErrorInvalidValue;
+    } else {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd::wgrad_kernel<KTW, CTW, TAPS, QS>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+        bwd::wgrad_kernel<KTW, CTW, TAPS, QS><<<dim3(p.nsplit, p.tiles_y), dim3(KTW * CTW * TAPS * QS * 64), p.lds, stream>>>(wa);
+        return hipGetLastError();
+    }
+}
+
 template <int KTW, int CTW, int TAPS>
 hipError_t launch_wgrad_t(const bwd::WgradArgs &wa, const WgradPlan &p, hipStream_t stream) {
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd::wgrad_kernel<KTW, CTW, TAPS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
+    switch (p.qs) {
+    case 1: return launch_wgrad_q<KTW, CTW, TAPS, 1>(wa, p, stream);
+    case 2: return launch_wgrad_q<KTW, CTW, TAPS, 2>(wa, p, stream);
+    case 4: return launch_wgrad_q<KTW, CTW, TAPS, 4>(wa, p, stream);
+    case 8: return launch_wgrad_q<KTW, CTW, TAPS, 8>(wa, p, stream);
+    default: return hipErrorInvalidValue;
     }
-    bwd::wgrad_kernel<KTW, CTW, TAPS><<<dim3(p.nsplit, p.tiles_y), dim3(KTW * CTW * TAPS * 64), p.lds, stream>>>(wa);
-    return hipGetLastError();
 }
 
 }  // namespace
