@@ -441,7 +441,7 @@ const char *conv_kernel_name(const ConvArgs &a) {
     if (conv1x1_stream_applies(a)) return "conv1x1_stream bf16";
     if (conv3x3_c64_applies(a)) return "conv3x3_c64 bf16 (persistent, nine taps resident in LDS)";
     if (conv3x3_halo_applies(a)) return "conv3x3_halo bf16 256x64 (4x1 waves)";
-    if (gemm_nt_applies(a)) return "gemm_nt bf16 256x256|192 (64x64 per wave, direct-to-LDS)";
+    if (gemm_nt_applies(a)) return gemm_nt_kernel_name(a);
     const int bn = conv_tile_n(a);
     if (a.bf16) return bn == 128 ? "conv_igemm bf16 128x128 (2x2 waves)" : "conv_igemm bf16 128x64 (4x1 waves)";
     return bn == 128 ? "conv_igemm f32 128x128 (2x2 waves)" : "conv_igemm f32 128x64 (4x1 waves)";

@@ -5,7 +5,9 @@
 // with many input channels - both are plain "NT" GEMMs (both operands contiguous along K), bound
 // by the matrix cores.  The tiled convolution kernel treats them as a convolution (64 x 64 tiles
 // per wavefront, slices staged through registers); this kernel is built for the GEMM:
-//  * workgroup tile 256 x 256 (16 wavefronts as 4 x 4) or 256 x 192 (12 wavefronts), 64 x 64 per
+//  * workgroup tile 256 x 256 (16 wavefronts as 4 x 4) or 256 x 192 (12 wavefronts) where the output is
+//    at least 192 channels wide, 128 x 128 (4 wavefronts, two workgroups per CU) for 128 channels;
+//    64 x 64 per
 //    wavefront and at most 128 registers, so that four (three) wavefronts share a SIMD: with
 //    128 x 64 per wavefront (8 | 6 wavefronts, two per SIMD, fewer operand reads per MFMA) the same
 //    kernel was 5-13 % slower - a SIMD needs more than two wavefronts to keep its MFMA pipe fed
@@ -49,10 +51,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kBM = 256, kBK = 64, kStages = 2;
-static constexpr int kWM = 4;                                           // wavefront rows: 256 / kWM = 64 rows of x each
-static constexpr int kTM = kBM / kWM / 32, kTN = 2;                     // kTM x 2 tiles of 32 x 32 per wavefront
-static constexpr int kXBytes = kBM * kBK * 2;                           // 16 KB of x per buffer
+static constexpr int kBK = 64, kStages = 2;
+static constexpr int kTM = 2, kTN = 2;                                  // 2 x 2 tiles of 32 x 32 per wavefront
 static constexpr int kStgPitch = 64 * 4 + 16;                          // fp32 staging row: 64 channels + pad
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -78,10 +78,12 @@ __device__ __forceinline__ float gelu_erf(float v) {     // v/2 (1 + erf(v / sqr
     return 0.5f * v * (v < 0.f ? c : 2.0f - c);
 }
 
-// BN: rows of w (output channels) per workgroup, 256 or 192; BN / 64 wavefront columns.
-template <int BN>
-__global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs a, int tiles_n, int tiles_total) {
-    constexpr int kBN = BN, kWN = BN / 64, kWaves = kWM * kWN;
+// BM: rows of x per workgroup, 256 or 128 (BM / 64 wavefront rows); BN: rows of w (output channels)
+// per workgroup, 256, 192 or 128 (BN / 64 wavefront columns).
+template <int BM, int BN>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs a, int tiles_n, int tiles_total) {
+    constexpr int kBM = BM, kBN = BN, kWM = BM / 64, kWN = BN / 64, kWaves = kWM * kWN;
+    constexpr int kXBytes = kBM * kBK * 2;                  // x rows of one buffer
     constexpr int kStageBytes = kXBytes + BN * kBK * 2;
     constexpr int XI = (kBM / 8 + kWaves - 1) / kWaves, WI = (BN / 8 + kWaves - 1) / kWaves;   // direct loads per wavefront and slice
     extern __shared__ __align__(16) unsigned char smem[];
@@ -276,55 +278,80 @@ __global__ __launch_bounds__(kWM * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs 
 
 namespace {
 
+// Workgroup tiles.  Measured at batch 128 on ResNet-50's 1x1 layers, us per launch when the layer is
+// repeated on its own (operands warm in the caches) | inside the forward pass (operands cold):
+//                         256x256      256x128      128x128      tiled convolution kernel
+//   512 -> 128, 28 x 28     38.2         32.9       29.6 | 37.2    34.0 | 38.3
+//   256 -> 128, 56 x 56    101.3         85.3       74.6 | 78.7    77.4 | 83.4
+//   1024 -> 256, 14 x 14    30.1       22.1 | 30.2    22.6         25.3 | 28.0
+//   2048 -> 512, 7 x 7         -         32.3       26.5 | 38.5    27.5 | 30.7
+//   512 -> 256, 28 x 28   40.3 | 55.5    52.7         47.0
+//   256 -> 1024, 14 x 14    31.4         38.6         34.2
+//   1024 -> 512, 14 x 14    32.0         39.1         39.5
+//   512 -> 2048, 7 x 7      22.5         27.5         26.3
+// With cold operands the two-deep pipeline of this kernel is short: one slice ahead does not cover a
+// miss to HBM, and the tiled kernel's three workgroups per CU cover each other's.  So the narrow tiles
+// take only the layers with at most 128 output channels, where they win both ways.
+struct Tile { int bm, bn; };
+const Tile kTiles[] = {{256, 256}, {256, 192}, {128, 128}};
+
+long long tiles_of(const ConvArgs &a, const Tile &t) {
+    return (((long long)a.M + t.bm - 1) / t.bm) * ((a.Cout + t.bn - 1) / t.bn);
+}
+
 // Width of the w tile: the one whose number of rounds over the 256 CUs (one workgroup per CU) times
 // its cost per tile is smaller; e.g. 768 output channels are 3 tiles of 256 (192 workgroups at
 // batch 32 x 512: a quarter of the chip idle) but 4 tiles of 192 (256 workgroups, one full round).
-int pick_bn(const ConvArgs &a) {
-    const long long tiles_m = ((long long)a.M + gemm::kBM - 1) / gemm::kBM;
-    long long best_cost = -1;
-    int best = 256;
-    for (int bn : {256, 192}) {
-        const long long tiles = tiles_m * ((a.Cout + bn - 1) / bn);
-        const long long cost = ((tiles + 255) / 256) * bn;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = bn; }
-    }
-    return best;
+const Tile &pick_tile(const ConvArgs &a) {
+    if (a.Cout <= 128) return kTiles[2];
+    const long long c256 = ((tiles_of(a, kTiles[0]) + 255) / 256) * 256, c192 = ((tiles_of(a, kTiles[1]) + 255) / 256) * 192;
+    return c192 < c256 ? kTiles[1] : kTiles[0];
 }
 
-template <int BN>
-hipError_t launch_bn(const ConvArgs &a, hipStream_t stream) {
-    constexpr size_t pipe = (size_t)gemm::kStages * (gemm::kXBytes + BN * gemm::kBK * 2);
-    constexpr size_t stage_out = (size_t)gemm::kWM * (BN / 64) * 32 * gemm::kStgPitch;
+template <int BM, int BN>
+hipError_t launch_tile(const ConvArgs &a, hipStream_t stream) {
+    constexpr size_t pipe = (size_t)gemm::kStages * ((size_t)BM * gemm::kBK * 2 + (size_t)BN * gemm::kBK * 2);
+    constexpr size_t stage_out = (size_t)(BM / 64) * (BN / 64) * 32 * gemm::kStgPitch;
     constexpr size_t lds = pipe > stage_out ? pipe : stage_out;
-    constexpr int threads = gemm::kWM * (BN / 64) * 64;
-    const int tiles_m = (a.M + gemm::kBM - 1) / gemm::kBM, tiles_n = (a.Cout + BN - 1) / BN;
+    constexpr int threads = (BM / 64) * (BN / 64) * 64;
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.Cout + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n;
     const long long blocks = (total + 7) / 8 * 8;
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm::gemm_nt_kernel<BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm::gemm_nt_kernel<BM, BN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    gemm::gemm_nt_kernel<BN><<<dim3((unsigned)blocks), dim3(threads), lds, stream>>>(a, tiles_n, (int)total);
+    gemm::gemm_nt_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(threads), lds, stream>>>(a, tiles_n, (int)total);
     return hipGetLastError();
 }
 
 }  // namespace
 
 // bf16 1x1 stride-1 layers (rows of x contiguous) with a reduction axis of at least 256 and enough
-// output to fill the chip with 256-row tiles.
+// output to fill the chip with its tiles.
 bool gemm_nt_applies(const ConvArgs &a) {
     if (!a.bf16 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0) return false;
-    if (a.Cin % 64 || a.Cin < 256 || a.Cout % 8 || a.Cout < 192) return false;
-    const long long tiles = (((long long)a.M + gemm::kBM - 1) / gemm::kBM) * ((a.Cout + 255) / 256);
-    return tiles >= 128 && tiles <= 0x3FFFFFF0LL;
+    if (a.Cin % 64 || a.Cin < 256 || a.Cout % 8 || a.Cout < 128 || (a.Cout > 128 && a.Cout < 192)) return false;
+    const long long tiles = tiles_of(a, pick_tile(a));
+    return tiles >= (a.Cout <= 128 ? 512 : 128) && tiles <= 0x3FFFFFF0LL;
+}
+
+const char *gemm_nt_kernel_name(const ConvArgs &a) {
+    const Tile &t = pick_tile(a);
+    if (t.bm == 256)
+        return t.bn == 256 ? "gemm_nt bf16 256x256 (64x64 per wave, direct-to-LDS)"
+                           : "gemm_nt bf16 256x192 (64x64 per wave, direct-to-LDS)";
+    return "gemm_nt bf16 128x128 (64x64 per wave, direct-to-LDS)";
 }
 
 hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream) {
     if (conv_check(a) || !gemm_nt_applies(a)) return hipErrorInvalidValue;
-    return pick_bn(a) == 192 ? launch_bn<192>(a, stream) : launch_bn<256>(a, stream);
+    const Tile &t = pick_tile(a);
+    if (t.bm == 256) return t.bn == 256 ? launch_tile<256, 256>(a, stream) : launch_tile<256, 192>(a, stream);
+    return launch_tile<128, 128>(a, stream);
 }
 
 }  // namespace delta

@@ -49,6 +49,7 @@ bool conv1x1_stream_applies(const ConvArgs &a);
 hipError_t launch_conv1x1_stream(const ConvArgs &a, hipStream_t stream);
 // gemm_nt.hip: bf16 1x1 stride-1 layers with a long reduction axis as a 256 x 256-tiled GEMM
 bool gemm_nt_applies(const ConvArgs &a);
+const char *gemm_nt_kernel_name(const ConvArgs &a);   // with the tile the launch will use
 hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream);
 // conv3x3_halo.hip: bf16 3x3 stride-1 kernel that keeps the input halo of a pixel tile in LDS
 bool conv3x3_halo_applies(const ConvArgs &a);

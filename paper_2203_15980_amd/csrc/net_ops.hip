@@ -33,103 +33,225 @@ __device__ __forceinline__ float bhi(uint32_t p) { return __uint_as_float(p & 0x
 // pixels are padded from 3 to 4 channels, starting at a 16-byte boundary (stride 2 x 4
 // channels x 2 bytes).  Each row is rounded up to 32 elements -- the extra tap and the
 // fourth channel carry zero weights -- so K = 7 x 32 = 224, fourteen 32x32x16 steps.
-// A workgroup owns 8 x 16 output pixels (each wavefront 2 rows x 16 columns), is persistent
-// over tiles, and stages the rearranged weights once.
-static constexpr int kStemWPitch = 7 * 64 + 16;       // bytes per output channel in LDS
-static constexpr int kStemPRows = 21, kStemPCols = 38; // patch: (2*8+5) rows, (2*16+5)+1 columns
-static constexpr int kStemPPitch = kStemPCols * 8;     // 304 bytes, a multiple of 16
+//
+// The layer is bound by its 128 bytes of output per pixel (24.5 input bytes, 224 MFMA steps per
+// 32 pixels), so the kernel is built around the memory side:
+//  * a workgroup (4 wavefronts, two workgroups per CU) owns 8 output rows x 112 output columns at
+//    a time and is persistent over such tiles; the 21 x 240 input pixels a tile needs are whole
+//    16-byte-aligned runs of the image rows when the image width is a multiple of 8: a thread
+//    fetches 8 pixels (48 bytes) with three 16-byte loads and writes them to LDS as 8 padded
+//    pixels.  The next tile's pixels are requested before the current tile is multiplied and wait
+//    in registers.  (Other widths take one pixel per thread and step.)
+//  * the rearranged weights live in registers (112 per lane) for the whole launch, so the inner
+//    loop is one 16-byte LDS read per two MFMAs;
+//  * a wavefront finishes 32 pixels (2 rows x 16 columns) at a time through a private fp32 LDS tile
+//    that turns channel-major accumulators into pixel rows; scale, shift, ReLU and the rounding
+//    happen on the row side, where a lane's 8 channels are the same for every pixel (16 registers
+//    instead of 32 LDS reads per 32 pixels), and stores are whole 128-byte lines.
+static constexpr int kStemRO = 8, kStemCQ = 112;              // output rows x columns of a tile
+static constexpr int kStemPRows = 2 * kStemRO + 5;             // 21 input rows
+static constexpr int kStemGroups = (2 * kStemCQ + 16) / 8;     // 30 groups of 8 input pixels per row
+// input pixel w of a tile whose first output column is q0 sits at position w - 2 q0 + 11 of its row:
+// groups start at position 3, the taps of output column q at position 2 (q - q0) + 8 (16-byte aligned)
+static constexpr int kStemPPitch = (3 + 8 * kStemGroups + 1) * 8;   // 1952 bytes
+static constexpr int kStemPatch = kStemPRows * kStemPPitch;          // 40992 bytes
+static constexpr int kStemTasks = kStemPRows * kStemGroups;          // 630 groups per tile
+static constexpr int kStemTPitch = 64 * 4 + 16;                      // fp32 row of 64 channels + pad
+static constexpr int kStemLds = kStemPatch + 4 * 32 * kStemTPitch;
+static_assert(64 * (7 * 64 + 16) <= kStemPatch, "the weights are staged in the patch buffer first");
 
-__global__ __launch_bounds__(256) void stem7x7_kernel(ConvArgs a, int tiles_p, int tiles_q, int ntiles) {
-    __shared__ __align__(16) unsigned char wl[64 * kStemWPitch];
-    __shared__ __align__(16) unsigned char patch[kStemPRows * kStemPPitch];
+__global__ __launch_bounds__(256, 2) void stem7x7_kernel(ConvArgs a, int tiles_p, int tiles_q, int ntiles, int aligned) {
+    __shared__ __align__(16) unsigned char lds[kStemLds];
+    unsigned char *patch = lds;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
+    unsigned char *ttile = lds + kStemPatch + wv * (32 * kStemTPitch);
     const uint16_t *wg = static_cast<const uint16_t *>(a.w);
     const uint16_t *xg = static_cast<const uint16_t *>(a.x);
 
-    // weights: wl[k][r][s*4 + c] = w[k][r][s][c], zero for s = 7 or c = 3
-    for (int e = tid; e < 64 * 7 * 32; e += 256) {
-        const int k = e / 224, rem = e - k * 224;
-        const int r = rem >> 5, el = rem & 31;
-        const int s = el >> 2, c = el & 3;
-        uint16_t v = 0;
-        if (s < 7 && c < 3) v = wg[((k * 7 + r) * 7 + s) * 3 + c];
-        *reinterpret_cast<uint16_t *>(wl + k * kStemWPitch + r * 64 + el * 2) = v;
+    // ---- weights: wl[k][r][s*4 + c] = w[k][r][s][c], zero for s = 7 or c = 3; through LDS (the patch
+    // buffer, not yet in use) into registers: wreg[r][hh][u] = 8 elements 16 hh + 8 half .. of row r of
+    // output channel 32 u + l32
+    {
+        constexpr int WP = 7 * 64 + 16;
+        for (int e = tid; e < 64 * 7 * 32; e += 256) {
+            const int k = e / 224, rem = e - k * 224;
+            const int r = rem >> 5, el = rem & 31;
+            const int s = el >> 2, c = el & 3;
+            uint16_t v = 0;
+            if (s < 7 && c < 3) v = wg[((k * 7 + r) * 7 + s) * 3 + c];
+            *reinterpret_cast<uint16_t *>(patch + k * WP + r * 64 + el * 2) = v;
+        }
+    }
+    __syncthreads();
+    u32x4_s wreg[7][2][2];
+    {
+        constexpr int WP = 7 * 64 + 16;
+        const unsigned char *wrow = patch + l32 * WP + half * 16;
+#pragma unroll
+        for (int r = 0; r < 7; ++r)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                wreg[r][hh][0] = *reinterpret_cast<const u32x4_s *>(wrow + r * 64 + hh * 32);
+                wreg[r][hh][1] = *reinterpret_cast<const u32x4_s *>(wrow + 32 * WP + r * 64 + hh * 32);
+            }
+    }
+    const int trow = lane >> 3, tseg = lane & 7;
+    float sc[8], sh[8];                             // of channels 8 tseg .. + 8, the ones this lane finishes
+    {
+        const f32x4_s s0 = *reinterpret_cast<const f32x4_s *>(a.scale + tseg * 8), s1 = *reinterpret_cast<const f32x4_s *>(a.scale + tseg * 8 + 4);
+        const f32x4_s h0 = *reinterpret_cast<const f32x4_s *>(a.shift + tseg * 8), h1 = *reinterpret_cast<const f32x4_s *>(a.shift + tseg * 8 + 4);
+        sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w; sc[4] = s1.x; sc[5] = s1.y; sc[6] = s1.z; sc[7] = s1.w;
+        sh[0] = h0.x; sh[1] = h0.y; sh[2] = h0.z; sh[3] = h0.w; sh[4] = h1.x; sh[5] = h1.y; sh[6] = h1.z; sh[7] = h1.w;
     }
 
-    const int prow = 2 * wv + (l32 >> 4), pcol = l32 & 15;     // this lane's pixel in the tile
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int n = tile / (tiles_p * tiles_q), t2 = tile - n * tiles_p * tiles_q;
-        const int p0 = (t2 / tiles_q) * 8, q0 = (t2 % tiles_q) * 16;
-        __syncthreads();                          // previous tile's patch is no longer read
-        for (int e = tid; e < kStemPRows * kStemPCols; e += 256) {
-            const int i = e / kStemPCols, j = e - i * kStemPCols;
-            const int h = 2 * p0 - 3 + i, w = 2 * q0 - 3 + j;
+    // ---- input staging.  Aligned form: task (row i, group g) = 8 pixels, three per thread and tile.
+    u32x4_s pre[3][3];
+    auto tile_origin = [&](int tile, int &n, int &p0, int &q0) {
+        n = tile / (tiles_p * tiles_q);
+        const int t2 = tile - n * tiles_p * tiles_q;
+        p0 = (t2 / tiles_q) * kStemRO;
+        q0 = (t2 % tiles_q) * kStemCQ;
+    };
+    // Every thread issues its three loads unconditionally (pieces outside the image or past the task list
+    // read the first bytes of the image instead and are zeroed when they are written to LDS): nothing
+    // depends on the loaded registers until then, so the loads stay in flight under the MFMAs.
+    uint32_t pre_ok = 0;
+    auto request = [&](int tile) {                   // aligned form only
+        int n, p0, q0;
+        tile_origin(tile, n, p0, q0);
+        pre_ok = 0;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const int idx = tid + 256 * t;
+            const int i = idx / kStemGroups, g = idx - i * kStemGroups;
+            const int h = 2 * p0 - 3 + i, w0 = 2 * q0 - 8 + 8 * g;
+            const bool ok = idx < kStemTasks && (unsigned)h < (unsigned)a.H && w0 >= 0 && w0 + 8 <= a.W;
+            pre_ok |= ok ? 1u << t : 0u;
+            const u32x4_s *src = reinterpret_cast<const u32x4_s *>(xg + ((size_t)((size_t)n * a.H + (ok ? h : 0)) * a.W + (ok ? w0 : 0)) * 3);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) pre[t][q] = src[q];
+        }
+    };
+    auto deposit = [&]() {                           // 24 bf16 = 8 pixels x 3 channels -> 8 x (3 channels + 0)
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const int idx = tid + 256 * t;
+            if (idx >= kStemTasks) continue;
+            const int i = idx / kStemGroups, g = idx - i * kStemGroups;
+            const uint32_t keep = (pre_ok >> t) & 1u ? 0xFFFFFFFFu : 0u;
+            const uint32_t d[12] = {pre[t][0].x & keep, pre[t][0].y & keep, pre[t][0].z & keep, pre[t][0].w & keep,
+                                    pre[t][1].x & keep, pre[t][1].y & keep, pre[t][1].z & keep, pre[t][1].w & keep,
+                                    pre[t][2].x & keep, pre[t][2].y & keep, pre[t][2].z & keep, pre[t][2].w & keep};
+            unsigned char *dst = patch + i * kStemPPitch + (3 + 8 * g) * 8;
+#pragma unroll
+            for (int px = 0; px < 8; ++px) {
+                // elements 3 px, 3 px + 1, 3 px + 2 of the 24
+                const int e0 = 3 * px;
+                uint32_t lo, hi;
+                if (e0 & 1) {                        // starts in the upper half of a dword
+                    lo = (d[e0 >> 1] >> 16) | (d[(e0 >> 1) + 1] << 16);
+                    hi = d[(e0 >> 1) + 1] >> 16;
+                } else {
+                    lo = d[e0 >> 1];
+                    hi = d[(e0 >> 1) + 1] & 0xFFFFu;
+                }
+                *reinterpret_cast<u32x2_s *>(dst + px * 8) = u32x2_s{lo, hi};
+            }
+        }
+    };
+    auto stage_any = [&](int tile) {                 // any width: one pixel per thread and step
+        int n, p0, q0;
+        tile_origin(tile, n, p0, q0);
+        constexpr int COLS = 8 * kStemGroups;
+        for (int e = tid; e < kStemPRows * COLS; e += 256) {
+            const int i = e / COLS, j = e - i * COLS;
+            const int h = 2 * p0 - 3 + i, w = 2 * q0 - 8 + j;
             u32x2_s v = {0u, 0u};
             if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W) {
                 const uint16_t *px = xg + ((size_t)((size_t)n * a.H + h) * a.W + w) * 3;
                 v.x = (uint32_t)px[0] | ((uint32_t)px[1] << 16);
                 v.y = (uint32_t)px[2];
             }
-            *reinterpret_cast<u32x2_s *>(patch + i * kStemPPitch + j * 8) = v;
+            *reinterpret_cast<u32x2_s *>(patch + i * kStemPPitch + (3 + j) * 8) = v;
         }
-        __syncthreads();
+    };
 
-        f32x16_s acc[2];
+    int tile = blockIdx.x;
+    if (aligned && tile < ntiles) request(tile);
+    for (; tile < ntiles; tile += gridDim.x) {
+        int n, p0, q0;
+        tile_origin(tile, n, p0, q0);
+        __syncthreads();                             // the previous tile's patch (or the weights) is no longer read
+        if (aligned) deposit(); else stage_any(tile);
+        __syncthreads();
+        if (aligned && tile + (int)gridDim.x < ntiles) request(tile + gridDim.x);   // in flight under the MFMAs
+
+        // ---- 28 units of 2 rows x 16 columns, seven per wavefront
+        for (int j = 0; j < 7; ++j) {
+            const int unit = wv + 4 * j, ur = unit / 7, uc = unit - ur * 7;
+            if (p0 + 2 * ur >= a.P || q0 + 16 * uc >= a.Q) continue;          // the same for the whole wavefront
+            const int prow = 2 * ur + (l32 >> 4), pcol = 16 * uc + (l32 & 15);
+            f32x16_s acc[2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-        const unsigned char *xrow = patch + (2 * prow) * kStemPPitch + pcol * 16 + half * 16;
-        const unsigned char *wrow = wl + l32 * kStemWPitch + half * 16;
+                for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+            const unsigned char *xrow = patch + (2 * prow) * kStemPPitch + pcol * 16 + 64 + half * 16;
+            // the pixel operand of step k + 4 is requested before step k is multiplied (a ring of four):
+            // with two wavefronts per SIMD one read ahead does not cover the LDS latency
+            u32x4_s xq[4];
 #pragma unroll
-        for (int r = 0; r < 7; ++r)
+            for (int k = 0; k < 4; ++k)
+                xq[k] = *reinterpret_cast<const u32x4_s *>(xrow + (k >> 1) * kStemPPitch + (k & 1) * 32);
+            __builtin_amdgcn_sched_barrier(0);       // (the scheduler would otherwise pull the reads back to one step ahead)
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                const u32x4_s xb = *reinterpret_cast<const u32x4_s *>(xrow + r * kStemPPitch + hh * 32);
-                const u32x4_s w0 = *reinterpret_cast<const u32x4_s *>(wrow + r * 64 + hh * 32);
-                const u32x4_s w1 = *reinterpret_cast<const u32x4_s *>(wrow + 32 * kStemWPitch + r * 64 + hh * 32);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_s, w0),
+            for (int k = 0; k < 14; ++k) {
+                const u32x4_s xb = xq[k & 3];
+                if (k + 4 < 14)
+                    xq[k & 3] = *reinterpret_cast<const u32x4_s *>(xrow + ((k + 4) >> 1) * kStemPPitch + ((k + 4) & 1) * 32);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_s, wreg[k >> 1][k & 1][0]),
                                                                  __builtin_bit_cast(bf16x8_s, xb), acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_s, w1),
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_s, wreg[k >> 1][k & 1][1]),
                                                                  __builtin_bit_cast(bf16x8_s, xb), acc[1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-        const int p = p0 + prow, q = q0 + pcol;
-        const bool valid = p < a.P && q < a.Q;
-        unsigned char *yrow = static_cast<unsigned char *>(a.y) +
-                              ((size_t)((size_t)n * a.P + (valid ? p : 0)) * a.Q + (valid ? q : 0)) * 128;
+            // acc[u][4 rb + e] = channel 32 u + 8 rb + 4 half + e of pixel l32 -> fp32 rows in the private tile
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int cb = u * 32;
-            float v[16];
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const f32x4_s sc = *reinterpret_cast<const f32x4_s *>(a.scale + cb + 8 * rb + 4 * half);
-                const f32x4_s sh = *reinterpret_cast<const f32x4_s *>(a.shift + cb + 8 * rb + 4 * half);
-                v[4 * rb + 0] = acc[u][4 * rb + 0] * sc.x + sh.x;
-                v[4 * rb + 1] = acc[u][4 * rb + 1] * sc.y + sh.y;
-                v[4 * rb + 2] = acc[u][4 * rb + 2] * sc.z + sh.z;
-                v[4 * rb + 3] = acc[u][4 * rb + 3] * sc.w + sh.w;
-            }
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2) {
-                float o[8];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]),
-                                                               __float_as_uint(v[8 * i2 + 4 + j]), false, false);
-                    o[j] = __uint_as_float(r2[0]);
-                    o[4 + j] = __uint_as_float(r2[1]);
+                for (int rb = 0; rb < 4; ++rb) {
+                    const f32x4_s v = {acc[u][4 * rb], acc[u][4 * rb + 1], acc[u][4 * rb + 2], acc[u][4 * rb + 3]};
+                    *reinterpret_cast<f32x4_s *>(ttile + l32 * kStemTPitch + (u * 32 + 8 * rb + 4 * half) * 4) = v;
                 }
+            // (LDS instructions of one wavefront execute in order; the fences only keep the compiler from
+            // moving accesses across the exchange)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int pr = trow + 8 * t;         // pixel of the unit: row pr / 16, column pr % 16
+                const f32x4_s f0 = *reinterpret_cast<const f32x4_s *>(ttile + pr * kStemTPitch + tseg * 32);
+                const f32x4_s f1 = *reinterpret_cast<const f32x4_s *>(ttile + pr * kStemTPitch + tseg * 32 + 16);
+                float o[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = o[e] * sc[e] + sh[e];
                 if (a.relu) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) o[e] = o[e] < 0.f ? 0.f : o[e];
                 }
-                u32x4_s out;
-                out.x = pack2s(o[0], o[1]); out.y = pack2s(o[2], o[3]);
-                out.z = pack2s(o[4], o[5]); out.w = pack2s(o[6], o[7]);
-                if (valid) *reinterpret_cast<u32x4_s *>(yrow + (cb + 16 * i2 + 8 * half) * 2) = out;
+                u32x4_s o4;
+                o4.x = pack2s(o[0], o[1]); o4.y = pack2s(o[2], o[3]);
+                o4.z = pack2s(o[4], o[5]); o4.w = pack2s(o[6], o[7]);
+                const int p = p0 + 2 * ur + (pr >> 4), q = q0 + 16 * uc + (pr & 15);
+                if (p < a.P && q < a.Q)
+                    *reinterpret_cast<u32x4_s *>(static_cast<unsigned char *>(a.y) +
+                                                 ((size_t)((size_t)n * a.P + p) * a.Q + q) * 128 + tseg * 16) = o4;
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
 }
@@ -151,11 +273,13 @@ const char *stem_check(const ConvArgs &a) {
 
 hipError_t launch_stem(const ConvArgs &a, hipStream_t stream) {
     if (!stem_applies(a) || stem_check(a)) return hipErrorInvalidValue;
-    const int tiles_p = (a.P + 7) / 8, tiles_q = (a.Q + 15) / 16;
+    const int tiles_p = (a.P + kStemRO - 1) / kStemRO, tiles_q = (a.Q + kStemCQ - 1) / kStemCQ;
     const long long ntiles = (long long)a.N * tiles_p * tiles_q;
-    if (ntiles <= 0 || ntiles > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    const int grid = (int)(ntiles < 1024 ? ntiles : 1024);
-    stem7x7_kernel<<<dim3(grid), dim3(256), 0, stream>>>(a, tiles_p, tiles_q, (int)ntiles);
+    if (ntiles <= 0 || ntiles > 0x3FFFFFFFLL) return hipErrorInvalidValue;
+    const int grid = (int)(ntiles < 512 ? ntiles : 512);            // two workgroups per CU
+    // whole 16-byte runs of 8 pixels: rows start 16-byte aligned when the width is a multiple of 8
+    const int aligned = a.W % 8 == 0 && ((uintptr_t)a.x & 15) == 0;
+    stem7x7_kernel<<<dim3(grid), dim3(256), 0, stream>>>(a, tiles_p, tiles_q, (int)ntiles, aligned);
     return hipGetLastError();
 }
 
