@@ -23,9 +23,11 @@
 //    same speed, this is 4-9 % faster on the encoder's and ResNet's shapes; with the loads switched
 //    off the loop runs at 1.3-1.5 PFLOP/s and removing the barrier changes nothing: what holds the
 //    kernel at about 1 PFLOP/s is the delivery of the operands from L2, not the barrier or LDS (LDS
-//    reads are a quarter of the cycles by the counters).  Also measured and slower: the loads of a
-//    slice spread over its four steps instead of issued at its start (5-8 %), and x three slices deep
-//    with w two deep in the same 160 KB (3-8 %);
+//    reads are a quarter of the cycles by the counters).  Re-measured inside ResNet-50's forward
+//    pass, where a layer's operands come from HBM rather than the caches: slices of 32 through four
+//    buffers, three of them in flight, were again 1 % slower.  Also measured and slower: the loads
+//    of a slice spread over its four steps instead of issued at its start (5-8 %), and x three
+//    slices deep with w two deep in the same 160 KB (3-8 %);
 //  * a tile row is 128 bytes = 8 pieces of 16; piece p of row r lives in slot p ^ ((r >> 1) & 7):
 //    the direct loads fix where a LANE's 16 bytes land, so the swizzle is applied to the global
 //    address each lane fetches; 16 lanes reading one piece of 16 consecutive rows then touch all
