@@ -25,8 +25,10 @@
 // column axis; lane half h owns bytes [64h, 64h + 64) of every 128-byte slice of both operands.
 // The order of every sum is fixed and does not depend on which tensors are stored, so whatever
 // this kernel produced in the forward pass it reproduces bit for bit in a recomputation.
-// (It does not promise the bits of the three per-layer kernels: a tensor is produced and
-// regenerated by one family of kernels only.)
+// Every reduction also runs in the order of the per-layer kernels (slices of the input channels in order,
+// the 3x3's taps in order, lane half h supplying bytes [64 h, 64 h + 64) of each 128-byte operand slice),
+// so the three tensors carry the bits the three per-layer launches produce: a plan may regenerate a
+// tensor with either.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -315,7 +317,26 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
     }
     if (!need3) return;
 
-    // ---- phase 3: out = relu(bn3(w3 . a2) + x), 64 output channels at a time
+    // ---- phase 3: out = relu(bn3(w3 . a2) + x), 64 output channels at a time.
+    // The two lanes of a pixel first trade pieces so that lane half h holds channels 32 h .. 32 h + 32 in
+    // order (bytes [64 h, 64 h + 64) of the a2 row, as a kernel that reads a2 from memory would): step j of
+    // the reduction then multiplies channels 8 j .. + 8 and 32 + 8 j .. + 8, the same sixteen products per
+    // MFMA, in the same order, as the per-layer 1x1 kernel - and so the same bits.
+    //   before: half 0 holds [0,8) [16,24) [32,40) [48,56), half 1 holds [8,16) [24,32) [40,48) [56,64)
+    //   after:  half 0 holds [0,8) [16,24) [8,16) [24,32),  half 1 holds [32,40) [48,56) [40,48) [56,64)
+    {
+        auto trade = [](u32x4 &lo_keeps, u32x4 &hi_keeps) {   // upper half of the first <-> lower half of the second
+            uint32_t *pa = reinterpret_cast<uint32_t *>(&lo_keeps), *pb = reinterpret_cast<uint32_t *>(&hi_keeps);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                auto r = __builtin_amdgcn_permlane32_swap(pa[e], pb[e], false, false);
+                pa[e] = r[0];
+                pb[e] = r[1];
+            }
+        };
+        trade(a2p[0][0], a2p[1][0]);
+        trade(a2p[0][1], a2p[1][1]);
+    }
     const bool mine = pi < BM && pm < M;
     const long long rm = mine ? pm : (M - 1);            // clamp: the shortcut loads stay in bounds
     const unsigned char *xres = xg + (size_t)rm * (kCin * 2);
@@ -336,17 +357,15 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-        const unsigned char *wrow = rc + (g * 64 + l32) * kPitch + half * 16;
+        const unsigned char *wrow = rc + (g * 64 + l32) * kPitch + half * 64;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2) {
-                // the piece holds channels 32 u + 16 i2 + 8 half .. + 8: the weight rows supply the same ones
-                const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + u * 64 + i2 * 32);
-                const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kPitch + u * 64 + i2 * 32);
-                acc[0] = mma(w0, a2p[u][i2], acc[0]);
-                acc[1] = mma(w1, a2p[u][i2], acc[1]);
-            }
+        for (int j = 0; j < 4; ++j) {
+            // step j: channels 32 half + 8 j .. + 8 - after the trade that is piece [j & 1][j >> 1]
+            const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + j * 16);
+            const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kPitch + j * 16);
+            acc[0] = mma(w0, a2p[j & 1][j >> 1], acc[0]);
+            acc[1] = mma(w1, a2p[j & 1][j >> 1], acc[1]);
+        }
         u32x4 piece[2][2];
         finish_tiles<true>(acc, f3s + g * 64, f3h + g * 64, half, rv, piece);
 #pragma unroll

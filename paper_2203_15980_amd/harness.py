@@ -95,6 +95,34 @@ class Net:
             self.shapes["loss"], self.np_dtype["loss"] = (1,), np.float32
         self.all_layers = B.layer_array(order)
         self.by_tensor = {self.ids[l.y]: l for l in layers}
+        # identity bottlenecks the block kernel takes (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + input, ReLU
+        # after each, bf16, rows of at most 223 pixels): its tensors carry the bits of the per-layer kernels,
+        # so wherever all three layers run back to back they run as one launch
+        self.blocks = {}
+        self._block_descs = {}
+        by_y = {l.y: l for l in layers}
+        for l in layers:
+            if not l.y.endswith(".a1") or dtype != "bf16":
+                continue
+            pre = l.y[:-3]
+            a2, out = by_y.get(pre + ".a2"), by_y.get(pre + ".out")
+            if a2 is None or out is None:
+                continue
+            if (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) != ("conv", 1, 1, 256, 64, True):
+                continue
+            if (a2.kind, a2.R, a2.stride, a2.pad, a2.Cin, a2.Cout, a2.relu, a2.x) != ("conv", 3, 1, 1, 64, 64, True, l.y):
+                continue
+            if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, l.x):
+                continue
+            if l.W > 223:
+                continue
+            self.blocks[pre] = (l.y, a2.y, out.y)
+        fused = B.layer_array([B.LayerDesc.from_buffer_copy(dsc) for dsc in order])
+        pos = {l.y: i for i, l in enumerate(layers)}
+        for pre, (n1, n2, n3) in self.blocks.items():
+            if pos[n2] == pos[n1] + 1 and pos[n3] == pos[n2] + 1:
+                fused[pos[n1]].fuse = B.FUSE_BLOCK
+        self.all_layers_fused = fused
         torch.cuda.synchronize()
 
     # -- raw access to arena contents
@@ -120,7 +148,7 @@ class Net:
     def forward(self):
         """Inputs plus every layer (and the loss when present), nothing released."""
         self.load_input()
-        self.delta.recompute_segment(self.all_layers)
+        self.delta.recompute_segment(self.all_layers_fused)
         if "loss" in self.desc:
             self.load_source(self.ids["labels"])
             self.delta.recompute_segment(self.desc["loss"])
@@ -130,12 +158,20 @@ class Net:
 
     def block_desc(self, prefix, store=None):
         """The three layers `prefix`.a1 / .a2 / .out of an identity bottleneck as one launch of the
-        block kernel; `store`: the tensor names to write (default: all three)."""
+        block kernel; `store`: the tensor names to write (default: all three).  A fresh array each time."""
         names = [prefix + ".a1", prefix + ".a2", prefix + ".out"]
         store = names if store is None else store
         arr = B.layer_array([B.LayerDesc.from_buffer_copy(self.desc[n][0]) for n in names])
         for i, n in enumerate(names):
             arr[i].fuse = (B.FUSE_BLOCK if i == 0 else 0) | (0 if n in store else B.FUSE_NO_STORE)
+        return arr
+
+    def _block_launch(self, prefix, stored):
+        """`block_desc` for the first `stored` tensors of the block, built once (replays call it per step)."""
+        key = (prefix, stored)
+        arr = self._block_descs.get(key)
+        if arr is None:
+            arr = self._block_descs[key] = self.block_desc(prefix, store=list(self.blocks[prefix][:stored]))
         return arr
 
     # -- backward pass
@@ -386,28 +422,64 @@ class Net:
 def run_plan(net, graph, events, backward_proxy=None):
     """One training-step replay.  Forward steps run their layer, backward steps call
     `backward_proxy(step_index)` when given; the plan's events are applied around them in
-    issue order (everything of a step before it runs, FREE after)."""
+    issue order (everything of a step before it runs, FREE after).
+    Where the three layers of an identity bottleneck that the block kernel takes run back to back with
+    nothing of the plan between them - three forward steps without events, or three RECOMPUTE events in
+    a row - they run as one launch (the same bits, `Net.blocks`)."""
     d = net.delta
     by_step = {}
     for (k, a, t) in events:
         by_step.setdefault(k, []).append((a, t))
     names = [t["name"] for t in graph.tensors]
-    for k, st in enumerate(graph.steps):
+    blocks = getattr(net, "blocks", {})
+    first_of = {net.ids[n1]: pre for pre, (n1, _, _) in blocks.items()}
+    steps = graph.steps
+    fused_away = set()                              # forward steps whose tensor an earlier block launch produced
+    for k, st in enumerate(steps):
         post = []
-        for (a, t) in by_step.get(k, ()):
+        evs = by_step.get(k, ())
+        i = 0
+        while i < len(evs):
+            a, t = evs[i]
             if a == B.EV_FREE:
                 post.append(t)
             elif a in (B.EV_EVICT, B.EV_OFFLOAD, B.EV_DROP_TEMP):
                 d.release(t, a)
             elif a == B.EV_RECOMPUTE:
+                pre = first_of.get(t)
+                chain = [net.ids[n] for n in blocks[pre]] if pre is not None else []
+                run = 0
+                while run < len(chain) and i + run < len(evs) and evs[i + run] == (B.EV_RECOMPUTE, chain[run]):
+                    run += 1
+                if run >= 2:                        # a1 + a2 (+ out) regenerated from the block's input in one launch
+                    d.recompute_segment(net._block_launch(pre, run))
+                    i += run
+                    continue
                 d.recompute_segment(net.desc[names[t]])
             else:
                 d.prefetch(t)
-        if st["produces"] >= 0:
-            if st["produces"] in net.sources:
-                net.load_source(st["produces"])
+            i += 1
+        p = st["produces"]
+        if p >= 0:
+            if p in net.sources:
+                net.load_source(p)
+            elif k in fused_away:
+                pass
             else:
-                d.recompute_segment(net.desc[names[st["produces"]]])
+                pre = first_of.get(p)
+                fuse = False
+                if pre is not None and k + 2 < len(steps):
+                    c = [net.ids[n] for n in blocks[pre]]
+                    # the next two steps produce a2 and out, the plan does nothing before them and frees
+                    # nothing after this step and the next: the block's memory is the same two steps early
+                    fuse = (steps[k + 1]["produces"] == c[1] and steps[k + 2]["produces"] == c[2] and not post
+                            and not by_step.get(k + 1)
+                            and all(a == B.EV_FREE for (a, _) in by_step.get(k + 2, ())))
+                if fuse:
+                    d.recompute_segment(net._block_launch(pre, 3))
+                    fused_away.update((k + 1, k + 2))
+                else:
+                    d.recompute_segment(net.desc[names[p]])
         elif backward_proxy is not None:
             backward_proxy(k)
         for t in post:

@@ -40,6 +40,27 @@ def _rel(got, ref):
     return float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
 
 
+def test_block_kernel_carries_the_bits_of_the_per_layer_kernels(torch_mod):
+    """The same three tensors from three per-layer launches and from one block launch: equal bit for bit
+    (every reduction runs in the same order), so a plan may mix the two."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    for shape in [(2, 7, 7), (3, 9, 11), (8, 56, 56)]:
+        print("shape", shape, flush=True)
+        d, net, layers = _net(torch, *shape)
+        net.load_input()
+        d.recompute_segment(net.all_layers)
+        d.sync()
+        per_layer = {n: net.read(n).copy() for n in NAMES}
+        for n in NAMES:
+            d.release(net.ids[n], dl.EV_EVICT)
+        d.recompute_segment(net.block_desc("blk"))
+        d.sync()
+        for n in NAMES:
+            assert np.array_equal(net.read(n), per_layer[n]), (shape, n)
+        d.close()
+
+
 SHAPES = [(2, 7, 7), (1, 14, 14), (3, 9, 11), (1, 1, 1), (2, 3, 100), (1, 5, 223), (5, 56, 56)]
 
 
