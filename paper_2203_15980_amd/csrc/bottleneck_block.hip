@@ -44,19 +44,19 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kWaves = 16, kThreads = kWaves * 64;
+static constexpr int kWaves = 8, kThreads = kWaves * 64;
 static constexpr int kCin = 256, kMid = 64, kCout = 256;
+static constexpr int kT = 14;                            // output tile: 14 x 14 pixels, its a1 halo 16 x 16 positions
 static constexpr int kPitch = 144;                       // 128-byte rows, 4 banks apart
 static constexpr int kW1Pitch = kCin * 2 + 16;           // 528
-static constexpr int kMaxHaloTiles = 16;                 // one 32-row tile of phase 1 per wavefront
 static constexpr int kTap = kMid * kPitch;               // one 64 x 64 tap of w2 in LDS: 9216 bytes
-static constexpr int kRA = (kMaxHaloTiles * 32 + 1) * kPitch;      // a1 rows + the zero row; later the store tiles
-static constexpr int kRB = 4 * kTap;                                // w1, then taps 5-8
-static constexpr int kRC = 5 * kTap;                                // taps 0-4, then w3
+static constexpr int kRA = 256 * kPitch;                 // the a1 halo tile; later one store tile per wavefront
+static constexpr int kRB = kCout * kPitch;               // w1, then three taps of w2 at a time, then w3
 static constexpr int kRD = (2 * kMid + 2 * kMid + 2 * kCout) * 4;   // scale/shift of the three layers
-static constexpr int kLds = kRA + kRB + kRC + kRD;
-static_assert(kW1Pitch * kMid <= kRB && kCout * kPitch <= kRC && kWaves * 32 * kPitch <= kRA, "LDS regions");
-static_assert(kLds <= 160 * 1024, "LDS budget of a CU");
+static constexpr int kLds = kRA + kRB + kRD;
+static_assert(kW1Pitch * kMid <= kRB && 3 * kTap <= kRB && kWaves * 32 * kPitch <= kRA, "LDS regions");
+static_assert(2 * kLds <= 160 * 1024, "two workgroups per CU");
+static_assert(kWaves * 32 == 256 && (kT + 2) * (kT + 2) == 256 && kT * kT <= (kWaves - 1) * 32, "tile geometry");
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     const f32x2 v = {lo, hi};
@@ -117,13 +117,12 @@ __device__ __forceinline__ void finish_tiles(const f32x16 (&acc)[2], const float
     }
 }
 
-// BM: pixels per workgroup; NT1 = ceil((BM + 2W + 2) / 32) <= 16 halo tiles; NT2 = ceil(BM / 32) <= 16.
-__global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a, int BM, int NT1, int NT2) {
+// One workgroup: the 14 x 14 output pixels (ty, tx) of image n.
+__global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs a, int tiles_y, int tiles_x) {
     extern __shared__ __align__(16) unsigned char lds[];
-    unsigned char *ra = lds;
-    unsigned char *rb = lds + kRA;
-    unsigned char *rc = rb + kRB;
-    float *f1s = reinterpret_cast<float *>(rc + kRC), *f1h = f1s + kMid, *f2s = f1h + kMid, *f2h = f2s + kMid,
+    unsigned char *ra = lds;                             // a1 halo tile, later the store tiles
+    unsigned char *rb = lds + kRA;                       // w1, then three taps of w2 at a time, then w3
+    float *f1s = reinterpret_cast<float *>(rb + kRB), *f1h = f1s + kMid, *f2s = f1h + kMid, *f2h = f2s + kMid,
           *f3s = f2h + kMid, *f3h = f3s + kCout;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -134,30 +133,35 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
         const unsigned xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
         logical = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
     }
-    const int W = a.W, HW = a.H * a.W, M = a.M;
-    const long long m0 = (long long)logical * BM;
+    const int H = a.H, W = a.W;
+    const int per_image = tiles_y * tiles_x;
+    const int n = (int)(logical / (unsigned)per_image), t2 = (int)(logical - (unsigned)n * per_image);
+    const int y0 = (t2 / tiles_x) * kT, x0 = (t2 % tiles_x) * kT;
     const bool need2 = a.a2 != nullptr || a.out != nullptr;
     const bool need3 = a.out != nullptr;
-    const int zrow = NT1 * 32;                           // the row of zeros behind the a1 rows
-
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
+    const size_t image = (size_t)n * H * W;
 
-    // ---- phase 1 operand: the x rows of halo tile wv, in flight before anything is staged.
-    // Row i of the a1 tile is pixel m0 - (W + 1) + i.  Without the 3x3 only the tile's own pixels count.
-    const int own_lo = W + 1, own_hi = W + 1 + BM;       // rows [own_lo, own_hi) are this workgroup's pixels
-    const bool p1 = wv < NT1 && (need2 || (wv * 32 < own_hi && wv * 32 + 32 > own_lo));
+    // ---- phase 1 operand: halo position hp = 32 wv + l32 is pixel (y0 - 1 + hp / 16, x0 - 1 + hp % 16);
+    // its x row goes into flight before anything is staged.  Positions outside the image hold zeros
+    // (the 3x3's padding), whatever w1 . x would give there.
+    const int hp = wv * 32 + l32, hy = hp >> 4, hx = hp & 15;
+    const int py = y0 - 1 + hy, px = x0 - 1 + hx;
+    const bool inside = (unsigned)py < (unsigned)H && (unsigned)px < (unsigned)W;
+    // without the 3x3 only the tile's own pixels count
+    const bool own = inside && hy >= 1 && hy <= kT && hx >= 1 && hx <= kT;
+    const bool p1 = __builtin_amdgcn_ballot_w64(need2 ? inside : own) != 0;      // this wavefront has a position to compute
     u32x4 xf[4][4];
     if (p1) {
-        long long q = m0 - (W + 1) + wv * 32 + l32;
-        q = q < 0 ? 0 : (q >= M ? (long long)M - 1 : q);                 // clamped rows are never read back
-        const unsigned char *xp = xg + (size_t)q * (kCin * 2) + half * 64;
+        const size_t q = image + (size_t)(inside ? py : 0) * W + (inside ? px : 0);      // clamped rows are overwritten by zeros
+        const unsigned char *xp = xg + q * (kCin * 2) + half * 64;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int j = 0; j < 4; ++j) xf[s][j] = *reinterpret_cast<const u32x4 *>(xp + s * 128 + j * 16);
     }
 
-    // ---- stage w1, the batch-norm factors, the zero row and (for the 3x3) taps 0-4 of w2
+    // ---- stage w1 and the batch-norm factors
     {
         const unsigned char *w1g = static_cast<const unsigned char *>(a.w1);
         for (int c = tid; c < kMid * 32; c += kThreads) {                 // 32 pieces of 16 bytes per row
@@ -169,135 +173,151 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
             f2s[tid] = a.s2[tid]; f2h[tid] = a.h2[tid];
         }
         if (tid < kCout) { f3s[tid] = a.s3[tid]; f3h[tid] = a.h3[tid]; }
-        if (tid < 9) *reinterpret_cast<u32x4 *>(ra + zrow * kPitch + tid * 16) = u32x4{0u, 0u, 0u, 0u};
-        if (need2) {
-            const unsigned char *w2g = static_cast<const unsigned char *>(a.w2);
-            for (int c = tid; c < 5 * kMid * 8; c += kThreads) {          // (tap, k, seg)
-                const int tap = c / (kMid * 8), rest = c - tap * (kMid * 8), k = rest >> 3, seg = rest & 7;
-                *reinterpret_cast<u32x4 *>(rc + tap * kTap + k * kPitch + seg * 16) =
-                    *reinterpret_cast<const u32x4 *>(w2g + ((size_t)(k * 9 + tap) * 8 + seg) * 16);
-            }
-        }
     }
     __syncthreads();
 
-    // ---- phase 1: a1 = relu(bn1(w1 . x)) for one halo tile per wavefront, into LDS
-    if (p1) {
-        f32x16 acc[2];
+    // The weights of the later phases are requested as early as registers allow, so that their latency is
+    // paid under the phases before them: taps 0-2 now, taps 3-8 and w3 as soon as phase 1 has freed x.
+    const unsigned char *w2g = static_cast<const unsigned char *>(a.w2);
+    auto fetch_taps = [&](int first, u32x4 (&dst)[3]) {   // 3 taps x 64 rows x 8 pieces = 1536 pieces, three per thread
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int j = 0; j < 3; ++j) {
+            const int c = tid + j * kThreads;
+            const int tap = first + c / (kMid * 8), rest = c % (kMid * 8), k = rest >> 3, seg = rest & 7;
+            dst[j] = *reinterpret_cast<const u32x4 *>(w2g + ((size_t)(k * 9 + tap) * 8 + seg) * 16);
+        }
+    };
+    auto deposit_taps = [&](const u32x4 (&src)[3]) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-        const unsigned char *wrow = rb + l32 * kW1Pitch + half * 64;
+        for (int j = 0; j < 3; ++j) {
+            const int c = tid + j * kThreads;
+            const int t = c / (kMid * 8), rest = c % (kMid * 8), k = rest >> 3, seg = rest & 7;
+            *reinterpret_cast<u32x4 *>(rb + t * kTap + k * kPitch + seg * 16) = src[j];
+        }
+    };
+    u32x4 wq0[3], wq1[3], wq2[3], w3q[4];
+    if (need2) fetch_taps(0, wq0);
+
+    // ---- phase 1: a1 = relu(bn1(w1 . x)) for one 32-position tile per wavefront, into LDS
+    {
+        u32x4 piece[2][2] = {};
+        if (p1) {
+            f32x16 acc[2];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + s * 128 + j * 16);
-                const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kW1Pitch + s * 128 + j * 16);
-                acc[0] = mma(w0, xf[s][j], acc[0]);
-                acc[1] = mma(w1, xf[s][j], acc[1]);
+                for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+            const unsigned char *wrow = rb + l32 * kW1Pitch + half * 64;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + s * 128 + j * 16);
+                    const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kW1Pitch + s * 128 + j * 16);
+                    acc[0] = mma(w0, xf[s][j], acc[0]);
+                    acc[1] = mma(w1, xf[s][j], acc[1]);
+                }
+            finish_tiles<false>(acc, f1s, f1h, half, nullptr, piece);
+        }
+        if (need2) {
+            fetch_taps(3, wq1);
+            fetch_taps(6, wq2);
+            if (need3) {
+                const unsigned char *w3g = static_cast<const unsigned char *>(a.w3);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)              // 256 rows x 8 pieces = 2048 pieces: four per thread
+                    w3q[j] = *reinterpret_cast<const u32x4 *>(w3g + (size_t)(tid + j * kThreads) * 16);
             }
-        u32x4 piece[2][2];
-        finish_tiles<false>(acc, f1s, f1h, half, nullptr, piece);
-        unsigned char *row = ra + (wv * 32 + l32) * kPitch;
+        }
+        unsigned char *row = ra + hp * kPitch;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int i2 = 0; i2 < 2; ++i2)
-                *reinterpret_cast<u32x4 *>(row + (u * 32 + 16 * i2 + 8 * half) * 2) = piece[u][i2];
+                *reinterpret_cast<u32x4 *>(row + (u * 32 + 16 * i2 + 8 * half) * 2) =
+                    (p1 && inside) ? piece[u][i2] : u32x4{0u, 0u, 0u, 0u};
     }
-    __syncthreads();
+    __syncthreads();                                     // the a1 tile is complete; w1 is dead
 
     // ---- a1 leaves as rows of 128 contiguous bytes (8 lanes per pixel), if it is stored
     if (a.a1) {
         unsigned char *a1g = static_cast<unsigned char *>(a.a1);
-        for (int c = tid; c < BM * 8; c += kThreads) {
-            const int i = c >> 3, seg = c & 7;
-            const long long m = m0 + i;
-            if (m < M)
-                *reinterpret_cast<u32x4 *>(a1g + (size_t)m * (kMid * 2) + seg * 16) =
-                    *reinterpret_cast<const u32x4 *>(ra + (own_lo + i) * kPitch + seg * 16);
+        for (int c = tid; c < kT * kT * 8; c += kThreads) {
+            const int i = c >> 3, seg = c & 7, iy = i / kT, ix = i - iy * kT;
+            if (y0 + iy < H && x0 + ix < W)
+                *reinterpret_cast<u32x4 *>(a1g + (image + (size_t)(y0 + iy) * W + x0 + ix) * (kMid * 2) + seg * 16) =
+                    *reinterpret_cast<const u32x4 *>(ra + ((iy + 1) * 16 + ix + 1) * kPitch + seg * 16);
         }
     }
     if (!need2) return;
 
-    // ---- phase 2: a2 = relu(bn2(conv3x3(a1))).  Taps 5-8 of w2 travel in registers while taps 0-4
-    // are multiplied, and land where w1 was; w3 travels while taps 5-8 are multiplied.
-    u32x4 wq[2];
-    {
-        const unsigned char *w2g = static_cast<const unsigned char *>(a.w2);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int c = tid + j * kThreads;                             // 4 taps x 64 rows x 8 pieces = 2048
-            const int tap = 5 + c / (kMid * 8), rest = c % (kMid * 8), k = rest >> 3, seg = rest & 7;
-            wq[j] = *reinterpret_cast<const u32x4 *>(w2g + ((size_t)(k * 9 + tap) * 8 + seg) * 16);
-        }
-    }
-    const bool p2 = wv < NT2;
-    const int pi = wv * 32 + l32;                        // this lane's pixel within the tile
-    const long long pm = m0 + pi;
-    uint32_t valid = 0;                                  // nine bits: tap inside the image
-    if (p2 && pi < BM && pm < M) {
-        const int hw = (int)(pm % HW), h = hw / W, w_ = hw - h * W;
-#pragma unroll
-        for (int r = 0; r < 3; ++r)
-#pragma unroll
-            for (int s = 0; s < 3; ++s)
-                if ((unsigned)(h + r - 1) < (unsigned)a.H && (unsigned)(w_ + s - 1) < (unsigned)W) valid |= 1u << (r * 3 + s);
-    }
+    // ---- phase 2: a2 = relu(bn2(conv3x3(a1))), three taps of w2 at a time through LDS (all nine, and w3,
+    // are already on their way in registers).
+    // This lane's output pixel: pi = 32 wv + l32 < 196 is pixel (pi / 14, pi % 14) of the tile.
+    const int pi = wv * 32 + l32;
+    const bool p2 = wv * 32 < kT * kT;                   // wavefronts 0 .. 6
+    const int iy = pi < kT * kT ? pi / kT : 0, ix = pi < kT * kT ? pi - (pi / kT) * kT : 0;   // lanes past the tile read row 0
+    const bool mine = pi < kT * kT && y0 + iy < H && x0 + ix < W;
     f32x16 acc2[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc2[u][e] = 0.f;
-    auto taps = [&](const unsigned char *wbase, int first, int count) {
 #pragma unroll
-        for (int t = 0; t < count; ++t) {
-            const int tap = first + t, r = tap / 3, s = tap - 3 * r;
-            const int row = ((valid >> tap) & 1u) ? pi + r * W + s : zrow;
-            const unsigned char *xp = ra + row * kPitch + half * 64;
-            const unsigned char *wp = wbase + t * kTap + l32 * kPitch + half * 64;
+    for (int g = 0; g < 3; ++g) {
+        deposit_taps(g == 0 ? wq0 : (g == 1 ? wq1 : wq2));   // the region is free: w1 / the previous taps are behind a barrier
+        __syncthreads();
+        if (p2) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const u32x4 xv = *reinterpret_cast<const u32x4 *>(xp + q * 16);
-                const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wp + q * 16);
-                const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wp + 32 * kPitch + q * 16);
-                acc2[0] = mma(w0, xv, acc2[0]);
-                acc2[1] = mma(w1, xv, acc2[1]);
+            for (int t = 0; t < 3; ++t) {
+                // tap 3 g + t is window position (g, t)
+                const unsigned char *xp = ra + ((iy + g) * 16 + ix + t) * kPitch + half * 64;
+                const unsigned char *wp = rb + t * kTap + l32 * kPitch + half * 64;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xp + q * 16);
+                    const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wp + q * 16);
+                    const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wp + 32 * kPitch + q * 16);
+                    acc2[0] = mma(w0, xv, acc2[0]);
+                    acc2[1] = mma(w1, xv, acc2[1]);
+                }
             }
         }
-    };
-    if (p2) taps(rc, 0, 5);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int c = tid + j * kThreads;
-        const int t = c / (kMid * 8), rest = c % (kMid * 8), k = rest >> 3, seg = rest & 7;
-        *reinterpret_cast<u32x4 *>(rb + t * kTap + k * kPitch + seg * 16) = wq[j];
+        __syncthreads();                                 // everyone is done with these taps (and, after the last, with a1)
     }
-    if (need3) {
-        const unsigned char *w3g = static_cast<const unsigned char *>(a.w3);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) wq[j] = *reinterpret_cast<const u32x4 *>(w3g + (size_t)(tid + j * kThreads) * 16);
-    }
-    __syncthreads();
-    if (p2) taps(rb, 5, 4);
     u32x4 a2p[2][2];                                     // this lane's pixel of a2: four pieces of 8 channels
     if (p2) finish_tiles<false>(acc2, f2s, f2h, half, nullptr, a2p);
-    if (need3) {
+    // the shortcut rows of the first two channel groups go into flight before the barrier that publishes w3
+    const size_t rm = image + (size_t)(mine ? y0 + iy : 0) * W + (mine ? x0 + ix : 0);   // clamp: the loads stay in bounds
+    const unsigned char *xres = xg + rm * (kCin * 2);
+    u32x4 rv[2][2][2];
+    auto load_res = [&](int g, u32x4 (&dst)[2][2]) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int c = tid + j * kThreads, row = c >> 3, seg = c & 7;  // 256 rows x 8 pieces
-            *reinterpret_cast<u32x4 *>(rc + row * kPitch + seg * 16) = wq[j];
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2)
+                dst[u][i2] = *reinterpret_cast<const u32x4 *>(xres + (size_t)(g * 64 + u * 32 + 16 * i2 + 8 * half) * 2);
+    };
+    if (need3) {
+        if (p2) { load_res(0, rv[0]); load_res(1, rv[1]); }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = tid + j * kThreads, row = c >> 3, seg = c & 7;
+            *reinterpret_cast<u32x4 *>(rb + row * kPitch + seg * 16) = w3q[j];
         }
     }
-    __syncthreads();                                     // a1 and w2 are dead from here on; w3 is in place
+    __syncthreads();                                     // w3 is in place
     if (!p2) return;
 
     unsigned char *ttile = ra + wv * (32 * kPitch);      // wavefront-private: pieces in, rows out
     const int trow = lane >> 3, tseg = lane & 7;
-    const long long mbase = m0 + wv * 32;
-    const int rows_here = BM - wv * 32;                  // rows of this tile that belong to the workgroup
+    // the pixels this lane stores rows of: pr = trow + 8 t of the wavefront's 32
+    long long srow[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int sp = wv * 32 + trow + 8 * t, sy = sp / kT, sx = sp - sy * kT;
+        srow[t] = sp < kT * kT && y0 + sy < H && x0 + sx < W ? (long long)(image + (size_t)(y0 + sy) * W + x0 + sx) : -1;
+    }
     if (a.a2) {
         unsigned char *a2g = static_cast<unsigned char *>(a.a2);
 #pragma unroll
@@ -308,10 +328,8 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
         wave_fence();
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int pr = trow + 8 * t;
-            const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + pr * kPitch + tseg * 16);
-            if (pr < rows_here && mbase + pr < M)
-                *reinterpret_cast<u32x4 *>(a2g + (size_t)(mbase + pr) * (kMid * 2) + tseg * 16) = o4;
+            const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + (trow + 8 * t) * kPitch + tseg * 16);
+            if (srow[t] >= 0) *reinterpret_cast<u32x4 *>(a2g + (size_t)srow[t] * (kMid * 2) + tseg * 16) = o4;
         }
         wave_fence();
     }
@@ -337,27 +355,15 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
         trade(a2p[0][0], a2p[1][0]);
         trade(a2p[0][1], a2p[1][1]);
     }
-    const bool mine = pi < BM && pm < M;
-    const long long rm = mine ? pm : (M - 1);            // clamp: the shortcut loads stay in bounds
-    const unsigned char *xres = xg + (size_t)rm * (kCin * 2);
     unsigned char *og = static_cast<unsigned char *>(a.out);
-    u32x4 rv[2][2];                                      // one group at a time: the MFMAs of the group cover the latency
-    auto load_res = [&](int g, u32x4 (&dst)[2][2]) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2)
-                dst[u][i2] = *reinterpret_cast<const u32x4 *>(xres + (size_t)(g * 64 + u * 32 + 16 * i2 + 8 * half) * 2);
-    };
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        load_res(g, rv);
         f32x16 acc[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-        const unsigned char *wrow = rc + (g * 64 + l32) * kPitch + half * 64;
+        const unsigned char *wrow = rb + (g * 64 + l32) * kPitch + half * 64;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             // step j: channels 32 half + 8 j .. + 8 - after the trade that is piece [j & 1][j >> 1]
@@ -367,7 +373,8 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
             acc[1] = mma(w1, a2p[j & 1][j >> 1], acc[1]);
         }
         u32x4 piece[2][2];
-        finish_tiles<true>(acc, f3s + g * 64, f3h + g * 64, half, rv, piece);
+        finish_tiles<true>(acc, f3s + g * 64, f3h + g * 64, half, rv[g & 1], piece);
+        if (g + 2 < 4) load_res(g + 2, rv[g & 1]);       // two groups ahead
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -376,16 +383,12 @@ __global__ __launch_bounds__(kThreads) void bottleneck_block_kernel(BlockArgs a,
         wave_fence();
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int pr = trow + 8 * t;
-            const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + pr * kPitch + tseg * 16);
-            if (pr < rows_here && mbase + pr < M)
-                *reinterpret_cast<u32x4 *>(og + ((size_t)(mbase + pr) * kCout + g * 64) * 2 + tseg * 16) = o4;
+            const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + (trow + 8 * t) * kPitch + tseg * 16);
+            if (srow[t] >= 0) *reinterpret_cast<u32x4 *>(og + ((size_t)srow[t] * kCout + g * 64) * 2 + tseg * 16) = o4;
         }
         wave_fence();
     }
 }
-
-static int max_tile(int W) { return (kMaxHaloTiles * 32 - 2 * W - 2) / 8 * 8; }
 
 }  // namespace block
 
@@ -393,38 +396,28 @@ const char *bottleneck_block_check(const BlockArgs &a) {
     if (a.N <= 0 || a.H <= 0 || a.W <= 0) return "non-positive dimension";
     const long long M = (long long)a.N * a.H * a.W;
     if (M != a.M || M > 0x7FFFFFFFLL / 2) return "pixel count out of range";
-    if (block::max_tile(a.W) < 64) return "rows wider than 223 pixels are not supported by the block kernel";
     if (!a.x || !a.w1 || !a.w2 || !a.w3 || !a.s1 || !a.h1 || !a.s2 || !a.h2 || !a.s3 || !a.h3) return "null operand";
     if (!a.a1 && !a.a2 && !a.out) return "nothing to store";
     const uintptr_t all = (uintptr_t)a.x | (uintptr_t)a.a1 | (uintptr_t)a.a2 | (uintptr_t)a.out | (uintptr_t)a.w1 |
                           (uintptr_t)a.w2 | (uintptr_t)a.w3 | (uintptr_t)a.s1 | (uintptr_t)a.h1 | (uintptr_t)a.s2 |
                           (uintptr_t)a.h2 | (uintptr_t)a.s3 | (uintptr_t)a.h3;
     if (all & 15) return "pointers must be 16-byte aligned";
+    const long long tiles = (long long)a.N * ((a.H + block::kT - 1) / block::kT) * ((a.W + block::kT - 1) / block::kT);
+    if (tiles > 0x7FFFFFF0LL) return "too many tiles";
     return nullptr;
 }
 
-// Pixels per workgroup: as few rounds of 256 workgroups (one per CU) as the LDS allows, then the
-// smallest tile that still gives that many rounds, so that the last round is as full as the others.
-int bottleneck_block_tile(const BlockArgs &a) {
-    const long long cap = block::max_tile(a.W);
-    const long long rounds = (a.M + 256 * cap - 1) / (256 * cap);
-    long long bm = (a.M + 256 * rounds - 1) / (256 * rounds);
-    bm = (bm + 7) / 8 * 8;
-    if (bm < 64) bm = 64;
-    if (bm > cap) bm = cap;
-    return (int)bm;
-}
+// Output pixels per workgroup
+int bottleneck_block_tile(const BlockArgs &) { return block::kT * block::kT; }
 
 hipError_t launch_bottleneck_block(const BlockArgs &a, hipStream_t stream) {
     if (bottleneck_block_check(a)) return hipErrorInvalidValue;
-    const int BM = bottleneck_block_tile(a);
-    const int NT1 = (BM + 2 * a.W + 2 + 31) / 32, NT2 = (BM + 31) / 32;
-    if (NT1 > block::kMaxHaloTiles || NT2 > block::kWaves) return hipErrorInvalidValue;
+    const int tiles_y = (a.H + block::kT - 1) / block::kT, tiles_x = (a.W + block::kT - 1) / block::kT;
     static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void *>(block::bottleneck_block_kernel),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, block::kLds);
     if (raised != hipSuccess) return raised;
-    const long long blocks = ((long long)a.M + BM - 1) / BM;
-    block::bottleneck_block_kernel<<<dim3((unsigned)blocks), dim3(block::kThreads), block::kLds, stream>>>(a, BM, NT1, NT2);
+    const long long blocks = (long long)a.N * tiles_y * tiles_x;
+    block::bottleneck_block_kernel<<<dim3((unsigned)blocks), dim3(block::kThreads), block::kLds, stream>>>(a, tiles_y, tiles_x);
     return hipGetLastError();
 }
 

@@ -96,7 +96,7 @@ class Net:
         self.all_layers = B.layer_array(order)
         self.by_tensor = {self.ids[l.y]: l for l in layers}
         # identity bottlenecks the block kernel takes (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + input, ReLU
-        # after each, bf16, rows of at most 223 pixels): its tensors carry the bits of the per-layer kernels,
+        # after each, bf16): its tensors carry the bits of the per-layer kernels,
         # so wherever all three layers run back to back they run as one launch
         self.blocks = {}
         self._block_descs = {}
@@ -113,8 +113,6 @@ class Net:
             if (a2.kind, a2.R, a2.stride, a2.pad, a2.Cin, a2.Cout, a2.relu, a2.x) != ("conv", 3, 1, 1, 64, 64, True, l.y):
                 continue
             if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, l.x):
-                continue
-            if l.W > 223:
                 continue
             self.blocks[pre] = (l.y, a2.y, out.y)
         fused = B.layer_array([B.LayerDesc.from_buffer_copy(dsc) for dsc in order])
