@@ -150,3 +150,52 @@ def test_block_kernel_refuses_what_it_does_not_take(torch_mod):
         d.recompute_segment(net.block_desc("blk"))
     assert e.value.status == dl.ERR_STATE
     d.close()
+
+
+def test_step_replay_runs_adjacent_block_layers_as_one_launch(torch_mod):
+    """`run_plan` on a graph with an identity bottleneck: three forward steps with no plan event between
+    them, and RECOMPUTE events for a1 and a2 in a row, each become one launch of the block kernel; a plan
+    event in between keeps the per-layer launches.  Every tensor carries the same bits either way."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import run_plan
+    d, net, layers = _net(torch, 3, 20, 17)
+    g = synth.fused_graph(layers, "bf16")
+    ids = [net.ids[n] for n in NAMES]
+    assert net.blocks == {"blk": NAMES}
+
+    def launches():
+        return d.stats()["recompute_launches"]
+
+    # per-layer reference bits
+    net.load_input()
+    d.recompute_segment(net.all_layers)
+    d.sync()
+    ref = {n: net.read(n).copy() for n in NAMES}
+    for t in [0] + ids:
+        d.release(t, dl.EV_FREE)
+
+    # (a) no events: the forward's three steps fuse
+    d.stats_reset()
+    run_plan(net, g, [])
+    d.sync()
+    fused_launches = launches()
+    for n in NAMES:
+        assert np.array_equal(net.read(n), ref[n]), n
+    for t in [0] + ids:
+        d.release(t, dl.EV_FREE)
+
+    # (b) an event before the second layer: per-layer launches; later a1 and a2 are evicted and regenerated in a row
+    k_a2 = [k for k, st in enumerate(g.steps) if st["produces"] == ids[1]][0]
+    k_bwd = g.n_fwd                                  # the first backward step
+    events = [(k_a2, dl.EV_EVICT, ids[0]), (k_a2, dl.EV_RECOMPUTE, ids[0]),
+              (k_bwd, dl.EV_EVICT, ids[0]), (k_bwd, dl.EV_EVICT, ids[1]),
+              (k_bwd, dl.EV_RECOMPUTE, ids[0]), (k_bwd, dl.EV_RECOMPUTE, ids[1])]
+    d.stats_reset()
+    run_plan(net, g, events)
+    d.sync()
+    for n in NAMES:
+        assert np.array_equal(net.read(n), ref[n]), n
+    # forward: 3 per-layer launches + 1 recomputation of a1; backward step: one block launch for a1 + a2
+    assert launches() - fused_launches == 4, (launches(), fused_launches)
+    d.close()
