@@ -8,19 +8,20 @@
 // 2 x (256 + 64 | 64 + 64 | 64 + 256 + 256) bytes per pixel; this kernel reads x once (plus the
 // shortcut's re-read, which the caches serve) and writes only what is stored.
 //
-// A workgroup of 16 wavefronts owns BM consecutive pixels (NHW order) and walks three phases:
-//   1. a1 for its pixels and the W + 1 pixels before and after them (the halo the 3x3 needs) is
-//      computed by all wavefronts, one 32-pixel tile each: x straight from global memory into
-//      registers (64 bytes per lane and 128-byte slice), w1 from LDS; the results go to LDS as
-//      bf16 rows of 128 bytes (pitch 144) - exactly the layout the 3x3 reads its operand in;
-//   2. a2: every wavefront takes 32 pixels x 64 channels; the nine taps read nine shifted rows of
-//      the a1 tile in LDS (taps outside the image are redirected to a row of zeros), w2 is
-//      resident in LDS (taps 0-4 staged during phase 1, taps 5-8 into the space w1 leaves);
-//      the result stays in registers as bf16, 8 consecutive channels per piece;
-//   3. out: those registers are the MFMA's pixel operand as they are (a piece of 8 channels per
-//      step; w3's rows are read from LDS in the same channel order), the shortcut is read from x
-//      in the same piece layout, and rows of 128 contiguous bytes leave through a
-//      wavefront-private LDS tile.
+// A workgroup of 8 wavefronts owns a 14 x 14 tile of output pixels of one image (two workgroups share
+// a CU's LDS) and walks three phases:
+//   1. a1 on the tile's 16 x 16 halo (256 positions, one 32-position block per wavefront): x straight
+//      from global memory into registers (64 bytes per lane and 128-byte slice), w1 from LDS; the
+//      results go to LDS as bf16 rows of 128 bytes (pitch 144) - exactly the layout the 3x3 reads its
+//      operand in; positions outside the image hold zeros (the 3x3's padding);
+//   2. a2: seven wavefronts take 32 of the 196 pixels x 64 channels each; the nine taps read nine
+//      shifted rows of the a1 tile in LDS, w2 passes through LDS three taps at a time (the next
+//      three are fetched into registers under the current three's MFMAs); the result stays in
+//      registers as bf16, 8 consecutive channels per piece;
+//   3. out: those registers, after one exchange between the lane halves, are the MFMA's pixel
+//      operand (a piece of 8 channels per step; w3's rows are read from LDS in the same channel
+//      order), the shortcut is read from x in the same piece layout, and rows of 128 contiguous
+//      bytes leave through a wavefront-private LDS tile.
 // Orientation as in the per-layer kernels: output channels on the MFMA row axis, pixels on the
 // column axis; lane half h owns bytes [64h, 64h + 64) of every 128-byte slice of both operands.
 // The order of every sum is fixed and does not depend on which tensors are stored, so whatever
@@ -406,9 +407,6 @@ const char *bottleneck_block_check(const BlockArgs &a) {
     if (tiles > 0x7FFFFFF0LL) return "too many tiles";
     return nullptr;
 }
-
-// Output pixels per workgroup
-int bottleneck_block_tile(const BlockArgs &) { return block::kT * block::kT; }
 
 hipError_t launch_bottleneck_block(const BlockArgs &a, hipStream_t stream) {
     if (bottleneck_block_check(a)) return hipErrorInvalidValue;

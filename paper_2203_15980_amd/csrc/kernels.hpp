@@ -67,7 +67,6 @@ struct BlockArgs {
     int N, H, W, M;
 };
 const char *bottleneck_block_check(const BlockArgs &a);
-int bottleneck_block_tile(const BlockArgs &a);          // pixels per workgroup the launch will use
 hipError_t launch_bottleneck_block(const BlockArgs &a, hipStream_t stream);
 // attention.hip: fused multi-head self-attention, head dimension 64, bf16.  qkv [N,S,3*64*heads], ctx [N,S,64*heads]
 const char *attention_check(const void *qkv, const void *ctx, int N, int S, int heads, int bf16);
