@@ -423,37 +423,43 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * QS * 64) void wgrad_kernel(Wgrad
             }
 }
 
-// gw[k][tap][c] = scale_k * sum over splits of the partial sums, in a fixed order.  A workgroup
-// takes 64 consecutive f32x4 of the blob (one per lane) and spreads the splits over its 8
-// wavefronts (wavefront g adds splits g, g + 8, ...), which keeps enough loads in flight for a
-// reduction that is pure HBM traffic; the 8 sums are then added in wavefront order.  The
+// gw[k][tap][c] = scale_k * sum over splits of the partial sums, in a fixed order.  A group of
+// 64 consecutive f32x4 of the blob (one per lane) is shared by G wavefronts (wavefront g of the
+// group adds splits g, g + G, ..., four loads in flight), whose G sums are then added in wavefront
+// order; a workgroup of 8 wavefronts takes 8 / G groups.  G follows the number of splits (about
+// four loads per lane): with few splits (the wide layers: 4 or 16) every wavefront still has
+// loads to issue, with many (256) the loads of a group are spread over the whole workgroup.  The
 // accumulator layout of a 32x32 tile is: lane l holds column l % 32 and rows 8 e4 + 4 (l / 32) + e
 // in register 4 e4 + e, so a thread's four sums go to four k rows of one c, and consecutive lanes
 // write consecutive c.
 // gw_taps: taps per (k, c) pair in gw; tapout: 4 bits per tap of this launch, its index among them.
+template <int G>
 __global__ __launch_bounds__(512) void wgrad_reduce_kernel(const float *partial, const float *scale, float *gw, int K,
                                                            int C, int taps, int KTW, int CTW, int nsplit, int gw_taps,
                                                            unsigned long long tapout) {
     __shared__ f32x4 part[8][64];
     const int ktiles = K / (64 * KTW), tiles_y = (C / (64 * CTW)) * ktiles;
     const int NW = KTW * CTW * taps;
-    const size_t per_split = (size_t)tiles_y * NW * 1024;      // f32x4 elements per split (a multiple of 64)
-    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const size_t idx = (size_t)blockIdx.x * 64 + lane;
+    const size_t per_split = (size_t)tiles_y * NW * 1024;      // f32x4 elements per split (a multiple of 512)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = wave % G, sub = wave / G;
+    const size_t idx = ((size_t)blockIdx.x * (8 / G) + sub) * 64 + lane;
     const f32x4 *src = reinterpret_cast<const f32x4 *>(partial) + idx;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     int sp = grp;
-    for (; sp + 24 < nsplit; sp += 32) {                       // four independent loads in flight
-        const f32x4 v0 = src[(size_t)sp * per_split], v1 = src[(size_t)(sp + 8) * per_split];
-        const f32x4 v2 = src[(size_t)(sp + 16) * per_split], v3 = src[(size_t)(sp + 24) * per_split];
+    for (; sp + 3 * G < nsplit; sp += 4 * G) {                 // four independent loads in flight
+        const f32x4 v0 = src[(size_t)sp * per_split], v1 = src[(size_t)(sp + G) * per_split];
+        const f32x4 v2 = src[(size_t)(sp + 2 * G) * per_split], v3 = src[(size_t)(sp + 3 * G) * per_split];
         sum += v0; sum += v1; sum += v2; sum += v3;
     }
-    for (; sp < nsplit; sp += 8) sum += src[(size_t)sp * per_split];
-    part[grp][lane] = sum;
-    __syncthreads();
-    if (grp != 0) return;
+    for (; sp < nsplit; sp += G) sum += src[(size_t)sp * per_split];
+    if constexpr (G > 1) {
+        part[wave][lane] = sum;
+        __syncthreads();
+        if (grp != 0) return;
 #pragma unroll
-    for (int g = 1; g < 8; ++g) sum += part[g][lane];
+        for (int g = 1; g < G; ++g) sum += part[wave + g][lane];
+    }
     // idx = (((ty * NW + wv) * 4 + tile) * 4 + e4) * 64 + lane
     const int e4 = (int)((idx >> 6) & 3), tile = (int)((idx >> 8) & 3);
     const int wv = (int)((idx >> 10) % NW), ty = (int)((idx >> 10) / NW);
@@ -782,8 +788,19 @@ hipError_t run_wgrad(const ConvArgs &a, const void *g, float *gw, void *workspac
     }
     if (e != hipSuccess) return e;
     const size_t quads = (size_t)p.tiles_y * p.waves * 1024;   // f32x4 elements of one split
-    bwd::wgrad_reduce_kernel<<<dim3((unsigned)(quads / 64)), dim3(512), 0, stream>>>(
-        wa.partial, a.scale, gw, a.Cout, a.Cin, p.taps, p.ktw, p.ctw, p.nsplit, gw_taps, tapout);
+    // wavefronts per group of 64 sums: about four splits each
+    const int G = p.nsplit <= 4 ? 1 : p.nsplit <= 8 ? 2 : p.nsplit <= 16 ? 4 : 8;
+    const dim3 grid((unsigned)(quads / 64 / (8 / G)));
+#define DELTA_REDUCE(g)                                                                                             \
+    bwd::wgrad_reduce_kernel<g><<<grid, dim3(512), 0, stream>>>(wa.partial, a.scale, gw, a.Cout, a.Cin, p.taps,     \
+                                                                p.ktw, p.ctw, p.nsplit, gw_taps, tapout)
+    switch (G) {
+    case 1: DELTA_REDUCE(1); break;
+    case 2: DELTA_REDUCE(2); break;
+    case 4: DELTA_REDUCE(4); break;
+    default: DELTA_REDUCE(8); break;
+    }
+#undef DELTA_REDUCE
     return hipGetLastError();
 }
 
