@@ -1,4 +1,5 @@
 // y[M, N] = act(scale_n * (x[M, K] . w[N, K]^T) + shift_n (+ res)) (* [mask > 0]) for gfx950, bf16.
+// Row m of x is pixel m of the input, or, for a strided 1x1 convolution, the input pixel under output pixel m.
 //
 // The dense layers of a recomputation segment whose reduction axis is long: the linear layers of a
 // transformer encoder (the paper's BERT-base workload, Sec. 5.2) and the 1x1 stride-1 convolutions
@@ -114,7 +115,12 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(Con
         const int piece = (lane & 7) ^ ((r >> 1) & 7);                 // which 16 bytes of the row land in this lane's slot
         int xr = m0 + r;
         xr = xr < M ? xr : M - 1;
-        xsrc[q] = xg + (size_t)xr * krow + piece * 16;
+        size_t xpix = (size_t)xr;
+        if (a.stride != 1) {                                            // a strided 1x1 layer reads every stride-th pixel
+            const int oq = xr % a.Q, t = xr / a.Q, op = t % a.P, n = t / a.P;
+            xpix = ((size_t)n * a.H + (size_t)op * a.stride) * a.W + (size_t)oq * a.stride;
+        }
+        xsrc[q] = xg + xpix * krow + piece * 16;
         xdst[q] = (uint32_t)g * 1024u;
     }
 #pragma unroll
@@ -335,7 +341,7 @@ hipError_t launch_tile(const ConvArgs &a, hipStream_t stream) {
 // bf16 1x1 stride-1 layers (rows of x contiguous) with a reduction axis of at least 256 and enough
 // output to fill the chip with its tiles.
 bool gemm_nt_applies(const ConvArgs &a) {
-    if (!a.bf16 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0) return false;
+    if (!a.bf16 || a.R != 1 || a.S != 1 || a.stride < 1 || a.pad != 0) return false;
     if (a.Cin % 64 || a.Cin < 256 || a.Cout % 8 || a.Cout < 128 || (a.Cout > 128 && a.Cout < 192)) return false;
     const long long tiles = tiles_of(a, pick_tile(a));
     return tiles >= (a.Cout <= 128 ? 512 : 128) && tiles <= 0x3FFFFFF0LL;

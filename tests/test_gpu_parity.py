@@ -59,6 +59,8 @@ CASES = [
     ("1x1_sl_128_192", 2, 10, 10, 128,  192, 1, 1, 0, False, False), # 3 slices of 64
     ("1x1_256_1k",     1, 14, 14, 256, 1024, 1, 1, 0, True, True),   # tiled kernel, 8 channel tiles
     ("1x1_512_128",    3,  9,  9, 512,  128, 1, 1, 0, True, False),
+    # a projection shortcut's shape: stride 2 on an odd image, enough tiles for the GEMM kernel (bf16), ragged last tile
+    ("1x1_s2_256_512", 3, 147, 147, 256, 512, 1, 2, 0, False, False),
     # 3x3 stride 1 (bf16: the LDS-halo kernel): image borders inside a pixel tile, ragged tail,
     # odd step count, non-square images, wide rows
     ("3x3_halo_res",  3, 13, 13, 128,  64, 3, 1, 1, True, True),    # M = 507: two tiles, ragged
@@ -88,8 +90,8 @@ def test_single_layer_matches_oracle(torch_mod, dtype, case):
         r = r if dtype == "f32" else synth.f32_to_bf16_bits(r).reshape(rshape)
     ref = on.conv_bn_act(x, p["w"], p, res=r, stride=stride, pad=pad, relu=relu, dtype=dtype)
 
-    d = make_delta(torch, 64 << 20)
     sizes = [x.nbytes, int(np.prod(rshape)) * es, int(np.prod(rshape)) * es]     # x, res, y
+    d = make_delta(torch, max(64 << 20, sum(sizes) + (8 << 20)))
     d.bind(sizes)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
     w = dev(p["w"])
@@ -108,6 +110,8 @@ def test_single_layer_matches_oracle(torch_mod, dtype, case):
                         dtype=dl.DTYPE_F32 if dtype == "f32" else dl.DTYPE_BF16, w=w.data_ptr(),
                         scale=scale.data_ptr(), shift=shift.data_ptr(), N=N, H=H, W=W, Cin=Cin, Cout=Cout,
                         R=R, S=R, stride=stride, pad=pad, relu=1 if relu else 0)
+    if name == "1x1_s2_256_512" and dtype == "bf16":
+        assert "gemm_nt" in d.layer_kernel(desc), d.layer_kernel(desc)
     d.recompute_segment([desc])
     py = d.tensor_ptr(2)
     d.sync()
