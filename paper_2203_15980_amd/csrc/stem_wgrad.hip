@@ -58,29 +58,67 @@ __global__ __launch_bounds__(kWaves * 64) void stem_wgrad_kernel(ConvArgs a, con
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
 
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // Staging: a thread carries 2 patch pixels (3 channels each) and 3 sixteen-byte pieces of the gpre
+    // tile; the next tile's are requested before the current tile's MFMAs and written to LDS after them.
+    constexpr int kNT = kWaves * 64;
+    constexpr int kPPix = (kPRows * kPCols + kNT - 1) / kNT, kGPieces = (kTP * kTQ * 8 + kNT - 1) / kNT;
+    static_assert(kPPix == 2 && kGPieces == 3, "staging registers are sized for these tiles");
+    uint16_t px[kPPix][3];
+    u32x4 gq[kGPieces];
+    uint32_t ok = 0;                              // bit c: patch pixel c is inside the image; bit 8 + c: gpre piece c is
+    auto request = [&](int tile) {
         const int n = tile / (tiles_p * tiles_q), t2 = tile - n * tiles_p * tiles_q;
         const int p0 = (t2 / tiles_q) * kTP, q0 = (t2 % tiles_q) * kTQ;
-        __syncthreads();                          // the previous tile is no longer read
-        for (int e = tid; e < kPRows * kPCols; e += kWaves * 64) {
+        ok = 0;
+#pragma unroll
+        for (int c = 0; c < kPPix; ++c) {
+            const int e = tid + c * kNT;
             const int i = e / kPCols, j = e - i * kPCols;
             const int h = 2 * p0 - 3 + i, w = 2 * q0 - 3 + j;
-            u32x2 v = {0u, 0u};
-            if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W) {
-                const uint16_t *px = xg + ((size_t)((size_t)n * a.H + h) * a.W + w) * 3;
-                v.x = (uint32_t)px[0] | ((uint32_t)px[1] << 16);
-                v.y = (uint32_t)px[2];
-            }
-            *reinterpret_cast<u32x2 *>(patch + i * kPPitch + j * 8) = v;
+            const bool in = e < kPRows * kPCols && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+            const uint16_t *src = xg + (in ? ((size_t)((size_t)n * a.H + h) * a.W + w) * 3 : 0);
+            px[c][0] = src[0]; px[c][1] = src[1]; px[c][2] = src[2];
+            ok |= (uint32_t)in << c;
         }
-        for (int e = tid; e < kTP * kTQ * 8; e += kWaves * 64) {
+#pragma unroll
+        for (int c = 0; c < kGPieces; ++c) {
+            const int e = tid + c * kNT;
             const int pix = e >> 3, seg = e & 7;
             const int p = p0 + pix / kTQ, q = q0 + pix % kTQ;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (p < a.P && q < a.Q)
-                v = *reinterpret_cast<const u32x4 *>(g + (((size_t)n * a.P + p) * a.Q + q) * 128 + seg * 16);
-            *reinterpret_cast<u32x4 *>(gs + pix * kGPitch + seg * 16) = v;
+            const bool in = e < kTP * kTQ * 8 && p < a.P && q < a.Q;
+            gq[c] = *reinterpret_cast<const u32x4 *>(g + (in ? (((size_t)n * a.P + p) * a.Q + q) * 128 + seg * 16 : 0));
+            ok |= (uint32_t)in << (8 + c);
         }
+    };
+    auto deposit = [&]() {
+#pragma unroll
+        for (int c = 0; c < kPPix; ++c) {
+            const int e = tid + c * kNT;
+            if (e < kPRows * kPCols) {
+                const bool in = (ok >> c) & 1u;
+                u32x2 v;
+                v.x = in ? (uint32_t)px[c][0] | ((uint32_t)px[c][1] << 16) : 0u;
+                v.y = in ? (uint32_t)px[c][2] : 0u;
+                const int i = e / kPCols, j = e - i * kPCols;
+                *reinterpret_cast<u32x2 *>(patch + i * kPPitch + j * 8) = v;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kGPieces; ++c) {
+            const int e = tid + c * kNT;
+            if (e < kTP * kTQ * 8) {
+                const bool in = (ok >> (8 + c)) & 1u;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(gs + (e >> 3) * kGPitch + (e & 7) * 16) = in ? gq[c] : zero;
+            }
+        }
+    };
+
+    if ((int)blockIdx.x < ntiles) request(blockIdx.x);
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        __syncthreads();                          // the previous tile is no longer read
+        deposit();
+        if (tile + (int)gridDim.x < ntiles) request(tile + gridDim.x);
         __syncthreads();
 #pragma unroll
         for (int pr = 0; pr < kTP; ++pr) {        // one k-step: the 16 pixels of tile row pr
