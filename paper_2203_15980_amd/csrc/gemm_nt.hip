@@ -19,7 +19,12 @@
 //    no registers, no LDS store instructions) through TWO buffers of 64 KB (56 KB): a tile row is a
 //    whole 128-byte line of the operand, one barrier per 64 of K, and the slice after the current one
 //    is in flight while the current one is multiplied (2000 cycles of MFMA work per SIMD at full
-//    rate).  Measured against four buffers of 32 (two and three slices ahead, also with a fifth
+//    rate).  The operand pieces of a 16-wide step are read from LDS into one of two register sets
+//    while the other set's MFMAs issue (the barrier of a slice stands before its last step, so the
+//    first pieces of the next slice are read under that step's MFMAs), and the scheduler is told to
+//    alternate LDS reads and MFMAs: with LDS reads and MFMAs left to the compiler's order every
+//    wavefront read all its pieces after the barrier and the matrix pipe idled meanwhile (3-9 % of a
+//    layer's time; the loop alone, operands resident in LDS: 1.75 -> 2.1 PFLOP/s).  Measured against four buffers of 32 (two and three slices ahead, also with a fifth
 //    buffer, also with the next slice's first operands read before the barrier): those were all the
 //    same speed, this is 4-9 % faster on the encoder's and ResNet's shapes; with the loads switched
 //    off the loop runs at 1.3-1.5 PFLOP/s and removing the barrier changes nothing: what holds the
@@ -173,30 +178,46 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(Con
         wsw[j] = (r >> 1) & 7;
     }
 
+    // Operand pieces of step q of the slice in buffer `buf`, into register set `f`
+    u32x4 xf[2][kTM], wf[2][kTN];
+    auto read_step = [&](int buf, int q, int f) {
+        const unsigned char *base = smem + (size_t)buf * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < kTM; ++i) xf[f][i] = *reinterpret_cast<const u32x4 *>(base + xoff[i] + (((2 * q + half) ^ xsw[i]) << 4));
+#pragma unroll
+        for (int j = 0; j < kTN; ++j) wf[f][j] = *reinterpret_cast<const u32x4 *>(base + woff[j] + (((2 * q + half) ^ wsw[j]) << 4));
+    };
     fetch(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (nslices > 1) fetch(1, 1);
+    read_step(0, 0, 0);
     for (int t = 0; t < nslices; ++t) {
         const int buf = t & 1;
-        if (t + 1 < nslices) fetch(t + 1, buf ^ 1);    // into the buffer that slice t - 1 has just left
-        const unsigned char *base = smem + (size_t)buf * kStageBytes;
 #pragma unroll
-        for (int k2 = 0; k2 < 4; ++k2) {
-            bf16x8 xf[kTM], wf[kTN];
-#pragma unroll
-            for (int i = 0; i < kTM; ++i)
-                xf[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + xoff[i] + (((2 * k2 + half) ^ xsw[i]) << 4)));
-#pragma unroll
-            for (int j = 0; j < kTN; ++j)
-                wf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + woff[j] + (((2 * k2 + half) ^ wsw[j]) << 4)));
+        for (int q = 0; q < 4; ++q) {
+            if (q == 3) {
+                // this wavefront's loads of slice t + 1 have landed, and its last reads of buffer `buf`
+                // (step 3's pieces, requested during step 2) are in registers
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                __syncthreads();                   // everyone's have
+                if (t + 2 < nslices) fetch(t + 2, buf);
+                if (t + 1 < nslices) read_step(buf ^ 1, 0, 0);
+            } else {
+                read_step(buf, q + 1, (q + 1) & 1);
+            }
 #pragma unroll
             for (int i = 0; i < kTM; ++i)
 #pragma unroll
                 for (int j = 0; j < kTN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[q & 1][j]),
+                                                                        __builtin_bit_cast(bf16x8, xf[q & 1][i]), acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int k = 0; k < kTM + kTN; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, (kTM * kTN) / (kTM + kTN), 0);
+            }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's loads of slice t + 1 have landed
-        __syncthreads();                           // everyone's have, and everyone is done reading buffer `buf`
     }
 
     // ---- epilogue.  acc[i][j]: lane holds pixel (x row) l32 of tile i and channels 8*rb + 4*half + e of tile j
