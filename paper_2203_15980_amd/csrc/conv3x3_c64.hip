@@ -131,21 +131,32 @@ __global__ __launch_bounds__(kThreads) void conv3x3_c64_kernel(ConvArgs a, int B
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-#pragma unroll
-            for (int tap = 0; tap < 9; ++tap) {
+            // 36 steps (tap, 16-byte piece q); the three operand pieces of step st + 1 are read while
+            // step st's two MFMAs issue
+            u32x4 xv[2], w0[2], w1[2];
+            auto read_step = [&](int st, int f) {
+                const int tap = st >> 2, q = st & 3;
                 const int r = tap / 3, s = tap - 3 * r;
                 const int row = ((valid >> tap) & 1u) ? pi + r * W + s : kMaxRows;
                 const unsigned char *xp = ra + row * kPitch + half * 64;
                 const unsigned char *wp = rw + tap * kTap + l32 * kPitch + half * 64;
+                xv[f] = *reinterpret_cast<const u32x4 *>(xp + q * 16);
+                w0[f] = *reinterpret_cast<const u32x4 *>(wp + q * 16);
+                w1[f] = *reinterpret_cast<const u32x4 *>(wp + 32 * kPitch + q * 16);
+            };
+            read_step(0, 0);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xp + q * 16);
-                    const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wp + q * 16);
-                    const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wp + 32 * kPitch + q * 16);
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w0), __builtin_bit_cast(bf16x8, xv),
-                                                                     acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w1), __builtin_bit_cast(bf16x8, xv),
-                                                                     acc[1], 0, 0, 0);
+            for (int st = 0; st < 36; ++st) {
+                if (st + 1 < 36) read_step(st + 1, (st + 1) & 1);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w0[st & 1]),
+                                                                 __builtin_bit_cast(bf16x8, xv[st & 1]), acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w1[st & 1]),
+                                                                 __builtin_bit_cast(bf16x8, xv[st & 1]), acc[1], 0, 0, 0);
+                if (st + 1 < 36) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 }
             }
             // ---- epilogue: scale/shift, lanes l and l + 32 swap so that each holds 8 consecutive channels,
