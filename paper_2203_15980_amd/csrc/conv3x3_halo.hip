@@ -13,9 +13,11 @@
 // (BM/64) x (BN/64) wavefronts of 64 pixels x 64 channels; 256 x 64 measured best on MI355X for
 // every ResNet-50 shape (two workgroups share a CU).
 // Pipeline: one step = one tap of one channel block = 16 MFMAs per wavefront and one barrier.
-// Weight tiles are requested D = 4 steps ahead into a register ring and move to the other of two
-// LDS buffers one step before use; the halo of the next channel block is requested at tap 0 and
-// stored after tap 8.  Taps outside the image are redirected to a row of zeros in LDS, so no
+// Weight tiles are requested D = 4 steps ahead into a register ring and move to one of two LDS
+// buffers a step before use; the halo of the next channel block is requested at tap 0 and stored
+// after tap 8.  The operand pieces of a 16-wide step are read into one of two register sets while
+// the other set's MFMAs issue; the barrier of a step stands before its last 16-wide step, so the
+// first pieces of the next step are read under the last MFMAs of this one.  Taps outside the image are redirected to a row of zeros in LDS, so no
 // operand needs masking.  The step order is fixed, so the first forward and every recomputation
 // add in the same order and a recomputed tensor is bit-identical to the original.
 #include <hip/hip_runtime.h>
@@ -162,43 +164,61 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    auto compute = [&](const unsigned char *wb, int tap) {
+    // Operand pieces.  `point` fixes the rows of a step (tap) in weight buffer wb; `read_pieces`
+    // reads the pieces of its 16-wide step q into register set f; `mfmas` multiplies set f.
+    const unsigned char *xp[TP], *wp;
+    auto point = [&](const unsigned char *wb, int tap) {
         const int r = tap / 3, s = tap - 3 * r;
         const int shift_rows = r * W + s;
-        const unsigned char *xp[TP];
 #pragma unroll
         for (int j = 0; j < TP; ++j) {
             const int row = ((valid[j] >> tap) & 1u) ? prow[j] + shift_rows : HR;
             xp[j] = hs + row * kPitch + half * (KB / 2);
         }
-        const unsigned char *wp = wb + (wn * 64 + l32) * kPitch + half * (KB / 2);
+        wp = wb + (wn * 64 + l32) * kPitch + half * (KB / 2);
+    };
+    u32x4 wf[2][2], xf[2][TP];
+    auto read_pieces = [&](int q, int f) {
 #pragma unroll
-        for (int q = 0; q < KB / 32; ++q) {
-            u32x4 wf[2], xf[TP];
+        for (int c = 0; c < 2; ++c) wf[f][c] = *reinterpret_cast<const u32x4 *>(wp + c * 32 * kPitch + q * 16);
 #pragma unroll
-            for (int c = 0; c < 2; ++c) wf[c] = *reinterpret_cast<const u32x4 *>(wp + c * 32 * kPitch + q * 16);
+        for (int j = 0; j < TP; ++j) xf[f][j] = *reinterpret_cast<const u32x4 *>(xp[j] + q * 16);
+    };
+    auto mfmas = [&](int f) {
 #pragma unroll
-            for (int j = 0; j < TP; ++j) xf[j] = *reinterpret_cast<const u32x4 *>(xp[j] + q * 16);
+        for (int j = 0; j < TP; ++j)
 #pragma unroll
-            for (int j = 0; j < TP; ++j)
+            for (int c = 0; c < 2; ++c)
+                acc[j][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, wf[f][c]), __builtin_bit_cast(bf16x8, xf[f][j]), acc[j][c], 0, 0, 0);
+    };
+    auto interleave = [&]() {                     // one LDS read, one MFMA, ... (2-3 % on 28x28 and 7x7 images, 1 % slower on 14x14)
 #pragma unroll
-                for (int c = 0; c < 2; ++c)
-                    acc[j][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, wf[c]), __builtin_bit_cast(bf16x8, xf[j]), acc[j][c], 0, 0, 0);
+        for (int k = 0; k < 2 + TP; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, (2 * TP) / (2 + TP), 0);
         }
     };
 
-    // ---- prologue: tile 0 to LDS, tiles 1..D in flight in registers (rw[i] holds tile t with t % D == i)
+    // ---- prologue: the weights of steps 0 and 1 to LDS, those of steps 2 .. D + 1 in flight in
+    // registers (rw[i] holds the tile of a step t with t % D == i)
     if (tid < SEGS + 1) *reinterpret_cast<u32x4 *>(hs + HR * kPitch + tid * 16) = u32x4{0u, 0u, 0u, 0u};
     load_halo(0);
     load_w(0, rw[0]);
-#pragma unroll
-    for (int i = 1; i < D; ++i)
-        if (i < T) load_w(i, rw[i]);
+    if (1 < T) load_w(1, rw[1]);
     store_halo();
     store_w(wbuf0, rw[0]);
-    if (D < T) load_w(D, rw[0]);
+    if (1 < T) store_w(wbuf1, rw[1]);
+#pragma unroll
+    for (int i = 2; i < D + 2; ++i)
+        if (i < T) load_w(i, rw[i % D]);
+    __syncthreads();
+    point(wbuf0, 0);
+    read_pieces(0, 0);
 
+    // Step t multiplies out of buffer t % 2.  Its barrier stands before its last 16-wide step, when every
+    // wavefront holds that step's pieces in registers: from there on buffer t % 2 takes the weights of
+    // step t + 2, and the first pieces of step t + 1 (stored a step earlier) are read under the last MFMAs.
     int tap = 0, cb = 0;
     for (int t0 = 0; t0 < T; t0 += D) {
 #pragma unroll
@@ -207,22 +227,36 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv3x3_halo_kerne
             if (t < T) {
                 unsigned char *cur = (i & 1) ? wbuf1 : wbuf0;   // D is even: t % 2 == i % 2
                 unsigned char *nxt = (i & 1) ? wbuf0 : wbuf1;
-                __syncthreads();
-                if (t + 1 < T) store_w(nxt, rw[(i + 1) % D]);
-                if (t + 1 + D < T) load_w(t + 1 + D, rw[(i + 1) % D]);
                 const bool more = cb + 1 < CB;
                 if (tap == HALO_TAP && more) load_halo(cb + 1);
-                compute(cur, tap);
+                read_pieces(1, 1);
+                mfmas(0);
+                interleave();
+                read_pieces(2, 0);
+                mfmas(1);
+                interleave();
+                read_pieces(3, 1);
+                mfmas(0);
+                interleave();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (t + 2 < T) store_w(cur, rw[(i + 2) % D]);
+                if (t + 2 + D < T) load_w(t + 2 + D, rw[(i + 2) % D]);
                 if (tap == 8) {
                     if (more) {
-                        __syncthreads();
                         store_halo();
+                        __syncthreads();
                     }
                     tap = 0;
                     ++cb;
                 } else {
                     ++tap;
                 }
+                if (t + 1 < T) {
+                    point(nxt, tap);
+                    read_pieces(0, 0);
+                }
+                mfmas(1);
             }
         }
     }
