@@ -318,6 +318,8 @@ namespace {
 //   256 -> 1024, 14 x 14    31.4         38.6         34.2
 //   1024 -> 512, 14 x 14    32.0         39.1         39.5
 //   512 -> 2048, 7 x 7      22.5         27.5         26.3
+// (128 x 256 for 1024 -> 256 at 14 x 14, twice the workgroups of the 256-wide tiles: 26 -> 22 us on its own,
+// no change inside the pass.)
 // With cold operands the two-deep pipeline of this kernel is short: one slice ahead does not cover a
 // miss to HBM, and the tiled kernel's three workgroups per CU cover each other's.  So the narrow tiles
 // take only the layers with at most 128 output channels, where they win both ways.
