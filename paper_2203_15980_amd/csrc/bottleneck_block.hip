@@ -269,18 +269,28 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
         deposit_taps(g == 0 ? wq0 : (g == 1 ? wq1 : wq2));   // the region is free: w1 / the previous taps are behind a barrier
         __syncthreads();
         if (p2) {
-#pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                // tap 3 g + t is window position (g, t)
+            // 12 steps (tap t, 16-byte piece q), tap 3 g + t being window position (g, t); the three operand
+            // pieces of the next step are read while this step's two MFMAs issue
+            u32x4 xv[2], w0[2], w1[2];
+            auto read_step = [&](int st, int f) {
+                const int t = st >> 2, q = st & 3;
                 const unsigned char *xp = ra + ((iy + g) * 16 + ix + t) * kPitch + half * 64;
                 const unsigned char *wp = rb + t * kTap + l32 * kPitch + half * 64;
+                xv[f] = *reinterpret_cast<const u32x4 *>(xp + q * 16);
+                w0[f] = *reinterpret_cast<const u32x4 *>(wp + q * 16);
+                w1[f] = *reinterpret_cast<const u32x4 *>(wp + 32 * kPitch + q * 16);
+            };
+            read_step(0, 0);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xp + q * 16);
-                    const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wp + q * 16);
-                    const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wp + 32 * kPitch + q * 16);
-                    acc2[0] = mma(w0, xv, acc2[0]);
-                    acc2[1] = mma(w1, xv, acc2[1]);
+            for (int st = 0; st < 12; ++st) {
+                if (st + 1 < 12) read_step(st + 1, (st + 1) & 1);
+                acc2[0] = mma(w0[st & 1], xv[st & 1], acc2[0]);
+                acc2[1] = mma(w1[st & 1], xv[st & 1], acc2[1]);
+                if (st + 1 < 12) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 }
             }
         }
