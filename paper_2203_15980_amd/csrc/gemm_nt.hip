@@ -28,8 +28,10 @@
 //    buffer, also with the next slice's first operands read before the barrier): those were all the
 //    same speed, this is 4-9 % faster on the encoder's and ResNet's shapes; with the loads switched
 //    off the loop runs at 1.3-1.5 PFLOP/s and removing the barrier changes nothing: what holds the
-//    kernel at about 1 PFLOP/s is the delivery of the operands from L2, not the barrier or LDS (LDS
-//    reads are a quarter of the cycles by the counters).  Re-measured inside ResNet-50's forward
+//    kernel at about 1 PFLOP/s is the delivery of the operands, not the barrier or LDS (LDS
+//    reads are a quarter of the cycles by the counters): with every slice served by the L2 the loop
+//    below runs at 1.8 PFLOP/s, served by the Infinity Cache at 0.93, by HBM at 0.8-0.87 (the L2
+//    delivers 35 TB/s, the two behind it 6-7 TB/s).  Re-measured inside ResNet-50's forward
 //    pass, where a layer's operands come from HBM rather than the caches: slices of 32 through four
 //    buffers, three of them in flight, were again 1 % slower.  Also measured and slower: the loads
 //    of a slice spread over its four steps instead of issued at its start (5-8 %), and x three

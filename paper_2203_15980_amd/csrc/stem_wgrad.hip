@@ -13,7 +13,8 @@
 //   row = pixel (p, q) -> address of patch[2p + r][2q], 32 elements wide (the rows of neighbouring
 //   pixels overlap in memory, which a transpose read does not mind).
 // A workgroup is 7 wavefronts, one per kernel row r, sharing the staged tiles (8 x 16 output pixels
-// per tile, one MFMA k-step per tile row); persistent over tiles, accumulators (64 k x 32 j per
+// per tile, one MFMA k-step per tile row); persistent over tiles (the next tile's pixels and gradient
+// rows travel in registers while the current tile is multiplied), accumulators (64 k x 32 j per
 // wavefront) in registers, written per workgroup to a partial buffer; a second kernel adds the
 // workgroups' partials in a fixed order, applies scale_k and drops the padding.  No atomics.
 #include <hip/hip_runtime.h>
