@@ -61,7 +61,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kBK = 64, kStages = 2;
+static constexpr int kBK = 64;
 static constexpr int kTM = 2, kTN = 2;                                  // 2 x 2 tiles of 32 x 32 per wavefront
 static constexpr int kStgPitch = 64 * 4 + 16;                          // fp32 staging row: 64 channels + pad
 
@@ -90,8 +90,10 @@ __device__ __forceinline__ float gelu_erf(float v) {     // v/2 (1 + erf(v / sqr
 
 // BM: rows of x per workgroup, 256 or 128 (BM / 64 wavefront rows); BN: rows of w (output channels)
 // per workgroup, 256, 192 or 128 (BN / 64 wavefront columns).
-template <int BM, int BN>
+// S: LDS buffers of one K slice each (2 or 4); S - 1 slices are in flight while one is multiplied.
+template <int BM, int BN, int S>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs a, int tiles_n, int tiles_total) {
+    static_assert(S == 2 || S == 4, "two or four slice buffers");
     constexpr int kBM = BM, kBN = BN, kWM = BM / 64, kWN = BN / 64, kWaves = kWM * kWN;
     constexpr int kXBytes = kBM * kBK * 2;                  // x rows of one buffer
     constexpr int kStageBytes = kXBytes + BN * kBK * 2;
@@ -189,22 +191,36 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(Con
 #pragma unroll
         for (int j = 0; j < kTN; ++j) wf[f][j] = *reinterpret_cast<const u32x4 *>(base + woff[j] + (((2 * q + half) ^ wsw[j]) << 4));
     };
-    fetch(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // Direct loads complete in order: "at most n later slices outstanding" is vmcnt(n * loads per slice).
+    constexpr int kLoads = XI + WI;
+    auto wait_slices = [&](int later) {
+        if (S == 2 || later <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kLoads) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kLoads) : "memory");
+    };
+#pragma unroll
+    for (int i = 0; i < S - 1; ++i)
+        if (i < nslices) fetch(i, i);
+    wait_slices((nslices - 1 < S - 2) ? nslices - 1 : S - 2);          // slice 0 has landed
     __syncthreads();
-    if (nslices > 1) fetch(1, 1);
+    if (S - 1 < nslices) fetch(S - 1, S - 1);
     read_step(0, 0, 0);
     for (int t = 0; t < nslices; ++t) {
-        const int buf = t & 1;
+        const int buf = t & (S - 1);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (q == 3) {
-                // this wavefront's loads of slice t + 1 have landed, and its last reads of buffer `buf`
-                // (step 3's pieces, requested during step 2) are in registers
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                // this wavefront's loads of slice t + 1 have landed (those of the slices after it may still
+                // travel), and its last reads of buffer `buf` (step 3's pieces, requested during step 2) are
+                // in registers
+                {
+                    const int last = t + S - 1 < nslices - 1 ? t + S - 1 : nslices - 1;   // last slice requested so far
+                    wait_slices(last - (t + 1));
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __syncthreads();                   // everyone's have
-                if (t + 2 < nslices) fetch(t + 2, buf);
-                if (t + 1 < nslices) read_step(buf ^ 1, 0, 0);
+                if (t + S < nslices) fetch(t + S, buf);
+                if (t + 1 < nslices) read_step((t + 1) & (S - 1), 0, 0);
             } else {
                 read_step(buf, q + 1, (q + 1) & 1);
             }
@@ -325,8 +341,8 @@ namespace {
 // With cold operands the two-deep pipeline of this kernel is short: one slice ahead does not cover a
 // miss to HBM, and the tiled kernel's three workgroups per CU cover each other's.  So the narrow tiles
 // take only the layers with at most 128 output channels, where they win both ways.
-struct Tile { int bm, bn; };
-const Tile kTiles[] = {{256, 256}, {256, 192}, {128, 128}};
+struct Tile { int bm, bn, stages; };
+const Tile kTiles[] = {{256, 256, 2}, {256, 192, 2}, {128, 128, 2}, {128, 128, 4}};
 
 long long tiles_of(const ConvArgs &a, const Tile &t) {
     return (((long long)a.M + t.bm - 1) / t.bm) * ((a.Cout + t.bn - 1) / t.bn);
@@ -341,50 +357,67 @@ const Tile &pick_tile(const ConvArgs &a) {
     return c192 < c256 ? kTiles[1] : kTiles[0];
 }
 
-template <int BM, int BN>
+// The tile a layer runs on, or nullptr where this kernel does not apply.  A layer that fills the chip
+// takes the two-buffer tiles above.  One that does not (2048 -> 512 on 7 x 7 images: 196 tiles of
+// 128 x 128; a classifier: 8) is a chain of slice latencies - about 0.8 us per slice of 64 on the tiled
+// kernel, whatever else the chip does - so with a long reduction it takes 128 x 128 tiles with FOUR
+// slice buffers: three slices in flight per workgroup (128 KB of LDS: one workgroup per CU, which is
+// all such a layer has).
+const Tile *choose_tile(const ConvArgs &a) {
+    if (!a.bf16 || a.R != 1 || a.S != 1 || a.stride < 1 || a.pad != 0) return nullptr;
+    if (a.Cin % 64 || a.Cin < 256 || a.Cout % 8 || a.Cout < 128) return nullptr;
+    if (a.Cout <= 128 || a.Cout >= 192) {
+        const Tile &t = pick_tile(a);
+        const long long tiles = tiles_of(a, t);
+        if (tiles > 0x3FFFFFF0LL) return nullptr;
+        if (tiles >= (a.Cout <= 128 ? 512 : 128)) return &t;
+    }
+    if (a.Cin >= 512 && tiles_of(a, kTiles[3]) <= 512) return &kTiles[3];
+    return nullptr;
+}
+
+template <int BM, int BN, int S>
 hipError_t launch_tile(const ConvArgs &a, hipStream_t stream) {
-    constexpr size_t pipe = (size_t)gemm::kStages * ((size_t)BM * gemm::kBK * 2 + (size_t)BN * gemm::kBK * 2);
+    constexpr size_t pipe = (size_t)S * ((size_t)BM * gemm::kBK * 2 + (size_t)BN * gemm::kBK * 2);
     constexpr size_t stage_out = (size_t)(BM / 64) * (BN / 64) * 32 * gemm::kStgPitch;
     constexpr size_t lds = pipe > stage_out ? pipe : stage_out;
+    static_assert(lds <= 160 * 1024, "LDS");
     constexpr int threads = (BM / 64) * (BN / 64) * 64;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.Cout + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n;
     const long long blocks = (total + 7) / 8 * 8;
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm::gemm_nt_kernel<BM, BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm::gemm_nt_kernel<BM, BN, S>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    gemm::gemm_nt_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(threads), lds, stream>>>(a, tiles_n, (int)total);
+    gemm::gemm_nt_kernel<BM, BN, S><<<dim3((unsigned)blocks), dim3(threads), lds, stream>>>(a, tiles_n, (int)total);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// bf16 1x1 stride-1 layers (rows of x contiguous) with a reduction axis of at least 256 and enough
-// output to fill the chip with its tiles.
-bool gemm_nt_applies(const ConvArgs &a) {
-    if (!a.bf16 || a.R != 1 || a.S != 1 || a.stride < 1 || a.pad != 0) return false;
-    if (a.Cin % 64 || a.Cin < 256 || a.Cout % 8 || a.Cout < 128 || (a.Cout > 128 && a.Cout < 192)) return false;
-    const long long tiles = tiles_of(a, pick_tile(a));
-    return tiles >= (a.Cout <= 128 ? 512 : 128) && tiles <= 0x3FFFFFF0LL;
-}
+// bf16 1x1 layers (rows of x contiguous) with a reduction axis of at least 256 and either enough
+// output to fill the chip with the two-buffer tiles or a reduction long enough for the four-buffer one.
+bool gemm_nt_applies(const ConvArgs &a) { return choose_tile(a) != nullptr; }
 
 const char *gemm_nt_kernel_name(const ConvArgs &a) {
-    const Tile &t = pick_tile(a);
-    if (t.bm == 256)
-        return t.bn == 256 ? "gemm_nt bf16 256x256 (64x64 per wave, direct-to-LDS)"
-                           : "gemm_nt bf16 256x192 (64x64 per wave, direct-to-LDS)";
-    return "gemm_nt bf16 128x128 (64x64 per wave, direct-to-LDS)";
+    const Tile *t = choose_tile(a);
+    if (!t) return "";
+    if (t->bm == 256)
+        return t->bn == 256 ? "gemm_nt bf16 256x256 (64x64 per wave, direct-to-LDS)"
+                            : "gemm_nt bf16 256x192 (64x64 per wave, direct-to-LDS)";
+    return t->stages == 4 ? "gemm_nt bf16 128x128, four slice buffers (64x64 per wave, direct-to-LDS)"
+                          : "gemm_nt bf16 128x128 (64x64 per wave, direct-to-LDS)";
 }
 
 hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream) {
-    if (conv_check(a) || !gemm_nt_applies(a)) return hipErrorInvalidValue;
-    const Tile &t = pick_tile(a);
-    if (t.bm == 256) return t.bn == 256 ? launch_tile<256, 256>(a, stream) : launch_tile<256, 192>(a, stream);
-    return launch_tile<128, 128>(a, stream);
+    const Tile *t = conv_check(a) ? nullptr : choose_tile(a);
+    if (!t) return hipErrorInvalidValue;
+    if (t->bm == 256) return t->bn == 256 ? launch_tile<256, 256, 2>(a, stream) : launch_tile<256, 192, 2>(a, stream);
+    return t->stages == 4 ? launch_tile<128, 128, 4>(a, stream) : launch_tile<128, 128, 2>(a, stream);
 }
 
 }  // namespace delta

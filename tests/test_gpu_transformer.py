@@ -112,7 +112,12 @@ def test_layernorm_matches_oracle(torch_mod, rows, C):
 
 
 @pytest.mark.parametrize("case", [("gelu", 2, 70, 128, 192, "gelu", False), ("res", 1, 45, 768, 64, None, True),
-                                  ("ffn2", 1, 40, 512, 128, None, True), ("plain", 3, 33, 64, 256, None, False),
+                                  ("plain", 3, 33, 64, 256, None, False),
+                                  # few tiles and a long reduction: the GEMM kernel's 128 x 128 tile with four slice
+                                  # buffers (8, 16 and 20 slices; one tile, ragged rows, ragged channels)
+                                  ("gemm4_ffn2", 1, 40, 512, 128, None, True),
+                                  ("gemm4_ragged", 3, 211, 1024, 200, "gelu", True),
+                                  ("gemm4_short_tail", 1, 300, 1280, 136, "relu", False),
                                   # large enough for the 256 x 256-tiled GEMM kernel; ragged rows and channels
                                   ("gemm_gelu", 1, 8465, 256, 1024, "gelu", False),
                                   ("gemm_res_ragged_n", 1, 8300, 768, 776, None, True),
