@@ -93,7 +93,7 @@ __device__ __forceinline__ float gelu_erf(float v) {     // v/2 (1 + erf(v / sqr
 // S: LDS buffers of one K slice each (2 or 4); S - 1 slices are in flight while one is multiplied.
 template <int BM, int BN, int S>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(ConvArgs a, int tiles_n, int tiles_total) {
-    static_assert(S == 2 || S == 4, "two or four slice buffers");
+    static_assert(S >= 2 && S <= 4, "two to four slice buffers");
     constexpr int kBM = BM, kBN = BN, kWM = BM / 64, kWN = BN / 64, kWaves = kWM * kWN;
     constexpr int kXBytes = kBM * kBK * 2;                  // x rows of one buffer
     constexpr int kStageBytes = kXBytes + BN * kBK * 2;
@@ -206,7 +206,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(Con
     if (S - 1 < nslices) fetch(S - 1, S - 1);
     read_step(0, 0, 0);
     for (int t = 0; t < nslices; ++t) {
-        const int buf = t & (S - 1);
+        const int buf = t % S;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (q == 3) {
@@ -220,7 +220,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void gemm_nt_kernel(Con
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __syncthreads();                   // everyone's have
                 if (t + S < nslices) fetch(t + S, buf);
-                if (t + 1 < nslices) read_step((t + 1) & (S - 1), 0, 0);
+                if (t + 1 < nslices) read_step((t + 1) % S, 0, 0);
             } else {
                 read_step(buf, q + 1, (q + 1) & 1);
             }
@@ -336,13 +336,15 @@ namespace {
 //   256 -> 1024, 14 x 14    31.4         38.6         34.2
 //   1024 -> 512, 14 x 14    32.0         39.1         39.5
 //   512 -> 2048, 7 x 7      22.5         27.5         26.3
-// (128 x 256 for 1024 -> 256 at 14 x 14, twice the workgroups of the 256-wide tiles: 26 -> 22 us on its own,
-// no change inside the pass.)
+// 128 x 256 for 1024 -> 256 at 14 x 14 (196 workgroups without padded columns instead of 196 with a third of their
+// columns padding): 26 -> 22 us on its own, no change inside the pass with two slice buffers, 23 us less for the five
+// layers inside the pass with THREE (two slices in flight per workgroup); the same tile on 512 -> 2048 at 7 x 7 and
+// 1024 -> 512 at 14 x 14 was 20 % slower than 256 x 256.
 // With cold operands the two-deep pipeline of this kernel is short: one slice ahead does not cover a
 // miss to HBM, and the tiled kernel's three workgroups per CU cover each other's.  So the narrow tiles
 // take only the layers with at most 128 output channels, where they win both ways.
 struct Tile { int bm, bn, stages; };
-const Tile kTiles[] = {{256, 256, 2}, {256, 192, 2}, {128, 128, 2}, {128, 128, 4}};
+const Tile kTiles[] = {{256, 256, 2}, {256, 192, 2}, {128, 128, 2}, {128, 128, 4}, {128, 256, 3}};
 
 long long tiles_of(const ConvArgs &a, const Tile &t) {
     return (((long long)a.M + t.bm - 1) / t.bm) * ((a.Cout + t.bn - 1) / t.bn);
@@ -353,6 +355,7 @@ long long tiles_of(const ConvArgs &a, const Tile &t) {
 // batch 32 x 512: a quarter of the chip idle) but 4 tiles of 192 (256 workgroups, one full round).
 const Tile &pick_tile(const ConvArgs &a) {
     if (a.Cout <= 128) return kTiles[2];
+    if (a.Cout <= 256 && tiles_of(a, kTiles[0]) < 192) return kTiles[4];
     const long long c256 = ((tiles_of(a, kTiles[0]) + 255) / 256) * 256, c192 = ((tiles_of(a, kTiles[1]) + 255) / 256) * 192;
     return c192 < c256 ? kTiles[1] : kTiles[0];
 }
@@ -409,6 +412,7 @@ const char *gemm_nt_kernel_name(const ConvArgs &a) {
     if (t->bm == 256)
         return t->bn == 256 ? "gemm_nt bf16 256x256 (64x64 per wave, direct-to-LDS)"
                             : "gemm_nt bf16 256x192 (64x64 per wave, direct-to-LDS)";
+    if (t->bn == 256) return "gemm_nt bf16 128x256, three slice buffers (64x64 per wave, direct-to-LDS)";
     return t->stages == 4 ? "gemm_nt bf16 128x128, four slice buffers (64x64 per wave, direct-to-LDS)"
                           : "gemm_nt bf16 128x128 (64x64 per wave, direct-to-LDS)";
 }
@@ -417,6 +421,7 @@ hipError_t launch_gemm_nt(const ConvArgs &a, hipStream_t stream) {
     const Tile *t = conv_check(a) ? nullptr : choose_tile(a);
     if (!t) return hipErrorInvalidValue;
     if (t->bm == 256) return t->bn == 256 ? launch_tile<256, 256, 2>(a, stream) : launch_tile<256, 192, 2>(a, stream);
+    if (t->bn == 256) return launch_tile<128, 256, 3>(a, stream);
     return t->stages == 4 ? launch_tile<128, 128, 4>(a, stream) : launch_tile<128, 128, 2>(a, stream);
 }
 
