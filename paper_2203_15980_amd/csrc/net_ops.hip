@@ -288,7 +288,13 @@ hipError_t launch_stem(const ConvArgs &a, hipStream_t stream) {
 // One thread: 16 bytes of channels (8 bf16 or 4 fp32) of one output pixel.
 template <bool BF16>
 __global__ __launch_bounds__(256) void maxpool_kernel(PoolArgs a, long long total) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    // Workgroups are dealt round-robin to the 8 XCDs; each XCD takes a contiguous range of outputs, so
+    // that the input rows two neighbouring output rows share are fetched into one L2, once (with
+    // neighbouring output rows on different XCDs the 3 x 3 stride-2 pool fetched 1.5 x its input).
+    const unsigned nb = gridDim.x, per = nb >> 3, rem = nb & 7u;
+    const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const unsigned logical = xcd < rem ? xcd * (per + 1) + slot : rem * (per + 1) + (xcd - rem) * per + slot;
+    const long long idx = (long long)logical * 256 + threadIdx.x;
     if (idx >= total) return;
     constexpr int CPT = BF16 ? 8 : 4;
     const int chunks = a.C / CPT;
