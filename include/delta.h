@@ -121,6 +121,14 @@ typedef struct {
                                               reload), at most this many times.  The operator sequence
                                               repeats every iteration (Assumption 1), so a failed
                                               iteration can teach the next.  0: fail at once */
+    uint32_t prefetch_rebuild_reads;       /* 0: Algorithm 4's queue is ordered by, and its look-ahead held
+                                              against, the next step that reads the offloaded tensor.
+                                              1: an access by a recomputation counts as well (Algorithm 1
+                                              accesses the parents of what it recomputes): the tensor is
+                                              wanted as soon as a step reads a tensor that is neither on the
+                                              GPU nor in host memory and whose recomputation reaches it
+                                              through such tensors; reloaded for that reason it is a leftover
+                                              of a recomputation (first to give way when memory is short) */
 } delta_plan_params;
 
 typedef struct { uint32_t step, action, tensor, pad; } delta_event;

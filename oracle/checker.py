@@ -36,6 +36,10 @@ def check(tensors, steps, params, events, check_trigger=True, check_prefetch_win
     for k, st in enumerate(steps):
         for t in st["reads"]:
             last_read[t] = k
+    children = [[] for _ in range(nT)]
+    for c, tc in enumerate(tensors):
+        for q in tc["parents"]:
+            children[q].append(c)
     resident = [False] * nT
     host = [False] * nT
     provisional = [False] * nT      # on the GPU only as a leftover operand of a recomputation
@@ -45,6 +49,19 @@ def check(tensors, steps, params, events, check_trigger=True, check_prefetch_win
 
     def fail(k, msg):
         raise PlanError("step %d: %s" % (k, msg))
+
+    def wanted(t, k, seen):
+        """First step >= k that reads t; with prefetch_rebuild_reads also through the recomputation of
+        a tensor that is on neither side of the link (such a tensor is rebuilt from its parents)."""
+        first = min([s for s in range(k, len(steps)) if t in steps[s]["reads"]], default=None)
+        if params.get("prefetch_rebuild_reads") and t not in seen:
+            seen = seen | {t}
+            for c in children[t]:
+                if not resident[c] and not host[c] and not (tensors[c]["flags"] & UNCOMPUTABLE):
+                    u = wanted(c, k, seen)
+                    if u is not None and (first is None or u < first):
+                        first = u
+        return first
 
     by_step = [[] for _ in steps]
     prev = 0
@@ -114,12 +131,14 @@ def check(tensors, steps, params, events, check_trigger=True, check_prefetch_win
                     if check_prefetch_window:
                         if fwd:
                             fail(k, "prefetch in the forward pass")
-                        nxt = min([s for s in range(k, len(steps)) if t in steps[s]["reads"]],
-                                  default=None)
+                        nxt = wanted(t, k, frozenset())
                         if nxt is None or nxt > k + params["prefetch_distance"]:
                             fail(k, "prefetch of %d outside the look-ahead window" % t)
                         if prefetched > params["max_reloads"]:
                             fail(k, "more than n prefetches in one step")
+                        own = min([s for s in range(k, len(steps)) if t in steps[s]["reads"]], default=None)
+                        if own is None or nxt < own:     # back for a recomputation: a leftover like the operands it reloads
+                            provisional[t] = True
                     stats["reload_prefetch"] += 1
                 else:
                     provisional[t] = t not in locked
@@ -172,7 +191,9 @@ def check(tensors, steps, params, events, check_trigger=True, check_prefetch_win
             stats["free"] += 1
         for t in range(nT):
             if resident[t] and last_read[t] <= k:
-                fail(k, "dead tensor %d left on the GPU" % t)
+                # prefetch_rebuild_reads: a tensor may wait for the recomputation it was prefetched for
+                if not (provisional[t] and wanted(t, k + 1, frozenset()) is not None):
+                    fail(k, "dead tensor %d left on the GPU" % t)
     if live != 0:
         fail(len(steps) - 1, "memory not returned at the end")
     stats["peak"] = peak

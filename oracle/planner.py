@@ -20,7 +20,14 @@ and notation:
     c_s is the time to offload plus the time to reload (Sec. 3); c_r is the
     tensor's own cost plus that of its non-resident ancestors (Sec. 3, Eq. 5).
   * Prefetcher (Algorithm 4): reload the head of the offloaded queue while
-    memory allows and fewer than n reloads have been issued.
+    memory allows and fewer than n reloads have been issued.  With the parameter
+    prefetch_rebuild_reads the "next use" that orders the queue and is held against
+    the look-ahead also counts the accesses Algorithm 1 makes on the way to a
+    recomputation: an offloaded tensor is needed as soon as a step reads a tensor
+    that is neither on the GPU nor in host memory and whose recomputation reaches
+    it through such tensors.  A tensor reloaded for that reason is a leftover of a
+    recomputation like the operands a recomputation reloads itself (it gives way
+    first when an allocation does not fit).
   * Assumption 2: no Evict/Offload after the last forward step -- unless the
     parameter release_when_short is set: then Algorithm 1 is taken literally
     (its release loop stands behind every access, and "memory is not enough" is
@@ -85,7 +92,7 @@ def swap_cost_ns(nbytes, bw_d2h, bw_h2d):
 def default_params(budget, n_fwd, **kw):
     p = dict(budget_bytes=int(budget), trigger_num=3, trigger_den=4, filter=FILTER_BASE,
              prefetch_distance=2, max_reloads=2, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9,
-             n_fwd_steps=int(n_fwd), release_when_short=0)
+             n_fwd_steps=int(n_fwd), release_when_short=0, prefetch_rebuild_reads=0)
     p.update(kw)
     return p
 
@@ -121,6 +128,10 @@ class _Sim:
         for k, st in enumerate(steps):
             for t in st["reads"]:
                 self.reads_at[t].append(k)
+        self.children = [[] for _ in range(n)]
+        for c, t in enumerate(tensors):
+            for q in t["parents"]:
+                self.children[q].append(c)
         self.tau = 0
         self.live = 0
         self.peak = 0
@@ -215,6 +226,12 @@ class _Sim:
                     self.drop(p)
                 else:
                     self.provisional[p] = True
+            for p in parents:
+                # a parent that was prefetched for this recomputation (prefetch_rebuild_reads) and that
+                # no step reads goes the way of the parents the recomputation brought back itself
+                if (p not in mine and self.provisional[p] and p not in self.locked and p not in self.held
+                        and self.next_read(p, self.k + 1) is None):
+                    self.drop(p)
         elif self.swapout[t]:
             self.grow(self.T[t]["bytes"])
             self.emit(EV_RELOAD_DEMAND, t)
@@ -263,14 +280,31 @@ class _Sim:
         return EV_EVICT if self.recompute_cost(t) <= c_s else EV_OFFLOAD
 
     # -- Algorithm 4 -------------------------------------------------------
+    def rebuild_read(self, t, memo):
+        """Earliest step from the running one on that reads t or, through tensors that are neither
+        on the GPU nor in host memory (an access recomputes them, Algorithm 1, and a recomputation
+        accesses its parents), a descendant of t; None when there is none."""
+        if t in memo:
+            return memo[t]
+        best = self.next_read(t, self.k)
+        for c in self.children[t]:
+            if not self.resident[c] and not self.swapout[c] and self.computable(c):
+                u = self.rebuild_read(c, memo)
+                if u is not None and (best is None or u < best):
+                    best = u
+        memo[t] = best
+        return best
+
     def prefetch(self):
         d, n = self.p["prefetch_distance"], self.p["max_reloads"]
+        wide = bool(self.p.get("prefetch_rebuild_reads"))
         issued = 0
         while issued < n:
             q = []
+            memo = {}
             for t in range(len(self.T)):
                 if self.swapout[t] and not self.resident[t]:
-                    nr = self.next_read(t, self.k)
+                    nr = self.rebuild_read(t, memo) if wide else self.next_read(t, self.k)
                     if nr is not None:
                         q.append((nr, t))
             if not q:
@@ -282,6 +316,9 @@ class _Sim:
             self.live += self.T[head]["bytes"]
             self.peak = max(self.peak, self.live)
             self.resident[head] = True
+            own = self.next_read(head, self.k)
+            if own is None or nr < own:                  # back for a recomputation, not for a step of its own
+                self.provisional[head] = True
             issued += 1
 
     # -- one step ----------------------------------------------------------

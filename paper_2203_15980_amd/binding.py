@@ -43,7 +43,8 @@ class PlanParams(C.Structure):
     _fields_ = [("budget_bytes", C.c_uint64), ("trigger_num", C.c_uint32), ("trigger_den", C.c_uint32),
                 ("filter", C.c_uint32), ("prefetch_distance", C.c_uint32), ("max_reloads", C.c_uint32),
                 ("n_fwd_steps", C.c_uint32), ("bw_d2h_Bps", C.c_uint64), ("bw_h2d_Bps", C.c_uint64),
-                ("release_when_short", C.c_uint32), ("repair_rounds", C.c_uint32)]
+                ("release_when_short", C.c_uint32), ("repair_rounds", C.c_uint32),
+                ("prefetch_rebuild_reads", C.c_uint32)]
 
 
 class Event(C.Structure):
@@ -150,7 +151,7 @@ def layer_array(descs):
     return arr
 
 
-_OPTIONAL_PLAN_PARAMS = ("release_when_short", "repair_rounds")      # 0 when the caller leaves them out
+_OPTIONAL_PLAN_PARAMS = ("release_when_short", "repair_rounds", "prefetch_rebuild_reads")   # 0 when the caller leaves them out
 
 
 def _plan_params(params):

@@ -100,6 +100,12 @@ class Manager {
         }
         for (uint32_t k = 0; k < steps.size(); ++k)
             for (uint32_t t : steps[k].reads) rec_[t].uses.push_back(k);
+        if (cfg_.prefetch_rebuild_reads) {
+            consumers_.resize(tensors.size());
+            for (uint32_t t = 0; t < tensors.size(); ++t)
+                for (uint32_t p : tensors[t].parents) consumers_[p].push_back(t);
+            wanted_.resize(tensors.size());
+        }
     }
 
     // One operator of the sequence.  Throws OutOfMemory.
@@ -147,6 +153,8 @@ class Manager {
     const delta_plan_params &cfg_;
     std::vector<Record> rec_;
     std::vector<uint32_t> mark_;       // visit stamps of the ancestor walk
+    std::vector<std::vector<uint32_t>> consumers_;   // prefetch_rebuild_reads: the tensors computed from each tensor
+    std::vector<uint32_t> wanted_;     // ... and, per prefetch round, when each tensor is wanted (kNoStep - 1: not worked out yet)
     uint32_t stamp_ = 0;
     uint32_t now_ = 0;
     uint64_t clock_ = 0, in_use_ = 0;
@@ -207,6 +215,15 @@ class Manager {
                 } else {
                     q.leftover = true;
                 }
+            }
+            // a parent that the Prefetcher brought back for this recomputation (prefetch_rebuild_reads)
+            // and that no operator reads leaves like the ones the recomputation fetched itself
+            for (uint32_t p : parents) {
+                Record &q = rec_[p];
+                if (!q.on_gpu || !q.leftover || q.operand || q.rebuilding || q.use_after(now_) != kNoStep) continue;
+                if (std::find(top.fetched.begin(), top.fetched.end(), p) != top.fetched.end()) continue;
+                note(DELTA_EV_DROP_TEMP, p);
+                vacate(q);
             }
             stack.pop_back();
         }
@@ -353,13 +370,31 @@ class Manager {
     }
 
     // ---- Algorithm 4
+    // When a tensor is wanted next: by a step that reads it, or - prefetch_rebuild_reads - by the
+    // recomputation of a tensor that a step reads: a tensor that is neither on the GPU nor in host
+    // memory is recomputed when it is accessed (Algorithm 1), and the recomputation accesses its parents.
+    uint32_t wanted_from_now(uint32_t t) {
+        const Record &r = rec_[t];
+        if (!cfg_.prefetch_rebuild_reads) return r.use_from_now();
+        if (wanted_[t] != kNoStep - 1) return wanted_[t];
+        uint32_t first = r.use_from_now();
+        for (uint32_t c : consumers_[t]) {
+            const Record &rc = rec_[c];
+            if (rc.on_gpu || rc.host_copy || rc.uncomputable) continue;
+            first = std::min(first, wanted_from_now(c));
+        }
+        wanted_[t] = first;
+        return first;
+    }
+
     void prefetch() {
         for (uint32_t issued = 0; issued < cfg_.max_reloads; ++issued) {
+            if (cfg_.prefetch_rebuild_reads) std::fill(wanted_.begin(), wanted_.end(), kNoStep - 1);
             uint32_t head = kNoTensor, head_use = kNoStep;
             for (uint32_t t = 0; t < rec_.size(); ++t) {
                 const Record &r = rec_[t];
                 if (r.on_gpu || !r.host_copy) continue;
-                const uint32_t u = r.use_from_now();
+                const uint32_t u = wanted_from_now(t);
                 if (u < head_use) {                      // kNoStep (never used again) is never below
                     head = t;
                     head_use = u;
@@ -371,6 +406,8 @@ class Manager {
             note(DELTA_EV_RELOAD_PREFETCH, head);
             occupy(rec_[head].memory);
             rec_[head].on_gpu = true;
+            // back for a recomputation rather than for a step of its own: a leftover, first to give way
+            if (head_use < rec_[head].use_from_now()) rec_[head].leftover = true;
         }
     }
 };
@@ -417,7 +454,7 @@ delta_status load_graph(const delta_tensor_desc *tensors, uint32_t n_tensors,
     }
     if (params->trigger_den == 0 || params->trigger_num > params->trigger_den ||
         params->filter > DELTA_FILTER_GREEDY || params->n_fwd_steps > n_steps ||
-        params->release_when_short > 1) {
+        params->release_when_short > 1 || params->prefetch_rebuild_reads > 1) {
         err = "bad plan parameters";
         return DELTA_ERR_INVALID;
     }

@@ -324,6 +324,61 @@ def test_swap_round_trip_of_tensors_larger_than_one_copy_piece(torch_mod):
     d.close()
 
 
+def test_replay_with_prefetch_for_recomputations_hands_every_step_its_forward_bits(torch_mod):
+    """prefetch_rebuild_reads: a plan in which the Prefetcher brings a tensor back for a recomputation (ahead of
+    the step that reads the recomputed tensor, and possibly after the tensor's own last read) replays with the bits
+    of the unconstrained forward at every backward step.  The plan is the first, over filters, links and budgets,
+    that the switch changes; it equals the oracle's."""
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net, run_plan
+    torch = torch_mod
+    layers = synth.bottleneck_stack(4, 56, 56)
+    g = synth.fused_graph(layers, "bf16")
+    d0 = make_delta(torch, g.total_bytes() + (1 << 20))
+    d0.bind([t["bytes"] for t in g.tensors])
+    net0 = Net(d0, layers, "bf16", 21)
+    net0.forward()
+    want = {t["name"]: net0.read(t["name"]).copy() for t in g.tensors}
+    d0.close()
+    found = None
+    for frac in (0.5, 0.6, 0.7, 0.45):
+        for kind in (dl.FILTER_BASE, dl.FILTER_LRU, dl.FILTER_GREEDY):
+            for bw in (2 * 10**9, 20 * 10**9, 10**12):
+                p = opl.default_params(int(g.total_bytes() * frac), g.n_fwd, filter=kind, bw_d2h_Bps=bw, bw_h2d_Bps=bw,
+                                       prefetch_distance=2, max_reloads=2, release_when_short=1, repair_rounds=4,
+                                       prefetch_rebuild_reads=1)
+                try:
+                    ev, peak = dl.plan(g.tensors, g.steps, p)
+                    ev0, _ = dl.plan(g.tensors, g.steps, dict(p, prefetch_rebuild_reads=0))
+                except dl.DeltaError as e:
+                    assert e.status == dl.ERR_INFEASIBLE
+                    continue
+                if ev != ev0 and found is None:
+                    assert (ev, peak) == opl.plan(g.tensors, g.steps, p)
+                    found = (ev, p)
+    assert found is not None, "the switch changed no plan of this graph"
+    ev, p = found
+    pre = [(k, g.tensors[t]["name"]) for (k, a, t) in ev if a == dl.EV_RELOAD_PREFETCH]
+    print("budget", p["budget_bytes"], "filter", p["filter"], "link", p["bw_d2h_Bps"], "prefetches", pre, flush=True)
+    d = make_delta(torch, p["budget_bytes"] * 3 // 2)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", 21)
+    checked = []
+
+    def proxy(k):
+        for t in g.steps[k]["reads"]:
+            n = g.tensors[t]["name"]
+            assert net.read(n).tobytes() == want[n].tobytes(), (k, n)
+            checked.append(n)
+
+    run_plan(net, g, ev, backward_proxy=proxy)
+    d.sync()
+    st = d.stats()
+    assert checked and st["arena_in_use"] == 0
+    assert st["arena_high_water"] <= p["budget_bytes"]
+    d.close()
+
+
 @pytest.mark.parametrize("dtype,N,HW", [("f32", 2, 32), ("bf16", 4, 56)])
 def test_plan_replay_hands_every_step_its_forward_bits(torch_mod, dtype, N, HW):
     """Plan with delta_plan at a 50 % budget, replay it in an arena of exactly that size, and

@@ -306,7 +306,7 @@ def test_training_step_replay_repeats_its_gradients_bit_for_bit(torch_mod, case)
     del d
     torch.cuda.empty_cache()
     budget = int(g.total_bytes() * amount) if how == "frac" else amount
-    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9, repair_rounds=8)
+    p = opl.default_params(budget, g.n_fwd, bw_d2h_Bps=50 * 10**9, bw_h2d_Bps=50 * 10**9, repair_rounds=8, prefetch_rebuild_reads=1)
     ev, peak = dl.plan(g.tensors, g.steps, p)
     kinds = {a for (_, a, _) in ev}
     arena_bytes = (int(act_mult * budget) + int(grad_mult * grad_peak) + 255) // 256 * 256

@@ -176,6 +176,52 @@ def test_plans_match_oracle_on_random_graphs():
     assert ok > 300 and bad > 30        # both outcomes are exercised
 
 
+def test_plans_match_oracle_with_rebuild_aware_prefetch():
+    """prefetch_rebuild_reads: the library's reading of "wanted by a recomputation" against the oracle's, on
+    random graphs (every switch drawn), on the configurations, and on the two hand-worked traces."""
+    rnd = random.Random(1598)
+    ok = bad = moved = 0
+    for trial in range(700):
+        T, S, n_fwd = _random_graph(rnd, rnd.randint(3, 40))
+        total = sum(t["bytes"] for t in T)
+        p = pl.default_params(int(total * rnd.uniform(0.15, 0.9)), n_fwd,
+                              filter=rnd.randrange(3), prefetch_distance=rnd.randrange(1, 6),
+                              max_reloads=rnd.randrange(1, 4),
+                              trigger_num=rnd.choice([1, 3, 3, 7]), trigger_den=rnd.choice([4, 8]),
+                              bw_d2h_Bps=rnd.choice([10**8, 10**9, 10**12]), bw_h2d_Bps=rnd.choice([10**8, 10**9, 10**12]),
+                              release_when_short=rnd.randrange(2), repair_rounds=rnd.choice([0, 1, 4]),
+                              prefetch_rebuild_reads=1)
+        p["trigger_num"] = min(p["trigger_num"], p["trigger_den"])
+        try:
+            ev, peak, pins = pl.plan_with_pins(T, S, p)
+            want = (ev, peak)
+        except pl.Infeasible as e:
+            with pytest.raises(dl.DeltaError) as got:
+                dl.plan(T, S, p)
+            assert got.value.status == dl.ERR_INFEASIBLE and ("step %d:" % e.step) in got.value.message
+            bad += 1
+            continue
+        assert dl.plan(T, S, p) == want
+        # the checker sees the graph as the last repair round planned it (its learned offload-only tensors)
+        checker.check([dict(t, flags=t["flags"] | pl.UNCOMPUTABLE) if i in pins else t for i, t in enumerate(T)], S, p, ev)
+        ok += 1
+        try:
+            moved += pl.plan(T, S, dict(p, prefetch_rebuild_reads=0)) != want
+        except pl.Infeasible:
+            moved += 1
+    assert ok > 300 and bad > 10 and moved > 25, (ok, bad, moved)
+    for cfg, frac in [(3, 0.5), (4, 0.4), (5, 0.3)]:
+        g = synth.config_graph(cfg)
+        for bw in (20 * 10**9, 55 * 10**9):
+            p = pl.default_params(int(frac * g.total_bytes()), g.n_fwd, bw_d2h_Bps=bw, bw_h2d_Bps=bw, prefetch_distance=2,
+                                  max_reloads=2, release_when_short=1, repair_rounds=8, prefetch_rebuild_reads=1)
+            want = pl.plan(g.tensors, g.steps, p)
+            assert dl.plan(g.tensors, g.steps, p) == want
+            checker.check(g.tensors, g.steps, p, want[0])
+    with pytest.raises(dl.DeltaError):
+        dl.plan(g.tensors, g.steps, dict(p, prefetch_rebuild_reads=2))
+
+
 def test_plan_rejects_malformed_graphs():
     g = synth.config_graph(1)
     p = pl.default_params(g.total_bytes(), g.n_fwd)

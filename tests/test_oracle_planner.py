@@ -330,6 +330,67 @@ def test_handworked_demand_reload_of_an_uncomputable_parent_inside_a_recomputati
     assert e.value.step == 7
 
 
+def _late_source_chain(n, extra):
+    """chain(n), but `extra` backward steps that read t1 alone stand between the backward of layer 2
+    and the one step that reads the source t0: its own next use lies far behind the recomputation
+    that needs it."""
+    tensors, steps, n_fwd = chain(n)
+    steps = steps[:-1] + [dict(produces=-1, reads=[1], cost_ns=20) for _ in range(extra)] + steps[-1:]
+    return tensors, steps, n_fwd
+
+
+def test_handworked_prefetch_for_a_recomputation_one_generation():
+    """t0 (source, uncomputable) -> t1 -> ... -> t4, m = 4 each, B = 12 (three tensors), no link (every computable
+    tensor is evicted, t0 can only be offloaded), release loop at B, d = n = 1.  Backward steps: 5 reads (t3, t4),
+    6 (t2, t3), 7 (t1, t2), 8 and 9 t1 alone, 10 (t0, t1).
+    Forward: step 3 needs room: t0 (staleness 10) against t1 (0): OFFLOAD t0; step 4: t1 (10) against t2 (0): EVICT t1.
+    Algorithm 4 as printed looks at t0's own next read, step 10: nothing is prefetched before step 9, and at step 7
+    the recomputation of t1 reloads t0 on demand.  With prefetch_rebuild_reads t0 is wanted at step 7 - t1 is neither on
+    the GPU nor in host memory, step 7 reads it, its recomputation accesses t0 - so it is prefetched at step 6 = 7 - d
+    (8 bytes in use + 4 fit), and step 7 recomputes t1 without a reload.
+    Mutation: looking at own reads only moves the reload to (7, RELOAD_DEMAND, 0)."""
+    tensors, steps, n_fwd = _late_source_chain(5, 2)
+    p = pl.default_params(12, n_fwd, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0,
+                          prefetch_distance=1, max_reloads=1)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(3, "OFFLOAD", 0), (4, "EVICT", 1), (5, "FREE", 4), (6, "FREE", 3),
+                         (7, "RELOAD_DEMAND", 0), (7, "RECOMPUTE", 1), (7, "FREE", 2),
+                         (10, "FREE", 0), (10, "FREE", 1)]
+    checker.check(tensors, steps, p, ev)
+    p = dict(p, prefetch_rebuild_reads=1)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(3, "OFFLOAD", 0), (4, "EVICT", 1), (5, "FREE", 4), (6, "RELOAD_PREFETCH", 0),
+                         (6, "FREE", 3), (7, "RECOMPUTE", 1), (7, "FREE", 2), (10, "FREE", 0), (10, "FREE", 1)]
+    assert peak == 12
+    checker.check(tensors, steps, p, ev)
+    with pytest.raises(checker.PlanError):               # the same events are outside Algorithm 4's own window
+        checker.check(tensors, steps, dict(p, prefetch_rebuild_reads=0), ev)
+
+
+def test_handworked_prefetch_for_a_recomputation_two_generations_and_it_is_a_leftover():
+    """The same with six tensors: forward OFFLOAD t0 (step 3), EVICT t1 (4), EVICT t2 (5).  Backward: 6 reads
+    (t4, t5), 7 (t3, t4), 8 (t2, t3), 9 (t1, t2), 10 t1 alone, 11 (t0, t1).
+    Step 8 reads t2, which is gone; its recomputation accesses t1, gone as well, whose recomputation accesses t0:
+    t0 is wanted at step 8 and prefetched at step 7 (8 bytes in use + 4 fit).  It is back for a recomputation, not
+    for a step of its own, so it is a leftover: at step 8, after t1 is rebuilt (12 bytes in use), the allocation of
+    t2 does not fit and t0 - not an operand of the recomputation still in progress - gives way (DROP_TEMP, as after a
+    demand reload), t1 stays as a leftover for step 9, and t0 returns at step 10 for its own read at step 11.
+    Mutation: stopping at the first generation (t1's own read is step 9) prefetches nothing at step 7 and reloads
+    on demand at step 8; not marking the prefetched tensor a leftover makes step 8 infeasible."""
+    tensors, steps, n_fwd = _late_source_chain(6, 1)
+    p = pl.default_params(12, n_fwd, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0,
+                          prefetch_distance=1, max_reloads=1, prefetch_rebuild_reads=1)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(3, "OFFLOAD", 0), (4, "EVICT", 1), (5, "EVICT", 2), (6, "FREE", 5),
+                         (7, "RELOAD_PREFETCH", 0), (7, "FREE", 4),
+                         (8, "RECOMPUTE", 1), (8, "DROP_TEMP", 0), (8, "RECOMPUTE", 2), (8, "FREE", 3),
+                         (9, "FREE", 2), (10, "RELOAD_PREFETCH", 0), (11, "FREE", 0), (11, "FREE", 1)]
+    assert peak == 12
+    checker.check(tensors, steps, p, ev)
+    ev0, _ = pl.plan(tensors, steps, dict(p, prefetch_rebuild_reads=0))
+    assert (8, "RELOAD_DEMAND", 0) in names(ev0) and (7, "RELOAD_PREFETCH", 0) not in names(ev0)
+
+
 def test_handworked_release_when_memory_is_short_in_the_backward_pass():
     """Algorithm 1 taken literally (release_when_short): its release loop also runs when an
     allocation of the backward pass does not fit.  t0 (m 4, cost 5) -> t1 -> t2 -> t3 (m 8,
