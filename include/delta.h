@@ -140,11 +140,15 @@ enum { DELTA_ACT_NONE = 0, DELTA_ACT_RELU = 1, DELTA_ACT_GELU = 2 /* x/2 (1 + er
  * of an identity bottleneck whose three layers stand next to each other in the segment and run in ONE
  * launch: [1x1, 256 -> 64, ReLU] [3x3, 64 -> 64, stride 1, pad 1, ReLU, x = the first layer's y]
  * [1x1, 64 -> 256, ReLU, x = the second layer's y, res = the first layer's x], bf16.
+ * Or it is the first of a stage's first bottleneck (config 2's block 1), whose FOUR layers stand next
+ * to each other: [1x1, 64 -> 64, ReLU] [3x3, 64 -> 64, stride 1, pad 1, ReLU, x = the first layer's y]
+ * [the projection shortcut: 1x1, 64 -> 256, no activation, x = the first layer's x]
+ * [1x1, 64 -> 256, ReLU, x = the second layer's y, res = the projection's y].
  * Only the first layer's x has to be resident: every output is regenerated from it, and an
- * output whose layer carries DELTA_FUSE_NO_STORE is neither allocated nor written (at least one of
- * the three must be stored).  The arithmetic does not depend on which outputs are stored, and every
+ * output whose layer carries DELTA_FUSE_NO_STORE is neither allocated nor written (at least one
+ * must be stored).  The arithmetic does not depend on which outputs are stored, and every
  * reduction runs in the order of the per-layer kernels: a tensor carries the same bits whether the
- * block kernel or the three per-layer launches produced it, so a plan may regenerate it with either. */
+ * block kernel or the per-layer launches produced it, so a plan may regenerate it with either. */
 enum { DELTA_FUSE_NONE = 0, DELTA_FUSE_BLOCK = 1, DELTA_FUSE_NO_STORE = 2 };
 
 /* One layer.  DELTA_OP_CONV: y = act(scale_k * conv(x, w) + shift_k (+ res)), activations

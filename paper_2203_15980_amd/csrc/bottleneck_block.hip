@@ -1,5 +1,6 @@
-// Block kernel: one identity bottleneck of ResNet's conv2_x stage in a single launch (bf16, fp32
-// accumulate):   a1 = relu(bn1(w1 . x))            1x1, 256 -> 64
+// Block kernel: one bottleneck of ResNet's conv2_x stage in a single launch (bf16, fp32 accumulate).
+// The identity blocks:
+//                a1 = relu(bn1(w1 . x))             1x1, 256 -> 64
 //                a2 = relu(bn2(conv3x3(a1, w2)))    3x3, 64 -> 64, stride 1, pad 1
 //                out = relu(bn3(w3 . a2) + x)       1x1, 64 -> 256, identity shortcut
 // This is the recompute segment DELTA's Recompute action re-runs for a released activation of such
@@ -26,6 +27,12 @@
 // column axis; lane half h owns bytes [64h, 64h + 64) of every 128-byte slice of both operands.
 // The order of every sum is fixed and does not depend on which tensors are stored, so whatever
 // this kernel produced in the forward pass it reproduces bit for bit in a recomputation.
+// The stage's first block (template argument PROJ; 64 input channels) has a projection in place of the identity
+// shortcut: sc = bn_sc(wsc . x), 1x1, 64 -> 256, no ReLU - a fourth tensor the launch can store.  Phase 1 then
+// reads one 128-byte slice per position; phase 3 multiplies each 64-channel group twice, wsc . x (the lane's half of
+// its pixel's x row, read again from the caches: 64 bytes) rounded to bf16 as the stored sc is, then w3 . a2 with
+// that added; w3 and wsc share the weight region of LDS, 128 rows each at a time (the second halves travel in
+// registers while the first are multiplied).
 // Every reduction also runs in the order of the per-layer kernels (slices of the input channels in order,
 // the 3x3's taps in order, lane half h supplying bytes [64 h, 64 h + 64) of each 128-byte operand slice),
 // so the three tensors carry the bits the three per-layer launches produce: a plan may regenerate a
@@ -53,8 +60,9 @@ static constexpr int kW1Pitch = kCin * 2 + 16;           // 528
 static constexpr int kTap = kMid * kPitch;               // one 64 x 64 tap of w2 in LDS: 9216 bytes
 static constexpr int kRA = 256 * kPitch;                 // the a1 halo tile; later one store tile per wavefront
 static constexpr int kRB = kCout * kPitch;               // w1, then three taps of w2 at a time, then w3
-static constexpr int kRD = (2 * kMid + 2 * kMid + 2 * kCout) * 4;   // scale/shift of the three layers
+static constexpr int kRD = (2 * kMid + 2 * kMid + 2 * kCout + 2 * kCout) * 4;   // scale/shift of the three layers and of a projection shortcut
 static constexpr int kLds = kRA + kRB + kRD;
+static constexpr int kCinProj = 64;                      // input channels of the block with a projection shortcut
 static_assert(kW1Pitch * kMid <= kRB && 3 * kTap <= kRB && kWaves * 32 * kPitch <= kRA, "LDS regions");
 static_assert(2 * kLds <= 160 * 1024, "two workgroups per CU");
 static_assert(kWaves * 32 == 256 && (kT + 2) * (kT + 2) == 256 && kT * kT <= (kWaves - 1) * 32, "tile geometry");
@@ -78,7 +86,7 @@ __device__ __forceinline__ f32x16 mma(const u32x4 w, const u32x4 x, const f32x16
 // Two 32-channel accumulator tiles of one 32-pixel column block -> scale/shift, (ReLU), bf16, as four
 // pieces of 8 consecutive channels: piece [u][i2] of lane (pixel, half) holds channels
 // 32 u + 16 i2 + 8 half .. + 8 of its pixel.  `add` (optional) is added before the ReLU in the same layout.
-template <bool HAS_ADD>
+template <bool HAS_ADD, bool RELU = true>
 __device__ __forceinline__ void finish_tiles(const f32x16 (&acc)[2], const float *scale, const float *shift, int half,
                                              const u32x4 (*add)[2], u32x4 (&piece)[2][2]) {
 #pragma unroll
@@ -108,8 +116,10 @@ __device__ __forceinline__ void finish_tiles(const f32x16 (&acc)[2], const float
                 o[0] += lo16(r4.x); o[1] += hi16(r4.x); o[2] += lo16(r4.y); o[3] += hi16(r4.y);
                 o[4] += lo16(r4.z); o[5] += hi16(r4.z); o[6] += lo16(r4.w); o[7] += hi16(r4.w);
             }
+            if constexpr (RELU) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
+                for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
+            }
             u32x4 out;
             out.x = pack2(o[0], o[1]); out.y = pack2(o[2], o[3]);
             out.z = pack2(o[4], o[5]); out.w = pack2(o[6], o[7]);
@@ -119,12 +129,17 @@ __device__ __forceinline__ void finish_tiles(const f32x16 (&acc)[2], const float
 }
 
 // One workgroup: the 14 x 14 output pixels (ty, tx) of image n.
+// PROJ: the stage's first block - 64 input channels, and instead of the identity shortcut the projection
+// sc = bn_sc(wsc . x) (1x1, 64 -> 256, no ReLU), which is the fourth tensor the block can store.
+template <bool PROJ>
 __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs a, int tiles_y, int tiles_x) {
+    constexpr int CIN = PROJ ? kCinProj : kCin, NS = CIN / 64;          // input channels, 128-byte slices of an x row
+    constexpr int W1P = CIN * 2 + 16;                                   // LDS pitch of a w1 row
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *ra = lds;                             // a1 halo tile, later the store tiles
     unsigned char *rb = lds + kRA;                       // w1, then three taps of w2 at a time, then w3
     float *f1s = reinterpret_cast<float *>(rb + kRB), *f1h = f1s + kMid, *f2s = f1h + kMid, *f2h = f2s + kMid,
-          *f3s = f2h + kMid, *f3h = f3s + kCout;
+          *f3s = f2h + kMid, *f3h = f3s + kCout, *fcs = f3h + kCout, *fch = fcs + kCout;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -138,8 +153,8 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
     const int per_image = tiles_y * tiles_x;
     const int n = (int)(logical / (unsigned)per_image), t2 = (int)(logical - (unsigned)n * per_image);
     const int y0 = (t2 / tiles_x) * kT, x0 = (t2 % tiles_x) * kT;
-    const bool need2 = a.a2 != nullptr || a.out != nullptr;
-    const bool need3 = a.out != nullptr;
+    const bool need3 = a.out != nullptr || (PROJ && a.sc != nullptr);
+    const bool need2 = a.a2 != nullptr || need3;
     const unsigned char *xg = static_cast<const unsigned char *>(a.x);
     const size_t image = (size_t)n * H * W;
 
@@ -152,12 +167,12 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
     // without the 3x3 only the tile's own pixels count
     const bool own = inside && hy >= 1 && hy <= kT && hx >= 1 && hx <= kT;
     const bool p1 = __builtin_amdgcn_ballot_w64(need2 ? inside : own) != 0;      // this wavefront has a position to compute
-    u32x4 xf[4][4];
+    u32x4 xf[NS][4];
     if (p1) {
         const size_t q = image + (size_t)(inside ? py : 0) * W + (inside ? px : 0);      // clamped rows are overwritten by zeros
-        const unsigned char *xp = xg + q * (kCin * 2) + half * 64;
+        const unsigned char *xp = xg + q * (CIN * 2) + half * 64;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
             for (int j = 0; j < 4; ++j) xf[s][j] = *reinterpret_cast<const u32x4 *>(xp + s * 128 + j * 16);
     }
@@ -165,15 +180,18 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
     // ---- stage w1 and the batch-norm factors
     {
         const unsigned char *w1g = static_cast<const unsigned char *>(a.w1);
-        for (int c = tid; c < kMid * 32; c += kThreads) {                 // 32 pieces of 16 bytes per row
-            const int row = c >> 5, seg = c & 31;
-            *reinterpret_cast<u32x4 *>(rb + row * kW1Pitch + seg * 16) = *reinterpret_cast<const u32x4 *>(w1g + (size_t)c * 16);
+        for (int c = tid; c < kMid * (CIN / 8); c += kThreads) {          // CIN / 8 pieces of 16 bytes per row
+            const int row = c / (CIN / 8), seg = c % (CIN / 8);
+            *reinterpret_cast<u32x4 *>(rb + row * W1P + seg * 16) = *reinterpret_cast<const u32x4 *>(w1g + (size_t)c * 16);
         }
         if (tid < kMid) {
             f1s[tid] = a.s1[tid]; f1h[tid] = a.h1[tid];
             f2s[tid] = a.s2[tid]; f2h[tid] = a.h2[tid];
         }
-        if (tid < kCout) { f3s[tid] = a.s3[tid]; f3h[tid] = a.h3[tid]; }
+        if (tid < kCout) {
+            f3s[tid] = a.s3[tid]; f3h[tid] = a.h3[tid];
+            if constexpr (PROJ) { fcs[tid] = a.ssc[tid]; fch[tid] = a.hsc[tid]; }
+        }
     }
     __syncthreads();
 
@@ -196,7 +214,7 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
             *reinterpret_cast<u32x4 *>(rb + t * kTap + k * kPitch + seg * 16) = src[j];
         }
     };
-    u32x4 wq0[3], wq1[3], wq2[3], w3q[4];
+    u32x4 wq0[3], wq1[3], wq2[3], w3q[PROJ ? 2 : 4], wcq[PROJ ? 2 : 1];   // with a projection: half of w3 / wsc at a time
     if (need2) fetch_taps(0, wq0);
 
     // ---- phase 1: a1 = relu(bn1(w1 . x)) for one 32-position tile per wavefront, into LDS
@@ -208,13 +226,13 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-            const unsigned char *wrow = rb + l32 * kW1Pitch + half * 64;
+            const unsigned char *wrow = rb + l32 * W1P + half * 64;
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int s = 0; s < NS; ++s)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + s * 128 + j * 16);
-                    const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kW1Pitch + s * 128 + j * 16);
+                    const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * W1P + s * 128 + j * 16);
                     acc[0] = mma(w0, xf[s][j], acc[0]);
                     acc[1] = mma(w1, xf[s][j], acc[1]);
                 }
@@ -223,10 +241,10 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
         if (need2) {
             fetch_taps(3, wq1);
             fetch_taps(6, wq2);
-            if (need3) {
+            if (a.out) {
                 const unsigned char *w3g = static_cast<const unsigned char *>(a.w3);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)              // 256 rows x 8 pieces = 2048 pieces: four per thread
+                for (int j = 0; j < (PROJ ? 2 : 4); ++j) // 256 rows x 8 pieces = 2048 pieces: four per thread
                     w3q[j] = *reinterpret_cast<const u32x4 *>(w3g + (size_t)(tid + j * kThreads) * 16);
             }
         }
@@ -267,6 +285,14 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
 #pragma unroll
     for (int g = 0; g < 3; ++g) {
         deposit_taps(g == 0 ? wq0 : (g == 1 ? wq1 : wq2));   // the region is free: w1 / the previous taps are behind a barrier
+        if constexpr (PROJ) {
+            if (g == 2 && need3) {                           // the tap registers are free: the projection's weights take them
+                const unsigned char *wcg = static_cast<const unsigned char *>(a.wsc);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)                  // rows 0 .. 127 (1024 pieces: two per thread); the rest follows in phase 3
+                    wcq[j] = *reinterpret_cast<const u32x4 *>(wcg + (size_t)(tid + j * kThreads) * 16);
+            }
+        }
         __syncthreads();
         if (p2) {
             // 12 steps (tap t, 16-byte piece q), tap 3 g + t being window position (g, t); the three operand
@@ -298,6 +324,114 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
     }
     u32x4 a2p[2][2];                                     // this lane's pixel of a2: four pieces of 8 channels
     if (p2) finish_tiles<false>(acc2, f2s, f2h, half, nullptr, a2p);
+    if constexpr (PROJ) {
+        // ---- phase 3 with a projection shortcut: sc = bn_sc(wsc . x) and out = relu(bn3(w3 . a2) + sc), 64 output
+        // channels at a time.  w3 and wsc (256 rows of 128 bytes each) pass through the weight region in two
+        // halves of 128 rows; every wavefront takes part in the barriers between them.
+        const size_t rm = image + (size_t)(mine ? y0 + iy : 0) * W + (mine ? x0 + ix : 0);   // clamp: the loads stay in bounds
+        u32x4 xs[4];                                         // this lane's half of its pixel's x row: the projection's operand
+        if (need3 && p2) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xs[j] = *reinterpret_cast<const u32x4 *>(xg + rm * (kCinProj * 2) + half * 64 + j * 16);
+        }
+        unsigned char *ttile = ra + wv * (32 * kPitch);      // wavefront-private: pieces in, rows out
+        const int trow = lane >> 3, tseg = lane & 7;
+        int srow[4];                                         // pixel index (below 2^30) or -1
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int sp = wv * 32 + trow + 8 * t, sy = sp / kT, sx = sp - sy * kT;
+            srow[t] = sp < kT * kT && y0 + sy < H && x0 + sx < W ? (int)(image + (size_t)(y0 + sy) * W + x0 + sx) : -1;
+        }
+        auto put_rows = [&](const u32x4 (&piece)[2][2], unsigned char *dst, int row_bytes, int col_bytes) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+                    *reinterpret_cast<u32x4 *>(ttile + l32 * kPitch + (u * 32 + 16 * i2 + 8 * half) * 2) = piece[u][i2];
+            wave_fence();
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + (trow + 8 * t) * kPitch + tseg * 16);
+                if (srow[t] >= 0) *reinterpret_cast<u32x4 *>(dst + (size_t)srow[t] * row_bytes + col_bytes + tseg * 16) = o4;
+            }
+            wave_fence();
+        };
+        if (p2 && a.a2) put_rows(a2p, static_cast<unsigned char *>(a.a2), kMid * 2, 0);
+        if (!need3) return;
+        if (p2 && a.out) {                                   // the two lanes of a pixel trade pieces (see the identity block below)
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                uint32_t *pa = reinterpret_cast<uint32_t *>(&a2p[0][i2]), *pb = reinterpret_cast<uint32_t *>(&a2p[1][i2]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    auto r = __builtin_amdgcn_permlane32_swap(pa[e], pb[e], false, false);
+                    pa[e] = r[0];
+                    pb[e] = r[1];
+                }
+            }
+        }
+        constexpr int kHalfRows = 128, kHalfBytes = kHalfRows * kPitch;
+        unsigned char *og = static_cast<unsigned char *>(a.out), *cg = static_cast<unsigned char *>(a.sc);
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+            if (round) __syncthreads();                      // everyone has read the first halves
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {                 // piece jj of a thread is row 64 jj + tid / 8 of this half
+                const int c = tid + jj * kThreads, row = c >> 3, seg = c & 7;
+                if (a.out) *reinterpret_cast<u32x4 *>(rb + row * kPitch + seg * 16) = w3q[jj];
+                *reinterpret_cast<u32x4 *>(rb + kHalfBytes + row * kPitch + seg * 16) = wcq[jj];
+            }
+            if (round == 0) {                                // the second halves travel while the first are multiplied
+                const unsigned char *w3g = static_cast<const unsigned char *>(a.w3), *wcg = static_cast<const unsigned char *>(a.wsc);
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const size_t c = (size_t)(tid + (2 + jj) * kThreads) * 16;
+                    if (a.out) w3q[jj] = *reinterpret_cast<const u32x4 *>(w3g + c);
+                    wcq[jj] = *reinterpret_cast<const u32x4 *>(wcg + c);
+                }
+            }
+            __syncthreads();
+            if (p2) {
+#pragma unroll
+                for (int gg = 0; gg < 2; ++gg) {
+                    const int g = 2 * round + gg;
+                    const unsigned char *wrow = rb + (gg * 64 + l32) * kPitch + half * 64;
+                    f32x16 acc[2];
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {            // the projection: one 128-byte slice of x, pieces in order
+                        const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + kHalfBytes + j * 16);
+                        const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + kHalfBytes + 32 * kPitch + j * 16);
+                        acc[0] = mma(w0, xs[j], acc[0]);
+                        acc[1] = mma(w1, xs[j], acc[1]);
+                    }
+                    u32x4 scp[2][2];
+                    finish_tiles<false, false>(acc, fcs + g * 64, fch + g * 64, half, nullptr, scp);
+                    if (a.sc) put_rows(scp, cg, kCout * 2, g * 128);
+                    if (a.out) {
+#pragma unroll
+                        for (int u = 0; u < 2; ++u)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + j * 16);
+                            const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kPitch + j * 16);
+                            acc[0] = mma(w0, a2p[j & 1][j >> 1], acc[0]);
+                            acc[1] = mma(w1, a2p[j & 1][j >> 1], acc[1]);
+                        }
+                        finish_tiles<true>(acc, f3s + g * 64, f3h + g * 64, half, scp, scp);   // in place: each piece is read, then written
+                        put_rows(scp, og, kCout * 2, g * 128);
+                    }
+                }
+            }
+        }
+        return;
+    } else {
     // the shortcut rows of the first two channel groups go into flight before the barrier that publishes w3
     const size_t rm = image + (size_t)(mine ? y0 + iy : 0) * W + (mine ? x0 + ix : 0);   // clamp: the loads stay in bounds
     const unsigned char *xres = xg + rm * (kCin * 2);
@@ -399,6 +533,7 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
         }
         wave_fence();
     }
+    }
 }
 
 }  // namespace block
@@ -408,10 +543,12 @@ const char *bottleneck_block_check(const BlockArgs &a) {
     const long long M = (long long)a.N * a.H * a.W;
     if (M != a.M || M > 0x7FFFFFFFLL / 2) return "pixel count out of range";
     if (!a.x || !a.w1 || !a.w2 || !a.w3 || !a.s1 || !a.h1 || !a.s2 || !a.h2 || !a.s3 || !a.h3) return "null operand";
-    if (!a.a1 && !a.a2 && !a.out) return "nothing to store";
+    if (a.proj ? (!a.wsc || !a.ssc || !a.hsc) : (a.wsc || a.ssc || a.hsc || a.sc)) return "projection operands do not match the block's kind";
+    if (!a.a1 && !a.a2 && !a.out && !a.sc) return "nothing to store";
     const uintptr_t all = (uintptr_t)a.x | (uintptr_t)a.a1 | (uintptr_t)a.a2 | (uintptr_t)a.out | (uintptr_t)a.w1 |
                           (uintptr_t)a.w2 | (uintptr_t)a.w3 | (uintptr_t)a.s1 | (uintptr_t)a.h1 | (uintptr_t)a.s2 |
-                          (uintptr_t)a.h2 | (uintptr_t)a.s3 | (uintptr_t)a.h3;
+                          (uintptr_t)a.h2 | (uintptr_t)a.s3 | (uintptr_t)a.h3 | (uintptr_t)a.wsc | (uintptr_t)a.ssc |
+                          (uintptr_t)a.hsc | (uintptr_t)a.sc;
     if (all & 15) return "pointers must be 16-byte aligned";
     const long long tiles = (long long)a.N * ((a.H + block::kT - 1) / block::kT) * ((a.W + block::kT - 1) / block::kT);
     if (tiles > 0x7FFFFFF0LL) return "too many tiles";
@@ -421,11 +558,17 @@ const char *bottleneck_block_check(const BlockArgs &a) {
 hipError_t launch_bottleneck_block(const BlockArgs &a, hipStream_t stream) {
     if (bottleneck_block_check(a)) return hipErrorInvalidValue;
     const int tiles_y = (a.H + block::kT - 1) / block::kT, tiles_x = (a.W + block::kT - 1) / block::kT;
-    static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void *>(block::bottleneck_block_kernel),
+    static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void *>(block::bottleneck_block_kernel<false>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, block::kLds);
+    static const hipError_t raised_proj = hipFuncSetAttribute(reinterpret_cast<const void *>(block::bottleneck_block_kernel<true>),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, block::kLds);
     if (raised != hipSuccess) return raised;
+    if (raised_proj != hipSuccess) return raised_proj;
     const long long blocks = (long long)a.N * tiles_y * tiles_x;
-    block::bottleneck_block_kernel<<<dim3((unsigned)blocks), dim3(block::kThreads), block::kLds, stream>>>(a, tiles_y, tiles_x);
+    if (a.proj)
+        block::bottleneck_block_kernel<true><<<dim3((unsigned)blocks), dim3(block::kThreads), block::kLds, stream>>>(a, tiles_y, tiles_x);
+    else
+        block::bottleneck_block_kernel<false><<<dim3((unsigned)blocks), dim3(block::kThreads), block::kLds, stream>>>(a, tiles_y, tiles_x);
     return hipGetLastError();
 }
 

@@ -837,15 +837,22 @@ static delta_status prepare_layer(delta_ctx *c, const delta_layer_desc &L, uint3
     return DELTA_OK;
 }
 
-// The three layers of an identity bottleneck that the block kernel runs in one launch (layers[i] carries
-// DELTA_FUSE_BLOCK).  Validates the chain and fills the launch arguments except device addresses.
+// The layers of a bottleneck that the block kernel runs in one launch (layers[i] carries DELTA_FUSE_BLOCK):
+// three of an identity block (1x1 256 -> 64, 3x3, 1x1 64 -> 256 + the block's input), or four of a stage's
+// first block (1x1 64 -> 64, 3x3, the projection shortcut 1x1 64 -> 256 of the block's input, 1x1 64 -> 256 +
+// the projection).  Validates the chain and fills the launch arguments except device addresses; `n_block`
+// is the number of layers the block takes.
 static delta_status prepare_block(delta_ctx *c, const delta_layer_desc *layers, uint32_t n_layers, uint32_t i,
-                                  delta::BlockArgs &b, uint64_t (&flops)[3]) {
-    if (i + 3 > n_layers) return fail(c, DELTA_ERR_INVALID, "layer %u: a fused block needs three layers", i);
-    const delta_layer_desc &L1 = layers[i], &L2 = layers[i + 1], &L3 = layers[i + 2];
+                                  delta::BlockArgs &b, uint64_t (&flops)[4], uint32_t &n_block) {
+    if (i + 3 > n_layers) return fail(c, DELTA_ERR_INVALID, "layer %u: a fused block needs three or four layers", i);
+    const bool proj = layers[i].Cin == 64;
+    n_block = proj ? 4 : 3;
+    if (i + n_block > n_layers) return fail(c, DELTA_ERR_INVALID, "layer %u: a fused block with a projection needs four layers", i);
+    const delta_layer_desc &L1 = layers[i], &L2 = layers[i + 1], &L3 = layers[i + n_block - 1];
     delta::ConvArgs a;
     delta::PoolArgs pa;
-    for (uint32_t j = 0; j < 3; ++j) {
+    flops[3] = 0;
+    for (uint32_t j = 0; j < n_block; ++j) {
         const delta_layer_desc &L = layers[i + j];
         if (L.op != DELTA_OP_CONV || L.dtype != DELTA_DTYPE_BF16)
             return fail(c, DELTA_ERR_INVALID, "layer %u: the block kernel takes bf16 convolutions", i + j);
@@ -854,25 +861,40 @@ static delta_status prepare_block(delta_ctx *c, const delta_layer_desc *layers, 
         delta_status r = prepare_layer(c, L, i + j, a, pa, flops[j]);
         if (r != DELTA_OK) return r;
     }
-    const bool geo = L1.R == 1 && L1.S == 1 && L1.stride == 1 && L1.pad == 0 && L1.Cin == 256 && L1.Cout == 64 &&
-                     L2.R == 3 && L2.S == 3 && L2.stride == 1 && L2.pad == 1 && L2.Cin == 64 && L2.Cout == 64 &&
-                     L3.R == 1 && L3.S == 1 && L3.stride == 1 && L3.pad == 0 && L3.Cin == 64 && L3.Cout == 256 &&
-                     L2.N == L1.N && L2.H == L1.H && L2.W == L1.W && L3.N == L1.N && L3.H == L1.H && L3.W == L1.W;
-    const bool chain = L2.x == L1.y && L3.x == L2.y && L3.res == L1.x && L1.res == DELTA_NO_TENSOR &&
-                       L2.res == DELTA_NO_TENSOR && L1.relu == DELTA_ACT_RELU && L2.relu == DELTA_ACT_RELU &&
-                       L3.relu == DELTA_ACT_RELU;
+    auto one_by_one = [](const delta_layer_desc &L, int cin, int cout) {
+        return L.R == 1 && L.S == 1 && L.stride == 1 && L.pad == 0 && (int)L.Cin == cin && (int)L.Cout == cout;
+    };
+    auto same_image = [&](const delta_layer_desc &L) { return L.N == L1.N && L.H == L1.H && L.W == L1.W; };
+    bool geo = one_by_one(L1, proj ? 64 : 256, 64) && L2.R == 3 && L2.S == 3 && L2.stride == 1 && L2.pad == 1 && L2.Cin == 64 &&
+               L2.Cout == 64 && one_by_one(L3, 64, 256) && same_image(L2) && same_image(L3);
+    bool chain = L2.x == L1.y && L3.x == L2.y && L1.res == DELTA_NO_TENSOR && L2.res == DELTA_NO_TENSOR &&
+                 L1.relu == DELTA_ACT_RELU && L2.relu == DELTA_ACT_RELU && L3.relu == DELTA_ACT_RELU;
+    bool distinct = L1.y != L1.x && L2.y != L1.x && L3.y != L1.x && L1.y != L2.y && L1.y != L3.y && L2.y != L3.y;
+    if (proj) {
+        const delta_layer_desc &Lc = layers[i + 2];
+        geo = geo && one_by_one(Lc, 64, 256) && same_image(Lc);
+        chain = chain && Lc.x == L1.x && Lc.res == DELTA_NO_TENSOR && Lc.relu == DELTA_ACT_NONE && L3.res == Lc.y;
+        distinct = distinct && Lc.y != L1.x && Lc.y != L1.y && Lc.y != L2.y && Lc.y != L3.y;
+    } else {
+        chain = chain && L3.res == L1.x;
+    }
     if (!geo || !chain)
-        return fail(c, DELTA_ERR_INVALID, "layer %u: not an identity bottleneck the block kernel takes "
-                    "(1x1 256->64, 3x3 64->64 s1 p1, 1x1 64->256 + the block's input, ReLU after each)", i);
-    if (L1.y == L1.x || L2.y == L1.x || L3.y == L1.x || L1.y == L2.y || L1.y == L3.y || L2.y == L3.y)
-        return fail(c, DELTA_ERR_INVALID, "layer %u: the block's tensors must be distinct", i);
-    if ((L1.fuse & L2.fuse & L3.fuse) & DELTA_FUSE_NO_STORE)
-        return fail(c, DELTA_ERR_INVALID, "layer %u: the block stores nothing", i);
+        return fail(c, DELTA_ERR_INVALID, "layer %u: not a bottleneck the block kernel takes (1x1 256->64, 3x3 64->64 s1 p1, "
+                    "1x1 64->256 + the block's input, ReLU after each; or 1x1 64->64, 3x3, the projection 1x1 64->256 of the "
+                    "block's input without ReLU, 1x1 64->256 + the projection)", i);
+    if (!distinct) return fail(c, DELTA_ERR_INVALID, "layer %u: the block's tensors must be distinct", i);
+    uint32_t all_skipped = DELTA_FUSE_NO_STORE;
+    for (uint32_t j = 0; j < n_block; ++j) all_skipped &= layers[i + j].fuse;
+    if (all_skipped) return fail(c, DELTA_ERR_INVALID, "layer %u: the block stores nothing", i);
     memset(&b, 0, sizeof b);
     b.N = L1.N; b.H = L1.H; b.W = L1.W;
     b.M = (int)((long long)L1.N * L1.H * L1.W);
     b.w1 = L1.w; b.w2 = L2.w; b.w3 = L3.w;
     b.s1 = L1.scale; b.h1 = L1.shift; b.s2 = L2.scale; b.h2 = L2.shift; b.s3 = L3.scale; b.h3 = L3.shift;
+    if (proj) {
+        const delta_layer_desc &Lc = layers[i + 2];
+        b.proj = 1; b.wsc = Lc.w; b.ssc = Lc.scale; b.hsc = Lc.shift;
+    }
     b.x = c->arena;                                  // placeholders for the checks
     b.out = c->arena;
     const char *why = delta::bottleneck_block_check(b);
@@ -905,18 +927,19 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
     delta::ConvArgs a;
     delta::PoolArgs pa;
     delta::BlockArgs blk;
-    uint64_t flops, bflops[3];
+    uint64_t flops, bflops[4];
+    uint32_t nb = 0;
     // Pass 1: validate everything before anything is launched or allocated.
     std::vector<uint8_t> will_exist(c->tensors.size(), 0);
     for (uint32_t i = 0; i < n_layers; ++i) {
         const delta_layer_desc &L = layers[i];
         if (L.op == DELTA_OP_CONV && (L.fuse & DELTA_FUSE_BLOCK)) {
-            if ((r = prepare_block(c, layers, n_layers, i, blk, bflops)) != DELTA_OK) return r;
+            if ((r = prepare_block(c, layers, n_layers, i, blk, bflops, nb)) != DELTA_OK) return r;
             if (!c->tensors[L.x].resident && !will_exist[L.x])
                 return fail(c, DELTA_ERR_STATE, "layer %u: input tensor %u is not resident", i, L.x);
-            for (uint32_t j = 0; j < 3; ++j)
+            for (uint32_t j = 0; j < nb; ++j)
                 if (!(layers[i + j].fuse & DELTA_FUSE_NO_STORE)) will_exist[layers[i + j].y] = 1;
-            i += 2;
+            i += nb - 1;
             continue;
         }
         if (L.fuse) return fail(c, DELTA_ERR_INVALID, "layer %u: fuse flags %u outside a fused block", i, L.fuse);
@@ -931,22 +954,29 @@ delta_status delta_recompute_segment(delta_ctx *c, const delta_layer_desc *layer
     for (uint32_t i = 0; i < n_layers; ++i) {
         const delta_layer_desc &L = layers[i];
         if (L.op == DELTA_OP_CONV && (L.fuse & DELTA_FUSE_BLOCK)) {
-            if ((r = prepare_block(c, layers, n_layers, i, blk, bflops)) != DELTA_OK) return r;
+            if ((r = prepare_block(c, layers, n_layers, i, blk, bflops, nb)) != DELTA_OK) return r;
             Tensor &tx = c->tensors[L.x];
             if ((r = compute_uses(c, tx)) != DELTA_OK) return r;
-            void *outp[3] = {nullptr, nullptr, nullptr};
-            for (uint32_t j = 0; j < 3; ++j) {
+            void *outp[4] = {nullptr, nullptr, nullptr, nullptr};
+            for (uint32_t j = 0; j < nb; ++j) {
                 if (layers[i + j].fuse & DELTA_FUSE_NO_STORE) continue;
                 Tensor &ty = c->tensors[layers[i + j].y];
                 if ((r = claim_output(c, ty)) != DELTA_OK) return r;
                 outp[j] = c->arena + ty.offset;
             }
             blk.x = c->arena + tx.offset;
-            blk.a1 = outp[0]; blk.a2 = outp[1]; blk.out = outp[2];
+            blk.a1 = outp[0]; blk.a2 = outp[1];
+            if (nb == 4) {                          // a1, a2, the projection, out
+                blk.sc = outp[2]; blk.out = outp[3];
+                c->st.recompute_flops += bflops[0] + ((outp[1] || outp[2] || outp[3]) ? bflops[1] : 0) +
+                                         ((outp[2] || outp[3]) ? bflops[2] : 0) + (outp[3] ? bflops[3] : 0);
+            } else {
+                blk.out = outp[2];
+                c->st.recompute_flops += bflops[0] + ((outp[1] || outp[2]) ? bflops[1] : 0) + (outp[2] ? bflops[2] : 0);
+            }
             HIP_TRY(c, delta::launch_bottleneck_block(blk, c->stream[S_COMPUTE]));
             c->st.recompute_launches += 1;
-            c->st.recompute_flops += bflops[0] + ((outp[1] || outp[2]) ? bflops[1] : 0) + (outp[2] ? bflops[2] : 0);
-            i += 2;
+            i += nb - 1;
             continue;
         }
         if ((r = prepare_layer(c, L, i, a, pa, flops)) != DELTA_OK) return r;

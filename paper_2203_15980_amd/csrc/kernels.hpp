@@ -60,11 +60,16 @@ hipError_t launch_conv3x3_c64(const ConvArgs &a, hipStream_t stream);
 // bottleneck_block.hip: one identity bottleneck of conv2_x (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + x,
 // ReLU after each, bf16) in a single launch; a1 / a2 / out may each be null (not stored)
 struct BlockArgs {
-    const void *x;                       // [M, 256] block input, also the shortcut
+    const void *x;                       // [M, 256] block input, also the shortcut ([M, 64] with a projection shortcut)
     void *a1, *a2, *out;                 // [M, 64], [M, 64], [M, 256]
-    const void *w1, *w2, *w3;            // [64][256], [64][3][3][64], [256][64]
+    const void *w1, *w2, *w3;            // [64][256] ([64][64]), [64][3][3][64], [256][64]
     const float *s1, *h1, *s2, *h2, *s3, *h3;   // folded batch-norm scale / shift of the three layers
     int N, H, W, M;
+    // projection shortcut (the first block of the stage): sc = ssc * (wsc . x) + hsc, added to the third layer
+    int proj;
+    const void *wsc;                     // [256][64]
+    const float *ssc, *hsc;
+    void *sc;                            // [M, 256] or nullptr: not stored
 };
 const char *bottleneck_block_check(const BlockArgs &a);
 hipError_t launch_bottleneck_block(const BlockArgs &a, hipStream_t stream);

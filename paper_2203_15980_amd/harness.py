@@ -95,9 +95,9 @@ class Net:
             self.shapes["loss"], self.np_dtype["loss"] = (1,), np.float32
         self.all_layers = B.layer_array(order)
         self.by_tensor = {self.ids[l.y]: l for l in layers}
-        # identity bottlenecks the block kernel takes (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + input, ReLU
-        # after each, bf16): its tensors carry the bits of the per-layer kernels,
-        # so wherever all three layers run back to back they run as one launch
+        # bottlenecks the block kernel takes (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + input, ReLU after each,
+        # bf16; or the stage's first block with its projection shortcut): its tensors carry the bits of the
+        # per-layer kernels, so wherever all the block's layers run back to back they run as one launch
         self.blocks = {}
         self._block_descs = {}
         by_y = {l.y: l for l in layers}
@@ -108,18 +108,26 @@ class Net:
             a2, out = by_y.get(pre + ".a2"), by_y.get(pre + ".out")
             if a2 is None or out is None:
                 continue
-            if (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) != ("conv", 1, 1, 256, 64, True):
-                continue
             if (a2.kind, a2.R, a2.stride, a2.pad, a2.Cin, a2.Cout, a2.relu, a2.x) != ("conv", 3, 1, 1, 64, 64, True, l.y):
                 continue
-            if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, l.x):
-                continue
-            self.blocks[pre] = (l.y, a2.y, out.y)
+            if (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) == ("conv", 1, 1, 256, 64, True):
+                if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, l.x):
+                    continue
+                self.blocks[pre] = (l.y, a2.y, out.y)
+            elif (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) == ("conv", 1, 1, 64, 64, True):
+                # the stage's first block: the projection shortcut sc = bn(w . x), 1x1 64 -> 256 without ReLU, is the
+                # fourth tensor of the launch (production order a1, a2, sc, out)
+                sc = by_y.get(pre + ".sc")
+                if sc is None or (sc.kind, sc.R, sc.stride, sc.Cin, sc.Cout, bool(sc.relu), sc.x, sc.res) != ("conv", 1, 1, 64, 256, False, l.x, None):
+                    continue
+                if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, sc.y):
+                    continue
+                self.blocks[pre] = (l.y, a2.y, sc.y, out.y)
         fused = B.layer_array([B.LayerDesc.from_buffer_copy(dsc) for dsc in order])
         pos = {l.y: i for i, l in enumerate(layers)}
-        for pre, (n1, n2, n3) in self.blocks.items():
-            if pos[n2] == pos[n1] + 1 and pos[n3] == pos[n2] + 1:
-                fused[pos[n1]].fuse = B.FUSE_BLOCK
+        for pre, chain in self.blocks.items():
+            if all(pos[chain[j]] == pos[chain[0]] + j for j in range(len(chain))):
+                fused[pos[chain[0]]].fuse = B.FUSE_BLOCK
         self.all_layers_fused = fused
         torch.cuda.synchronize()
 
@@ -155,9 +163,10 @@ class Net:
         self.delta.recompute_segment(self.desc[name])
 
     def block_desc(self, prefix, store=None):
-        """The three layers `prefix`.a1 / .a2 / .out of an identity bottleneck as one launch of the
-        block kernel; `store`: the tensor names to write (default: all three).  A fresh array each time."""
-        names = [prefix + ".a1", prefix + ".a2", prefix + ".out"]
+        """The layers of bottleneck `prefix` (.a1 / .a2 / .out of an identity block; .a1 / .a2 / .sc / .out of a
+        block with a projection shortcut) as one launch of the block kernel; `store`: the tensor names to
+        write (default: all).  A fresh array each time."""
+        names = list(self.blocks[prefix])
         store = names if store is None else store
         arr = B.layer_array([B.LayerDesc.from_buffer_copy(self.desc[n][0]) for n in names])
         for i, n in enumerate(names):
@@ -430,7 +439,7 @@ def run_plan(net, graph, events, backward_proxy=None):
         by_step.setdefault(k, []).append((a, t))
     names = [t["name"] for t in graph.tensors]
     blocks = getattr(net, "blocks", {})
-    first_of = {net.ids[n1]: pre for pre, (n1, _, _) in blocks.items()}
+    first_of = {net.ids[chain[0]]: pre for pre, chain in blocks.items()}
     steps = graph.steps
     fused_away = set()                              # forward steps whose tensor an earlier block launch produced
     for k, st in enumerate(steps):
@@ -466,16 +475,17 @@ def run_plan(net, graph, events, backward_proxy=None):
             else:
                 pre = first_of.get(p)
                 fuse = False
-                if pre is not None and k + 2 < len(steps):
-                    c = [net.ids[n] for n in blocks[pre]]
-                    # the next two steps produce a2 and out, the plan does nothing before them and frees
-                    # nothing after this step and the next: the block's memory is the same two steps early
-                    fuse = (steps[k + 1]["produces"] == c[1] and steps[k + 2]["produces"] == c[2] and not post
-                            and not by_step.get(k + 1)
-                            and all(a == B.EV_FREE for (a, _) in by_step.get(k + 2, ())))
+                c = [net.ids[n] for n in blocks[pre]] if pre is not None else []
+                if pre is not None and k + len(c) - 1 < len(steps):
+                    # the next steps produce the block's other tensors, the plan does nothing before them and frees
+                    # nothing until after the last: the block's memory is the same a few steps early
+                    last = k + len(c) - 1
+                    fuse = (all(steps[k + j]["produces"] == c[j] for j in range(1, len(c))) and not post
+                            and not any(by_step.get(k + j) for j in range(1, len(c) - 1))
+                            and all(a == B.EV_FREE for (a, _) in by_step.get(last, ())))
                 if fuse:
-                    d.recompute_segment(net._block_launch(pre, 3))
-                    fused_away.update((k + 1, k + 2))
+                    d.recompute_segment(net._block_launch(pre, len(c)))
+                    fused_away.update(range(k + 1, k + len(c)))
                 else:
                     d.recompute_segment(net.desc[names[p]])
         elif backward_proxy is not None:

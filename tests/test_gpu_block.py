@@ -1,5 +1,6 @@
-"""GPU parity of the block kernel (one identity bottleneck 1x1 -> 3x3 -> 1x1 + shortcut in a single
-launch, selected with DELTA_FUSE_BLOCK) against the CPU oracle's layer chain, through the C ABI.
+"""GPU parity of the block kernel (one bottleneck 1x1 -> 3x3 -> 1x1 + shortcut in a single launch, selected
+with DELTA_FUSE_BLOCK: the identity blocks, and the stage's first block with its projection shortcut) against
+the CPU oracle's layer chain, through the C ABI.
 
 Bars: every stored tensor within 2e-2 (bf16) of the oracle's; whatever subset of {a1, a2, out} a
 launch stores, the stored tensors carry the same bits; a recomputation after a release (at
@@ -102,6 +103,154 @@ def test_block_kernel_matches_the_oracle_chain(torch_mod, shape):
     d.sync()
     st = d.stats()
     assert st["recompute_launches"] == 1 + 2 * 6
+    d.close()
+
+
+PROJ_NAMES = ("b1.a1", "b1.a2", "b1.sc", "b1.out")
+
+
+def _proj_net(torch, N, H, W, master=61, extra=4):
+    """The first block of a stage: 64 input channels and a projection shortcut (config 2's block 1)."""
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    layers = synth.bottleneck_stack(N, H, W, nblocks=1)
+    g = synth.fused_graph(layers, "bf16")
+    arena = torch.empty(extra * g.total_bytes() + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", master)
+    assert net.blocks == {"b1": PROJ_NAMES}
+    return d, net, layers
+
+
+@pytest.mark.parametrize("shape", [(2, 7, 7), (3, 9, 11), (1, 1, 1), (2, 15, 29), (5, 56, 56), (1, 4, 224)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_projection_block_carries_the_per_layer_bits_and_matches_the_oracle(torch_mod, shape):
+    """The block with a projection shortcut (1x1 64 -> 64, 3x3, the projection 1x1 64 -> 256 of the block's input, 1x1
+    64 -> 256 + the projection) in one launch: within 2e-2 of the oracle's chain, and every subset of its four
+    tensors carries the bits of the four per-layer launches; what is not stored is not allocated."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    print("shape", shape, flush=True)
+    d, net, layers = _proj_net(torch, *shape)
+    net.load_input()
+    d.recompute_segment(net.all_layers)
+    d.sync()
+    per_layer = {n: net.read(n).copy() for n in PROJ_NAMES}
+    ref = on.run_layers(layers, net.params_np, net.x0_np, "bf16")
+    for n in PROJ_NAMES:
+        err = _rel(per_layer[n], ref[n])
+        print("  %s err %.2e" % (n, err), flush=True)
+        assert err <= 2e-2, (shape, n, err)
+    launches = 0
+    for k in (1, 2, 3, 4):
+        for keep in itertools.combinations(PROJ_NAMES, k):
+            for n in PROJ_NAMES:
+                d.release(net.ids[n], dl.EV_EVICT)
+            d.stats_reset()
+            d.recompute_segment(net.block_desc("b1", store=keep))
+            d.sync()
+            launches += d.stats()["recompute_launches"]
+            for n in PROJ_NAMES:
+                if n in keep:
+                    assert np.array_equal(net.read(n), per_layer[n]), (shape, keep, n)
+                else:
+                    with pytest.raises(dl.DeltaError) as e:
+                        d.tensor_ptr(net.ids[n])
+                    assert e.value.status == dl.ERR_STATE
+            for n in keep:
+                d.release(net.ids[n], dl.EV_EVICT)
+            d.recompute_segment(net.all_layers)                                     # all four back for the next round
+    assert launches == 15
+    d.close()
+
+
+def test_projection_block_at_config2_size_on_sampled_images(torch_mod):
+    """Config 2's block 1 at its launch shape (batch 32, 56 x 56); the oracle computes the first and the last image."""
+    torch = torch_mod
+    d, net, layers = _proj_net(torch, 32, 56, 56, extra=2)
+    net.load_input()
+    d.recompute_segment(net.block_desc("b1"))
+    d.sync()
+    for img in (0, 31):
+        sub = synth.bottleneck_stack(1, 56, 56, nblocks=1)
+        ref = on.run_layers(sub, net.params_np, net.x0_np[img:img + 1], "bf16")
+        for n in PROJ_NAMES:
+            err = _rel(net.read(n)[img:img + 1], ref[n])
+            print("image %d %s err %.2e" % (img, n, err), flush=True)
+            assert err <= 2e-2, (img, n, err)
+    d.close()
+
+
+def test_projection_block_refuses_a_broken_chain(torch_mod):
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    d, net, layers = _proj_net(torch, 2, 6, 6)
+    net.load_input()
+    arr = net.block_desc("b1")
+    arr[3].res = dl.NO_TENSOR                                  # the last layer must add the projection
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(arr)
+    assert e.value.status == dl.ERR_INVALID
+    arr = net.block_desc("b1")
+    arr[2].relu = 1                                            # the projection has no ReLU
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(arr)
+    assert e.value.status == dl.ERR_INVALID
+    arr = net.block_desc("b1")
+    arr[2].x = arr[1].y                                        # ... and reads the block's input
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(arr)
+    assert e.value.status == dl.ERR_INVALID
+    with pytest.raises(dl.DeltaError) as e:                   # a block cut short
+        d.recompute_segment(net.block_desc("b1"), 3)
+    assert e.value.status == dl.ERR_INVALID
+    with pytest.raises(dl.DeltaError) as e:
+        d.recompute_segment(net.block_desc("b1", store=()))
+    assert e.value.status == dl.ERR_INVALID
+    d.recompute_segment(net.block_desc("b1"))                  # and the intact chain runs
+    d.sync()
+    d.close()
+
+
+def test_step_replay_runs_a_projection_block_as_one_launch(torch_mod):
+    """`run_plan` on config 2's stack (block 1 with a projection, blocks 2 and 3 identity): without plan events the
+    forward is three launches; RECOMPUTE events for a1, a2, sc, out of block 1 in a row are one launch; the bits are
+    those of the per-layer launches."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net, run_plan
+    layers = synth.bottleneck_stack(2, 20, 17)
+    g = synth.fused_graph(layers, "bf16")
+    arena = torch.empty(4 * g.total_bytes() + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", 61)
+    assert set(net.blocks) == {"b1", "b2", "b3"} and len(net.blocks["b1"]) == 4
+    names = [t["name"] for t in g.tensors]
+    net.load_input()
+    d.recompute_segment(net.all_layers)
+    d.sync()
+    ref = {n: net.read(n).copy() for n in names if n != "x0"}
+    for t in range(len(names)):
+        d.release(t, dl.EV_FREE)
+    d.stats_reset()
+    run_plan(net, g, [])
+    d.sync()
+    assert d.stats()["recompute_launches"] == 3
+    for n in ref:
+        assert np.array_equal(net.read(n), ref[n]), n
+    for t in range(len(names)):
+        d.release(t, dl.EV_FREE)
+    ids = [net.ids[n] for n in net.blocks["b1"]]
+    k_bwd = g.n_fwd
+    events = [(k_bwd, dl.EV_EVICT, t) for t in ids] + [(k_bwd, dl.EV_RECOMPUTE, t) for t in ids]
+    d.stats_reset()
+    run_plan(net, g, events)
+    d.sync()
+    assert d.stats()["recompute_launches"] == 3 + 1
+    for n in ref:
+        assert np.array_equal(net.read(n), ref[n]), n
     d.close()
 
 
