@@ -702,7 +702,7 @@ const char *wgrad_plan(const ConvArgs &a_in, WgradPlan &p, int ntaps = 0) {
 
 template <int KTW, int CTW, int TAPS, int QS>
 hipError_t launch_wgrad_q(const bwd::WgradArgs &wa, const WgradPlan &p, hipStream_t stream) {
-    if constexpr (KTW * CTW * TAPS * QS > 16) {
+    if constexpr (KTW * CTW * TAPS * QS > 9) {      // wgrad_plan never asks for more (nine taps, or eight wavefronts)
         return hipErrorInvalidValue;
     } else {
         static bool raised = false;

@@ -23,6 +23,10 @@
 //      operand (a piece of 8 channels per step; w3's rows are read from LDS in the same channel
 //      order), the shortcut is read from x in the same piece layout, and rows of 128 contiguous
 //      bytes leave through a wavefront-private LDS tile.
+// Everything the kernel stores leaves with non-temporal stores: nothing in this launch reads it again, and
+// the rows of x that phase 3 reads a second time then stay in the caches more often (batch 128: all three
+// tensors 161-168 -> 149-151 us, out alone 156-160 -> 128-143 us; batch 32, where everything fits the
+// Infinity Cache anyway, unchanged).
 // Orientation as in the per-layer kernels: output channels on the MFMA row axis, pixels on the
 // column axis; lane half h owns bytes [64h, 64h + 64) of every 128-byte slice of both operands.
 // The order of every sum is fixed and does not depend on which tensors are stored, so whatever
@@ -83,49 +87,55 @@ __device__ __forceinline__ f32x16 mma(const u32x4 w, const u32x4 x, const f32x16
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc, 0, 0, 0);
 }
 
-// Two 32-channel accumulator tiles of one 32-pixel column block -> scale/shift, (ReLU), bf16, as four
-// pieces of 8 consecutive channels: piece [u][i2] of lane (pixel, half) holds channels
-// 32 u + 16 i2 + 8 half .. + 8 of its pixel.  `add` (optional) is added before the ReLU in the same layout.
+// One 32-channel accumulator tile of a 32-pixel column block -> scale/shift, (ReLU), bf16, as two pieces of
+// 8 consecutive channels: piece [i2] of lane (pixel, half) holds channels 16 i2 + 8 half .. + 8 of the tile for
+// its pixel.  `add` (optional, the same layout; may be `piece` itself) is added before the ReLU.
+template <bool HAS_ADD, bool RELU = true>
+__device__ __forceinline__ void finish_tile(const f32x16 &acc, const float *scale, const float *shift, int half,
+                                            const u32x4 *add, u32x4 *piece) {
+    float v[16];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+        const f32x4 sc = *reinterpret_cast<const f32x4 *>(scale + 8 * rb + 4 * half);
+        const f32x4 sh = *reinterpret_cast<const f32x4 *>(shift + 8 * rb + 4 * half);
+        v[4 * rb + 0] = acc[4 * rb + 0] * sc.x + sh.x;
+        v[4 * rb + 1] = acc[4 * rb + 1] * sc.y + sh.y;
+        v[4 * rb + 2] = acc[4 * rb + 2] * sc.z + sh.z;
+        v[4 * rb + 3] = acc[4 * rb + 3] * sc.w + sh.w;
+    }
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2) {
+        float o[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]), __float_as_uint(v[8 * i2 + 4 + j]),
+                                                      false, false);
+            o[j] = __uint_as_float(r[0]);
+            o[4 + j] = __uint_as_float(r[1]);
+        }
+        if constexpr (HAS_ADD) {
+            const u32x4 r4 = add[i2];
+            o[0] += lo16(r4.x); o[1] += hi16(r4.x); o[2] += lo16(r4.y); o[3] += hi16(r4.y);
+            o[4] += lo16(r4.z); o[5] += hi16(r4.z); o[6] += lo16(r4.w); o[7] += hi16(r4.w);
+        }
+        if constexpr (RELU) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
+        }
+        u32x4 out;
+        out.x = pack2(o[0], o[1]); out.y = pack2(o[2], o[3]);
+        out.z = pack2(o[4], o[5]); out.w = pack2(o[6], o[7]);
+        piece[i2] = out;
+    }
+}
+
+// Two such tiles (channels 32 u .. 32 u + 32 of a 64-channel group): piece [u][i2].
 template <bool HAS_ADD, bool RELU = true>
 __device__ __forceinline__ void finish_tiles(const f32x16 (&acc)[2], const float *scale, const float *shift, int half,
                                              const u32x4 (*add)[2], u32x4 (&piece)[2][2]) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        float v[16];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const f32x4 sc = *reinterpret_cast<const f32x4 *>(scale + u * 32 + 8 * rb + 4 * half);
-            const f32x4 sh = *reinterpret_cast<const f32x4 *>(shift + u * 32 + 8 * rb + 4 * half);
-            v[4 * rb + 0] = acc[u][4 * rb + 0] * sc.x + sh.x;
-            v[4 * rb + 1] = acc[u][4 * rb + 1] * sc.y + sh.y;
-            v[4 * rb + 2] = acc[u][4 * rb + 2] * sc.z + sh.z;
-            v[4 * rb + 3] = acc[u][4 * rb + 3] * sc.w + sh.w;
-        }
-#pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2) {
-            float o[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * i2 + j]), __float_as_uint(v[8 * i2 + 4 + j]),
-                                                          false, false);
-                o[j] = __uint_as_float(r[0]);
-                o[4 + j] = __uint_as_float(r[1]);
-            }
-            if constexpr (HAS_ADD) {
-                const u32x4 r4 = add[u][i2];
-                o[0] += lo16(r4.x); o[1] += hi16(r4.x); o[2] += lo16(r4.y); o[3] += hi16(r4.y);
-                o[4] += lo16(r4.z); o[5] += hi16(r4.z); o[6] += lo16(r4.w); o[7] += hi16(r4.w);
-            }
-            if constexpr (RELU) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = relu_keep_nan(o[e]);
-            }
-            u32x4 out;
-            out.x = pack2(o[0], o[1]); out.y = pack2(o[2], o[3]);
-            out.z = pack2(o[4], o[5]); out.w = pack2(o[6], o[7]);
-            piece[u][i2] = out;
-        }
-    }
+    for (int u = 0; u < 2; ++u)
+        finish_tile<HAS_ADD, RELU>(acc[u], scale + u * 32, shift + u * 32, half, HAS_ADD ? add[u] : nullptr, piece[u]);
 }
 
 // One workgroup: the 14 x 14 output pixels (ty, tx) of image n.
@@ -264,8 +274,8 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
         for (int c = tid; c < kT * kT * 8; c += kThreads) {
             const int i = c >> 3, seg = c & 7, iy = i / kT, ix = i - iy * kT;
             if (y0 + iy < H && x0 + ix < W)
-                *reinterpret_cast<u32x4 *>(a1g + (image + (size_t)(y0 + iy) * W + x0 + ix) * (kMid * 2) + seg * 16) =
-                    *reinterpret_cast<const u32x4 *>(ra + ((iy + 1) * 16 + ix + 1) * kPitch + seg * 16);
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(ra + ((iy + 1) * 16 + ix + 1) * kPitch + seg * 16),
+                                            reinterpret_cast<u32x4 *>(a1g + (image + (size_t)(y0 + iy) * W + x0 + ix) * (kMid * 2) + seg * 16));
         }
     }
     if (!need2) return;
@@ -353,7 +363,7 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + (trow + 8 * t) * kPitch + tseg * 16);
-                if (srow[t] >= 0) *reinterpret_cast<u32x4 *>(dst + (size_t)srow[t] * row_bytes + col_bytes + tseg * 16) = o4;
+                if (srow[t] >= 0) __builtin_nontemporal_store(o4, reinterpret_cast<u32x4 *>(dst + (size_t)srow[t] * row_bytes + col_bytes + tseg * 16));
             }
             wave_fence();
         };
@@ -397,34 +407,31 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
                 for (int gg = 0; gg < 2; ++gg) {
                     const int g = 2 * round + gg;
                     const unsigned char *wrow = rb + (gg * 64 + l32) * kPitch + half * 64;
-                    f32x16 acc[2];
-#pragma unroll
-                    for (int u = 0; u < 2; ++u)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {            // the projection: one 128-byte slice of x, pieces in order
-                        const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + kHalfBytes + j * 16);
-                        const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + kHalfBytes + 32 * kPitch + j * 16);
-                        acc[0] = mma(w0, xs[j], acc[0]);
-                        acc[1] = mma(w1, xs[j], acc[1]);
-                    }
+                    // one 32-channel tile at a time: a single accumulator tile is live beside x, a2 and the pieces
                     u32x4 scp[2][2];
-                    finish_tiles<false, false>(acc, fcs + g * 64, fch + g * 64, half, nullptr, scp);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {            // the projection: one 128-byte slice of x, pieces in order
+                        f32x16 acc;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc = mma(*reinterpret_cast<const u32x4 *>(wrow + kHalfBytes + u * 32 * kPitch + j * 16), xs[j], acc);
+                        finish_tile<false, false>(acc, fcs + g * 64 + u * 32, fch + g * 64 + u * 32, half, nullptr, scp[u]);
+                    }
                     if (a.sc) put_rows(scp, cg, kCout * 2, g * 128);
                     if (a.out) {
 #pragma unroll
-                        for (int u = 0; u < 2; ++u)
+                        for (int u = 0; u < 2; ++u) {
+                            f32x16 acc;
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+                            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const u32x4 w0 = *reinterpret_cast<const u32x4 *>(wrow + j * 16);
-                            const u32x4 w1 = *reinterpret_cast<const u32x4 *>(wrow + 32 * kPitch + j * 16);
-                            acc[0] = mma(w0, a2p[j & 1][j >> 1], acc[0]);
-                            acc[1] = mma(w1, a2p[j & 1][j >> 1], acc[1]);
+                            for (int j = 0; j < 4; ++j)
+                                acc = mma(*reinterpret_cast<const u32x4 *>(wrow + u * 32 * kPitch + j * 16), a2p[j & 1][j >> 1], acc);
+                            // in place: each piece is read, then written
+                            finish_tile<true>(acc, f3s + g * 64 + u * 32, f3h + g * 64 + u * 32, half, scp[u], scp[u]);
                         }
-                        finish_tiles<true>(acc, f3s + g * 64, f3h + g * 64, half, scp, scp);   // in place: each piece is read, then written
                         put_rows(scp, og, kCout * 2, g * 128);
                     }
                 }
@@ -474,7 +481,7 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + (trow + 8 * t) * kPitch + tseg * 16);
-            if (srow[t] >= 0) *reinterpret_cast<u32x4 *>(a2g + (size_t)srow[t] * (kMid * 2) + tseg * 16) = o4;
+            if (srow[t] >= 0) __builtin_nontemporal_store(o4, reinterpret_cast<u32x4 *>(a2g + (size_t)srow[t] * (kMid * 2) + tseg * 16));
         }
         wave_fence();
     }
@@ -529,7 +536,7 @@ __global__ __launch_bounds__(kThreads, 4) void bottleneck_block_kernel(BlockArgs
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const u32x4 o4 = *reinterpret_cast<const u32x4 *>(ttile + (trow + 8 * t) * kPitch + tseg * 16);
-            if (srow[t] >= 0) *reinterpret_cast<u32x4 *>(og + ((size_t)srow[t] * kCout + g * 64) * 2 + tseg * 16) = o4;
+            if (srow[t] >= 0) __builtin_nontemporal_store(o4, reinterpret_cast<u32x4 *>(og + ((size_t)srow[t] * kCout + g * 64) * 2 + tseg * 16));
         }
         wave_fence();
     }
