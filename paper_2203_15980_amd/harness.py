@@ -17,6 +17,57 @@ def _dev(a, device):
     return torch.from_numpy(np.ascontiguousarray(a)).to(device)
 
 
+def find_blocks(layers, dtype="bf16"):
+    """Bottlenecks the block kernel takes, {name prefix: its tensors in production order}: 1x1 256 -> 64, 3x3
+    64 -> 64, 1x1 64 -> 256 + the block's input, ReLU after each, bf16 (.a1, .a2, .out); or the stage's first
+    block, 64 input channels, whose shortcut is the projection sc = bn(w . x), 1x1 64 -> 256 without ReLU
+    (.a1, .a2, .sc, .out)."""
+    blocks = {}
+    by_y = {l.y: l for l in layers}
+    for l in layers:
+        if not l.y.endswith(".a1") or dtype != "bf16":
+            continue
+        pre = l.y[:-3]
+        a2, out = by_y.get(pre + ".a2"), by_y.get(pre + ".out")
+        if a2 is None or out is None:
+            continue
+        if (a2.kind, a2.R, a2.stride, a2.pad, a2.Cin, a2.Cout, a2.relu, a2.x) != ("conv", 3, 1, 1, 64, 64, True, l.y):
+            continue
+        if (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) == ("conv", 1, 1, 256, 64, True):
+            if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, l.x):
+                continue
+            blocks[pre] = (l.y, a2.y, out.y)
+        elif (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) == ("conv", 1, 1, 64, 64, True):
+            sc = by_y.get(pre + ".sc")
+            if sc is None or (sc.kind, sc.R, sc.stride, sc.Cin, sc.Cout, bool(sc.relu), sc.x, sc.res) != ("conv", 1, 1, 64, 256, False, l.x, None):
+                continue
+            if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, sc.y):
+                continue
+            blocks[pre] = (l.y, a2.y, sc.y, out.y)
+    return blocks
+
+
+def block_rebuild(layers, dtype="bf16"):
+    """What a recomputation needs for the tensors of such blocks, for `synth.fused_graph(rebuild=...)`: the block
+    kernel regenerates any of them from the block's input alone (DELTA's Recompute action, Sec. 3, Table 1, with
+    the block as the recompute segment), so .a2 and .out get that input as their only parent - rebuilding .out
+    then needs neither .a1 nor .a2 (nor .sc) in memory - with the flops of every layer the kernel runs for them
+    and the bytes of the input and the tensor itself.  .a1 and .sc already come from the input alone."""
+    by_y = {l.y: l for l in layers}
+    es = 2
+    out = {}
+    for pre, chain in find_blocks(layers, dtype).items():
+        first = by_y[chain[0]]
+        for j, n in enumerate(chain):
+            l = by_y[n]
+            if l.x == first.x and not l.res:
+                continue
+            runs = [by_y[m] for m in chain[:j + 1] if not (m.endswith(".sc") and not n.endswith(".out"))]
+            out[n] = dict(parents=[first.x], flops=sum(m.flops for m in runs),
+                          bytes=(first.in_elems() + l.out_elems()) * es)
+    return out
+
+
 class Net:
     """Weights, folded batch-norm factors and layer descriptors of a list of synth.LayerSpec
     layers, resident on the GPU.  Tensor ids follow synth.fused_graph (x0 is 0; with
@@ -95,34 +146,11 @@ class Net:
             self.shapes["loss"], self.np_dtype["loss"] = (1,), np.float32
         self.all_layers = B.layer_array(order)
         self.by_tensor = {self.ids[l.y]: l for l in layers}
-        # bottlenecks the block kernel takes (1x1 256 -> 64, 3x3 64 -> 64, 1x1 64 -> 256 + input, ReLU after each,
-        # bf16; or the stage's first block with its projection shortcut): its tensors carry the bits of the
-        # per-layer kernels, so wherever all the block's layers run back to back they run as one launch
-        self.blocks = {}
+        # bottlenecks the block kernel takes: their tensors carry the bits of the per-layer kernels, so wherever all
+        # the block's layers run back to back they run as one launch
+        self.blocks = find_blocks(layers, dtype)
+        self.block_rebuild = False            # True: the plan was made on a graph with `block_rebuild` (see run_plan)
         self._block_descs = {}
-        by_y = {l.y: l for l in layers}
-        for l in layers:
-            if not l.y.endswith(".a1") or dtype != "bf16":
-                continue
-            pre = l.y[:-3]
-            a2, out = by_y.get(pre + ".a2"), by_y.get(pre + ".out")
-            if a2 is None or out is None:
-                continue
-            if (a2.kind, a2.R, a2.stride, a2.pad, a2.Cin, a2.Cout, a2.relu, a2.x) != ("conv", 3, 1, 1, 64, 64, True, l.y):
-                continue
-            if (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) == ("conv", 1, 1, 256, 64, True):
-                if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, l.x):
-                    continue
-                self.blocks[pre] = (l.y, a2.y, out.y)
-            elif (l.kind, l.R, l.stride, l.Cin, l.Cout, l.relu) == ("conv", 1, 1, 64, 64, True):
-                # the stage's first block: the projection shortcut sc = bn(w . x), 1x1 64 -> 256 without ReLU, is the
-                # fourth tensor of the launch (production order a1, a2, sc, out)
-                sc = by_y.get(pre + ".sc")
-                if sc is None or (sc.kind, sc.R, sc.stride, sc.Cin, sc.Cout, bool(sc.relu), sc.x, sc.res) != ("conv", 1, 1, 64, 256, False, l.x, None):
-                    continue
-                if (out.kind, out.R, out.stride, out.Cin, out.Cout, out.relu, out.x, out.res) != ("conv", 1, 1, 64, 256, True, a2.y, sc.y):
-                    continue
-                self.blocks[pre] = (l.y, a2.y, sc.y, out.y)
         fused = B.layer_array([B.LayerDesc.from_buffer_copy(dsc) for dsc in order])
         pos = {l.y: i for i, l in enumerate(layers)}
         for pre, chain in self.blocks.items():
@@ -174,11 +202,13 @@ class Net:
         return arr
 
     def _block_launch(self, prefix, stored):
-        """`block_desc` for the first `stored` tensors of the block, built once (replays call it per step)."""
-        key = (prefix, stored)
+        """`block_desc` for the first `stored` tensors of the block (an int) or for the given tensor names, built
+        once (replays call it per step)."""
+        names = tuple(self.blocks[prefix][:stored]) if isinstance(stored, int) else tuple(sorted(stored))
+        key = (prefix, names)
         arr = self._block_descs.get(key)
         if arr is None:
-            arr = self._block_descs[key] = self.block_desc(prefix, store=list(self.blocks[prefix][:stored]))
+            arr = self._block_descs[key] = self.block_desc(prefix, store=list(names))
         return arr
 
     # -- backward pass
@@ -432,7 +462,10 @@ def run_plan(net, graph, events, backward_proxy=None):
     issue order (everything of a step before it runs, FREE after).
     Where the three layers of an identity bottleneck that the block kernel takes run back to back with
     nothing of the plan between them - three forward steps without events, or three RECOMPUTE events in
-    a row - they run as one launch (the same bits, `Net.blocks`)."""
+    a row - they run as one launch (the same bits, `Net.blocks`).
+    With `net.block_rebuild` (the plan was made on `synth.fused_graph(rebuild=block_rebuild(layers))`: a block's
+    tensors have the block's input as their only parent) every RECOMPUTE of .a2 / .out, and every run of RECOMPUTE
+    events of one block, is one launch of the block kernel that stores exactly those tensors."""
     d = net.delta
     by_step = {}
     for (k, a, t) in events:
@@ -440,6 +473,9 @@ def run_plan(net, graph, events, backward_proxy=None):
     names = [t["name"] for t in graph.tensors]
     blocks = getattr(net, "blocks", {})
     first_of = {net.ids[chain[0]]: pre for pre, chain in blocks.items()}
+    member_of = {net.ids[n]: pre for pre, chain in blocks.items() for n in chain} if getattr(net, "block_rebuild", False) else {}
+    from_input = {net.ids[n] for chain in blocks.values() for n in chain
+                  if n.endswith((".a1", ".sc"))}            # their per-layer kernel reads the block's input alone
     steps = graph.steps
     fused_away = set()                              # forward steps whose tensor an earlier block launch produced
     for k, st in enumerate(steps):
@@ -453,6 +489,19 @@ def run_plan(net, graph, events, backward_proxy=None):
             elif a in (B.EV_EVICT, B.EV_OFFLOAD, B.EV_DROP_TEMP):
                 d.release(t, a)
             elif a == B.EV_RECOMPUTE:
+                pre = member_of.get(t)
+                if pre is not None:
+                    run = [t]
+                    while i + len(run) < len(evs) and evs[i + len(run)][0] == B.EV_RECOMPUTE and \
+                            member_of.get(evs[i + len(run)][1]) == pre:
+                        run.append(evs[i + len(run)][1])
+                    if len(run) > 1 or t not in from_input:
+                        d.recompute_segment(net._block_launch(pre, [names[r] for r in run]))
+                        i += len(run)
+                        continue
+                    d.recompute_segment(net.desc[names[t]])
+                    i += 1
+                    continue
                 pre = first_of.get(t)
                 chain = [net.ids[n] for n in blocks[pre]] if pre is not None else []
                 run = 0

@@ -221,22 +221,35 @@ def _esize(dtype):
     return 4 if dtype == "f32" else 2
 
 
-def fused_graph(layers: List[LayerSpec], dtype, with_loss=False, costs=None) -> Graph:
+def fused_graph(layers: List[LayerSpec], dtype, with_loss=False, costs=None, rebuild=None) -> Graph:
     """One tensor per fused layer output.  Backward is an access trace: the backward of a
     layer reads its input (weight gradient) and, when it ends in ReLU or is a max-pool,
-    its output (mask).  `costs` optionally maps layer name -> measured ns."""
+    its output (mask).  `costs` optionally maps layer name -> measured ns.
+    `rebuild` optionally maps a tensor name -> dict(parents=[tensor names], flops, bytes) where a
+    recomputation regenerates the tensor by another route than its forward step (a kernel that
+    runs several layers from an earlier tensor): the tensor record then carries those parents and
+    that route's cost (`costs[name + "@rebuild"]` when measured), the forward step keeps the
+    layer's own reads and cost."""
     g = Graph()
     es = _esize(dtype)
     first = layers[0]
     x0 = g.add_tensor("x0", first.in_elems() * es, 0, 0, FLAG_UNCOMPUTABLE, [])
     g.add_fwd(x0, [], 0)
+    fwd_cost = {}
     for l in layers:
         reads = [g.names[l.x]] + ([g.names[l.res]] if l.res else [])
         nbytes = l.out_elems() * es
         traffic = l.in_elems() * es + nbytes + (nbytes if l.res else 0)
         c = costs[l.name] if costs and l.name in costs else cost_model_ns(l.flops, traffic)
-        t = g.add_tensor(l.y, nbytes, c, l.flops, 0, reads)
+        rb = rebuild.get(l.y) if rebuild else None
+        if rb:
+            key = l.name + "@rebuild"
+            rc = costs[key] if costs and key in costs else cost_model_ns(rb["flops"], rb["bytes"])
+            t = g.add_tensor(l.y, nbytes, rc, rb["flops"], 0, [g.names[p] for p in rb["parents"]])
+        else:
+            t = g.add_tensor(l.y, nbytes, c, l.flops, 0, reads)
         g.add_fwd(t, reads, c)
+        fwd_cost[l.y] = c
     if with_loss:
         lab = g.add_tensor("labels", first.N * 8, 0, 0, FLAG_UNCOMPUTABLE, [])
         g.add_fwd(lab, [], 0)
@@ -250,7 +263,7 @@ def fused_graph(layers: List[LayerSpec], dtype, with_loss=False, costs=None) -> 
             reads.append(g.names[l.x])
         if (l.kind == "conv" and l.relu) or l.kind in ("maxpool", "attention") or (l.kind == "linear" and l.act):
             reads.append(g.names[l.y])
-        g.add_bwd(reads, 2 * g.tensors[g.names[l.y]]["cost_ns"])
+        g.add_bwd(reads, 2 * fwd_cost[l.y])
     return g
 
 

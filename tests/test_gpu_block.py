@@ -348,3 +348,56 @@ def test_step_replay_runs_adjacent_block_layers_as_one_launch(torch_mod):
     # forward: 3 per-layer launches + 1 recomputation of a1; backward step: one block launch for a1 + a2
     assert launches() - fused_launches == 4, (launches(), fused_launches)
     d.close()
+
+
+@pytest.mark.parametrize("frac", [0.5, 0.4])
+def test_single_pass_plan_with_blocks_rebuilt_from_their_input_replays_with_forward_bits(torch_mod, frac):
+    """Config 2's stack planned on the graph in which the block kernel is the recompute route (`block_rebuild`): the
+    single greedy pass (no repair rounds) plans it at 50 % and 40 %, where the per-layer graph is infeasible; the
+    replay keeps the bytes in use within the budget, every RECOMPUTE of .a2 / .out is one block-kernel launch that stores only
+    that tensor (its block-mates stay released), and every backward step finds the bits of the unconstrained forward."""
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from oracle import planner as opl
+    from paper_2203_15980_amd.harness import Net, run_plan, block_rebuild
+    layers = synth.bottleneck_stack(4, 56, 56)
+    g0 = synth.fused_graph(layers, "bf16")
+    g = synth.fused_graph(layers, "bf16", rebuild=block_rebuild(layers))
+    total = g.total_bytes()
+    arena = torch.empty(total + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    d0 = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d0.bind([t["bytes"] for t in g.tensors])
+    net0 = Net(d0, layers, "bf16", 23)
+    net0.forward()
+    want = {t["name"]: net0.read(t["name"]).copy() for t in g.tensors}
+    d0.close()
+    del net0, d0, arena
+    p = opl.default_params(int(total * frac), g.n_fwd, bw_d2h_Bps=48 * 10**9, bw_h2d_Bps=52 * 10**9,
+                           prefetch_distance=2, max_reloads=2, release_when_short=1)
+    with pytest.raises(dl.DeltaError) as e:
+        dl.plan(g0.tensors, g0.steps, p)
+    assert e.value.status == dl.ERR_INFEASIBLE
+    ev, peak = dl.plan(g.tensors, g.steps, p)
+    assert (ev, peak) == opl.plan(g.tensors, g.steps, p)
+    rebuilt = [g.tensors[t]["name"] for (_, a, t) in ev if a == dl.EV_RECOMPUTE]
+    print("frac", frac, "events", len(ev), "recomputed", rebuilt, flush=True)
+    assert any(n.endswith((".a2", ".out")) for n in rebuilt)
+    arena = torch.empty(p["budget_bytes"] * 3 // 2, dtype=torch.uint8, device="cuda:0")   # room for placement; the bytes in use are checked below
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", 23)
+    net.block_rebuild = True
+    checked = []
+
+    def proxy(k):
+        for t in g.steps[k]["reads"]:
+            n = g.tensors[t]["name"]
+            assert net.read(n).tobytes() == want[n].tobytes(), (k, n)
+            checked.append(n)
+
+    run_plan(net, g, ev, backward_proxy=proxy)
+    d.sync()
+    st = d.stats()
+    assert checked and st["arena_in_use"] == 0
+    assert st["arena_high_water"] <= p["budget_bytes"]
+    d.close()

@@ -59,6 +59,60 @@ def test_plans_match_oracle_on_configs(cfg, frac):
                 assert dl.plan(g.tensors, g.steps, p) == want
 
 
+def test_config2_plans_in_a_single_pass_when_a_block_is_rebuilt_from_its_input():
+    """The block kernel regenerates any tensor of a bottleneck from the block's input alone.  With that as the
+    tensors' recompute route (`block_rebuild`: .a2 and .out have the block's input as their only parent) the single
+    greedy pass of Algorithms 1-4 plans config 2 from 60 % down to 40 % of its activation bytes; with per-layer
+    parents it fails at step 14 below 60 % (rebuilding b*.out drags a1 and a2 back into memory).  Library and
+    oracle agree event by event on both graphs, the checker accepts every plan, and ResNet-50 with its three such
+    blocks plans alike."""
+    from paper_2203_15980_amd.harness import block_rebuild, find_blocks
+    layers = synth.bottleneck_stack(32, 56, 56)
+    assert sorted(find_blocks(layers)) == ["b1", "b2", "b3"]
+    rb = block_rebuild(layers)
+    assert sorted(rb) == ["b1.a2", "b1.out", "b2.a2", "b2.out", "b3.a2", "b3.out"]
+    assert rb["b2.out"]["parents"] == ["b1.out"] and rb["b1.out"]["parents"] == ["x0"]
+    by = {l.y: l for l in layers}
+    assert rb["b2.out"]["flops"] == by["b2.a1"].flops + by["b2.a2"].flops + by["b2.out"].flops
+    assert rb["b1.out"]["flops"] == sum(by["b1." + k].flops for k in ("a1", "a2", "sc", "out"))
+    assert rb["b1.a2"]["flops"] == by["b1.a1"].flops + by["b1.a2"].flops
+    per_layer = synth.fused_graph(layers, "bf16")
+    block = synth.fused_graph(layers, "bf16", rebuild=rb)
+    assert [t["bytes"] for t in block.tensors] == [t["bytes"] for t in per_layer.tensors]
+    assert block.steps == per_layer.steps                     # the forward and backward steps are the same
+    total = per_layer.total_bytes()
+    for frac in (0.6, 0.55, 0.5, 0.45, 0.4):
+        for kind in (pl.FILTER_BASE, pl.FILTER_LRU, pl.FILTER_GREEDY):
+            p = pl.default_params(int(frac * total), block.n_fwd, filter=kind, bw_d2h_Bps=48 * 10**9, bw_h2d_Bps=52 * 10**9,
+                                  prefetch_distance=2, max_reloads=2, release_when_short=1)
+            want = pl.plan(block.tensors, block.steps, p)
+            assert dl.plan(block.tensors, block.steps, p) == want
+            st = checker.check(block.tensors, block.steps, p, want[0])
+            assert st["peak"] <= p["budget_bytes"]
+            if frac < 0.6 and kind == pl.FILTER_BASE:
+                with pytest.raises(pl.Infeasible) as e:
+                    pl.plan(per_layer.tensors, per_layer.steps, p)
+                assert e.value.step == 14
+                with pytest.raises(dl.DeltaError) as got:
+                    dl.plan(per_layer.tensors, per_layer.steps, p)
+                assert got.value.status == dl.ERR_INFEASIBLE
+    r50 = synth.resnet_layers(128, (3, 4, 6, 3))
+    rb = block_rebuild(r50)
+    assert len(rb) == 6
+    g = synth.fused_graph(r50, "bf16", with_loss=True, rebuild=rb)
+    for frac in (0.5, 0.3):
+        p = pl.default_params(int(frac * g.total_bytes()), g.n_fwd, bw_d2h_Bps=48 * 10**9, bw_h2d_Bps=52 * 10**9,
+                              prefetch_distance=2, max_reloads=2, release_when_short=1, repair_rounds=8)
+        try:
+            want = pl.plan(g.tensors, g.steps, p)
+        except pl.Infeasible:
+            with pytest.raises(dl.DeltaError):
+                dl.plan(g.tensors, g.steps, p)
+            continue
+        assert dl.plan(g.tensors, g.steps, p) == want
+        checker.check(g.tensors, g.steps, p, want[0])
+
+
 @pytest.mark.parametrize("cfg,frac", [(2, 0.5), (2, 0.4), (3, 0.3), (4, 0.25), (5, 0.2)])
 def test_plans_match_oracle_with_the_optional_switches(cfg, frac):
     """release_when_short and repair_rounds, alone and together, at budgets where the single
