@@ -428,7 +428,10 @@ __global__ __launch_bounds__(KTW * CTW * TAPS * QS * 64) void wgrad_kernel(Wgrad
 // group adds splits g, g + G, ..., four loads in flight), whose G sums are then added in wavefront
 // order; a workgroup of 8 wavefronts takes 8 / G groups.  G follows the number of splits (about
 // four loads per lane): with few splits (the wide layers: 4 or 16) every wavefront still has
-// loads to issue, with many (256) the loads of a group are spread over the whole workgroup.  The
+// loads to issue, with many (256) the loads of a group are spread over the whole workgroup.  (Splitting
+// a wavefront's lanes over four splits as well - 256 workgroups instead of 64 for the single-tile layers,
+// eight loads in flight - makes this kernel faster alone, 4 us at best, and the backward pass 3 % slower:
+// beside the data-gradient stream its time is mostly waiting for free CUs, and more workgroups wait more.)  The
 // accumulator layout of a 32x32 tile is: lane l holds column l % 32 and rows 8 e4 + 4 (l / 32) + e
 // in register 4 e4 + e, so a thread's four sums go to four k rows of one c, and consecutive lanes
 // write consecutive c.
