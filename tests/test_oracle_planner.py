@@ -621,3 +621,32 @@ def test_config1_optimum_and_heuristic_gap():
     ev, _ = pl.plan(g.tensors, g.steps, p)
     h = checker.check(g.tensors, g.steps, p, ev)
     print("config 1: heuristic cost %d ns, static optimum %d ns" % (h["cost_ns"], o["cost"]))
+
+
+def test_handworked_recomputation_follows_the_tensor_parents_not_the_forward_reads():
+    """A tensor's parents say what its recomputation reads; they need not be what its forward step read (a kernel that
+    regenerates t2 from t0 directly, while the forward step of t2 read t1).  t0 (source) -> ... -> t5, m = 4, B = 12,
+    no link, release loop at B, no prefetch.  Forward, as with per-layer parents: OFFLOAD t0 (step 3), EVICT t1 (4),
+    EVICT t2 (5).  Backward: 6 reads (t4, t5), 7 (t3, t4), 8 (t2, t3), 9 (t1, t2), 10 (t0, t1).
+    Per-layer parents: step 8 rebuilds t2 through t1: t0 back on demand, t1 recomputed (12 bytes in use), t0 gives way
+    for t2 (DROP_TEMP), t1 stays for step 9, and step 10 reloads t0 once more.
+    t2's parents = (t0): step 8 reloads t0 and recomputes t2 from it (t3, t0, t2 = 12 bytes: nothing gives way), t0
+    stays because step 10 reads it, step 9 recomputes t1 from it, and there is no second reload.
+    Mutation: following the forward step's reads in the recomputation gives the first event list for both graphs."""
+    tensors, steps, n_fwd = chain(6)
+    p = pl.default_params(12, n_fwd, trigger_num=1, trigger_den=1, bw_d2h_Bps=0, bw_h2d_Bps=0,
+                          prefetch_distance=1, max_reloads=0)
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(3, "OFFLOAD", 0), (4, "EVICT", 1), (5, "EVICT", 2), (6, "FREE", 5), (7, "FREE", 4),
+                         (8, "RELOAD_DEMAND", 0), (8, "RECOMPUTE", 1), (8, "DROP_TEMP", 0), (8, "RECOMPUTE", 2),
+                         (8, "FREE", 3), (9, "FREE", 2), (10, "RELOAD_DEMAND", 0), (10, "FREE", 0), (10, "FREE", 1)]
+    assert peak == 12
+    checker.check(tensors, steps, p, ev)
+    tensors[2] = dict(tensors[2], parents=[0])
+    assert steps[2]["reads"] == [1]
+    ev, peak = pl.plan(tensors, steps, p)
+    assert names(ev) == [(3, "OFFLOAD", 0), (4, "EVICT", 1), (5, "EVICT", 2), (6, "FREE", 5), (7, "FREE", 4),
+                         (8, "RELOAD_DEMAND", 0), (8, "RECOMPUTE", 2), (8, "FREE", 3),
+                         (9, "RECOMPUTE", 1), (9, "FREE", 2), (10, "FREE", 0), (10, "FREE", 1)]
+    assert peak == 12
+    checker.check(tensors, steps, p, ev)
