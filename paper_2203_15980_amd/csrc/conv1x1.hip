@@ -302,6 +302,8 @@ static int slice_groups(const ConvArgs &a) {
 // for any number of output slices (128 -> 512 at 28 x 28: 49 against 62 us); with 256 input
 // channels only while all output channels fit one slice of 64 (each further slice re-reads a
 // 512-byte activation row that the tiled kernel shares through LDS), and never with 512.
+// (256 -> 128 at 56 x 56 with both 64-channel groups in one slice: 59 against 72 us for the GEMM kernel when the
+// layer is repeated on its own, no difference inside the forward pass - left with the GEMM kernel.)
 bool conv1x1_stream_applies(const ConvArgs &a) {
     if (!a.bf16 || a.R != 1 || a.S != 1 || a.pad != 0 || a.Cout % 64 || a.relu > 1) return false;
     if (a.Cin == 256) return a.Cout == 64;
