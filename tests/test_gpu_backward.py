@@ -796,3 +796,38 @@ def test_config3_full_size_backward_sampled_entries(torch_mod):
         assert ex <= 2e-2, (lname, ex)
     assert seen_add
     d.close()
+
+
+def _random_backward_cases(seed, count):
+    """Seeded random layer shapes for both gradients: 1x1 and 3x3, stride 1 and 2, 64 to 512 channels (192 among them),
+    with and without ReLU, residual, an accumulated gx and the fused masks; the class-wise strided weight gradient
+    ("g") where the channel counts allow it."""
+    import random
+    rnd = random.Random(seed)
+    chs = [64, 128, 192, 256, 512]
+    cases = []
+    while len(cases) < count:
+        R = rnd.choice([1, 1, 3]); stride = rnd.choice([1, 1, 1, 2]); pad = (R - 1) // 2
+        Cin, Cout = rnd.choice(chs), rnd.choice(chs)
+        N, H, W = rnd.randint(1, 3), rnd.randint(1, 24), rnd.randint(1, 24)
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+        if P < 1 or Q < 1 or N * H * W * Cin * Cout * R * R > 6e8:
+            continue
+        relu = rnd.random() < 0.7
+        has_res = R == 1 and stride == 1 and rnd.random() < 0.4
+        has_add = rnd.random() < 0.5
+        fuse = rnd.choice(["", "x", "y", "xy"])
+        if not relu:
+            fuse = fuse.replace("y", "")
+        if R == 3 and stride == 2 and Cin % 128 == 0 and Cout % 128 == 0 and rnd.random() < 0.5:
+            fuse += "g"
+            if "x" not in fuse and "y" not in fuse:
+                fuse = ("y" if relu else "x") + fuse
+        cases.append(("rnd%d" % len(cases), N, H, W, Cin, Cout, R, relu, has_res, has_add, stride, fuse))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_backward_cases(5, 12), ids=lambda c: "%s_%dx%dx%d_%d_%d_r%d_s%d%s" % (c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[10], c[11]))
+def test_random_layer_shapes_backward_match_oracle(torch_mod, case):
+    """The single-layer backward comparison on seeded random shapes."""
+    test_layer_backward_matches_oracle(torch_mod, case)

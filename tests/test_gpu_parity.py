@@ -546,3 +546,29 @@ def test_degenerate_inputs(torch_mod):
     for t in (0, 2, 4, 6, 8):                                # nothing wrote outside its tensor
         assert (get(t, 256) == 0xA5).all(), t
     d.close()
+
+
+def _random_layer_cases(seed, count):
+    """Seeded random layer shapes the library takes: 1x1 and 3x3, stride 1 and 2, channel counts from 64 to 1024
+    (192 and 320 among them), up to 4 images of up to 40 x 40, with and without residual and ReLU; small enough for
+    the oracle (at most 1.5e9 multiply-adds each)."""
+    import random
+    rnd = random.Random(seed)
+    chs = [64, 128, 192, 256, 320, 512, 1024]
+    cases = []
+    while len(cases) < count:
+        R = rnd.choice([1, 1, 3]); stride = rnd.choice([1, 1, 2]); pad = (R - 1) // 2
+        Cin, Cout = rnd.choice(chs), rnd.choice(chs)
+        N, H, W = rnd.randint(1, 4), rnd.randint(1, 40), rnd.randint(1, 40)
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+        if P < 1 or Q < 1 or N * P * Q * Cin * Cout * R * R > 1.5e9:
+            continue
+        cases.append(("rnd%d" % len(cases), N, H, W, Cin, Cout, R, stride, pad, rnd.random() < 0.6, rnd.random() < 0.4))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_layer_cases(11, 16), ids=lambda c: "%s_%dx%dx%d_%d_%d_r%d_s%d" % (c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7]))
+def test_random_layer_shapes_match_oracle(torch_mod, case):
+    """The single-layer comparison on seeded random shapes: whatever kernel the dispatch picks for them (streaming,
+    GEMM tiles with two to four slice buffers, halo, tiled), ragged tiles and odd image sizes included."""
+    test_single_layer_matches_oracle(torch_mod, "bf16", case)
