@@ -401,3 +401,45 @@ def test_single_pass_plan_with_blocks_rebuilt_from_their_input_replays_with_forw
     assert checked and st["arena_in_use"] == 0
     assert st["arena_high_water"] <= p["budget_bytes"]
     d.close()
+
+
+def _random_block_shapes(seed, count):
+    import random
+    rnd = random.Random(seed)
+    return [(i % 2 == 0, rnd.randint(1, 5), rnd.randint(1, 61), rnd.randint(1, 61), rnd.randint(0, 10**6)) for i in range(count)]
+
+
+@pytest.mark.parametrize("case", _random_block_shapes(7, 12), ids=lambda c: "%s_%dx%dx%d" % ("proj" if c[0] else "ident", c[1], c[2], c[3]))
+def test_block_kernels_carry_the_per_layer_bits_on_random_shapes(torch_mod, case):
+    """Both forms of the block kernel on seeded random image sizes (tiles cut by every border, single rows and
+    columns): one random subset of each size of the block's tensors, bit for bit against the per-layer launches."""
+    import random
+    torch = torch_mod
+    import paper_2203_15980_amd as dl
+    from paper_2203_15980_amd.harness import Net
+    proj, N, H, W, sub = case
+    print("case", case, flush=True)
+    rnd = random.Random(sub)
+    layers = synth.bottleneck_stack(N, H, W, nblocks=1) if proj else synth.identity_block(N, H, W)
+    g = synth.fused_graph(layers, "bf16")
+    arena = torch.empty(4 * g.total_bytes() + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    d = dl.Delta(arena, torch.cuda.current_stream().cuda_stream)
+    d.bind([t["bytes"] for t in g.tensors])
+    net = Net(d, layers, "bf16", 100 + sub % 1000)
+    (pre, chain), = net.blocks.items()
+    net.load_input()
+    d.recompute_segment(net.all_layers)
+    d.sync()
+    ref = {n: net.read(n).copy() for n in chain}
+    for k in range(1, len(chain) + 1):
+        keep = rnd.sample(chain, k)
+        for n in chain:
+            d.release(net.ids[n], dl.EV_EVICT)
+        d.recompute_segment(net.block_desc(pre, store=keep))
+        d.sync()
+        for n in keep:
+            assert np.array_equal(net.read(n), ref[n]), (case, keep, n)
+        for n in keep:
+            d.release(net.ids[n], dl.EV_EVICT)
+        d.recompute_segment(net.all_layers)
+    d.close()
